@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Headline benchmark: the discount task (paper Fig. 1 / Query 1) at M = N = K = 8192, fp32,
+on one MI355X, through the library's C ABI.
+
+A step is one amulet_mmlike_f32 call (the whole hot path: operand staging, per-product g,
+k-reduction, R += write-back) on synthetic retail-style inputs already resident in HBM.
+Prints one JSON line: effective GFLOP/s = 2MNK/t (the paper's SPR times two), the kernel's
+share of the fp32 vector peak ("roofline"), and the CPU oracle timed on a bounded sample of
+the same workload ("cpu_baseline", a reported baseline only).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks used as roofline denominators
+FP32_VECTOR_PEAK_TFLOPS = 157.3          # 256 CU x 2.4 GHz x 256 flop/clk/CU (packed FMA)
+VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # unpacked lane-operations/s: 256 CU x 64 lanes/clk x 2.4 GHz
+VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 3, "identity": 1}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="headline_discount_8192")
+    ap.add_argument("--no-tune", action="store_true", help="use the built-in default tile shape")
+    ap.add_argument("--cpu-rows", type=int, default=128,
+                    help="rows of the workload the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over rows of A "
+              "without any exchange, but no multi-GPU run is part of it.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import amulet_workloads as wl
+    import paper_2305_08872_amd as am
+
+    am.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+
+    spec, A, B, P = wl.make(args.workload)
+    task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
+    if task == "count_i8":
+        print("bench.py: the int8 join count is a parity workload, not the bench line", file=sys.stderr)
+        return 2
+    tname = wl.TASK_NAMES[task]
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dP = torch.from_numpy(P).cuda() if P is not None else None
+    dR = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    shape = am.amulet_selected_shape(task, M, N, K) if args.no_tune else am.amulet_tune(task, M, N, K)
+    tune_s = time.perf_counter() - t0
+
+    for _ in range(args.warmup):
+        am.amulet_mmlike_f32(task, dA, dB, dP, dR)
+    torch.cuda.synchronize()
+
+    # per-launch HIP events on the stream the kernel runs on (torch's current stream)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        am.amulet_mmlike_f32(task, dA, dB, dP, dR)
+        stops[i].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    ms_per_step = wall_ms / args.steps
+    kernel_ms_avg = sum(kern_ms) / len(kern_ms)
+
+    flops = 2.0 * M * N * K
+    value = flops / (ms_per_step * 1e-3) / 1e9                 # GFLOP/s, whole job
+    achieved_tflops = flops / (kernel_ms_avg * 1e-3) / 1e12    # dominant (only) kernel
+    ops = VALU_OPS_PER_PRODUCT[tname]
+    ceiling_tflops = 2.0 * VALU_LANE_OPS_PER_S / ops / 1e12
+
+    # parity spot check + CPU baseline: the oracle on a bounded sample of whole rows
+    cpu = None
+    parity = None
+    if args.cpu_rows > 0:
+        import oracle
+        g = np.random.Generator(np.random.PCG64(99))
+        rows = np.sort(g.choice(M, min(args.cpu_rows, M), replace=False))
+        Rz = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+        am.amulet_mmlike_f32(task, dA, dB, dP, Rz)
+        torch.cuda.synchronize()
+        R_rows = Rz[torch.from_numpy(rows).cuda()].cpu().numpy()
+        As = np.ascontiguousarray(A[rows])
+        c0 = time.perf_counter()
+        R_ref, ab, threads = oracle.mmlike_f32(task, As, B, P)
+        cpu_s = time.perf_counter() - c0
+        cpu = {"value": round(2.0 * len(rows) * N * K / cpu_s / 1e9, 3), "unit": "GFLOP/s (2MNK/t)",
+               "cores": threads, "kind": "oracle",
+               "sample": "%d whole rows of the %dx%dx%d workload (%.2e products), %.1f s"
+                         % (len(rows), M, N, K, float(len(rows)) * N * K, cpu_s)}
+        den = np.where(ab > 0, ab, 1.0)
+        parity = float(np.max(np.abs(R_rows.astype(np.float64) - R_ref) / den))
+
+    out = {
+        "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp32" % (tname, M, N, K),
+        "value": round(value, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "task": tname, "M": M, "N": N, "K": K,
+                   "tile_shape": am.amulet_shape_name(task, shape), "tuned": not args.no_tune,
+                   "tune_seconds": round(tune_s, 3)},
+        "pct_of_fp32_vector_peak": round(100.0 * value / 1e3 / FP32_VECTOR_PEAK_TFLOPS, 2),
+        "roofline": {"bound": "alu", "achieved": round(achieved_tflops, 3),
+                     "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved_tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel_ms_avg": round(kernel_ms_avg, 4),
+                     "valu_ops_per_product": ops,
+                     "op_mix_ceiling_tflops": round(ceiling_tflops, 3),
+                     "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4)},
+        "cpu_baseline": cpu,
+        "parity_worst_ratio_on_sample": parity,
+        "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)",
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

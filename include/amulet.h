@@ -1,0 +1,171 @@
+/*
+ * amulet.h - C ABI of the MI355X (gfx950) library for AMULET's
+ * matrix-multiplication-like tasks.
+ *
+ * A matrix-multiplication-like task (paper Sec. 4.2) is the triple loop
+ *
+ *     for i < M, j < N, k < K:   R[i][j] += g( A[i][k] * B[k][j], params[j] )
+ *
+ * in which g acts on every single product before the k-reduction, so the task
+ * is not a GEMM.  The tasks built here are the ones the paper states and
+ * measures (Fig. 1, Fig. 2, "Test Queries" figure of Sec. 6.3, Sec. 6.1), plus
+ * the join-count-as-matmul case its introduction cites.
+ *
+ * Conventions common to every entry point
+ *  - Every matrix pointer is a DEVICE pointer owned by the caller.  The
+ *    library reads A, B, params and reads+writes R; it never frees, retains
+ *    or reallocates them.  R must not overlap A, B or params.
+ *  - Matrices are row-major with a leading dimension in ELEMENTS (lda >= K,
+ *    ldb >= N, ldr >= N), mirroring the paper's "rows need not be contiguous"
+ *    (Sec. 5).  Any M, N, K >= 0 is accepted; edge tiles are handled inside.
+ *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *    Calls only enqueue work and return; they never synchronise or allocate.
+ *  - Return value: AMULET_OK (0) or a negative amulet_status_t.  Nothing is
+ *    enqueued when an argument error is returned.  M == 0, N == 0 or K == 0 is
+ *    a successful no-op (R unchanged).
+ *  - A or B holding NaN or +-inf gives unspecified results; +-inf in thres is
+ *    supported (thres = +inf never triggers, -inf always does).
+ */
+#ifndef AMULET_H
+#define AMULET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    AMULET_IDENTITY = 0, /* g = p                         plain matmul, Sec. 6.1            */
+    AMULET_DISCOUNT = 1, /* g = p - (p > thres[j])*p*dis[j]        Fig. 1 / Query 1         */
+    AMULET_BOOST = 2,    /* g = p + (p > thres[j])*(p - thres[j])  Fig. 2 / Query 2         */
+    AMULET_COUNT_GT = 3  /* g = (p > thres[j])   Query 3, constant in its thres[j] form     */
+} amulet_task_t;
+
+typedef enum {
+    AMULET_OK = 0,
+    AMULET_ERR_TASK = -1,   /* unknown task                                   */
+    AMULET_ERR_DIM = -2,    /* a negative dimension                           */
+    AMULET_ERR_NULL = -3,   /* a required pointer is NULL                     */
+    AMULET_ERR_LD = -4,     /* a leading dimension is smaller than the row    */
+    AMULET_ERR_LAUNCH = -5, /* HIP reported an error at launch                */
+    AMULET_ERR_SHAPE = -6,  /* unknown tile-shape id, or one the task lacks   */
+    AMULET_ERR_RANGE = -7   /* a dimension exceeds what the kernels index     */
+} amulet_status_t;
+
+/*
+ * R[i][j] += sum_k g(fl32(A[i][k]*B[k][j]), params[j])        (Fig. 1, Fig. 2, Query 1-3)
+ *
+ * p is one IEEE round-to-nearest fp32 multiply and "p > thres[j]" is decided
+ * on that rounded value, strictly, exactly as a plain fp32 loop would; the
+ * predicate acts as a mask (the paper's "Mask -" node, Sec. 4.3.1).  The k-sum
+ * is formed in fp32 in an order the library chooses (the paper's loop is
+ * order-free, Sec. 4.1): results agree with a double-accumulating loop to
+ * within 1e-5 * sum_k |term|.
+ *
+ *   task    one of amulet_task_t
+ *   A       M x K fp32, lda >= K            B   K x N fp32, ldb >= N
+ *   params  planar fp32: DISCOUNT thres[0..N) then dis[0..N); BOOST and
+ *           COUNT_GT thres[0..N); IDENTITY ignores it (may be NULL)
+ *   R       M x N fp32, ldr >= N, accumulated into ("+=", Fig. "12x16 inner kernel")
+ *
+ * The tile shape is the one amulet_tune() cached for this (task, M, N, K), or
+ * a built-in default.  Each dimension must be below 2^31 - 2^16.
+ */
+int amulet_mmlike_f32(int task, int64_t M, int64_t N, int64_t K,
+                      const float *A, int64_t lda,
+                      const float *B, int64_t ldb,
+                      const float *params,
+                      float *R, int64_t ldr,
+                      void *stream);
+
+/* Same, with the tile shape given explicitly (0 <= shape < amulet_shape_count(task)):
+ * the parameterised form of the loop nest, Sec. 4.4, used by the selector's
+ * trials and by tests that exercise every shape. */
+int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K,
+                            const float *A, int64_t lda,
+                            const float *B, int64_t ldb,
+                            const float *params,
+                            float *R, int64_t ldr,
+                            void *stream);
+
+/*
+ * Natural-join count as a matrix product (the join-as-matmul translation cited
+ * in Sec. 1): R[i][j] += sum_k A[i][k]*B[k][j], int8 operands (any values; the
+ * workload is 0/1 indicators), int32 result, exact (wraps modulo 2^32 only if
+ * the true sum leaves int32).  A is M x K (lda >= K), B is K x N (ldb >= N),
+ * R is M x N int32 (ldr >= N).
+ */
+int amulet_count_i8(int64_t M, int64_t N, int64_t K,
+                    const int8_t *A, int64_t lda,
+                    const int8_t *B, int64_t ldb,
+                    int32_t *R, int64_t ldr,
+                    void *stream);
+
+/* Same, with the kernel shape given explicitly
+ * (0 <= shape < amulet_shape_count(AMULET_TASK_COUNT_I8)). */
+int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
+                          const int8_t *A, int64_t lda,
+                          const int8_t *B, int64_t ldb,
+                          int32_t *R, int64_t ldr,
+                          void *stream);
+
+/*
+ * Adaptive shape selection (the stand-in for the paper's adaptive execution,
+ * Sec. 4.4-4.6): times the candidate tile shapes of `task` on synthetic
+ * operands of this size that the call allocates and frees itself, walks them
+ * with the paper's two-stage greedy search, caches the winner for
+ * (task, M, N, K) and synchronises `stream`.  Unlike the compute calls this
+ * one allocates and blocks; it is meant to run once, outside the hot path.
+ * task may be 0..3, or AMULET_TASK_COUNT_I8 for amulet_count_i8.
+ * Returns the chosen shape id (>= 0) or a negative status.
+ */
+#define AMULET_TASK_COUNT_I8 100
+int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream);
+
+/* Shape table introspection: number of tile shapes of a task, a printable name
+ * for one, and the shape amulet_mmlike_f32 / amulet_count_i8 would use now. */
+int amulet_shape_count(int task);
+const char *amulet_shape_name(int task, int shape);
+int amulet_selected_shape(int task, int64_t M, int64_t N, int64_t K);
+/* Forget every cached selection. */
+void amulet_clear_selections(void);
+
+/*
+ * The paper's two-stage greedy parameter search (Sec. 4.4-4.6), over a grid
+ * axis0 x axis1 of candidates (k_c-like and n_c-like): with axis1 fixed at
+ * its first value, score every axis0 candidate and keep the lowest; then walk
+ * axis1 upward from its first value and stop at the first score that is
+ * higher than its predecessor's, keeping the predecessor.  `score` is called
+ * on the host as score(i0, i1, ctx) and returns a cost (lower is better).
+ * Writes the chosen indices; returns the number of score() calls made, or
+ * AMULET_ERR_DIM if an axis is empty, AMULET_ERR_NULL for a NULL argument.
+ */
+typedef double (*amulet_score_fn)(int i0, int i1, void *ctx);
+int amulet_greedy_search(int n0, int n1, amulet_score_fn score, void *ctx, int *best0, int *best1);
+
+/*
+ * Register demand of an I_h x I_w inner kernel (Sec. 3 inequality and its
+ * extension in Sec. 4.3.2), in SIMD registers of width S_w elements:
+ *   I_h*ceil(I_w/S_w) sub-results + 1 for A + ceil(I_w/S_w) for B
+ *   + 1 per constant leaf + 1 per [i]-indexed leaf + ceil(I_w/S_w) per
+ *   [j]-indexed leaf + 1 per [i][j]-indexed leaf + n_temp temporaries.
+ * amulet_choose_kernel_height returns the largest I_h <= I_h_max whose demand
+ * fits `budget` registers (0 if none does).  The library sizes its per-lane
+ * micro-tiles with the same rule against the VGPR budget.
+ */
+int amulet_register_demand(int I_h, int I_w, int S_w, int n_const, int n_i, int n_j, int n_ij,
+                           int n_temp);
+int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int n_i, int n_j,
+                                int n_ij, int n_temp, int budget);
+
+/* Printable text for a status code (static storage). */
+const char *amulet_strerror(int code);
+
+/* Library version string (static storage). */
+const char *amulet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMULET_H */

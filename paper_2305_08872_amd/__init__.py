@@ -1,0 +1,31 @@
+"""MI355X-native library for AMULET's matrix-multiplication-like tasks.
+
+The work is done by ``libamulet.so`` (hand-written HIP for gfx950, built
+in-tree by ``paper_2305_08872_amd.build``); this package is the thin ctypes
+binding over its C ABI (``include/amulet.h``).  PyTorch is used by callers for
+device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    AMULET_BOOST,
+    AMULET_COUNT_GT,
+    AMULET_DISCOUNT,
+    AMULET_IDENTITY,
+    AMULET_TASK_COUNT_I8,
+    AmuletError,
+    amulet_choose_kernel_height,
+    amulet_clear_selections,
+    amulet_count_i8,
+    amulet_count_i8_shape,
+    amulet_greedy_search,
+    amulet_mmlike_f32,
+    amulet_mmlike_f32_shape,
+    amulet_register_demand,
+    amulet_selected_shape,
+    amulet_shape_count,
+    amulet_shape_name,
+    amulet_strerror,
+    amulet_tune,
+    amulet_version,
+    library_path,
+    load_library,
+)

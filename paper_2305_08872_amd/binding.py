@@ -1,0 +1,213 @@
+"""ctypes binding over the C ABI of libamulet.so (argument marshalling only).
+
+Each function has the name of the C entry point it calls.  Tensor arguments
+are torch tensors already resident on the GPU; the binding takes their data
+pointers, row strides and the current torch stream and passes them through.
+There is no fallback: if the shared library has not been built, every call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+AMULET_IDENTITY, AMULET_DISCOUNT, AMULET_BOOST, AMULET_COUNT_GT = 0, 1, 2, 3
+AMULET_TASK_COUNT_I8 = 100
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libamulet.so")
+_lib = None
+
+
+class AmuletError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s (status %d)" % (where, amulet_strerror(code), code))
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libamulet.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            "libamulet.so is missing at %s: build it with "
+            "`python -m paper_2305_08872_amd.build` (needs hipcc); there is no fallback path"
+            % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    lib.amulet_mmlike_f32.restype = i32
+    lib.amulet_mmlike_f32.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.amulet_mmlike_f32_shape.restype = i32
+    lib.amulet_mmlike_f32_shape.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.amulet_count_i8.restype = i32
+    lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.amulet_count_i8_shape.restype = i32
+    lib.amulet_count_i8_shape.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.amulet_tune.restype = i32
+    lib.amulet_tune.argtypes = [i32, i64, i64, i64, vp]
+    lib.amulet_shape_count.restype = i32
+    lib.amulet_shape_count.argtypes = [i32]
+    lib.amulet_shape_name.restype = ctypes.c_char_p
+    lib.amulet_shape_name.argtypes = [i32, i32]
+    lib.amulet_selected_shape.restype = i32
+    lib.amulet_selected_shape.argtypes = [i32, i64, i64, i64]
+    lib.amulet_clear_selections.restype = None
+    lib.amulet_clear_selections.argtypes = []
+    lib.amulet_greedy_search.restype = i32
+    lib.amulet_greedy_search.argtypes = [i32, i32, _SCORE_FN, vp, ctypes.POINTER(i32),
+                                         ctypes.POINTER(i32)]
+    lib.amulet_register_demand.restype = i32
+    lib.amulet_register_demand.argtypes = [i32] * 8
+    lib.amulet_choose_kernel_height.restype = i32
+    lib.amulet_choose_kernel_height.argtypes = [i32] * 9
+    lib.amulet_strerror.restype = ctypes.c_char_p
+    lib.amulet_strerror.argtypes = [i32]
+    lib.amulet_version.restype = ctypes.c_char_p
+    lib.amulet_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+_SCORE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_void_p)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _mat(t, dtype_name: str, what: str):
+    """(data_ptr, rows, cols, leading dimension in elements) of a 2-D device tensor."""
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % what)
+    if t.dim() != 2 or str(t.dtype) != dtype_name:
+        raise ValueError("%s must be a 2-D %s tensor" % (what, dtype_name))
+    rows, cols = t.shape
+    if cols > 1 and t.stride(1) != 1:
+        raise ValueError("%s must have unit column stride" % what)
+    ld = t.stride(0) if rows > 1 else max(cols, 1)
+    return t.data_ptr(), rows, cols, max(ld, 1)
+
+
+def _params_ptr(task: int, params, N: int):
+    n_rows = {AMULET_IDENTITY: 0, AMULET_DISCOUNT: 2, AMULET_BOOST: 1, AMULET_COUNT_GT: 1}.get(task, 0)
+    if n_rows == 0 or params is None:
+        return None
+    if not params.is_cuda or str(params.dtype) != "torch.float32" or not params.is_contiguous() \
+            or params.numel() != n_rows * N:
+        raise ValueError("params must be a contiguous fp32 device tensor of %d x %d" % (n_rows, N))
+    return params.data_ptr()
+
+
+def _check(rc: int, where: str):
+    if rc < 0:
+        raise AmuletError(rc, where)
+    return rc
+
+
+def amulet_mmlike_f32(task: int, A, B, params, R, stream=None):
+    """R += sum_k g(A[i,k]*B[k,j], params[:, j]) on the GPU, in place; enqueues and returns."""
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.float32", "A")
+    pb, K2, N, ldb = _mat(B, "torch.float32", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.float32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    _check(lib.amulet_mmlike_f32(task, M, N, K, pa, lda, pb, ldb, _params_ptr(task, params, N), pr, ldr,
+                                 _stream_ptr(stream)), "amulet_mmlike_f32")
+
+
+def amulet_mmlike_f32_shape(task: int, shape: int, A, B, params, R, stream=None):
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.float32", "A")
+    pb, K2, N, ldb = _mat(B, "torch.float32", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.float32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    _check(lib.amulet_mmlike_f32_shape(task, shape, M, N, K, pa, lda, pb, ldb,
+                                       _params_ptr(task, params, N), pr, ldr, _stream_ptr(stream)),
+           "amulet_mmlike_f32_shape")
+
+
+def amulet_count_i8(A, B, R, stream=None):
+    """R += A @ B for int8 A, B and int32 R on the GPU, exact; enqueues and returns."""
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.int8", "A")
+    pb, K2, N, ldb = _mat(B, "torch.int8", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.int32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    _check(lib.amulet_count_i8(M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
+           "amulet_count_i8")
+
+
+def amulet_count_i8_shape(shape: int, A, B, R, stream=None):
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.int8", "A")
+    pb, K2, N, ldb = _mat(B, "torch.int8", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.int32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    _check(lib.amulet_count_i8_shape(shape, M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
+           "amulet_count_i8_shape")
+
+
+def amulet_tune(task: int, M: int, N: int, K: int, stream=None) -> int:
+    """Time the task's tile shapes at this size, cache and return the winner's id."""
+    return _check(load_library().amulet_tune(task, M, N, K, _stream_ptr(stream)), "amulet_tune")
+
+
+def amulet_shape_count(task: int) -> int:
+    return load_library().amulet_shape_count(task)
+
+
+def amulet_shape_name(task: int, shape: int) -> str:
+    return load_library().amulet_shape_name(task, shape).decode()
+
+
+def amulet_selected_shape(task: int, M: int, N: int, K: int) -> int:
+    return _check(load_library().amulet_selected_shape(task, M, N, K), "amulet_selected_shape")
+
+
+def amulet_clear_selections() -> None:
+    load_library().amulet_clear_selections()
+
+
+def amulet_greedy_search(n0: int, n1: int, score):
+    """Run the library's two-stage greedy search with a Python score(i0, i1) callback.
+    Returns (best0, best1, number of score calls)."""
+    lib = load_library()
+    cb = _SCORE_FN(lambda i0, i1, _ctx: float(score(i0, i1)))
+    b0, b1 = ctypes.c_int(-1), ctypes.c_int(-1)
+    calls = _check(lib.amulet_greedy_search(n0, n1, cb, None, ctypes.byref(b0), ctypes.byref(b1)),
+                   "amulet_greedy_search")
+    return b0.value, b1.value, calls
+
+
+def amulet_register_demand(I_h, I_w, S_w, n_const, n_i, n_j, n_ij, n_temp) -> int:
+    return _check(load_library().amulet_register_demand(I_h, I_w, S_w, n_const, n_i, n_j, n_ij, n_temp),
+                  "amulet_register_demand")
+
+
+def amulet_choose_kernel_height(I_h_max, I_w, S_w, n_const, n_i, n_j, n_ij, n_temp, budget) -> int:
+    return _check(load_library().amulet_choose_kernel_height(I_h_max, I_w, S_w, n_const, n_i, n_j, n_ij,
+                                                             n_temp, budget),
+                  "amulet_choose_kernel_height")
+
+
+def amulet_strerror(code: int) -> str:
+    if _lib is None and not os.path.exists(_LIB_PATH):
+        return "status %d" % code
+    return load_library().amulet_strerror(code).decode()
+
+
+def amulet_version() -> str:
+    return load_library().amulet_version().decode()

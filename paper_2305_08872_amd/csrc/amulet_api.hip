@@ -1,0 +1,379 @@
+// C ABI of the library: argument checks, tile-shape selection, launches.
+// Everything a compute call does on the host is here; it enqueues one kernel
+// (or a few for very tall int8 problems) on the caller's stream and returns.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+#include "amulet.h"
+#include "amulet_internal.h"
+
+namespace amulet {
+
+const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
+    {4, 1, 4, 8, "valu_16x256_k8"},   {8, 1, 4, 8, "valu_32x256_k8"},
+    {8, 2, 4, 8, "valu_32x512_k8"},   {8, 2, 8, 8, "valu_64x512_k8"},
+    {4, 1, 4, 16, "valu_16x256_k16"}, {8, 1, 4, 16, "valu_32x256_k16"},
+    {8, 2, 4, 16, "valu_32x512_k16"}, {8, 2, 8, 16, "valu_64x512_k16"},
+};
+
+static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple"};
+
+// ---- selection cache ---------------------------------------------------------
+typedef std::tuple<int, int64_t, int64_t, int64_t> SelKey;
+static std::mutex g_sel_mutex;
+static std::map<SelKey, int> g_selected;
+
+static int n_shapes(int task)
+{
+    if (task >= TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
+    if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
+    return 0;
+}
+
+// Built-in choice when nothing was tuned: the widest tile that still gives
+// every compute unit at least two workgroups, at the deeper B staging.
+static int default_shape(int task, int64_t M, int64_t N, int64_t)
+{
+    if (task == AMULET_TASK_COUNT_I8) return 0;
+    const int64_t want = 2 * 256;
+    for (int t = VALU_TILES - 1; t > 0; --t) {
+        const ValuShapeDesc &d = kValuShapes[VALU_TILES + t];
+        const int64_t rows = (int64_t)d.NW * d.TM, cols = 256LL * d.NG;
+        const int64_t wgs = ((M + rows - 1) / rows) * ((N + cols - 1) / cols);
+        if (wgs >= want) return VALU_TILES + t;
+    }
+    return VALU_TILES + 0;
+}
+
+static int lookup_shape(int task, int64_t M, int64_t N, int64_t K)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_sel_mutex);
+        auto it = g_selected.find(SelKey(task, M, N, K));
+        if (it != g_selected.end()) return it->second;
+    }
+    return default_shape(task, M, N, K);
+}
+
+static const int64_t kMaxDim = 2147483647LL - 65536LL;
+
+static int check_common(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                        int64_t ldb, const void *R, int64_t ldr)
+{
+    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
+    if (M == 0 || N == 0 || K == 0) return 1;  // nothing to do
+    if (!A || !B || !R) return AMULET_ERR_NULL;
+    if (lda < K || ldb < N || ldr < N) return AMULET_ERR_LD;
+    return AMULET_OK;
+}
+
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static int run_mmlike(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                      const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
+                      void *stream)
+{
+    MmlikeArgs a;
+    a.A = A; a.B = B; a.params = params; a.R = R;
+    a.lda = lda; a.ldb = ldb; a.ldr = ldr;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.vec = (aligned16(B) && aligned16(R) && ldb % 4 == 0 && ldr % 4 == 0) ? 1 : 0;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    switch (task) {
+    case TASK_IDENTITY: e = launch_mmlike_valu_task<TASK_IDENTITY>(shape, a, s); break;
+    case TASK_DISCOUNT: e = launch_mmlike_valu_task<TASK_DISCOUNT>(shape, a, s); break;
+    case TASK_BOOST: e = launch_mmlike_valu_task<TASK_BOOST>(shape, a, s); break;
+    default: e = launch_mmlike_valu_task<TASK_COUNT_GT>(shape, a, s); break;
+    }
+    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                     const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+{
+    CountArgs a;
+    a.A = A; a.B = B; a.R = R;
+    a.lda = lda; a.ldb = ldb; a.ldr = ldr;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
+    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+// ---- synthetic operands for the selector's trials ----------------------------
+__global__ void fill_f32_kernel(float *p, size_t n, float lo, float span, uint32_t salt)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        uint32_t h = (uint32_t)i * 2654435761u + salt;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        p[i] = lo + span * (float)(h >> 8) * (1.0f / 16777216.0f);
+    }
+}
+__global__ void fill_i8_kernel(int8_t *p, size_t n, uint32_t salt)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        uint32_t h = (uint32_t)i * 2654435761u + salt;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        p[i] = (int8_t)((h >> 8) % 20u == 0u);
+    }
+}
+
+struct TrialCtx {
+    int task;
+    int64_t M, N, K;
+    void *A, *B, *params, *R;
+    hipStream_t stream;
+    hipEvent_t e0, e1;
+    int status;
+};
+
+static double time_shape(TrialCtx *c, int shape)
+{
+    float best = 1e30f;
+    for (int rep = 0; rep < 3; ++rep) {  // first repetition doubles as warm-up
+        (void)hipEventRecord(c->e0, c->stream);
+        int rc;
+        if (c->task == AMULET_TASK_COUNT_I8)
+            rc = run_count(shape, c->M, c->N, c->K, (const int8_t *)c->A, c->K, (const int8_t *)c->B,
+                           c->N, (int32_t *)c->R, c->N, c->stream);
+        else
+            rc = run_mmlike(c->task, shape, c->M, c->N, c->K, (const float *)c->A, c->K,
+                            (const float *)c->B, c->N, (const float *)c->params, (float *)c->R, c->N,
+                            c->stream);
+        (void)hipEventRecord(c->e1, c->stream);
+        if (rc != AMULET_OK || hipEventSynchronize(c->e1) != hipSuccess) {
+            c->status = AMULET_ERR_LAUNCH;
+            return 1e30;
+        }
+        float ms = 0.0f;
+        (void)hipEventElapsedTime(&ms, c->e0, c->e1);
+        if (rep > 0 && ms < best) best = ms;
+    }
+    return (double)best;
+}
+
+static double valu_trial_score(int i0, int i1, void *ctx)
+{
+    return time_shape((TrialCtx *)ctx, i0 * VALU_TILES + i1);
+}
+
+}  // namespace amulet
+
+using namespace amulet;
+
+extern "C" {
+
+int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A,
+                            int64_t lda, const float *B, int64_t ldb, const float *params, float *R,
+                            int64_t ldr, void *stream)
+{
+    if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
+    if (shape < 0 || shape >= VALU_SHAPE_COUNT) return AMULET_ERR_SHAPE;
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    if (rc == 1) return AMULET_OK;
+    if (task != TASK_IDENTITY && !params) return AMULET_ERR_NULL;
+    return run_mmlike(task, shape, M, N, K, A, lda, B, ldb, params, R, ldr, stream);
+}
+
+int amulet_mmlike_f32(int task, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                      const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
+                      void *stream)
+{
+    if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
+    return amulet_mmlike_f32_shape(task, lookup_shape(task, M, N, K), M, N, K, A, lda, B, ldb, params,
+                                   R, ldr, stream);
+}
+
+int amulet_count_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
+                    int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+{
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    if (rc == 1) return AMULET_OK;
+    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, K), M, N, K, A, lda, B, ldb, R, ldr,
+                     stream);
+}
+
+int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                          const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+{
+    if (shape < 0 || shape >= COUNT_SHAPE_COUNT) return AMULET_ERR_SHAPE;
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    if (rc == 1) return AMULET_OK;
+    return run_count(shape, M, N, K, A, lda, B, ldb, R, ldr, stream);
+}
+
+int amulet_greedy_search(int n0, int n1, amulet_score_fn score, void *ctx, int *best0, int *best1)
+{
+    if (!score || !best0 || !best1) return AMULET_ERR_NULL;
+    if (n0 <= 0 || n1 <= 0) return AMULET_ERR_DIM;
+    int calls = 0;
+    // stage 1: axis 1 at its first value, every axis-0 candidate, keep the lowest score
+    int b0 = 0;
+    double s_best = 0.0;
+    for (int i = 0; i < n0; ++i) {
+        const double sc = score(i, 0, ctx);
+        ++calls;
+        if (i == 0 || sc < s_best) { s_best = sc; b0 = i; }
+    }
+    // stage 2: walk axis 1 upward; the first score above its predecessor ends the walk
+    int b1 = 0;
+    double prev = s_best;
+    for (int j = 1; j < n1; ++j) {
+        const double sc = score(b0, j, ctx);
+        ++calls;
+        if (sc > prev) break;
+        prev = sc;
+        b1 = j;
+    }
+    *best0 = b0;
+    *best1 = b1;
+    return calls;
+}
+
+int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
+{
+    const int ns = n_shapes(task);
+    if (ns == 0) return AMULET_ERR_TASK;
+    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
+    if (M == 0 || N == 0 || K == 0) return default_shape(task, M, N, K);
+
+    // Trials run on a row slab of the task when the whole task would take long
+    // (the paper tests parameters on a small part of the input, Sec. 4.4).
+    int64_t Mt = M;
+    const double cap = 68719476736.0;  // 2^36 products per trial
+    if ((double)M * (double)N * (double)K > cap) {
+        Mt = (int64_t)(cap / ((double)N * (double)K));
+        if (Mt < 2048) Mt = 2048;
+        if (Mt > M) Mt = M;
+    }
+    const bool i8 = task == AMULET_TASK_COUNT_I8;
+    const size_t es = i8 ? 1 : 4;
+    TrialCtx c;
+    memset(&c, 0, sizeof(c));
+    c.task = task; c.M = Mt; c.N = N; c.K = K; c.stream = (hipStream_t)stream;
+    int result = AMULET_ERR_LAUNCH;
+    bool ok = hipMalloc(&c.A, (size_t)Mt * K * es) == hipSuccess &&
+              hipMalloc(&c.B, (size_t)K * N * es) == hipSuccess &&
+              hipMalloc(&c.R, (size_t)Mt * N * 4) == hipSuccess &&
+              hipMalloc(&c.params, (size_t)2 * N * 4) == hipSuccess &&
+              hipEventCreate(&c.e0) == hipSuccess && hipEventCreate(&c.e1) == hipSuccess;
+    if (ok) {
+        if (i8) {
+            hipLaunchKernelGGL(fill_i8_kernel, dim3(1024), dim3(256), 0, c.stream, (int8_t *)c.A,
+                               (size_t)Mt * K, 17u);
+            hipLaunchKernelGGL(fill_i8_kernel, dim3(1024), dim3(256), 0, c.stream, (int8_t *)c.B,
+                               (size_t)K * N, 29u);
+        } else {
+            hipLaunchKernelGGL(fill_f32_kernel, dim3(1024), dim3(256), 0, c.stream, (float *)c.A,
+                               (size_t)Mt * K, 0.0f, 1.0f, 17u);
+            hipLaunchKernelGGL(fill_f32_kernel, dim3(1024), dim3(256), 0, c.stream, (float *)c.B,
+                               (size_t)K * N, 0.0f, 1.0f, 29u);
+        }
+        hipLaunchKernelGGL(fill_f32_kernel, dim3(64), dim3(256), 0, c.stream, (float *)c.params,
+                           (size_t)N, 0.25f, 0.0f, 1u);
+        hipLaunchKernelGGL(fill_f32_kernel, dim3(64), dim3(256), 0, c.stream, (float *)c.params + N,
+                           (size_t)N, 0.1f, 0.0f, 1u);
+        hipLaunchKernelGGL(fill_f32_kernel, dim3(1024), dim3(256), 0, c.stream, (float *)c.R,
+                           (size_t)Mt * N, 0.0f, 0.0f, 1u);
+        int chosen;
+        if (i8) {
+            chosen = 0;
+            double best = 0.0;
+            for (int sidx = 0; sidx < COUNT_SHAPE_COUNT; ++sidx) {
+                const double t = time_shape(&c, sidx);
+                if (sidx == 0 || t < best) { best = t; chosen = sidx; }
+            }
+        } else {
+            int b0 = 0, b1 = 0;
+            amulet_greedy_search(VALU_DEPTHS, VALU_TILES, valu_trial_score, &c, &b0, &b1);
+            chosen = b0 * VALU_TILES + b1;
+        }
+        (void)hipStreamSynchronize(c.stream);
+        if (c.status == AMULET_OK) {
+            std::lock_guard<std::mutex> lock(g_sel_mutex);
+            g_selected[SelKey(task, M, N, K)] = chosen;
+            result = chosen;
+        }
+    }
+    if (c.e0) (void)hipEventDestroy(c.e0);
+    if (c.e1) (void)hipEventDestroy(c.e1);
+    (void)hipFree(c.A); (void)hipFree(c.B); (void)hipFree(c.R); (void)hipFree(c.params);
+    return result;
+}
+
+int amulet_shape_count(int task) { return n_shapes(task); }
+
+const char *amulet_shape_name(int task, int shape)
+{
+    if (shape < 0 || shape >= n_shapes(task)) return "invalid";
+    return task == AMULET_TASK_COUNT_I8 ? kCountShapeNames[shape] : kValuShapes[shape].name;
+}
+
+int amulet_selected_shape(int task, int64_t M, int64_t N, int64_t K)
+{
+    if (n_shapes(task) == 0) return AMULET_ERR_TASK;
+    return lookup_shape(task, M, N, K);
+}
+
+void amulet_clear_selections(void)
+{
+    std::lock_guard<std::mutex> lock(g_sel_mutex);
+    g_selected.clear();
+}
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int amulet_register_demand(int I_h, int I_w, int S_w, int n_const, int n_i, int n_j, int n_ij,
+                           int n_temp)
+{
+    if (I_h <= 0 || I_w <= 0 || S_w <= 0 || n_const < 0 || n_i < 0 || n_j < 0 || n_ij < 0 || n_temp < 0)
+        return AMULET_ERR_DIM;
+    const int w = ceil_div(I_w, S_w);
+    return I_h * w + 1 + w + n_const + n_i + n_j * w + n_ij + n_temp;
+}
+
+int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int n_i, int n_j, int n_ij,
+                                int n_temp, int budget)
+{
+    for (int h = I_h_max; h >= 1; --h) {
+        const int need = amulet_register_demand(h, I_w, S_w, n_const, n_i, n_j, n_ij, n_temp);
+        if (need < 0) return need;
+        if (need <= budget) return h;
+    }
+    return 0;
+}
+
+const char *amulet_strerror(int code)
+{
+    switch (code) {
+    case AMULET_OK: return "success";
+    case AMULET_ERR_TASK: return "unknown task";
+    case AMULET_ERR_DIM: return "negative or empty dimension";
+    case AMULET_ERR_NULL: return "required pointer is NULL";
+    case AMULET_ERR_LD: return "leading dimension smaller than the row length";
+    case AMULET_ERR_LAUNCH: return "HIP reported an error at launch";
+    case AMULET_ERR_SHAPE: return "unknown tile shape";
+    case AMULET_ERR_RANGE: return "dimension too large for the kernels' 32-bit indexing";
+    default: return "unknown status code";
+    }
+}
+
+const char *amulet_version(void) { return "amulet-gfx950 0.1"; }
+
+}  // extern "C"

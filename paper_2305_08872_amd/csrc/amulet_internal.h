@@ -1,0 +1,53 @@
+// Declarations shared by the library's own translation units (not part of the
+// C ABI and not used by the CPU oracle).
+#ifndef AMULET_INTERNAL_H
+#define AMULET_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amulet {
+
+enum { TASK_IDENTITY = 0, TASK_DISCOUNT = 1, TASK_BOOST = 2, TASK_COUNT_GT = 3 };
+
+// Arguments of an fp32 task launch, already validated on the host.
+struct MmlikeArgs {
+    const float *A;
+    const float *B;
+    const float *params;
+    float *R;
+    int64_t lda, ldb, ldr;
+    int M, N, K;
+    int vec;  // 1 when B, R and their row pitches allow 16-byte vector accesses
+};
+
+// Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy
+// parameter search walks (paper Sec. 4.4): axis 0 is the depth BK of the B tile
+// staged per barrier (the k_c analogue), axis 1 the workgroup's R tile from
+// narrow to wide (the n_c analogue).  shape id = depth index * VALU_TILES + tile.
+//   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 8x4, 4 waves -> 32 x 256
+//   tile 2: 8x8 per lane, 4 waves  -> 32 x 512      tile 3: 8x8, 8 waves -> 64 x 512
+enum { VALU_DEPTHS = 2, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES };
+
+struct ValuShapeDesc {
+    int TM, NG, NW, BK;
+    const char *name;
+};
+extern const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT];
+
+// Arguments of an int8 join-count launch, already validated on the host.
+struct CountArgs {
+    const int8_t *A;
+    const int8_t *B;
+    int32_t *R;
+    int64_t lda, ldb, ldr;
+    int M, N, K;
+};
+enum { COUNT_SHAPE_COUNT = 1 };
+hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
+
+template <int TASK>
+hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);
+
+}  // namespace amulet
+#endif

@@ -1,0 +1,7 @@
+// VALU tile kernels of the identity task: one translation unit per task so the
+// tile shapes of the four tasks compile in parallel.
+#include "mmlike_valu_impl.h"
+
+namespace amulet {
+template hipError_t launch_mmlike_valu_task<0>(int, const MmlikeArgs &, hipStream_t);
+}

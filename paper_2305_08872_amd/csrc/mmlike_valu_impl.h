@@ -1,0 +1,326 @@
+// fp32 VALU tile kernels for the matrix-multiplication-like tasks whose g acts
+// on each product before the k-sum (paper Fig. 1, Fig. 2, Query 1-3): these
+// cannot run on the matrix cores, so the inner kernel is a per-lane register
+// micro-tile on the vector ALU, the CDNA form of the paper's register-blocked
+// inner kernel (Sec. 3, Fig. "12x16 inner kernel"; Sec. 4.3.3 for the version
+// with g inside the kk loop).
+//
+// Mapping (one workgroup = NW waves, one R tile of NW*TM rows x 256*NG columns):
+//   * a lane owns 4*NG columns: column groups g*256 + lane*4 .. +3.  thres[j]
+//     and the per-column factor derived from dis[j] live in registers for the
+//     whole K loop (the paper reloads them every kk and budgets registers for
+//     them, Sec. 4.3.2).
+//   * a wave owns TM rows, the same for all its lanes, so A[i][k] is wave
+//     uniform: it is fetched through the scalar data cache into SGPRs and used
+//     directly as the scalar operand of the multiply.  A never touches LDS or
+//     vector registers.
+//   * the BK x (256*NG) tile of B is staged global -> registers -> LDS, double
+//     buffered, one barrier per tile; a lane reads its own 16-byte column groups
+//     back with conflict-free ds_read_b128.
+//   * the k-sum is two-level: a partial accumulator per BK tile, folded into
+//     the main accumulator after each tile, which keeps fp32 round-off of long
+//     same-sign sums (K = 8192 retail data) far inside the 1e-5 budget.
+//   * the K remainder is computed by a k-by-k tail loop, never by zero padding:
+//     g(0) is not 0 in general (BOOST with thres < 0, COUNT_GT with thres < 0).
+//
+// Per product the discount task costs 4 VALU lane-operations (multiply rounded
+// to fp32, compare, select of the factor, fused multiply-add), the paper's
+// sequence "mul, gtcmp, mul, masksub, add" (Sec. 4.3.1) minus one.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "amulet_internal.h"
+
+#ifndef AMULET_MMLIKE_VALU_IMPL_H
+#define AMULET_MMLIKE_VALU_IMPL_H
+
+namespace amulet {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(4))) float *sptr_f;      // read through the scalar cache
+
+template <int TASK> struct AccT { typedef float type; };
+template <> struct AccT<TASK_COUNT_GT> { typedef int type; };
+
+// Four products of one A value with a lane's group of four B values, folded
+// into the (partial) accumulators.  The multiply is a separately rounded fp32
+// operation wherever a comparison depends on it.  The four compares are issued
+// back to back before the four selects, so each select is at least three
+// instructions behind the compare whose mask it reads (the distance gfx950
+// wants between a VALU write of a lane mask and its VALU read).
+template <int TASK>
+__device__ __forceinline__ void fold4(float a, f4 b, const float *th, const float *q,
+                                      typename AccT<TASK>::type *acc)
+{
+    if constexpr (TASK == TASK_IDENTITY) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_fmaf(a, b[c], acc[c]);
+    } else if constexpr (TASK == TASK_DISCOUNT) {
+        float p[4], s[4];
+        bool m[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) p[c] = a * b[c];          // one RN multiply (contraction is off)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) m[c] = p[c] > th[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s[c] = m[c] ? q[c] : 1.0f;  // q = 1 - dis[j]
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_fmaf(p[c], s[c], acc[c]);
+    } else if constexpr (TASK == TASK_BOOST) {
+        // p + (p > th)(p - th) = p + max(p - th, 0) is continuous in p, so the
+        // unrounded product inside the fused operations is within tolerance.
+        float d[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaf(a, b[c], -th[c]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_fmaf(a, b[c], acc[c]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaxf(d[c], 0.0f);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += d[c];
+    } else {
+        float p[4];
+        bool m[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) p[c] = a * b[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) m[c] = p[c] > th[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += m[c] ? 1 : 0;
+    }
+}
+
+template <int TASK, int TM, int NG, int NW, int BK, int KA>
+__global__ void __launch_bounds__(64 * NW)
+mmlike_valu_kernel(const MmlikeArgs args)
+{
+    typedef typename AccT<TASK>::type acc_t;
+    constexpr int BN = 256 * NG;           // tile columns
+    constexpr int NT = 64 * NW;            // threads
+    constexpr int F4_PER_ROW = BN / 4;     // float4 slots in one LDS row
+    constexpr int LOADS = (BK * F4_PER_ROW) / NT;  // float4 slots staged per thread per tile
+    static_assert((BK * F4_PER_ROW) % NT == 0, "B tile must split evenly over the threads");
+    static_assert(BK % KA == 0 && (KA == 2 || KA == 4), "A is fetched KA k at a time");
+    typedef float av_raw __attribute__((ext_vector_type(KA)));
+    typedef av_raw av_t __attribute__((aligned(4)));
+    typedef const __attribute__((address_space(4))) av_t *sptr_av;
+
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+
+    const int M = args.M, N = args.N, K = args.K;
+    const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned: float4 global accesses
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tiles_m = (M + NW * TM - 1) / (NW * TM);
+    const int tm = blockIdx.x % tiles_m;   // row tiles vary fastest: neighbours share a B panel in L2
+    const int tn = blockIdx.x / tiles_m;
+    const int row0 = tm * (NW * TM) + wave * TM;
+    const int col0 = tn * BN;
+
+    const float *__restrict__ Bg = args.B;
+    const sptr_f As = (sptr_f)args.A;
+
+    // Wave-uniform row offsets, clamped so edge waves read valid rows.
+    int64_t arow[TM];
+#pragma unroll
+    for (int r = 0; r < TM; ++r) {
+        int row = row0 + r;
+        row = row < M ? row : M - 1;
+        arow[r] = (int64_t)row * args.lda;
+    }
+
+    // Per-column parameters held in registers for the whole K loop.
+    float th[NG * 4], q[NG * 4];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int col = col0 + g * 256 + lane * 4 + c;
+            th[g * 4 + c] = __builtin_inff();
+            q[g * 4 + c] = 1.0f;
+            if (TASK != TASK_IDENTITY && col < N) {
+                th[g * 4 + c] = args.params[col];
+                if (TASK == TASK_DISCOUNT)
+                    q[g * 4 + c] = 1.0f - args.params[(int64_t)N + col];
+            }
+        }
+
+    acc_t part[TM][NG * 4];
+    float mainacc[TM][NG * 4];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int c = 0; c < NG * 4; ++c) {
+            part[r][c] = 0;
+            mainacc[r][c] = 0.0f;
+        }
+
+    // ---- B tile staging: global -> registers -> LDS -------------------------
+    f4 stage[LOADS];
+    auto load_tile = [&](int k0, int krows) {
+#pragma unroll
+        for (int it = 0; it < LOADS; ++it) {
+            const int f = threadIdx.x + it * NT;
+            const int kk = f / F4_PER_ROW;
+            const int col = col0 + (f % F4_PER_ROW) * 4;
+            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (kk < krows) {
+                const float *src = Bg + (int64_t)(k0 + kk) * args.ldb + col;
+                if (VEC && col + 3 < N) {
+                    v = *(const f4 *)src;
+                } else {
+                    if (col + 0 < N) v.x = src[0];
+                    if (col + 1 < N) v.y = src[1];
+                    if (col + 2 < N) v.z = src[2];
+                    if (col + 3 < N) v.w = src[3];
+                }
+            }
+            stage[it] = v;
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < LOADS; ++it) {
+            const int f = threadIdx.x + it * NT;
+            *(f4 *)&Bs[buf][f / F4_PER_ROW][(f % F4_PER_ROW) * 4] = stage[it];
+        }
+    };
+
+    const int full_tiles = K / BK;
+    const int tail = K - full_tiles * BK;
+    const int n_tiles = full_tiles + (tail ? 1 : 0);
+
+    av_t a_next[TM];
+    if (n_tiles > 0) {
+        load_tile(0, full_tiles > 0 ? BK : tail);
+        store_tile(0);
+        if (full_tiles > 0) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r]);
+        }
+    }
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const int k0 = t * BK;
+        if (t + 1 < n_tiles)
+            load_tile(k0 + BK, (t + 1 < full_tiles) ? BK : tail);
+
+        if (t < full_tiles) {
+#pragma unroll 1
+            for (int kc = 0; kc < BK; kc += KA) {
+                // this chunk's A values; fetch the next chunk's behind them
+                av_t a[TM];
+#pragma unroll
+                for (int r = 0; r < TM; ++r) a[r] = a_next[r];
+                {
+                    int kn = k0 + kc + KA;
+                    kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
+#pragma unroll
+                    for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
+                }
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk) {
+                    f4 b[NG];
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        b[g] = *(const f4 *)&Bs[buf][kc + kk][g * 256 + lane * 4];
+#pragma unroll
+                    for (int r = 0; r < TM; ++r)
+#pragma unroll
+                        for (int g = 0; g < NG; ++g)
+                            fold4<TASK>(a[r][kk], b[g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
+                }
+            }
+        } else {
+            // K remainder: k by k, so no padded product is ever evaluated.
+            for (int kk = 0; kk < tail; ++kk) {
+                float a1[TM];
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+                    a1[r] = As[arow[r] + k0 + kk];
+                f4 b[NG];
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    b[g] = *(const f4 *)&Bs[buf][kk][g * 256 + lane * 4];
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        fold4<TASK>(a1[r], b[g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
+            }
+        }
+
+        // fold the tile's partial sums into the main accumulators
+        if constexpr (TASK != TASK_COUNT_GT) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int c = 0; c < NG * 4; ++c) {
+                    mainacc[r][c] += part[r][c];
+                    part[r][c] = 0;
+                }
+        }
+
+        if (t + 1 < n_tiles)
+            store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- write-back: R += acc, once per tile ---------------------------------
+#pragma unroll
+    for (int r = 0; r < TM; ++r) {
+        const int row = row0 + r;
+        if (row >= M) continue;
+        float *dst_row = args.R + (int64_t)row * args.ldr;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int col = col0 + g * 256 + lane * 4;
+            float v[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                v[c] = (TASK == TASK_COUNT_GT) ? (float)part[r][g * 4 + c] : mainacc[r][g * 4 + c];
+            if (VEC && col + 3 < N) {
+                f4 o = *(f4 *)(dst_row + col);
+                o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+                *(f4 *)(dst_row + col) = o;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (col + c < N) dst_row[col + c] += v[c];
+            }
+        }
+    }
+}
+
+template <int TASK, int TM, int NG, int NW, int BK, int KA>
+static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
+{
+    const int64_t tiles_m = (a.M + NW * TM - 1) / (NW * TM);
+    const int64_t tiles_n = (a.N + 256 * NG - 1) / (256 * NG);
+    if (tiles_m * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * NW);
+    hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+// Shape id = depth index * VALU_TILES + tile index (see amulet_internal.h).
+template <int TASK>
+hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s)
+{
+    switch (shape) {
+    case 0: return launch_one<TASK, 4, 1, 4, 8, 4>(a, s);
+    case 1: return launch_one<TASK, 8, 1, 4, 8, 4>(a, s);
+    case 2: return launch_one<TASK, 8, 2, 4, 8, 4>(a, s);
+    case 3: return launch_one<TASK, 8, 2, 8, 8, 4>(a, s);
+    case 4: return launch_one<TASK, 4, 1, 4, 16, 4>(a, s);
+    case 5: return launch_one<TASK, 8, 1, 4, 16, 4>(a, s);
+    case 6: return launch_one<TASK, 8, 2, 4, 16, 4>(a, s);
+    case 7: return launch_one<TASK, 8, 2, 8, 16, 4>(a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace amulet
+#endif

@@ -1,0 +1,284 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import amulet_workloads as wl
+import oracle
+from parity import TOL_F32, assert_parity_f32
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+NPAR = {0: 0, 1: 2, 2: 1, 3: 1}
+TASKS = [0, 1, 2, 3]
+
+
+@pytest.fixture(scope="module")
+def am():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2305_08872_amd as am
+    am.load_library()  # raises if the HIP library is missing: there is no fallback
+    return am
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def rand_case(task, M, N, K, seed):
+    g = np.random.Generator(np.random.PCG64(seed))
+    A = (g.standard_normal((M, K)) * 2).astype(np.float32)
+    B = (g.standard_normal((K, N)) * 2).astype(np.float32)
+    rows = []
+    if NPAR[task] >= 1:
+        rows.append(g.standard_normal(N).astype(np.float32) * 3)
+    if NPAR[task] == 2:
+        rows.append(g.uniform(0, 1, N).astype(np.float32))
+    params = np.stack(rows) if rows else None
+    R_in = g.standard_normal((M, N)).astype(np.float32) * 5
+    return A, B, params, R_in
+
+
+def run_gpu(am, task, A, B, params, R_in, shape=None):
+    dA, dB, dR = dev(A), dev(B), dev(R_in)
+    dP = dev(params) if params is not None else None
+    if shape is None:
+        am.amulet_mmlike_f32(task, dA, dB, dP, dR)
+    else:
+        am.amulet_mmlike_f32_shape(task, shape, dA, dB, dP, dR)
+    torch.cuda.synchronize()
+    return dR.cpu().numpy()
+
+
+# several tiles in each direction plus ragged tails in M, N and K for every shape
+ODD_SHAPES = [(70, 300, 37), (33, 513, 100), (1, 1, 1), (129, 1030, 77), (5, 257, 16), (64, 512, 8)]
+
+
+@pytest.mark.parametrize("task", TASKS)
+@pytest.mark.parametrize("shape", range(8))
+def test_every_shape_on_ragged_sizes(am, task, shape):
+    for idx, (M, N, K) in enumerate(ODD_SHAPES):
+        A, B, params, R_in = rand_case(task, M, N, K, seed=1000 + 17 * task + idx)
+        print("case", task, shape, M, N, K, flush=True)
+        R_ref, ab, _ = oracle.mmlike_f32(task, A, B, params, R_in)
+        R = run_gpu(am, task, A, B, params, R_in, shape)
+        if task == 3:
+            assert np.array_equal(R, R_ref), (task, shape, M, N, K)
+        else:
+            assert_parity_f32(R, R_ref, ab, R_in, what="task %d shape %d %dx%dx%d" % (task, shape, M, N, K))
+
+
+@pytest.mark.parametrize("task", TASKS)
+def test_strided_and_unaligned_operands(am, task):
+    M, N, K = 45, 301, 53
+    A, B, params, R_in = rand_case(task, M, N, K, seed=77 + task)
+    R_ref, ab, _ = oracle.mmlike_f32(task, A, B, params, R_in)
+    # lda = K + 3, ldb = N + 2 (odd pitch: no 16-byte rows), ldr = N + 5, all sliced from bigger buffers
+    bigA = torch.zeros(M, K + 3, device="cuda"); bigA[:, :K] = dev(A)
+    bigB = torch.full((K, N + 2), 7.0, device="cuda"); bigB[:, :N] = dev(B)
+    bigR = torch.full((M, N + 5), -3.0, device="cuda"); bigR[:, :N] = dev(R_in)
+    dP = dev(params) if params is not None else None
+    am.amulet_mmlike_f32(task, bigA[:, :K], bigB[:, :N], dP, bigR[:, :N])
+    torch.cuda.synchronize()
+    out = bigR.cpu().numpy()
+    assert np.all(out[:, N:] == -3.0)  # nothing written beyond column N
+    if task == 3:
+        assert np.array_equal(out[:, :N], R_ref)
+    else:
+        assert_parity_f32(out[:, :N], R_ref, ab, R_in, what="strided task %d" % task)
+    # offset base pointer: 4-byte but not 16-byte aligned B and R
+    flatB = torch.zeros(K * N + 1, device="cuda"); flatB[1:] = dev(B).reshape(-1)
+    flatR = torch.zeros(M * N + 3, device="cuda"); flatR[3:] = dev(R_in).reshape(-1)
+    am.amulet_mmlike_f32(task, dev(A), flatB[1:].view(K, N), dP, flatR[3:].view(M, N))
+    torch.cuda.synchronize()
+    out2 = flatR[3:].view(M, N).cpu().numpy()
+    if task == 3:
+        assert np.array_equal(out2, R_ref)
+    else:
+        assert_parity_f32(out2, R_ref, ab, R_in, what="unaligned task %d" % task)
+
+
+def test_exact_data_is_bit_exact_for_all_tasks(am):
+    # every product, term and partial sum is a small dyadic rational: any order of
+    # fp32 summation is exact, so the GPU must equal the oracle bit for bit (ties included)
+    for task in TASKS:
+        A, B, params = wl.small_exact(97, 700, 83, seed=5 + task, n_param=NPAR[task])
+        R_in = np.zeros((97, 700), np.float32)
+        R_ref, _, _ = oracle.mmlike_f32(task, A, B, params, R_in)
+        for shape in (0, 3, 7):
+            R = run_gpu(am, task, A, B, params, R_in, shape)
+            assert np.array_equal(R, R_ref), (task, shape)
+
+
+def test_infinite_thresholds_and_zero_result_invariants(am):
+    M, N, K = 40, 520, 130
+    A, B, _, R_in = rand_case(1, M, N, K, seed=9)
+    g = np.random.Generator(np.random.PCG64(10))
+    dis = g.uniform(0, 1, N).astype(np.float32)
+    inf = np.full(N, np.inf, np.float32)
+    R_id = run_gpu(am, 0, A, B, None, R_in)
+    # thres = +inf: discount and boost are plain matmul, count is zero
+    assert np.array_equal(run_gpu(am, 1, A, B, np.stack([inf, dis]), R_in), R_id)
+    R_b = run_gpu(am, 2, A, B, inf[None], R_in)
+    R_ref, ab, _ = oracle.mmlike_f32(0, A, B, None, R_in)
+    assert_parity_f32(R_b, R_ref, ab, R_in, what="boost thres=+inf")
+    assert np.array_equal(run_gpu(am, 3, A, B, inf[None], R_in), R_in)
+    # thres = -inf: count is K; discount with dis = 1 leaves R exactly unchanged
+    assert np.array_equal(run_gpu(am, 3, A, B, -inf[None], np.zeros_like(R_in)), np.full((M, N), K, np.float32))
+    P = np.stack([-inf, np.ones(N, np.float32)])
+    assert np.array_equal(run_gpu(am, 1, A, B, P, R_in), R_in)
+    # boost with thres = -inf is +inf everywhere, as in the oracle
+    R_ref, ab, _ = oracle.mmlike_f32(2, A, B, -inf[None], R_in)
+    assert np.array_equal(run_gpu(am, 2, A, B, -inf[None], R_in), R_ref)
+
+
+def test_negative_thresholds_and_k_tail_without_padding(am):
+    # g(0) = -thres for boost with thres < 0 and 1 for count: a zero-padded K tail would show
+    for K in (1, 7, 17, 31):
+        A = np.zeros((20, K), np.float32)
+        B = np.ones((K, 300), np.float32)
+        th = np.full((1, 300), -2.0, np.float32)
+        R0 = np.zeros((20, 300), np.float32)
+        assert np.array_equal(run_gpu(am, 2, A, B, th, R0), np.full((20, 300), 2.0 * K, np.float32))
+        assert np.array_equal(run_gpu(am, 3, A, B, th, R0), np.full((20, 300), float(K), np.float32))
+
+
+def test_predicate_on_rounded_product(am):
+    a = np.float32(1 + 2.0 ** -12)
+    p32 = np.float32(a * a)
+    A = np.full((3, 5), a, np.float32)
+    B = np.full((5, 260), a, np.float32)
+    th = np.full((1, 260), p32, np.float32)   # exact product exceeds thres, rounded product equals it
+    R0 = np.zeros((3, 260), np.float32)
+    assert not run_gpu(am, 3, A, B, th, R0).any()
+    R = run_gpu(am, 1, A, B, np.concatenate([th, np.full((1, 260), 0.5, np.float32)]), R0)
+    R_ref, _, _ = oracle.mmlike_f32(1, A, B, np.concatenate([th, np.full((1, 260), 0.5, np.float32)]), R0)
+    assert np.array_equal(R, R_ref)
+
+
+def test_empty_dimensions_are_noops(am):
+    R = torch.full((4, 6), 2.5, device="cuda")
+    am.amulet_mmlike_f32(1, torch.zeros(4, 0, device="cuda"), torch.zeros(0, 6, device="cuda"),
+                         torch.zeros(2, 6, device="cuda"), R)
+    torch.cuda.synchronize()
+    assert torch.all(R == 2.5)
+
+
+# ---- join count -----------------------------------------------------------------
+@pytest.mark.parametrize("shape", [None, 0])
+def test_count_i8_bit_exact_ragged(am, shape):
+    for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (1, 1, 1), (257, 129, 1000), (64, 64, 64)]):
+        g = np.random.Generator(np.random.PCG64(300 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        dR = dev(R_in)
+        if shape is None:
+            am.amulet_count_i8(dev(A), dev(B), dR)
+        else:
+            am.amulet_count_i8_shape(shape, dev(A), dev(B), dR)
+        torch.cuda.synchronize()
+        assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
+
+
+def test_count_i8_strided(am):
+    M, N, K = 50, 130, 75
+    A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)
+    R_ref, _ = oracle.count_i8(A, B)
+    bigA = torch.zeros(M, K + 5, dtype=torch.int8, device="cuda"); bigA[:, :K] = dev(A)
+    bigB = torch.ones(K, N + 3, dtype=torch.int8, device="cuda"); bigB[:, :N] = dev(B)
+    bigR = torch.full((M, N + 1), 9, dtype=torch.int32, device="cuda"); bigR[:, :N] = 0
+    am.amulet_count_i8(bigA[:, :K], bigB[:, :N], bigR[:, :N])
+    torch.cuda.synchronize()
+    out = bigR.cpu().numpy()
+    assert np.array_equal(out[:, :N], R_ref) and np.all(out[:, N] == 9)
+
+
+# ---- the named workloads ----------------------------------------------------------
+def test_cfg0_discount_256_full(am):
+    spec, A, B, P = wl.make("cfg0_discount_256")
+    R_ref, ab, _ = oracle.mmlike_f32(spec["task"], A, B, P)
+    R = run_gpu(am, spec["task"], A, B, P, np.zeros_like(R_ref))
+    assert_parity_f32(R, R_ref, ab, what="cfg0")
+
+
+def test_cfg1_boost_2048_full(am):
+    spec, A, B, P = wl.make("cfg1_boost_2048")
+    R = run_gpu(am, spec["task"], A, B, P, np.zeros((2048, 2048), np.float32))
+    print("cfg1: oracle on the full 2048^3 matrix", flush=True)
+    R_ref, ab, _ = oracle.mmlike_f32(spec["task"], A, B, P)
+    assert_parity_f32(R, R_ref, ab, what="cfg1")
+
+
+def _sampled_rows_cols(am, name, n_rows=24, n_cols=24):
+    """Full-size run in the default launch configuration; the oracle recomputes a
+    seeded sample of whole rows and whole columns one by one."""
+    spec, A, B, P = wl.make(name)
+    M, N, K = spec["M"], spec["N"], spec["K"]
+    print(name, "gpu run", flush=True)
+    R = run_gpu(am, spec["task"], A, B, P, np.zeros((M, N), np.float32))
+    g = np.random.Generator(np.random.PCG64(4242))
+    rows = np.sort(g.choice(M, n_rows, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, n_cols, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    print(name, "oracle rows", flush=True)
+    R_ref, ab, _ = oracle.mmlike_f32(spec["task"], np.ascontiguousarray(A[rows]), B, P)
+    w1 = assert_parity_f32(R[rows], R_ref, ab, what=name + " rows")
+    print(name, "oracle cols", flush=True)
+    Pc = None if P is None else np.ascontiguousarray(P[:, cols])
+    R_ref, ab, _ = oracle.mmlike_f32(spec["task"], A, np.ascontiguousarray(B[:, cols]), Pc)
+    w2 = assert_parity_f32(R[:, cols], R_ref, ab, what=name + " cols")
+    print(name, "worst ratio", max(w1, w2), flush=True)
+    return R, A, B, P
+
+
+def test_cfg2_identity_4096_sampled(am):
+    R, A, B, _ = _sampled_rows_cols(am, "cfg2_identity_4096")
+    # whole-matrix property: column sums of R equal (column sums of A) @ B
+    ref = A.astype(np.float64).sum(0) @ B.astype(np.float64)
+    scale = np.abs(A).astype(np.float64).sum(0) @ np.abs(B).astype(np.float64)
+    assert np.max(np.abs(R.astype(np.float64).sum(0) - ref) / scale) < 1e-5
+
+
+def test_cfg4_discount_rect_sampled(am):
+    _sampled_rows_cols(am, "cfg4_discount_16384x2048x8192", n_rows=12, n_cols=6)
+
+
+def test_headline_discount_8192_sampled(am):
+    _sampled_rows_cols(am, "headline_discount_8192", n_rows=12, n_cols=12)
+
+
+def test_cfg3_join_count_full_size_sampled(am):
+    spec, A, B, _ = wl.make("cfg3_count_i8_8192x8192x4096")
+    M, N = spec["M"], spec["N"]
+    dR = torch.zeros(M, N, dtype=torch.int32, device="cuda")
+    am.amulet_count_i8(dev(A), dev(B), dR)
+    torch.cuda.synchronize()
+    R = dR.cpu().numpy()
+    g = np.random.Generator(np.random.PCG64(4243))
+    rows = np.sort(g.choice(M, 32, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 32, replace=False)); cols[0], cols[-1] = 0, N - 1
+    R_ref, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B)
+    assert np.array_equal(R[rows], R_ref)
+    R_ref, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]))
+    assert np.array_equal(R[:, cols], R_ref)
+    # whole-matrix checksum: sum_j R[i][j] = sum_k A[i][k] * (sum_j B[k][j]), exact in int64
+    assert np.array_equal(R.astype(np.int64).sum(1), A.astype(np.int64) @ B.astype(np.int64).sum(1))
+    assert np.array_equal(R.astype(np.int64).sum(0), A.astype(np.int64).sum(0) @ B.astype(np.int64))
+
+
+def test_tune_picks_a_valid_shape_and_result_still_matches(am):
+    M, N, K = 512, 1024, 256
+    chosen = am.amulet_tune(1, M, N, K)
+    assert 0 <= chosen < am.amulet_shape_count(1)
+    assert am.amulet_selected_shape(1, M, N, K) == chosen
+    A, B, P = wl.retail(M, N, K, seed=21)
+    R_ref, ab, _ = oracle.mmlike_f32(1, A, B, P)
+    R = run_gpu(am, 1, A, B, P, np.zeros_like(R_ref))
+    assert_parity_f32(R, R_ref, ab, what="after tune")
+    am.amulet_clear_selections()

@@ -1,0 +1,110 @@
+"""CPU-side checks of the library: it loads, exports the declared symbols, and its
+host logic (argument errors, greedy search, register rule) behaves as the paper states."""
+import ctypes
+import json
+import os
+import re
+
+import pytest
+
+import paper_2305_08872_amd as am
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(am.library_path()):
+        from paper_2305_08872_amd import build
+        build.build()
+    return am.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "amulet.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(amulet_[a-z0-9_]+)\s*\(", header))
+    names.discard("amulet_score_fn")
+    assert {"amulet_mmlike_f32", "amulet_count_i8", "amulet_tune", "amulet_strerror"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), "libamulet.so does not export " + n
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    f = lib.amulet_mmlike_f32
+    one = ctypes.c_void_p(16)  # never dereferenced: every call below fails validation first
+    assert f(9, 1, 1, 1, one, 1, one, 1, one, one, 1, None) == -1
+    assert f(1, -1, 1, 1, one, 1, one, 1, one, one, 1, None) == -2
+    assert f(1, 1, 1, 1, None, 1, one, 1, one, one, 1, None) == -3
+    assert f(1, 1, 1, 1, one, 1, one, 1, None, one, 1, None) == -3   # discount needs params
+    assert f(1, 2, 3, 4, one, 3, one, 3, one, one, 3, None) == -4    # lda < K
+    assert f(1, 2, 3, 4, one, 4, one, 2, one, one, 3, None) == -4    # ldb < N
+    assert f(1, 2, 3, 4, one, 4, one, 3, one, one, 2, None) == -4    # ldr < N
+    assert f(1, 2 ** 31, 3, 4, one, 4, one, 3, one, one, 3, None) == -7
+    assert f(1, 0, 3, 4, None, 4, None, 3, None, None, 3, None) == 0  # empty: no-op
+    assert lib.amulet_mmlike_f32_shape(1, 99, 2, 3, 4, one, 4, one, 3, one, one, 3, None) == -6
+    g = lib.amulet_count_i8
+    assert g(2, 3, 4, one, 3, one, 3, one, 3, None) == -4
+    assert g(2, 3, 4, None, 4, one, 3, one, 3, None) == -3
+    assert g(2, 3, 0, None, 4, None, 3, None, 3, None) == 0
+    assert am.amulet_strerror(-4).startswith("leading dimension")
+    assert lib.amulet_tune(55, 8, 8, 8, None) == -1
+
+
+@pytest.fixture(scope="module")
+def table1(golden_dir):
+    with open(os.path.join(golden_dir, "table1_kc_nc_seconds.json")) as f:
+        return json.load(f)
+
+
+@pytest.mark.parametrize("machine", ["machine1", "machine2"])
+def test_greedy_search_reproduces_table1_choice(lib, table1, machine):
+    """Feeding the paper's measured k_c x n_c grid as the timer, the two-stage
+    search must land on the parameters the paper says it finds."""
+    grid = table1[machine]["seconds"]
+    axis = table1["axis"]
+    calls = []
+
+    def score(i0, i1):
+        calls.append((i0, i1))
+        return grid[i0][i1]
+
+    b0, b1, n = am.amulet_greedy_search(len(axis), len(axis), score)
+    assert (axis[b0], axis[b1]) == tuple(table1[machine]["paper_choice"])
+    assert n == len(calls)
+    # stage 1 visits the whole first column, stage 2 stops at the first increase
+    assert calls[:len(axis)] == [(i, 0) for i in range(len(axis))]
+    assert len(calls) == len(axis) + b1 + (1 if b1 + 1 < len(axis) else 0)
+
+
+def test_greedy_search_edge_cases(lib):
+    assert am.amulet_greedy_search(1, 1, lambda a, b: 1.0)[:2] == (0, 0)
+    # monotone improvement along axis 1 walks to the end
+    assert am.amulet_greedy_search(3, 4, lambda a, b: 10 - a - b)[:2] == (2, 3)
+    with pytest.raises(am.AmuletError):
+        am.amulet_greedy_search(0, 3, lambda a, b: 0.0)
+
+
+def test_register_rule_matches_paper_worked_example(lib, golden_dir):
+    with open(os.path.join(golden_dir, "register_count_example.json")) as f:
+        ex = json.load(f)
+    a = ex["args"]
+    need = am.amulet_register_demand(ex["I_h"], ex["I_w"], ex["S_w"], a["n_const"], a["n_i"], a["n_j"],
+                                     a["n_ij"], a["n_temp"])
+    assert need == ex["demand_12x16"]
+    assert am.amulet_register_demand(11, ex["I_w"], ex["S_w"], a["n_const"], a["n_i"], a["n_j"],
+                                     a["n_ij"], a["n_temp"]) == ex["demand_11x16"]
+    assert am.amulet_choose_kernel_height(12, ex["I_w"], ex["S_w"], a["n_const"], a["n_i"], a["n_j"],
+                                          a["n_ij"], a["n_temp"], ex["budget"]) == ex["chosen_I_h"]
+    # plain matmul: 12*2 + 1 + 2 = 27 <= 32, the full 12x16 kernel fits (Sec. 3 inequality)
+    assert am.amulet_register_demand(12, 16, 8, 0, 0, 0, 0, 0) == 27
+    assert am.amulet_choose_kernel_height(12, 16, 8, 0, 0, 0, 0, 0, 32) == 12
+
+
+def test_shape_table_is_the_two_axis_grid(lib):
+    n = am.amulet_shape_count(am.AMULET_DISCOUNT)
+    assert n == 8 and am.amulet_shape_count(77) == 0
+    names = [am.amulet_shape_name(1, i) for i in range(n)]
+    assert len(set(names)) == n and all(x.startswith("valu_") for x in names)
+    assert 0 <= am.amulet_selected_shape(1, 8192, 8192, 8192) < n
+    assert am.amulet_shape_count(am.AMULET_TASK_COUNT_I8) >= 1
