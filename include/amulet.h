@@ -162,6 +162,10 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
 /* Printable text for a status code (static storage). */
 const char *amulet_strerror(int code);
 
+/* HIP's text for the error behind the calling thread's last AMULET_ERR_LAUNCH
+ * ("no error" if its last launch succeeded).  Static storage. */
+const char *amulet_last_launch_error(void);
+
 /* Library version string (static storage). */
 const char *amulet_version(void);
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     amulet_count_i8,
     amulet_count_i8_shape,
     amulet_greedy_search,
+    amulet_last_launch_error,
     amulet_mmlike_f32,
     amulet_mmlike_f32_shape,
     amulet_register_demand,

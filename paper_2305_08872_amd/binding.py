@@ -22,7 +22,10 @@ _lib = None
 class AmuletError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__("%s failed: %s (status %d)" % (where, amulet_strerror(code), code))
+        detail = ""
+        if code == -5 and _lib is not None:
+            detail = ": " + _lib.amulet_last_launch_error().decode()
+        super().__init__("%s failed: %s (status %d)%s" % (where, amulet_strerror(code), code, detail))
 
 
 def library_path() -> str:
@@ -39,6 +42,10 @@ def load_library():
             "libamulet.so is missing at %s: build it with "
             "`python -m paper_2305_08872_amd.build` (needs hipcc); there is no fallback path"
             % _LIB_PATH)
+    # torch ships its own HIP runtime (same soname as the system one): import it
+    # first so that libamulet.so binds to the runtime torch's allocations and
+    # streams live in, instead of bringing a second runtime into the process.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
     lib.amulet_mmlike_f32.restype = i32
@@ -68,6 +75,8 @@ def load_library():
     lib.amulet_choose_kernel_height.argtypes = [i32] * 9
     lib.amulet_strerror.restype = ctypes.c_char_p
     lib.amulet_strerror.argtypes = [i32]
+    lib.amulet_last_launch_error.restype = ctypes.c_char_p
+    lib.amulet_last_launch_error.argtypes = []
     lib.amulet_version.restype = ctypes.c_char_p
     lib.amulet_version.argtypes = []
     _lib = lib
@@ -207,6 +216,10 @@ def amulet_strerror(code: int) -> str:
     if _lib is None and not os.path.exists(_LIB_PATH):
         return "status %d" % code
     return load_library().amulet_strerror(code).decode()
+
+
+def amulet_last_launch_error() -> str:
+    return load_library().amulet_last_launch_error().decode()
 
 
 def amulet_version() -> str:

@@ -62,6 +62,9 @@ static int lookup_shape(int task, int64_t M, int64_t N, int64_t K)
     return default_shape(task, M, N, K);
 }
 
+// text of the last HIP error a launch reported (diagnostics for AMULET_ERR_LAUNCH)
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+
 static const int64_t kMaxDim = 2147483647LL - 65536LL;
 
 static int check_common(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
@@ -94,6 +97,7 @@ static int run_mmlike(int task, int shape, int64_t M, int64_t N, int64_t K, cons
     case TASK_BOOST: e = launch_mmlike_valu_task<TASK_BOOST>(shape, a, s); break;
     default: e = launch_mmlike_valu_task<TASK_COUNT_GT>(shape, a, s); break;
     }
+    g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
 }
 
@@ -105,6 +109,7 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.lda = lda; a.ldb = ldb; a.ldr = ldr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
+    g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
 }
 
@@ -373,6 +378,8 @@ const char *amulet_strerror(int code)
     default: return "unknown status code";
     }
 }
+
+const char *amulet_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char *amulet_version(void) { return "amulet-gfx950 0.1"; }
 

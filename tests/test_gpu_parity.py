@@ -119,12 +119,12 @@ def test_infinite_thresholds_and_zero_result_invariants(am):
     g = np.random.Generator(np.random.PCG64(10))
     dis = g.uniform(0, 1, N).astype(np.float32)
     inf = np.full(N, np.inf, np.float32)
-    R_id = run_gpu(am, 0, A, B, None, R_in)
-    # thres = +inf: discount and boost are plain matmul, count is zero
-    assert np.array_equal(run_gpu(am, 1, A, B, np.stack([inf, dis]), R_in), R_id)
-    R_b = run_gpu(am, 2, A, B, inf[None], R_in)
+    # thres = +inf: discount and boost are plain matmul (the oracle's identity result), count is zero
     R_ref, ab, _ = oracle.mmlike_f32(0, A, B, None, R_in)
-    assert_parity_f32(R_b, R_ref, ab, R_in, what="boost thres=+inf")
+    assert_parity_f32(run_gpu(am, 0, A, B, None, R_in), R_ref, ab, R_in, what="identity")
+    assert_parity_f32(run_gpu(am, 1, A, B, np.stack([inf, dis]), R_in), R_ref, ab, R_in,
+                      what="discount thres=+inf")
+    assert_parity_f32(run_gpu(am, 2, A, B, inf[None], R_in), R_ref, ab, R_in, what="boost thres=+inf")
     assert np.array_equal(run_gpu(am, 3, A, B, inf[None], R_in), R_in)
     # thres = -inf: count is K; discount with dis = 1 leaves R exactly unchanged
     assert np.array_equal(run_gpu(am, 3, A, B, -inf[None], np.zeros_like(R_in)), np.full((M, N), K, np.float32))
