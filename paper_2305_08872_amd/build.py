@@ -24,6 +24,7 @@ SOURCES = [
     "mmlike_valu_discount.hip",
     "mmlike_valu_boost.hip",
     "mmlike_valu_count_gt.hip",
+    "identity_mfma.hip",
     "count_i8.hip",
 ]
 

@@ -17,10 +17,10 @@
 namespace amulet {
 
 const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
-    {4, 1, 4, 8, "valu_16x256_k8"},   {8, 1, 4, 8, "valu_32x256_k8"},
-    {8, 2, 4, 8, "valu_32x512_k8"},   {8, 2, 8, 8, "valu_64x512_k8"},
-    {4, 1, 4, 16, "valu_16x256_k16"}, {8, 1, 4, 16, "valu_32x256_k16"},
-    {8, 2, 4, 16, "valu_32x512_k16"}, {8, 2, 8, 16, "valu_64x512_k16"},
+    {4, 1, 4, 8, "valu_16x256_k8"},   {4, 1, 8, 8, "valu_32x256_w8_k8"},
+    {8, 1, 8, 8, "valu_64x256_k8"},   {8, 2, 8, 8, "valu_64x512_k8"},
+    {4, 1, 4, 16, "valu_16x256_k16"}, {4, 1, 8, 16, "valu_32x256_w8_k16"},
+    {8, 1, 8, 16, "valu_64x256_k16"}, {8, 2, 8, 16, "valu_64x512_k16"},
 };
 
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple"};
@@ -32,7 +32,8 @@ static std::map<SelKey, int> g_selected;
 
 static int n_shapes(int task)
 {
-    if (task >= TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
+    if (task == TASK_IDENTITY) return VALU_SHAPE_COUNT + 1;  // plus the matrix-core kernel
+    if (task > TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
     if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
     return 0;
 }
@@ -42,6 +43,7 @@ static int n_shapes(int task)
 static int default_shape(int task, int64_t M, int64_t N, int64_t)
 {
     if (task == AMULET_TASK_COUNT_I8) return 0;
+    if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
     const int64_t want = 2 * 256;
     for (int t = VALU_TILES - 1; t > 0; --t) {
         const ValuShapeDesc &d = kValuShapes[VALU_TILES + t];
@@ -89,10 +91,14 @@ static int run_mmlike(int task, int shape, int64_t M, int64_t N, int64_t K, cons
     a.lda = lda; a.ldb = ldb; a.ldr = ldr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
     a.vec = (aligned16(B) && aligned16(R) && ldb % 4 == 0 && ldr % 4 == 0) ? 1 : 0;
+    a.vecA = (aligned16(A) && lda % 4 == 0) ? 1 : 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (task) {
-    case TASK_IDENTITY: e = launch_mmlike_valu_task<TASK_IDENTITY>(shape, a, s); break;
+    case TASK_IDENTITY:
+        e = shape == IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, s)
+                                         : launch_mmlike_valu_task<TASK_IDENTITY>(shape, a, s);
+        break;
     case TASK_DISCOUNT: e = launch_mmlike_valu_task<TASK_DISCOUNT>(shape, a, s); break;
     case TASK_BOOST: e = launch_mmlike_valu_task<TASK_BOOST>(shape, a, s); break;
     default: e = launch_mmlike_valu_task<TASK_COUNT_GT>(shape, a, s); break;
@@ -185,7 +191,7 @@ int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K
                             int64_t ldr, void *stream)
 {
     if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
-    if (shape < 0 || shape >= VALU_SHAPE_COUNT) return AMULET_ERR_SHAPE;
+    if (shape < 0 || shape >= n_shapes(task)) return AMULET_ERR_SHAPE;
     const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
     if (rc < 0) return rc;
     if (rc == 1) return AMULET_OK;
@@ -308,6 +314,9 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
             int b0 = 0, b1 = 0;
             amulet_greedy_search(VALU_DEPTHS, VALU_TILES, valu_trial_score, &c, &b0, &b1);
             chosen = b0 * VALU_TILES + b1;
+            if (task == TASK_IDENTITY &&
+                time_shape(&c, IDENTITY_MFMA_SHAPE) < time_shape(&c, chosen))
+                chosen = IDENTITY_MFMA_SHAPE;
         }
         (void)hipStreamSynchronize(c.stream);
         if (c.status == AMULET_OK) {
@@ -327,7 +336,9 @@ int amulet_shape_count(int task) { return n_shapes(task); }
 const char *amulet_shape_name(int task, int shape)
 {
     if (shape < 0 || shape >= n_shapes(task)) return "invalid";
-    return task == AMULET_TASK_COUNT_I8 ? kCountShapeNames[shape] : kValuShapes[shape].name;
+    if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
+    if (shape == IDENTITY_MFMA_SHAPE) return "mfma_f32_128x128_k16";
+    return kValuShapes[shape].name;
 }
 
 int amulet_selected_shape(int task, int64_t M, int64_t N, int64_t K)

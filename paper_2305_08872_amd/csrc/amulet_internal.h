@@ -18,15 +18,16 @@ struct MmlikeArgs {
     float *R;
     int64_t lda, ldb, ldr;
     int M, N, K;
-    int vec;  // 1 when B, R and their row pitches allow 16-byte vector accesses
+    int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
+    int vecA;  // 1 when A and its row pitch do
 };
 
 // Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy
 // parameter search walks (paper Sec. 4.4): axis 0 is the depth BK of the B tile
 // staged per barrier (the k_c analogue), axis 1 the workgroup's R tile from
 // narrow to wide (the n_c analogue).  shape id = depth index * VALU_TILES + tile.
-//   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 8x4, 4 waves -> 32 x 256
-//   tile 2: 8x8 per lane, 4 waves  -> 32 x 512      tile 3: 8x8, 8 waves -> 64 x 512
+//   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 4x4, 8 waves -> 32 x 256
+//   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 8x8, 8 waves -> 64 x 512
 enum { VALU_DEPTHS = 2, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES };
 
 struct ValuShapeDesc {
@@ -45,6 +46,10 @@ struct CountArgs {
 };
 enum { COUNT_SHAPE_COUNT = 1 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
+
+// Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.
+enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT };
+hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s);
 
 template <int TASK>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);

@@ -1,0 +1,169 @@
+// Identity task (g = p, plain matmul; paper Sec. 6.1) on the fp32 matrix cores.
+// With no per-product step this one task is a dense contraction, so it runs as
+// v_mfma_f32_32x32x2_f32 tiles instead of the vector-ALU micro-tiles.
+//
+// Workgroup: 256 threads = 4 waves in a 2x2 grid, R tile 128 x 128, each wave a
+// 64 x 64 sub-tile = 2x2 MFMA blocks of 32 x 32 (64 accumulator registers).
+// K is staged 16 at a time: A tile 128 x 16 (k contiguous, row pitch padded to
+// 20 floats so 16-byte fragment reads spread over all banks) and B tile
+// 16 x 128 (as in global memory), global -> registers -> LDS, double buffered,
+// one barrier per stage.
+//
+// Fragment mapping: lane l supplies row i = l % 32 (A) or column j = l % 32 (B)
+// and k-slot h = l / 32.  The hardware multiplies A's slot h with B's slot h,
+// so which k a slot carries is free as long as both operands agree: per group
+// of 8 k, slot h of MFMA t carries k = 4h + t.  A lane then reads its four A
+// values of a group as one ds_read_b128.
+//
+// Rows/columns beyond M/N and the K remainder are zero-filled in LDS: for the
+// identity task a zero product adds nothing (this is NOT true of the predicate
+// tasks, which never take this path).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "amulet_internal.h"
+
+namespace amulet {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int MI_BM = 128, MI_BN = 128, MI_BK = 16;
+constexpr int MI_APITCH = MI_BK + 4;   // floats
+
+__global__ void __launch_bounds__(256)
+identity_mfma_kernel(const MmlikeArgs args)
+{
+    __shared__ __attribute__((aligned(16))) float As[2][MI_BM][MI_APITCH];
+    __shared__ __attribute__((aligned(16))) float Bs[2][MI_BK][MI_BN];
+
+    const int M = args.M, N = args.N, K = args.K;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const int tiles_m = (M + MI_BM - 1) / MI_BM;
+    const int tm = blockIdx.x % tiles_m;
+    const int tn = blockIdx.x / tiles_m;
+    const int row0 = tm * MI_BM, col0 = tn * MI_BN;
+    const bool vecA = args.vecA != 0, vecB = args.vec != 0;
+
+    // staging slots: A tile 128 rows x 4 float4, thread -> (row = tid / 4 + 64*it, kq = tid % 4)
+    //                B tile 16 rows x 32 float4, thread -> (k = tid / 32 + 8*it, cq = tid % 32)
+    f4 sa[2], sb[2];
+    auto load_stage = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int r = row0 + (tid >> 2) + 64 * it;
+            const int k = k0 + (tid & 3) * 4;
+            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (r < M) {
+                const float *src = args.A + (int64_t)r * args.lda + k;
+                if (vecA && k + 3 < K) {
+                    v = *(const f4 *)src;
+                } else {
+                    if (k + 0 < K) v.x = src[0];
+                    if (k + 1 < K) v.y = src[1];
+                    if (k + 2 < K) v.z = src[2];
+                    if (k + 3 < K) v.w = src[3];
+                }
+            }
+            sa[it] = v;
+        }
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int k = k0 + (tid >> 5) + 8 * it;
+            const int c = col0 + (tid & 31) * 4;
+            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (k < K) {
+                const float *src = args.B + (int64_t)k * args.ldb + c;
+                if (vecB && c + 3 < N) {
+                    v = *(const f4 *)src;
+                } else {
+                    if (c + 0 < N) v.x = src[0];
+                    if (c + 1 < N) v.y = src[1];
+                    if (c + 2 < N) v.z = src[2];
+                    if (c + 3 < N) v.w = src[3];
+                }
+            }
+            sb[it] = v;
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            *(f4 *)&As[buf][(tid >> 2) + 64 * it][(tid & 3) * 4] = sa[it];
+            *(f4 *)&Bs[buf][(tid >> 5) + 8 * it][(tid & 31) * 4] = sb[it];
+        }
+    };
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const int n_stages = (K + MI_BK - 1) / MI_BK;
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+
+    for (int s = 0; s < n_stages; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < n_stages) load_stage((s + 1) * MI_BK);
+#pragma unroll
+        for (int kb = 0; kb < MI_BK; kb += 8) {
+            f4 a[2];
+            float b[2][4];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                a[mi] = *(const f4 *)&As[buf][wr * 64 + mi * 32 + li][kb + 4 * lh];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    b[ni][t] = Bs[buf][kb + 4 * lh + t][wc * 64 + ni * 32 + li];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][t], b[ni][t], acc[mi][ni], 0, 0, 0);
+        }
+        if (s + 1 < n_stages) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int col = col0 + wc * 64 + ni * 32 + li;
+            if (col >= N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < M) {
+                    float *dst = args.R + (int64_t)row * args.ldr + col;
+                    *dst += acc[mi][ni][v];
+                }
+            }
+        }
+}
+
+hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s)
+{
+    const int64_t tiles_m = (a.M + MI_BM - 1) / MI_BM;
+    const int64_t tiles_n = (a.N + MI_BN - 1) / MI_BN;
+    if (tiles_m * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(identity_mfma_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace amulet

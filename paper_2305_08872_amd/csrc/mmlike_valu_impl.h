@@ -17,9 +17,10 @@
 //   * the BK x (256*NG) tile of B is staged global -> registers -> LDS, double
 //     buffered, one barrier per tile; a lane reads its own 16-byte column groups
 //     back with conflict-free ds_read_b128.
-//   * the k-sum is two-level: a partial accumulator per BK tile, folded into
-//     the main accumulator after each tile, which keeps fp32 round-off of long
-//     same-sign sums (K = 8192 retail data) far inside the 1e-5 budget.
+//   * the k-sum is two-level: a partial accumulator over FLUSH_K products,
+//     folded into the main accumulator after that many, which keeps fp32
+//     round-off of long same-sign sums (K = 8192 retail data) far inside the
+//     1e-5 budget.
 //   * the K remainder is computed by a k-by-k tail loop, never by zero padding:
 //     g(0) is not 0 in general (BOOST with thres < 0, COUNT_GT with thres < 0).
 //
@@ -35,6 +36,9 @@
 #define AMULET_MMLIKE_VALU_IMPL_H
 
 namespace amulet {
+
+// k-extent of one partial sum of the two-level fp32 accumulation
+constexpr int FLUSH_K = 64;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(4))) float *sptr_f;      // read through the scalar cache
@@ -156,82 +160,111 @@ mmlike_valu_kernel(const MmlikeArgs args)
         }
 
     // ---- B tile staging: global -> registers -> LDS -------------------------
+    // Thread t stages float4 slot (row t / F4_PER_ROW + it * ROWS_PER_PASS, column group
+    // t % F4_PER_ROW) of every tile.  Interior tiles (all columns inside N, rows 16-byte
+    // aligned, BK full rows) take the branch-free path.
+    constexpr int ROWS_PER_PASS = NT / F4_PER_ROW;
+    static_assert(NT % F4_PER_ROW == 0 && LOADS * ROWS_PER_PASS == BK, "slot mapping");
+    const int srow = threadIdx.x / F4_PER_ROW;
+    const int scol = col0 + (threadIdx.x % F4_PER_ROW) * 4;
+    const bool fast_cols = VEC && (col0 + BN <= N);
+    const float *bsrc = Bg + (int64_t)srow * args.ldb + scol;   // advanced by BK rows per tile
+    const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
+    const int64_t tile_stride = (int64_t)BK * args.ldb;
     f4 stage[LOADS];
-    auto load_tile = [&](int k0, int krows) {
+    auto load_tile = [&](int krows) {
+        if (fast_cols && krows == BK) {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it) {
-            const int f = threadIdx.x + it * NT;
-            const int kk = f / F4_PER_ROW;
-            const int col = col0 + (f % F4_PER_ROW) * 4;
-            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (kk < krows) {
-                const float *src = Bg + (int64_t)(k0 + kk) * args.ldb + col;
-                if (VEC && col + 3 < N) {
-                    v = *(const f4 *)src;
-                } else {
-                    if (col + 0 < N) v.x = src[0];
-                    if (col + 1 < N) v.y = src[1];
-                    if (col + 2 < N) v.z = src[2];
-                    if (col + 3 < N) v.w = src[3];
+            for (int it = 0; it < LOADS; ++it)
+                stage[it] = *(const f4 *)(bsrc + it * pass_stride);
+        } else {
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it) {
+                f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (srow + it * ROWS_PER_PASS < krows) {
+                    const float *src = bsrc + it * pass_stride;
+                    if (scol + 0 < N) v.x = src[0];
+                    if (scol + 1 < N) v.y = src[1];
+                    if (scol + 2 < N) v.z = src[2];
+                    if (scol + 3 < N) v.w = src[3];
                 }
+                stage[it] = v;
             }
-            stage[it] = v;
         }
+        bsrc += tile_stride;
     };
+    float *const bdst = &Bs[0][srow][(threadIdx.x % F4_PER_ROW) * 4];
     auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it) {
-            const int f = threadIdx.x + it * NT;
-            *(f4 *)&Bs[buf][f / F4_PER_ROW][(f % F4_PER_ROW) * 4] = stage[it];
+        for (int it = 0; it < LOADS; ++it)
+            *(f4 *)(bdst + (buf * BK + it * ROWS_PER_PASS) * BN) = stage[it];
+    };
+    auto flush = [&]() {
+        if constexpr (TASK != TASK_COUNT_GT) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int c = 0; c < NG * 4; ++c) {
+                    mainacc[r][c] += part[r][c];
+                    part[r][c] = 0;
+                }
         }
     };
 
     const int full_tiles = K / BK;
     const int tail = K - full_tiles * BK;
     const int n_tiles = full_tiles + (tail ? 1 : 0);
+    constexpr int FLUSH_TILES = (FLUSH_K / BK) > 0 ? (FLUSH_K / BK) : 1;  // tiles per partial sum
 
     av_t a_next[TM];
-    if (n_tiles > 0) {
-        load_tile(0, full_tiles > 0 ? BK : tail);
-        store_tile(0);
-        if (full_tiles > 0) {
+    load_tile(full_tiles > 0 ? BK : tail);
+    store_tile(0);
+    if (full_tiles > 0) {
 #pragma unroll
-            for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r]);
-        }
+        for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r]);
     }
     __syncthreads();
 
+    const float *bs_lane = &Bs[0][0][lane * 4];
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int k0 = t * BK;
         if (t + 1 < n_tiles)
-            load_tile(k0 + BK, (t + 1 < full_tiles) ? BK : tail);
+            load_tile((t + 1 < full_tiles) ? BK : tail);
+        const float *bs = bs_lane + buf * (BK * BN);
 
         if (t < full_tiles) {
 #pragma unroll 1
             for (int kc = 0; kc < BK; kc += KA) {
-                // this chunk's A values; fetch the next chunk's behind them
+                // B values of the whole chunk first, so that one wait covers them ...
+                f4 b[KA][NG];
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        b[kk][g] = *(const f4 *)(bs + (kc + kk) * BN + g * 256);
                 av_t a[TM];
 #pragma unroll
                 for (int r = 0; r < TM; ++r) a[r] = a_next[r];
+                // ... and the scalar fetch of the next chunk's A values is issued only after
+                // that wait: scalar loads return out of order, so any later LDS wait would
+                // have to drain them too.  Here they have the whole chunk's arithmetic to land.
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), vmcnt and expcnt untouched
+                __builtin_amdgcn_sched_barrier(0);
                 {
                     int kn = k0 + kc + KA;
                     kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
 #pragma unroll
                     for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
                 }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kk = 0; kk < KA; ++kk) {
-                    f4 b[NG];
-#pragma unroll
-                    for (int g = 0; g < NG; ++g)
-                        b[g] = *(const f4 *)&Bs[buf][kc + kk][g * 256 + lane * 4];
+                for (int kk = 0; kk < KA; ++kk)
 #pragma unroll
                     for (int r = 0; r < TM; ++r)
 #pragma unroll
                         for (int g = 0; g < NG; ++g)
-                            fold4<TASK>(a[r][kk], b[g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
-                }
+                            fold4<TASK>(a[r][kk], b[kk][g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
             }
         } else {
             // K remainder: k by k, so no padded product is ever evaluated.
@@ -243,7 +276,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 f4 b[NG];
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
-                    b[g] = *(const f4 *)&Bs[buf][kk][g * 256 + lane * 4];
+                    b[g] = *(const f4 *)(bs + kk * BN + g * 256);
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
 #pragma unroll
@@ -252,21 +285,15 @@ mmlike_valu_kernel(const MmlikeArgs args)
             }
         }
 
-        // fold the tile's partial sums into the main accumulators
-        if constexpr (TASK != TASK_COUNT_GT) {
-#pragma unroll
-            for (int r = 0; r < TM; ++r)
-#pragma unroll
-                for (int c = 0; c < NG * 4; ++c) {
-                    mainacc[r][c] += part[r][c];
-                    part[r][c] = 0;
-                }
-        }
+        // fold the partial sums into the main accumulators every FLUSH_K products
+        if ((t + 1) % FLUSH_TILES == 0)
+            flush();
 
         if (t + 1 < n_tiles)
             store_tile(buf ^ 1);
         __syncthreads();
     }
+    flush();
 
     // ---- write-back: R += acc, once per tile ---------------------------------
 #pragma unroll
@@ -311,12 +338,12 @@ hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s
 {
     switch (shape) {
     case 0: return launch_one<TASK, 4, 1, 4, 8, 4>(a, s);
-    case 1: return launch_one<TASK, 8, 1, 4, 8, 4>(a, s);
-    case 2: return launch_one<TASK, 8, 2, 4, 8, 4>(a, s);
+    case 1: return launch_one<TASK, 4, 1, 8, 8, 4>(a, s);
+    case 2: return launch_one<TASK, 8, 1, 8, 8, 4>(a, s);
     case 3: return launch_one<TASK, 8, 2, 8, 8, 4>(a, s);
     case 4: return launch_one<TASK, 4, 1, 4, 16, 4>(a, s);
-    case 5: return launch_one<TASK, 8, 1, 4, 16, 4>(a, s);
-    case 6: return launch_one<TASK, 8, 2, 4, 16, 4>(a, s);
+    case 5: return launch_one<TASK, 4, 1, 8, 16, 4>(a, s);
+    case 6: return launch_one<TASK, 8, 1, 8, 16, 4>(a, s);
     case 7: return launch_one<TASK, 8, 2, 8, 16, 4>(a, s);
     default: return hipErrorInvalidValue;
     }

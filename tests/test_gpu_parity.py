@@ -58,8 +58,10 @@ ODD_SHAPES = [(70, 300, 37), (33, 513, 100), (1, 1, 1), (129, 1030, 77), (5, 257
 
 
 @pytest.mark.parametrize("task", TASKS)
-@pytest.mark.parametrize("shape", range(8))
+@pytest.mark.parametrize("shape", range(9))
 def test_every_shape_on_ragged_sizes(am, task, shape):
+    if shape >= am.amulet_shape_count(task):
+        pytest.skip("task %d has no shape %d" % (task, shape))
     for idx, (M, N, K) in enumerate(ODD_SHAPES):
         A, B, params, R_in = rand_case(task, M, N, K, seed=1000 + 17 * task + idx)
         print("case", task, shape, M, N, K, flush=True)
@@ -108,7 +110,9 @@ def test_exact_data_is_bit_exact_for_all_tasks(am):
         A, B, params = wl.small_exact(97, 700, 83, seed=5 + task, n_param=NPAR[task])
         R_in = np.zeros((97, 700), np.float32)
         R_ref, _, _ = oracle.mmlike_f32(task, A, B, params, R_in)
-        for shape in (0, 3, 7):
+        for shape in (0, 3, 7, 8):
+            if shape >= am.amulet_shape_count(task):
+                continue
             R = run_gpu(am, task, A, B, params, R_in, shape)
             assert np.array_equal(R, R_ref), (task, shape)
 
