@@ -23,7 +23,8 @@ const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
     {8, 1, 8, 16, "valu_64x256_k16"}, {8, 2, 8, 16, "valu_64x512_k16"},
 };
 
-static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple"};
+static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
+                                                                "mfma_i8_256x128_k64"};
 
 // ---- selection cache ---------------------------------------------------------
 typedef std::tuple<int, int64_t, int64_t, int64_t> SelKey;
@@ -42,7 +43,7 @@ static int n_shapes(int task)
 // every compute unit at least two workgroups, at the deeper B staging.
 static int default_shape(int task, int64_t M, int64_t N, int64_t)
 {
-    if (task == AMULET_TASK_COUNT_I8) return 0;
+    if (task == AMULET_TASK_COUNT_I8) return 1;  // matrix cores, 128 x 128 tile
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
     const int64_t want = 2 * 256;
     for (int t = VALU_TILES - 1; t > 0; --t) {
@@ -114,6 +115,8 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.A = A; a.B = B; a.R = R;
     a.lda = lda; a.ldb = ldb; a.ldr = ldr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.vecA = (aligned16(A) && lda % 16 == 0) ? 1 : 0;
+    a.vecB = (aligned16(B) && ldb % 16 == 0) ? 1 : 0;
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

@@ -43,8 +43,10 @@ struct CountArgs {
     int32_t *R;
     int64_t lda, ldb, ldr;
     int M, N, K;
+    int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
 };
-enum { COUNT_SHAPE_COUNT = 1 };
+// shape 0: plain per-output loop; 1: MFMA 128 x 128 tile; 2: MFMA 256 x 128 tile
+enum { COUNT_SHAPE_COUNT = 3 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 
 // Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.

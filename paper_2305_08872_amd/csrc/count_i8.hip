@@ -1,12 +1,168 @@
 // Join count as a matrix product on int8 indicator matrices:
 // R[i][j] += sum_k A[i][k]*B[k][j], int32, exact (the join-as-matmul
-// translation cited in the paper's introduction).
+// translation cited in the paper's introduction).  This is a dense
+// contraction, so it runs on the int8 matrix cores
+// (v_mfma_i32_32x32x32_i8: a 32 x 32 block of R advances 32 k per instruction).
+//
+// Workgroup = 4 waves (2 x 2); each wave owns MB x NB MFMA blocks.  K is
+// staged 64 bytes at a time, global -> registers -> LDS, double buffered:
+//   A tile [BM][64] keeps its global layout (k contiguous), row pitch 80 B so
+//     the 16-byte fragment reads of 8 neighbouring lanes fall in distinct banks;
+//   B tile [64][BN] ALSO keeps its global layout (n contiguous).  The matrix
+//     core wants, per column, 16 consecutive k in one lane; that transposition
+//     is done by the LDS itself with ds_read_b64_tr_b8 (gfx950): in each block
+//     of 16 lanes, lane t supplies the address of 8 bytes and receives byte
+//     t%8 of the 8 lanes of parity t/8.  Even lanes point at columns c..c+7 and
+//     odd lanes at c+8..c+15 of 8 consecutive k rows, so lane t gets column
+//     c+t, rows k..k+7: two such reads give a lane its 16 k.  No VALU work
+//     and no scattered LDS writes are spent on the transpose.
+//
+// Fragment convention: lane l supplies row/column l % 32 and k-slot h = l / 32;
+// byte t of slot h is k = 16h + t for both operands.
+// Rows, columns and k beyond the matrix are zero-filled in LDS (a zero product
+// adds nothing to an integer dot product).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "amulet_internal.h"
 
 namespace amulet {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) v2i *lds_v2i_ptr;
+
+constexpr int CI_BK = 64;            // bytes of k per stage
+constexpr int CI_APITCH = CI_BK + 16;
+
+// 16 bytes of a row starting at src; n_valid of them exist (the rest read as 0).
+__device__ __forceinline__ v4i load16_i8(const int8_t *src, bool vec, int n_valid)
+{
+    v4i v = {0, 0, 0, 0};
+    if (n_valid <= 0) return v;
+    if (vec && n_valid >= 16) return *(const v4i *)src;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    for (int t = 0; t < 16; ++t)
+        if (t < n_valid) w[t >> 2] |= (uint32_t)(uint8_t)src[t] << (8 * (t & 3));
+    v.x = (int)w[0]; v.y = (int)w[1]; v.z = (int)w[2]; v.w = (int)w[3];
+    return v;
+}
+
+template <int MB, int NB>
+__global__ void __launch_bounds__(256)
+count_i8_mfma_kernel(const CountArgs args)
+{
+    constexpr int BM = 2 * MB * 32, BN = 2 * NB * 32;
+    constexpr int BPITCH = BN + 16;
+    constexpr int A_UNITS = BM * (CI_BK / 16) / 256;   // 16-byte slots per thread per stage
+    constexpr int B_UNITS = CI_BK * (BN / 16) / 256;
+    static_assert(A_UNITS >= 1 && B_UNITS >= 1, "tile too small for 256 threads");
+
+    __shared__ __attribute__((aligned(16))) int8_t As[2][BM][CI_APITCH];
+    __shared__ __attribute__((aligned(16))) int8_t Bs[2][CI_BK][BPITCH];
+
+    const int M = args.M, N = args.N, K = args.K;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const int tiles_m = (M + BM - 1) / BM;
+    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    const int row0 = tm * BM, col0 = tn * BN;
+    const bool vecA = args.vecA != 0, vecB = args.vecB != 0;
+
+    v4i sa[A_UNITS], sb[B_UNITS];
+    auto load_stage = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < A_UNITS; ++it) {
+            const int u = tid + it * 256;
+            const int r = row0 + (u >> 2), k = k0 + (u & 3) * 16;
+            sa[it] = (r < M) ? load16_i8(args.A + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int it = 0; it < B_UNITS; ++it) {
+            const int u = tid + it * 256;
+            const int k = k0 + u / (BN / 16), c = col0 + (u % (BN / 16)) * 16;
+            sb[it] = (k < K) ? load16_i8(args.B + (int64_t)k * args.ldb + c, vecB, N - c) : v4i{0, 0, 0, 0};
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < A_UNITS; ++it) {
+            const int u = tid + it * 256;
+            *(v4i *)&As[buf][u >> 2][(u & 3) * 16] = sa[it];
+        }
+#pragma unroll
+        for (int it = 0; it < B_UNITS; ++it) {
+            const int u = tid + it * 256;
+            *(v4i *)&Bs[buf][u / (BN / 16)][(u % (BN / 16)) * 16] = sb[it];
+        }
+    };
+
+    v16i acc[MB][NB];
+#pragma unroll
+    for (int mi = 0; mi < MB; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NB; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0;
+
+    // transpose-read addressing inside a 16-lane block (see the header comment)
+    const int tb = lane >> 4;                 // block 0..3: column half tb%2, k-slot tb/2 (= lh)
+    const int ts = lane & 15;
+    const int b_krow = 16 * (tb >> 1) + (ts >> 1);             // + 8 for the second read, + 32 per k-step
+    const int b_col = 16 * (tb & 1) + 8 * (ts & 1);            // + 32*ni + the wave's column offset
+
+    const int n_stages = (K + CI_BK - 1) / CI_BK;
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+
+    for (int s = 0; s < n_stages; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < n_stages) load_stage((s + 1) * CI_BK);
+#pragma unroll
+        for (int ks = 0; ks < CI_BK; ks += 32) {
+            v4i a[MB], b[NB];
+#pragma unroll
+            for (int mi = 0; mi < MB; ++mi)
+                a[mi] = *(const v4i *)&As[buf][(wr * MB + mi) * 32 + li][ks + 16 * lh];
+#pragma unroll
+            for (int ni = 0; ni < NB; ++ni) {
+                const int8_t *p = &Bs[buf][ks + b_krow][(wc * NB + ni) * 32 + b_col];
+                const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)p);
+                const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 8 * BPITCH));
+                b[ni] = v4i{lo.x, lo.y, hi.x, hi.y};
+            }
+#pragma unroll
+            for (int mi = 0; mi < MB; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NB; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (s + 1 < n_stages) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+#pragma unroll
+    for (int mi = 0; mi < MB; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NB; ++ni) {
+            const int col = col0 + (wc * NB + ni) * 32 + li;
+            if (col >= N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (wr * MB + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < M) {
+                    int32_t *dst = args.R + (int64_t)row * args.ldr + col;
+                    *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc[mi][ni][v]);
+                }
+            }
+        }
+}
 
 // Shape 0: one output per thread, plain k loop.  Kept as the simplest exact
 // form; every other shape is checked against the same oracle.
@@ -25,27 +181,34 @@ count_i8_simple_kernel(const CountArgs args)
     *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc);
 }
 
+template <int MB, int NB>
+static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
+{
+    const int64_t tiles_m = (a.M + 64 * MB - 1) / (64 * MB), tiles_n = (a.N + 64 * NB - 1) / (64 * NB);
+    if (tiles_m * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
 {
     switch (shape) {
     case 0: {
-        const int64_t gx = (a.N + 63) / 64, gy = (a.M + 3) / 4;
-        if (gy > 65535) {
-            // grid.y is limited: walk the rows in slabs
-            for (int64_t r0 = 0; r0 < a.M; r0 += 65535LL * 4) {
-                CountArgs sub = a;
-                const int64_t rows = (a.M - r0 < 65535LL * 4) ? a.M - r0 : 65535LL * 4;
-                sub.A = a.A + r0 * a.lda;
-                sub.R = a.R + r0 * a.ldr;
-                sub.M = (int)rows;
-                hipLaunchKernelGGL(count_i8_simple_kernel, dim3((unsigned)gx, (unsigned)((rows + 3) / 4)),
-                                   dim3(256), 0, s, sub);
-            }
-        } else {
-            hipLaunchKernelGGL(count_i8_simple_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, a);
+        const int64_t gx = (a.N + 63) / 64;
+        // grid.y is limited to 65535: walk the rows in slabs
+        for (int64_t r0 = 0; r0 < a.M; r0 += 65535LL * 4) {
+            CountArgs sub = a;
+            const int64_t rows = (a.M - r0 < 65535LL * 4) ? a.M - r0 : 65535LL * 4;
+            sub.A = a.A + r0 * a.lda;
+            sub.R = a.R + r0 * a.ldr;
+            sub.M = (int)rows;
+            hipLaunchKernelGGL(count_i8_simple_kernel, dim3((unsigned)gx, (unsigned)((rows + 3) / 4)),
+                               dim3(256), 0, s, sub);
         }
         return hipGetLastError();
     }
+    case 1: return launch_mfma<2, 2>(a, s);   // 128 x 128 tile
+    case 2: return launch_mfma<4, 2>(a, s);   // 256 x 128 tile
     default:
         return hipErrorInvalidValue;
     }
