@@ -18,9 +18,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X published peaks used as roofline denominators
-FP32_VECTOR_PEAK_TFLOPS = 157.3          # 256 CU x 2.4 GHz x 256 flop/clk/CU (packed FMA)
-VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # unpacked lane-operations/s: 256 CU x 64 lanes/clk x 2.4 GHz
+# MI355X published peak used as the roofline denominator: fp32 vector 157.3 TFLOP/s
+# = 256 CU x 2.4 GHz x 128 lanes/clk/CU x 2 flop (one FMA per lane-operation).
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+# The same units counted in lane-operations: a predicate task spends several VALU
+# lane-operations per product (discount: multiply, compare, select, FMA), so its ceiling
+# in the metric's 2-flop-per-product convention is 2 x 78.6e12 / ops.
+VALU_LANE_OPS_PER_S = 256 * 128 * 2.4e9
 VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 3, "identity": 1}
 
 
@@ -33,6 +37,9 @@ def main() -> int:
     ap.add_argument("--no-tune", action="store_true", help="use the built-in default tile shape")
     ap.add_argument("--cpu-rows", type=int, default=128,
                     help="rows of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes, "
+                         "the counter calibration) followed by --steps launches of the kernel; prints no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over rows of A "
@@ -61,6 +68,21 @@ def main() -> int:
     dP = torch.from_numpy(P).cuda() if P is not None else None
     dR = torch.zeros(M, N, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
+
+    if args.traffic_probe:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # 256 MiB read + 256 MiB written by one plain copy kernel
+        torch.cuda.synchronize()
+        if not args.no_tune:
+            am.amulet_tune(task, M, N, K)
+        for _ in range(args.steps):
+            am.amulet_mmlike_f32(task, dA, dB, dP, dR)
+        torch.cuda.synchronize()
+        print("traffic probe done: 1 copy of %d bytes, %d launches of %s" %
+              (src.numel() * 4, args.steps, am.amulet_shape_name(task, am.amulet_selected_shape(task, M, N, K))))
+        return 0
 
     t0 = time.perf_counter()
     shape = am.amulet_selected_shape(task, M, N, K) if args.no_tune else am.amulet_tune(task, M, N, K)
@@ -113,6 +135,29 @@ def main() -> int:
         den = np.where(ab > 0, ab, 1.0)
         parity = float(np.max(np.abs(R_rows.astype(np.float64) - R_ref) / den))
 
+    # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/), when recorded for this workload
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            rec = json.load(f).get(args.workload)
+        if rec:
+            traffic = rec["hbm_bytes_per_launch"]
+
+    lib_ratio = None
+    if tname == "identity":
+        # the library SGEMM (rocBLAS / hipBLASLt behind torch.mm) on the same device buffers
+        for _ in range(args.warmup):
+            torch.mm(dA, dB)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            torch.mm(dA, dB)
+        e1.record()
+        torch.cuda.synchronize()
+        lib_ms = e0.elapsed_time(e1) / args.steps
+        lib_ratio = {"library_sgemm_ms": round(lib_ms, 4), "ours_over_library_rate": round(lib_ms / kernel_ms_avg, 4)}
+
     out = {
         "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp32" % (tname, M, N, K),
         "value": round(value, 1),
@@ -130,15 +175,16 @@ def main() -> int:
                    "tile_shape": am.amulet_shape_name(task, shape), "tuned": not args.no_tune,
                    "tune_seconds": round(tune_s, 3)},
         "pct_of_fp32_vector_peak": round(100.0 * value / 1e3 / FP32_VECTOR_PEAK_TFLOPS, 2),
-        "roofline": {"bound": "alu", "achieved": round(achieved_tflops, 3),
+        "roofline": {"bound": "mfma" if am.amulet_shape_name(task, shape).startswith("mfma") else "alu", "achieved": round(achieved_tflops, 3),
                      "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved_tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved_tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": traffic,
                      "kernel_ms_avg": round(kernel_ms_avg, 4),
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(ceiling_tflops, 3),
                      "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4)},
         "cpu_baseline": cpu,
         "parity_worst_ratio_on_sample": parity,
+        "library_sgemm": lib_ratio,
         "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)",
     }
     print(json.dumps(out))

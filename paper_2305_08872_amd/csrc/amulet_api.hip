@@ -18,9 +18,9 @@ namespace amulet {
 
 const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
     {4, 1, 4, 8, "valu_16x256_k8"},   {4, 1, 8, 8, "valu_32x256_w8_k8"},
-    {8, 1, 8, 8, "valu_64x256_k8"},   {8, 2, 8, 8, "valu_64x512_k8"},
+    {8, 1, 8, 8, "valu_64x256_k8"},   {4, 2, 8, 8, "valu_32x512_k8"},
     {4, 1, 4, 16, "valu_16x256_k16"}, {4, 1, 8, 16, "valu_32x256_w8_k16"},
-    {8, 1, 8, 16, "valu_64x256_k16"}, {8, 2, 8, 16, "valu_64x512_k16"},
+    {8, 1, 8, 16, "valu_64x256_k16"}, {4, 2, 8, 16, "valu_32x512_k16"},
 };
 
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
@@ -39,19 +39,14 @@ static int n_shapes(int task)
     return 0;
 }
 
-// Built-in choice when nothing was tuned: the widest tile that still gives
-// every compute unit at least two workgroups, at the deeper B staging.
-static int default_shape(int task, int64_t M, int64_t N, int64_t)
+// Built-in choice when nothing was tuned.  The predicate tasks are bound by
+// VALU issue, which needs several resident waves per SIMD to keep both issue
+// slots busy, so the small 4x4 micro-tile (16 x 256 tile, about 100 registers)
+// with 16-deep staging is the measured best from 256^3 up to 16384 x 2048 x 8192.
+static int default_shape(int task, int64_t, int64_t, int64_t)
 {
     if (task == AMULET_TASK_COUNT_I8) return 1;  // matrix cores, 128 x 128 tile
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
-    const int64_t want = 2 * 256;
-    for (int t = VALU_TILES - 1; t > 0; --t) {
-        const ValuShapeDesc &d = kValuShapes[VALU_TILES + t];
-        const int64_t rows = (int64_t)d.NW * d.TM, cols = 256LL * d.NG;
-        const int64_t wgs = ((M + rows - 1) / rows) * ((N + cols - 1) / cols);
-        if (wgs >= want) return VALU_TILES + t;
-    }
     return VALU_TILES + 0;
 }
 

@@ -27,7 +27,7 @@ struct MmlikeArgs {
 // staged per barrier (the k_c analogue), axis 1 the workgroup's R tile from
 // narrow to wide (the n_c analogue).  shape id = depth index * VALU_TILES + tile.
 //   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 4x4, 8 waves -> 32 x 256
-//   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 8x8, 8 waves -> 64 x 512
+//   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 4x8, 8 waves -> 32 x 512
 enum { VALU_DEPTHS = 2, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES };
 
 struct ValuShapeDesc {
