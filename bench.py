@@ -158,6 +158,14 @@ def main() -> int:
         lib_ms = e0.elapsed_time(e1) / args.steps
         lib_ratio = {"library_sgemm_ms": round(lib_ms, 4), "ours_over_library_rate": round(lib_ms / kernel_ms_avg, 4)}
 
+    # register-only issue rate of this task's instruction mix on this chip (measured ceiling)
+    probe = None
+    mix = {"identity": 0, "discount": 1, "boost": 2}.get(tname)
+    if mix is not None:
+        pps = max(am.amulet_probe_valu(mix, w) for w in (4, 8))
+        probe = {"mix": tname, "tflops_equiv": round(2.0 * pps / 1e12, 3),
+                 "kernel_over_probe": round(achieved_tflops / (2.0 * pps / 1e12), 4)}
+
     out = {
         "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp32" % (tname, M, N, K),
         "value": round(value, 1),
@@ -182,6 +190,7 @@ def main() -> int:
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(ceiling_tflops, 3),
                      "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4)},
+        "valu_probe": probe,
         "cpu_baseline": cpu,
         "parity_worst_ratio_on_sample": parity,
         "library_sgemm": lib_ratio,

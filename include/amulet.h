@@ -159,6 +159,18 @@ int amulet_register_demand(int I_h, int I_w, int S_w, int n_const, int n_i, int 
 int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int n_i, int n_j,
                                 int n_ij, int n_temp, int budget);
 
+/*
+ * Measurement aid for the roofline of the vector-ALU tasks (the instruction
+ * sequence of Sec. 4.3.1 with nothing around it): runs a register-only loop
+ * of the instruction mix of a task (mix 0: fused multiply-add only, as the
+ * identity task; 1: multiply, compare, select, FMA, as the discount task;
+ * 2: fma, fma, max, add, as the boost task) with `waves_per_simd` (1..8)
+ * resident waves per SIMD on every compute unit, synchronises `stream`, and
+ * writes the sustained products per second.  Allocates a small scratch buffer
+ * and blocks, like amulet_tune.  Returns AMULET_OK or a negative status.
+ */
+int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream);
+
 /* Printable text for a status code (static storage). */
 const char *amulet_strerror(int code);
 

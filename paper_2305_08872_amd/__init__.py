@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     amulet_last_launch_error,
     amulet_mmlike_f32,
     amulet_mmlike_f32_shape,
+    amulet_probe_valu,
     amulet_register_demand,
     amulet_selected_shape,
     amulet_shape_count,

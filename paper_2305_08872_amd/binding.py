@@ -73,6 +73,8 @@ def load_library():
     lib.amulet_register_demand.argtypes = [i32] * 8
     lib.amulet_choose_kernel_height.restype = i32
     lib.amulet_choose_kernel_height.argtypes = [i32] * 9
+    lib.amulet_probe_valu.restype = i32
+    lib.amulet_probe_valu.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.amulet_strerror.restype = ctypes.c_char_p
     lib.amulet_strerror.argtypes = [i32]
     lib.amulet_last_launch_error.restype = ctypes.c_char_p
@@ -210,6 +212,14 @@ def amulet_choose_kernel_height(I_h_max, I_w, S_w, n_const, n_i, n_j, n_ij, n_te
     return _check(load_library().amulet_choose_kernel_height(I_h_max, I_w, S_w, n_const, n_i, n_j, n_ij,
                                                              n_temp, budget),
                   "amulet_choose_kernel_height")
+
+
+def amulet_probe_valu(mix: int, waves_per_simd: int, stream=None) -> float:
+    """Sustained products/s of a register-only loop of a task's instruction mix."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().amulet_probe_valu(mix, waves_per_simd, ctypes.byref(out), _stream_ptr(stream)),
+           "amulet_probe_valu")
+    return out.value
 
 
 def amulet_strerror(code: int) -> str:

@@ -26,6 +26,7 @@ SOURCES = [
     "mmlike_valu_count_gt.hip",
     "identity_mfma.hip",
     "count_i8.hip",
+    "valu_probe.hip",
 ]
 
 HIPCC_FLAGS = [

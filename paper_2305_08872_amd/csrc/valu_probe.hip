@@ -1,0 +1,110 @@
+// Register-only issue-rate probe: what the vector ALU of this chip sustains on
+// the instruction mix of a task when nothing but arithmetic is in the way (no
+// LDS, no global memory, no barriers).  The bench reports it beside the kernel's
+// rate, so the roofline fraction can also be read against a measured ceiling.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "amulet.h"
+#include "amulet_internal.h"
+
+namespace amulet {
+
+// mix 0: fused multiply-add only (the identity task's inner operation)
+// mix 1: multiply, compare, select, fused multiply-add (the discount task)
+// mix 2: fma, fma, max, add (the boost task)
+template <int MIX>
+__global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, int iters)
+{
+    float acc[16], b[16], th[16], q[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        acc[i] = threadIdx.x * 0.001f + i;
+        b[i] = 1.0f + i * 0.01f + threadIdx.x * 1e-6f;
+        th[i] = 1.5f + i;
+        q[i] = 0.9f - i * 0.01f;
+    }
+    float a = a0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (MIX == 0) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(a, b[g * 4 + c], acc[g * 4 + c]);
+                } else if (MIX == 1) {
+                    float p[4], s[4];
+                    bool m[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) p[c] = a * b[g * 4 + c];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) m[c] = p[c] > th[g * 4 + c];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) s[c] = m[c] ? q[g * 4 + c] : 1.0f;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(p[c], s[c], acc[g * 4 + c]);
+                } else {
+                    float d[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaf(a, b[g * 4 + c], -th[g * 4 + c]);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(a, b[g * 4 + c], acc[g * 4 + c]);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaxf(d[c], 0.0f);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] += d[c];
+                }
+            }
+            a += 1e-7f;
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+}  // namespace amulet
+
+using namespace amulet;
+
+extern "C" int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream)
+{
+    if (mix < 0 || mix > 2) return AMULET_ERR_TASK;
+    if (waves_per_simd < 1 || waves_per_simd > 8) return AMULET_ERR_DIM;
+    if (!products_per_second) return AMULET_ERR_NULL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return AMULET_ERR_LAUNCH;
+    const int iters = 10000;
+    const int grid = cus * waves_per_simd;  // 256 threads = 4 waves = one wave per SIMD per workgroup
+    float *out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipStream_t s = (hipStream_t)stream;
+    int rc = AMULET_ERR_LAUNCH;
+    if (hipMalloc(&out, (size_t)grid * 256 * sizeof(float)) == hipSuccess &&
+        hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
+        for (int rep = 0; rep < 2; ++rep) {  // first repetition is the warm-up
+            (void)hipEventRecord(e0, s);
+            switch (mix) {
+            case 0: hipLaunchKernelGGL(valu_probe_kernel<0>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
+            case 1: hipLaunchKernelGGL(valu_probe_kernel<1>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
+            default: hipLaunchKernelGGL(valu_probe_kernel<2>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
+            }
+            (void)hipEventRecord(e1, s);
+        }
+        float ms = 0.0f;
+        if (hipGetLastError() == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+            hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.0f) {
+            // 16 accumulators x 4 unrolled passes = 64 products per lane per iteration
+            *products_per_second = (double)grid * 256.0 * iters * 64.0 / (ms * 1e-3);
+            rc = AMULET_OK;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (out) (void)hipFree(out);
+    return rc;
+}
