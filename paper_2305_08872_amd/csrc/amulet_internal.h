@@ -45,8 +45,9 @@ struct CountArgs {
     int M, N, K;
     int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
 };
-// shape 0: plain per-output loop; 1: MFMA 128 x 128 tile; 2: MFMA 256 x 128 tile
-enum { COUNT_SHAPE_COUNT = 3 };
+// shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
+// 3: 128 x 256 (8 waves)
+enum { COUNT_SHAPE_COUNT = 4 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 
 // Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.

@@ -4,7 +4,7 @@
 // contraction, so it runs on the int8 matrix cores
 // (v_mfma_i32_32x32x32_i8: a 32 x 32 block of R advances 32 k per instruction).
 //
-// Workgroup = 4 waves (2 x 2); each wave owns MB x NB MFMA blocks.  K is
+// Workgroup = WR x WC waves; each wave owns MB x NB MFMA blocks.  K is
 // staged 64 bytes at a time, global -> registers -> LDS, double buffered:
 //   A tile [BM][64] keeps its global layout (k contiguous), row pitch 80 B so
 //     the 16-byte fragment reads of 8 neighbouring lanes fall in distinct banks;
@@ -49,56 +49,103 @@ __device__ __forceinline__ v4i load16_i8(const int8_t *src, bool vec, int n_vali
     return v;
 }
 
-template <int MB, int NB>
-__global__ void __launch_bounds__(256)
+template <int MB, int NB, int WR, int WC>
+struct CountTile {
+    static constexpr int NT = 64 * WR * WC;
+    static constexpr int BM = WR * MB * 32, BN = WC * NB * 32;
+    static constexpr int BPITCH = BN + 16;
+    static constexpr int A_BYTES = BM * CI_APITCH, B_BYTES = CI_BK * BPITCH;
+    static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
+};
+
+template <int MB, int NB, int WR, int WC>
+__global__ void __launch_bounds__(64 * WR * WC)
 count_i8_mfma_kernel(const CountArgs args)
 {
-    constexpr int BM = 2 * MB * 32, BN = 2 * NB * 32;
-    constexpr int BPITCH = BN + 16;
-    constexpr int A_UNITS = BM * (CI_BK / 16) / 256;   // 16-byte slots per thread per stage
-    constexpr int B_UNITS = CI_BK * (BN / 16) / 256;
-    static_assert(A_UNITS >= 1 && B_UNITS >= 1, "tile too small for 256 threads");
+    typedef CountTile<MB, NB, WR, WC> T;
+    constexpr int NT = T::NT, BM = T::BM, BN = T::BN, BPITCH = T::BPITCH;
+    constexpr int A_UNITS = BM * (CI_BK / 16) / NT;   // 16-byte slots per thread per stage
+    constexpr int B_UNITS = CI_BK * (BN / 16) / NT;
+    static_assert(A_UNITS >= 1 && B_UNITS >= 1, "tile too small for the workgroup");
+    static_assert(BM * (CI_BK / 16) % NT == 0 && CI_BK * (BN / 16) % NT == 0, "slots must split evenly");
 
-    __shared__ __attribute__((aligned(16))) int8_t As[2][BM][CI_APITCH];
-    __shared__ __attribute__((aligned(16))) int8_t Bs[2][CI_BK][BPITCH];
+    // dynamic LDS: [2][BM][CI_APITCH] for A, then [2][CI_BK][BPITCH] for B
+    extern __shared__ __attribute__((aligned(16))) int8_t count_smem[];
+    int8_t *const As = count_smem;
+    int8_t *const Bs = count_smem + 2 * T::A_BYTES;
 
     const int M = args.M, N = args.N, K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / WC, wc = wave % WC;
     const int li = lane & 31, lh = lane >> 5;
 
+    // XCD-aware tile order.  Workgroups are handed to the 8 XCDs round-robin (workgroup b
+    // runs on XCD b % 8) and each XCD has its own L2.  XCD x is given its own band of column
+    // tiles and walks it row tile by row tile, so the workgroups resident on an XCD at any
+    // moment form a compact block of R that shares its A rows and B columns through that L2.
     const int tiles_m = (M + BM - 1) / BM;
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int band = (tiles_n + 7) / 8;              // column tiles per XCD
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tn = xcd * band + slot % band;
+    const int tm = slot / band;
+    if (tn >= tiles_n || tm >= tiles_m) return;      // padding of the last band (whole workgroup leaves)
     const int row0 = tm * BM, col0 = tn * BN;
     const bool vecA = args.vecA != 0, vecB = args.vecB != 0;
 
+    // Staging slots: thread t, pass `it` handles 16-byte slot u = t + 256*it of each tile.
+    // Interior workgroups (tile inside the matrix, 16-byte aligned rows) run a branch-free
+    // loader off pointers that only advance by one stage per iteration; edge tiles and
+    // unaligned operands take the guarded byte-wise loader.
+    const bool interior = vecA && vecB && row0 + BM <= M && col0 + BN <= N;
+    const int8_t *pa[A_UNITS];
+    const int8_t *pb[B_UNITS];
+    int8_t *la[A_UNITS];
+    int8_t *lb[B_UNITS];
+#pragma unroll
+    for (int it = 0; it < A_UNITS; ++it) {
+        const int u = tid + it * NT;
+        int r = row0 + (u >> 2);
+        r = r < M ? r : M - 1;   // clamped rows are only dereferenced on the interior path, where none clamp
+        pa[it] = args.A + (int64_t)r * args.lda + (u & 3) * 16;
+        la[it] = As + (u >> 2) * CI_APITCH + (u & 3) * 16;
+    }
+#pragma unroll
+    for (int it = 0; it < B_UNITS; ++it) {
+        const int u = tid + it * NT;
+        pb[it] = args.B + (int64_t)(u / (BN / 16)) * args.ldb + col0 + (u % (BN / 16)) * 16;
+        lb[it] = Bs + (u / (BN / 16)) * BPITCH + (u % (BN / 16)) * 16;
+    }
+    const int64_t b_stage_stride = (int64_t)CI_BK * args.ldb;
+
     v4i sa[A_UNITS], sb[B_UNITS];
     auto load_stage = [&](int k0) {
+        if (interior && k0 + CI_BK <= K) {
 #pragma unroll
-        for (int it = 0; it < A_UNITS; ++it) {
-            const int u = tid + it * 256;
-            const int r = row0 + (u >> 2), k = k0 + (u & 3) * 16;
-            sa[it] = (r < M) ? load16_i8(args.A + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
-        }
+            for (int it = 0; it < A_UNITS; ++it) sa[it] = *(const v4i *)(pa[it] + k0);
 #pragma unroll
-        for (int it = 0; it < B_UNITS; ++it) {
-            const int u = tid + it * 256;
-            const int k = k0 + u / (BN / 16), c = col0 + (u % (BN / 16)) * 16;
-            sb[it] = (k < K) ? load16_i8(args.B + (int64_t)k * args.ldb + c, vecB, N - c) : v4i{0, 0, 0, 0};
+            for (int it = 0; it < B_UNITS; ++it) sb[it] = *(const v4i *)(pb[it] + (int64_t)(k0 / CI_BK) * b_stage_stride);
+        } else {
+#pragma unroll
+            for (int it = 0; it < A_UNITS; ++it) {
+                const int u = tid + it * NT;
+                const int r = row0 + (u >> 2), k = k0 + (u & 3) * 16;
+                sa[it] = (r < M) ? load16_i8(args.A + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int it = 0; it < B_UNITS; ++it) {
+                const int u = tid + it * NT;
+                const int k = k0 + u / (BN / 16), c = col0 + (u % (BN / 16)) * 16;
+                sb[it] = (k < K) ? load16_i8(args.B + (int64_t)k * args.ldb + c, vecB, N - c) : v4i{0, 0, 0, 0};
+            }
         }
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
-        for (int it = 0; it < A_UNITS; ++it) {
-            const int u = tid + it * 256;
-            *(v4i *)&As[buf][u >> 2][(u & 3) * 16] = sa[it];
-        }
+        for (int it = 0; it < A_UNITS; ++it) *(v4i *)(la[it] + buf * T::A_BYTES) = sa[it];
 #pragma unroll
-        for (int it = 0; it < B_UNITS; ++it) {
-            const int u = tid + it * 256;
-            *(v4i *)&Bs[buf][u / (BN / 16)][(u % (BN / 16)) * 16] = sb[it];
-        }
+        for (int it = 0; it < B_UNITS; ++it) *(v4i *)(lb[it] + buf * T::B_BYTES) = sb[it];
     };
 
     v16i acc[MB][NB];
@@ -128,10 +175,10 @@ count_i8_mfma_kernel(const CountArgs args)
             v4i a[MB], b[NB];
 #pragma unroll
             for (int mi = 0; mi < MB; ++mi)
-                a[mi] = *(const v4i *)&As[buf][(wr * MB + mi) * 32 + li][ks + 16 * lh];
+                a[mi] = *(const v4i *)(As + buf * T::A_BYTES + ((wr * MB + mi) * 32 + li) * CI_APITCH + ks + 16 * lh);
 #pragma unroll
             for (int ni = 0; ni < NB; ++ni) {
-                const int8_t *p = &Bs[buf][ks + b_krow][(wc * NB + ni) * 32 + b_col];
+                const int8_t *p = Bs + buf * T::B_BYTES + (ks + b_krow) * BPITCH + (wc * NB + ni) * 32 + b_col;
                 const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)p);
                 const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 8 * BPITCH));
                 b[ni] = v4i{lo.x, lo.y, hi.x, hi.y};
@@ -181,12 +228,22 @@ count_i8_simple_kernel(const CountArgs args)
     *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc);
 }
 
-template <int MB, int NB>
+template <int MB, int NB, int WR, int WC>
 static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
 {
-    const int64_t tiles_m = (a.M + 64 * MB - 1) / (64 * MB), tiles_n = (a.N + 64 * NB - 1) / (64 * NB);
-    if (tiles_m * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s, a);
+    typedef CountTile<MB, NB, WR, WC> T;
+    const int64_t tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
+    const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (T::LDS_BYTES > 65536) {
+        // more than 64 KB of LDS per workgroup has to be granted once per kernel
+        static hipError_t granted = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&count_i8_mfma_kernel<MB, NB, WR, WC>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (granted != hipSuccess) return granted;
+    }
+    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC>), dim3((unsigned)grid), dim3(T::NT),
+                       T::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
@@ -207,8 +264,9 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
         }
         return hipGetLastError();
     }
-    case 1: return launch_mfma<2, 2>(a, s);   // 128 x 128 tile
-    case 2: return launch_mfma<4, 2>(a, s);   // 256 x 128 tile
+    case 1: return launch_mfma<2, 2, 2, 2>(a, s);   // 128 x 128 tile, 4 waves
+    case 2: return launch_mfma<4, 2, 2, 4>(a, s);   // 256 x 256 tile, 8 waves of 128 x 64
+    case 3: return launch_mfma<2, 2, 2, 4>(a, s);   // 128 x 256 tile, 8 waves of 64 x 64
     default:
         return hipErrorInvalidValue;
     }
