@@ -19,6 +19,7 @@ import subprocess
 import numpy as np
 
 IDENTITY, DISCOUNT, BOOST, COUNT_GT = 0, 1, 2, 3
+THRES_COL, THRES_ROW, THRES_CONST, THRES_ELEM = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "amulet_oracle.c")
@@ -44,6 +45,9 @@ def _load():
         lib.oracle_mmlike_f32.restype = i32
         lib.oracle_mmlike_f32.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64,
                                           vp, i32, ctypes.POINTER(i32)]
+        lib.oracle_mmlike_f32_general.restype = i32
+        lib.oracle_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
+                                                  vp, vp, i64, vp, i32, ctypes.POINTER(i32)]
         lib.oracle_count_i8.restype = i32
         lib.oracle_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32,
                                         ctypes.POINTER(i32)]
@@ -96,6 +100,41 @@ def mmlike_f32(task: int, A: np.ndarray, B: np.ndarray, params, R_in=None, *, th
                                ctypes.byref(used))
     if rc != 0:
         raise ValueError("oracle_mmlike_f32 returned %d" % rc)
+    return R, abs_sum, used.value
+
+
+def mmlike_f32_general(task: int, A: np.ndarray, B: np.ndarray, thres=None, dis=None, R_in=None, *,
+                       thres_form: int = THRES_COL, trans_a: bool = False, trans_b: bool = False,
+                       threads: int = 0):
+    """The general test-query form: operands optionally stored transposed (A as K x M,
+    B as N x K) and the threshold operand as thres[j], thres[i], a constant or thres[i][j].
+    Returns (R, abs_sum, threads_used)."""
+    lib = _load()
+    A = _rowmajor(A, np.float32)
+    B = _rowmajor(B, np.float32)
+    M, K = (A.shape[1], A.shape[0]) if trans_a else A.shape
+    K2, N = (B.shape[1], B.shape[0]) if trans_b else B.shape
+    if K2 != K:
+        raise ValueError("inner dimensions differ")
+    tptr, ldt, T = None, 0, None
+    if task != IDENTITY:
+        want = {THRES_COL: (N,), THRES_ROW: (M,), THRES_CONST: (1,), THRES_ELEM: (M, N)}[thres_form]
+        T = np.ascontiguousarray(np.asarray(thres, dtype=np.float32).reshape(want))
+        tptr, ldt = T.ctypes.data, (N if thres_form == THRES_ELEM else 0)
+    D = None
+    if task == DISCOUNT:
+        D = np.ascontiguousarray(np.asarray(dis, dtype=np.float32).reshape(N))
+    R = np.zeros((M, N), np.float32) if R_in is None else np.array(R_in, dtype=np.float32, order="C")
+    if R.shape != (M, N):
+        raise ValueError("R_in has the wrong shape")
+    abs_sum = np.zeros((M, N), np.float64)
+    used = ctypes.c_int(0)
+    rc = lib.oracle_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), M, N, K,
+                                       A.ctypes.data, A.strides[0] // 4, B.ctypes.data, B.strides[0] // 4,
+                                       tptr, ldt, D.ctypes.data if D is not None else None,
+                                       R.ctypes.data, N, abs_sum.ctypes.data, threads, ctypes.byref(used))
+    if rc != 0:
+        raise ValueError("oracle_mmlike_f32_general returned %d" % rc)
     return R, abs_sum, used.value
 
 

@@ -58,36 +58,98 @@
 
 enum { ORACLE_IDENTITY = 0, ORACLE_DISCOUNT = 1, ORACLE_BOOST = 2, ORACLE_COUNT_GT = 3 };
 
-/* One term g(p, params[j]) in double; p is the already rounded fp32 product. */
-static double oracle_term(int task, float p, const float *params, int64_t N, int64_t j)
+enum { ORACLE_THRES_COL = 0, ORACLE_THRES_ROW = 1, ORACLE_THRES_CONST = 2, ORACLE_THRES_ELEM = 3 };
+
+/* One term g(p, thres, dis) in double; p is the already rounded fp32 product. */
+static double oracle_term(int task, float p, float thres, double dis)
 {
     const double pd = (double)p;
     switch (task) {
     case ORACLE_IDENTITY:
         return pd;
-    case ORACLE_DISCOUNT: {
-        const float thres = params[j];
-        const double dis = (double)params[N + j];
+    case ORACLE_DISCOUNT:
         if (p > thres)
             return pd - pd * dis;
         return pd;
-    }
-    case ORACLE_BOOST: {
-        const float thres = params[j];
+    case ORACLE_BOOST:
         if (p > thres)
             return pd + (pd - (double)thres);
         return pd;
-    }
-    case ORACLE_COUNT_GT: {
-        const float thres = params[j];
+    case ORACLE_COUNT_GT:
         return (p > thres) ? 1.0 : 0.0;
-    }
     default:
         return NAN;
     }
 }
 
 /*
+ * The general form of the paper's test queries ("Test Queries" figure, Sec. 6.3):
+ *
+ *   R[i][j] += sum_k g( fl32(a(i,k) * b(k,j)), thres(i,j), dis[j] )
+ *
+ * a(i,k) is A[i*lda+k], or A[k*lda+i] when transA ("A[i][k] is replaced with
+ * A[k][i]"); b(k,j) is B[k*ldb+j], or B[j*ldb+k] when transB.  The threshold
+ * operand takes the four forms the figure lists: thres[j] (COL), thres[i] (ROW),
+ * a constant (CONST, thres[0]) and thres[i][j] (ELEM, row pitch ldt).  dis is
+ * indexed by j as printed (only the DISCOUNT task reads it).
+ */
+int oracle_mmlike_f32_general(int task, int thres_form, int transA, int transB,
+                              int64_t M, int64_t N, int64_t K,
+                              const float *A, int64_t lda,
+                              const float *B, int64_t ldb,
+                              const float *thres, int64_t ldt, const float *dis,
+                              float *R, int64_t ldr,
+                              double *abs_sum, int nthreads, int *threads_used)
+{
+    if (task < ORACLE_IDENTITY || task > ORACLE_COUNT_GT)
+        return -1;
+    if (thres_form < ORACLE_THRES_COL || thres_form > ORACLE_THRES_ELEM)
+        return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads <= 0)
+        nthreads = omp_get_max_threads();
+    if ((int64_t)nthreads > M)
+        nthreads = M > 0 ? (int)M : 1;
+    used = nthreads;
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+#endif
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            float th = 0.0f;
+            double d = 0.0;
+            if (task != ORACLE_IDENTITY) {
+                switch (thres_form) {
+                case ORACLE_THRES_COL: th = thres[j]; break;
+                case ORACLE_THRES_ROW: th = thres[i]; break;
+                case ORACLE_THRES_CONST: th = thres[0]; break;
+                default: th = thres[i * ldt + j]; break;
+                }
+                if (task == ORACLE_DISCOUNT)
+                    d = (double)dis[j];
+            }
+            double acc = 0.0;
+            double abs_acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const float a = transA ? A[k * lda + i] : A[i * lda + k];
+                const float b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                const float p = a * b; /* one fp32 RN multiply */
+                const double t = oracle_term(task, p, th, d);
+                acc += t;
+                abs_acc += fabs(t);
+            }
+            R[i * ldr + j] = (float)((double)R[i * ldr + j] + acc);
+            if (abs_sum)
+                abs_sum[i * N + j] = abs_acc;
+        }
+    }
+    if (threads_used)
+        *threads_used = used;
+    return 0;
+}
+
+/*
+ * The row-major, thres[j] form with planar parameters:
  * R[i*ldr+j] = (float)( (double)R[i*ldr+j] + sum_k g(fl32(A[i*lda+k]*B[k*ldb+j]), params[j]) )
  *
  * params: DISCOUNT thres[0..N) then dis[0..N); BOOST and COUNT_GT thres[0..N);
@@ -104,35 +166,9 @@ int oracle_mmlike_f32(int task, int64_t M, int64_t N, int64_t K,
                       float *R, int64_t ldr,
                       double *abs_sum, int nthreads, int *threads_used)
 {
-    if (task < ORACLE_IDENTITY || task > ORACLE_COUNT_GT)
-        return -1;
-    int used = 1;
-#ifdef _OPENMP
-    if (nthreads <= 0)
-        nthreads = omp_get_max_threads();
-    if ((int64_t)nthreads > M)
-        nthreads = M > 0 ? (int)M : 1;
-    used = nthreads;
-#pragma omp parallel for schedule(static) num_threads(nthreads)
-#endif
-    for (int64_t i = 0; i < M; ++i) {
-        for (int64_t j = 0; j < N; ++j) {
-            double acc = 0.0;
-            double abs_acc = 0.0;
-            for (int64_t k = 0; k < K; ++k) {
-                const float p = A[i * lda + k] * B[k * ldb + j]; /* one fp32 RN multiply */
-                const double t = oracle_term(task, p, params, N, j);
-                acc += t;
-                abs_acc += fabs(t);
-            }
-            R[i * ldr + j] = (float)((double)R[i * ldr + j] + acc);
-            if (abs_sum)
-                abs_sum[i * N + j] = abs_acc;
-        }
-    }
-    if (threads_used)
-        *threads_used = used;
-    return 0;
+    return oracle_mmlike_f32_general(task, ORACLE_THRES_COL, 0, 0, M, N, K, A, lda, B, ldb, params, 0,
+                                     params ? params + N : NULL, R, ldr, abs_sum, nthreads,
+                                     threads_used);
 }
 
 /*
