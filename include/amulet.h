@@ -89,6 +89,41 @@ int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K
                             float *R, int64_t ldr,
                             void *stream);
 
+/* Form of the threshold operand of a predicate task: the four the paper's
+ * "Test Queries" figure lists (Sec. 6.3). */
+typedef enum {
+    AMULET_THRES_COL = 0,   /* thres[j], N values                      */
+    AMULET_THRES_ROW = 1,   /* thres[i], M values                      */
+    AMULET_THRES_CONST = 2, /* one constant, thres[0]                  */
+    AMULET_THRES_ELEM = 3   /* thres[i][j], M x N row-major, pitch ldt */
+} amulet_thres_form_t;
+
+/*
+ * The general form of the test queries (Sec. 6.3):
+ *
+ *   R[i][j] += sum_k g( fl32(a(i,k)*b(k,j)), thres(i,j), dis[j] )
+ *
+ * a(i,k) = A[i*lda+k], or A[k*lda+i] when trans_a != 0 ("A[i][k] is replaced
+ * with A[k][i]": A is then K x M, lda >= M); b(k,j) = B[k*ldb+j], or B[j*ldb+k]
+ * when trans_b != 0 (B is then N x K, ldb >= K).  `thres` is read in the form
+ * `thres_form` names (ldt >= N is used by AMULET_THRES_ELEM only); `dis` is
+ * dis[0..N) and is read by AMULET_DISCOUNT only; both are ignored (may be
+ * NULL) for AMULET_IDENTITY.  `shape` is a tile-shape id of the task, or -1
+ * for the selected/default one (the matrix-core identity kernel takes
+ * row-major operands only: with a transposed operand the identity task runs
+ * on the vector-ALU kernels, and asking for that shape explicitly is
+ * AMULET_ERR_SHAPE).  Other conventions as for amulet_mmlike_f32, which is
+ * this call with thres[j], no transposition, shape -1 and planar params.
+ */
+int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b, int shape,
+                              int64_t M, int64_t N, int64_t K,
+                              const float *A, int64_t lda,
+                              const float *B, int64_t ldb,
+                              const float *thres, int64_t ldt,
+                              const float *dis,
+                              float *R, int64_t ldr,
+                              void *stream);
+
 /*
  * Natural-join count as a matrix product (the join-as-matmul translation cited
  * in Sec. 1): R[i][j] += sum_k A[i][k]*B[k][j], int8 operands (any values; the

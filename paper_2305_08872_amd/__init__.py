@@ -11,6 +11,10 @@ from .binding import (  # noqa: F401
     AMULET_DISCOUNT,
     AMULET_IDENTITY,
     AMULET_TASK_COUNT_I8,
+    AMULET_THRES_COL,
+    AMULET_THRES_CONST,
+    AMULET_THRES_ELEM,
+    AMULET_THRES_ROW,
     AmuletError,
     amulet_choose_kernel_height,
     amulet_clear_selections,
@@ -19,6 +23,7 @@ from .binding import (  # noqa: F401
     amulet_greedy_search,
     amulet_last_launch_error,
     amulet_mmlike_f32,
+    amulet_mmlike_f32_general,
     amulet_mmlike_f32_shape,
     amulet_probe_valu,
     amulet_register_demand,

@@ -13,6 +13,7 @@ import os
 
 AMULET_IDENTITY, AMULET_DISCOUNT, AMULET_BOOST, AMULET_COUNT_GT = 0, 1, 2, 3
 AMULET_TASK_COUNT_I8 = 100
+AMULET_THRES_COL, AMULET_THRES_ROW, AMULET_THRES_CONST, AMULET_THRES_ELEM = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libamulet.so")
@@ -52,6 +53,9 @@ def load_library():
     lib.amulet_mmlike_f32.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.amulet_mmlike_f32_shape.restype = i32
     lib.amulet_mmlike_f32_shape.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.amulet_mmlike_f32_general.restype = i32
+    lib.amulet_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
+                                              vp, vp, i64, vp]
     lib.amulet_count_i8.restype = i32
     lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_count_i8_shape.restype = i32
@@ -146,6 +150,42 @@ def amulet_mmlike_f32_shape(task: int, shape: int, A, B, params, R, stream=None)
     _check(lib.amulet_mmlike_f32_shape(task, shape, M, N, K, pa, lda, pb, ldb,
                                        _params_ptr(task, params, N), pr, ldr, _stream_ptr(stream)),
            "amulet_mmlike_f32_shape")
+
+
+def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
+                              trans_a: bool = False, trans_b: bool = False, shape: int = -1, stream=None):
+    """General test-query form: A may be stored K x M (trans_a), B N x K (trans_b); `thres` is a
+    device tensor of N, M, 1 or M x N values according to `thres_form`; `dis` has N values."""
+    lib = load_library()
+    pa, ra, ca, lda = _mat(A, "torch.float32", "A")
+    pb, rb, cb, ldb = _mat(B, "torch.float32", "B")
+    pr, M, N, ldr = _mat(R, "torch.float32", "R")
+    Ma, K = (ca, ra) if trans_a else (ra, ca)
+    K2, Nb = (cb, rb) if trans_b else (rb, cb)
+    if K2 != K or Ma != M or Nb != N:
+        raise ValueError("shape mismatch between A, B and R")
+    pt, ldt = None, 0
+    if task != AMULET_IDENTITY:
+        if thres is None or not thres.is_cuda or str(thres.dtype) != "torch.float32":
+            raise ValueError("thres must be an fp32 device tensor")
+        if thres_form == AMULET_THRES_ELEM:
+            pt, tm, tn, ldt = _mat(thres, "torch.float32", "thres")
+            if (tm, tn) != (M, N):
+                raise ValueError("thres[i][j] must be M x N")
+        else:
+            want = {AMULET_THRES_COL: N, AMULET_THRES_ROW: M, AMULET_THRES_CONST: 1}[thres_form]
+            if not thres.is_contiguous() or thres.numel() != want:
+                raise ValueError("thres must hold %d contiguous values" % want)
+            pt = thres.data_ptr()
+    pd = None
+    if task == AMULET_DISCOUNT:
+        if dis is None or not dis.is_cuda or str(dis.dtype) != "torch.float32" or not dis.is_contiguous() \
+                or dis.numel() != N:
+            raise ValueError("dis must hold N contiguous fp32 values on the device")
+        pd = dis.data_ptr()
+    _check(lib.amulet_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), shape, M, N, K,
+                                         pa, lda, pb, ldb, pt, ldt, pd, pr, ldr, _stream_ptr(stream)),
+           "amulet_mmlike_f32_general")
 
 
 def amulet_count_i8(A, B, R, stream=None):

@@ -18,16 +18,11 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libamulet.so")
 
-SOURCES = [
-    "amulet_api.hip",
-    "mmlike_valu_identity.hip",
-    "mmlike_valu_discount.hip",
-    "mmlike_valu_boost.hip",
-    "mmlike_valu_count_gt.hip",
-    "identity_mfma.hip",
-    "count_i8.hip",
-    "valu_probe.hip",
-]
+SOURCES = ["amulet_api.hip", "mmlike_valu_identity_col.hip"] + [
+    "mmlike_valu_%s_%s.hip" % (task, form)
+    for task in ("discount", "boost", "count_gt")
+    for form in ("col", "row", "const", "elem")
+] + ["identity_mfma.hip", "count_i8.hip", "valu_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -56,7 +51,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 6) -> str:
+def build(jobs: int = 8) -> str:
     """Compile every HIP source for gfx950 and link libamulet.so; returns its path."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:

@@ -78,29 +78,67 @@ static int check_common(int64_t M, int64_t N, int64_t K, const void *A, int64_t 
 
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
-static int run_mmlike(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-                      const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
-                      void *stream)
+// Operands of an fp32 task in the general form of the paper's test queries (Sec. 6.3).
+struct MmlikeCall {
+    int task, thres_form, trans_a, trans_b;
+    int64_t M, N, K;
+    const float *A; int64_t lda;
+    const float *B; int64_t ldb;
+    const float *thres; int64_t ldt;
+    const float *dis;
+    float *R; int64_t ldr;
+};
+
+template <int TASK>
+static hipError_t launch_form(int form, int shape, const MmlikeArgs &a, hipStream_t s)
+{
+    switch (form) {
+    case THRES_COL: return launch_mmlike_valu_task<TASK, THRES_COL>(shape, a, s);
+    case THRES_ROW: return launch_mmlike_valu_task<TASK, THRES_ROW>(shape, a, s);
+    case THRES_CONST: return launch_mmlike_valu_task<TASK, THRES_CONST>(shape, a, s);
+    default: return launch_mmlike_valu_task<TASK, THRES_ELEM>(shape, a, s);
+    }
+}
+
+static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
 {
     MmlikeArgs a;
-    a.A = A; a.B = B; a.params = params; a.R = R;
-    a.lda = lda; a.ldb = ldb; a.ldr = ldr;
-    a.M = (int)M; a.N = (int)N; a.K = (int)K;
-    a.vec = (aligned16(B) && aligned16(R) && ldb % 4 == 0 && ldr % 4 == 0) ? 1 : 0;
-    a.vecA = (aligned16(A) && lda % 4 == 0) ? 1 : 0;
+    a.A = c.A; a.B = c.B; a.thres = c.thres; a.dis = c.dis; a.R = c.R;
+    a.lda = c.lda; a.ldb = c.ldb; a.ldr = c.ldr; a.ldt = c.ldt;
+    a.M = (int)c.M; a.N = (int)c.N; a.K = (int)c.K;
+    a.transA = c.trans_a; a.transB = c.trans_b;
+    a.vec = (aligned16(c.B) && aligned16(c.R) && c.ldb % 4 == 0 && c.ldr % 4 == 0) ? 1 : 0;
+    a.vecA = (aligned16(c.A) && c.lda % 4 == 0) ? 1 : 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
-    switch (task) {
+    switch (c.task) {
     case TASK_IDENTITY:
         e = shape == IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, s)
-                                         : launch_mmlike_valu_task<TASK_IDENTITY>(shape, a, s);
+                                         : launch_mmlike_valu_task<TASK_IDENTITY, THRES_COL>(shape, a, s);
         break;
-    case TASK_DISCOUNT: e = launch_mmlike_valu_task<TASK_DISCOUNT>(shape, a, s); break;
-    case TASK_BOOST: e = launch_mmlike_valu_task<TASK_BOOST>(shape, a, s); break;
-    default: e = launch_mmlike_valu_task<TASK_COUNT_GT>(shape, a, s); break;
+    case TASK_DISCOUNT: e = launch_form<TASK_DISCOUNT>(c.thres_form, shape, a, s); break;
+    case TASK_BOOST: e = launch_form<TASK_BOOST>(c.thres_form, shape, a, s); break;
+    default: e = launch_form<TASK_COUNT_GT>(c.thres_form, shape, a, s); break;
     }
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+// Argument checks of an fp32 call; returns 1 when there is nothing to do.
+static int check_mmlike(const MmlikeCall &c)
+{
+    if (c.task < TASK_IDENTITY || c.task > TASK_COUNT_GT) return AMULET_ERR_TASK;
+    if (c.thres_form < THRES_COL || c.thres_form > THRES_ELEM) return AMULET_ERR_TASK;
+    if (c.M < 0 || c.N < 0 || c.K < 0) return AMULET_ERR_DIM;
+    if (c.M > kMaxDim || c.N > kMaxDim || c.K > kMaxDim) return AMULET_ERR_RANGE;
+    if (c.M == 0 || c.N == 0 || c.K == 0) return 1;
+    if (!c.A || !c.B || !c.R) return AMULET_ERR_NULL;
+    if (c.task != TASK_IDENTITY && !c.thres) return AMULET_ERR_NULL;
+    if (c.task == TASK_DISCOUNT && !c.dis) return AMULET_ERR_NULL;
+    if (c.lda < (c.trans_a ? c.M : c.K) || c.ldb < (c.trans_b ? c.K : c.N) || c.ldr < c.N)
+        return AMULET_ERR_LD;
+    if (c.task != TASK_IDENTITY && c.thres_form == THRES_ELEM && c.ldt < c.N) return AMULET_ERR_LD;
+    return AMULET_OK;
 }
 
 static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
@@ -158,9 +196,12 @@ static double time_shape(TrialCtx *c, int shape)
             rc = run_count(shape, c->M, c->N, c->K, (const int8_t *)c->A, c->K, (const int8_t *)c->B,
                            c->N, (int32_t *)c->R, c->N, c->stream);
         else
-            rc = run_mmlike(c->task, shape, c->M, c->N, c->K, (const float *)c->A, c->K,
-                            (const float *)c->B, c->N, (const float *)c->params, (float *)c->R, c->N,
-                            c->stream);
+        {
+            MmlikeCall call = {c->task, THRES_COL, 0, 0, c->M, c->N, c->K, (const float *)c->A, c->K,
+                               (const float *)c->B, c->N, (const float *)c->params, 0,
+                               (const float *)c->params + c->N, (float *)c->R, c->N};
+            rc = run_mmlike(call, shape, c->stream);
+        }
         (void)hipEventRecord(c->e1, c->stream);
         if (rc != AMULET_OK || hipEventSynchronize(c->e1) != hipSuccess) {
             c->status = AMULET_ERR_LAUNCH;
@@ -184,26 +225,44 @@ using namespace amulet;
 
 extern "C" {
 
+int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b, int shape,
+                              int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                              const float *B, int64_t ldb, const float *thres, int64_t ldt,
+                              const float *dis, float *R, int64_t ldr, void *stream)
+{
+    const MmlikeCall c = {task, thres_form, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb,
+                          thres, ldt, dis, R, ldr};
+    const int rc = check_mmlike(c);
+    if (rc < 0) return rc;
+    const bool transposed = c.trans_a || c.trans_b;
+    if (shape < 0) {
+        shape = lookup_shape(task, M, N, K);
+        // the matrix-core identity kernel reads row-major operands only
+        if (transposed && task == TASK_IDENTITY && shape == IDENTITY_MFMA_SHAPE) shape = VALU_TILES + 0;
+    } else if (shape >= n_shapes(task) ||
+               (transposed && task == TASK_IDENTITY && shape == IDENTITY_MFMA_SHAPE)) {
+        return AMULET_ERR_SHAPE;
+    }
+    if (rc == 1) return AMULET_OK;
+    return run_mmlike(c, shape, stream);
+}
+
 int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A,
                             int64_t lda, const float *B, int64_t ldb, const float *params, float *R,
                             int64_t ldr, void *stream)
 {
     if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
     if (shape < 0 || shape >= n_shapes(task)) return AMULET_ERR_SHAPE;
-    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
-    if (rc < 0) return rc;
-    if (rc == 1) return AMULET_OK;
-    if (task != TASK_IDENTITY && !params) return AMULET_ERR_NULL;
-    return run_mmlike(task, shape, M, N, K, A, lda, B, ldb, params, R, ldr, stream);
+    return amulet_mmlike_f32_general(task, THRES_COL, 0, 0, shape, M, N, K, A, lda, B, ldb, params, 0,
+                                     params ? params + N : nullptr, R, ldr, stream);
 }
 
 int amulet_mmlike_f32(int task, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                       const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
                       void *stream)
 {
-    if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
-    return amulet_mmlike_f32_shape(task, lookup_shape(task, M, N, K), M, N, K, A, lda, B, ldb, params,
-                                   R, ldr, stream);
+    return amulet_mmlike_f32_general(task, THRES_COL, 0, 0, -1, M, N, K, A, lda, B, ldb, params, 0,
+                                     params ? params + N : nullptr, R, ldr, stream);
 }
 
 int amulet_count_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,

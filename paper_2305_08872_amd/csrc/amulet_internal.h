@@ -9,15 +9,19 @@
 namespace amulet {
 
 enum { TASK_IDENTITY = 0, TASK_DISCOUNT = 1, TASK_BOOST = 2, TASK_COUNT_GT = 3 };
+// form of the threshold operand (paper Sec. 6.3): thres[j], thres[i], a constant, thres[i][j]
+enum { THRES_COL = 0, THRES_ROW = 1, THRES_CONST = 2, THRES_ELEM = 3 };
 
 // Arguments of an fp32 task launch, already validated on the host.
 struct MmlikeArgs {
     const float *A;
     const float *B;
-    const float *params;
+    const float *thres;  // indexed as the launch's threshold form says; unused by the identity task
+    const float *dis;    // dis[0..N), discount task only
     float *R;
-    int64_t lda, ldb, ldr;
+    int64_t lda, ldb, ldr, ldt;   // ldt: row pitch of thres[i][j]
     int M, N, K;
+    int transA, transB;  // operand stored transposed: a(i,k) = A[k*lda+i], b(k,j) = B[j*ldb+k]
     int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
     int vecA;  // 1 when A and its row pitch do
 };
@@ -54,7 +58,7 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT };
 hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s);
 
-template <int TASK>
+template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);
 
 }  // namespace amulet

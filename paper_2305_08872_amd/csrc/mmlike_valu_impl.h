@@ -95,11 +95,12 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
     }
 }
 
-template <int TASK, int TM, int NG, int NW, int BK, int KA>
+template <int TASK, int TF, bool TRANS, int TM, int NG, int NW, int BK, int KA>
 __global__ void __launch_bounds__(64 * NW)
 mmlike_valu_kernel(const MmlikeArgs args)
 {
     typedef typename AccT<TASK>::type acc_t;
+    static_assert(KA == 4 && TM % 4 == 0, "a transposed A is fetched as 4 rows x 4 k blocks");
     constexpr int BN = 256 * NG;           // tile columns
     constexpr int NT = 64 * NW;            // threads
     constexpr int F4_PER_ROW = BN / 4;     // float4 slots in one LDS row
@@ -133,30 +134,63 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const float *__restrict__ Bg = args.B;
     const sptr_f As = (sptr_f)args.A;
 
-    // Wave-uniform row offsets, clamped so edge waves read valid rows.
+    // Wave-uniform row offsets, clamped so edge waves read valid rows.  a(i,k) lives at
+    // A[i*lda + k], or at A[k*lda + i] when A is stored transposed (paper Sec. 6.3:
+    // "A[i][k] is replaced with A[k][i]"): element offset = arow[r] + k * kstride.
+    // TRANS = false compiles the transposed paths out: their addressing state would otherwise
+    // cost the row-major kernels scalar registers in the hot loop.
+    const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
+    const int64_t kstride = transA ? args.lda : 1;
+    const bool rows_full = row0 + TM <= M;
+    auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
     int64_t arow[TM];
 #pragma unroll
-    for (int r = 0; r < TM; ++r) {
-        int row = row0 + r;
-        row = row < M ? row : M - 1;
-        arow[r] = (int64_t)row * args.lda;
-    }
+    for (int r = 0; r < TM; ++r) arow[r] = transA ? (int64_t)rowc(r) : (int64_t)rowc(r) * args.lda;
 
-    // Per-column parameters held in registers for the whole K loop.
-    float th[NG * 4], q[NG * 4];
+    // Parameters held in registers for the whole K loop: the discount factor 1 - dis[j] per
+    // column, and the threshold in the operand form TF (paper Sec. 6.3): thres[j] per column,
+    // thres[i] per row (wave-uniform, scalar), one constant, or thres[i][j] per output (read
+    // once per tile, not once per product as a CPU kernel must).
+    float q[NG * 4];
+    float th_col[TF == THRES_COL ? NG * 4 : 1];
+    float th_row[TF == THRES_ROW ? TM : 1];
+    float th_el[TF == THRES_ELEM ? TM : 1][TF == THRES_ELEM ? NG * 4 : 1];
+    float th_const = __builtin_inff();
+    if constexpr (TASK != TASK_IDENTITY) {
+        if constexpr (TF == THRES_CONST) th_const = ((sptr_f)args.thres)[0];
+        if constexpr (TF == THRES_ROW) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r) th_row[r] = ((sptr_f)args.thres)[rowc(r)];
+        }
+    }
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int col = col0 + g * 256 + lane * 4 + c;
-            th[g * 4 + c] = __builtin_inff();
             q[g * 4 + c] = 1.0f;
+            if constexpr (TF == THRES_COL) th_col[g * 4 + c] = __builtin_inff();
             if (TASK != TASK_IDENTITY && col < N) {
-                th[g * 4 + c] = args.params[col];
-                if (TASK == TASK_DISCOUNT)
-                    q[g * 4 + c] = 1.0f - args.params[(int64_t)N + col];
+                if constexpr (TF == THRES_COL) th_col[g * 4 + c] = args.thres[col];
+                if (TASK == TASK_DISCOUNT) q[g * 4 + c] = 1.0f - args.dis[col];
+            }
+            if constexpr (TF == THRES_ELEM && TASK != TASK_IDENTITY) {
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+                    th_el[r][g * 4 + c] = (col < N) ? args.thres[(int64_t)rowc(r) * args.ldt + col]
+                                                    : __builtin_inff();
             }
         }
+    // the four thresholds facing row r, column group g
+    auto thres4 = [&](int r, int g, float *t4) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if constexpr (TF == THRES_COL) t4[c] = th_col[g * 4 + c];
+            else if constexpr (TF == THRES_ROW) t4[c] = th_row[r];
+            else if constexpr (TF == THRES_CONST) t4[c] = th_const;
+            else t4[c] = th_el[r][g * 4 + c];
+        }
+    };
 
     acc_t part[TM][NG * 4];
     float mainacc[TM][NG * 4];
@@ -181,11 +215,41 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
     const int64_t tile_stride = (int64_t)BK * args.ldb;
     f4 stage[LOADS];
+    // B stored transposed (b(k,j) at B[j*ldb + k], "B[k][j] is replaced with B[j][k]"): a thread
+    // owns one column of the tile and KPT consecutive k of it, read as float4 along k and
+    // scattered into the same [k][n] LDS tile (neighbouring lanes hit neighbouring banks).
+    constexpr int TPC = NT / BN;          // threads per column
+    constexpr int KPT = BK / TPC;         // k per thread
+    static_assert(NT % BN == 0 && BK % TPC == 0 && KPT == 4 * LOADS, "transposed-B slot mapping");
+    const int tcol = threadIdx.x % BN;
+    const int tk = (threadIdx.x / BN) * KPT;
+    const float *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
     auto load_tile = [&](int krows) {
-        if (fast_cols && krows == BK) {
+        if (transB) {
+            const bool colok = col0 + tcol < N;
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it) {
+                f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                const int kk = tk + 4 * it;
+                if (colok) {
+                    const float *src = btsrc + 4 * it;
+                    if (VEC && kk + 3 < krows) {
+                        v = *(const f4 *)src;
+                    } else {
+                        if (kk + 0 < krows) v.x = src[0];
+                        if (kk + 1 < krows) v.y = src[1];
+                        if (kk + 2 < krows) v.z = src[2];
+                        if (kk + 3 < krows) v.w = src[3];
+                    }
+                }
+                stage[it] = v;
+            }
+            btsrc += BK;
+        } else if (fast_cols && krows == BK) {
 #pragma unroll
             for (int it = 0; it < LOADS; ++it)
                 stage[it] = *(const f4 *)(bsrc + it * pass_stride);
+            bsrc += tile_stride;
         } else {
 #pragma unroll
             for (int it = 0; it < LOADS; ++it) {
@@ -199,14 +263,23 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 }
                 stage[it] = v;
             }
+            bsrc += tile_stride;
         }
-        bsrc += tile_stride;
     };
     float *const bdst = &Bs[0][srow][(threadIdx.x % F4_PER_ROW) * 4];
+    float *const btdst = &Bs[0][tk][tcol];
     auto store_tile = [&](int buf) {
+        if (transB) {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it)
-            *(f4 *)(bdst + (buf * BK + it * ROWS_PER_PASS) * BN) = stage[it];
+            for (int it = 0; it < LOADS; ++it)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    btdst[(buf * BK + 4 * it + e) * BN] = stage[it][e];
+        } else {
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it)
+                *(f4 *)(bdst + (buf * BK + it * ROWS_PER_PASS) * BN) = stage[it];
+        }
     };
     auto flush = [&]() {
         if constexpr (TASK != TASK_COUNT_GT) {
@@ -225,13 +298,33 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int n_tiles = full_tiles + (tail ? 1 : 0);
     constexpr int FLUSH_TILES = (FLUSH_K / BK) > 0 ? (FLUSH_K / BK) : 1;  // tiles per partial sum
 
+    // A values of the chunk of KA k starting at kn, for the wave's TM rows, into SGPRs.
     av_t a_next[TM];
+    auto fetch_a = [&](int kn) {
+        if (!transA) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
+        } else if (rows_full) {
+            // 4 consecutive rows of one k are contiguous in the transposed storage
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                for (int v = 0; v < TM / 4; ++v) {
+                    const av_t t = *(sptr_av)(As + (int64_t)(kn + kk) * args.lda + arow[4 * v]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a_next[4 * v + e][kk] = t[e];
+                }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+                    a_next[r][kk] = As[(int64_t)(kn + kk) * args.lda + arow[r]];
+        }
+    };
     load_tile(full_tiles > 0 ? BK : tail);
     store_tile(0);
-    if (full_tiles > 0) {
-#pragma unroll
-        for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r]);
-    }
+    if (full_tiles > 0) fetch_a(0);
     __syncthreads();
 
     const float *bs_lane = &Bs[0][0][lane * 4];
@@ -263,8 +356,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 {
                     int kn = k0 + kc + KA;
                     kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
-#pragma unroll
-                    for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
+                    fetch_a(kn);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -272,8 +364,11 @@ mmlike_valu_kernel(const MmlikeArgs args)
 #pragma unroll
                     for (int r = 0; r < TM; ++r)
 #pragma unroll
-                        for (int g = 0; g < NG; ++g)
-                            fold4<TASK>(a[r][kk], b[kk][g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
+                        for (int g = 0; g < NG; ++g) {
+                            float t4[4];
+                            thres4(r, g, t4);
+                            fold4<TASK>(a[r][kk], b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
+                        }
             }
         } else {
             // K remainder: k by k, so no padded product is ever evaluated.
@@ -281,7 +376,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 float a1[TM];
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
-                    a1[r] = As[arow[r] + k0 + kk];
+                    a1[r] = As[arow[r] + (int64_t)(k0 + kk) * kstride];
                 f4 b[NG];
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
@@ -289,8 +384,11 @@ mmlike_valu_kernel(const MmlikeArgs args)
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
 #pragma unroll
-                    for (int g = 0; g < NG; ++g)
-                        fold4<TASK>(a1[r], b[g], &th[g * 4], &q[g * 4], &part[r][g * 4]);
+                    for (int g = 0; g < NG; ++g) {
+                        float t4[4];
+                        thres4(r, g, t4);
+                        fold4<TASK>(a1[r], b[g], t4, &q[g * 4], &part[r][g * 4]);
+                    }
             }
         }
 
@@ -330,7 +428,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     }
 }
 
-template <int TASK, int TM, int NG, int NW, int BK, int KA>
+template <int TASK, int TF, int TM, int NG, int NW, int BK, int KA>
 static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + NW * TM - 1) / (NW * TM);
@@ -338,23 +436,26 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     const int64_t wgs = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs), block(64 * NW);
-    hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
+    if (a.transA || a.transB)
+        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 // Shape id = depth index * VALU_TILES + tile index (see amulet_internal.h).
-template <int TASK>
+template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s)
 {
     switch (shape) {
-    case 0: return launch_one<TASK, 4, 1, 4, 8, 4>(a, s);
-    case 1: return launch_one<TASK, 4, 1, 8, 8, 4>(a, s);
-    case 2: return launch_one<TASK, 8, 1, 8, 8, 4>(a, s);
-    case 3: return launch_one<TASK, 4, 2, 8, 8, 4>(a, s);
-    case 4: return launch_one<TASK, 4, 1, 4, 16, 4>(a, s);
-    case 5: return launch_one<TASK, 4, 1, 8, 16, 4>(a, s);
-    case 6: return launch_one<TASK, 8, 1, 8, 16, 4>(a, s);
-    case 7: return launch_one<TASK, 4, 2, 8, 16, 4>(a, s);
+    case 0: return launch_one<TASK, TF, 4, 1, 4, 8, 4>(a, s);
+    case 1: return launch_one<TASK, TF, 4, 1, 8, 8, 4>(a, s);
+    case 2: return launch_one<TASK, TF, 8, 1, 8, 8, 4>(a, s);
+    case 3: return launch_one<TASK, TF, 4, 2, 8, 8, 4>(a, s);
+    case 4: return launch_one<TASK, TF, 4, 1, 4, 16, 4>(a, s);
+    case 5: return launch_one<TASK, TF, 4, 1, 8, 16, 4>(a, s);
+    case 6: return launch_one<TASK, TF, 8, 1, 8, 16, 4>(a, s);
+    case 7: return launch_one<TASK, TF, 4, 2, 8, 16, 4>(a, s);
     default: return hipErrorInvalidValue;
     }
 }

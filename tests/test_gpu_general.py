@@ -1,0 +1,122 @@
+"""GPU parity for the general test-query form: threshold operand forms and transposed
+operand storage, against the oracle's general form on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from parity import assert_parity_f32
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+FORMS = [0, 1, 2, 3]
+TASKS = [1, 2, 3]
+
+
+@pytest.fixture(scope="module")
+def am():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2305_08872_amd as am
+    am.load_library()
+    return am
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def make_case(task, form, tA, tB, M, N, K, seed, exact=False):
+    g = np.random.Generator(np.random.PCG64(seed))
+    if exact:
+        A = g.integers(-8, 9, (M, K)).astype(np.float32)
+        B = g.integers(-8, 9, (K, N)).astype(np.float32)
+    else:
+        A = (g.standard_normal((M, K)) * 2).astype(np.float32)
+        B = (g.standard_normal((K, N)) * 2).astype(np.float32)
+    shape = {0: (N,), 1: (M,), 2: (1,), 3: (M, N)}[form]
+    th = (g.integers(-24, 25, shape) / 2.0).astype(np.float32) if exact else \
+        (g.standard_normal(shape) * 3).astype(np.float32)
+    dis = (g.integers(0, 9, N) / 8.0).astype(np.float32) if exact else g.uniform(0, 1, N).astype(np.float32)
+    R_in = (g.integers(-5, 6, (M, N))).astype(np.float32)
+    As = np.ascontiguousarray(A.T) if tA else A
+    Bs = np.ascontiguousarray(B.T) if tB else B
+    return As, Bs, th, dis, R_in
+
+
+def run(am, task, form, tA, tB, As, Bs, th, dis, R_in, shape=-1):
+    dR = dev(R_in)
+    am.amulet_mmlike_f32_general(task, dev(As), dev(Bs), dev(th) if task else None,
+                                 dev(dis) if task == 1 else None, dR,
+                                 thres_form=form, trans_a=tA, trans_b=tB, shape=shape)
+    torch.cuda.synchronize()
+    return dR.cpu().numpy()
+
+
+SIZES = [(70, 300, 37), (33, 513, 100), (129, 1030, 77), (3, 5, 2)]
+
+
+@pytest.mark.parametrize("task", TASKS)
+@pytest.mark.parametrize("form", FORMS)
+def test_threshold_forms_all_shapes(am, task, form):
+    for shape in range(8):
+        M, N, K = SIZES[shape % len(SIZES)]
+        As, Bs, th, dis, R_in = make_case(task, form, False, False, M, N, K, 2000 + 40 * task + 8 * form + shape)
+        print("case", task, form, shape, M, N, K, flush=True)
+        R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form)
+        R = run(am, task, form, False, False, As, Bs, th, dis, R_in, shape)
+        if task == 3:
+            assert np.array_equal(R, R_ref), (task, form, shape)
+        else:
+            assert_parity_f32(R, R_ref, ab, R_in, what="task %d form %d shape %d" % (task, form, shape))
+
+
+@pytest.mark.parametrize("task", [0, 1, 2, 3])
+@pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True)])
+def test_transposed_operands(am, task, tA, tB):
+    for idx, (M, N, K) in enumerate(SIZES + [(64, 512, 64)]):
+        for shape in ((0, 7) if idx % 2 == 0 else (2, 5)):
+            form = (idx + shape) % 4 if task else 0
+            As, Bs, th, dis, R_in = make_case(task, form, tA, tB, M, N, K, 3000 + 50 * task + idx)
+            print("case", task, tA, tB, shape, M, N, K, flush=True)
+            R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form,
+                                                     trans_a=tA, trans_b=tB)
+            R = run(am, task, form, tA, tB, As, Bs, th, dis, R_in, shape)
+            if task == 3:
+                assert np.array_equal(R, R_ref), (task, tA, tB, shape, M, N, K)
+            else:
+                assert_parity_f32(R, R_ref, ab, R_in, what="task %d tA %d tB %d %dx%dx%d" % (task, tA, tB, M, N, K))
+
+
+def test_exact_data_bit_exact_all_forms_and_layouts(am):
+    for task in TASKS:
+        for form in FORMS:
+            for tA, tB in ((False, False), (True, True)):
+                As, Bs, th, dis, R_in = make_case(task, form, tA, tB, 50, 520, 45, 4000 + task * 9 + form, exact=True)
+                R_ref, _, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form,
+                                                        trans_a=tA, trans_b=tB)
+                R = run(am, task, form, tA, tB, As, Bs, th, dis, R_in)
+                assert np.array_equal(R, R_ref), (task, form, tA, tB)
+
+
+def test_transposed_strided_unaligned(am):
+    M, N, K = 37, 290, 53
+    task, form = 2, 1
+    As, Bs, th, dis, R_in = make_case(task, form, True, True, M, N, K, 5000)
+    R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=True, trans_b=True)
+    bigA = torch.zeros(K, M + 3, device="cuda"); bigA[:, :M] = dev(As)     # lda = M + 3 (odd pitch)
+    bigB = torch.zeros(N, K + 1, device="cuda"); bigB[:, :K] = dev(Bs)     # ldb = K + 1
+    dR = dev(R_in)
+    am.amulet_mmlike_f32_general(task, bigA[:, :M], bigB[:, :K], dev(th), None, dR, thres_form=form,
+                                 trans_a=True, trans_b=True)
+    torch.cuda.synchronize()
+    assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="transposed strided")
+
+
+def test_identity_transposed_never_uses_the_mfma_shape(am):
+    A = torch.ones(8, 4, device="cuda"); B = torch.ones(8, 6, device="cuda"); R = torch.zeros(4, 6, device="cuda")
+    with pytest.raises(am.AmuletError):
+        am.amulet_mmlike_f32_general(0, A, B, None, None, R, trans_a=True, shape=8)
+    am.amulet_mmlike_f32_general(0, A, B, None, None, R, trans_a=True)   # auto shape: VALU path
+    torch.cuda.synchronize()
+    assert torch.all(R == 8)
