@@ -146,6 +146,28 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
                           void *stream);
 
 /*
+ * Adaptive execution as the paper runs it (Sec. 4.4-4.6): the task is split
+ * into disjoint row slabs; the first slabs are computed with trial tile
+ * shapes, walked by the two-stage greedy search and scored by time per row,
+ * and the rest of the task runs with the winner, so every trial also
+ * contributes its part of R ("these intermediate computations also all
+ * contribute to the final result").  At most half of the rows serve as
+ * trials; a task too small for two trial slabs runs whole with the default
+ * shape.  The winner is cached for (task, M, N, K) as amulet_tune does.
+ * Unlike amulet_mmlike_f32 this call synchronises with `stream` after each
+ * trial (it reads their timings); the remainder is only enqueued.  It
+ * allocates no device memory.  Arguments as amulet_mmlike_f32; chosen_shape
+ * and n_trials (either may be NULL) receive the winner's id and the number
+ * of trial slabs run.
+ */
+int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K,
+                               const float *A, int64_t lda,
+                               const float *B, int64_t ldb,
+                               const float *params,
+                               float *R, int64_t ldr,
+                               void *stream, int *chosen_shape, int *n_trials);
+
+/*
  * Adaptive shape selection (the stand-in for the paper's adaptive execution,
  * Sec. 4.4-4.6): times the candidate tile shapes of `task` on synthetic
  * operands of this size that the call allocates and frees itself, walks them

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     amulet_greedy_search,
     amulet_last_launch_error,
     amulet_mmlike_f32,
+    amulet_mmlike_f32_adaptive,
     amulet_mmlike_f32_general,
     amulet_mmlike_f32_shape,
     amulet_probe_valu,

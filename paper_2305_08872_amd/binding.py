@@ -56,6 +56,9 @@ def load_library():
     lib.amulet_mmlike_f32_general.restype = i32
     lib.amulet_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
                                               vp, vp, i64, vp]
+    lib.amulet_mmlike_f32_adaptive.restype = i32
+    lib.amulet_mmlike_f32_adaptive.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp,
+                                               ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.amulet_count_i8.restype = i32
     lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_count_i8_shape.restype = i32
@@ -138,6 +141,22 @@ def amulet_mmlike_f32(task: int, A, B, params, R, stream=None):
         raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
     _check(lib.amulet_mmlike_f32(task, M, N, K, pa, lda, pb, ldb, _params_ptr(task, params, N), pr, ldr,
                                  _stream_ptr(stream)), "amulet_mmlike_f32")
+
+
+def amulet_mmlike_f32_adaptive(task: int, A, B, params, R, stream=None):
+    """R += task(A, B, params) with the paper's in-flight adaptive execution: trial tile shapes
+    run on row slabs of this very task.  Returns (chosen shape id, number of trial slabs)."""
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.float32", "A")
+    pb, K2, N, ldb = _mat(B, "torch.float32", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.float32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    chosen, trials = ctypes.c_int(-1), ctypes.c_int(0)
+    _check(lib.amulet_mmlike_f32_adaptive(task, M, N, K, pa, lda, pb, ldb, _params_ptr(task, params, N), pr,
+                                          ldr, _stream_ptr(stream), ctypes.byref(chosen), ctypes.byref(trials)),
+           "amulet_mmlike_f32_adaptive")
+    return chosen.value, trials.value
 
 
 def amulet_mmlike_f32_shape(task: int, shape: int, A, B, params, R, stream=None):

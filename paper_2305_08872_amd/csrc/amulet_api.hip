@@ -219,6 +219,71 @@ static double valu_trial_score(int i0, int i1, void *ctx)
     return time_shape((TrialCtx *)ctx, i0 * VALU_TILES + i1);
 }
 
+// ---- in-flight adaptive execution (paper Sec. 4.4-4.6) ---------------------------
+// Trials run on disjoint row slabs of the caller's own task, so every trial also
+// contributes its part of R; whatever is left runs with the winner.
+struct AdaptiveCtx {
+    MmlikeCall call;      // the whole task
+    int64_t next_row;     // first row no trial has computed yet
+    int64_t budget_rows;  // trials may use rows below this
+    hipStream_t stream;
+    hipEvent_t e0, e1;
+    int status;
+    int trials;
+    double best_valu_score;  // lowest score a vector-ALU shape reached
+};
+
+static int64_t trial_rows(const MmlikeCall &c, int shape)
+{
+    // enough row tiles for about five workgroups on each of the 256 compute units
+    int64_t tile_rows = 128, tile_cols = 128;
+    if (shape < VALU_SHAPE_COUNT) {
+        tile_rows = (int64_t)kValuShapes[shape].NW * kValuShapes[shape].TM;
+        tile_cols = 256LL * kValuShapes[shape].NG;
+    }
+    const int64_t tiles_n = (c.N + tile_cols - 1) / tile_cols;
+    const int64_t row_tiles = (1280 + tiles_n - 1) / tiles_n;
+    return row_tiles * tile_rows;
+}
+
+// Runs rows [r0, r0 + rows) of the task with `shape`.
+static int run_rows(const MmlikeCall &c, int shape, int64_t r0, int64_t rows, hipStream_t s)
+{
+    MmlikeCall sub = c;
+    sub.M = rows;
+    sub.A = c.trans_a ? c.A + r0 : c.A + r0 * c.lda;
+    sub.R = c.R + r0 * c.ldr;
+    if (c.thres_form == THRES_ROW && c.thres) sub.thres = c.thres + r0;
+    if (c.thres_form == THRES_ELEM && c.thres) sub.thres = c.thres + r0 * c.ldt;
+    return run_mmlike(sub, shape, s);
+}
+
+static double adaptive_trial(AdaptiveCtx *x, int shape)
+{
+    const int64_t rows = trial_rows(x->call, shape);
+    if (x->status != AMULET_OK || x->next_row + rows > x->budget_rows) return 1e300;  // no data left to test on
+    (void)hipEventRecord(x->e0, x->stream);
+    const int rc = run_rows(x->call, shape, x->next_row, rows, x->stream);
+    (void)hipEventRecord(x->e1, x->stream);
+    if (rc != AMULET_OK || hipEventSynchronize(x->e1) != hipSuccess) {
+        x->status = AMULET_ERR_LAUNCH;
+        return 1e300;
+    }
+    x->next_row += rows;
+    x->trials += 1;
+    float ms = 0.0f;
+    (void)hipEventElapsedTime(&ms, x->e0, x->e1);
+    return (double)ms / (double)rows;   // the paper's score: execution time per unit of work
+}
+
+static double adaptive_valu_score(int i0, int i1, void *ctx)
+{
+    AdaptiveCtx *x = (AdaptiveCtx *)ctx;
+    const double sc = adaptive_trial(x, i0 * VALU_TILES + i1);
+    if (sc < x->best_valu_score) x->best_valu_score = sc;
+    return sc;
+}
+
 }  // namespace amulet
 
 using namespace amulet;
@@ -311,6 +376,49 @@ int amulet_greedy_search(int n0, int n1, amulet_score_fn score, void *ctx, int *
     *best0 = b0;
     *best1 = b1;
     return calls;
+}
+
+int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                               const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
+                               void *stream, int *chosen_shape, int *n_trials)
+{
+    const MmlikeCall c = {task, THRES_COL, 0, 0, M, N, K, A, lda, B, ldb, params, 0,
+                          params ? params + N : nullptr, R, ldr};
+    const int rc = check_mmlike(c);
+    if (rc < 0) return rc;
+    if (chosen_shape) *chosen_shape = lookup_shape(task, M, N, K);
+    if (n_trials) *n_trials = 0;
+    if (rc == 1) return AMULET_OK;
+
+    AdaptiveCtx x;
+    memset(&x, 0, sizeof(x));
+    x.call = c;
+    x.stream = (hipStream_t)stream;
+    x.budget_rows = M / 2;   // at least half of the task runs with the winner
+    int best = lookup_shape(task, M, N, K);
+    // too small to spare even two trial slabs: run it whole with the default shape
+    const bool can_test = 2 * trial_rows(c, VALU_TILES + 0) <= x.budget_rows;
+    if (can_test && hipEventCreate(&x.e0) == hipSuccess && hipEventCreate(&x.e1) == hipSuccess) {
+        // the dense contraction also has its matrix-core kernel: its slab goes first
+        const double t_mfma = task == TASK_IDENTITY ? adaptive_trial(&x, IDENTITY_MFMA_SHAPE) : 1e300;
+        int b0 = 0, b1 = 0;
+        x.best_valu_score = 1e300;
+        amulet_greedy_search(VALU_DEPTHS, VALU_TILES, adaptive_valu_score, &x, &b0, &b1);
+        best = b0 * VALU_TILES + b1;
+        if (t_mfma <= x.best_valu_score) best = IDENTITY_MFMA_SHAPE;
+    }
+    if (x.e0) (void)hipEventDestroy(x.e0);
+    if (x.e1) (void)hipEventDestroy(x.e1);
+    if (x.status != AMULET_OK) return x.status;
+    int out = AMULET_OK;
+    if (x.next_row < M) out = run_rows(c, best, x.next_row, M - x.next_row, x.stream);
+    if (out == AMULET_OK && x.trials > 0) {
+        std::lock_guard<std::mutex> lock(g_sel_mutex);
+        g_selected[SelKey(task, M, N, K)] = best;
+    }
+    if (chosen_shape) *chosen_shape = best;
+    if (n_trials) *n_trials = x.trials;
+    return out;
 }
 
 int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)

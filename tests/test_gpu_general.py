@@ -120,3 +120,37 @@ def test_identity_transposed_never_uses_the_mfma_shape(am):
     am.amulet_mmlike_f32_general(0, A, B, None, None, R, trans_a=True)   # auto shape: VALU path
     torch.cuda.synchronize()
     assert torch.all(R == 8)
+
+
+def test_adaptive_execution_trials_contribute_to_the_result(am):
+    import amulet_workloads as wl
+    M, N, K = 8192, 8192, 48
+    A, B, P = wl.retail(M, N, K, seed=31)
+    R_in = np.ones((M, N), np.float32)
+    dR = dev(R_in)
+    am.amulet_clear_selections()
+    chosen, trials = am.amulet_mmlike_f32_adaptive(1, dev(A), dev(B), dev(P), dR)
+    torch.cuda.synchronize()
+    assert 0 <= chosen < am.amulet_shape_count(1)
+    assert trials >= 3                      # two depths, then at least one step along the tile axis
+    assert am.amulet_selected_shape(1, M, N, K) == chosen
+    R_ref, ab, _ = oracle.mmlike_f32(1, A, B, P, R_in)
+    assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="adaptive execution")
+    # a task too small for trial slabs still runs, with the default shape and no trials
+    A2, B2, P2 = wl.retail(40, 300, 50, seed=32)
+    dR2 = torch.zeros(40, 300, device="cuda")
+    _, t2 = am.amulet_mmlike_f32_adaptive(1, dev(A2), dev(B2), dev(P2), dR2)
+    torch.cuda.synchronize()
+    assert t2 == 0
+    R_ref, ab, _ = oracle.mmlike_f32(1, A2, B2, P2)
+    assert_parity_f32(dR2.cpu().numpy(), R_ref, ab, what="adaptive, small")
+    # identity: the matrix-core kernel takes part in the trials
+    A3 = np.random.Generator(np.random.PCG64(5)).standard_normal((8192, 40)).astype(np.float32)
+    B3 = np.random.Generator(np.random.PCG64(6)).standard_normal((40, 8192)).astype(np.float32)
+    dR3 = torch.zeros(8192, 8192, device="cuda")
+    c3, t3 = am.amulet_mmlike_f32_adaptive(0, dev(A3), dev(B3), None, dR3)
+    torch.cuda.synchronize()
+    R_ref, ab, _ = oracle.mmlike_f32(0, A3, B3, None)
+    assert_parity_f32(dR3.cpu().numpy(), R_ref, ab, what="adaptive identity")
+    assert t3 >= 2
+    am.amulet_clear_selections()
