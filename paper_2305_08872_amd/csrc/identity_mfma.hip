@@ -27,11 +27,14 @@ namespace amulet {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int MI_BM = 128, MI_BN = 128, MI_BK = 16;
 constexpr int MI_APITCH = MI_BK + 4;   // floats
 
-__global__ void __launch_bounds__(256)
+// 4 waves per SIMD (at most 128 registers): four 128 x 128 workgroups per compute unit, which is
+// what lets a 4096 x 4096 result (1024 tiles on 256 compute units) run as one full round.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_kernel(const MmlikeArgs args)
 {
     __shared__ __attribute__((aligned(16))) float As[2][MI_BM][MI_APITCH];
@@ -44,16 +47,50 @@ identity_mfma_kernel(const MmlikeArgs args)
     const int wr = wave >> 1, wc = wave & 1;
     const int li = lane & 31, lh = lane >> 5;
 
+    // XCD-aware tile order: workgroup b runs on XCD b % 8; each XCD walks its own band of
+    // column tiles row tile by row tile, so its resident workgroups share A rows and B
+    // columns through that XCD's L2.
     const int tiles_m = (M + MI_BM - 1) / MI_BM;
-    const int tm = blockIdx.x % tiles_m;
-    const int tn = blockIdx.x / tiles_m;
+    const int tiles_n = (N + MI_BN - 1) / MI_BN;
+    const int band = (tiles_n + 7) / 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tn = xcd * band + slot % band;
+    const int tm = slot / band;
+    if (tn >= tiles_n || tm >= tiles_m) return;   // padding of the last band
     const int row0 = tm * MI_BM, col0 = tn * MI_BN;
     const bool vecA = args.vecA != 0, vecB = args.vec != 0;
+    // Interior tiles with 16-byte aligned rows are staged as (wave-uniform base that advances
+    // with k) + (fixed 32-bit per-thread offset): the address arithmetic stays on the scalar
+    // unit, which matters because vector-ALU instructions share the issue port with the MFMAs.
+    const bool interior = vecA && vecB && row0 + MI_BM <= M && col0 + MI_BN <= N &&
+                          (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
+    const float *const a_base = args.A + (int64_t)row0 * args.lda;
+    const float *const b_base = args.B + col0;
+    unsigned offa[2], offb[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        // byte offsets
+        offa[it] = ((unsigned)((tid >> 2) + 64 * it) * (unsigned)args.lda + (unsigned)(tid & 3) * 4u) * 4u;
+        offb[it] = ((unsigned)((tid >> 5) + 8 * it) * (unsigned)args.ldb + (unsigned)(tid & 31) * 4u) * 4u;
+    }
 
     // staging slots: A tile 128 rows x 4 float4, thread -> (row = tid / 4 + 64*it, kq = tid % 4)
     //                B tile 16 rows x 32 float4, thread -> (k = tid / 32 + 8*it, cq = tid % 32)
     f4 sa[2], sb[2];
     auto load_stage = [&](int k0) {
+        if (interior && k0 + MI_BK <= K) {
+            // buffer loads: scalar resource (uniform base) + 32-bit per-thread byte offset
+            const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(a_base + k0), 0, 0x7fffffff, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(b_base + (int64_t)k0 * args.ldb), 0, 0x7fffffff, 0x00020000);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                sa[it] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(ra, offa[it], 0, 0));
+                sb[it] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rb, offb[it], 0, 0));
+            }
+            return;
+        }
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int r = row0 + (tid >> 2) + 64 * it;
@@ -161,8 +198,9 @@ hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + MI_BM - 1) / MI_BM;
     const int64_t tiles_n = (a.N + MI_BN - 1) / MI_BN;
-    if (tiles_m * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(identity_mfma_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s, a);
+    const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(identity_mfma_kernel, dim3((unsigned)grid), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
