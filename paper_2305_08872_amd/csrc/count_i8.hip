@@ -98,34 +98,40 @@ count_i8_mfma_kernel(const CountArgs args)
     // Interior workgroups (tile inside the matrix, 16-byte aligned rows) run a branch-free
     // loader off pointers that only advance by one stage per iteration; edge tiles and
     // unaligned operands take the guarded byte-wise loader.
-    const bool interior = vecA && vecB && row0 + BM <= M && col0 + BN <= N;
-    const int8_t *pa[A_UNITS];
-    const int8_t *pb[B_UNITS];
+    const bool interior = vecA && vecB && row0 + BM <= M && col0 + BN <= N &&
+                          (int64_t)BM * args.lda < 0x7fffffffLL && (int64_t)CI_BK * args.ldb < 0x7fffffffLL;
+    // interior path: buffer loads off a wave-uniform base that advances with k plus a fixed
+    // 32-bit per-thread byte offset, so the address arithmetic stays on the scalar unit
+    // (vector-ALU instructions share the issue port with the MFMAs)
+    const int8_t *const a_base = args.A + (int64_t)row0 * args.lda;
+    const int8_t *const b_base = args.B + col0;
+    unsigned offa[A_UNITS], offb[B_UNITS];
     int8_t *la[A_UNITS];
     int8_t *lb[B_UNITS];
 #pragma unroll
     for (int it = 0; it < A_UNITS; ++it) {
         const int u = tid + it * NT;
-        int r = row0 + (u >> 2);
-        r = r < M ? r : M - 1;   // clamped rows are only dereferenced on the interior path, where none clamp
-        pa[it] = args.A + (int64_t)r * args.lda + (u & 3) * 16;
+        offa[it] = (unsigned)(u >> 2) * (unsigned)args.lda + (unsigned)(u & 3) * 16u;
         la[it] = As + (u >> 2) * CI_APITCH + (u & 3) * 16;
     }
 #pragma unroll
     for (int it = 0; it < B_UNITS; ++it) {
         const int u = tid + it * NT;
-        pb[it] = args.B + (int64_t)(u / (BN / 16)) * args.ldb + col0 + (u % (BN / 16)) * 16;
+        offb[it] = (unsigned)(u / (BN / 16)) * (unsigned)args.ldb + (unsigned)(u % (BN / 16)) * 16u;
         lb[it] = Bs + (u / (BN / 16)) * BPITCH + (u % (BN / 16)) * 16;
     }
-    const int64_t b_stage_stride = (int64_t)CI_BK * args.ldb;
 
     v4i sa[A_UNITS], sb[B_UNITS];
     auto load_stage = [&](int k0) {
         if (interior && k0 + CI_BK <= K) {
+            const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(a_base + k0), 0, 0x7fffffff, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(b_base + (int64_t)k0 * args.ldb), 0, 0x7fffffff, 0x00020000);
 #pragma unroll
-            for (int it = 0; it < A_UNITS; ++it) sa[it] = *(const v4i *)(pa[it] + k0);
+            for (int it = 0; it < A_UNITS; ++it) sa[it] = __builtin_amdgcn_raw_buffer_load_b128(ra, offa[it], 0, 0);
 #pragma unroll
-            for (int it = 0; it < B_UNITS; ++it) sb[it] = *(const v4i *)(pb[it] + (int64_t)(k0 / CI_BK) * b_stage_stride);
+            for (int it = 0; it < B_UNITS; ++it) sb[it] = __builtin_amdgcn_raw_buffer_load_b128(rb, offb[it], 0, 0);
         } else {
 #pragma unroll
             for (int it = 0; it < A_UNITS; ++it) {
