@@ -152,25 +152,34 @@ identity_mfma_kernel(const MmlikeArgs args)
     for (int s = 0; s < n_stages; ++s) {
         const int buf = s & 1;
         if (s + 1 < n_stages) load_stage((s + 1) * MI_BK);
+        // A fragments of the whole stage (4 x ds_read_b128), then the 8 k-steps of the stage,
+        // software-pipelined: the B values of step t+1 are read from LDS before the four MFMAs
+        // of step t are issued, so the matrix pipe never waits on an LDS round trip.
+        f4 a[2][2];
 #pragma unroll
-        for (int kb = 0; kb < MI_BK; kb += 8) {
-            f4 a[2];
-            float b[2][4];
+        for (int g = 0; g < 2; ++g)
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
-                a[mi] = *(const f4 *)&As[buf][wr * 64 + mi * 32 + li][kb + 4 * lh];
+                a[g][mi] = *(const f4 *)&As[buf][wr * 64 + mi * 32 + li][8 * g + 4 * lh];
+        float bq[2][2];
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 2; ++ni) bq[0][ni] = Bs[buf][4 * lh][wc * 64 + ni * 32 + li];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    b[ni][t] = Bs[buf][kb + 4 * lh + t][wc * 64 + ni * 32 + li];
+        for (int step = 0; step < 8; ++step) {
+            const int g = step >> 2, t = step & 3, cur = step & 1;
+            if (step + 1 < 8) {
+                const int g1 = (step + 1) >> 2, t1 = (step + 1) & 3;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+                for (int ni = 0; ni < 2; ++ni)
+                    bq[cur ^ 1][ni] = Bs[buf][8 * g1 + 4 * lh + t1][wc * 64 + ni * 32 + li];
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                    for (int ni = 0; ni < 2; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][t], b[ni][t], acc[mi][ni], 0, 0, 0);
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][mi][t], bq[cur][ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (s + 1 < n_stages) store_stage(buf ^ 1);
         __syncthreads();
