@@ -24,7 +24,8 @@ const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
 };
 
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
-                                                                "mfma_i8_256x256_k64", "mfma_i8_128x256_k64"};
+                                                                "mfma_i8_256x256_k64", "mfma_i8_128x256_k64",
+                                                                "mfma_i8_128x128_w8_k128", "mfma_i8_256x256_w16_k64"};
 
 // ---- selection cache ---------------------------------------------------------
 typedef std::tuple<int, int64_t, int64_t, int64_t> SelKey;

@@ -51,7 +51,7 @@ struct CountArgs {
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)
-enum { COUNT_SHAPE_COUNT = 4 };
+enum { COUNT_SHAPE_COUNT = 6 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 
 // Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.

@@ -33,8 +33,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) v2i *lds_v2i_ptr;
 
-constexpr int CI_BK = 64;            // bytes of k per stage
-constexpr int CI_APITCH = CI_BK + 16;
 
 // 16 bytes of a row starting at src; n_valid of them exist (the rest read as 0).
 __device__ __forceinline__ v4i load16_i8(const int8_t *src, bool vec, int n_valid)
@@ -49,8 +47,10 @@ __device__ __forceinline__ v4i load16_i8(const int8_t *src, bool vec, int n_vali
     return v;
 }
 
-template <int MB, int NB, int WR, int WC>
+// BK = bytes of k staged per barrier
+template <int MB, int NB, int WR, int WC, int BK>
 struct CountTile {
+    static constexpr int CI_BK = BK, CI_APITCH = BK + 16;
     static constexpr int NT = 64 * WR * WC;
     static constexpr int BM = WR * MB * 32, BN = WC * NB * 32;
     static constexpr int BPITCH = BN + 16;
@@ -58,12 +58,16 @@ struct CountTile {
     static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
 };
 
-template <int MB, int NB, int WR, int WC>
+// WPE: resident waves per SIMD the register allocation is held to (512 / WPE registers per lane)
+template <int MB, int NB, int WR, int WC, int WPE, int BK>
 __global__ void __launch_bounds__(64 * WR * WC)
+__attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 count_i8_mfma_kernel(const CountArgs args)
 {
-    typedef CountTile<MB, NB, WR, WC> T;
+    typedef CountTile<MB, NB, WR, WC, BK> T;
     constexpr int NT = T::NT, BM = T::BM, BN = T::BN, BPITCH = T::BPITCH;
+    constexpr int CI_BK = BK, CI_APITCH = T::CI_APITCH;
+    constexpr int AU = BK / 16;   // 16-byte slots per A row
     constexpr int A_UNITS = BM * (CI_BK / 16) / NT;   // 16-byte slots per thread per stage
     constexpr int B_UNITS = CI_BK * (BN / 16) / NT;
     static_assert(A_UNITS >= 1 && B_UNITS >= 1, "tile too small for the workgroup");
@@ -111,8 +115,8 @@ count_i8_mfma_kernel(const CountArgs args)
 #pragma unroll
     for (int it = 0; it < A_UNITS; ++it) {
         const int u = tid + it * NT;
-        offa[it] = (unsigned)(u >> 2) * (unsigned)args.lda + (unsigned)(u & 3) * 16u;
-        la[it] = As + (u >> 2) * CI_APITCH + (u & 3) * 16;
+        offa[it] = (unsigned)(u / AU) * (unsigned)args.lda + (unsigned)(u % AU) * 16u;
+        la[it] = As + (u / AU) * CI_APITCH + (u % AU) * 16;
     }
 #pragma unroll
     for (int it = 0; it < B_UNITS; ++it) {
@@ -136,7 +140,7 @@ count_i8_mfma_kernel(const CountArgs args)
 #pragma unroll
             for (int it = 0; it < A_UNITS; ++it) {
                 const int u = tid + it * NT;
-                const int r = row0 + (u >> 2), k = k0 + (u & 3) * 16;
+                const int r = row0 + u / AU, k = k0 + (u % AU) * 16;
                 sa[it] = (r < M) ? load16_i8(args.A + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
             }
 #pragma unroll
@@ -234,21 +238,21 @@ count_i8_simple_kernel(const CountArgs args)
     *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc);
 }
 
-template <int MB, int NB, int WR, int WC>
+template <int MB, int NB, int WR, int WC, int WPE, int BK>
 static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
 {
-    typedef CountTile<MB, NB, WR, WC> T;
+    typedef CountTile<MB, NB, WR, WC, BK> T;
     const int64_t tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (T::LDS_BYTES > 65536) {
         // more than 64 KB of LDS per workgroup has to be granted once per kernel
         static hipError_t granted = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&count_i8_mfma_kernel<MB, NB, WR, WC>),
+            reinterpret_cast<const void *>(&count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>),
             hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (granted != hipSuccess) return granted;
     }
-    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC>), dim3((unsigned)grid), dim3(T::NT),
+    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3((unsigned)grid), dim3(T::NT),
                        T::LDS_BYTES, s, a);
     return hipGetLastError();
 }
@@ -270,9 +274,11 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
         }
         return hipGetLastError();
     }
-    case 1: return launch_mfma<2, 2, 2, 2>(a, s);   // 128 x 128 tile, 4 waves
-    case 2: return launch_mfma<4, 2, 2, 4>(a, s);   // 256 x 256 tile, 8 waves of 128 x 64
-    case 3: return launch_mfma<2, 2, 2, 4>(a, s);   // 128 x 256 tile, 8 waves of 64 x 64
+    case 1: return launch_mfma<2, 2, 2, 2, 3, 64>(a, s);   // 128 x 128 tile, 4 waves
+    case 2: return launch_mfma<4, 2, 2, 4, 2, 64>(a, s);   // 256 x 256 tile, 8 waves of 128 x 64
+    case 3: return launch_mfma<2, 2, 2, 4, 4, 64>(a, s);   // 128 x 256 tile, 8 waves of 64 x 64
+    case 4: return launch_mfma<2, 1, 2, 4, 4, 128>(a, s);  // 128 x 128 tile, 8 waves of 64 x 32, 128-byte stages
+    case 5: return launch_mfma<2, 2, 4, 4, 4, 64>(a, s);   // 256 x 256 tile, 16 waves of 64 x 64
     default:
         return hipErrorInvalidValue;
     }

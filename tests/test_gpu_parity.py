@@ -172,7 +172,7 @@ def test_empty_dimensions_are_noops(am):
 
 
 # ---- join count -----------------------------------------------------------------
-@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5])
 def test_count_i8_bit_exact_ragged(am, shape):
     for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (1, 1, 1), (257, 129, 1000), (64, 64, 64),
                                        (300, 272, 128), (512, 256, 192)]):
