@@ -48,6 +48,7 @@ struct CountArgs {
     int64_t lda, ldb, ldr;
     int M, N, K;
     int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
+    int vecR;        // 1 when R and its row pitch allow 16-byte accesses
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)

@@ -15,7 +15,8 @@
 // stage's data is the wait for loads issued two stages of arithmetic earlier.
 //
 // Used only when the whole problem is interior: M % 128 == 0, N % 256 == 0,
-// K % 64 == 0 and 16-byte aligned rows; every other case runs count_i8_mfma_kernel.
+// K % 64 == 0 and 16-byte aligned rows of A, B and R; every other case runs
+// count_i8_mfma_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -163,25 +164,48 @@ count_i8_dma_kernel(const CountArgs args)
         buf = buf == 2 ? 0 : buf + 1;
     }
 
-    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+    // ---- write-back through LDS: R += acc as whole 1 KB rows ----------------------------------
+    // Accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block: a
+    // lane holds one column.  The operand ring is free now, so the tile is transposed through it
+    // in two halves of 64 rows x 256 columns (64 KB): the waves owning the half scatter their
+    // accumulators into a row-major image, then all 8 waves add it to R with 16-byte accesses,
+    // one full 1 KB tile row per wave instruction.
+    int32_t *const img = (int32_t *)dma_smem;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int half = 0; half < 2; ++half) {
+        __builtin_amdgcn_s_barrier();          // the ring (or the previous half's image) is no longer read
+        asm volatile("" ::: "memory");
+        if (wr == half) {
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const int col = col0 + (wc * 2 + ni) * 32 + li;
+            for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + (wr * 2 + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                int32_t *dst = args.R + (int64_t)row * args.ldr + col;
-                *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc[mi][ni][v]);
-            }
+                for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                        img[r * DM_BN + (wc * 2 + ni) * 32 + li] = acc[mi][ni][v];
+                    }
         }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = wave * 8 + j;           // row of the half this wave adds
+            const v4i part = *(const v4i *)(img + r * DM_BN + lane * 4);
+            v4i *dst = (v4i *)(args.R + (int64_t)(row0 + half * 64 + r) * args.ldr + col0 + lane * 4);
+            v4i cur = *dst;
+            cur.x = (int)((uint32_t)cur.x + (uint32_t)part.x);
+            cur.y = (int)((uint32_t)cur.y + (uint32_t)part.y);
+            cur.z = (int)((uint32_t)cur.z + (uint32_t)part.z);
+            cur.w = (int)((uint32_t)cur.w + (uint32_t)part.w);
+            *dst = cur;
+        }
+    }
 }
 
 // True when the direct-to-LDS kernel may run this problem (everything interior and aligned).
 bool count_i8_dma_eligible(const CountArgs &a)
 {
-    return a.vecA && a.vecB && a.M % DM_BM == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
+    return a.vecA && a.vecB && a.vecR && a.M % DM_BM == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
 }
 
 hipError_t launch_count_i8_dma(const CountArgs &a, hipStream_t s)
