@@ -48,6 +48,8 @@ def _load():
         lib.oracle_mmlike_f32_general.restype = i32
         lib.oracle_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
                                                   vp, vp, i64, vp, i32, ctypes.POINTER(i32)]
+        lib.oracle_mmlike_f64_general.restype = i32
+        lib.oracle_mmlike_f64_general.argtypes = lib.oracle_mmlike_f32_general.argtypes
         lib.oracle_count_i8.restype = i32
         lib.oracle_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32,
                                         ctypes.POINTER(i32)]
@@ -103,15 +105,31 @@ def mmlike_f32(task: int, A: np.ndarray, B: np.ndarray, params, R_in=None, *, th
     return R, abs_sum, used.value
 
 
+def mmlike_f64_general(task: int, A: np.ndarray, B: np.ndarray, thres=None, dis=None, R_in=None, *,
+                       thres_form: int = THRES_COL, trans_a: bool = False, trans_b: bool = False,
+                       threads: int = 0):
+    """The general test-query form in the paper's own element type: fp64 operands, one fp64
+    product per (i, j, k), strict fp64 comparison, long-double accumulation.
+    Returns (R fp64, abs_sum fp64, threads_used)."""
+    return _general(np.float64, "oracle_mmlike_f64_general", task, A, B, thres, dis, R_in, thres_form,
+                    trans_a, trans_b, threads)
+
+
 def mmlike_f32_general(task: int, A: np.ndarray, B: np.ndarray, thres=None, dis=None, R_in=None, *,
                        thres_form: int = THRES_COL, trans_a: bool = False, trans_b: bool = False,
                        threads: int = 0):
     """The general test-query form: operands optionally stored transposed (A as K x M,
     B as N x K) and the threshold operand as thres[j], thres[i], a constant or thres[i][j].
     Returns (R, abs_sum, threads_used)."""
+    return _general(np.float32, "oracle_mmlike_f32_general", task, A, B, thres, dis, R_in, thres_form,
+                    trans_a, trans_b, threads)
+
+
+def _general(dtype, fn_name, task, A, B, thres, dis, R_in, thres_form, trans_a, trans_b, threads):
     lib = _load()
-    A = _rowmajor(A, np.float32)
-    B = _rowmajor(B, np.float32)
+    es = np.dtype(dtype).itemsize
+    A = _rowmajor(A, dtype)
+    B = _rowmajor(B, dtype)
     M, K = (A.shape[1], A.shape[0]) if trans_a else A.shape
     K2, N = (B.shape[1], B.shape[0]) if trans_b else B.shape
     if K2 != K:
@@ -119,22 +137,22 @@ def mmlike_f32_general(task: int, A: np.ndarray, B: np.ndarray, thres=None, dis=
     tptr, ldt, T = None, 0, None
     if task != IDENTITY:
         want = {THRES_COL: (N,), THRES_ROW: (M,), THRES_CONST: (1,), THRES_ELEM: (M, N)}[thres_form]
-        T = np.ascontiguousarray(np.asarray(thres, dtype=np.float32).reshape(want))
+        T = np.ascontiguousarray(np.asarray(thres, dtype=dtype).reshape(want))
         tptr, ldt = T.ctypes.data, (N if thres_form == THRES_ELEM else 0)
     D = None
     if task == DISCOUNT:
-        D = np.ascontiguousarray(np.asarray(dis, dtype=np.float32).reshape(N))
-    R = np.zeros((M, N), np.float32) if R_in is None else np.array(R_in, dtype=np.float32, order="C")
+        D = np.ascontiguousarray(np.asarray(dis, dtype=dtype).reshape(N))
+    R = np.zeros((M, N), dtype) if R_in is None else np.array(R_in, dtype=dtype, order="C")
     if R.shape != (M, N):
         raise ValueError("R_in has the wrong shape")
     abs_sum = np.zeros((M, N), np.float64)
     used = ctypes.c_int(0)
-    rc = lib.oracle_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), M, N, K,
-                                       A.ctypes.data, A.strides[0] // 4, B.ctypes.data, B.strides[0] // 4,
-                                       tptr, ldt, D.ctypes.data if D is not None else None,
-                                       R.ctypes.data, N, abs_sum.ctypes.data, threads, ctypes.byref(used))
+    rc = getattr(lib, fn_name)(task, thres_form, int(trans_a), int(trans_b), M, N, K,
+                               A.ctypes.data, A.strides[0] // es, B.ctypes.data, B.strides[0] // es,
+                               tptr, ldt, D.ctypes.data if D is not None else None,
+                               R.ctypes.data, N, abs_sum.ctypes.data, threads, ctypes.byref(used))
     if rc != 0:
-        raise ValueError("oracle_mmlike_f32_general returned %d" % rc)
+        raise ValueError("%s returned %d" % (fn_name, rc))
     return R, abs_sum, used.value
 
 

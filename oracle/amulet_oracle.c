@@ -172,6 +172,88 @@ int oracle_mmlike_f32(int task, int64_t M, int64_t N, int64_t K,
 }
 
 /*
+ * The same general form in the paper's own element type, double (its listings declare
+ * double A[M][K], B[K][N], C[M][N]; Sec. 3, Sec. 4.3.3): inputs, outputs and parameters are
+ * fp64, the product p is ONE round-to-nearest fp64 multiply, the comparison is made on that
+ * fp64 value, strictly, and everything after it (terms, k-sum, the addition to R) is carried
+ * in long double (64-bit significand on x86-64), so the reference is more precise than any
+ * fp64 summation order it is compared with.
+ */
+static long double oracle_term_f64(int task, double p, double thres, double dis)
+{
+    const long double pd = (long double)p;
+    switch (task) {
+    case ORACLE_IDENTITY:
+        return pd;
+    case ORACLE_DISCOUNT:
+        if (p > thres)
+            return pd - pd * (long double)dis;
+        return pd;
+    case ORACLE_BOOST:
+        if (p > thres)
+            return pd + (pd - (long double)thres);
+        return pd;
+    case ORACLE_COUNT_GT:
+        return (p > thres) ? 1.0L : 0.0L;
+    default:
+        return NAN;
+    }
+}
+
+int oracle_mmlike_f64_general(int task, int thres_form, int transA, int transB,
+                              int64_t M, int64_t N, int64_t K,
+                              const double *A, int64_t lda,
+                              const double *B, int64_t ldb,
+                              const double *thres, int64_t ldt, const double *dis,
+                              double *R, int64_t ldr,
+                              double *abs_sum, int nthreads, int *threads_used)
+{
+    if (task < ORACLE_IDENTITY || task > ORACLE_COUNT_GT)
+        return -1;
+    if (thres_form < ORACLE_THRES_COL || thres_form > ORACLE_THRES_ELEM)
+        return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads <= 0)
+        nthreads = omp_get_max_threads();
+    if ((int64_t)nthreads > M)
+        nthreads = M > 0 ? (int)M : 1;
+    used = nthreads;
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+#endif
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double th = 0.0, d = 0.0;
+            if (task != ORACLE_IDENTITY) {
+                switch (thres_form) {
+                case ORACLE_THRES_COL: th = thres[j]; break;
+                case ORACLE_THRES_ROW: th = thres[i]; break;
+                case ORACLE_THRES_CONST: th = thres[0]; break;
+                default: th = thres[i * ldt + j]; break;
+                }
+                if (task == ORACLE_DISCOUNT)
+                    d = dis[j];
+            }
+            long double acc = 0.0L, abs_acc = 0.0L;
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = transA ? A[k * lda + i] : A[i * lda + k];
+                const double b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                const double p = a * b; /* one fp64 RN multiply */
+                const long double t = oracle_term_f64(task, p, th, d);
+                acc += t;
+                abs_acc += fabsl(t);
+            }
+            R[i * ldr + j] = (double)((long double)R[i * ldr + j] + acc);
+            if (abs_sum)
+                abs_sum[i * N + j] = (double)abs_acc;
+        }
+    }
+    if (threads_used)
+        *threads_used = used;
+    return 0;
+}
+
+/*
  * Natural-join count written as a matrix product (the join-as-matmul
  * translation the paper's introduction cites): with A[i][k] = 1 when tuple i
  * of the left relation carries join key k, and B[k][j] likewise for the right

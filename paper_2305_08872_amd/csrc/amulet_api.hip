@@ -473,11 +473,13 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
                            (size_t)Mt * N, 0.0f, 0.0f, 1u);
         int chosen;
         if (i8) {
-            chosen = 0;
+            // shape 0 is the plain per-output loop kept for checking; only the matrix-core
+            // shapes are candidates
+            chosen = 1;
             double best = 0.0;
-            for (int sidx = 0; sidx < COUNT_SHAPE_COUNT; ++sidx) {
+            for (int sidx = 1; sidx < COUNT_SHAPE_COUNT; ++sidx) {
                 const double t = time_shape(&c, sidx);
-                if (sidx == 0 || t < best) { best = t; chosen = sidx; }
+                if (sidx == 1 || t < best) { best = t; chosen = sidx; }
             }
         } else {
             int b0 = 0, b1 = 0;
