@@ -125,6 +125,28 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
                               void *stream);
 
 /*
+ * The same tasks in the paper's own element type (its listings declare
+ * double A[M][K], B[K][N], C[M][N]: Sec. 3, Sec. 4.3.3, Sec. 6.3):
+ *
+ *   R[i][j] += sum_k g( fl64(A[i*lda+k]*B[k*ldb+j]), thres(i,j), dis[j] )
+ *
+ * One IEEE fp64 multiply per product, strict fp64 comparison, fp64 accumulation
+ * in unspecified order.  Row-major operands only; `thres_form`, `thres`, `ldt`
+ * and `dis` as for amulet_mmlike_f32_general; all pointers are device pointers
+ * to doubles (8-byte aligned), owned by the caller; pitches in elements.  One
+ * vector-ALU tile shape (16 x 128, 16 k per stage).  Enqueues on `stream` and
+ * returns; same error codes as the fp32 calls.
+ */
+int amulet_mmlike_f64(int task, int thres_form,
+                      int64_t M, int64_t N, int64_t K,
+                      const double *A, int64_t lda,
+                      const double *B, int64_t ldb,
+                      const double *thres, int64_t ldt,
+                      const double *dis,
+                      double *R, int64_t ldr,
+                      void *stream);
+
+/*
  * Natural-join count as a matrix product (the join-as-matmul translation cited
  * in Sec. 1): R[i][j] += sum_k A[i][k]*B[k][j], int8 operands (any values; the
  * workload is 0/1 indicators), int32 result, exact (wraps modulo 2^32 only if

@@ -53,6 +53,8 @@ def load_library():
     lib.amulet_mmlike_f32.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.amulet_mmlike_f32_shape.restype = i32
     lib.amulet_mmlike_f32_shape.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.amulet_mmlike_f64.restype = i32
+    lib.amulet_mmlike_f64.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.amulet_mmlike_f32_general.restype = i32
     lib.amulet_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
                                               vp, vp, i64, vp]
@@ -205,6 +207,39 @@ def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int
     _check(lib.amulet_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), shape, M, N, K,
                                          pa, lda, pb, ldb, pt, ldt, pd, pr, ldr, _stream_ptr(stream)),
            "amulet_mmlike_f32_general")
+
+
+def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL, stream=None):
+    """The tasks in the paper's own element type: fp64 device tensors, row-major; `thres` holds
+    N, M, 1 or M x N values according to `thres_form`; `dis` has N values."""
+    lib = load_library()
+    f64 = "torch.float64"
+    pa, M, K, lda = _mat(A, f64, "A")
+    pb, K2, N, ldb = _mat(B, f64, "B")
+    pr, M2, N2, ldr = _mat(R, f64, "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch between A, B and R")
+    pt, ldt = None, 0
+    if task != AMULET_IDENTITY:
+        if thres is None or not thres.is_cuda or str(thres.dtype) != f64:
+            raise ValueError("thres must be an fp64 device tensor")
+        if thres_form == AMULET_THRES_ELEM:
+            pt, tm, tn, ldt = _mat(thres, f64, "thres")
+            if (tm, tn) != (M, N):
+                raise ValueError("thres[i][j] must be M x N")
+        else:
+            want = {AMULET_THRES_COL: N, AMULET_THRES_ROW: M, AMULET_THRES_CONST: 1}[thres_form]
+            if not thres.is_contiguous() or thres.numel() != want:
+                raise ValueError("thres must hold %d contiguous values" % want)
+            pt = thres.data_ptr()
+    pd = None
+    if task == AMULET_DISCOUNT:
+        if dis is None or not dis.is_cuda or str(dis.dtype) != f64 or not dis.is_contiguous() \
+                or dis.numel() != N:
+            raise ValueError("dis must hold N contiguous fp64 values on the device")
+        pd = dis.data_ptr()
+    _check(lib.amulet_mmlike_f64(task, thres_form, M, N, K, pa, lda, pb, ldb, pt, ldt, pd, pr, ldr,
+                                 _stream_ptr(stream)), "amulet_mmlike_f64")
 
 
 def amulet_count_i8(A, B, R, stream=None):

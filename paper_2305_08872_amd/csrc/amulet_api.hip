@@ -316,6 +316,28 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
     return run_mmlike(c, shape, stream);
 }
 
+int amulet_mmlike_f64(int task, int thres_form, int64_t M, int64_t N, int64_t K, const double *A,
+                      int64_t lda, const double *B, int64_t ldb, const double *thres, int64_t ldt,
+                      const double *dis, double *R, int64_t ldr, void *stream)
+{
+    if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
+    if (thres_form < THRES_COL || thres_form > THRES_ELEM) return AMULET_ERR_TASK;
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    if (rc == 1) return AMULET_OK;
+    if (task != TASK_IDENTITY && !thres) return AMULET_ERR_NULL;
+    if (task == TASK_DISCOUNT && !dis) return AMULET_ERR_NULL;
+    if (task != TASK_IDENTITY && thres_form == THRES_ELEM && ldt < N) return AMULET_ERR_LD;
+    MmlikeArgsF64 a;
+    a.A = A; a.B = B; a.thres = thres; a.dis = dis; a.R = R;
+    a.lda = lda; a.ldb = ldb; a.ldr = ldr; a.ldt = ldt;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.vec = (aligned16(B) && aligned16(R) && ldb % 2 == 0 && ldr % 2 == 0) ? 1 : 0;
+    const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
+    g_last_hip_error = e;
+    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
 int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A,
                             int64_t lda, const float *B, int64_t ldb, const float *params, float *R,
                             int64_t ldr, void *stream)

@@ -64,5 +64,18 @@ hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s);
 template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);
 
+// Arguments of an fp64 task launch (row-major operands), already validated on the host.
+struct MmlikeArgsF64 {
+    const double *A;
+    const double *B;
+    const double *thres;
+    const double *dis;
+    double *R;
+    int64_t lda, ldb, ldr, ldt;
+    int M, N, K;
+    int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
+};
+hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);
+
 }  // namespace amulet
 #endif

@@ -1,0 +1,283 @@
+// The matrix-multiplication-like tasks in the paper's own element type, double (its
+// listings declare double A[M][K], B[K][N], C[M][N]; Sec. 3, Sec. 4.3.3).  Same mapping as
+// the fp32 vector-ALU kernels (mmlike_valu_impl.h): a lane owns columns, a wave owns TM rows
+// whose A values arrive through the scalar cache into SGPR pairs, the B tile goes through
+// LDS, the thresholds stay in registers, the K remainder is computed k by k.  One tile
+// shape: 16 x 128 per workgroup (4 waves x 4 rows, 2 columns per lane), 16 k per barrier.
+// fp64 accumulation needs no second level: K * 2^-53 stays far below the tolerance.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "amulet_internal.h"
+
+namespace amulet {
+
+typedef double d2 __attribute__((ext_vector_type(2)));
+typedef d2 d2_a8 __attribute__((aligned(8)));
+typedef const __attribute__((address_space(4))) double *sptr_d;     // read through the scalar cache
+typedef const __attribute__((address_space(4))) d2_a8 *sptr_d2;
+
+constexpr int D_TM = 4, D_NW = 4, D_BK = 16, D_BN = 128, D_NT = 64 * D_NW;
+
+template <int TASK> struct AccD { typedef double type; };
+template <> struct AccD<TASK_COUNT_GT> { typedef int type; };
+
+// Two products of one A value with a lane's two B values.  The multiply is a separately
+// rounded fp64 operation wherever a comparison depends on it (contraction is off).
+template <int TASK>
+__device__ __forceinline__ void fold2(double a, d2 b, const double *th, const double *q,
+                                      typename AccD<TASK>::type *acc)
+{
+    if constexpr (TASK == TASK_IDENTITY) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) acc[c] = __builtin_fma(a, b[c], acc[c]);
+    } else if constexpr (TASK == TASK_DISCOUNT) {
+        double p[2], s[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) p[c] = a * b[c];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) s[c] = (p[c] > th[c]) ? q[c] : 1.0;   // q = 1 - dis[j]
+#pragma unroll
+        for (int c = 0; c < 2; ++c) acc[c] = __builtin_fma(p[c], s[c], acc[c]);
+    } else if constexpr (TASK == TASK_BOOST) {
+        // p + max(p - th, 0): continuous in p, so the fused product is within tolerance
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const double d = __builtin_fma(a, b[c], -th[c]);
+            acc[c] = __builtin_fma(a, b[c], acc[c]);
+            acc[c] += __builtin_fmax(d, 0.0);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const double p = a * b[c];
+            acc[c] += (int)(p > th[c]);
+        }
+    }
+}
+
+template <int TASK, int TF>
+__global__ void __launch_bounds__(D_NT)
+mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
+{
+    typedef typename AccD<TASK>::type acc_t;
+    constexpr int D2_PER_ROW = D_BN / 2;                     // 16-byte slots in one LDS row
+    constexpr int ROWS_PER_PASS = D_NT / D2_PER_ROW;         // 4
+    constexpr int LOADS = D_BK / ROWS_PER_PASS;              // 4 slots staged per thread per tile
+    constexpr int KA = 2;                                    // A is fetched two k at a time (one 16-byte scalar load per row)
+
+    __shared__ __attribute__((aligned(16))) double Bs[2][D_BK][D_BN];
+
+    const int M = args.M, N = args.N, K = args.K;
+    const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    // XCD-aware tile order, as in the fp32 kernels
+    const int tiles_m = (M + D_NW * D_TM - 1) / (D_NW * D_TM);
+    const int tiles_n = (N + D_BN - 1) / D_BN;
+    const int band = (tiles_n + 7) / 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tn = xcd * band + slot % band;
+    const int tm = slot / band;
+    if (tn >= tiles_n || tm >= tiles_m) return;
+    const int row0 = tm * (D_NW * D_TM) + wave * D_TM;
+    const int col0 = tn * D_BN;
+
+    const sptr_d As = (sptr_d)args.A;
+    auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
+    int64_t arow[D_TM];
+#pragma unroll
+    for (int r = 0; r < D_TM; ++r) arow[r] = (int64_t)rowc(r) * args.lda;
+
+    // parameters in registers for the whole K loop (threshold in the operand form TF)
+    double q[2];
+    double th_col[TF == THRES_COL ? 2 : 1];
+    double th_row[TF == THRES_ROW ? D_TM : 1];
+    double th_el[TF == THRES_ELEM ? D_TM : 1][TF == THRES_ELEM ? 2 : 1];
+    double th_const = __builtin_inf();
+    if constexpr (TASK != TASK_IDENTITY) {
+        if constexpr (TF == THRES_CONST) th_const = ((sptr_d)args.thres)[0];
+        if constexpr (TF == THRES_ROW) {
+#pragma unroll
+            for (int r = 0; r < D_TM; ++r) th_row[r] = ((sptr_d)args.thres)[rowc(r)];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int col = col0 + lane * 2 + c;
+        q[c] = 1.0;
+        if constexpr (TF == THRES_COL) th_col[c] = __builtin_inf();
+        if (TASK != TASK_IDENTITY && col < N) {
+            if constexpr (TF == THRES_COL) th_col[c] = args.thres[col];
+            if (TASK == TASK_DISCOUNT) q[c] = 1.0 - args.dis[col];
+        }
+        if constexpr (TF == THRES_ELEM && TASK != TASK_IDENTITY) {
+#pragma unroll
+            for (int r = 0; r < D_TM; ++r)
+                th_el[r][c] = (col < N) ? args.thres[(int64_t)rowc(r) * args.ldt + col] : __builtin_inf();
+        }
+    }
+    auto thres2 = [&](int r, double *t2) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            if constexpr (TF == THRES_COL) t2[c] = th_col[c];
+            else if constexpr (TF == THRES_ROW) t2[c] = th_row[r];
+            else if constexpr (TF == THRES_CONST) t2[c] = th_const;
+            else t2[c] = th_el[r][c];
+        }
+    };
+
+    acc_t acc[D_TM][2];
+#pragma unroll
+    for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) acc[r][c] = 0;
+
+    // ---- B tile staging: global -> registers -> LDS ---------------------------------------
+    const int srow = threadIdx.x / D2_PER_ROW;
+    const int scol = col0 + (threadIdx.x % D2_PER_ROW) * 2;
+    const bool fast_cols = VEC && (col0 + D_BN <= N);
+    const double *bsrc = args.B + (int64_t)srow * args.ldb + scol;
+    const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
+    const int64_t tile_stride = (int64_t)D_BK * args.ldb;
+    d2 stage[LOADS];
+    auto load_tile = [&](int krows) {
+        if (fast_cols && krows == D_BK) {
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it) stage[it] = *(const d2 *)(bsrc + it * pass_stride);
+        } else {
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it) {
+                d2 v = {0.0, 0.0};
+                if (srow + it * ROWS_PER_PASS < krows) {
+                    const double *src = bsrc + it * pass_stride;
+                    if (scol + 0 < N) v.x = src[0];
+                    if (scol + 1 < N) v.y = src[1];
+                }
+                stage[it] = v;
+            }
+        }
+        bsrc += tile_stride;
+    };
+    double *const bdst = &Bs[0][srow][(threadIdx.x % D2_PER_ROW) * 2];
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < LOADS; ++it)
+            *(d2 *)(bdst + (buf * D_BK + it * ROWS_PER_PASS) * D_BN) = stage[it];
+    };
+
+    const int full_tiles = K / D_BK;
+    const int tail = K - full_tiles * D_BK;
+    const int n_tiles = full_tiles + (tail ? 1 : 0);
+
+    d2_a8 a_next[D_TM];
+    load_tile(full_tiles > 0 ? D_BK : tail);
+    store_tile(0);
+    if (full_tiles > 0) {
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r]);
+    }
+    __syncthreads();
+
+    const double *bs_lane = &Bs[0][0][lane * 2];
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const int k0 = t * D_BK;
+        if (t + 1 < n_tiles) load_tile((t + 1 < full_tiles) ? D_BK : tail);
+        const double *bs = bs_lane + buf * (D_BK * D_BN);
+
+        if (t < full_tiles) {
+#pragma unroll 1
+            for (int kc = 0; kc < D_BK; kc += KA) {
+                d2 b[KA];
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk) b[kk] = *(const d2 *)(bs + (kc + kk) * D_BN);
+                d2_a8 a[D_TM];
+#pragma unroll
+                for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                // the scalar fetch of the next chunk goes out right after the LDS wait (scalar
+                // loads return out of order: any later LDS wait would drain them too)
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    int kn = k0 + kc + KA;
+                    kn = kn + KA <= K ? kn : k0 + kc;
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r] + kn);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r) {
+                        double t2[2];
+                        thres2(r, t2);
+                        fold2<TASK>(a[r][kk], b[kk], t2, q, acc[r]);
+                    }
+            }
+        } else {
+            // K remainder: k by k, never zero-padded (g(0) is not 0 in general)
+            for (int kk = 0; kk < tail; ++kk) {
+                const d2 b = *(const d2 *)(bs + kk * D_BN);
+#pragma unroll
+                for (int r = 0; r < D_TM; ++r) {
+                    const double a1 = As[arow[r] + k0 + kk];
+                    double t2[2];
+                    thres2(r, t2);
+                    fold2<TASK>(a1, b, t2, q, acc[r]);
+                }
+            }
+        }
+        if (t + 1 < n_tiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- write-back: R += acc ------------------------------------------------------------
+#pragma unroll
+    for (int r = 0; r < D_TM; ++r) {
+        const int row = row0 + r;
+        if (row >= M) continue;
+        double *dst_row = args.R + (int64_t)row * args.ldr;
+        const int col = col0 + lane * 2;
+        const double v0 = (double)acc[r][0], v1 = (double)acc[r][1];
+        if (VEC && col + 1 < N) {
+            d2 o = *(d2 *)(dst_row + col);
+            o.x += v0; o.y += v1;
+            *(d2 *)(dst_row + col) = o;
+        } else {
+            if (col + 0 < N) dst_row[col + 0] += v0;
+            if (col + 1 < N) dst_row[col + 1] += v1;
+        }
+    }
+}
+
+template <int TASK>
+static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
+{
+    switch (form) {
+    case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL>), grid, dim3(D_NT), 0, s, a); break;
+    case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW>), grid, dim3(D_NT), 0, s, a); break;
+    case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST>), grid, dim3(D_NT), 0, s, a); break;
+    default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM>), grid, dim3(D_NT), 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s)
+{
+    const int64_t tiles_m = (a.M + D_NW * D_TM - 1) / (D_NW * D_TM);
+    const int64_t tiles_n = (a.N + D_BN - 1) / D_BN;
+    const int64_t wgs = 8 * ((tiles_n + 7) / 8) * tiles_m;
+    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs);
+    switch (task) {
+    case TASK_IDENTITY: return launch_f64_form<TASK_IDENTITY>(THRES_COL, a, grid, s);
+    case TASK_DISCOUNT: return launch_f64_form<TASK_DISCOUNT>(form, a, grid, s);
+    case TASK_BOOST: return launch_f64_form<TASK_BOOST>(form, a, grid, s);
+    case TASK_COUNT_GT: return launch_f64_form<TASK_COUNT_GT>(form, a, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace amulet

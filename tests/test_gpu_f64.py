@@ -1,0 +1,168 @@
+"""GPU parity of the fp64 tasks (the paper's own element type) against the fp64 oracle.
+
+Tolerance: both sides round every product once to fp64; the oracle then accumulates in
+long double, the GPU in fp64 in its own order.  A sum of K fp64 terms in any order is
+within (K - 1) * 2^-53 * sum|term| of the exact sum; the discount factor 1 - dis[j]
+rounded once and the fused p * (1 - dis) add at most 2 * 2^-53 per term.  With K <= 4096
+in these cases the bound is below 5e-13; the tests use 1e-12.  COUNT_GT is an integer
+count and is compared bit for bit, as are all tasks on dyadic data whose every partial
+sum is exactly representable.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from parity import worst_ratio
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+TOL_F64 = 1e-12
+TASKS = [0, 1, 2, 3]
+FORMS = [0, 1, 2, 3]
+
+
+@pytest.fixture(scope="module")
+def am():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2305_08872_amd as am
+    am.load_library()
+    return am
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def make_case(form, M, N, K, seed, exact=False):
+    g = np.random.Generator(np.random.PCG64(seed))
+    if exact:
+        A = g.integers(-8, 9, (M, K)).astype(np.float64)
+        B = g.integers(-8, 9, (K, N)).astype(np.float64)
+    else:
+        A = g.standard_normal((M, K)) * 2
+        B = g.standard_normal((K, N)) * 2
+    shape = {0: (N,), 1: (M,), 2: (1,), 3: (M, N)}[form]
+    th = (g.integers(-24, 25, shape) / 2.0) if exact else g.standard_normal(shape) * 3
+    dis = (g.integers(0, 9, N) / 8.0) if exact else g.uniform(0, 1, N)
+    R_in = g.integers(-5, 6, (M, N)).astype(np.float64)
+    return A, B, np.asarray(th, dtype=np.float64), np.asarray(dis, dtype=np.float64), R_in
+
+
+def run(am, task, form, dA, dB, th, dis, dR):
+    am.amulet_mmlike_f64(task, dA, dB, dev(th) if task else None, dev(dis) if task == 1 else None, dR,
+                         thres_form=form)
+    torch.cuda.synchronize()
+    return dR.cpu().numpy()
+
+
+def check(R, R_ref, ab, R_in, task, what):
+    if task == 3:
+        assert np.array_equal(R, R_ref), what
+        return
+    w = worst_ratio(R, R_ref, ab, R_in)
+    assert w <= TOL_F64, "%s: worst |diff|/sum|term| = %.3e" % (what, w)
+
+
+# several tiles (16 x 128) in both directions, ragged M, N and K (K % 16 and K % 2 != 0)
+SIZES = [(70, 300, 37), (33, 513, 100), (129, 1030, 77), (3, 5, 2), (16, 128, 16), (17, 129, 1),
+         (64, 256, 4096)]
+
+
+@pytest.mark.parametrize("task", TASKS)
+@pytest.mark.parametrize("form", FORMS)
+def test_f64_forms_and_ragged_sizes(am, task, form):
+    if task == 0 and form != 0:
+        pytest.skip("the identity task has no threshold operand")
+    for idx, (M, N, K) in enumerate(SIZES):
+        A, B, th, dis, R_in = make_case(form, M, N, K, 7000 + 64 * task + 8 * form + idx)
+        print("case f64", task, form, M, N, K, flush=True)
+        R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in, thres_form=form)
+        R = run(am, task, form, dev(A), dev(B), th, dis, dev(R_in))
+        check(R, R_ref, ab, R_in, task, "task %d form %d %dx%dx%d" % (task, form, M, N, K))
+
+
+@pytest.mark.parametrize("task", TASKS)
+def test_f64_exact_dyadic_data_with_ties(am, task):
+    """Small integers and thresholds on multiples of 1/2: products hit thresholds exactly
+    (strict >), and every sum is exact in fp64, so the result is bit-exact in any order."""
+    for form in ([0] if task == 0 else FORMS):
+        M, N, K = 50, 260, 45
+        A, B, th, dis, R_in = make_case(form, M, N, K, 7700 + 8 * task + form, exact=True)
+        if task:
+            if form == 2:
+                th = np.array([6.0])   # a value integer products do hit
+            thb = (th[None, None, :] if form == 0 else th[:, None, None] if form == 1 else
+                   th.reshape(1, 1, 1) if form == 2 else th[:, None, :])
+            ties = np.sum((A[:, :, None] * B[None, :, :]) == thb)
+            assert ties > 0
+        R_ref, _, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in, thres_form=form)
+        R = run(am, task, form, dev(A), dev(B), th, dis, dev(R_in))
+        assert np.array_equal(R, R_ref), (task, form)
+
+
+@pytest.mark.parametrize("task", TASKS)
+def test_f64_strided_and_unaligned_operands(am, task):
+    """Row pitches larger than the row, odd pitches and views that start 8 bytes off a
+    16-byte boundary (the scalar path instead of the 16-byte one)."""
+    M, N, K = 37, 301, 53
+    A, B, th, dis, R_in = make_case(0, M, N, K, 7800 + task)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in)
+    for pad_a, pad_b, pad_r, off in [(3, 5, 7, 0), (0, 1, 1, 1), (2, 2, 2, 1), (0, 0, 0, 0)]:
+        bufA = torch.zeros(M, K + pad_a + off, dtype=torch.float64, device="cuda")
+        bufB = torch.zeros(K, N + pad_b + off, dtype=torch.float64, device="cuda")
+        bufR = torch.full((M, N + pad_r + off), -77.0, dtype=torch.float64, device="cuda")
+        dA, dB, dR = bufA[:, off:off + K], bufB[:, off:off + N], bufR[:, off:off + N]
+        dA.copy_(dev(A)); dB.copy_(dev(B)); dR.copy_(dev(R_in))
+        print("case f64 strided", task, pad_a, pad_b, pad_r, off, flush=True)
+        am.amulet_mmlike_f64(task, dA, dB, dev(th) if task else None, dev(dis) if task == 1 else None, dR)
+        torch.cuda.synchronize()
+        check(dR.cpu().numpy(), R_ref, ab, R_in, task, "strided %r" % ((pad_a, pad_b, pad_r, off),))
+        full = bufR.cpu().numpy()
+        assert np.all(full[:, :off] == -77.0) and np.all(full[:, off + N:] == -77.0), "wrote outside R"
+
+
+def test_f64_accumulates_into_R_and_special_thresholds(am):
+    M, N, K = 40, 200, 64
+    A, B, th, dis, R_in = make_case(0, M, N, K, 7900)
+    dA, dB = dev(A), dev(B)
+    # thres = +inf: nothing is over it, DISCOUNT and BOOST reduce to the plain product, COUNT_GT to 0
+    inf = np.full(N, np.inf)
+    ident, ab, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
+    for task in (1, 2):
+        R = run(am, task, 0, dA, dB, inf, dis, dev(R_in))
+        assert worst_ratio(R, ident, ab, R_in) <= TOL_F64
+    R = run(am, 3, 0, dA, dB, inf, dis, dev(R_in))
+    assert np.array_equal(R, R_in)
+    # thres = -inf: every product is over it
+    R = run(am, 3, 0, dA, dB, -inf, dis, dev(R_in))
+    assert np.array_equal(R, R_in + K)
+    # two calls accumulate
+    dR = dev(R_in)
+    am.amulet_mmlike_f64(1, dA, dB, dev(th), dev(dis), dR)
+    am.amulet_mmlike_f64(1, dA, dB, dev(th), dev(dis), dR)
+    torch.cuda.synchronize()
+    once, ab1, _ = oracle.mmlike_f64_general(1, A, B, th, dis, R_in)
+    twice, ab2, _ = oracle.mmlike_f64_general(1, A, B, th, dis, once)
+    assert worst_ratio(dR.cpu().numpy(), twice, ab1 + ab2, R_in) <= TOL_F64
+
+
+def test_f64_argument_errors_and_empty(am):
+    z = torch.zeros(4, 4, dtype=torch.float64, device="cuda")
+    v = torch.zeros(4, dtype=torch.float64, device="cuda")
+    with pytest.raises(am.AmuletError):
+        am.amulet_mmlike_f64(7, z, z, v, v, z)
+    lib = am.load_library()
+    assert lib.amulet_mmlike_f64(1, 9, 4, 4, 4, z.data_ptr(), 4, z.data_ptr(), 4, v.data_ptr(), 0, v.data_ptr(),
+                                 z.data_ptr(), 4, None) == -1   # unknown threshold form
+    assert lib.amulet_mmlike_f64(1, 0, 4, 4, 4, z.data_ptr(), 4, z.data_ptr(), 4, None, 0, v.data_ptr(),
+                                 z.data_ptr(), 4, None) == -3   # thres missing
+    assert lib.amulet_mmlike_f64(1, 0, 4, 4, 4, z.data_ptr(), 3, z.data_ptr(), 4, v.data_ptr(), 0,
+                                 v.data_ptr(), z.data_ptr(), 4, None) == -4   # lda < K
+    # empty problems are accepted and leave R untouched
+    R = torch.full((4, 4), 3.0, dtype=torch.float64, device="cuda")
+    e = torch.zeros(4, 0, dtype=torch.float64, device="cuda")
+    am.amulet_mmlike_f64(1, e, torch.zeros(0, 4, dtype=torch.float64, device="cuda"), v, v, R)
+    torch.cuda.synchronize()
+    assert torch.all(R == 3.0)
