@@ -25,7 +25,8 @@ const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
 
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
                                                                 "mfma_i8_256x256_k64", "mfma_i8_128x256_k64",
-                                                                "mfma_i8_128x128_w8_k128", "mfma_i8_256x256_w16_k64", "mfma_i8_128x256_dma3"};
+                                                                "mfma_i8_128x128_w8_k128", "mfma_i8_256x256_w16_k64", "mfma_i8_128x256_dma3",
+                                                                "mfma_i8_256x256_w16_dma3"};
 
 // ---- selection cache ---------------------------------------------------------
 typedef std::tuple<int, int64_t, int64_t, int64_t> SelKey;
@@ -44,11 +45,12 @@ static int n_shapes(int task)
 // VALU issue, which needs several resident waves per SIMD to keep both issue
 // slots busy, so the small 4x4 micro-tile (16 x 256 tile, about 100 registers)
 // with 16-deep staging is the measured best from 256^3 up to 16384 x 2048 x 8192.
-static int default_shape(int task, int64_t, int64_t, int64_t)
+static int default_shape(int task, int64_t M, int64_t N, int64_t)
 {
-    // matrix cores, 128 x 256 tile streamed straight into LDS (falls back to the register-staged
-    // kernel of the same tile when the problem is not fully interior and aligned)
-    if (task == AMULET_TASK_COUNT_I8) return 6;
+    // matrix cores, operands streamed straight into LDS: the 256 x 256 tile when it still gives
+    // every compute unit two tiles or more, else 128 x 256 (both fall back to the register-staged
+    // kernel when the problem is not fully interior and aligned)
+    if (task == AMULET_TASK_COUNT_I8) return ((M / 256) * ((N + 255) / 256) >= 512) ? 7 : 6;
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
     return VALU_TILES + 0;
 }

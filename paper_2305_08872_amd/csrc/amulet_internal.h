@@ -52,10 +52,11 @@ struct CountArgs {
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)
-enum { COUNT_SHAPE_COUNT = 7 };
+enum { COUNT_SHAPE_COUNT = 8 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
-bool count_i8_dma_eligible(const CountArgs &a);
-hipError_t launch_count_i8_dma(const CountArgs &a, hipStream_t s);
+// direct HBM -> LDS kernels: tile (64 * wr) x 256, wr = 2 or 4
+bool count_i8_dma_eligible(const CountArgs &a, int wr);
+hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s);
 
 // Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.
 enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT };

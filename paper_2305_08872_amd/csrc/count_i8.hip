@@ -280,7 +280,10 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
     case 4: return launch_mfma<2, 1, 2, 4, 4, 128>(a, s);  // 128 x 128 tile, 8 waves of 64 x 32, 128-byte stages
     case 5: return launch_mfma<2, 2, 4, 4, 4, 64>(a, s);   // 256 x 256 tile, 16 waves of 64 x 64
     case 6:   // 128 x 256 tile streamed HBM -> LDS directly; needs a fully interior, aligned problem
-        return count_i8_dma_eligible(a) ? launch_count_i8_dma(a, s) : launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
+        return count_i8_dma_eligible(a, 2) ? launch_count_i8_dma(a, 2, s) : launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
+    case 7:   // 256 x 256 tile, 16 waves, streamed HBM -> LDS directly; same condition, else as shape 6
+        if (count_i8_dma_eligible(a, 4)) return launch_count_i8_dma(a, 4, s);
+        return count_i8_dma_eligible(a, 2) ? launch_count_i8_dma(a, 2, s) : launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
     default:
         return hipErrorInvalidValue;
     }

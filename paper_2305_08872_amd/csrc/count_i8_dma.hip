@@ -7,16 +7,17 @@
 // lane may fetch from any global address, so the LDS tiles are un-padded and
 // XOR-swizzled at 16-byte granularity instead of padded:
 //   A tile [128 rows][64 B]: row r keeps its logical 16-byte unit u at physical unit
-//     u ^ ((r >> 1) & 3), so the ds_read_b128 of 8 neighbouring rows fall in 8 distinct
-//     bank groups;
+//     u ^ ((r >> 2) & 3).  A ds_read_b128 is served 16 lanes (256 bytes, all 64 banks) per
+//     clock, and 16 neighbouring rows fall in 16 distinct 16-byte bank groups:
+//     4 * (r & 3) + (u ^ ((r >> 2) & 3)) runs through 0..15;
 //   B tile [64 k][256 B]: row k keeps logical unit u at u ^ (k & 7), so the 8 rows a
 //     ds_read_b64_tr_b8 block reads (same logical unit) fall in 8 distinct bank groups.
-// With the loads of NSTAGE-1 stages in flight and one barrier per stage, the wait for a
-// stage's data is the wait for loads issued two stages of arithmetic earlier.
+// One barrier per stage, placed between the stage's two k-steps (see the main loop), with the
+// loads of NSTAGE-2 later stages in flight behind it.
 //
-// Used only when the whole problem is interior: M % 128 == 0, N % 256 == 0,
-// K % 64 == 0 and 16-byte aligned rows of A, B and R; every other case runs
-// count_i8_mfma_kernel.
+// Used only when the whole problem is interior: M a multiple of the tile height (128 or
+// 256), N % 256 == 0, K % 64 == 0 and 16-byte aligned rows of A, B and R; every other case
+// runs count_i8_mfma_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,22 +35,38 @@ typedef __attribute__((address_space(3))) v2i *lds_v2i_ptr;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
-constexpr int DM_BM = 128, DM_BN = 256, DM_BK = 64;
-constexpr int DM_A_BYTES = DM_BM * DM_BK;          // 8 KB  = 8 wave-loads
+constexpr int DM_BN = 256, DM_BK = 64;
 constexpr int DM_B_BYTES = DM_BK * DM_BN;          // 16 KB = 16 wave-loads
-constexpr int DM_STAGE_BYTES = DM_A_BYTES + DM_B_BYTES;
 
-template <int NSTAGE>
-__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+// WR = rows of the 4-wide wave grid: the workgroup has 4 * WR waves, each owning a 64 x 64
+// block of the (64 * WR) x 256 tile.  WR = 2: 128 x 256, 8 waves, 72 KB ring (two workgroups
+// per compute unit); WR = 4: 256 x 256, 16 waves, 96 KB ring (one workgroup per compute unit,
+// a third less operand traffic out of the L2 per multiply-add).
+template <int WR, int NSTAGE>
+struct DmaTile {
+    static constexpr int BM = 64 * WR, NW = 4 * WR, NT = 64 * NW;
+    static constexpr int A_BYTES = BM * DM_BK;          // one wave-load (1 KB) per 16 rows
+    static constexpr int STAGE_BYTES = A_BYTES + DM_B_BYTES;
+    static constexpr int B_LOADS = 16 / NW;             // B wave-loads per wave per stage
+    static constexpr int LOADS = 1 + B_LOADS;           // DMA instructions per wave per stage
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+};
+
+template <int WR, int NSTAGE>
+__global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4, 4)))
 count_i8_dma_kernel(const CountArgs args)
 {
-    static_assert(NSTAGE == 3, "the wait counts below are written for a ring of three stages");
+    typedef DmaTile<WR, NSTAGE> T;
+    static_assert(NSTAGE == 3 || NSTAGE == 4, "the wait counts are written for rings of 3 or 4 stages");
+    constexpr int DM_BM = T::BM, DM_A_BYTES = T::A_BYTES, DM_STAGE_BYTES = T::STAGE_BYTES;
+    constexpr int NW = T::NW, B_LOADS = T::B_LOADS;
+    static_assert(WR == 2 || WR == 4, "wave grid is 2 x 4 or 4 x 4");
     extern __shared__ __attribute__((aligned(16))) int8_t dma_smem[];
 
     const int K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..7, 2 x 4 grid
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // WR x 4 grid
     const int wr = wave >> 2, wc = wave & 3;
     const int li = lane & 31, lh = lane >> 5;
 
@@ -62,16 +79,16 @@ count_i8_dma_kernel(const CountArgs args)
     if (tn >= tiles_n || tm >= tiles_m) return;
     const int row0 = tm * DM_BM, col0 = tn * DM_BN;
 
-    // ---- what each lane fetches: one A slot and two B slots per stage ------------------
+    // ---- what each lane fetches: one A slot and B_LOADS B slots per stage ----------------
     // A: wave w owns LDS slots [64w, 64w+64): slot s = 64w + lane -> row s/4, physical unit s%4
     const int a_row = wave * 16 + (lane >> 2);
-    const int a_log = (lane & 3) ^ ((a_row >> 1) & 3);
+    const int a_log = (lane & 3) ^ ((a_row >> 2) & 3);
     const int8_t *ga = args.A + (int64_t)(row0 + a_row) * args.lda + a_log * 16;
-    // B: wave w owns slot groups j = w and w + 8: slot s = 64j + lane -> k row s/16, physical unit s%16
-    const int8_t *gb[2];
+    // B: wave w owns slot groups j = w (+ NW): slot s = 64j + lane -> k row s/16, physical unit s%16
+    const int8_t *gb[B_LOADS];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int krow = (wave + 8 * q) * 4 + (lane >> 4);
+    for (int q = 0; q < B_LOADS; ++q) {
+        const int krow = (wave + NW * q) * 4 + (lane >> 4);
         const int blog = (lane & 15) ^ (krow & 7);
         gb[q] = args.B + (int64_t)krow * args.ldb + col0 + blog * 16;
     }
@@ -80,7 +97,7 @@ count_i8_dma_kernel(const CountArgs args)
     // The loads are written as asm so that the compiler's wait-count pass does not see a
     // vector-memory instruction writing LDS: it would otherwise drain ALL outstanding loads
     // (vmcnt(0)) before every LDS read, which serialises the ring.  Completion is tracked by
-    // hand below: s_waitcnt vmcnt(3) / vmcnt(0) before the stage's barrier.  M0 carries the
+    // hand below: s_waitcnt vmcnt(loads per stage) / vmcnt(0) before the stage's barrier.  M0 carries the
     // wave-uniform LDS destination; each lane's 16 bytes land at M0 + 16 * lane.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)dma_smem;
     auto dma16 = [&](const int8_t *g, uint32_t lds_addr) {
@@ -93,8 +110,8 @@ count_i8_dma_kernel(const CountArgs args)
         const uint32_t base = lds_base + (uint32_t)(buf * DM_STAGE_BYTES);
         dma16(ga + (int64_t)stage * DM_BK, base + (uint32_t)wave * 1024u);
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-            dma16(gb[q] + (int64_t)stage * b_stage, base + (uint32_t)(DM_A_BYTES + (wave + 8 * q) * 1024));
+        for (int q = 0; q < B_LOADS; ++q)
+            dma16(gb[q] + (int64_t)stage * b_stage, base + (uint32_t)(DM_A_BYTES + (wave + NW * q) * 1024));
     };
 
     // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
@@ -102,7 +119,7 @@ count_i8_dma_kernel(const CountArgs args)
 #pragma unroll
     for (int ksi = 0; ksi < 2; ++ksi) {
         const int row = wr * 64 + li;
-        const int phys = (2 * ksi + lh) ^ ((row >> 1) & 3);
+        const int phys = (2 * ksi + lh) ^ ((row >> 2) & 3);
         a_off[ksi] = row * DM_BK + phys * 16;
     }
     const int tb = lane >> 4, ts = lane & 15;   // transpose-read block and slot (see count_i8.hip)
@@ -116,66 +133,105 @@ count_i8_dma_kernel(const CountArgs args)
     }
 
     v16i acc[2][2];
+
+    // One fragment set = the operands of one k-step of 32: two A row blocks, two B column blocks.
+    auto read_frags = [&](int buf, int ksi, v4i (&a)[2], v4i (&b)[2]) {
+        const int8_t *st = dma_smem + buf * DM_STAGE_BYTES;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+            a[mi] = *(const v4i *)(st + a_off[ksi] + mi * 2048);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int8_t *p = st + b_off[ni] + ksi * 8192;
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)p);
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 2048));
+            b[ni] = v4i{lo.x, lo.y, hi.x, hi.y};
+        }
+    };
+    auto mma = [&](const v4i (&a)[2], const v4i (&b)[2]) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    };
+    // wait until at most `stages` stages of this wave's loads are still in flight
+    auto wait_pending = [&](int stages) {
+        if (stages <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (stages == 1) {
+            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        } else {
+            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        }
+    };
+
+    // The barrier of a stage sits BETWEEN its two k-steps, so that the wait for the other
+    // waves and the latency of the LDS reads that follow it are covered by matrix-core work
+    // already queued: when a wave reaches barrier s it holds the fragments of k-step 1 of
+    // stage s in registers, and right after the barrier it issues the reads of k-step 0 of
+    // stage s+1 and then runs k-step 1 of stage s while they land.
+    // Barrier s certifies for all waves: the loads of stage s+1 have landed, and every read
+    // of stage s-1 is complete (its last fragments were consumed before the barrier), so the
+    // buffer of stage s-1 is refilled right after it with stage s+NSTAGE-1.
+    const int n_stages = K / DM_BK;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0;
+    int issued = 0;
+#pragma unroll
+    for (int d = 0; d < NSTAGE - 1; ++d)
+        if (d < n_stages) { issue(d, d); ++issued; }
+    wait_pending(issued - 1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
-    const int n_stages = K / DM_BK;
-    issue(0, 0);
-    if (n_stages > 1) issue(1, 1);
-
-    int buf = 0;
-    for (int s = 0; s < n_stages; ++s) {
-        // this wave's loads of stage s have landed once at most the 3 loads of stage s+1 are pending
-        if (s + 1 < n_stages)
-            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        // ... and so have every other wave's after the barrier.  A bare s_barrier: every LDS read
-        // of the previous stage was already waited for by the MFMAs that consumed it, and the
-        // full fence of __syncthreads() would drain the loads in flight for the next stages.
+    v4i fa0[2], fb0[2], fa1[2], fb1[2];
+    read_frags(0, 0, fa0, fb0);
+    int buf = 0;                                  // buffer of stage s
+    for (int s = 0; s + 1 < n_stages; ++s) {
+        const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
+        read_frags(buf, 1, fa1, fb1);
+        mma(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        // in flight now: stages s+1 .. min(s+NSTAGE-2, n_stages-1); stage s+1 must have landed
+        const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
+        wait_pending(last - (s + 1));
+        // A bare s_barrier: the full fence of __syncthreads() would drain the loads in flight.
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        // the buffer of stage s-1 is free now (all waves are past its arithmetic): refill it
-        if (s + 2 < n_stages) issue(s + 2, buf == 0 ? 2 : buf - 1);
-        const int8_t *st = dma_smem + buf * DM_STAGE_BYTES;
-#pragma unroll
-        for (int ksi = 0; ksi < 2; ++ksi) {
-            v4i a[2], b[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                a[mi] = *(const v4i *)(st + a_off[ksi] + mi * 2048);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int8_t *p = st + b_off[ni] + ksi * 8192;
-                const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)p);
-                const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(p + 2048));
-                b[ni] = v4i{lo.x, lo.y, hi.x, hi.y};
-            }
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-        }
-        buf = buf == 2 ? 0 : buf + 1;
+        if (s + NSTAGE - 1 < n_stages) issue(s + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        read_frags(nbuf, 0, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa1, fb1);
+        buf = nbuf;
     }
+    // last stage: nothing left to wait for or to fetch
+    read_frags(buf, 1, fa1, fb1);
+    mma(fa0, fb0);
+    mma(fa1, fb1);
 
     // ---- write-back through LDS: R += acc as whole 1 KB rows ----------------------------------
     // Accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block: a
     // lane holds one column.  The operand ring is free now, so the tile is transposed through it
-    // in two halves of 64 rows x 256 columns (64 KB): the waves owning the half scatter their
-    // accumulators into a row-major image, then all 8 waves add it to R with 16-byte accesses,
-    // one full 1 KB tile row per wave instruction.
+    // in WR parts of 64 rows x 256 columns: the waves owning the part scatter their accumulators
+    // into a row-major image, then all waves add it to R with 16-byte accesses, one full 1 KB
+    // tile row per wave instruction.
+    // Image row pitch 264 words: the two half-waves of a scatter store write rows 4 apart,
+    // and 4 * 264 words is 32 banks off, so the 64 lanes hit 64 distinct banks.
+    constexpr int IMG_PITCH = DM_BN + 8;
+    static_assert(64 * IMG_PITCH * 4 <= NSTAGE * DM_STAGE_BYTES, "the image must fit in the ring");
+    constexpr int ROWS_PER_WAVE = 64 / NW;
     int32_t *const img = (int32_t *)dma_smem;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        __builtin_amdgcn_s_barrier();          // the ring (or the previous half's image) is no longer read
+    for (int part = 0; part < WR; ++part) {
+        __builtin_amdgcn_s_barrier();          // the ring (or the previous part's image) is no longer read
         asm volatile("" ::: "memory");
-        if (wr == half) {
+        if (wr == part) {
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -183,42 +239,49 @@ count_i8_dma_kernel(const CountArgs args)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int r = mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        img[r * DM_BN + (wc * 2 + ni) * 32 + li] = acc[mi][ni][v];
+                        img[r * IMG_PITCH + (wc * 2 + ni) * 32 + li] = acc[mi][ni][v];
                     }
         }
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = wave * 8 + j;           // row of the half this wave adds
-            const v4i part = *(const v4i *)(img + r * DM_BN + lane * 4);
-            v4i *dst = (v4i *)(args.R + (int64_t)(row0 + half * 64 + r) * args.ldr + col0 + lane * 4);
+        for (int j = 0; j < ROWS_PER_WAVE; ++j) {
+            const int r = wave * ROWS_PER_WAVE + j;           // row of the part this wave adds
+            const v4i part4 = *(const v4i *)(img + r * IMG_PITCH + lane * 4);
+            v4i *dst = (v4i *)(args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0 + lane * 4);
             v4i cur = *dst;
-            cur.x = (int)((uint32_t)cur.x + (uint32_t)part.x);
-            cur.y = (int)((uint32_t)cur.y + (uint32_t)part.y);
-            cur.z = (int)((uint32_t)cur.z + (uint32_t)part.z);
-            cur.w = (int)((uint32_t)cur.w + (uint32_t)part.w);
+            cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
+            cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
+            cur.z = (int)((uint32_t)cur.z + (uint32_t)part4.z);
+            cur.w = (int)((uint32_t)cur.w + (uint32_t)part4.w);
             *dst = cur;
         }
     }
 }
 
-// True when the direct-to-LDS kernel may run this problem (everything interior and aligned).
-bool count_i8_dma_eligible(const CountArgs &a)
+// True when the direct-to-LDS kernel with a (64 * wr) x 256 tile may run this problem
+// (everything interior and aligned).
+bool count_i8_dma_eligible(const CountArgs &a, int wr)
 {
-    return a.vecA && a.vecB && a.vecR && a.M % DM_BM == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
+    return a.vecA && a.vecB && a.vecR && a.M % (64 * wr) == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
 }
 
-hipError_t launch_count_i8_dma(const CountArgs &a, hipStream_t s)
+template <int WR, int NSTAGE>
+static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
 {
-    constexpr int LDS = 3 * DM_STAGE_BYTES;   // 72 KB: two workgroups per compute unit
-    const int64_t tiles_m = a.M / DM_BM, tiles_n = a.N / DM_BN;
+    typedef DmaTile<WR, NSTAGE> T;
+    const int64_t tiles_m = a.M / T::BM, tiles_n = a.N / DM_BN;
     const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&count_i8_dma_kernel<3>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&count_i8_dma_kernel<WR, NSTAGE>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((count_i8_dma_kernel<3>), dim3((unsigned)grid), dim3(512), LDS, s, a);
+    hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3((unsigned)grid), dim3(T::NT), T::LDS_BYTES, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s)
+{
+    return wr == 4 ? launch_dma<4, 4>(a, s) : launch_dma<2, 3>(a, s);
 }
 
 }  // namespace amulet

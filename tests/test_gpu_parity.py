@@ -172,10 +172,11 @@ def test_empty_dimensions_are_noops(am):
 
 
 # ---- join count -----------------------------------------------------------------
-@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5, 6, 7])
 def test_count_i8_bit_exact_ragged(am, shape):
     for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (1, 1, 1), (257, 129, 1000), (64, 64, 64),
-                                       (300, 272, 128), (512, 256, 192), (256, 512, 64), (384, 768, 448)]):
+                                       (300, 272, 128), (512, 256, 192), (256, 512, 64), (384, 768, 448),
+                                       (768, 512, 320)]):
         g = np.random.Generator(np.random.PCG64(300 + idx))
         A = g.integers(-128, 128, (M, K)).astype(np.int8)
         B = g.integers(-128, 128, (K, N)).astype(np.int8)
