@@ -55,6 +55,9 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
     kernel_ms_avg = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
     ops = 2.0 * M * N * K
     achieved = ops / (kernel_ms_avg * 1e-3) / 1e12
+    # what the matrix cores sustain on this instruction with nothing around it (the clock
+    # drops under matrix-core load, so this is below the nominal peak)
+    probe_tops = 2.0 * am.amulet_probe_mfma_i8(4) / 1e12
     cpu, exact = None, None
     if args.cpu_rows > 0:
         import oracle
@@ -79,7 +82,9 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
                      "kernel_ms_avg": round(kernel_ms_avg, 4),
-                     "compulsory_bytes": M * K + K * N + 8 * M * N},
+                     "compulsory_bytes": M * K + K * N + 8 * M * N,
+                     "mfma_probe_tops": round(probe_tops, 1),
+                     "frac_of_mfma_probe": round(achieved / probe_tops, 4)},
         "cpu_baseline": cpu, "bit_exact_on_sample": exact}))
     return 0
 

@@ -250,6 +250,16 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
  */
 int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream);
 
+/*
+ * The same aid for the join count (the matrix product of Sec. 1's join
+ * translation): a register-only loop of the int8 matrix-core instruction the
+ * kernels use, on four independent accumulators per wave, `waves_per_simd`
+ * (1..8) waves per SIMD on every compute unit; writes the sustained int8
+ * multiply-adds per second (operations = 2 x that).  Allocates a small
+ * scratch buffer and blocks.  Returns AMULET_OK or a negative status.
+ */
+int amulet_probe_mfma_i8(int waves_per_simd, double *macs_per_second, void *stream);
+
 /* Printable text for a status code (static storage). */
 const char *amulet_strerror(int code);
 

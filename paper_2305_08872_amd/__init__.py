@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     amulet_mmlike_f32_general,
     amulet_mmlike_f32_shape,
     amulet_mmlike_f64,
+    amulet_probe_mfma_i8,
     amulet_probe_valu,
     amulet_register_demand,
     amulet_selected_shape,

@@ -84,6 +84,8 @@ def load_library():
     lib.amulet_choose_kernel_height.argtypes = [i32] * 9
     lib.amulet_probe_valu.restype = i32
     lib.amulet_probe_valu.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+    lib.amulet_probe_mfma_i8.restype = i32
+    lib.amulet_probe_mfma_i8.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.amulet_strerror.restype = ctypes.c_char_p
     lib.amulet_strerror.argtypes = [i32]
     lib.amulet_last_launch_error.restype = ctypes.c_char_p
@@ -313,6 +315,14 @@ def amulet_probe_valu(mix: int, waves_per_simd: int, stream=None) -> float:
     out = ctypes.c_double(0.0)
     _check(load_library().amulet_probe_valu(mix, waves_per_simd, ctypes.byref(out), _stream_ptr(stream)),
            "amulet_probe_valu")
+    return out.value
+
+
+def amulet_probe_mfma_i8(waves_per_simd: int, stream=None) -> float:
+    """Sustained int8 multiply-adds/s of a register-only loop of the join count's matrix-core instruction."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().amulet_probe_mfma_i8(waves_per_simd, ctypes.byref(out), _stream_ptr(stream)),
+           "amulet_probe_mfma_i8")
     return out.value
 
 

@@ -53,7 +53,7 @@ struct CountTile {
     static constexpr int CI_BK = BK, CI_APITCH = BK + 16;
     static constexpr int NT = 64 * WR * WC;
     static constexpr int BM = WR * MB * 32, BN = WC * NB * 32;
-    static constexpr int BPITCH = BN + 16;
+    static constexpr int BPITCH = BN + 32;
     static constexpr int A_BYTES = BM * CI_APITCH, B_BYTES = CI_BK * BPITCH;
     static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
 };

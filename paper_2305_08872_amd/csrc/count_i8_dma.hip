@@ -10,8 +10,10 @@
 //     u ^ ((r >> 2) & 3).  A ds_read_b128 is served 16 lanes (256 bytes, all 64 banks) per
 //     clock, and 16 neighbouring rows fall in 16 distinct 16-byte bank groups:
 //     4 * (r & 3) + (u ^ ((r >> 2) & 3)) runs through 0..15;
-//   B tile [64 k][256 B]: row k keeps logical unit u at u ^ (k & 7), so the 8 rows a
-//     ds_read_b64_tr_b8 block reads (same logical unit) fall in 8 distinct bank groups.
+//   B tile [64 k][256 B]: row k keeps logical unit u at u ^ (2 * (k & 7)).  A 16-lane block of a
+//     ds_read_b64_tr_b8 reads one logical unit of 8 consecutive rows and its neighbour block
+//     the unit next to it (u ^ 1): the 16 (row, unit) pairs of two blocks fall in 16 distinct
+//     bank groups.
 // One barrier per stage, placed between the stage's two k-steps (see the main loop), with the
 // loads of NSTAGE-2 later stages in flight behind it.
 //
@@ -89,7 +91,7 @@ count_i8_dma_kernel(const CountArgs args)
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) {
         const int krow = (wave + NW * q) * 4 + (lane >> 4);
-        const int blog = (lane & 15) ^ (krow & 7);
+        const int blog = (lane & 15) ^ ((krow & 7) << 1);
         gb[q] = args.B + (int64_t)krow * args.ldb + col0 + blog * 16;
     }
     const int64_t b_stage = (int64_t)DM_BK * args.ldb;
@@ -128,7 +130,7 @@ count_i8_dma_kernel(const CountArgs args)
     for (int ni = 0; ni < 2; ++ni) {
         const int krow = 16 * (tb >> 1) + (ts >> 1);
         const int colbyte = (wc * 2 + ni) * 32 + 16 * (tb & 1) + 8 * (ts & 1);
-        const int phys = (colbyte >> 4) ^ (krow & 7);
+        const int phys = (colbyte >> 4) ^ ((krow & 7) << 1);
         b_off[ni] = DM_A_BYTES + krow * DM_BN + phys * 16 + (colbyte & 15);
     }
 

@@ -65,9 +65,72 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+typedef int probe_v4i __attribute__((ext_vector_type(4)));
+typedef int probe_v16i __attribute__((ext_vector_type(16)));
+
+// Register-only loop of the join count's matrix-core instruction (v_mfma_i32_32x32x32_i8)
+// on four independent accumulators, as in the kernel's 2 x 2 block.
+__global__ void __launch_bounds__(256) mfma_i8_probe_kernel(int *out, int iters)
+{
+    const int lane = threadIdx.x;
+    const probe_v4i a = {lane, lane * 3, lane * 5, lane * 7}, b = {lane * 11, lane ^ 0x55, lane + 9, lane * 13};
+    probe_v16i acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace amulet
 
 using namespace amulet;
+
+extern "C" int amulet_probe_mfma_i8(int waves_per_simd, double *macs_per_second, void *stream)
+{
+    if (waves_per_simd < 1 || waves_per_simd > 8) return AMULET_ERR_DIM;
+    if (!macs_per_second) return AMULET_ERR_NULL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return AMULET_ERR_LAUNCH;
+    const int iters = 2000;
+    const int grid = cus * waves_per_simd;  // 256 threads = one wave per SIMD per workgroup
+    int *out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipStream_t s = (hipStream_t)stream;
+    int rc = AMULET_ERR_LAUNCH;
+    if (hipMalloc(&out, (size_t)grid * 256 * sizeof(int)) == hipSuccess &&
+        hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
+        for (int rep = 0; rep < 2; ++rep) {  // first repetition is the warm-up
+            (void)hipEventRecord(e0, s);
+            hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(grid), dim3(256), 0, s, out, iters);
+            (void)hipEventRecord(e1, s);
+        }
+        float ms = 0.0f;
+        if (hipGetLastError() == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+            hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.0f) {
+            // per wave and iteration: 16 instructions of 32 x 32 x 32 multiply-adds
+            *macs_per_second = (double)grid * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e-3);
+            rc = AMULET_OK;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (out) (void)hipFree(out);
+    return rc;
+}
 
 extern "C" int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream)
 {
