@@ -98,6 +98,9 @@ CONFIGS = {
     "cfg4_discount_16384x2048x8192": dict(task=DISCOUNT, M=16384, N=2048, K=8192, seed=4,
                                           gen="retail"),
     "headline_discount_8192": dict(task=DISCOUNT, M=8192, N=8192, K=8192, seed=4, gen="retail"),
+    # the paper's own element type (its listings are double): same recipes, widened to fp64
+    "f64_discount_4096": dict(task=DISCOUNT, M=4096, N=4096, K=4096, seed=5, gen="retail", dtype="f64"),
+    "f64_boost_2048": dict(task=BOOST, M=2048, N=2048, K=2048, seed=6, gen="signal", dtype="f64"),
 }
 
 _GENS = {"retail": retail, "signal": signal, "uniform_pm1": uniform_pm1,
@@ -113,4 +116,7 @@ def make(name: str):
         A, B = out
         return spec, A, B, None
     A, B, params = out
+    if spec.get("dtype") == "f64":
+        A, B = A.astype(np.float64), B.astype(np.float64)
+        params = None if params is None else params.astype(np.float64)
     return spec, A, B, params

@@ -29,6 +29,7 @@ VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 3, "identity": 1}
 
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, 5.0 POP/s
+FP64_VECTOR_PEAK_TFLOPS = 78.6  # MI355X fp64 vector peak
 
 
 def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
@@ -89,6 +90,65 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
     return 0
 
 
+def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
+    """Secondary line: a task in the paper's own element type (fp64) on the vector ALU."""
+    task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
+    tname = wl.TASK_NAMES[task]
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    th = torch.from_numpy(P[0]).cuda() if P is not None else None
+    dis = torch.from_numpy(P[1]).cuda() if (P is not None and P.shape[0] > 1) else None
+    dR = torch.zeros(M, N, dtype=torch.float64, device="cuda")
+    for _ in range(args.warmup):
+        am.amulet_mmlike_f64(task, dA, dB, th, dis, dR)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        am.amulet_mmlike_f64(task, dA, dB, th, dis, dR)
+        stops[i].record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
+    kernel_ms_avg = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    flops = 2.0 * M * N * K
+    achieved = flops / (kernel_ms_avg * 1e-3) / 1e12
+    # issue slots per product: a 64-bit select is two v_cndmask_b32
+    ops = {"identity": 1, "discount": 5, "boost": 4, "count_gt": 4}[tname]
+    cpu, parity = None, None
+    if args.cpu_rows > 0:
+        import oracle
+        rows = np.sort(np.random.Generator(np.random.PCG64(99)).choice(M, min(args.cpu_rows, M), replace=False))
+        Rz = torch.zeros(M, N, dtype=torch.float64, device="cuda")
+        am.amulet_mmlike_f64(task, dA, dB, th, dis, Rz)
+        torch.cuda.synchronize()
+        R_rows = Rz[torch.from_numpy(rows).cuda()].cpu().numpy()
+        c0 = time.perf_counter()
+        R_ref, ab, threads = oracle.mmlike_f64_general(task, np.ascontiguousarray(A[rows]), B,
+                                                       None if P is None else P[0],
+                                                       None if (P is None or P.shape[0] < 2) else P[1])
+        cpu_s = time.perf_counter() - c0
+        cpu = {"value": round(2.0 * len(rows) * N * K / cpu_s / 1e9, 3), "unit": "GFLOP/s (2MNK/t)",
+               "cores": threads, "kind": "oracle",
+               "sample": "%d whole rows of the %dx%dx%d workload, %.1f s" % (len(rows), M, N, K, cpu_s)}
+        parity = float(np.max(np.abs(R_rows - R_ref) / np.where(ab > 0, ab, 1.0)))
+    print(json.dumps({
+        "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp64" % (tname, M, N, K),
+        "value": round(flops / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": args.workload, "task": tname, "M": M, "N": N, "K": K,
+                   "tile_shape": "valu_f64_16x128_k16"},
+        "roofline": {"bound": "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel_ms_avg": round(kernel_ms_avg, 4), "valu_ops_per_product": ops,
+                     "op_mix_ceiling_tflops": round(FP64_VECTOR_PEAK_TFLOPS / ops, 3),
+                     "frac_of_op_mix_ceiling": round(achieved * ops / FP64_VECTOR_PEAK_TFLOPS, 4)},
+        "cpu_baseline": cpu, "parity_worst_ratio_on_sample": parity,
+        "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)"}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +183,8 @@ def main() -> int:
     task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
     if task == "count_i8":
         return bench_count_i8(args, am, torch, np, spec, A, B)
+    if spec.get("dtype") == "f64":
+        return bench_f64(args, am, torch, np, wl, spec, A, B, P)
     tname = wl.TASK_NAMES[task]
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dP = torch.from_numpy(P).cuda() if P is not None else None
