@@ -22,37 +22,62 @@ constexpr int D_TM = 4, D_NW = 4, D_BK = 16, D_BN = 128, D_NT = 64 * D_NW;
 template <int TASK> struct AccD { typedef double type; };
 template <> struct AccD<TASK_COUNT_GT> { typedef int type; };
 
-// Two products of one A value with a lane's two B values.  The multiply is a separately
-// rounded fp64 operation wherever a comparison depends on it (contraction is off).
+// One k of the micro-tile: the D_TM x 2 products of the wave's A values with a lane's two B
+// values, written stage by stage over all eight products so that no instruction waits on the
+// one just issued.  The multiply is a separately rounded fp64 operation wherever a comparison
+// depends on it (contraction is off).
 template <int TASK>
-__device__ __forceinline__ void fold2(double a, d2 b, const double *th, const double *q,
-                                      typename AccD<TASK>::type *acc)
+__device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const double (&th)[D_TM][2],
+                                          const double *q, typename AccD<TASK>::type (&acc)[D_TM][2])
 {
     if constexpr (TASK == TASK_IDENTITY) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) acc[c] = __builtin_fma(a, b[c], acc[c]);
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) acc[r][c] = __builtin_fma(a[r], b[c], acc[r][c]);
     } else if constexpr (TASK == TASK_DISCOUNT) {
-        double p[2], s[2];
+        double p[D_TM][2], s[D_TM][2];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) p[c] = a * b[c];
+        for (int r = 0; r < D_TM; ++r)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) s[c] = (p[c] > th[c]) ? q[c] : 1.0;   // q = 1 - dis[j]
+            for (int c = 0; c < 2; ++c) p[r][c] = a[r] * b[c];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) acc[c] = __builtin_fma(p[c], s[c], acc[c]);
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) s[r][c] = (p[r][c] > th[r][c]) ? q[c] : 1.0;   // q = 1 - dis[j]
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) acc[r][c] = __builtin_fma(p[r][c], s[r][c], acc[r][c]);
     } else if constexpr (TASK == TASK_BOOST) {
         // p + max(p - th, 0): continuous in p, so the fused product is within tolerance
+        double d[D_TM][2];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const double d = __builtin_fma(a, b[c], -th[c]);
-            acc[c] = __builtin_fma(a, b[c], acc[c]);
-            acc[c] += __builtin_fmax(d, 0.0);
-        }
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) d[r][c] = __builtin_fma(a[r], b[c], -th[r][c]);
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) acc[r][c] = __builtin_fma(a[r], b[c], acc[r][c]);
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) d[r][c] = __builtin_fmax(d[r][c], 0.0);
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) acc[r][c] += d[r][c];
     } else {
+        double p[D_TM][2];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const double p = a * b[c];
-            acc[c] += (int)(p > th[c]);
-        }
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) p[r][c] = a[r] * b[c];
+#pragma unroll
+        for (int r = 0; r < D_TM; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) acc[r][c] += (int)(p[r][c] > th[r][c]);
     }
 }
 
@@ -118,15 +143,18 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 th_el[r][c] = (col < N) ? args.thres[(int64_t)rowc(r) * args.ldt + col] : __builtin_inf();
         }
     }
-    auto thres2 = [&](int r, double *t2) {
+    // the micro-tile's thresholds as one table (copies of the same registers: the forms differ
+    // only in which registers repeat)
+    double th[D_TM][2];
+#pragma unroll
+    for (int r = 0; r < D_TM; ++r)
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            if constexpr (TF == THRES_COL) t2[c] = th_col[c];
-            else if constexpr (TF == THRES_ROW) t2[c] = th_row[r];
-            else if constexpr (TF == THRES_CONST) t2[c] = th_const;
-            else t2[c] = th_el[r][c];
+            if constexpr (TF == THRES_COL) th[r][c] = th_col[c];
+            else if constexpr (TF == THRES_ROW) th[r][c] = th_row[r];
+            else if constexpr (TF == THRES_CONST) th[r][c] = th_const;
+            else th[r][c] = th_el[r][c];
         }
-    };
 
     acc_t acc[D_TM][2];
 #pragma unroll
@@ -208,25 +236,21 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kk = 0; kk < KA; ++kk)
+                for (int kk = 0; kk < KA; ++kk) {
+                    double ak[D_TM];
 #pragma unroll
-                    for (int r = 0; r < D_TM; ++r) {
-                        double t2[2];
-                        thres2(r, t2);
-                        fold2<TASK>(a[r][kk], b[kk], t2, q, acc[r]);
-                    }
+                    for (int r = 0; r < D_TM; ++r) ak[r] = a[r][kk];
+                    fold_rows<TASK>(ak, b[kk], th, q, acc);
+                }
             }
         } else {
             // K remainder: k by k, never zero-padded (g(0) is not 0 in general)
             for (int kk = 0; kk < tail; ++kk) {
                 const d2 b = *(const d2 *)(bs + kk * D_BN);
+                double ak[D_TM];
 #pragma unroll
-                for (int r = 0; r < D_TM; ++r) {
-                    const double a1 = As[arow[r] + k0 + kk];
-                    double t2[2];
-                    thres2(r, t2);
-                    fold2<TASK>(a1, b, t2, q, acc[r]);
-                }
+                for (int r = 0; r < D_TM; ++r) ak[r] = As[arow[r] + k0 + kk];
+                fold_rows<TASK>(ak, b, th, q, acc);
             }
         }
         if (t + 1 < n_tiles) store_tile(buf ^ 1);
