@@ -6,8 +6,8 @@
 // 64 x 64 sub-tile = 2x2 MFMA blocks of 32 x 32 (64 accumulator registers).
 // K is staged 16 at a time: A tile 128 x 16 (k contiguous, row pitch padded to
 // 20 floats so 16-byte fragment reads spread over all banks) and B tile
-// 16 x 128 (as in global memory, rows padded to 136 floats), global -> registers
-// -> LDS, double buffered, one barrier per stage.
+// 16 x 128 (as in global memory), global -> registers -> LDS, double buffered,
+// one barrier per stage.
 //
 // Fragment mapping: lane l supplies row i = l % 32 (A) or column j = l % 32 (B)
 // and k-slot h = l / 32.  The hardware multiplies A's slot h with B's slot h,
@@ -31,9 +31,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int MI_BM = 128, MI_BN = 128, MI_BK = 16;
 constexpr int MI_APITCH = MI_BK + 4;   // floats
-// B rows are padded by 8 floats: the two half-waves of a fragment read take rows 4 apart,
-// and 4 * 136 floats is 32 banks off, so the 64 lanes of the read hit 64 distinct banks
-constexpr int MI_BPITCH = MI_BN + 8;
 
 // 4 waves per SIMD (at most 128 registers): four 128 x 128 workgroups per compute unit, which is
 // what lets a 4096 x 4096 result (1024 tiles on 256 compute units) run as one full round.
@@ -41,7 +38,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))
 identity_mfma_kernel(const MmlikeArgs args)
 {
     __shared__ __attribute__((aligned(16))) float As[2][MI_BM][MI_APITCH];
-    __shared__ __attribute__((aligned(16))) float Bs[2][MI_BK][MI_BPITCH];
+    __shared__ __attribute__((aligned(16))) float Bs[2][MI_BK][MI_BN];
 
     const int M = args.M, N = args.N, K = args.K;
     const int tid = threadIdx.x;
