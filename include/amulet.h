@@ -248,6 +248,20 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
  * writes the sustained products per second.  Allocates a small scratch buffer
  * and blocks, like amulet_tune.  Returns AMULET_OK or a negative status.
  */
+/*
+ * The tile order of the kernels (an MI355X-side analogue of the loop order the
+ * paper's tiling fixes, Sec. 3): a launch covers a tiles_m x tiles_n grid of
+ * R tiles with amulet_tile_grid() workgroups; workgroup b runs on XCD b % 8,
+ * and the grid is cut into 8 rectangular parts, one per XCD, so that the
+ * workgroups resident on an XCD share A rows and B columns through its L2.
+ * amulet_tile_of_workgroup writes the tile (tm, tn) of workgroup `block` and
+ * returns 1, or returns 0 when that workgroup is padding (it exits at once),
+ * or a negative status for bad arguments.  Host-only helpers; every tile is
+ * owned by exactly one workgroup.
+ */
+int64_t amulet_tile_grid(int64_t tiles_m, int64_t tiles_n);
+int amulet_tile_of_workgroup(int64_t block, int64_t tiles_m, int64_t tiles_n, int64_t *tm, int64_t *tn);
+
 int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream);
 
 /*

@@ -34,6 +34,8 @@ from .binding import (  # noqa: F401
     amulet_shape_count,
     amulet_shape_name,
     amulet_strerror,
+    amulet_tile_grid,
+    amulet_tile_of_workgroup,
     amulet_tune,
     amulet_version,
     library_path,

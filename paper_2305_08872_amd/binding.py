@@ -84,6 +84,10 @@ def load_library():
     lib.amulet_choose_kernel_height.argtypes = [i32] * 9
     lib.amulet_probe_valu.restype = i32
     lib.amulet_probe_valu.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+    lib.amulet_tile_grid.restype = i64
+    lib.amulet_tile_grid.argtypes = [i64, i64]
+    lib.amulet_tile_of_workgroup.restype = i32
+    lib.amulet_tile_of_workgroup.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.amulet_probe_mfma_i8.restype = i32
     lib.amulet_probe_mfma_i8.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.amulet_strerror.restype = ctypes.c_char_p
@@ -316,6 +320,19 @@ def amulet_probe_valu(mix: int, waves_per_simd: int, stream=None) -> float:
     _check(load_library().amulet_probe_valu(mix, waves_per_simd, ctypes.byref(out), _stream_ptr(stream)),
            "amulet_probe_valu")
     return out.value
+
+
+def amulet_tile_grid(tiles_m: int, tiles_n: int) -> int:
+    """Workgroups launched for a tiles_m x tiles_n grid of R tiles (padding included)."""
+    return load_library().amulet_tile_grid(tiles_m, tiles_n)
+
+
+def amulet_tile_of_workgroup(block: int, tiles_m: int, tiles_n: int):
+    """(tm, tn) of workgroup `block`, or None when that workgroup is padding."""
+    tm, tn = ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = _check(load_library().amulet_tile_of_workgroup(block, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn)),
+                "amulet_tile_of_workgroup")
+    return (tm.value, tn.value) if rc == 1 else None
 
 
 def amulet_probe_mfma_i8(waves_per_simd: int, stream=None) -> float:

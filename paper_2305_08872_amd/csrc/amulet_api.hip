@@ -526,6 +526,25 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
     return result;
 }
 
+int64_t amulet_tile_grid(int64_t tiles_m, int64_t tiles_n)
+{
+    if (tiles_m <= 0 || tiles_n <= 0) return 0;
+    return xcd_grid(tiles_m, tiles_n);
+}
+
+int amulet_tile_of_workgroup(int64_t block, int64_t tiles_m, int64_t tiles_n, int64_t *tm, int64_t *tn)
+{
+    if (!tm || !tn) return AMULET_ERR_NULL;
+    if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > kMaxDim || tiles_n > kMaxDim || block < 0 ||
+        block >= xcd_grid(tiles_m, tiles_n) || block > 0x7fffffffLL)
+        return AMULET_ERR_DIM;
+    int m = 0, n = 0;
+    const bool real = xcd_tile((int)block, (int)tiles_m, (int)tiles_n, m, n);
+    *tm = m;
+    *tn = n;
+    return real ? 1 : 0;
+}
+
 int amulet_shape_count(int task) { return n_shapes(task); }
 
 const char *amulet_shape_name(int task, int shape)

@@ -12,6 +12,51 @@ enum { TASK_IDENTITY = 0, TASK_DISCOUNT = 1, TASK_BOOST = 2, TASK_COUNT_GT = 3 }
 // form of the threshold operand (paper Sec. 6.3): thres[j], thres[i], a constant, thres[i][j]
 enum { THRES_COL = 0, THRES_ROW = 1, THRES_CONST = 2, THRES_ELEM = 3 };
 
+// XCD-aware tile order, shared by every tiled kernel.  Workgroups are handed to the 8 XCDs
+// round-robin (workgroup b runs on XCD b % 8) and each XCD has its own L2.  The tile grid of R
+// is cut into 8 rectangular parts, px column parts by 8 / px row parts, and XCD x walks its
+// part row tile by row tile: the workgroups resident on an XCD at any moment form a compact
+// block of R that shares A rows and B columns through that L2.  px is the one of 8, 4, 2, 1
+// whose largest part is smallest (ties go to more column parts), so that narrow grids and
+// column counts that are not multiples of 8 still load all XCDs evenly.  The grid is padded
+// to 8 * cw * rh workgroups; those past the edge leave at once.
+struct XcdParts {
+    int px;   // column parts
+    int cw;   // column tiles per part
+    int rh;   // row tiles per part
+};
+__host__ __device__ inline XcdParts xcd_parts(int64_t tiles_m, int64_t tiles_n)
+{
+    XcdParts best = {8, 0, 0};
+    int64_t best_size = -1;
+    for (int px = 8; px >= 1; px >>= 1) {
+        const int py = 8 / px;
+        const int64_t cw = (tiles_n + px - 1) / px, rh = (tiles_m + py - 1) / py;
+        if (best_size < 0 || cw * rh < best_size) {
+            best_size = cw * rh;
+            best.px = px;
+            best.cw = (int)cw;
+            best.rh = (int)rh;
+        }
+    }
+    return best;
+}
+// workgroups to launch for a tile grid
+inline int64_t xcd_grid(int64_t tiles_m, int64_t tiles_n)
+{
+    const XcdParts g = xcd_parts(tiles_m, tiles_n);
+    return 8LL * g.cw * g.rh;
+}
+// tile of workgroup `block`; false when the workgroup is padding
+__host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const XcdParts g = xcd_parts(tiles_m, tiles_n);
+    const int xcd = block & 7, slot = block >> 3;
+    tn = (xcd % g.px) * g.cw + slot % g.cw;
+    tm = (xcd / g.px) * g.rh + slot / g.cw;
+    return tn < tiles_n && tm < tiles_m;
+}
+
 // Arguments of an fp32 task launch, already validated on the host.
 struct MmlikeArgs {
     const float *A;

@@ -84,17 +84,12 @@ count_i8_mfma_kernel(const CountArgs args)
     const int wr = wave / WC, wc = wave % WC;
     const int li = lane & 31, lh = lane >> 5;
 
-    // XCD-aware tile order.  Workgroups are handed to the 8 XCDs round-robin (workgroup b
-    // runs on XCD b % 8) and each XCD has its own L2.  XCD x is given its own band of column
-    // tiles and walks it row tile by row tile, so the workgroups resident on an XCD at any
-    // moment form a compact block of R that shares its A rows and B columns through that L2.
+    // XCD-aware tile order (xcd_tile in amulet_internal.h): each XCD walks its own rectangular
+    // part of the tile grid, so its resident workgroups share A rows and B columns through its L2
     const int tiles_m = (M + BM - 1) / BM;
     const int tiles_n = (N + BN - 1) / BN;
-    const int band = (tiles_n + 7) / 8;              // column tiles per XCD
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tn = xcd * band + slot % band;
-    const int tm = slot / band;
-    if (tn >= tiles_n || tm >= tiles_m) return;      // padding of the last band (whole workgroup leaves)
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * BM, col0 = tn * BN;
     const bool vecA = args.vecA != 0, vecB = args.vecB != 0;
 
@@ -243,7 +238,7 @@ static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
 {
     typedef CountTile<MB, NB, WR, WC, BK> T;
     const int64_t tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
-    const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
+    const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (T::LDS_BYTES > 65536) {
         // more than 64 KB of LDS per workgroup has to be granted once per kernel

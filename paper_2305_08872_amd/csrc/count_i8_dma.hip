@@ -72,13 +72,10 @@ count_i8_dma_kernel(const CountArgs args)
     const int wr = wave >> 2, wc = wave & 3;
     const int li = lane & 31, lh = lane >> 5;
 
-    // XCD-aware tile order (see count_i8.hip)
+    // XCD-aware tile order (xcd_tile in amulet_internal.h)
     const int tiles_m = args.M / DM_BM, tiles_n = args.N / DM_BN;
-    const int band = (tiles_n + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tn = xcd * band + slot % band;
-    const int tm = slot / band;
-    if (tn >= tiles_n || tm >= tiles_m) return;
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * DM_BM, col0 = tn * DM_BN;
 
     // ---- what each lane fetches: one A slot and B_LOADS B slots per stage ----------------
@@ -272,7 +269,7 @@ static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
 {
     typedef DmaTile<WR, NSTAGE> T;
     const int64_t tiles_m = a.M / T::BM, tiles_n = a.N / DM_BN;
-    const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;
+    const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&count_i8_dma_kernel<WR, NSTAGE>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);

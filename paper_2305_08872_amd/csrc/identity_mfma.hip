@@ -47,16 +47,12 @@ identity_mfma_kernel(const MmlikeArgs args)
     const int wr = wave >> 1, wc = wave & 1;
     const int li = lane & 31, lh = lane >> 5;
 
-    // XCD-aware tile order: workgroup b runs on XCD b % 8; each XCD walks its own band of
-    // column tiles row tile by row tile, so its resident workgroups share A rows and B
-    // columns through that XCD's L2.
+    // XCD-aware tile order (xcd_tile in amulet_internal.h): each XCD walks its own rectangular
+    // part of the tile grid, so its resident workgroups share A rows and B columns through its L2
     const int tiles_m = (M + MI_BM - 1) / MI_BM;
     const int tiles_n = (N + MI_BN - 1) / MI_BN;
-    const int band = (tiles_n + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tn = xcd * band + slot % band;
-    const int tm = slot / band;
-    if (tn >= tiles_n || tm >= tiles_m) return;   // padding of the last band
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * MI_BM, col0 = tn * MI_BN;
     const bool vecA = args.vecA != 0, vecB = args.vec != 0;
     // Interior tiles with 16-byte aligned rows are staged as (wave-uniform base that advances
@@ -207,7 +203,7 @@ hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + MI_BM - 1) / MI_BM;
     const int64_t tiles_n = (a.N + MI_BN - 1) / MI_BN;
-    const int64_t grid = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
+    const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(identity_mfma_kernel, dim3((unsigned)grid), dim3(256), 0, s, a);
     return hipGetLastError();

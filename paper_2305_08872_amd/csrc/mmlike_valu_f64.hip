@@ -101,11 +101,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     // XCD-aware tile order, as in the fp32 kernels
     const int tiles_m = (M + D_NW * D_TM - 1) / (D_NW * D_TM);
     const int tiles_n = (N + D_BN - 1) / D_BN;
-    const int band = (tiles_n + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tn = xcd * band + slot % band;
-    const int tm = slot / band;
-    if (tn >= tiles_n || tm >= tiles_m) return;
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * (D_NW * D_TM) + wave * D_TM;
     const int col0 = tn * D_BN;
 
@@ -292,7 +289,7 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
 {
     const int64_t tiles_m = (a.M + D_NW * D_TM - 1) / (D_NW * D_TM);
     const int64_t tiles_n = (a.N + D_BN - 1) / D_BN;
-    const int64_t wgs = 8 * ((tiles_n + 7) / 8) * tiles_m;
+    const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs);
     switch (task) {

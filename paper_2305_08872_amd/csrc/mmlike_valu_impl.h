@@ -117,17 +117,12 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned: float4 global accesses
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // XCD-aware tile order.  Workgroups are handed to the 8 XCDs round-robin (workgroup b runs
-    // on XCD b % 8) and each XCD has its own L2: XCD x gets its own band of column tiles and
-    // walks it row tile by row tile, so the workgroups resident on an XCD at any moment form a
-    // compact block of R sharing A rows and B columns through that L2.
+    // XCD-aware tile order (xcd_tile in amulet_internal.h): each XCD walks its own rectangular
+    // part of the tile grid, so its resident workgroups share A rows and B columns through its L2
     const int tiles_m = (M + NW * TM - 1) / (NW * TM);
     const int tiles_n = (N + BN - 1) / BN;
-    const int band = (tiles_n + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tn = xcd * band + slot % band;
-    const int tm = slot / band;
-    if (tn >= tiles_n || tm >= tiles_m) return;   // padding of the last band: the whole workgroup leaves
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * (NW * TM) + wave * TM;
     const int col0 = tn * BN;
 
@@ -433,7 +428,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + NW * TM - 1) / (NW * TM);
     const int64_t tiles_n = (a.N + 256 * NG - 1) / (256 * NG);
-    const int64_t wgs = 8 * ((tiles_n + 7) / 8) * tiles_m;   // 8 XCD bands, the last one padded
+    const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs), block(64 * NW);
     if (a.transA || a.transB)

@@ -109,3 +109,42 @@ def test_shape_table_is_the_two_axis_grid(lib):
     assert len(set(names)) == n and all(x.startswith("valu_") for x in names)
     assert 0 <= am.amulet_selected_shape(1, 8192, 8192, 8192) < n
     assert am.amulet_shape_count(am.AMULET_TASK_COUNT_I8) >= 1
+
+
+def test_tile_order_covers_every_tile_exactly_once(lib):
+    """The XCD-aware workgroup -> tile map: every tile of the grid has exactly one owner, padding
+    workgroups own none, and narrow grids still give work to all 8 XCDs (workgroup b runs on
+    XCD b % 8)."""
+    for tiles_m, tiles_n in [(1, 1), (16, 1), (128, 8), (512, 32), (7, 3), (5, 9), (64, 4), (33, 2), (3, 100),
+                             (1, 8), (9, 17), (512, 9), (64, 17), (1000, 1)]:
+        grid = am.amulet_tile_grid(tiles_m, tiles_n)
+        assert grid % 8 == 0 and grid >= tiles_m * tiles_n
+        owners = {}
+        xcds_used = set()
+        for b in range(grid):
+            t = am.amulet_tile_of_workgroup(b, tiles_m, tiles_n)
+            if t is None:
+                continue
+            assert 0 <= t[0] < tiles_m and 0 <= t[1] < tiles_n
+            assert t not in owners, (tiles_m, tiles_n, b, owners.get(t))
+            owners[t] = b
+            xcds_used.add(b % 8)
+        assert len(owners) == tiles_m * tiles_n
+        # load balance: no XCD owns more than its even share plus what rounding to whole
+        # rows and columns of tiles costs
+        per_xcd = [sum(1 for b in owners.values() if b % 8 == x) for x in range(8)]
+        assert max(per_xcd) * 8 == grid
+        if tiles_m * tiles_n >= 64:
+            assert len(xcds_used) == 8
+            assert max(per_xcd) <= 1.5 * tiles_m * tiles_n / 8 + 1, (tiles_m, tiles_n, per_xcd)
+        # an XCD's tiles form one rectangle
+        for x in xcds_used:
+            ts = [t for t, b in owners.items() if b % 8 == x]
+            rows, cols = {t[0] for t in ts}, {t[1] for t in ts}
+            assert len(ts) == len(rows) * len(cols)
+            assert max(rows) - min(rows) + 1 == len(rows) and max(cols) - min(cols) + 1 == len(cols)
+    # wide grids: 8 column bands, one per XCD
+    assert am.amulet_tile_grid(512, 32) == 8 * 4 * 512
+    assert am.amulet_tile_of_workgroup(8 * 4 * 512 - 1, 512, 32) == (511, 31)
+    with pytest.raises(am.AmuletError):
+        am.amulet_tile_of_workgroup(10 ** 9, 4, 4)
