@@ -43,8 +43,10 @@ static int n_shapes(int task)
 
 // Built-in choice when nothing was tuned.  The predicate tasks are bound by
 // VALU issue, which needs several resident waves per SIMD to keep both issue
-// slots busy, so the small 4x4 micro-tile (16 x 256 tile, about 100 registers)
-// with 16-deep staging is the measured best from 256^3 up to 16384 x 2048 x 8192.
+// slots busy, so the small 4x4 micro-tile (about 110 registers) with 16-deep
+// staging is the measured best at every size; of its two workgroup sizes the
+// 8-wave one (32 x 256) is ahead by 2-9 % once there are two such tiles per
+// compute unit, the 4-wave one (16 x 256) below that.
 static int default_shape(int task, int64_t M, int64_t N, int64_t)
 {
     // matrix cores, operands streamed straight into LDS: the 256 x 256 tile when it still gives
@@ -52,7 +54,8 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t)
     // kernel when the problem is not fully interior and aligned)
     if (task == AMULET_TASK_COUNT_I8) return ((M / 256) * ((N + 255) / 256) >= 512) ? 7 : 6;
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
-    return VALU_TILES + 0;
+    const int64_t tiles32 = ((M + 31) / 32) * ((N + 255) / 256);
+    return tiles32 >= 512 ? VALU_TILES + 1 : VALU_TILES + 0;
 }
 
 static int lookup_shape(int task, int64_t M, int64_t N, int64_t K)

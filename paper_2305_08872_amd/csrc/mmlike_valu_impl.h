@@ -355,15 +355,24 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kk = 0; kk < KA; ++kk)
+                for (int kk = 0; kk < KA; ++kk) {
 #pragma unroll
-                    for (int r = 0; r < TM; ++r)
+                    for (int r = 0; r < TM; ++r) {
 #pragma unroll
                         for (int g = 0; g < NG; ++g) {
                             float t4[4];
                             thres4(r, g, t4);
                             fold4<TASK>(a[r][kk], b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
                         }
+                        // At most 4 rows of one k between fences: left alone, the scheduler may
+                        // gather the compares of the whole chunk, and their lane masks (a scalar
+                        // register pair each) overflow the scalar register file into spills.
+                        // (The 8-row micro-tiles spill their A values regardless and lose more
+                        // from the fence than they gain: they are left to the scheduler.)
+                        if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
+                            if (r == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
         } else {
             // K remainder: k by k, so no padded product is ever evaluated.
