@@ -279,7 +279,7 @@ def main() -> int:
     if os.path.exists(tpath):
         with open(tpath) as f:
             rec = json.load(f).get(args.workload)
-        if rec:
+        if rec and rec.get("tile_shape") == am.amulet_shape_name(task, shape):   # measured for this very kernel
             traffic = rec["hbm_bytes_per_launch"]
 
     lib_ratio = None
