@@ -101,6 +101,7 @@ CONFIGS = {
     # the paper's own element type (its listings are double): same recipes, widened to fp64
     "f64_discount_4096": dict(task=DISCOUNT, M=4096, N=4096, K=4096, seed=5, gen="retail", dtype="f64"),
     "f64_boost_2048": dict(task=BOOST, M=2048, N=2048, K=2048, seed=6, gen="signal", dtype="f64"),
+    "f64_identity_4096": dict(task=IDENTITY, M=4096, N=4096, K=4096, seed=7, gen="uniform_pm1", dtype="f64"),
 }
 
 _GENS = {"retail": retail, "signal": signal, "uniform_pm1": uniform_pm1,

@@ -338,6 +338,7 @@ int amulet_mmlike_f64(int task, int thres_form, int64_t M, int64_t N, int64_t K,
     a.lda = lda; a.ldb = ldb; a.ldr = ldr; a.ldt = ldt;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
     a.vec = (aligned16(B) && aligned16(R) && ldb % 2 == 0 && ldr % 2 == 0) ? 1 : 0;
+    a.vecA = (aligned16(A) && lda % 2 == 0) ? 1 : 0;
     const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

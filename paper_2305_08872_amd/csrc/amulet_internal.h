@@ -120,8 +120,11 @@ struct MmlikeArgsF64 {
     int64_t lda, ldb, ldr, ldt;
     int M, N, K;
     int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
+    int vecA;  // 1 when A and its row pitch do
 };
+// predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);
+hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
 
 }  // namespace amulet
 #endif

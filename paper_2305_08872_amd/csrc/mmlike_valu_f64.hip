@@ -293,7 +293,7 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs);
     switch (task) {
-    case TASK_IDENTITY: return launch_f64_form<TASK_IDENTITY>(THRES_COL, a, grid, s);
+    case TASK_IDENTITY: return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
     case TASK_DISCOUNT: return launch_f64_form<TASK_DISCOUNT>(form, a, grid, s);
     case TASK_BOOST: return launch_f64_form<TASK_BOOST>(form, a, grid, s);
     case TASK_COUNT_GT: return launch_f64_form<TASK_COUNT_GT>(form, a, grid, s);
