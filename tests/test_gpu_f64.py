@@ -166,3 +166,42 @@ def test_f64_argument_errors_and_empty(am):
     am.amulet_mmlike_f64(1, e, torch.zeros(0, 4, dtype=torch.float64, device="cuda"), v, v, R)
     torch.cuda.synchronize()
     assert torch.all(R == 3.0)
+
+
+@pytest.mark.parametrize("name", ["f64_discount_4096", "f64_boost_2048", "f64_identity_4096"])
+def test_f64_named_workloads_full_size_sampled(am, name):
+    """The bench's fp64 workloads at full size, in the launch configuration the bench times;
+    the oracle recomputes a seeded sample of whole rows and whole columns."""
+    import amulet_workloads as wl
+    spec, A, B, P = wl.make(name)
+    task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
+    th = None if P is None else P[0]
+    dis = None if (P is None or P.shape[0] < 2) else P[1]
+    print(name, "gpu run", flush=True)
+    dR = torch.zeros(M, N, dtype=torch.float64, device="cuda")
+    am.amulet_mmlike_f64(task, dev(A), dev(B), None if th is None else dev(th), None if dis is None else dev(dis), dR)
+    torch.cuda.synchronize()
+    R = dR.cpu().numpy()
+    g = np.random.Generator(np.random.PCG64(4244))
+    rows = np.sort(g.choice(M, 12, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 12, replace=False)); cols[0], cols[-1] = 0, N - 1
+    print(name, "oracle rows", flush=True)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, np.ascontiguousarray(A[rows]), B, th, dis)
+    assert worst_ratio(R[rows], R_ref, ab) <= TOL_F64
+    print(name, "oracle cols", flush=True)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, A, np.ascontiguousarray(B[:, cols]),
+                                             None if th is None else th[cols], None if dis is None else dis[cols])
+    assert worst_ratio(R[:, cols], R_ref, ab) <= TOL_F64
+    if task == 0:
+        # whole-matrix property: column sums of R equal (column sums of A) @ B
+        ref = A.sum(0) @ B
+        scale = np.abs(A).sum(0) @ np.abs(B)
+        assert np.max(np.abs(R.sum(0) - ref) / scale) < 1e-12
+
+
+def test_matrix_core_probe_reports_a_plausible_rate(am):
+    macs = am.amulet_probe_mfma_i8(4)
+    # between a tenth of and the whole nominal int8 peak (2.5e15 multiply-adds per second)
+    assert 2.5e14 < macs < 2.6e15
+    with pytest.raises(am.AmuletError):
+        am.amulet_probe_mfma_i8(0)
