@@ -16,8 +16,8 @@
  *    library reads A, B, params and reads+writes R; it never frees, retains
  *    or reallocates them.  R must not overlap A, B or params.
  *  - Matrices are row-major with a leading dimension in ELEMENTS (lda >= K,
- *    ldb >= N, ldr >= N), mirroring the paper's "rows need not be contiguous"
- *    (Sec. 5).  Any M, N, K >= 0 is accepted; edge tiles are handled inside.
+ *    ldb >= N, ldr >= N): as in the paper's interface (Sec. 5) the rows of a
+ *    matrix may be spaced apart in memory.  Any M, N, K >= 0 is accepted; edge tiles are handled inside.
  *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *    Calls only enqueue work and return; they never synchronise or allocate.
  *  - Return value: AMULET_OK (0) or a negative amulet_status_t.  Nothing is
@@ -103,8 +103,8 @@ typedef enum {
  *
  *   R[i][j] += sum_k g( fl32(a(i,k)*b(k,j)), thres(i,j), dis[j] )
  *
- * a(i,k) = A[i*lda+k], or A[k*lda+i] when trans_a != 0 ("A[i][k] is replaced
- * with A[k][i]": A is then K x M, lda >= M); b(k,j) = B[k*ldb+j], or B[j*ldb+k]
+ * a(i,k) = A[i*lda+k], or A[k*lda+i] when trans_a != 0 (the variant of
+ * Sec. 6.3 that indexes A as [k][i]: A is then K x M, lda >= M); b(k,j) = B[k*ldb+j], or B[j*ldb+k]
  * when trans_b != 0 (B is then N x K, ldb >= K).  `thres` is read in the form
  * `thres_form` names (ldt >= N is used by AMULET_THRES_ELEM only); `dis` is
  * dis[0..N) and is read by AMULET_DISCOUNT only; both are ignored (may be

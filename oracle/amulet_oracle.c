@@ -87,8 +87,8 @@ static double oracle_term(int task, float p, float thres, double dis)
  *
  *   R[i][j] += sum_k g( fl32(a(i,k) * b(k,j)), thres(i,j), dis[j] )
  *
- * a(i,k) is A[i*lda+k], or A[k*lda+i] when transA ("A[i][k] is replaced with
- * A[k][i]"); b(k,j) is B[k*ldb+j], or B[j*ldb+k] when transB.  The threshold
+ * a(i,k) is A[i*lda+k], or A[k*lda+i] when transA (the variant that indexes
+ * A as [k][i]); b(k,j) is B[k*ldb+j], or B[j*ldb+k] when transB.  The threshold
  * operand takes the four forms the figure lists: thres[j] (COL), thres[i] (ROW),
  * a constant (CONST, thres[0]) and thres[i][j] (ELEM, row pitch ldt).  dis is
  * indexed by j as printed (only the DISCOUNT task reads it).

@@ -130,8 +130,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const sptr_f As = (sptr_f)args.A;
 
     // Wave-uniform row offsets, clamped so edge waves read valid rows.  a(i,k) lives at
-    // A[i*lda + k], or at A[k*lda + i] when A is stored transposed (paper Sec. 6.3:
-    // "A[i][k] is replaced with A[k][i]"): element offset = arow[r] + k * kstride.
+    // A[i*lda + k], or at A[k*lda + i] when A is stored transposed (the [k][i]-indexed
+    // variant of paper Sec. 6.3): element offset = arow[r] + k * kstride.
     // TRANS = false compiles the transposed paths out: their addressing state would otherwise
     // cost the row-major kernels scalar registers in the hot loop.
     const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
@@ -210,7 +210,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
     const int64_t tile_stride = (int64_t)BK * args.ldb;
     f4 stage[LOADS];
-    // B stored transposed (b(k,j) at B[j*ldb + k], "B[k][j] is replaced with B[j][k]"): a thread
+    // B stored transposed (b(k,j) at B[j*ldb + k], the [j][k]-indexed variant of Sec. 6.3): a thread
     // owns one column of the tile and KPT consecutive k of it, read as float4 along k and
     // scattered into the same [k][n] LDS tile (neighbouring lanes hit neighbouring banks).
     constexpr int TPC = NT / BN;          // threads per column
