@@ -147,6 +147,22 @@ int amulet_mmlike_f64(int task, int thres_form,
                       void *stream);
 
 /*
+ * amulet_mmlike_f64 with the transposed operand layouts of Sec. 6.3 (as in
+ * amulet_mmlike_f32_general: A stored K x M with lda >= M when trans_a != 0,
+ * B stored N x K with ldb >= K when trans_b != 0).  The fp64 matrix-core
+ * kernel of the identity task reads row-major operands only: with a
+ * transposed operand the identity task runs on the vector-ALU kernel.
+ */
+int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b,
+                              int64_t M, int64_t N, int64_t K,
+                              const double *A, int64_t lda,
+                              const double *B, int64_t ldb,
+                              const double *thres, int64_t ldt,
+                              const double *dis,
+                              double *R, int64_t ldr,
+                              void *stream);
+
+/*
  * Natural-join count as a matrix product (the join-as-matmul translation cited
  * in Sec. 1): R[i][j] += sum_k A[i][k]*B[k][j], int8 operands (any values; the
  * workload is 0/1 indicators), int32 result, exact (wraps modulo 2^32 only if

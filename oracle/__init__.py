@@ -60,7 +60,12 @@ def _load():
 def _rowmajor(x: np.ndarray, dtype) -> np.ndarray:
     if x.ndim == 2 and x.size == 0 and x.dtype == dtype:
         return np.zeros((x.shape[0], max(x.shape[1], 1)), dtype)[:, :x.shape[1]]
-    if x.dtype != dtype or x.ndim != 2 or x.strides[1] != x.itemsize or x.strides[0] % x.itemsize:
+    if x.dtype != dtype or x.ndim != 2:
+        raise ValueError("oracle wants a 2-D %s array with unit column stride" % np.dtype(dtype).name)
+    if x.shape[0] == 1 or x.shape[1] == 1:
+        # numpy keeps arbitrary strides along axes of length 1: give such arrays the plain layout
+        return np.array(x, dtype=dtype, order="C", copy=True).reshape(x.shape)
+    if x.strides[1] != x.itemsize or x.strides[0] % x.itemsize:
         raise ValueError("oracle wants a 2-D %s array with unit column stride" % np.dtype(dtype).name)
     return x
 

@@ -55,6 +55,9 @@ def load_library():
     lib.amulet_mmlike_f32_shape.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.amulet_mmlike_f64.restype = i32
     lib.amulet_mmlike_f64.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.amulet_mmlike_f64_general.restype = i32
+    lib.amulet_mmlike_f64_general.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp,
+                                              i64, vp]
     lib.amulet_mmlike_f32_general.restype = i32
     lib.amulet_mmlike_f32_general.argtypes = [i32, i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
                                               vp, vp, i64, vp]
@@ -215,15 +218,19 @@ def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int
            "amulet_mmlike_f32_general")
 
 
-def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL, stream=None):
-    """The tasks in the paper's own element type: fp64 device tensors, row-major; `thres` holds
-    N, M, 1 or M x N values according to `thres_form`; `dis` has N values."""
+def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
+                      trans_a: bool = False, trans_b: bool = False, stream=None):
+    """The tasks in the paper's own element type: fp64 device tensors; A may be stored K x M
+    (trans_a), B N x K (trans_b); `thres` holds N, M, 1 or M x N values according to
+    `thres_form`; `dis` has N values."""
     lib = load_library()
     f64 = "torch.float64"
-    pa, M, K, lda = _mat(A, f64, "A")
-    pb, K2, N, ldb = _mat(B, f64, "B")
-    pr, M2, N2, ldr = _mat(R, f64, "R")
-    if K2 != K or M2 != M or N2 != N:
+    pa, ra, ca, lda = _mat(A, f64, "A")
+    pb, rb, cb, ldb = _mat(B, f64, "B")
+    pr, M, N, ldr = _mat(R, f64, "R")
+    Ma, K = (ca, ra) if trans_a else (ra, ca)
+    K2, Nb = (cb, rb) if trans_b else (rb, cb)
+    if K2 != K or Ma != M or Nb != N:
         raise ValueError("shape mismatch between A, B and R")
     pt, ldt = None, 0
     if task != AMULET_IDENTITY:
@@ -244,8 +251,8 @@ def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULE
                 or dis.numel() != N:
             raise ValueError("dis must hold N contiguous fp64 values on the device")
         pd = dis.data_ptr()
-    _check(lib.amulet_mmlike_f64(task, thres_form, M, N, K, pa, lda, pb, ldb, pt, ldt, pd, pr, ldr,
-                                 _stream_ptr(stream)), "amulet_mmlike_f64")
+    _check(lib.amulet_mmlike_f64_general(task, thres_form, int(trans_a), int(trans_b), M, N, K, pa, lda, pb, ldb,
+                                         pt, ldt, pd, pr, ldr, _stream_ptr(stream)), "amulet_mmlike_f64_general")
 
 
 def amulet_count_i8(A, B, R, stream=None):

@@ -321,27 +321,42 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
     return run_mmlike(c, shape, stream);
 }
 
-int amulet_mmlike_f64(int task, int thres_form, int64_t M, int64_t N, int64_t K, const double *A,
-                      int64_t lda, const double *B, int64_t ldb, const double *thres, int64_t ldt,
-                      const double *dis, double *R, int64_t ldr, void *stream)
+int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
+                              int64_t K, const double *A, int64_t lda, const double *B, int64_t ldb,
+                              const double *thres, int64_t ldt, const double *dis, double *R, int64_t ldr,
+                              void *stream)
 {
     if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
     if (thres_form < THRES_COL || thres_form > THRES_ELEM) return AMULET_ERR_TASK;
-    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
-    if (rc < 0) return rc;
-    if (rc == 1) return AMULET_OK;
+    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
+    if (M == 0 || N == 0 || K == 0) return AMULET_OK;
+    if (!A || !B || !R) return AMULET_ERR_NULL;
     if (task != TASK_IDENTITY && !thres) return AMULET_ERR_NULL;
     if (task == TASK_DISCOUNT && !dis) return AMULET_ERR_NULL;
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldr < N) return AMULET_ERR_LD;
     if (task != TASK_IDENTITY && thres_form == THRES_ELEM && ldt < N) return AMULET_ERR_LD;
     MmlikeArgsF64 a;
     a.A = A; a.B = B; a.thres = thres; a.dis = dis; a.R = R;
     a.lda = lda; a.ldb = ldb; a.ldr = ldr; a.ldt = ldt;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
-    a.vec = (aligned16(B) && aligned16(R) && ldb % 2 == 0 && ldr % 2 == 0) ? 1 : 0;
+    a.transA = trans_a ? 1 : 0; a.transB = trans_b ? 1 : 0;
+    const bool b16 = aligned16(B) && ldb % 2 == 0;
+    // vec: 16-byte accesses to R, and to the rows of a row-major B
+    a.vec = (aligned16(R) && ldr % 2 == 0 && (a.transB || b16)) ? 1 : 0;
+    a.vecBt = b16 ? 1 : 0;
     a.vecA = (aligned16(A) && lda % 2 == 0) ? 1 : 0;
     const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+int amulet_mmlike_f64(int task, int thres_form, int64_t M, int64_t N, int64_t K, const double *A,
+                      int64_t lda, const double *B, int64_t ldb, const double *thres, int64_t ldt,
+                      const double *dis, double *R, int64_t ldr, void *stream)
+{
+    return amulet_mmlike_f64_general(task, thres_form, 0, 0, M, N, K, A, lda, B, ldb, thres, ldt, dis, R, ldr,
+                                     stream);
 }
 
 int amulet_mmlike_f32_shape(int task, int shape, int64_t M, int64_t N, int64_t K, const float *A,

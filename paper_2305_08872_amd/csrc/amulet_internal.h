@@ -121,6 +121,8 @@ struct MmlikeArgsF64 {
     int M, N, K;
     int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
     int vecA;  // 1 when A and its row pitch do
+    int transA, transB;  // operand stored transposed: a(i,k) = A[k*lda+i], b(k,j) = B[j*ldb+k]
+    int vecBt; // transposed B: 1 when B and its row pitch allow 16-byte loads along k
 };
 // predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);

@@ -16,6 +16,9 @@ typedef double d2 __attribute__((ext_vector_type(2)));
 typedef d2 d2_a8 __attribute__((aligned(8)));
 typedef const __attribute__((address_space(4))) double *sptr_d;     // read through the scalar cache
 typedef const __attribute__((address_space(4))) d2_a8 *sptr_d2;
+typedef double d4r __attribute__((ext_vector_type(4)));
+typedef d4r d4_a8 __attribute__((aligned(8)));
+typedef const __attribute__((address_space(4))) d4_a8 *sptr_d4;
 
 constexpr int D_TM = 4, D_NW = 4, D_BK = 16, D_BN = 128, D_NT = 64 * D_NW;
 
@@ -81,7 +84,10 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
     }
 }
 
-template <int TASK, int TF>
+// TRANS = true compiles in the transposed operand layouts (a(i,k) at A[k*lda + i], b(k,j) at
+// B[j*ldb + k], selected at run time by args.transA / args.transB); TRANS = false keeps their
+// addressing state out of the row-major kernels.
+template <int TASK, int TF, bool TRANS>
 __global__ void __launch_bounds__(D_NT)
 mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 {
@@ -95,6 +101,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 
     const int M = args.M, N = args.N, K = args.K;
     const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned
+    const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
@@ -108,9 +115,11 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 
     const sptr_d As = (sptr_d)args.A;
     auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
+    // a(i,k) lives at arow[r] + k * kstride (elements)
     int64_t arow[D_TM];
 #pragma unroll
-    for (int r = 0; r < D_TM; ++r) arow[r] = (int64_t)rowc(r) * args.lda;
+    for (int r = 0; r < D_TM; ++r) arow[r] = transA ? (int64_t)rowc(r) : (int64_t)rowc(r) * args.lda;
+    const bool rows_full = row0 + D_TM <= M;   // the wave's 4 rows exist: contiguous in a transposed A
 
     // parameters in registers for the whole K loop (threshold in the operand form TF)
     double q[2];
@@ -167,8 +176,34 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
     const int64_t tile_stride = (int64_t)D_BK * args.ldb;
     d2 stage[LOADS];
+    // B stored transposed: a thread owns one column of the tile and 8 consecutive k of it,
+    // read as four 16-byte pieces along k and scattered into the same [k][n] LDS tile
+    // (neighbouring lanes hit neighbouring banks).
+    static_assert(D_NT == 2 * D_BN && D_BK == 16 && LOADS == 4, "transposed-B slot mapping");
+    const int tcol = threadIdx.x % D_BN;
+    const int tk = (threadIdx.x / D_BN) * 8;
+    const double *btsrc = args.B + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
+    const bool vecBt = TRANS && args.vecBt != 0;
     auto load_tile = [&](int krows) {
-        if (fast_cols && krows == D_BK) {
+        if (transB) {
+            const bool colok = col0 + tcol < N;
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it) {
+                d2 v = {0.0, 0.0};
+                const int kk = tk + 2 * it;
+                if (colok) {
+                    const double *src = btsrc + 2 * it;
+                    if (vecBt && kk + 1 < krows) {
+                        v = *(const d2 *)src;
+                    } else {
+                        if (kk + 0 < krows) v.x = src[0];
+                        if (kk + 1 < krows) v.y = src[1];
+                    }
+                }
+                stage[it] = v;
+            }
+            btsrc += D_BK;
+        } else if (fast_cols && krows == D_BK) {
 #pragma unroll
             for (int it = 0; it < LOADS; ++it) stage[it] = *(const d2 *)(bsrc + it * pass_stride);
         } else {
@@ -186,23 +221,48 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
         bsrc += tile_stride;
     };
     double *const bdst = &Bs[0][srow][(threadIdx.x % D2_PER_ROW) * 2];
+    double *const btdst = &Bs[0][tk][tcol];
     auto store_tile = [&](int buf) {
+        if (transB) {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it)
-            *(d2 *)(bdst + (buf * D_BK + it * ROWS_PER_PASS) * D_BN) = stage[it];
+            for (int it = 0; it < LOADS; ++it)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) btdst[(buf * D_BK + 2 * it + e) * D_BN] = stage[it][e];
+        } else {
+#pragma unroll
+            for (int it = 0; it < LOADS; ++it)
+                *(d2 *)(bdst + (buf * D_BK + it * ROWS_PER_PASS) * D_BN) = stage[it];
+        }
     };
 
     const int full_tiles = K / D_BK;
     const int tail = K - full_tiles * D_BK;
     const int n_tiles = full_tiles + (tail ? 1 : 0);
 
+    // A values of the chunk of KA k starting at kn, for the wave's D_TM rows, into SGPR pairs
     d2_a8 a_next[D_TM];
+    auto fetch_a = [&](int kn) {
+        if (!transA) {
+#pragma unroll
+            for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r] + kn);
+        } else if (rows_full) {
+            // the 4 rows of one k are contiguous in the transposed storage
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk) {
+                const d4_a8 t = *(sptr_d4)(As + (int64_t)(kn + kk) * args.lda + arow[0]);
+#pragma unroll
+                for (int r = 0; r < D_TM; ++r) a_next[r][kk] = t[r];
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                for (int r = 0; r < D_TM; ++r) a_next[r][kk] = As[(int64_t)(kn + kk) * args.lda + arow[r]];
+        }
+    };
     load_tile(full_tiles > 0 ? D_BK : tail);
     store_tile(0);
-    if (full_tiles > 0) {
-#pragma unroll
-        for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r]);
-    }
+    if (full_tiles > 0) fetch_a(0);
     __syncthreads();
 
     const double *bs_lane = &Bs[0][0][lane * 2];
@@ -228,8 +288,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 {
                     int kn = k0 + kc + KA;
                     kn = kn + KA <= K ? kn : k0 + kc;
-#pragma unroll
-                    for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r] + kn);
+                    fetch_a(kn);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -246,7 +305,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 const d2 b = *(const d2 *)(bs + kk * D_BN);
                 double ak[D_TM];
 #pragma unroll
-                for (int r = 0; r < D_TM; ++r) ak[r] = As[arow[r] + k0 + kk];
+                for (int r = 0; r < D_TM; ++r)
+                    ak[r] = transA ? As[(int64_t)(k0 + kk) * args.lda + arow[r]] : As[arow[r] + k0 + kk];
                 fold_rows<TASK>(ak, b, th, q, acc);
             }
         }
@@ -273,14 +333,14 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     }
 }
 
-template <int TASK>
+template <int TASK, bool TRANS>
 static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
 {
     switch (form) {
-    case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL>), grid, dim3(D_NT), 0, s, a); break;
-    case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW>), grid, dim3(D_NT), 0, s, a); break;
-    case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST>), grid, dim3(D_NT), 0, s, a); break;
-    default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM>), grid, dim3(D_NT), 0, s, a); break;
+    case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+    case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+    case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+    default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS>), grid, dim3(D_NT), 0, s, a); break;
     }
     return hipGetLastError();
 }
@@ -292,11 +352,19 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs);
+    const bool trans = a.transA || a.transB;
     switch (task) {
-    case TASK_IDENTITY: return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
-    case TASK_DISCOUNT: return launch_f64_form<TASK_DISCOUNT>(form, a, grid, s);
-    case TASK_BOOST: return launch_f64_form<TASK_BOOST>(form, a, grid, s);
-    case TASK_COUNT_GT: return launch_f64_form<TASK_COUNT_GT>(form, a, grid, s);
+    case TASK_IDENTITY:
+        // a dense contraction: matrix cores; their kernel reads row-major operands only
+        if (!trans) return launch_identity_mfma_f64(a, s);
+        hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK_IDENTITY, THRES_COL, true>), grid, dim3(D_NT), 0, s, a);
+        return hipGetLastError();
+    case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, a, grid, s)
+                                     : launch_f64_form<TASK_DISCOUNT, false>(form, a, grid, s);
+    case TASK_BOOST: return trans ? launch_f64_form<TASK_BOOST, true>(form, a, grid, s)
+                                  : launch_f64_form<TASK_BOOST, false>(form, a, grid, s);
+    case TASK_COUNT_GT: return trans ? launch_f64_form<TASK_COUNT_GT, true>(form, a, grid, s)
+                                     : launch_f64_form<TASK_COUNT_GT, false>(form, a, grid, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -205,3 +205,32 @@ def test_matrix_core_probe_reports_a_plausible_rate(am):
     assert 2.5e14 < macs < 2.6e15
     with pytest.raises(am.AmuletError):
         am.amulet_probe_mfma_i8(0)
+
+
+@pytest.mark.parametrize("task", TASKS)
+@pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True)])
+def test_f64_transposed_operands(am, task, tA, tB):
+    """A stored K x M and / or B stored N x K (the transposed variants of the test queries), over
+    ragged sizes, all threshold forms, aligned and 8-byte-offset views."""
+    for idx, (M, N, K) in enumerate([(70, 300, 37), (33, 513, 100), (129, 130, 77), (3, 5, 2), (64, 256, 64),
+                                     (5, 129, 1)]):
+        form = (idx + task) % 4 if task else 0
+        A, B, th, dis, R_in = make_case(form, M, N, K, 8000 + 50 * task + idx)
+        As = np.ascontiguousarray(A.T) if tA else A
+        Bs = np.ascontiguousarray(B.T) if tB else B
+        print("case f64 trans", task, tA, tB, form, M, N, K, flush=True)
+        R_ref, ab, _ = oracle.mmlike_f64_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=tA,
+                                                 trans_b=tB)
+        # the oracle's transposed form against its own row-major form (same arithmetic, other indexing)
+        R_rm, _, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in, thres_form=form)
+        assert np.array_equal(R_ref, R_rm)
+        off = idx % 2
+        bufA = torch.zeros(As.shape[0], As.shape[1] + off, dtype=torch.float64, device="cuda")
+        bufB = torch.zeros(Bs.shape[0], Bs.shape[1] + off, dtype=torch.float64, device="cuda")
+        dA, dB = bufA[:, off:], bufB[:, off:]
+        dA.copy_(dev(As)); dB.copy_(dev(Bs))
+        dR = dev(R_in)
+        am.amulet_mmlike_f64(task, dA, dB, dev(th) if task else None, dev(dis) if task == 1 else None, dR,
+                             thres_form=form, trans_a=tA, trans_b=tB)
+        torch.cuda.synchronize()
+        check(dR.cpu().numpy(), R_ref, ab, R_in, task, "trans %r %r task %d %dx%dx%d" % (tA, tB, task, M, N, K))
