@@ -109,10 +109,8 @@ typedef enum {
  * `thres_form` names (ldt >= N is used by AMULET_THRES_ELEM only); `dis` is
  * dis[0..N) and is read by AMULET_DISCOUNT only; both are ignored (may be
  * NULL) for AMULET_IDENTITY.  `shape` is a tile-shape id of the task, or -1
- * for the selected/default one (the matrix-core identity kernel takes
- * row-major operands only: with a transposed operand the identity task runs
- * on the vector-ALU kernels, and asking for that shape explicitly is
- * AMULET_ERR_SHAPE).  Other conventions as for amulet_mmlike_f32, which is
+ * for the selected/default one (every shape of a task, the matrix-core
+ * identity kernel included, takes all four layouts).  Other conventions as for amulet_mmlike_f32, which is
  * this call with thres[j], no transposition, shape -1 and planar params.
  */
 int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b, int shape,

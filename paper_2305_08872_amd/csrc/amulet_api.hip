@@ -308,15 +308,10 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
                           thres, ldt, dis, R, ldr};
     const int rc = check_mmlike(c);
     if (rc < 0) return rc;
-    const bool transposed = c.trans_a || c.trans_b;
-    if (shape < 0) {
+    if (shape < 0)
         shape = lookup_shape(task, M, N, K);
-        // the matrix-core identity kernel reads row-major operands only
-        if (transposed && task == TASK_IDENTITY && shape == IDENTITY_MFMA_SHAPE) shape = VALU_TILES + 0;
-    } else if (shape >= n_shapes(task) ||
-               (transposed && task == TASK_IDENTITY && shape == IDENTITY_MFMA_SHAPE)) {
+    else if (shape >= n_shapes(task))
         return AMULET_ERR_SHAPE;
-    }
     if (rc == 1) return AMULET_OK;
     return run_mmlike(c, shape, stream);
 }

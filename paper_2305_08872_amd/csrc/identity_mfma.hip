@@ -15,6 +15,12 @@
 // of 8 k, slot h of MFMA t carries k = 4h + t.  A lane then reads its four A
 // values of a group as one ds_read_b128.
 //
+// Transposed operands (template parameters TA, TB; paper Sec. 6.3): an operand is staged either
+// "k-minor" (a tile of 128 rows or columns x 16 k, k contiguous: row-major A, transposed B) or
+// "k-major" (16 k x 128, as row-major B and transposed A are stored).  Both keep their global
+// layout in LDS; a k-minor operand's fragment values come from one ds_read_b128 per 4 k, a
+// k-major operand's from one ds_read_b32 per MFMA step, read one step ahead.
+//
 // Rows/columns beyond M/N and the K remainder are zero-filled in LDS: for the
 // identity task a zero product adds nothing (this is NOT true of the predicate
 // tasks, which never take this path).
@@ -34,11 +40,17 @@ constexpr int MI_APITCH = MI_BK + 4;   // floats
 
 // 4 waves per SIMD (at most 128 registers): four 128 x 128 workgroups per compute unit, which is
 // what lets a 4096 x 4096 result (1024 tiles on 256 compute units) run as one full round.
+constexpr int MI_KMINOR_FLOATS = MI_BM * MI_APITCH;   // one k-minor tile: 128 x 20
+constexpr int MI_KMAJOR_FLOATS = MI_BK * MI_BN;       // one k-major tile: 16 x 128
+
+template <bool TA, bool TB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_kernel(const MmlikeArgs args)
 {
-    __shared__ __attribute__((aligned(16))) float As[2][MI_BM][MI_APITCH];
-    __shared__ __attribute__((aligned(16))) float Bs[2][MI_BK][MI_BN];
+    constexpr int A_TILE = TA ? MI_KMAJOR_FLOATS : MI_KMINOR_FLOATS;
+    constexpr int B_TILE = TB ? MI_KMINOR_FLOATS : MI_KMAJOR_FLOATS;
+    __shared__ __attribute__((aligned(16))) float As[2 * A_TILE];
+    __shared__ __attribute__((aligned(16))) float Bs[2 * B_TILE];
 
     const int M = args.M, N = args.N, K = args.K;
     const int tid = threadIdx.x;
@@ -58,7 +70,7 @@ identity_mfma_kernel(const MmlikeArgs args)
     // Interior tiles with 16-byte aligned rows are staged as (wave-uniform base that advances
     // with k) + (fixed 32-bit per-thread offset): the address arithmetic stays on the scalar
     // unit, which matters because vector-ALU instructions share the issue port with the MFMAs.
-    const bool interior = vecA && vecB && row0 + MI_BM <= M && col0 + MI_BN <= N &&
+    const bool interior = !TA && !TB && vecA && vecB && row0 + MI_BM <= M && col0 + MI_BN <= N &&
                           (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
     const float *const a_base = args.A + (int64_t)row0 * args.lda;
     const float *const b_base = args.B + col0;
@@ -87,48 +99,60 @@ identity_mfma_kernel(const MmlikeArgs args)
             }
             return;
         }
+        // k-minor operand: thread -> (line = tid / 4 + 64*it, k quad = tid % 4) of 128 lines x 16 k
+        auto load_kminor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[2]) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int r = row0 + (tid >> 2) + 64 * it;
-            const int k = k0 + (tid & 3) * 4;
-            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (r < M) {
-                const float *src = args.A + (int64_t)r * args.lda + k;
-                if (vecA && k + 3 < K) {
-                    v = *(const f4 *)src;
-                } else {
-                    if (k + 0 < K) v.x = src[0];
-                    if (k + 1 < K) v.y = src[1];
-                    if (k + 2 < K) v.z = src[2];
-                    if (k + 3 < K) v.w = src[3];
+            for (int it = 0; it < 2; ++it) {
+                const int r = line0 + (tid >> 2) + 64 * it;
+                const int k = k0 + (tid & 3) * 4;
+                f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (r < n_lines) {
+                    const float *src = base + (int64_t)r * ld + k;
+                    if (vec && k + 3 < K) {
+                        v = *(const f4 *)src;
+                    } else {
+                        if (k + 0 < K) v.x = src[0];
+                        if (k + 1 < K) v.y = src[1];
+                        if (k + 2 < K) v.z = src[2];
+                        if (k + 3 < K) v.w = src[3];
+                    }
                 }
+                dst[it] = v;
             }
-            sa[it] = v;
-        }
+        };
+        // k-major operand: thread -> (k = tid / 32 + 8*it, line quad = tid % 32) of 16 k x 128 lines
+        auto load_kmajor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[2]) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int k = k0 + (tid >> 5) + 8 * it;
-            const int c = col0 + (tid & 31) * 4;
-            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (k < K) {
-                const float *src = args.B + (int64_t)k * args.ldb + c;
-                if (vecB && c + 3 < N) {
-                    v = *(const f4 *)src;
-                } else {
-                    if (c + 0 < N) v.x = src[0];
-                    if (c + 1 < N) v.y = src[1];
-                    if (c + 2 < N) v.z = src[2];
-                    if (c + 3 < N) v.w = src[3];
+            for (int it = 0; it < 2; ++it) {
+                const int k = k0 + (tid >> 5) + 8 * it;
+                const int c = line0 + (tid & 31) * 4;
+                f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (k < K) {
+                    const float *src = base + (int64_t)k * ld + c;
+                    if (vec && c + 3 < n_lines) {
+                        v = *(const f4 *)src;
+                    } else {
+                        if (c + 0 < n_lines) v.x = src[0];
+                        if (c + 1 < n_lines) v.y = src[1];
+                        if (c + 2 < n_lines) v.z = src[2];
+                        if (c + 3 < n_lines) v.w = src[3];
+                    }
                 }
+                dst[it] = v;
             }
-            sb[it] = v;
-        }
+        };
+        if constexpr (TA) load_kmajor(args.A, args.lda, row0, M, vecA, sa);
+        else load_kminor(args.A, args.lda, row0, M, vecA, sa);
+        if constexpr (TB) load_kminor(args.B, args.ldb, col0, N, vecB, sb);
+        else load_kmajor(args.B, args.ldb, col0, N, vecB, sb);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            *(f4 *)&As[buf][(tid >> 2) + 64 * it][(tid & 3) * 4] = sa[it];
-            *(f4 *)&Bs[buf][(tid >> 5) + 8 * it][(tid & 31) * 4] = sb[it];
+            const int kminor = ((tid >> 2) + 64 * it) * MI_APITCH + (tid & 3) * 4;
+            const int kmajor = ((tid >> 5) + 8 * it) * MI_BN + (tid & 31) * 4;
+            *(f4 *)&As[buf * A_TILE + (TA ? kmajor : kminor)] = sa[it];
+            *(f4 *)&Bs[buf * B_TILE + (TB ? kminor : kmajor)] = sb[it];
         }
     };
 
@@ -148,33 +172,59 @@ identity_mfma_kernel(const MmlikeArgs args)
     for (int s = 0; s < n_stages; ++s) {
         const int buf = s & 1;
         if (s + 1 < n_stages) load_stage((s + 1) * MI_BK);
-        // A fragments of the whole stage (4 x ds_read_b128), then the 8 k-steps of the stage,
-        // software-pipelined: the B values of step t+1 are read from LDS before the four MFMAs
-        // of step t are issued, so the matrix pipe never waits on an LDS round trip.
-        f4 a[2][2];
+        // The 8 k-steps of the stage.  A k-minor operand's values of the whole stage are read
+        // first (4 x ds_read_b128); a k-major operand's values of step t+1 are read from LDS
+        // before the four MFMAs of step t are issued, so the matrix pipe never waits on an LDS
+        // round trip.
+        const float *at = As + buf * A_TILE, *bt = Bs + buf * B_TILE;
+        f4 a4[2][2], b4[2][2];
+        float aq[2][2], bq[2][2];
+        const int arow = wr * 64 + li, bcol = wc * 64 + li;   // + 32 for the second block
+        if constexpr (!TA) {
 #pragma unroll
-        for (int g = 0; g < 2; ++g)
+            for (int g = 0; g < 2; ++g)
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                a[g][mi] = *(const f4 *)&As[buf][wr * 64 + mi * 32 + li][8 * g + 4 * lh];
-        float bq[2][2];
+                for (int mi = 0; mi < 2; ++mi)
+                    a4[g][mi] = *(const f4 *)&at[(arow + mi * 32) * MI_APITCH + 8 * g + 4 * lh];
+        } else {
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) bq[0][ni] = Bs[buf][4 * lh][wc * 64 + ni * 32 + li];
+            for (int mi = 0; mi < 2; ++mi) aq[0][mi] = at[(4 * lh) * MI_BN + arow + mi * 32];
+        }
+        if constexpr (TB) {
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    b4[g][ni] = *(const f4 *)&bt[(bcol + ni * 32) * MI_APITCH + 8 * g + 4 * lh];
+        } else {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) bq[0][ni] = bt[(4 * lh) * MI_BN + bcol + ni * 32];
+        }
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
             const int g = step >> 2, t = step & 3, cur = step & 1;
             if (step + 1 < 8) {
                 const int g1 = (step + 1) >> 2, t1 = (step + 1) & 3;
+                if constexpr (TA) {
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    bq[cur ^ 1][ni] = Bs[buf][8 * g1 + 4 * lh + t1][wc * 64 + ni * 32 + li];
+                    for (int mi = 0; mi < 2; ++mi)
+                        aq[cur ^ 1][mi] = at[(8 * g1 + 4 * lh + t1) * MI_BN + arow + mi * 32];
+                }
+                if constexpr (!TB) {
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        bq[cur ^ 1][ni] = bt[(8 * g1 + 4 * lh + t1) * MI_BN + bcol + ni * 32];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][mi][t], bq[cur][ni], acc[mi][ni], 0, 0, 0);
+                for (int ni = 0; ni < 2; ++ni) {
+                    const float av = TA ? aq[cur][mi] : a4[g][mi][t];
+                    const float bv = TB ? b4[g][ni][t] : bq[cur][ni];
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[mi][ni], 0, 0, 0);
+                }
             __builtin_amdgcn_sched_barrier(0);
         }
         if (s + 1 < n_stages) store_stage(buf ^ 1);
@@ -199,13 +249,22 @@ identity_mfma_kernel(const MmlikeArgs args)
         }
 }
 
+template <bool TA, bool TB>
+static void launch_identity_layout(const MmlikeArgs &a, unsigned grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((identity_mfma_kernel<TA, TB>), dim3(grid), dim3(256), 0, s, a);
+}
+
 hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + MI_BM - 1) / MI_BM;
     const int64_t tiles_n = (a.N + MI_BN - 1) / MI_BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(identity_mfma_kernel, dim3((unsigned)grid), dim3(256), 0, s, a);
+    if (a.transA && a.transB) launch_identity_layout<true, true>(a, (unsigned)grid, s);
+    else if (a.transA) launch_identity_layout<true, false>(a, (unsigned)grid, s);
+    else if (a.transB) launch_identity_layout<false, true>(a, (unsigned)grid, s);
+    else launch_identity_layout<false, false>(a, (unsigned)grid, s);
     return hipGetLastError();
 }
 

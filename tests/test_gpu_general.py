@@ -113,13 +113,24 @@ def test_transposed_strided_unaligned(am):
     assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="transposed strided")
 
 
-def test_identity_transposed_never_uses_the_mfma_shape(am):
-    A = torch.ones(8, 4, device="cuda"); B = torch.ones(8, 6, device="cuda"); R = torch.zeros(4, 6, device="cuda")
-    with pytest.raises(am.AmuletError):
-        am.amulet_mmlike_f32_general(0, A, B, None, None, R, trans_a=True, shape=8)
-    am.amulet_mmlike_f32_general(0, A, B, None, None, R, trans_a=True)   # auto shape: VALU path
-    torch.cuda.synchronize()
-    assert torch.all(R == 8)
+@pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True)])
+def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
+    """The matrix-core identity kernel (shape 8, the default) with transposed operands: ragged
+    and multi-tile sizes, odd pitches (scalar path) and aligned ones (16-byte path)."""
+    for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (3, 5, 2), (256, 256, 64), (200, 136, 100),
+                                     (130, 129, 17)]):
+        As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, M, N, K, 5200 + idx)
+        R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
+        for pad in (0, 3):
+            bufA = torch.zeros(As.shape[0], As.shape[1] + pad, device="cuda"); bufA[:, :As.shape[1]] = dev(As)
+            bufB = torch.zeros(Bs.shape[0], Bs.shape[1] + pad, device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
+            for shape in (8, -1):
+                print("identity trans", tA, tB, M, N, K, pad, shape, flush=True)
+                dR = dev(R_in)
+                am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,
+                                             trans_a=tA, trans_b=tB, shape=shape)
+                torch.cuda.synchronize()
+                assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity trans %r %r" % (tA, tB))
 
 
 def test_adaptive_execution_trials_contribute_to_the_result(am):
