@@ -147,9 +147,7 @@ int amulet_mmlike_f64(int task, int thres_form,
 /*
  * amulet_mmlike_f64 with the transposed operand layouts of Sec. 6.3 (as in
  * amulet_mmlike_f32_general: A stored K x M with lda >= M when trans_a != 0,
- * B stored N x K with ldb >= K when trans_b != 0).  The fp64 matrix-core
- * kernel of the identity task reads row-major operands only: with a
- * transposed operand the identity task runs on the vector-ALU kernel.
+ * B stored N x K with ldb >= K when trans_b != 0).
  */
 int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b,
                               int64_t M, int64_t N, int64_t K,

@@ -14,6 +14,11 @@
 // k a slot carries is free as long as both operands agree: slot h of MFMA t carries
 // k = 4 h + t, and a lane reads its four A values of a stage as two 16-byte LDS reads.
 //
+// Transposed operands (template parameters TA, TB; paper Sec. 6.3), as in the fp32 kernel: an
+// operand keeps its global layout in LDS, k-minor (128 x 16, k contiguous: row-major A,
+// transposed B; a lane's four values of a stage are two 16-byte reads) or k-major (16 x 128:
+// row-major B, transposed A; one 8-byte read per MFMA step).
+//
 // Rows/columns beyond M/N and the K remainder are zero-filled in LDS: for the identity task
 // a zero product adds nothing (NOT true of the predicate tasks, which never take this path).
 #include <hip/hip_runtime.h>
@@ -29,15 +34,24 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 constexpr int DI_BM = 128, DI_BN = 128, DI_BK = 16, DI_NT = 512;
 constexpr int DI_APITCH = DI_BK + 2;    // doubles
 constexpr int DI_BPITCH = DI_BN + 4;    // doubles
-constexpr int DI_A_DOUBLES = DI_BM * DI_APITCH, DI_B_DOUBLES = DI_BK * DI_BPITCH;
-constexpr int DI_LDS_BYTES = 2 * (DI_A_DOUBLES + DI_B_DOUBLES) * 8;   // 70 656: two workgroups per compute unit
+constexpr int DI_KMINOR_DOUBLES = DI_BM * DI_APITCH;   // one k-minor tile: 128 x 18
+constexpr int DI_KMAJOR_DOUBLES = DI_BK * DI_BPITCH;   // one k-major tile: 16 x 132
 
+template <bool TA, bool TB>
+struct DiLayout {
+    static constexpr int A_TILE = TA ? DI_KMAJOR_DOUBLES : DI_KMINOR_DOUBLES;
+    static constexpr int B_TILE = TB ? DI_KMINOR_DOUBLES : DI_KMAJOR_DOUBLES;
+    static constexpr int LDS_BYTES = 2 * (A_TILE + B_TILE) * 8;   // 66-72 KB: two workgroups per compute unit
+};
+
+template <bool TA, bool TB>
 __global__ void __launch_bounds__(DI_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_f64_kernel(const MmlikeArgsF64 args)
 {
+    constexpr int A_TILE = DiLayout<TA, TB>::A_TILE, B_TILE = DiLayout<TA, TB>::B_TILE;
     extern __shared__ __attribute__((aligned(16))) double di_smem[];
-    double *const As = di_smem;                        // [2][DI_BM][DI_APITCH]
-    double *const Bs = di_smem + 2 * DI_A_DOUBLES;     // [2][DI_BK][DI_BPITCH]
+    double *const As = di_smem;                  // [2][A_TILE]
+    double *const Bs = di_smem + 2 * A_TILE;     // [2][B_TILE]
 
     const int M = args.M, N = args.N, K = args.K;
     const int tid = threadIdx.x;
@@ -52,54 +66,65 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     int tm, tn;
     if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * DI_BM, col0 = tn * DI_BN;
-    const bool vecA = args.vecA != 0, vecB = args.vec != 0;
+    // 16-byte loads allowed along the operand's contiguous axis
+    const bool vecA = args.vecA != 0, vecB = TB ? args.vecBt != 0 : args.vec != 0;
 
     // staging slots of 16 bytes, u = tid + 512 * it:
-    //   A tile 128 rows x 8 slots: row = u / 8, k pair = u % 8
-    //   B tile  16 rows x 64 slots: k = u / 64, column pair = u % 64
+    //   k-minor tile, 128 lines x 8 slots: line = u / 8, k pair = u % 8
+    //   k-major tile,  16 k x 64 slots:    k = u / 64, line pair = u % 64
     d2 sa[2], sb[2];
     auto load_stage = [&](int k0) {
+        auto load_kminor = [&](const double *base, int64_t ld, int line0, int n_lines, bool vec, d2 (&dst)[2]) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int u = tid + DI_NT * it;
-            const int r = row0 + (u >> 3);
-            const int k = k0 + (u & 7) * 2;
-            d2 v = {0.0, 0.0};
-            if (r < M) {
-                const double *src = args.A + (int64_t)r * args.lda + k;
-                if (vecA && k + 1 < K) {
-                    v = *(const d2 *)src;
-                } else {
-                    if (k + 0 < K) v.x = src[0];
-                    if (k + 1 < K) v.y = src[1];
+            for (int it = 0; it < 2; ++it) {
+                const int u = tid + DI_NT * it;
+                const int r = line0 + (u >> 3);
+                const int k = k0 + (u & 7) * 2;
+                d2 v = {0.0, 0.0};
+                if (r < n_lines) {
+                    const double *src = base + (int64_t)r * ld + k;
+                    if (vec && k + 1 < K) {
+                        v = *(const d2 *)src;
+                    } else {
+                        if (k + 0 < K) v.x = src[0];
+                        if (k + 1 < K) v.y = src[1];
+                    }
                 }
+                dst[it] = v;
             }
-            sa[it] = v;
-        }
+        };
+        auto load_kmajor = [&](const double *base, int64_t ld, int line0, int n_lines, bool vec, d2 (&dst)[2]) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int u = tid + DI_NT * it;
-            const int k = k0 + (u >> 6);
-            const int c = col0 + (u & 63) * 2;
-            d2 v = {0.0, 0.0};
-            if (k < K) {
-                const double *src = args.B + (int64_t)k * args.ldb + c;
-                if (vecB && c + 1 < N) {
-                    v = *(const d2 *)src;
-                } else {
-                    if (c + 0 < N) v.x = src[0];
-                    if (c + 1 < N) v.y = src[1];
+            for (int it = 0; it < 2; ++it) {
+                const int u = tid + DI_NT * it;
+                const int k = k0 + (u >> 6);
+                const int c = line0 + (u & 63) * 2;
+                d2 v = {0.0, 0.0};
+                if (k < K) {
+                    const double *src = base + (int64_t)k * ld + c;
+                    if (vec && c + 1 < n_lines) {
+                        v = *(const d2 *)src;
+                    } else {
+                        if (c + 0 < n_lines) v.x = src[0];
+                        if (c + 1 < n_lines) v.y = src[1];
+                    }
                 }
+                dst[it] = v;
             }
-            sb[it] = v;
-        }
+        };
+        if constexpr (TA) load_kmajor(args.A, args.lda, row0, M, vecA, sa);
+        else load_kminor(args.A, args.lda, row0, M, vecA, sa);
+        if constexpr (TB) load_kminor(args.B, args.ldb, col0, N, vecB, sb);
+        else load_kmajor(args.B, args.ldb, col0, N, vecB, sb);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int u = tid + DI_NT * it;
-            *(d2 *)(As + buf * DI_A_DOUBLES + (u >> 3) * DI_APITCH + (u & 7) * 2) = sa[it];
-            *(d2 *)(Bs + buf * DI_B_DOUBLES + (u >> 6) * DI_BPITCH + (u & 63) * 2) = sb[it];
+            const int kminor = (u >> 3) * DI_APITCH + (u & 7) * 2;
+            const int kmajor = (u >> 6) * DI_BPITCH + (u & 63) * 2;
+            *(d2 *)(As + buf * A_TILE + (TA ? kmajor : kminor)) = sa[it];
+            *(d2 *)(Bs + buf * B_TILE + (TB ? kminor : kmajor)) = sb[it];
         }
     };
 
@@ -119,26 +144,40 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     for (int s = 0; s < n_stages; ++s) {
         const int buf = s & 1;
         if (s + 1 < n_stages) load_stage((s + 1) * DI_BK);
-        const double *as = As + buf * DI_A_DOUBLES + (wr * 32 + li) * DI_APITCH + 4 * lh;
-        const double *bs = Bs + buf * DI_B_DOUBLES + (4 * lh) * DI_BPITCH + wc * 64 + li;
-        // the lane's A values of the stage: k = 4 lh .. 4 lh + 3 of its row in both row blocks
-        double a[2][4];
+        const double *at = As + buf * A_TILE, *bt = Bs + buf * B_TILE;
+        const int arow = wr * 32 + li, bcol = wc * 64 + li;   // + 16 per further block
+        // k-minor operands: the lane's values of the stage, k = 4 lh .. 4 lh + 3 of its line
+        double a4[2][4], b4[4][4];
+        if constexpr (!TA) {
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            const d2 lo = *(const d2 *)(as + mi * 16 * DI_APITCH);
-            const d2 hi = *(const d2 *)(as + mi * 16 * DI_APITCH + 2);
-            a[mi][0] = lo.x; a[mi][1] = lo.y; a[mi][2] = hi.x; a[mi][3] = hi.y;
+            for (int mi = 0; mi < 2; ++mi) {
+                const double *p = at + (arow + mi * 16) * DI_APITCH + 4 * lh;
+                const d2 lo = *(const d2 *)p, hi = *(const d2 *)(p + 2);
+                a4[mi][0] = lo.x; a4[mi][1] = lo.y; a4[mi][2] = hi.x; a4[mi][3] = hi.y;
+            }
+        }
+        if constexpr (TB) {
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+                const double *p = bt + (bcol + ni * 16) * DI_APITCH + 4 * lh;
+                const d2 lo = *(const d2 *)p, hi = *(const d2 *)(p + 2);
+                b4[ni][0] = lo.x; b4[ni][1] = lo.y; b4[ni][2] = hi.x; b4[ni][3] = hi.y;
+            }
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            double b[4];
+            double a[2], b[4];
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) b[ni] = bs[t * DI_BPITCH + ni * 16];
+            for (int mi = 0; mi < 2; ++mi)
+                a[mi] = TA ? at[(4 * lh + t) * DI_BPITCH + arow + mi * 16] : a4[mi][t];
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                b[ni] = TB ? b4[ni][t] : bt[(4 * lh + t) * DI_BPITCH + bcol + ni * 16];
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mi][t], b[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
         }
         if (s + 1 < n_stages) store_stage(buf ^ 1);
         __syncthreads();
@@ -162,17 +201,27 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
         }
 }
 
+template <bool TA, bool TB>
+static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, hipStream_t s)
+{
+    constexpr int LDS = DiLayout<TA, TB>::LDS_BYTES;
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (granted != hipSuccess) return granted;
+    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(grid), dim3(DI_NT), LDS, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + DI_BM - 1) / DI_BM;
     const int64_t tiles_n = (a.N + DI_BN - 1) / DI_BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, DI_LDS_BYTES);
-    if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL(identity_mfma_f64_kernel, dim3((unsigned)grid), dim3(DI_NT), DI_LDS_BYTES, s, a);
-    return hipGetLastError();
+    if (a.transA && a.transB) return launch_di_layout<true, true>(a, (unsigned)grid, s);
+    if (a.transA) return launch_di_layout<true, false>(a, (unsigned)grid, s);
+    if (a.transB) return launch_di_layout<false, true>(a, (unsigned)grid, s);
+    return launch_di_layout<false, false>(a, (unsigned)grid, s);
 }
 
 }  // namespace amulet

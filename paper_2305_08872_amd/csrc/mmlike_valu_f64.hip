@@ -354,11 +354,7 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     const dim3 grid((unsigned)wgs);
     const bool trans = a.transA || a.transB;
     switch (task) {
-    case TASK_IDENTITY:
-        // a dense contraction: matrix cores; their kernel reads row-major operands only
-        if (!trans) return launch_identity_mfma_f64(a, s);
-        hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK_IDENTITY, THRES_COL, true>), grid, dim3(D_NT), 0, s, a);
-        return hipGetLastError();
+    case TASK_IDENTITY: return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
     case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, a, grid, s)
                                      : launch_f64_form<TASK_DISCOUNT, false>(form, a, grid, s);
     case TASK_BOOST: return trans ? launch_f64_form<TASK_BOOST, true>(form, a, grid, s)
