@@ -53,7 +53,9 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
         stops[i].record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
-    kernel_ms_avg = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    kernel_ms_avg = sum(kern_ms) / args.steps
+    kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
     ops = 2.0 * M * N * K
     achieved = ops / (kernel_ms_avg * 1e-3) / 1e12
     # what the matrix cores sustain on this instruction with nothing around it (the clock
@@ -82,7 +84,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
                    "tune_seconds": round(tune_s, 3)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
-                     "kernel_ms_avg": round(kernel_ms_avg, 4),
+                     "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
                      "compulsory_bytes": M * K + K * N + 8 * M * N,
                      "mfma_probe_tops": round(probe_tops, 1),
                      "frac_of_mfma_probe": round(achieved / probe_tops, 4)},
@@ -122,7 +124,9 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
         stops[i].record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
-    kernel_ms_avg = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    kernel_ms_avg = sum(kern_ms) / args.steps
+    kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
     flops = 2.0 * M * N * K
     achieved = flops / (kernel_ms_avg * 1e-3) / 1e12
     # issue slots per product: a 64-bit select is two v_cndmask_b32
@@ -157,7 +161,8 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
                    "tile_shape": "mfma_f64_128x128_k16" if tname == "identity" else "valu_f64_16x128_k16"},
         "roofline": {"bound": "mfma" if tname == "identity" else "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel_ms_avg": round(kernel_ms_avg, 4), "valu_ops_per_product": ops,
+                     "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
+                     "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(FP64_VECTOR_PEAK_TFLOPS / ops, 3),
                      "frac_of_op_mix_ceiling": round(achieved * ops / FP64_VECTOR_PEAK_TFLOPS, 4)},
         "cpu_baseline": cpu, "parity_worst_ratio_on_sample": parity, "library_dgemm": lib_ratio,
@@ -260,6 +265,7 @@ def main() -> int:
     kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
     ms_per_step = wall_ms / args.steps
     kernel_ms_avg = sum(kern_ms) / len(kern_ms)
+    kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
 
     flops = 2.0 * M * N * K
     value = flops / (ms_per_step * 1e-3) / 1e9                 # GFLOP/s, whole job
@@ -331,7 +337,7 @@ def main() -> int:
         "roofline": {"bound": "mfma" if am.amulet_shape_name(task, shape).startswith("mfma") else "alu", "achieved": round(achieved_tflops, 3),
                      "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved_tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": traffic,
-                     "kernel_ms_avg": round(kernel_ms_avg, 4),
+                     "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(ceiling_tflops, 3),
                      "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4)},

@@ -17,9 +17,12 @@
  *    or reallocates them.  R must not overlap A, B or params.
  *  - Matrices are row-major with a leading dimension in ELEMENTS (lda >= K,
  *    ldb >= N, ldr >= N): as in the paper's interface (Sec. 5) the rows of a
- *    matrix may be spaced apart in memory.  Any M, N, K >= 0 is accepted; edge tiles are handled inside.
+ *    matrix may be spaced apart in memory.  Any M, N, K >= 0 is accepted;
+ *    edge tiles are handled inside.
  *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
- *    Calls only enqueue work and return; they never synchronise or allocate.
+ *    Compute calls only enqueue work and return; they never synchronise or
+ *    allocate (amulet_tune, amulet_mmlike_f32_adaptive and the two probes do
+ *    both, and say so below).
  *  - Return value: AMULET_OK (0) or a negative amulet_status_t.  Nothing is
  *    enqueued when an argument error is returned.  M == 0, N == 0 or K == 0 is
  *    a successful no-op (R unchanged).

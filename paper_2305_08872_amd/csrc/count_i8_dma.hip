@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4
 count_i8_dma_kernel(const CountArgs args)
 {
     typedef DmaTile<WR, NSTAGE> T;
-    static_assert(NSTAGE == 3 || NSTAGE == 4, "the wait counts are written for rings of 3 or 4 stages");
+    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
     constexpr int DM_BM = T::BM, DM_A_BYTES = T::A_BYTES, DM_STAGE_BYTES = T::STAGE_BYTES;
     constexpr int NW = T::NW, B_LOADS = T::B_LOADS;
     static_assert(WR == 2 || WR == 4, "wave grid is 2 x 4 or 4 x 4");
@@ -160,9 +160,12 @@ count_i8_dma_kernel(const CountArgs args)
         else if (stages == 1) {
             if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        } else {
+        } else if (stages == 2) {
             if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else {
+            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
         }
     };
 
