@@ -323,9 +323,22 @@ mmlike_valu_kernel(const MmlikeArgs args)
     __syncthreads();
 
     const float *bs_lane = &Bs[0][0][lane * 4];
+    // Workgroups 256 apart in launch order tend to share a compute unit (8 XCDs x 32 CUs are
+    // filled round-robin).  Their wave priority rotates with the tile step so that they take
+    // turns being served first: left at equal priority the oldest wave always wins the issue
+    // slots, the workgroups of a round finish one after the other and the round's tail runs
+    // with too few waves to fill both slots (measured: +5 % when a launch is one or two rounds
+    // of workgroups, +0-2 % at sixteen).
+    const int prio_phase = (int)(blockIdx.x >> 8);
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int k0 = t * BK;
+        switch ((t + prio_phase) & 3) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        default: __builtin_amdgcn_s_setprio(3); break;
+        }
         if (t + 1 < n_tiles)
             load_tile((t + 1 < full_tiles) ? BK : tail);
         const float *bs = bs_lane + buf * (BK * BN);
