@@ -35,7 +35,7 @@ static std::map<SelKey, int> g_selected;
 
 static int n_shapes(int task)
 {
-    if (task == TASK_IDENTITY) return VALU_SHAPE_COUNT + 1;  // plus the matrix-core kernel
+    if (task == TASK_IDENTITY) return VALU_SHAPE_COUNT + 2;  // plus the two matrix-core tiles
     if (task > TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
     if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
     return 0;
@@ -53,7 +53,9 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t)
     // every compute unit two tiles or more, else 128 x 256 (both fall back to the register-staged
     // kernel when the problem is not fully interior and aligned)
     if (task == AMULET_TASK_COUNT_I8) return ((M / 256) * ((N + 255) / 256) >= 512) ? 7 : 6;
-    if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;  // a dense contraction: matrix cores
+    // a dense contraction: matrix cores (the 128 x 128 tile measures 1 % ahead of the 256 x 256
+    // one even at 8192^3; the selector tries both)
+    if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;
     const int64_t tiles32 = ((M + 31) / 32) * ((N + 255) / 256);
     return tiles32 >= 512 ? VALU_TILES + 1 : VALU_TILES + 0;
 }
@@ -121,7 +123,7 @@ static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
     hipError_t e;
     switch (c.task) {
     case TASK_IDENTITY:
-        e = shape == IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, s)
+        e = shape >= IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, shape == IDENTITY_MFMA_BIG_SHAPE, s)
                                          : launch_mmlike_valu_task<TASK_IDENTITY, THRES_COL>(shape, a, s);
         break;
     case TASK_DISCOUNT: e = launch_form<TASK_DISCOUNT>(c.thres_form, shape, a, s); break;
@@ -246,6 +248,7 @@ static int64_t trial_rows(const MmlikeCall &c, int shape)
 {
     // enough row tiles for about five workgroups on each of the 256 compute units
     int64_t tile_rows = 128, tile_cols = 128;
+    if (shape == IDENTITY_MFMA_BIG_SHAPE) tile_rows = tile_cols = 256;
     if (shape < VALU_SHAPE_COUNT) {
         tile_rows = (int64_t)kValuShapes[shape].NW * kValuShapes[shape].TM;
         tile_cols = 256LL * kValuShapes[shape].NG;
@@ -523,9 +526,13 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
             int b0 = 0, b1 = 0;
             amulet_greedy_search(VALU_DEPTHS, VALU_TILES, valu_trial_score, &c, &b0, &b1);
             chosen = b0 * VALU_TILES + b1;
-            if (task == TASK_IDENTITY &&
-                time_shape(&c, IDENTITY_MFMA_SHAPE) < time_shape(&c, chosen))
-                chosen = IDENTITY_MFMA_SHAPE;
+            if (task == TASK_IDENTITY) {
+                double best = time_shape(&c, chosen);
+                for (int sidx = IDENTITY_MFMA_SHAPE; sidx <= IDENTITY_MFMA_BIG_SHAPE; ++sidx) {
+                    const double t = time_shape(&c, sidx);
+                    if (t < best) { best = t; chosen = sidx; }
+                }
+            }
         }
         (void)hipStreamSynchronize(c.stream);
         if (c.status == AMULET_OK) {
@@ -566,6 +573,7 @@ const char *amulet_shape_name(int task, int shape)
     if (shape < 0 || shape >= n_shapes(task)) return "invalid";
     if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
     if (shape == IDENTITY_MFMA_SHAPE) return "mfma_f32_128x128_k16";
+    if (shape == IDENTITY_MFMA_BIG_SHAPE) return "mfma_f32_256x256_w16_k16";
     return kValuShapes[shape].name;
 }
 

@@ -103,9 +103,10 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s);
 
-// Identity task on the fp32 matrix cores; its shape id follows the VALU shapes.
-enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT };
-hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s);
+// Identity task on the fp32 matrix cores; its two shape ids follow the VALU shapes:
+// a 128 x 128 tile (4 waves) and a 256 x 256 tile (16 waves).
+enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT, IDENTITY_MFMA_BIG_SHAPE = VALU_SHAPE_COUNT + 1 };
+hipError_t launch_identity_mfma(const MmlikeArgs &a, int big, hipStream_t s);
 
 template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);

@@ -2,8 +2,9 @@
 // With no per-product step this one task is a dense contraction, so it runs as
 // v_mfma_f32_32x32x2_f32 tiles instead of the vector-ALU micro-tiles.
 //
-// Workgroup: 256 threads = 4 waves in a 2x2 grid, R tile 128 x 128, each wave a
-// 64 x 64 sub-tile = 2x2 MFMA blocks of 32 x 32 (64 accumulator registers).
+// Workgroup: G x G waves (template parameter G = 2 or 4), R tile 64 G x 64 G (128 x 128 with
+// 4 waves, or 256 x 256 with 16 waves: half the operand traffic per multiply-add, for large
+// problems), each wave a 64 x 64 sub-tile = 2x2 MFMA blocks of 32 x 32 (64 accumulator registers).
 // K is staged 16 at a time: A tile 128 x 16 (k contiguous, row pitch padded to
 // 20 floats so 16-byte fragment reads spread over all banks) and B tile
 // 16 x 128 (as in global memory), global -> registers -> LDS, double buffered,
@@ -35,28 +36,39 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int MI_BM = 128, MI_BN = 128, MI_BK = 16;
+constexpr int MI_BK = 16;
 constexpr int MI_APITCH = MI_BK + 4;   // floats
 
 // 4 waves per SIMD (at most 128 registers): four 128 x 128 workgroups per compute unit, which is
 // what lets a 4096 x 4096 result (1024 tiles on 256 compute units) run as one full round.
-constexpr int MI_KMINOR_FLOATS = MI_BM * MI_APITCH;   // one k-minor tile: 128 x 20
-constexpr int MI_KMAJOR_FLOATS = MI_BK * MI_BN;       // one k-major tile: 16 x 128
+template <int G, bool TA, bool TB>
+struct MiLayout {
+    static constexpr int BM = 64 * G, BN = 64 * G, NT = 64 * G * G;
+    static constexpr int KMINOR_FLOATS = BM * MI_APITCH;   // one k-minor tile: BM x 20
+    static constexpr int KMAJOR_FLOATS = MI_BK * BN;       // one k-major tile: 16 x BN
+    static constexpr int A_TILE = TA ? KMAJOR_FLOATS : KMINOR_FLOATS;
+    static constexpr int B_TILE = TB ? KMINOR_FLOATS : KMAJOR_FLOATS;
+    static constexpr int LDS_BYTES = 2 * (A_TILE + B_TILE) * 4;   // 32-40 KB (G = 2), 64-80 KB (G = 4)
+    static constexpr int ITERS = 4 / G;                    // 16-byte staging slots per thread and operand
+};
 
-template <bool TA, bool TB>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+template <int G, bool TA, bool TB>
+__global__ void __launch_bounds__(64 * G * G) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_kernel(const MmlikeArgs args)
 {
-    constexpr int A_TILE = TA ? MI_KMAJOR_FLOATS : MI_KMINOR_FLOATS;
-    constexpr int B_TILE = TB ? MI_KMINOR_FLOATS : MI_KMAJOR_FLOATS;
-    __shared__ __attribute__((aligned(16))) float As[2 * A_TILE];
-    __shared__ __attribute__((aligned(16))) float Bs[2 * B_TILE];
+    typedef MiLayout<G, TA, TB> L;
+    constexpr int MI_BM = L::BM, MI_BN = L::BN, NT = L::NT, ITERS = L::ITERS;
+    constexpr int A_TILE = L::A_TILE, B_TILE = L::B_TILE;
+    constexpr int QB = MI_BN / 4;   // float4 slots in one k-major row
+    extern __shared__ __attribute__((aligned(16))) float mi_smem[];
+    float *const As = mi_smem;                 // [2][A_TILE]
+    float *const Bs = mi_smem + 2 * A_TILE;    // [2][B_TILE]
 
     const int M = args.M, N = args.N, K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / G, wc = wave % G;
     const int li = lane & 31, lh = lane >> 5;
 
     // XCD-aware tile order (xcd_tile in amulet_internal.h): each XCD walks its own rectangular
@@ -74,17 +86,19 @@ identity_mfma_kernel(const MmlikeArgs args)
                           (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
     const float *const a_base = args.A + (int64_t)row0 * args.lda;
     const float *const b_base = args.B + col0;
-    unsigned offa[2], offb[2];
+    // staging slots of 16 bytes, u = tid + NT * it:
+    //   k-minor tile, BM lines x 4 slots:  line = u / 4, k quad = u % 4
+    //   k-major tile, 16 k x BN/4 slots:   k = u / (BN/4), line quad = u % (BN/4)
+    unsigned offa[ITERS], offb[ITERS];
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
+    for (int it = 0; it < ITERS; ++it) {
+        const int u = tid + NT * it;
         // byte offsets
-        offa[it] = ((unsigned)((tid >> 2) + 64 * it) * (unsigned)args.lda + (unsigned)(tid & 3) * 4u) * 4u;
-        offb[it] = ((unsigned)((tid >> 5) + 8 * it) * (unsigned)args.ldb + (unsigned)(tid & 31) * 4u) * 4u;
+        offa[it] = ((unsigned)(u >> 2) * (unsigned)args.lda + (unsigned)(u & 3) * 4u) * 4u;
+        offb[it] = ((unsigned)(u / QB) * (unsigned)args.ldb + (unsigned)(u % QB) * 4u) * 4u;
     }
 
-    // staging slots: A tile 128 rows x 4 float4, thread -> (row = tid / 4 + 64*it, kq = tid % 4)
-    //                B tile 16 rows x 32 float4, thread -> (k = tid / 32 + 8*it, cq = tid % 32)
-    f4 sa[2], sb[2];
+    f4 sa[ITERS], sb[ITERS];
     auto load_stage = [&](int k0) {
         if (interior && k0 + MI_BK <= K) {
             // buffer loads: scalar resource (uniform base) + 32-bit per-thread byte offset
@@ -93,18 +107,18 @@ identity_mfma_kernel(const MmlikeArgs args)
             const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
                 (void *)(b_base + (int64_t)k0 * args.ldb), 0, 0x7fffffff, 0x00020000);
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
+            for (int it = 0; it < ITERS; ++it) {
                 sa[it] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(ra, offa[it], 0, 0));
                 sb[it] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rb, offb[it], 0, 0));
             }
             return;
         }
-        // k-minor operand: thread -> (line = tid / 4 + 64*it, k quad = tid % 4) of 128 lines x 16 k
-        auto load_kminor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[2]) {
+        auto load_kminor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[ITERS]) {
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int r = line0 + (tid >> 2) + 64 * it;
-                const int k = k0 + (tid & 3) * 4;
+            for (int it = 0; it < ITERS; ++it) {
+                const int u = tid + NT * it;
+                const int r = line0 + (u >> 2);
+                const int k = k0 + (u & 3) * 4;
                 f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (r < n_lines) {
                     const float *src = base + (int64_t)r * ld + k;
@@ -120,12 +134,12 @@ identity_mfma_kernel(const MmlikeArgs args)
                 dst[it] = v;
             }
         };
-        // k-major operand: thread -> (k = tid / 32 + 8*it, line quad = tid % 32) of 16 k x 128 lines
-        auto load_kmajor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[2]) {
+        auto load_kmajor = [&](const float *base, int64_t ld, int line0, int n_lines, bool vec, f4 (&dst)[ITERS]) {
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int k = k0 + (tid >> 5) + 8 * it;
-                const int c = line0 + (tid & 31) * 4;
+            for (int it = 0; it < ITERS; ++it) {
+                const int u = tid + NT * it;
+                const int k = k0 + u / QB;
+                const int c = line0 + (u % QB) * 4;
                 f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (k < K) {
                     const float *src = base + (int64_t)k * ld + c;
@@ -148,9 +162,10 @@ identity_mfma_kernel(const MmlikeArgs args)
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int kminor = ((tid >> 2) + 64 * it) * MI_APITCH + (tid & 3) * 4;
-            const int kmajor = ((tid >> 5) + 8 * it) * MI_BN + (tid & 31) * 4;
+        for (int it = 0; it < ITERS; ++it) {
+            const int u = tid + NT * it;
+            const int kminor = (u >> 2) * MI_APITCH + (u & 3) * 4;
+            const int kmajor = (u / QB) * MI_BN + (u % QB) * 4;
             *(f4 *)&As[buf * A_TILE + (TA ? kmajor : kminor)] = sa[it];
             *(f4 *)&Bs[buf * B_TILE + (TB ? kminor : kmajor)] = sb[it];
         }
@@ -249,23 +264,34 @@ identity_mfma_kernel(const MmlikeArgs args)
         }
 }
 
-template <bool TA, bool TB>
-static void launch_identity_layout(const MmlikeArgs &a, unsigned grid, hipStream_t s)
+template <int G, bool TA, bool TB>
+static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((identity_mfma_kernel<TA, TB>), dim3(grid), dim3(256), 0, s, a);
-}
-
-hipError_t launch_identity_mfma(const MmlikeArgs &a, hipStream_t s)
-{
-    const int64_t tiles_m = (a.M + MI_BM - 1) / MI_BM;
-    const int64_t tiles_n = (a.N + MI_BN - 1) / MI_BN;
+    typedef MiLayout<G, TA, TB> L;
+    const int64_t tiles_m = (a.M + L::BM - 1) / L::BM;
+    const int64_t tiles_n = (a.N + L::BN - 1) / L::BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.transA && a.transB) launch_identity_layout<true, true>(a, (unsigned)grid, s);
-    else if (a.transA) launch_identity_layout<true, false>(a, (unsigned)grid, s);
-    else if (a.transB) launch_identity_layout<false, true>(a, (unsigned)grid, s);
-    else launch_identity_layout<false, false>(a, (unsigned)grid, s);
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
+    if (granted != hipSuccess) return granted;
+    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3((unsigned)grid), dim3(L::NT), L::LDS_BYTES, s, a);
     return hipGetLastError();
+}
+
+template <int G>
+static hipError_t launch_identity_grid(const MmlikeArgs &a, hipStream_t s)
+{
+    if (a.transA && a.transB) return launch_identity_layout<G, true, true>(a, s);
+    if (a.transA) return launch_identity_layout<G, true, false>(a, s);
+    if (a.transB) return launch_identity_layout<G, false, true>(a, s);
+    return launch_identity_layout<G, false, false>(a, s);
+}
+
+// big = 0: 128 x 128 tile (4 waves); big = 1: 256 x 256 tile (16 waves)
+hipError_t launch_identity_mfma(const MmlikeArgs &a, int big, hipStream_t s)
+{
+    return big ? launch_identity_grid<4>(a, s) : launch_identity_grid<2>(a, s);
 }
 
 }  // namespace amulet

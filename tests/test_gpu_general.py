@@ -124,7 +124,7 @@ def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
         for pad in (0, 3):
             bufA = torch.zeros(As.shape[0], As.shape[1] + pad, device="cuda"); bufA[:, :As.shape[1]] = dev(As)
             bufB = torch.zeros(Bs.shape[0], Bs.shape[1] + pad, device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
-            for shape in (8, -1):
+            for shape in (8, 9, -1):
                 print("identity trans", tA, tB, M, N, K, pad, shape, flush=True)
                 dR = dev(R_in)
                 am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,

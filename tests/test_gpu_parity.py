@@ -58,7 +58,7 @@ ODD_SHAPES = [(70, 300, 37), (33, 513, 100), (1, 1, 1), (129, 1030, 77), (5, 257
 
 
 @pytest.mark.parametrize("task", TASKS)
-@pytest.mark.parametrize("shape", range(9))
+@pytest.mark.parametrize("shape", range(10))
 def test_every_shape_on_ragged_sizes(am, task, shape):
     if shape >= am.amulet_shape_count(task):
         pytest.skip("task %d has no shape %d" % (task, shape))

@@ -104,7 +104,7 @@ def test_register_rule_matches_paper_worked_example(lib, golden_dir):
 def test_shape_table_is_the_two_axis_grid(lib):
     n = am.amulet_shape_count(am.AMULET_DISCOUNT)
     assert n == 8 and am.amulet_shape_count(77) == 0
-    assert am.amulet_shape_count(am.AMULET_IDENTITY) == 9  # plus the matrix-core kernel
+    assert am.amulet_shape_count(am.AMULET_IDENTITY) == 10  # plus the two matrix-core tiles
     names = [am.amulet_shape_name(1, i) for i in range(n)]
     assert len(set(names)) == n and all(x.startswith("valu_") for x in names)
     assert 0 <= am.amulet_selected_shape(1, 8192, 8192, 8192) < n
