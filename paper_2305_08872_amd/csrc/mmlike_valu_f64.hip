@@ -1,10 +1,12 @@
-// The matrix-multiplication-like tasks in the paper's own element type, double (its
-// listings declare double A[M][K], B[K][N], C[M][N]; Sec. 3, Sec. 4.3.3).  Same mapping as
+// The predicate tasks (discount, boost, count over threshold) in the paper's own element
+// type, double (its listings declare double A[M][K], B[K][N], C[M][N]; Sec. 3,
+// Sec. 4.3.3).  Same mapping as
 // the fp32 vector-ALU kernels (mmlike_valu_impl.h): a lane owns columns, a wave owns TM rows
 // whose A values arrive through the scalar cache into SGPR pairs, the B tile goes through
 // LDS, the thresholds stay in registers, the K remainder is computed k by k.  One tile
 // shape: 16 x 128 per workgroup (4 waves x 4 rows, 2 columns per lane), 16 k per barrier.
 // fp64 accumulation needs no second level: K * 2^-53 stays far below the tolerance.
+// (The identity task, a dense contraction, has its own matrix-core kernel: identity_mfma_f64.hip.)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,12 +35,8 @@ template <int TASK>
 __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const double (&th)[D_TM][2],
                                           const double *q, typename AccD<TASK>::type (&acc)[D_TM][2])
 {
-    if constexpr (TASK == TASK_IDENTITY) {
-#pragma unroll
-        for (int r = 0; r < D_TM; ++r)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) acc[r][c] = __builtin_fma(a[r], b[c], acc[r][c]);
-    } else if constexpr (TASK == TASK_DISCOUNT) {
+    static_assert(TASK == TASK_DISCOUNT || TASK == TASK_BOOST || TASK == TASK_COUNT_GT, "predicate tasks only");
+    if constexpr (TASK == TASK_DISCOUNT) {
         double p[D_TM][2], s[D_TM][2];
 #pragma unroll
         for (int r = 0; r < D_TM; ++r)
@@ -127,7 +125,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     double th_row[TF == THRES_ROW ? D_TM : 1];
     double th_el[TF == THRES_ELEM ? D_TM : 1][TF == THRES_ELEM ? 2 : 1];
     double th_const = __builtin_inf();
-    if constexpr (TASK != TASK_IDENTITY) {
+    {
         if constexpr (TF == THRES_CONST) th_const = ((sptr_d)args.thres)[0];
         if constexpr (TF == THRES_ROW) {
 #pragma unroll
@@ -139,11 +137,11 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
         const int col = col0 + lane * 2 + c;
         q[c] = 1.0;
         if constexpr (TF == THRES_COL) th_col[c] = __builtin_inf();
-        if (TASK != TASK_IDENTITY && col < N) {
+        if (col < N) {
             if constexpr (TF == THRES_COL) th_col[c] = args.thres[col];
             if (TASK == TASK_DISCOUNT) q[c] = 1.0 - args.dis[col];
         }
-        if constexpr (TF == THRES_ELEM && TASK != TASK_IDENTITY) {
+        if constexpr (TF == THRES_ELEM) {
 #pragma unroll
             for (int r = 0; r < D_TM; ++r)
                 th_el[r][c] = (col < N) ? args.thres[(int64_t)rowc(r) * args.ldt + col] : __builtin_inf();
