@@ -119,6 +119,7 @@ static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
     a.transA = c.trans_a; a.transB = c.trans_b;
     a.vec = (aligned16(c.B) && aligned16(c.R) && c.ldb % 4 == 0 && c.ldr % 4 == 0) ? 1 : 0;
     a.vecA = (aligned16(c.A) && c.lda % 4 == 0) ? 1 : 0;
+    a.kchunk = (int)c.K;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (c.task) {

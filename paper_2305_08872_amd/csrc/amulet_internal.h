@@ -69,6 +69,7 @@ struct MmlikeArgs {
     int transA, transB;  // operand stored transposed: a(i,k) = A[k*lda+i], b(k,j) = B[j*ldb+k]
     int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
     int vecA;  // 1 when A and its row pitch do
+    int kchunk;  // k range of one workgroup when a launch splits K (set by the launcher)
 };
 
 // Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy

@@ -64,7 +64,8 @@ identity_mfma_kernel(const MmlikeArgs args)
     float *const As = mi_smem;                 // [2][A_TILE]
     float *const Bs = mi_smem + 2 * A_TILE;    // [2][B_TILE]
 
-    const int M = args.M, N = args.N, K = args.K;
+    const int M = args.M, N = args.N;
+    int K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -84,8 +85,18 @@ identity_mfma_kernel(const MmlikeArgs args)
     // unit, which matters because vector-ALU instructions share the issue port with the MFMAs.
     const bool interior = !TA && !TB && vecA && vecB && row0 + MI_BM <= M && col0 + MI_BN <= N &&
                           (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
-    const float *const a_base = args.A + (int64_t)row0 * args.lda;
-    const float *const b_base = args.B + col0;
+    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
+    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    const float *Ag = args.A, *Bg = args.B;
+    if (ksplit) {
+        const int kb = (int)blockIdx.y * args.kchunk;
+        Ag += TA ? (int64_t)kb * args.lda : (int64_t)kb;
+        Bg += TB ? (int64_t)kb : (int64_t)kb * args.ldb;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
+    const float *const a_base = Ag + (int64_t)row0 * args.lda;
+    const float *const b_base = Bg + col0;
     // staging slots of 16 bytes, u = tid + NT * it:
     //   k-minor tile, BM lines x 4 slots:  line = u / 4, k quad = u % 4
     //   k-major tile, 16 k x BN/4 slots:   k = u / (BN/4), line quad = u % (BN/4)
@@ -155,10 +166,10 @@ identity_mfma_kernel(const MmlikeArgs args)
                 dst[it] = v;
             }
         };
-        if constexpr (TA) load_kmajor(args.A, args.lda, row0, M, vecA, sa);
-        else load_kminor(args.A, args.lda, row0, M, vecA, sa);
-        if constexpr (TB) load_kminor(args.B, args.ldb, col0, N, vecB, sb);
-        else load_kmajor(args.B, args.ldb, col0, N, vecB, sb);
+        if constexpr (TA) load_kmajor(Ag, args.lda, row0, M, vecA, sa);
+        else load_kminor(Ag, args.lda, row0, M, vecA, sa);
+        if constexpr (TB) load_kminor(Bg, args.ldb, col0, N, vecB, sb);
+        else load_kmajor(Bg, args.ldb, col0, N, vecB, sb);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
@@ -258,7 +269,8 @@ identity_mfma_kernel(const MmlikeArgs args)
                 const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (row < M) {
                     float *dst = args.R + (int64_t)row * args.ldr + col;
-                    *dst += acc[mi][ni][v];
+                    if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                    else *dst += acc[mi][ni][v];
                 }
             }
         }
@@ -275,7 +287,22 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3((unsigned)grid), dim3(L::NT), L::LDS_BYTES, s, a);
+    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // (at least 128 k each), which add their parts to R with hardware float atomics
+    MmlikeArgs b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = tiles_m * tiles_n * G * G;
+    if (waves < 2048 && a.K >= 256) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 128) want = a.K / 128;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + MI_BK - 1) / MI_BK * MI_BK;
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3((unsigned)grid, (unsigned)splits), dim3(L::NT),
+                       L::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 

@@ -113,7 +113,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
 
     __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
 
-    const int M = args.M, N = args.N, K = args.K;
+    const int M = args.M, N = args.N;
+    int K = args.K;
     const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned: float4 global accesses
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -127,7 +128,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int col0 = tn * BN;
 
     const float *__restrict__ Bg = args.B;
-    const sptr_f As = (sptr_f)args.A;
+    sptr_f As = (sptr_f)args.A;
 
     // Wave-uniform row offsets, clamped so edge waves read valid rows.  a(i,k) lives at
     // A[i*lda + k], or at A[k*lda + i] when A is stored transposed (the [k][i]-indexed
@@ -136,6 +137,15 @@ mmlike_valu_kernel(const MmlikeArgs args)
     // cost the row-major kernels scalar registers in the hot loop.
     const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
     const int64_t kstride = transA ? args.lda : 1;
+    // Split K (gridDim.y > 1; chosen by the host for problems with too few tiles to fill the
+    // chip): this workgroup sums k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    if (ksplit) {
+        const int kb = (int)blockIdx.y * args.kchunk;
+        As += (int64_t)kb * kstride;
+        Bg += transB ? (int64_t)kb : (int64_t)kb * args.ldb;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
     const bool rows_full = row0 + TM <= M;
     auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
     int64_t arow[TM];
@@ -432,7 +442,12 @@ mmlike_valu_kernel(const MmlikeArgs args)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 v[c] = (TASK == TASK_COUNT_GT) ? (float)part[r][g * 4 + c] : mainacc[r][g * 4 + c];
-            if (VEC && col + 3 < N) {
+            if (ksplit) {
+                // several workgroups own this tile: hardware float adds, in whatever order
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (col + c < N) unsafeAtomicAdd(dst_row + col + c, v[c]);
+            } else if (VEC && col + 3 < N) {
                 f4 o = *(f4 *)(dst_row + col);
                 o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
                 *(f4 *)(dst_row + col) = o;
@@ -452,11 +467,26 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     const int64_t tiles_n = (a.N + 256 * NG - 1) / (256 * NG);
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs), block(64 * NW);
+    // Too few tiles to give every SIMD two waves (tiny M x N, e.g. an aggregation over a long K):
+    // split K over several workgroups per tile, at least 64 k each; each adds its part to R
+    // with hardware float atomics (the sum order is free, Sec. 4.1).
+    MmlikeArgs b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = tiles_m * tiles_n * NW;
+    if (waves < 2048 && a.K >= 128) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 64) want = a.K / 64;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + 63) / 64 * 64;   // whole partial-sum periods
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    const dim3 grid((unsigned)wgs, (unsigned)splits), block(64 * NW);
     if (a.transA || a.transB)
-        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
     else
-        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
     return hipGetLastError();
 }
 

@@ -165,3 +165,28 @@ def test_adaptive_execution_trials_contribute_to_the_result(am):
     assert_parity_f32(dR3.cpu().numpy(), R_ref, ab, what="adaptive identity")
     assert t3 >= 2
     am.amulet_clear_selections()
+
+
+@pytest.mark.parametrize("task", [0, 1, 2, 3])
+def test_few_tiles_long_k_split_over_workgroups(am, task):
+    """Tiny M x N with a long K: the launcher splits K over several workgroups per tile, which add
+    their parts to R atomically.  Checked for every vector-ALU shape, ragged K, non-zero R_in, a
+    transposed layout and data whose sums are exact in any order (bit-exact then)."""
+    cases = [(64, 64, 5000, False), (20, 300, 1037, False), (130, 260, 777, True), (5, 5, 4096, False)]
+    for idx, (M, N, K, trans) in enumerate(cases):
+        for shape in (4, 0, 5, 7) + ((8, 9) if task == 0 else ()):   # 8, 9: the matrix-core identity kernels
+            form = (idx + shape) % 4 if task else 0
+            As, Bs, th, dis, R_in = make_case(task, form, trans, trans, M, N, K, 6100 + 10 * task + idx)
+            R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=trans,
+                                                     trans_b=trans)
+            print("split-K case", task, form, shape, M, N, K, trans, flush=True)
+            R = run(am, task, form, trans, trans, As, Bs, th, dis, R_in, shape)
+            if task == 3:
+                assert np.array_equal(R, R_ref), (task, form, shape, M, N, K)
+            else:
+                assert_parity_f32(R, R_ref, ab, R_in, what="split-K task %d shape %d %dx%dx%d" % (task, shape, M, N, K))
+    # exact data: small integers and half-integer thresholds, every partial sum exact in fp32
+    As, Bs, th, dis, R_in = make_case(task, 0, False, False, 48, 200, 1500, 6200 + task, exact=True)
+    R_ref, _, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in)
+    R = run(am, task, 0, False, False, As, Bs, th, dis, R_in)
+    assert np.array_equal(R, R_ref)
