@@ -345,6 +345,7 @@ int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b
     a.vec = (aligned16(R) && ldr % 2 == 0 && (a.transB || b16)) ? 1 : 0;
     a.vecBt = b16 ? 1 : 0;
     a.vecA = (aligned16(A) && lda % 2 == 0) ? 1 : 0;
+    a.kchunk = (int)K;
     const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

@@ -125,6 +125,7 @@ struct MmlikeArgsF64 {
     int vecA;  // 1 when A and its row pitch do
     int transA, transB;  // operand stored transposed: a(i,k) = A[k*lda+i], b(k,j) = B[j*ldb+k]
     int vecBt; // transposed B: 1 when B and its row pitch allow 16-byte loads along k
+    int kchunk;  // k range of one workgroup when a launch splits K (set by the launcher)
 };
 // predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);

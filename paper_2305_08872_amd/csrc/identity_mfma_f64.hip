@@ -53,7 +53,8 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     double *const As = di_smem;                  // [2][A_TILE]
     double *const Bs = di_smem + 2 * A_TILE;     // [2][B_TILE]
 
-    const int M = args.M, N = args.N, K = args.K;
+    const int M = args.M, N = args.N;
+    int K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -68,6 +69,17 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     const int row0 = tm * DI_BM, col0 = tn * DI_BN;
     // 16-byte loads allowed along the operand's contiguous axis
     const bool vecA = args.vecA != 0, vecB = TB ? args.vecBt != 0 : args.vec != 0;
+
+    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
+    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    const double *Ag = args.A, *Bg = args.B;
+    if (ksplit) {
+        const int kb = (int)blockIdx.y * args.kchunk;
+        Ag += TA ? (int64_t)kb * args.lda : (int64_t)kb;
+        Bg += TB ? (int64_t)kb : (int64_t)kb * args.ldb;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
 
     // staging slots of 16 bytes, u = tid + 512 * it:
     //   k-minor tile, 128 lines x 8 slots: line = u / 8, k pair = u % 8
@@ -112,10 +124,10 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
                 dst[it] = v;
             }
         };
-        if constexpr (TA) load_kmajor(args.A, args.lda, row0, M, vecA, sa);
-        else load_kminor(args.A, args.lda, row0, M, vecA, sa);
-        if constexpr (TB) load_kminor(args.B, args.ldb, col0, N, vecB, sb);
-        else load_kmajor(args.B, args.ldb, col0, N, vecB, sb);
+        if constexpr (TA) load_kmajor(Ag, args.lda, row0, M, vecA, sa);
+        else load_kminor(Ag, args.lda, row0, M, vecA, sa);
+        if constexpr (TB) load_kminor(Bg, args.ldb, col0, N, vecB, sb);
+        else load_kmajor(Bg, args.ldb, col0, N, vecB, sb);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
@@ -195,20 +207,35 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
                 const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
                 if (row < M) {
                     double *dst = args.R + (int64_t)row * args.ldr + col;
-                    *dst += acc[mi][ni][v];
+                    if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                    else *dst += acc[mi][ni][v];
                 }
             }
         }
 }
 
 template <bool TA, bool TB>
-static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, hipStream_t s)
+static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_t n_tiles, hipStream_t s)
 {
     constexpr int LDS = DiLayout<TA, TB>::LDS_BYTES;
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(grid), dim3(DI_NT), LDS, s, a);
+    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // (at least 128 k each), which add their parts to R with hardware fp64 atomics
+    MmlikeArgsF64 b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = (int64_t)n_tiles * (DI_NT / 64);
+    if (waves < 2048 && a.K >= 256) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 128) want = a.K / 128;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + DI_BK - 1) / DI_BK * DI_BK;
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(grid, (unsigned)splits), dim3(DI_NT), LDS, s, b);
     return hipGetLastError();
 }
 
@@ -218,10 +245,10 @@ hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s)
     const int64_t tiles_n = (a.N + DI_BN - 1) / DI_BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.transA && a.transB) return launch_di_layout<true, true>(a, (unsigned)grid, s);
-    if (a.transA) return launch_di_layout<true, false>(a, (unsigned)grid, s);
-    if (a.transB) return launch_di_layout<false, true>(a, (unsigned)grid, s);
-    return launch_di_layout<false, false>(a, (unsigned)grid, s);
+    if (a.transA && a.transB) return launch_di_layout<true, true>(a, (unsigned)grid, tiles_m * tiles_n, s);
+    if (a.transA) return launch_di_layout<true, false>(a, (unsigned)grid, tiles_m * tiles_n, s);
+    if (a.transB) return launch_di_layout<false, true>(a, (unsigned)grid, tiles_m * tiles_n, s);
+    return launch_di_layout<false, false>(a, (unsigned)grid, tiles_m * tiles_n, s);
 }
 
 }  // namespace amulet

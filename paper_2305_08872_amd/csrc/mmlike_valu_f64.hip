@@ -97,7 +97,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 
     __shared__ __attribute__((aligned(16))) double Bs[2][D_BK][D_BN];
 
-    const int M = args.M, N = args.N, K = args.K;
+    const int M = args.M, N = args.N;
+    int K = args.K;
     const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned
     const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
     const int lane = threadIdx.x & 63;
@@ -111,7 +112,17 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int row0 = tm * (D_NW * D_TM) + wave * D_TM;
     const int col0 = tn * D_BN;
 
-    const sptr_d As = (sptr_d)args.A;
+    // Split K (gridDim.y > 1; chosen by the host for problems with too few tiles to fill the
+    // chip): this workgroup sums k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    sptr_d As = (sptr_d)args.A;
+    const double *Bg = args.B;
+    if (ksplit) {
+        const int kb = (int)blockIdx.y * args.kchunk;
+        As += transA ? (int64_t)kb * args.lda : (int64_t)kb;
+        Bg += transB ? (int64_t)kb : (int64_t)kb * args.ldb;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
     auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
     // a(i,k) lives at arow[r] + k * kstride (elements)
     int64_t arow[D_TM];
@@ -170,7 +181,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int srow = threadIdx.x / D2_PER_ROW;
     const int scol = col0 + (threadIdx.x % D2_PER_ROW) * 2;
     const bool fast_cols = VEC && (col0 + D_BN <= N);
-    const double *bsrc = args.B + (int64_t)srow * args.ldb + scol;
+    const double *bsrc = Bg + (int64_t)srow * args.ldb + scol;
     const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
     const int64_t tile_stride = (int64_t)D_BK * args.ldb;
     d2 stage[LOADS];
@@ -180,7 +191,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     static_assert(D_NT == 2 * D_BN && D_BK == 16 && LOADS == 4, "transposed-B slot mapping");
     const int tcol = threadIdx.x % D_BN;
     const int tk = (threadIdx.x / D_BN) * 8;
-    const double *btsrc = args.B + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
+    const double *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
     const bool vecBt = TRANS && args.vecBt != 0;
     auto load_tile = [&](int krows) {
         if (transB) {
@@ -320,7 +331,11 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
         double *dst_row = args.R + (int64_t)row * args.ldr;
         const int col = col0 + lane * 2;
         const double v0 = (double)acc[r][0], v1 = (double)acc[r][1];
-        if (VEC && col + 1 < N) {
+        if (ksplit) {
+            // several workgroups own this tile: hardware fp64 adds, in whatever order
+            if (col + 0 < N) unsafeAtomicAdd(dst_row + col + 0, v0);
+            if (col + 1 < N) unsafeAtomicAdd(dst_row + col + 1, v1);
+        } else if (VEC && col + 1 < N) {
             d2 o = *(d2 *)(dst_row + col);
             o.x += v0; o.y += v1;
             *(d2 *)(dst_row + col) = o;
@@ -349,16 +364,30 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     const int64_t tiles_n = (a.N + D_BN - 1) / D_BN;
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs);
+    if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
+    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // (at least 64 k each), which add their parts to R with hardware fp64 atomics
+    MmlikeArgsF64 b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = tiles_m * tiles_n * D_NW;
+    if (waves < 2048 && a.K >= 128) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 64) want = a.K / 64;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + D_BK - 1) / D_BK * D_BK;
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    const dim3 grid((unsigned)wgs, (unsigned)splits);
     const bool trans = a.transA || a.transB;
     switch (task) {
-    case TASK_IDENTITY: return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
-    case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, a, grid, s)
-                                     : launch_f64_form<TASK_DISCOUNT, false>(form, a, grid, s);
-    case TASK_BOOST: return trans ? launch_f64_form<TASK_BOOST, true>(form, a, grid, s)
-                                  : launch_f64_form<TASK_BOOST, false>(form, a, grid, s);
-    case TASK_COUNT_GT: return trans ? launch_f64_form<TASK_COUNT_GT, true>(form, a, grid, s)
-                                     : launch_f64_form<TASK_COUNT_GT, false>(form, a, grid, s);
+    case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, b, grid, s)
+                                     : launch_f64_form<TASK_DISCOUNT, false>(form, b, grid, s);
+    case TASK_BOOST: return trans ? launch_f64_form<TASK_BOOST, true>(form, b, grid, s)
+                                  : launch_f64_form<TASK_BOOST, false>(form, b, grid, s);
+    case TASK_COUNT_GT: return trans ? launch_f64_form<TASK_COUNT_GT, true>(form, b, grid, s)
+                                     : launch_f64_form<TASK_COUNT_GT, false>(form, b, grid, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -234,3 +234,29 @@ def test_f64_transposed_operands(am, task, tA, tB):
                              thres_form=form, trans_a=tA, trans_b=tB)
         torch.cuda.synchronize()
         check(dR.cpu().numpy(), R_ref, ab, R_in, task, "trans %r %r task %d %dx%dx%d" % (tA, tB, task, M, N, K))
+
+
+@pytest.mark.parametrize("task", TASKS)
+def test_f64_few_tiles_long_k_split_over_workgroups(am, task):
+    """Tiny M x N with a long K: K is split over several workgroups per tile, which add their
+    parts to R with fp64 atomics (vector-ALU kernel and matrix-core identity kernel)."""
+    for idx, (M, N, K, trans) in enumerate([(64, 64, 5000, False), (20, 300, 1037, False), (130, 260, 777, True),
+                                            (5, 5, 4096, False)]):
+        form = (idx + task) % 4 if task else 0
+        A, B, th, dis, R_in = make_case(form, M, N, K, 8300 + 10 * task + idx)
+        As = np.ascontiguousarray(A.T) if trans else A
+        Bs = np.ascontiguousarray(B.T) if trans else B
+        R_ref, ab, _ = oracle.mmlike_f64_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=trans,
+                                                 trans_b=trans)
+        print("f64 split-K case", task, form, M, N, K, trans, flush=True)
+        dR = dev(R_in)
+        am.amulet_mmlike_f64(task, dev(As), dev(Bs), dev(th) if task else None, dev(dis) if task == 1 else None, dR,
+                             thres_form=form, trans_a=trans, trans_b=trans)
+        torch.cuda.synchronize()
+        check(dR.cpu().numpy(), R_ref, ab, R_in, task, "f64 split-K task %d %dx%dx%d" % (task, M, N, K))
+    A, B, th, dis, R_in = make_case(0, 48, 200, 1500, 8400 + task, exact=True)
+    R_ref, _, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in)
+    dR = dev(R_in)
+    am.amulet_mmlike_f64(task, dev(A), dev(B), dev(th) if task else None, dev(dis) if task == 1 else None, dR)
+    torch.cuda.synchronize()
+    assert np.array_equal(dR.cpu().numpy(), R_ref)
