@@ -162,6 +162,7 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.vecA = (aligned16(A) && lda % 16 == 0) ? 1 : 0;
     a.vecB = (aligned16(B) && ldb % 16 == 0) ? 1 : 0;
     a.vecR = (aligned16(R) && ldr % 4 == 0) ? 1 : 0;
+    a.kchunk = (int)K;
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

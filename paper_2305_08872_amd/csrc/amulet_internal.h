@@ -95,6 +95,7 @@ struct CountArgs {
     int M, N, K;
     int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
     int vecR;        // 1 when R and its row pitch allow 16-byte accesses
+    int kchunk;      // k range of one workgroup when a launch splits K (set by the launcher)
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)

@@ -78,7 +78,8 @@ count_i8_mfma_kernel(const CountArgs args)
     int8_t *const As = count_smem;
     int8_t *const Bs = count_smem + 2 * T::A_BYTES;
 
-    const int M = args.M, N = args.N, K = args.K;
+    const int M = args.M, N = args.N;
+    int K = args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wr = wave / WC, wc = wave % WC;
@@ -102,8 +103,18 @@ count_i8_mfma_kernel(const CountArgs args)
     // interior path: buffer loads off a wave-uniform base that advances with k plus a fixed
     // 32-bit per-thread byte offset, so the address arithmetic stays on the scalar unit
     // (vector-ALU instructions share the issue port with the MFMAs)
-    const int8_t *const a_base = args.A + (int64_t)row0 * args.lda;
-    const int8_t *const b_base = args.B + col0;
+    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
+    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    const int8_t *Ag = args.A, *Bg = args.B;
+    if (ksplit) {
+        const int kb = (int)blockIdx.y * args.kchunk;
+        Ag += kb;
+        Bg += (int64_t)kb * args.ldb;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
+    const int8_t *const a_base = Ag + (int64_t)row0 * args.lda;
+    const int8_t *const b_base = Bg + col0;
     unsigned offa[A_UNITS], offb[B_UNITS];
     int8_t *la[A_UNITS];
     int8_t *lb[B_UNITS];
@@ -136,13 +147,13 @@ count_i8_mfma_kernel(const CountArgs args)
             for (int it = 0; it < A_UNITS; ++it) {
                 const int u = tid + it * NT;
                 const int r = row0 + u / AU, k = k0 + (u % AU) * 16;
-                sa[it] = (r < M) ? load16_i8(args.A + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
+                sa[it] = (r < M) ? load16_i8(Ag + (int64_t)r * args.lda + k, vecA, K - k) : v4i{0, 0, 0, 0};
             }
 #pragma unroll
             for (int it = 0; it < B_UNITS; ++it) {
                 const int u = tid + it * NT;
                 const int k = k0 + u / (BN / 16), c = col0 + (u % (BN / 16)) * 16;
-                sb[it] = (k < K) ? load16_i8(args.B + (int64_t)k * args.ldb + c, vecB, N - c) : v4i{0, 0, 0, 0};
+                sb[it] = (k < K) ? load16_i8(Bg + (int64_t)k * args.ldb + c, vecB, N - c) : v4i{0, 0, 0, 0};
             }
         }
     };
@@ -210,7 +221,8 @@ count_i8_mfma_kernel(const CountArgs args)
                 const int row = row0 + (wr * MB + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (row < M) {
                     int32_t *dst = args.R + (int64_t)row * args.ldr + col;
-                    *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc[mi][ni][v]);
+                    if (ksplit) atomicAdd(dst, acc[mi][ni][v]);
+                    else *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc[mi][ni][v]);
                 }
             }
         }
@@ -247,8 +259,22 @@ static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
             hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (granted != hipSuccess) return granted;
     }
-    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3((unsigned)grid), dim3(T::NT),
-                       T::LDS_BYTES, s, a);
+    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // (at least 512 k each), which add their parts to R with integer atomics
+    CountArgs b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = tiles_m * tiles_n * WR * WC;
+    if (waves < 2048 && a.K >= 1024) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 512) want = a.K / 512;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + BK - 1) / BK * BK;
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3((unsigned)grid, (unsigned)splits),
+                       dim3(T::NT), T::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 

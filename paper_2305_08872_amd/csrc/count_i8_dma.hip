@@ -65,7 +65,11 @@ count_i8_dma_kernel(const CountArgs args)
     static_assert(WR == 2 || WR == 4, "wave grid is 2 x 4 or 4 x 4");
     extern __shared__ __attribute__((aligned(16))) int8_t dma_smem[];
 
-    const int K = args.K;
+    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
+    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    const int kb = ksplit ? (int)blockIdx.y * args.kchunk : 0;
+    const int K = ksplit ? ((args.K - kb < args.kchunk) ? args.K - kb : args.kchunk) : args.K;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // WR x 4 grid
@@ -82,14 +86,14 @@ count_i8_dma_kernel(const CountArgs args)
     // A: wave w owns LDS slots [64w, 64w+64): slot s = 64w + lane -> row s/4, physical unit s%4
     const int a_row = wave * 16 + (lane >> 2);
     const int a_log = (lane & 3) ^ ((a_row >> 2) & 3);
-    const int8_t *ga = args.A + (int64_t)(row0 + a_row) * args.lda + a_log * 16;
+    const int8_t *ga = args.A + (int64_t)(row0 + a_row) * args.lda + kb + a_log * 16;
     // B: wave w owns slot groups j = w (+ NW): slot s = 64j + lane -> k row s/16, physical unit s%16
     const int8_t *gb[B_LOADS];
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) {
         const int krow = (wave + NW * q) * 4 + (lane >> 4);
         const int blog = (lane & 15) ^ ((krow & 7) << 1);
-        gb[q] = args.B + (int64_t)krow * args.ldb + col0 + blog * 16;
+        gb[q] = args.B + (int64_t)(kb + krow) * args.ldb + col0 + blog * 16;
     }
     const int64_t b_stage = (int64_t)DM_BK * args.ldb;
 
@@ -248,6 +252,15 @@ count_i8_dma_kernel(const CountArgs args)
 #pragma unroll
         for (int j = 0; j < ROWS_PER_WAVE; ++j) {
             const int r = wave * ROWS_PER_WAVE + j;           // row of the part this wave adds
+            if (ksplit) {
+                // several workgroups own this tile: integer atomic adds (exact in any order),
+                // 256 contiguous bytes per wave instruction
+                int32_t *drow = args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    atomicAdd(drow + e * 64 + lane, img[r * IMG_PITCH + e * 64 + lane]);
+                continue;
+            }
             const v4i part4 = *(const v4i *)(img + r * IMG_PITCH + lane * 4);
             v4i *dst = (v4i *)(args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0 + lane * 4);
             v4i cur = *dst;
@@ -277,7 +290,22 @@ static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&count_i8_dma_kernel<WR, NSTAGE>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3((unsigned)grid), dim3(T::NT), T::LDS_BYTES, s, a);
+    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // (at least 512 k each), which add their parts to R with integer atomics
+    CountArgs b = a;
+    int splits = 1;
+    b.kchunk = a.K;
+    const int64_t waves = tiles_m * tiles_n * T::NW;
+    if (waves < 2048 && a.K >= 1024) {
+        int64_t want = (2048 + waves - 1) / waves;
+        if (want > a.K / 512) want = a.K / 512;
+        if (want > 1024) want = 1024;
+        const int64_t chunk = ((a.K + want - 1) / want + DM_BK - 1) / DM_BK * DM_BK;
+        b.kchunk = (int)chunk;
+        splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3((unsigned)grid, (unsigned)splits), dim3(T::NT),
+                       T::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 

@@ -191,6 +191,26 @@ def test_count_i8_bit_exact_ragged(am, shape):
         assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
 
 
+@pytest.mark.parametrize("shape", [None, 1, 3, 5, 6, 7])
+def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
+    """Tiny M x N with a long K: K is split over several workgroups per tile, which add their parts
+    to R with integer atomics (exact in any order), in the streamed and the register-staged kernels."""
+    for idx, (M, N, K) in enumerate([(128, 256, 8192), (256, 256, 4096), (100, 300, 5000), (256, 512, 3000)]):
+        g = np.random.Generator(np.random.PCG64(350 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        dR = dev(R_in)
+        print("i8 split-K case", shape, M, N, K, flush=True)
+        if shape is None:
+            am.amulet_count_i8(dev(A), dev(B), dR)
+        else:
+            am.amulet_count_i8_shape(shape, dev(A), dev(B), dR)
+        torch.cuda.synchronize()
+        assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
+
+
 def test_count_i8_strided(am):
     M, N, K = 50, 130, 75
     A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)
