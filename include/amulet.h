@@ -26,6 +26,11 @@
  *  - Return value: AMULET_OK (0) or a negative amulet_status_t.  Nothing is
  *    enqueued when an argument error is returned.  M == 0, N == 0 or K == 0 is
  *    a successful no-op (R unchanged).
+ *  - The k-sum is formed in an order the library chooses (the paper's loop
+ *    is order-free, Sec. 4.1).  Problems whose M x N gives too few tiles to
+ *    fill the chip have K split over several workgroups that add their
+ *    parts to R atomically: floating-point results of such calls may differ
+ *    in the last bits from run to run (integer results never do).
  *  - A or B holding NaN or +-inf gives unspecified results; +-inf in thres is
  *    supported (thres = +inf never triggers, -inf always does).
  */
