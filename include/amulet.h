@@ -30,7 +30,10 @@
  *    is order-free, Sec. 4.1).  Problems whose M x N gives too few tiles to
  *    fill the chip have K split over several workgroups that add their
  *    parts to R atomically: floating-point results of such calls may differ
- *    in the last bits from run to run (integer results never do).
+ *    in the last bits from run to run (integer results never do).  R must be
+ *    ordinary device memory (hipMalloc or a framework's device allocator):
+ *    the hardware atomics used there are not defined on fine-grained or
+ *    host-mapped memory.
  *  - A or B holding NaN or +-inf gives unspecified results; +-inf in thres is
  *    supported (thres = +inf never triggers, -inf always does).
  */
