@@ -39,7 +39,15 @@ __device__ __forceinline__ v4i load16_i8(const int8_t *src, bool vec, int n_vali
 {
     v4i v = {0, 0, 0, 0};
     if (n_valid <= 0) return v;
-    if (vec && n_valid >= 16) return *(const v4i *)src;
+    if (n_valid >= 16) {
+        // 16 whole bytes in range: one vector load either way.  The second form tells the
+        // compiler nothing about alignment; the target's global loads accept any address,
+        // so it still becomes one 16-byte load (slower than an aligned one, far faster
+        // than sixteen byte loads).
+        if (vec) return *(const v4i *)src;
+        typedef v4i v4i_anyaddr __attribute__((aligned(1)));
+        return *(const v4i_anyaddr *)src;
+    }
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     for (int t = 0; t < 16; ++t)
         if (t < n_valid) w[t >> 2] |= (uint32_t)(uint8_t)src[t] << (8 * (t & 3));
@@ -300,11 +308,33 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
     case 3: return launch_mfma<2, 2, 2, 4, 4, 64>(a, s);   // 128 x 256 tile, 8 waves of 64 x 64
     case 4: return launch_mfma<2, 1, 2, 4, 4, 128>(a, s);  // 128 x 128 tile, 8 waves of 64 x 32, 128-byte stages
     case 5: return launch_mfma<2, 2, 4, 4, 4, 64>(a, s);   // 256 x 256 tile, 16 waves of 64 x 64
-    case 6:   // 128 x 256 tile streamed HBM -> LDS directly; needs a fully interior, aligned problem
-        return count_i8_dma_eligible(a, 2) ? launch_count_i8_dma(a, 2, s) : launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
-    case 7:   // 256 x 256 tile, 16 waves, streamed HBM -> LDS directly; same condition, else as shape 6
-        if (count_i8_dma_eligible(a, 4)) return launch_count_i8_dma(a, 4, s);
-        return count_i8_dma_eligible(a, 2) ? launch_count_i8_dma(a, 2, s) : launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
+    case 6:   // 128 x 256 tile streamed HBM -> LDS directly
+    case 7: { // 256 x 256 tile, 16 waves, streamed HBM -> LDS directly
+        // The streamed kernels take whole tiles of aligned operands with K % 64 == 0.  A problem
+        // with ragged M or N is cut into its interior (whole tiles, streamed) and up to two edge
+        // strips (bottom rows, right-hand columns) that the register-staged kernel of the same
+        // tile handles: the three launches write disjoint parts of R.
+        const bool aligned = a.vecA && a.vecB && a.vecR && a.K % 64 == 0;
+        int wr = (shape == 7) ? 4 : 2;
+        if (wr == 4 && a.M < 256) wr = 2;
+        const int bm = 64 * wr;
+        const int Mi = aligned ? a.M - a.M % bm : 0, Ni = aligned ? a.N - a.N % 256 : 0;
+        if (Mi == 0 || Ni == 0) return launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
+        CountArgs in = a;
+        in.M = Mi; in.N = Ni;
+        hipError_t e = launch_count_i8_dma(in, wr, s);
+        if (e == hipSuccess && a.M > Mi) {          // bottom strip: rows Mi.., all columns
+            CountArgs bot = a;
+            bot.A = a.A + (int64_t)Mi * a.lda; bot.R = a.R + (int64_t)Mi * a.ldr; bot.M = a.M - Mi;
+            e = launch_mfma<2, 2, 2, 4, 4, 64>(bot, s);
+        }
+        if (e == hipSuccess && a.N > Ni) {          // right-hand strip: rows 0..Mi, columns Ni..
+            CountArgs right = a;
+            right.B = a.B + Ni; right.R = a.R + Ni; right.M = Mi; right.N = a.N - Ni;
+            e = launch_mfma<2, 2, 2, 4, 4, 64>(right, s);
+        }
+        return e;
+    }
     default:
         return hipErrorInvalidValue;
     }

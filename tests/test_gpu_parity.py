@@ -176,7 +176,7 @@ def test_empty_dimensions_are_noops(am):
 def test_count_i8_bit_exact_ragged(am, shape):
     for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (1, 1, 1), (257, 129, 1000), (64, 64, 64),
                                        (300, 272, 128), (512, 256, 192), (256, 512, 64), (384, 768, 448),
-                                       (768, 512, 320)]):
+                                       (768, 512, 320), (1000, 1300, 256), (513, 257, 64)]):
         g = np.random.Generator(np.random.PCG64(300 + idx))
         A = g.integers(-128, 128, (M, K)).astype(np.int8)
         B = g.integers(-128, 128, (K, N)).astype(np.int8)
