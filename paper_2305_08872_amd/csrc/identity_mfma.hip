@@ -33,6 +33,7 @@
 namespace amulet {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef f4 f4_any __attribute__((aligned(4)));   // four floats at any float address
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
@@ -133,8 +134,8 @@ identity_mfma_kernel(const MmlikeArgs args)
                 f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (r < n_lines) {
                     const float *src = base + (int64_t)r * ld + k;
-                    if (vec && k + 3 < K) {
-                        v = *(const f4 *)src;
+                    if (k + 3 < K) {
+                        v = *(const f4_any *)src;   // one 16-byte load whether or not the row is aligned
                     } else {
                         if (k + 0 < K) v.x = src[0];
                         if (k + 1 < K) v.y = src[1];
@@ -154,8 +155,8 @@ identity_mfma_kernel(const MmlikeArgs args)
                 f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (k < K) {
                     const float *src = base + (int64_t)k * ld + c;
-                    if (vec && c + 3 < n_lines) {
-                        v = *(const f4 *)src;
+                    if (c + 3 < n_lines) {
+                        v = *(const f4_any *)src;   // one 16-byte load whether or not the row is aligned
                     } else {
                         if (c + 0 < n_lines) v.x = src[0];
                         if (c + 1 < n_lines) v.y = src[1];

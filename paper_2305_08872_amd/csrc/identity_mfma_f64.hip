@@ -29,6 +29,7 @@
 namespace amulet {
 
 typedef double d2 __attribute__((ext_vector_type(2)));
+typedef d2 d2_any __attribute__((aligned(8)));   // two doubles at any double address
 typedef double d4 __attribute__((ext_vector_type(4)));
 
 constexpr int DI_BM = 128, DI_BN = 128, DI_BK = 16, DI_NT = 512;
@@ -95,8 +96,8 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
                 d2 v = {0.0, 0.0};
                 if (r < n_lines) {
                     const double *src = base + (int64_t)r * ld + k;
-                    if (vec && k + 1 < K) {
-                        v = *(const d2 *)src;
+                    if (k + 1 < K) {
+                        v = *(const d2_any *)src;   // one 16-byte load at any double address
                     } else {
                         if (k + 0 < K) v.x = src[0];
                         if (k + 1 < K) v.y = src[1];
@@ -114,8 +115,8 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
                 d2 v = {0.0, 0.0};
                 if (k < K) {
                     const double *src = base + (int64_t)k * ld + c;
-                    if (vec && c + 1 < n_lines) {
-                        v = *(const d2 *)src;
+                    if (c + 1 < n_lines) {
+                        v = *(const d2_any *)src;
                     } else {
                         if (c + 0 < n_lines) v.x = src[0];
                         if (c + 1 < n_lines) v.y = src[1];

@@ -15,6 +15,9 @@
 namespace amulet {
 
 typedef double d2 __attribute__((ext_vector_type(2)));
+// the same two doubles at any double address: still one 16-byte access (global accesses
+// take any address on this target), used where rows are not 16-byte aligned
+typedef d2 d2_any __attribute__((aligned(8)));
 typedef d2 d2_a8 __attribute__((aligned(8)));
 typedef const __attribute__((address_space(4))) double *sptr_d;     // read through the scalar cache
 typedef const __attribute__((address_space(4))) d2_a8 *sptr_d2;
@@ -192,7 +195,6 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int tcol = threadIdx.x % D_BN;
     const int tk = (threadIdx.x / D_BN) * 8;
     const double *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
-    const bool vecBt = TRANS && args.vecBt != 0;
     auto load_tile = [&](int krows) {
         if (transB) {
             const bool colok = col0 + tcol < N;
@@ -202,8 +204,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 const int kk = tk + 2 * it;
                 if (colok) {
                     const double *src = btsrc + 2 * it;
-                    if (vecBt && kk + 1 < krows) {
-                        v = *(const d2 *)src;
+                    if (kk + 1 < krows) {
+                        v = *(const d2_any *)src;
                     } else {
                         if (kk + 0 < krows) v.x = src[0];
                         if (kk + 1 < krows) v.y = src[1];
@@ -221,8 +223,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 d2 v = {0.0, 0.0};
                 if (srow + it * ROWS_PER_PASS < krows) {
                     const double *src = bsrc + it * pass_stride;
-                    if (scol + 0 < N) v.x = src[0];
-                    if (scol + 1 < N) v.y = src[1];
+                    if (scol + 1 < N) v = *(const d2_any *)src;
+                    else if (scol < N) v.x = src[0];
                 }
                 stage[it] = v;
             }
@@ -339,9 +341,12 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
             d2 o = *(d2 *)(dst_row + col);
             o.x += v0; o.y += v1;
             *(d2 *)(dst_row + col) = o;
-        } else {
-            if (col + 0 < N) dst_row[col + 0] += v0;
-            if (col + 1 < N) dst_row[col + 1] += v1;
+        } else if (col + 1 < N) {
+            d2 o = *(d2_any *)(dst_row + col);
+            o.x += v0; o.y += v1;
+            *(d2_any *)(dst_row + col) = o;
+        } else if (col < N) {
+            dst_row[col] += v0;
         }
     }
 }

@@ -41,6 +41,9 @@ namespace amulet {
 constexpr int FLUSH_K = 64;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+// the same four floats at any float address: still one 16-byte access (global accesses take
+// any address on this target), used where rows are not 16-byte aligned
+typedef f4 f4_any __attribute__((aligned(4)));
 typedef const __attribute__((address_space(4))) float *sptr_f;      // read through the scalar cache
 
 template <int TASK> struct AccT { typedef float type; };
@@ -238,8 +241,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 const int kk = tk + 4 * it;
                 if (colok) {
                     const float *src = btsrc + 4 * it;
-                    if (VEC && kk + 3 < krows) {
-                        v = *(const f4 *)src;
+                    if (kk + 3 < krows) {
+                        v = *(const f4_any *)src;
                     } else {
                         if (kk + 0 < krows) v.x = src[0];
                         if (kk + 1 < krows) v.y = src[1];
@@ -261,10 +264,13 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (srow + it * ROWS_PER_PASS < krows) {
                     const float *src = bsrc + it * pass_stride;
-                    if (scol + 0 < N) v.x = src[0];
-                    if (scol + 1 < N) v.y = src[1];
-                    if (scol + 2 < N) v.z = src[2];
-                    if (scol + 3 < N) v.w = src[3];
+                    if (scol + 3 < N) {
+                        v = *(const f4_any *)src;
+                    } else {
+                        if (scol + 0 < N) v.x = src[0];
+                        if (scol + 1 < N) v.y = src[1];
+                        if (scol + 2 < N) v.z = src[2];
+                    }
                 }
                 stage[it] = v;
             }
@@ -451,6 +457,10 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 f4 o = *(f4 *)(dst_row + col);
                 o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
                 *(f4 *)(dst_row + col) = o;
+            } else if (col + 3 < N) {
+                f4 o = *(f4_any *)(dst_row + col);
+                o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+                *(f4_any *)(dst_row + col) = o;
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
