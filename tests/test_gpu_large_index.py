@@ -1,0 +1,112 @@
+"""GPU parity where the output has more than 2^31 elements, so that an element offset
+i * ldr + j no longer fits 32 bits: every kernel family must index R (and the wide operand)
+in 64 bits.  K is short, so the launches are quick; the oracle checks sampled whole rows,
+among them the last ones, whose offsets are the largest."""
+import numpy as np
+import pytest
+
+import oracle
+from parity import assert_parity_f32, worst_ratio
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+M, N, K = 46400, 46400, 24            # M * N = 2.153e9 > 2^31 = 2.147e9
+ROWS = np.array([0, 1, 255, 256, M // 2 + 3, 46336, M - 3, M - 2, M - 1])
+
+
+@pytest.fixture(scope="module")
+def am():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2305_08872_amd as am
+    am.load_library()
+    return am
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def sampled_rows(dR):
+    return dR[torch.from_numpy(ROWS).cuda()].cpu().numpy()
+
+
+def test_offsets_really_exceed_32_bits():
+    assert M * N > 2 ** 31 and (ROWS[-1] * N + N - 1) > 2 ** 31
+
+
+@pytest.mark.parametrize("task", [0, 1, 2, 3])
+def test_f32_tasks_beyond_2_31_outputs(am, task):
+    g = np.random.Generator(np.random.PCG64(9100 + task))
+    A = (g.standard_normal((M, K)) * 2).astype(np.float32)
+    B = (g.standard_normal((K, N)) * 2).astype(np.float32)
+    thres = (g.standard_normal(N) * 2).astype(np.float32)
+    dis = g.uniform(0, 1, N).astype(np.float32)
+    params = {0: None, 1: np.stack([thres, dis]), 2: thres[None, :], 3: thres[None, :]}[task]
+    print("f32 task", task, M, N, K, flush=True)
+    dR = torch.full((M, N), 1.5, dtype=torch.float32, device="cuda")
+    am.amulet_mmlike_f32(task, dev(A), dev(B), dev(params) if params is not None else None, dR)
+    torch.cuda.synchronize()
+    R = sampled_rows(dR)
+    del dR
+    R_in = np.full((len(ROWS), N), 1.5, np.float32)
+    R_ref, ab, _ = oracle.mmlike_f32(task, A[ROWS], B, params, R_in)
+    if task == 3:
+        assert np.array_equal(R, R_ref)
+    else:
+        assert_parity_f32(R, R_ref, ab, R_in, what="f32 task %d, 2^31+ outputs" % task)
+
+
+@pytest.mark.parametrize("task", [0, 1])
+def test_f64_tasks_beyond_2_31_outputs(am, task):
+    g = np.random.Generator(np.random.PCG64(9200 + task))
+    A = g.standard_normal((M, K)) * 2
+    B = g.standard_normal((K, N)) * 2
+    thres = g.standard_normal(N) * 2
+    dis = g.uniform(0, 1, N)
+    print("f64 task", task, M, N, K, flush=True)
+    dR = torch.full((M, N), -2.0, dtype=torch.float64, device="cuda")
+    am.amulet_mmlike_f64(task, dev(A), dev(B), dev(thres) if task else None, dev(dis) if task == 1 else None, dR)
+    torch.cuda.synchronize()
+    R = sampled_rows(dR)
+    del dR
+    R_in = np.full((len(ROWS), N), -2.0)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, A[ROWS], B, thres if task else None,
+                                            dis if task == 1 else None, R_in)
+    assert worst_ratio(R, R_ref, ab, R_in) <= 1e-12
+
+
+def test_count_i8_beyond_2_31_outputs(am):
+    g = np.random.Generator(np.random.PCG64(9300))
+    Kc = 64                                   # whole 64-byte stages: the streamed kernel takes the interior
+    A = g.integers(-128, 128, (M, Kc)).astype(np.int8)
+    B = g.integers(-128, 128, (Kc, N)).astype(np.int8)
+    print("count_i8", M, N, Kc, flush=True)
+    dR = torch.full((M, N), 7, dtype=torch.int32, device="cuda")
+    am.amulet_count_i8(dev(A), dev(B), dR)
+    torch.cuda.synchronize()
+    R = sampled_rows(dR)
+    del dR
+    R_ref, _ = oracle.count_i8(A[ROWS], B, np.full((len(ROWS), N), 7, np.int32))
+    assert np.array_equal(R, R_ref)
+
+
+def test_elementwise_threshold_and_transposed_operands_beyond_2_31(am):
+    """thres[i][j] is itself an M x N array (offsets past 2^31), and A stored K x M makes the
+    row index the fast one of a wide operand."""
+    g = np.random.Generator(np.random.PCG64(9400))
+    At = (g.standard_normal((K, M)) * 2).astype(np.float32)      # A stored transposed
+    Bt = (g.standard_normal((N, K)) * 2).astype(np.float32)      # B stored transposed
+    print("f32 general boost, thres[i][j], both transposed", M, N, K, flush=True)
+    dT = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+    dR = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    am.amulet_mmlike_f32_general(2, dev(At), dev(Bt), dT, None, dR, thres_form=3, trans_a=True, trans_b=True)
+    torch.cuda.synchronize()
+    R = sampled_rows(dR)
+    del dR, dT
+    R_ref, ab, _ = oracle.mmlike_f32_general(2, np.ascontiguousarray(At[:, ROWS]), Bt,
+                                            np.full((len(ROWS), N), 0.25, np.float32), None,
+                                            np.zeros((len(ROWS), N), np.float32),
+                                            thres_form=3, trans_a=True, trans_b=True)
+    assert_parity_f32(R, R_ref, ab, None, what="general boost, 2^31+ outputs")
