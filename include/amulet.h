@@ -40,6 +40,7 @@
 #ifndef AMULET_H
 #define AMULET_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -61,7 +62,8 @@ typedef enum {
     AMULET_ERR_LD = -4,     /* a leading dimension is smaller than the row    */
     AMULET_ERR_LAUNCH = -5, /* HIP reported an error at launch                */
     AMULET_ERR_SHAPE = -6,  /* unknown tile-shape id, or one the task lacks   */
-    AMULET_ERR_RANGE = -7   /* a dimension exceeds what the kernels index     */
+    AMULET_ERR_RANGE = -7,  /* a dimension exceeds what the kernels index     */
+    AMULET_ERR_WORKSPACE = -8 /* the workspace lent to the call is too small   */
 } amulet_status_t;
 
 /*
@@ -168,6 +170,66 @@ int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b
                               const double *dis,
                               double *R, int64_t ldr,
                               void *stream);
+
+/*
+ * Packing (Sec. 3.1 and the "with packing" series of Sec. 6): an operand is copied
+ * once into storage whose layout suits the kernels' access order, at the price of
+ * memory the caller must agree to spend.  The kernels of this library read the
+ * caller's row-major operands in place at full speed with one exception, which
+ * is what the packed copy removes: when the row pitch of A in bytes is a multiple
+ * of 32 KiB and at least 64 KiB (a long power-of-two K), the rows a workgroup of
+ * the vector-ALU kernels reads at one k fall into the same cache sets and memory
+ * channel, and those kernels run at 45-95 % of their rate.  The packed copy
+ * spaces its rows by amulet_packed_ld(), which never collides.
+ *
+ *   amulet_pitch_collides   1 if rows `ld` elements of `elem_bytes` (1, 4, 8) apart
+ *                           collide in that way, else 0
+ *   amulet_packed_ld        pitch, in elements, for a packed copy of rows of `cols`
+ *                           elements (>= cols; 0 for invalid arguments)
+ *   amulet_pack             dst[r*ld_dst + c] = src[r*ld_src + c] for r < rows,
+ *                           c < cols; device pointers, dst and src must not overlap;
+ *                           enqueued on `stream`; AMULET_ERR_DIM for an element size
+ *                           other than 1, 4, 8 or a negative extent, AMULET_ERR_LD
+ *                           for a pitch below cols, AMULET_ERR_NULL
+ */
+int amulet_pitch_collides(int64_t ld, int elem_bytes);
+int64_t amulet_packed_ld(int64_t cols, int elem_bytes);
+int amulet_pack(int elem_bytes, int64_t rows, int64_t cols,
+                const void *src, int64_t ld_src,
+                void *dst, int64_t ld_dst, void *stream);
+
+/*
+ * The general calls with packing allowed (the user-granted "auto-packing" of
+ * Sec. 3.1).  `workspace` is device memory the caller lends for the duration of
+ * the call's work on `stream` (the library never allocates in a compute call);
+ * amulet_autopack_workspace_bytes(elem_bytes, M, K) is the size a call may need.
+ * When A is row-major, its pitch collides (above), the task runs on the vector
+ * ALUs and N >= 128, A is first copied to the workspace with a packed pitch
+ * (one more kernel on the same stream) and the task reads the copy; otherwise,
+ * or when `workspace` is NULL, the call is the plain general call.  Results are
+ * those of the plain call (the same kernels on the same values).
+ * AMULET_ERR_WORKSPACE if the call wants to pack and `workspace_bytes` is too
+ * small; other errors as for the general calls.
+ */
+size_t amulet_autopack_workspace_bytes(int elem_bytes, int64_t M, int64_t K);
+int amulet_mmlike_f32_autopack(int task, int thres_form, int trans_a, int trans_b,
+                               int64_t M, int64_t N, int64_t K,
+                               const float *A, int64_t lda,
+                               const float *B, int64_t ldb,
+                               const float *thres, int64_t ldt,
+                               const float *dis,
+                               float *R, int64_t ldr,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream);
+int amulet_mmlike_f64_autopack(int task, int thres_form, int trans_a, int trans_b,
+                               int64_t M, int64_t N, int64_t K,
+                               const double *A, int64_t lda,
+                               const double *B, int64_t ldb,
+                               const double *thres, int64_t ldt,
+                               const double *dis,
+                               double *R, int64_t ldr,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream);
 
 /*
  * Natural-join count as a matrix product (the join-as-matmul translation cited

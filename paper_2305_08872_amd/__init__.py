@@ -26,7 +26,13 @@ from .binding import (  # noqa: F401
     amulet_mmlike_f32_adaptive,
     amulet_mmlike_f32_general,
     amulet_mmlike_f32_shape,
+    amulet_mmlike_f32_autopack,
     amulet_mmlike_f64,
+    amulet_mmlike_f64_autopack,
+    amulet_autopack_workspace_bytes,
+    amulet_pack,
+    amulet_packed_ld,
+    amulet_pitch_collides,
     amulet_probe_mfma_i8,
     amulet_probe_valu,
     amulet_register_demand,

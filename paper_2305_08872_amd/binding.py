@@ -66,6 +66,19 @@ def load_library():
                                                ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.amulet_count_i8.restype = i32
     lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.amulet_pitch_collides.restype = i32
+    lib.amulet_pitch_collides.argtypes = [i64, i32]
+    lib.amulet_packed_ld.restype = i64
+    lib.amulet_packed_ld.argtypes = [i64, i32]
+    lib.amulet_pack.restype = i32
+    lib.amulet_pack.argtypes = [i32, i64, i64, vp, i64, vp, i64, vp]
+    lib.amulet_autopack_workspace_bytes.restype = ctypes.c_size_t
+    lib.amulet_autopack_workspace_bytes.argtypes = [i32, i64, i64]
+    lib.amulet_mmlike_f32_autopack.restype = i32
+    lib.amulet_mmlike_f32_autopack.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp,
+                                               i64, vp, ctypes.c_size_t, vp]
+    lib.amulet_mmlike_f64_autopack.restype = i32
+    lib.amulet_mmlike_f64_autopack.argtypes = lib.amulet_mmlike_f32_autopack.argtypes
     lib.amulet_count_i8_shape.restype = i32
     lib.amulet_count_i8_shape.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_tune.restype = i32
@@ -182,24 +195,23 @@ def amulet_mmlike_f32_shape(task: int, shape: int, A, B, params, R, stream=None)
            "amulet_mmlike_f32_shape")
 
 
-def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
-                              trans_a: bool = False, trans_b: bool = False, shape: int = -1, stream=None):
-    """General test-query form: A may be stored K x M (trans_a), B N x K (trans_b); `thres` is a
-    device tensor of N, M, 1 or M x N values according to `thres_form`; `dis` has N values."""
-    lib = load_library()
-    pa, ra, ca, lda = _mat(A, "torch.float32", "A")
-    pb, rb, cb, ldb = _mat(B, "torch.float32", "B")
-    pr, M, N, ldr = _mat(R, "torch.float32", "R")
+def _general_args(dtype_name: str, task: int, A, B, thres, dis, R, thres_form: int, trans_a: bool,
+                  trans_b: bool):
+    """Pointers, sizes and pitches of a general-form call, in the order the C entry points take
+    them from M on: (M, N, K, A, lda, B, ldb, thres, ldt, dis, R, ldr)."""
+    pa, ra, ca, lda = _mat(A, dtype_name, "A")
+    pb, rb, cb, ldb = _mat(B, dtype_name, "B")
+    pr, M, N, ldr = _mat(R, dtype_name, "R")
     Ma, K = (ca, ra) if trans_a else (ra, ca)
     K2, Nb = (cb, rb) if trans_b else (rb, cb)
     if K2 != K or Ma != M or Nb != N:
         raise ValueError("shape mismatch between A, B and R")
     pt, ldt = None, 0
     if task != AMULET_IDENTITY:
-        if thres is None or not thres.is_cuda or str(thres.dtype) != "torch.float32":
-            raise ValueError("thres must be an fp32 device tensor")
+        if thres is None or not thres.is_cuda or str(thres.dtype) != dtype_name:
+            raise ValueError("thres must be a device tensor of the operands' type")
         if thres_form == AMULET_THRES_ELEM:
-            pt, tm, tn, ldt = _mat(thres, "torch.float32", "thres")
+            pt, tm, tn, ldt = _mat(thres, dtype_name, "thres")
             if (tm, tn) != (M, N):
                 raise ValueError("thres[i][j] must be M x N")
         else:
@@ -209,13 +221,21 @@ def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int
             pt = thres.data_ptr()
     pd = None
     if task == AMULET_DISCOUNT:
-        if dis is None or not dis.is_cuda or str(dis.dtype) != "torch.float32" or not dis.is_contiguous() \
+        if dis is None or not dis.is_cuda or str(dis.dtype) != dtype_name or not dis.is_contiguous() \
                 or dis.numel() != N:
-            raise ValueError("dis must hold N contiguous fp32 values on the device")
+            raise ValueError("dis must hold N contiguous values of the operands' type on the device")
         pd = dis.data_ptr()
-    _check(lib.amulet_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), shape, M, N, K,
-                                         pa, lda, pb, ldb, pt, ldt, pd, pr, ldr, _stream_ptr(stream)),
-           "amulet_mmlike_f32_general")
+    return M, N, K, pa, lda, pb, ldb, pt, ldt, pd, pr, ldr
+
+
+def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
+                              trans_a: bool = False, trans_b: bool = False, shape: int = -1, stream=None):
+    """General test-query form: A may be stored K x M (trans_a), B N x K (trans_b); `thres` is a
+    device tensor of N, M, 1 or M x N values according to `thres_form`; `dis` has N values."""
+    lib = load_library()
+    args = _general_args("torch.float32", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
+    _check(lib.amulet_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), shape, *args,
+                                         _stream_ptr(stream)), "amulet_mmlike_f32_general")
 
 
 def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
@@ -224,35 +244,68 @@ def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULE
     (trans_a), B N x K (trans_b); `thres` holds N, M, 1 or M x N values according to
     `thres_form`; `dis` has N values."""
     lib = load_library()
-    f64 = "torch.float64"
-    pa, ra, ca, lda = _mat(A, f64, "A")
-    pb, rb, cb, ldb = _mat(B, f64, "B")
-    pr, M, N, ldr = _mat(R, f64, "R")
-    Ma, K = (ca, ra) if trans_a else (ra, ca)
-    K2, Nb = (cb, rb) if trans_b else (rb, cb)
-    if K2 != K or Ma != M or Nb != N:
-        raise ValueError("shape mismatch between A, B and R")
-    pt, ldt = None, 0
-    if task != AMULET_IDENTITY:
-        if thres is None or not thres.is_cuda or str(thres.dtype) != f64:
-            raise ValueError("thres must be an fp64 device tensor")
-        if thres_form == AMULET_THRES_ELEM:
-            pt, tm, tn, ldt = _mat(thres, f64, "thres")
-            if (tm, tn) != (M, N):
-                raise ValueError("thres[i][j] must be M x N")
-        else:
-            want = {AMULET_THRES_COL: N, AMULET_THRES_ROW: M, AMULET_THRES_CONST: 1}[thres_form]
-            if not thres.is_contiguous() or thres.numel() != want:
-                raise ValueError("thres must hold %d contiguous values" % want)
-            pt = thres.data_ptr()
-    pd = None
-    if task == AMULET_DISCOUNT:
-        if dis is None or not dis.is_cuda or str(dis.dtype) != f64 or not dis.is_contiguous() \
-                or dis.numel() != N:
-            raise ValueError("dis must hold N contiguous fp64 values on the device")
-        pd = dis.data_ptr()
-    _check(lib.amulet_mmlike_f64_general(task, thres_form, int(trans_a), int(trans_b), M, N, K, pa, lda, pb, ldb,
-                                         pt, ldt, pd, pr, ldr, _stream_ptr(stream)), "amulet_mmlike_f64_general")
+    args = _general_args("torch.float64", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
+    _check(lib.amulet_mmlike_f64_general(task, thres_form, int(trans_a), int(trans_b), *args,
+                                         _stream_ptr(stream)), "amulet_mmlike_f64_general")
+
+
+def amulet_pitch_collides(ld: int, elem_bytes: int) -> bool:
+    """True if rows `ld` elements apart fall into the same cache sets and memory channel."""
+    return bool(load_library().amulet_pitch_collides(ld, elem_bytes))
+
+
+def amulet_packed_ld(cols: int, elem_bytes: int) -> int:
+    """Row pitch, in elements, of a packed copy of rows of `cols` elements."""
+    return int(load_library().amulet_packed_ld(cols, elem_bytes))
+
+
+def amulet_autopack_workspace_bytes(elem_bytes: int, M: int, K: int) -> int:
+    """Bytes of workspace an auto-packing call on an M x K operand A may need."""
+    return int(load_library().amulet_autopack_workspace_bytes(elem_bytes, M, K))
+
+
+def amulet_pack(src, dst, stream=None):
+    """Copy the 2-D device tensor `src` into `dst` (same shape and element size, any row
+    pitches); enqueues and returns."""
+    lib = load_library()
+    if not (src.is_cuda and dst.is_cuda) or src.dim() != 2 or dst.shape != src.shape or \
+            src.element_size() != dst.element_size():
+        raise ValueError("src and dst must be 2-D device tensors of one shape and element size")
+    if (src.shape[1] > 1 and src.stride(1) != 1) or (dst.shape[1] > 1 and dst.stride(1) != 1):
+        raise ValueError("rows must be contiguous")
+    rows, cols = int(src.shape[0]), int(src.shape[1])
+    _check(lib.amulet_pack(src.element_size(), rows, cols, src.data_ptr(), int(src.stride(0)) if rows > 1 else cols,
+                           dst.data_ptr(), int(dst.stride(0)) if rows > 1 else cols, _stream_ptr(stream)),
+           "amulet_pack")
+
+
+def _autopack(fn_name: str, dtype_name: str, task, A, B, thres, dis, R, workspace, thres_form, trans_a, trans_b,
+              stream):
+    lib = load_library()
+    args = _general_args(dtype_name, task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
+    pw, nw = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous device tensor")
+        pw, nw = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(getattr(lib, fn_name)(task, thres_form, int(trans_a), int(trans_b), *args, pw, nw,
+                                 _stream_ptr(stream)), fn_name)
+
+
+def amulet_mmlike_f32_autopack(task: int, A, B, thres, dis, R, workspace, *, thres_form: int = AMULET_THRES_COL,
+                               trans_a: bool = False, trans_b: bool = False, stream=None):
+    """amulet_mmlike_f32_general with packing allowed: `workspace` (any contiguous device tensor
+    of at least amulet_autopack_workspace_bytes(4, M, K) bytes, or None) may receive a packed
+    copy of A that the task then reads."""
+    _autopack("amulet_mmlike_f32_autopack", "torch.float32", task, A, B, thres, dis, R, workspace, thres_form,
+              trans_a, trans_b, stream)
+
+
+def amulet_mmlike_f64_autopack(task: int, A, B, thres, dis, R, workspace, *, thres_form: int = AMULET_THRES_COL,
+                               trans_a: bool = False, trans_b: bool = False, stream=None):
+    """amulet_mmlike_f64 with packing allowed (see amulet_mmlike_f32_autopack; 8-byte elements)."""
+    _autopack("amulet_mmlike_f64_autopack", "torch.float64", task, A, B, thres, dis, R, workspace, thres_form,
+              trans_a, trans_b, stream)
 
 
 def amulet_count_i8(A, B, R, stream=None):

@@ -378,6 +378,94 @@ int amulet_mmlike_f32(int task, int64_t M, int64_t N, int64_t K, const float *A,
                                      params ? params + N : nullptr, R, ldr, stream);
 }
 
+// ---- packing (paper Sec. 3.1) ---------------------------------------------------------------
+// Measured on the vector-ALU kernels (4096 x 4096 outputs, K = 4096 of each row used): A row pitch
+// 48, 80, 96 KiB 31.7 TFLOP/s; 64 KiB 30.0; 128 KiB 27.0; 192 KiB 29.4; 256 and 512 KiB 20;
+// any of these plus 128 bytes 31.7.  With the whole row used (K = 65536 fp32) 14 against 32.
+int amulet_pitch_collides(int64_t ld, int elem_bytes)
+{
+    if (ld <= 0 || (elem_bytes != 1 && elem_bytes != 4 && elem_bytes != 8)) return 0;
+    const int64_t pitch = ld * elem_bytes;
+    return (pitch >= 65536 && pitch % 32768 == 0) ? 1 : 0;
+}
+
+int64_t amulet_packed_ld(int64_t cols, int elem_bytes)
+{
+    if (cols <= 0 || (elem_bytes != 1 && elem_bytes != 4 && elem_bytes != 8)) return 0;
+    int64_t pitch = (cols * elem_bytes + 127) / 128 * 128;   // whole 128-byte lines
+    if (pitch % 4096 == 0) pitch += 128;                      // successive rows start 128 bytes apart in a page
+    return pitch / elem_bytes;
+}
+
+int amulet_pack(int elem_bytes, int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst,
+                int64_t ld_dst, void *stream)
+{
+    if (elem_bytes != 1 && elem_bytes != 4 && elem_bytes != 8) return AMULET_ERR_DIM;
+    if (rows < 0 || cols < 0) return AMULET_ERR_DIM;
+    if (rows == 0 || cols == 0) return AMULET_OK;
+    if (!src || !dst) return AMULET_ERR_NULL;
+    if (ld_src < cols || ld_dst < cols) return AMULET_ERR_LD;
+    const hipError_t e = launch_pack(elem_bytes, rows, cols, src, ld_src, dst, ld_dst, (hipStream_t)stream);
+    g_last_hip_error = e;
+    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+// Would a vector-ALU task with these operands run on a packed copy of A?  Only a row-major A is
+// read row by row at one k (a transposed A is read along its rows), only the vector-ALU kernels
+// read it through the scalar path that suffers, and a copy pays only when A is read many times.
+static bool autopack_wanted(bool valu_task, int trans_a, int64_t N, int64_t lda, int elem_bytes)
+{
+    return valu_task && !trans_a && N >= 128 && amulet_pitch_collides(lda, elem_bytes);
+}
+
+size_t amulet_autopack_workspace_bytes(int elem_bytes, int64_t M, int64_t K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    const int64_t ld = amulet_packed_ld(K, elem_bytes);
+    return ld > 0 ? (size_t)M * (size_t)ld * (size_t)elem_bytes : 0;
+}
+
+int amulet_mmlike_f32_autopack(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
+                               int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                               const float *thres, int64_t ldt, const float *dis, float *R, int64_t ldr,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    const MmlikeCall c = {task, thres_form, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb,
+                          thres, ldt, dis, R, ldr};
+    const int rc = check_mmlike(c);
+    if (rc < 0) return rc;
+    if (rc == 1) return AMULET_OK;
+    if (workspace && autopack_wanted(task != TASK_IDENTITY, trans_a, N, lda, 4)) {
+        if (workspace_bytes < amulet_autopack_workspace_bytes(4, M, K)) return AMULET_ERR_WORKSPACE;
+        const int64_t ld = amulet_packed_ld(K, 4);
+        const int prc = amulet_pack(4, M, K, A, lda, workspace, ld, stream);
+        if (prc != AMULET_OK) return prc;
+        A = (const float *)workspace;
+        lda = ld;
+    }
+    return amulet_mmlike_f32_general(task, thres_form, trans_a, trans_b, -1, M, N, K, A, lda, B, ldb, thres,
+                                     ldt, dis, R, ldr, stream);
+}
+
+int amulet_mmlike_f64_autopack(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
+                               int64_t K, const double *A, int64_t lda, const double *B, int64_t ldb,
+                               const double *thres, int64_t ldt, const double *dis, double *R, int64_t ldr,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    // the plain call validates everything; only what the copy itself relies on is checked before it
+    if (workspace && A && M > 0 && N > 0 && K > 0 && M <= kMaxDim && K <= kMaxDim && lda >= K &&
+        task > TASK_IDENTITY && task <= TASK_COUNT_GT && autopack_wanted(true, trans_a, N, lda, 8)) {
+        if (workspace_bytes < amulet_autopack_workspace_bytes(8, M, K)) return AMULET_ERR_WORKSPACE;
+        const int64_t ld = amulet_packed_ld(K, 8);
+        const int prc = amulet_pack(8, M, K, A, lda, workspace, ld, stream);
+        if (prc != AMULET_OK) return prc;
+        A = (const double *)workspace;
+        lda = ld;
+    }
+    return amulet_mmlike_f64_general(task, thres_form, trans_a, trans_b, M, N, K, A, lda, B, ldb, thres, ldt,
+                                     dis, R, ldr, stream);
+}
+
 int amulet_count_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
                     int64_t ldb, int32_t *R, int64_t ldr, void *stream)
 {
@@ -625,6 +713,7 @@ const char *amulet_strerror(int code)
     case AMULET_ERR_LAUNCH: return "HIP reported an error at launch";
     case AMULET_ERR_SHAPE: return "unknown tile shape";
     case AMULET_ERR_RANGE: return "dimension too large for the kernels' 32-bit indexing";
+    case AMULET_ERR_WORKSPACE: return "workspace too small for the packed copy";
     default: return "unknown status code";
     }
 }

@@ -370,14 +370,15 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
-    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
-    // (at least 64 k each), which add their parts to R with hardware fp64 atomics
+    // tiles for at most half of the waves the chip holds at once (4 per SIMD): split K over
+    // as many workgroups per tile as still fit (at least 64 k each), which add their parts
+    // to R with hardware fp64 atomics
     MmlikeArgsF64 b = a;
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * D_NW;
-    if (waves < 2048 && a.K >= 128) {
-        int64_t want = (2048 + waves - 1) / waves;
+    if (waves <= 2048 && a.K >= 128) {
+        int64_t want = 4096 / waves;
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;
         const int64_t chunk = ((a.K + want - 1) / want + D_BK - 1) / D_BK * D_BK;

@@ -477,15 +477,16 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     const int64_t tiles_n = (a.N + 256 * NG - 1) / (256 * NG);
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    // Too few tiles to give every SIMD two waves (tiny M x N, e.g. an aggregation over a long K):
-    // split K over several workgroups per tile, at least 64 k each; each adds its part to R
-    // with hardware float atomics (the sum order is free, Sec. 4.1).
+    // Tiles for at most half of the waves the chip holds at once (small M x N, e.g. an
+    // aggregation over a long K): split K over as many workgroups per tile as still fit, at
+    // least 64 k each; each adds its part to R with hardware float atomics (the sum order is
+    // free, Sec. 4.1).  A SIMD with two waves runs a wave's work 20 % slower than one with four.
     MmlikeArgs b = a;
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * NW;
-    if (waves < 2048 && a.K >= 128) {
-        int64_t want = (2048 + waves - 1) / waves;
+    if (waves <= 2048 && a.K >= 128) {
+        int64_t want = 4096 / waves;   // as many as still fit the chip at once (4 waves per SIMD)
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;
         const int64_t chunk = ((a.K + want - 1) / want + 63) / 64 * 64;   // whole partial-sum periods

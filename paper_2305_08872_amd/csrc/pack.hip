@@ -1,0 +1,70 @@
+// Packing (paper Sec. 3.1): copy an operand once into storage whose layout suits the kernels'
+// access order.  On this GPU "suits" means one thing only: a row pitch that does not put the
+// rows a workgroup reads at one k into the same L2 sets and memory channel.  The copy is a
+// strided 2-D copy into rows spaced by amulet_packed_ld(); the compute kernels then read it
+// in place like any other row-major operand.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "amulet.h"
+#include "amulet_internal.h"
+
+namespace amulet {
+
+typedef unsigned int pk_u4 __attribute__((ext_vector_type(4)));
+
+// One workgroup row of 256 threads copies `row_units` 16-byte units of a row per pass; rows are
+// walked with a grid stride in y, so any row count fits the grid limits.
+__global__ void __launch_bounds__(256)
+pack_rows16_kernel(const uint8_t *src, int64_t pitch_src, uint8_t *dst, int64_t pitch_dst,
+                   int64_t rows, int64_t row_units)
+{
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        const pk_u4 *s = (const pk_u4 *)(src + r * pitch_src);
+        pk_u4 *d = (pk_u4 *)(dst + r * pitch_dst);
+        for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < row_units; u += (int64_t)gridDim.x * 256)
+            d[u] = s[u];
+    }
+}
+
+// Same walk, one element per thread and pass: for rows that are not 16-byte aligned.
+template <typename T>
+__global__ void __launch_bounds__(256)
+pack_rows_elem_kernel(const T *src, int64_t ld_src, T *dst, int64_t ld_dst, int64_t rows, int64_t cols)
+{
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        const T *s = src + r * ld_src;
+        T *d = dst + r * ld_dst;
+        for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < cols; c += (int64_t)gridDim.x * 256)
+            d[c] = s[c];
+    }
+}
+
+hipError_t launch_pack(int elem_bytes, int64_t rows, int64_t cols, const void *src, int64_t ld_src,
+                       void *dst, int64_t ld_dst, hipStream_t s)
+{
+    const int64_t row_bytes = cols * elem_bytes;
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15u) == 0 && (ld_src * elem_bytes) % 16 == 0 &&
+                     (ld_dst * elem_bytes) % 16 == 0 && row_bytes % 16 == 0;
+    const int64_t units = vec ? row_bytes / 16 : cols;
+    int64_t gx = (units + 255) / 256;
+    if (gx > 64) gx = 64;                       // a row of up to 256 KiB in one pass, longer rows in several
+    const int64_t gy = rows < 65535 ? rows : 65535;
+    const dim3 grid((unsigned)gx, (unsigned)gy), block(256);
+    if (vec) {
+        hipLaunchKernelGGL(pack_rows16_kernel, grid, block, 0, s, (const uint8_t *)src, ld_src * elem_bytes,
+                           (uint8_t *)dst, ld_dst * elem_bytes, rows, units);
+    } else if (elem_bytes == 8) {
+        hipLaunchKernelGGL(pack_rows_elem_kernel<uint64_t>, grid, block, 0, s, (const uint64_t *)src, ld_src,
+                           (uint64_t *)dst, ld_dst, rows, cols);
+    } else if (elem_bytes == 4) {
+        hipLaunchKernelGGL(pack_rows_elem_kernel<uint32_t>, grid, block, 0, s, (const uint32_t *)src, ld_src,
+                           (uint32_t *)dst, ld_dst, rows, cols);
+    } else {
+        hipLaunchKernelGGL(pack_rows_elem_kernel<uint8_t>, grid, block, 0, s, (const uint8_t *)src, ld_src,
+                           (uint8_t *)dst, ld_dst, rows, cols);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace amulet

@@ -51,6 +51,38 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.amulet_tune(55, 8, 8, 8, None) == -1
 
 
+def test_packed_pitch_never_collides_and_argument_errors(lib):
+    """The packed pitch holds the row, keeps rows on whole 128-byte lines and is never a pitch
+    the library itself calls colliding; a call that wants to pack checks its workspace before
+    anything is launched."""
+    for eb in (1, 4, 8):
+        for cols in [1, 3, 31, 32, 1000, 1024, 4096, 8191, 8192, 16384, 32768, 65536, 100000, 2 ** 20]:
+            ld = am.amulet_packed_ld(cols, eb)
+            assert ld >= cols and (ld * eb) % 128 == 0 and ld * eb < cols * eb + 256
+            assert not am.amulet_pitch_collides(ld, eb)
+            assert (ld * eb) % 4096 != 0
+    assert am.amulet_packed_ld(0, 4) == 0 and am.amulet_packed_ld(5, 3) == 0
+    # the measured rule: multiples of 32 KiB from 64 KiB on
+    assert [am.amulet_pitch_collides(n, 4) for n in (4096, 8192, 12288, 16384, 16400, 20480, 24576, 32768, 65536)] == \
+        [False, False, False, True, False, False, True, True, True]
+    assert am.amulet_pitch_collides(8192, 8) and not am.amulet_pitch_collides(8192, 4)
+    assert am.amulet_autopack_workspace_bytes(4, 10, 16384) == 10 * 16416 * 4
+    one = ctypes.c_void_p(16)   # never dereferenced: every call below fails validation first
+    assert lib.amulet_pack(3, 1, 1, one, 1, one, 1, None) == -2
+    assert lib.amulet_pack(4, -1, 1, one, 1, one, 1, None) == -2
+    assert lib.amulet_pack(4, 2, 2, None, 2, one, 2, None) == -3
+    assert lib.amulet_pack(4, 2, 2, one, 1, one, 2, None) == -4
+    assert lib.amulet_pack(4, 0, 2, None, 2, None, 2, None) == 0
+    f = lib.amulet_mmlike_f32_autopack
+    # discount, 8 x 128 x 16384 with a colliding lda: wants 8 * 16416 * 4 bytes
+    assert f(1, 0, 0, 0, 8, 128, 16384, one, 16384, one, 128, one, 0, one, one, 128, one, 100, None) == -8
+    assert f(9, 0, 0, 0, 8, 128, 16384, one, 16384, one, 128, one, 0, one, one, 128, one, 100, None) == -1
+    assert f(1, 0, 0, 0, 8, 128, 16384, one, 16383, one, 128, one, 0, one, one, 128, one, 100, None) == -4
+    assert lib.amulet_mmlike_f64_autopack(1, 0, 0, 0, 8, 128, 8192, one, 8192, one, 128, one, 0, one, one, 128,
+                                          one, 100, None) == -8
+    assert am.amulet_strerror(-8).startswith("workspace")
+
+
 @pytest.fixture(scope="module")
 def table1(golden_dir):
     with open(os.path.join(golden_dir, "table1_kc_nc_seconds.json")) as f:
