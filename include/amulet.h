@@ -279,7 +279,10 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K,
  * Sec. 4.4-4.6): times the candidate tile shapes of `task` on synthetic
  * operands of this size that the call allocates and frees itself, walks them
  * with the paper's two-stage greedy search, caches the winner for
- * (task, M, N, K) and synchronises `stream`.  Unlike the compute calls this
+ * (task, M, N, K) and synchronises `stream`.  The device is first run up to
+ * its loaded clocks, a trial is the better of two spans of about 2 ms of
+ * back-to-back launches, and the search's winner replaces the built-in default
+ * only if it also beats it in a direct rematch.  Unlike the compute calls this
  * one allocates and blocks; it is meant to run once, outside the hot path.
  * task may be 0..3, or AMULET_TASK_COUNT_I8 for amulet_count_i8.
  * Returns the chosen shape id (>= 0) or a negative status.
