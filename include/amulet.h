@@ -27,10 +27,13 @@
  *    enqueued when an argument error is returned.  M == 0, N == 0 or K == 0 is
  *    a successful no-op (R unchanged).
  *  - The k-sum is formed in an order the library chooses (the paper's loop
- *    is order-free, Sec. 4.1).  Problems whose M x N gives too few tiles to
- *    fill the chip have K split over several workgroups that add their
- *    parts to R atomically: floating-point results of such calls may differ
- *    in the last bits from run to run (integer results never do).  R must be
+ *    is order-free, Sec. 4.1).  Tiles that would leave most of the chip idle
+ *    (all of them when M x N gives too few tiles to fill it, else those of a
+ *    last round of workgroups that is at most half full) have K split over
+ *    several workgroups that add their parts to R atomically: floating-point
+ *    results of such tiles may differ in the last bits from run to run
+ *    (integer results never do; a COUNT_GT count added in parts to a
+ *    fractional R is rounded once per part).  R must be
  *    ordinary device memory (hipMalloc or a framework's device allocator):
  *    the hardware atomics used there are not defined on fine-grained or
  *    host-mapped memory.

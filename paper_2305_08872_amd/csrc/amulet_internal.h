@@ -58,6 +58,63 @@ __host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, in
 }
 
 // Arguments of an fp32 task launch, already validated on the host.
+// Compute units of the current device (256 on MI355X), asked once per device.
+inline int compute_units()
+{
+    static int cached[16] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// Tail split of the vector-ALU launchers.  The chip holds `round` workgroups at once (4 waves
+// per SIMD) and workgroups take equally long, so a launch runs in rounds, and a last round with
+// few workgroups leaves most of the chip idle for a whole K loop.  The tiles of the last round
+// (or of the last two, or all of them when there is less than one round) are therefore launched
+// once per k range, s ranges, when that shortens the launch: x rounds' worth of tiles then take
+// ceil(x s) / s rounds.  They add their parts to R with hardware atomics and follow the whole
+// tiles in the same grid, so they start as the last whole tiles finish.  Counted in real tiles:
+// the blocks that pad the XCD parts to equal length come last in launch order and leave at once.
+struct TailSplit {
+    int64_t base;     // first block (place in the tile order) of the split region
+    int64_t blocks;   // places from there to the end of the padded order
+    int splits;       // k ranges per tile
+    int chunk;        // k per range, a multiple of k_align
+    int64_t grid;     // blocks to launch: base + blocks * splits
+};
+inline bool choose_tail_split(int64_t real, int64_t wgs, int64_t round, int64_t K, int k_align, TailSplit &t)
+{
+    if (K < 512 || round <= 0 || real % round == 0) return false;
+    const int64_t tail = real % round;
+    const int max_s = K / 256 < 8 ? (int)(K / 256) : 8;
+    double best_cost = (double)((real + round - 1) / round);   // rounds of the plain launch
+    int64_t best_region = 0;
+    int best_s = 1;
+    for (int two = 0; two < 2; ++two) {
+        const int64_t region = tail + (two ? round : 0);
+        if (region > real) break;
+        for (int sp = 2; sp <= max_s; ++sp) {
+            const int64_t parts = (region * sp + round - 1) / round;      // ceil(x s)
+            // a k range costs a little more than its share of the K loop (set-up, atomics)
+            const double cost = (double)((real - region) / round) + (double)parts / sp * (1.0 + 0.01 * sp);
+            if (cost < best_cost - 0.03) { best_cost = cost; best_region = region; best_s = sp; }
+        }
+    }
+    if (best_s <= 1) return false;
+    const int64_t chunk = ((K + best_s - 1) / best_s + k_align - 1) / k_align * k_align;
+    t.splits = (int)((K + chunk - 1) / chunk);
+    t.chunk = (int)chunk;
+    t.base = real - best_region;
+    t.blocks = wgs - t.base;
+    t.grid = t.base + t.blocks * t.splits;
+    return t.splits > 1 && t.grid <= 0x7fffffffLL;
+}
+
 struct MmlikeArgs {
     const float *A;
     const float *B;
@@ -70,6 +127,9 @@ struct MmlikeArgs {
     int vec;   // 1 when B, R and their row pitches allow 16-byte vector accesses
     int vecA;  // 1 when A and its row pitch do
     int kchunk;  // k range of one workgroup when a launch splits K (set by the launcher)
+    // Tail split: blocks from tail_base on are the launch's last `tail_blocks` places of the tile
+    // order, each present tail_splits times, once per k range (tail_splits <= 1: no such blocks).
+    int tail_base, tail_blocks, tail_splits;
 };
 
 // Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy
@@ -127,6 +187,7 @@ struct MmlikeArgsF64 {
     int transA, transB;  // operand stored transposed: a(i,k) = A[k*lda+i], b(k,j) = B[j*ldb+k]
     int vecBt; // transposed B: 1 when B and its row pitch allow 16-byte loads along k
     int kchunk;  // k range of one workgroup when a launch splits K (set by the launcher)
+    int tail_base, tail_blocks, tail_splits;   // as in MmlikeArgs
 };
 // predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);

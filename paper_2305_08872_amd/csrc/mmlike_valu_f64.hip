@@ -111,17 +111,25 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int tiles_m = (M + D_NW * D_TM - 1) / (D_NW * D_TM);
     const int tiles_n = (N + D_BN - 1) / D_BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    // place in the tile order, and which k range of it (tail split, see choose_tail_split)
+    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * (D_NW * D_TM) + wave * D_TM;
     const int col0 = tn * D_BN;
 
     // Split K (gridDim.y > 1; chosen by the host for problems with too few tiles to fill the
     // chip): this workgroup sums k in [kb, kb + kchunk) only and adds its part to R atomically.
-    const bool ksplit = gridDim.y > 1;
+    const bool ksplit = gridDim.y > 1 || tail_part;
     sptr_d As = (sptr_d)args.A;
     const double *Bg = args.B;
     if (ksplit) {
-        const int kb = (int)blockIdx.y * args.kchunk;
+        const int kb = ksplit_idx * args.kchunk;
         As += transA ? (int64_t)kb * args.lda : (int64_t)kb;
         Bg += transB ? (int64_t)kb : (int64_t)kb * args.ldb;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
@@ -385,7 +393,18 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    const dim3 grid((unsigned)wgs, (unsigned)splits);
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    dim3 grid((unsigned)wgs, (unsigned)splits);
+    // a last round of workgroups that would leave most of the chip idle: its tiles are launched
+    // once per k range instead (choose_tail_split in amulet_internal.h)
+    TailSplit t;
+    if (splits == 1 && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / D_NW), a.K, D_BK, t)) {
+        b.tail_base = (int)t.base;
+        b.tail_blocks = (int)t.blocks;
+        b.tail_splits = t.splits;
+        b.kchunk = t.chunk;
+        grid = dim3((unsigned)t.grid, 1u);
+    }
     const bool trans = a.transA || a.transB;
     switch (task) {
     case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, b, grid, s)

@@ -126,7 +126,15 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int tiles_m = (M + NW * TM - 1) / (NW * TM);
     const int tiles_n = (N + BN - 1) / BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    // place in the tile order, and which k range of it (see launch_one)
+    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * (NW * TM) + wave * TM;
     const int col0 = tn * BN;
 
@@ -140,11 +148,12 @@ mmlike_valu_kernel(const MmlikeArgs args)
     // cost the row-major kernels scalar registers in the hot loop.
     const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
     const int64_t kstride = transA ? args.lda : 1;
-    // Split K (gridDim.y > 1; chosen by the host for problems with too few tiles to fill the
-    // chip): this workgroup sums k in [kb, kb + kchunk) only and adds its part to R atomically.
-    const bool ksplit = gridDim.y > 1;
+    // Split K (every tile when gridDim.y > 1, chosen by the host for problems with too few tiles
+    // to fill the chip; else the tail blocks): this workgroup sums k in [kb, kb + kchunk) only
+    // and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1 || tail_part;
     if (ksplit) {
-        const int kb = (int)blockIdx.y * args.kchunk;
+        const int kb = ksplit_idx * args.kchunk;
         As += (int64_t)kb * kstride;
         Bg += transB ? (int64_t)kb : (int64_t)kb * args.ldb;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
@@ -345,7 +354,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     // slots, the workgroups of a round finish one after the other and the round's tail runs
     // with too few waves to fill both slots (measured: +5 % when a launch is one or two rounds
     // of workgroups, +0-2 % at sixteen).
-    const int prio_phase = (int)(blockIdx.x >> 8);
+    const int prio_phase = block >> 8;
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int k0 = t * BK;
@@ -493,11 +502,26 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    const dim3 grid((unsigned)wgs, (unsigned)splits), block(64 * NW);
-    if (a.transA || a.transB)
-        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
-    else
-        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    auto launch = [&](int64_t n_blocks, int n_splits) {
+        const dim3 grid((unsigned)n_blocks, (unsigned)n_splits), block(64 * NW);
+        if (a.transA || a.transB)
+            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+        else
+            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+    };
+    // a last round of workgroups that would leave most of the chip idle: its tiles are launched
+    // once per k range instead (choose_tail_split in amulet_internal.h)
+    TailSplit t;
+    if (splits == 1 && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / NW), a.K, 64, t)) {
+        b.tail_base = (int)t.base;
+        b.tail_blocks = (int)t.blocks;
+        b.tail_splits = t.splits;
+        b.kchunk = t.chunk;
+        launch(t.grid, 1);
+        return hipGetLastError();
+    }
+    launch(wgs, splits);
     return hipGetLastError();
 }
 

@@ -260,3 +260,16 @@ def test_f64_few_tiles_long_k_split_over_workgroups(am, task):
     am.amulet_mmlike_f64(task, dev(A), dev(B), dev(th) if task else None, dev(dis) if task == 1 else None, dR)
     torch.cuda.synchronize()
     assert np.array_equal(dR.cpu().numpy(), R_ref)
+
+
+@pytest.mark.parametrize("task", [1, 3])
+def test_last_round_of_workgroups_split_over_k(am, task):
+    """More tiles than the chip holds workgroups at once (1176 tiles of 16 x 128 against 1024),
+    with a last round far from full: those tiles run once per k range and add their parts to R
+    atomically.  Ragged in M, N and K; every output is checked."""
+    M, N, K = 770, 3050, 1100
+    A, B, th, dis, R_in = make_case(0, M, N, K, seed=880 + task, exact=(task == 3))
+    print("f64 tail-split case", task, M, N, K, flush=True)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th, dis if task == 1 else None, R_in)
+    R = run(am, task, 0, dev(A), dev(B), th, dis, dev(R_in))
+    check(R, R_ref, ab, R_in, task, "f64 tail split task %d" % task)

@@ -171,6 +171,27 @@ def test_empty_dimensions_are_noops(am):
     assert torch.all(R == 2.5)
 
 
+@pytest.mark.parametrize("shape", [None, 4, 5])
+@pytest.mark.parametrize("task", [1, 3])
+def test_last_round_of_workgroups_split_over_k(am, task, shape):
+    """More tiles than the chip holds workgroups at once, with a last round at most half full:
+    the launcher runs those last tiles as a second launch that splits K (atomic adds into R).
+    Ragged in M, N and K; every output is checked (a tile run twice, or not at all, shows)."""
+    M, N, K = 770, 6100, 1100      # 25 x 24 tiles of 32 x 256 (600 > 512), 49 x 24 of 16 x 256 (1176 > 1024)
+    A, B, params, R_in = rand_case(task, M, N, K, seed=640 + task)
+    if task == 3:
+        # a split tile's count reaches R in several adds: exact as long as R holds integers
+        # (a fractional R_in would be rounded once per add instead of once)
+        R_in = np.rint(R_in)
+    print("tail-split case", task, shape, M, N, K, flush=True)
+    R_ref, ab, _ = oracle.mmlike_f32(task, A, B, params, R_in)
+    R = run_gpu(am, task, A, B, params, R_in, shape)
+    if task == 3:
+        assert np.array_equal(R, R_ref)
+    else:
+        assert_parity_f32(R, R_ref, ab, R_in, what="tail split, task %d shape %s" % (task, shape))
+
+
 # ---- join count -----------------------------------------------------------------
 @pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5, 6, 7])
 def test_count_i8_bit_exact_ragged(am, shape):
