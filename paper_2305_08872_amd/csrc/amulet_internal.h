@@ -57,7 +57,6 @@ __host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, in
     return tn < tiles_n && tm < tiles_m;
 }
 
-// Arguments of an fp32 task launch, already validated on the host.
 // Compute units of the current device (256 on MI355X), asked once per device.
 inline int compute_units()
 {
@@ -115,6 +114,33 @@ inline bool choose_tail_split(int64_t real, int64_t wgs, int64_t round, int64_t 
     return t.splits > 1 && t.grid <= 0x7fffffffLL;
 }
 
+// K split of every tile for the matrix-core kernels when the tiles are few (at most four per
+// compute unit).  One workgroup does not keep a compute unit's matrix cores busy: measured on
+// the fp32 kernel, a unit with 1 / 2 / 3+ resident workgroups runs at 0.72 / 0.81 / 1.0 of its
+// full rate (fp64, 8 waves per workgroup: 0.86 / 1.0).  With every tile launched once per k
+// range, s ranges, the busiest unit of the busiest XCD (each XCD walks its own part of the tile
+// grid, `part_tiles` places, on its own `units_per_xcd` units) gets n = ceil(part_tiles s /
+// units_per_xcd) workgroups of 1/s of a tile each.  The estimate (n / s) / rate(n), plus 1 %
+// per range for set-up and the atomic adds into R (mostly hidden behind other workgroups'
+// K loops), is minimised over s <= 8 with at least 256 k per range.  Returns s (1: do not
+// split).  Checked against sweeps of s = 1..8 at 144 ... 1024 tiles (fp32, K = 2048 ... 8192):
+// the chosen s is within 4 % of the best one measured.
+inline int choose_full_split(int64_t part_tiles, int64_t units_per_xcd, int64_t K, const double *rate,
+                             int n_rates)
+{
+    const int max_s = K / 256 < 8 ? (int)(K / 256) : 8;
+    int best_s = 1;
+    double best = 0.0;
+    for (int sp = 1; sp <= max_s; ++sp) {
+        const int64_t n = (part_tiles * sp + units_per_xcd - 1) / units_per_xcd;
+        const double r = rate[(n < n_rates ? n : n_rates) - 1];
+        const double cost = (double)n / sp / r * (sp > 1 ? 1.0 + 0.01 * sp : 1.0);
+        if (sp == 1 || cost < best - 0.02) { best = cost; best_s = sp; }
+    }
+    return best_s;
+}
+
+// Arguments of an fp32 task launch, already validated on the host.
 struct MmlikeArgs {
     const float *A;
     const float *B;

@@ -78,7 +78,15 @@ identity_mfma_kernel(const MmlikeArgs args)
     const int tiles_m = (M + MI_BM - 1) / MI_BM;
     const int tiles_n = (N + MI_BN - 1) / MI_BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    // place in the tile order, and which k range of it (tail split, see choose_tail_split)
+    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * MI_BM, col0 = tn * MI_BN;
     const bool vecA = args.vecA != 0, vecB = args.vec != 0;
     // Interior tiles with 16-byte aligned rows are staged as (wave-uniform base that advances
@@ -88,10 +96,10 @@ identity_mfma_kernel(const MmlikeArgs args)
                           (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
     // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
     // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
-    const bool ksplit = gridDim.y > 1;
+    const bool ksplit = gridDim.y > 1 || tail_part;
     const float *Ag = args.A, *Bg = args.B;
     if (ksplit) {
-        const int kb = (int)blockIdx.y * args.kchunk;
+        const int kb = ksplit_idx * args.kchunk;
         Ag += TA ? (int64_t)kb * args.lda : (int64_t)kb;
         Bg += TB ? (int64_t)kb : (int64_t)kb * args.ldb;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
@@ -288,13 +296,13 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
     if (granted != hipSuccess) return granted;
-    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // tiles for at most half of the compute units: split K over several workgroups per tile
     // (at least 128 k each), which add their parts to R with hardware float atomics
     MmlikeArgs b = a;
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * G * G;
-    if (waves < 2048 && a.K >= 256) {
+    if (2 * tiles_m * tiles_n <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;
@@ -302,8 +310,35 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3((unsigned)grid, (unsigned)splits), dim3(L::NT),
-                       L::LDS_BYTES, s, b);
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    dim3 launch_grid((unsigned)grid, (unsigned)splits);
+    // Up to four tiles per compute unit: every tile once per k range, as many ranges as the
+    // occupancy model likes best (choose_full_split in amulet_internal.h).
+    const int64_t tiles = tiles_m * tiles_n;
+    if (splits == 1 && tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
+        static const double rate[3] = {0.72, 0.81, 1.0};
+        const int sp = choose_full_split(grid / 8, compute_units() / 8, a.K, rate, 3);
+        if (sp > 1) {
+            const int64_t chunk = ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK;
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+            launch_grid = dim3((unsigned)grid, (unsigned)splits);
+        }
+    }
+    // More tiles than that: the launch runs in rounds of about one tile per compute unit, and a
+    // last round with few tiles leaves most of the chip idle for a whole K loop: its tiles are
+    // launched once per k range instead (choose_tail_split in amulet_internal.h; rounds of 1, 2,
+    // 3 and 4 workgroups per compute unit were tried in the model: 1 is never worse).
+    TailSplit t;
+    if (splits == 1 && tiles > 4 * (int64_t)compute_units() &&
+        choose_tail_split(tiles, grid, compute_units(), a.K, MI_BK, t)) {
+        b.tail_base = (int)t.base;
+        b.tail_blocks = (int)t.blocks;
+        b.tail_splits = t.splits;
+        b.kchunk = t.chunk;
+        launch_grid = dim3((unsigned)t.grid, 1u);
+    }
+    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), launch_grid, dim3(L::NT), L::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 

@@ -66,17 +66,25 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     const int tiles_m = (M + DI_BM - 1) / DI_BM;
     const int tiles_n = (N + DI_BN - 1) / DI_BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    // place in the tile order, and which k range of it (tail split, see choose_tail_split)
+    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * DI_BM, col0 = tn * DI_BN;
     // 16-byte loads allowed along the operand's contiguous axis
     const bool vecA = args.vecA != 0, vecB = TB ? args.vecBt != 0 : args.vec != 0;
 
     // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
     // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
-    const bool ksplit = gridDim.y > 1;
+    const bool ksplit = gridDim.y > 1 || tail_part;
     const double *Ag = args.A, *Bg = args.B;
     if (ksplit) {
-        const int kb = (int)blockIdx.y * args.kchunk;
+        const int kb = ksplit_idx * args.kchunk;
         Ag += TA ? (int64_t)kb * args.lda : (int64_t)kb;
         Bg += TB ? (int64_t)kb : (int64_t)kb * args.ldb;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
@@ -222,13 +230,13 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (granted != hipSuccess) return granted;
-    // too few tiles to give every SIMD two waves: split K over several workgroups per tile
+    // tiles for at most half of the compute units: split K over several workgroups per tile
     // (at least 128 k each), which add their parts to R with hardware fp64 atomics
     MmlikeArgsF64 b = a;
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = (int64_t)n_tiles * (DI_NT / 64);
-    if (waves < 2048 && a.K >= 256) {
+    if (2 * n_tiles <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;
@@ -236,7 +244,33 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(grid, (unsigned)splits), dim3(DI_NT), LDS, s, b);
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    dim3 launch_grid(grid, (unsigned)splits);
+    // Up to four tiles per compute unit: every tile once per k range, as many ranges as the
+    // occupancy model likes best (choose_full_split in amulet_internal.h).
+    if (splits == 1 && n_tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
+        static const double rate[2] = {0.86, 1.0};
+        const int sp = choose_full_split(grid / 8, compute_units() / 8, a.K, rate, 2);
+        if (sp > 1) {
+            const int64_t chunk = ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK;
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+            launch_grid = dim3(grid, (unsigned)splits);
+        }
+    }
+    // more tiles than that: the launch runs in rounds of about one tile per compute unit (as in
+    // the fp32 kernel); the tiles of a nearly empty last round are launched once per k range
+    // instead (choose_tail_split in amulet_internal.h)
+    TailSplit t;
+    if (splits == 1 && n_tiles > 4 * (int64_t)compute_units() &&
+        choose_tail_split(n_tiles, grid, compute_units(), a.K, DI_BK, t)) {
+        b.tail_base = (int)t.base;
+        b.tail_blocks = (int)t.blocks;
+        b.tail_splits = t.splits;
+        b.kchunk = t.chunk;
+        launch_grid = dim3((unsigned)t.grid, 1u);
+    }
+    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), launch_grid, dim3(DI_NT), LDS, s, b);
     return hipGetLastError();
 }
 

@@ -273,3 +273,14 @@ def test_last_round_of_workgroups_split_over_k(am, task):
     R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th, dis if task == 1 else None, R_in)
     R = run(am, task, 0, dev(A), dev(B), th, dis, dev(R_in))
     check(R, R_ref, ab, R_in, task, "f64 tail split task %d" % task)
+
+
+def test_identity_last_round_of_tiles_split_over_k(am):
+    """fp64 matrix-core identity kernel with a few more tiles than compute units (275 of
+    128 x 128 against 256): the last round's tiles run once per k range (fp64 atomics)."""
+    M, N, K = 1300, 3200, 1100
+    A, B, th, dis, R_in = make_case(0, M, N, K, seed=890)
+    print("f64 identity tail-split case", M, N, K, flush=True)
+    R_ref, ab, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
+    R = run(am, 0, 0, dev(A), dev(B), th, dis, dev(R_in))
+    check(R, R_ref, ab, R_in, 0, "f64 identity tail split")

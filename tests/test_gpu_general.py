@@ -192,6 +192,21 @@ def test_few_tiles_long_k_split_over_workgroups(am, task):
     assert np.array_equal(R, R_ref)
 
 
+@pytest.mark.parametrize("trans", [False, True])
+def test_identity_last_round_of_tiles_split_over_k(am, trans):
+    """Matrix-core identity kernels with a few more tiles than compute units (275 tiles of
+    128 x 128 against 256): the tiles of the nearly empty last round run once per k range and
+    add their parts to R atomically.  Ragged M, N, K; every output checked; the 256 x 256
+    shape (77 tiles: fewer than half the compute units, every tile split) rides along."""
+    M, N, K = 1300, 3200, 1100
+    As, Bs, th, dis, R_in = make_case(0, 0, trans, trans, M, N, K, 6400 + int(trans))
+    R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=trans, trans_b=trans)
+    for shape in (8, 9, -1):
+        print("identity tail split", trans, shape, M, N, K, flush=True)
+        R = run(am, 0, 0, trans, trans, As, Bs, th, dis, R_in, shape)
+        assert_parity_f32(R, R_ref, ab, R_in, what="identity tail split shape %d" % shape)
+
+
 def test_compute_calls_can_be_captured_in_a_graph(am):
     """Compute calls only enqueue kernels on the caller's stream (no allocation, no sync, no
     memset), so a sequence of them can be captured once and replayed: three tasks of different
