@@ -49,10 +49,18 @@ static int n_shapes(int task)
 // compute unit, the 4-wave one (16 x 256) below that.
 static int default_shape(int task, int64_t M, int64_t N, int64_t)
 {
-    // matrix cores, operands streamed straight into LDS: the 256 x 256 tile when it still gives
-    // every compute unit two tiles or more, else 128 x 256 (both fall back to the register-staged
-    // kernel when the problem is not fully interior and aligned)
-    if (task == AMULET_TASK_COUNT_I8) return ((M / 256) * ((N + 255) / 256) >= 512) ? 7 : 6;
+    // Matrix cores.  Fewer 128 x 256 tiles than compute units: the register-staged 128 x 128 tile
+    // with 8 waves (twice the workgroups; 2048^2 x 4096: 945 against 787 TOP/s).  Else operands
+    // streamed straight into LDS: the 256 x 256 tile (one workgroup per compute unit) when its
+    // tiles fill whole rounds of the chip, at least two of them, else 128 x 256, whose partial
+    // last round costs half as much (6144^2 x 4096: 2074 against 1748 TOP/s).  Both fall back to
+    // the register-staged kernel where the problem is not interior and aligned.
+    if (task == AMULET_TASK_COUNT_I8) {
+        const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
+        const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+        if (tiles128 < 256) return 4;
+        return (tiles256 >= 512 && tiles256 % 256 == 0) ? 7 : 6;
+    }
     // a dense contraction: matrix cores (the 128 x 128 tile measures 1 % ahead of the 256 x 256
     // one even at 8192^3; the selector tries both)
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;
