@@ -256,6 +256,27 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
                           void *stream);
 
 /*
+ * The join count with operands stored transposed (the layouts of Sec. 6.3
+ * applied to this task): A stored K x M (lda >= M) when trans_a != 0, B stored
+ * N x K (ldb >= K) when trans_b != 0.  The matrix-core kernels read row-major
+ * operands; a transposed operand is first copied, transposed, into `workspace`
+ * (device memory the caller lends for the duration of the call's work on
+ * `stream`; amulet_count_i8_workspace_bytes gives the size, 0 when neither
+ * flag is set, and then `workspace` may be NULL): one more kernel per such
+ * operand on the same stream, 3-4 % of the 8192 x 8192 x 4096 join each.
+ * The result is that of amulet_count_i8 on the row-major operands, exact.
+ * AMULET_ERR_NULL if a workspace is needed and NULL, AMULET_ERR_WORKSPACE if
+ * it is too small; other errors as amulet_count_i8.
+ */
+size_t amulet_count_i8_workspace_bytes(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K);
+int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                            const int8_t *A, int64_t lda,
+                            const int8_t *B, int64_t ldb,
+                            int32_t *R, int64_t ldr,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
  * Adaptive execution as the paper runs it (Sec. 4.4-4.6): the task is split
  * into disjoint row slabs; the first slabs are computed with trial tile
  * shapes, walked by the two-stage greedy search and scored by time per row,

@@ -79,6 +79,10 @@ def load_library():
                                                i64, vp, ctypes.c_size_t, vp]
     lib.amulet_mmlike_f64_autopack.restype = i32
     lib.amulet_mmlike_f64_autopack.argtypes = lib.amulet_mmlike_f32_autopack.argtypes
+    lib.amulet_count_i8_workspace_bytes.restype = ctypes.c_size_t
+    lib.amulet_count_i8_workspace_bytes.argtypes = [i32, i32, i64, i64, i64]
+    lib.amulet_count_i8_general.restype = i32
+    lib.amulet_count_i8_general.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
     lib.amulet_count_i8_shape.restype = i32
     lib.amulet_count_i8_shape.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_tune.restype = i32
@@ -318,6 +322,31 @@ def amulet_count_i8(A, B, R, stream=None):
         raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
     _check(lib.amulet_count_i8(M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
            "amulet_count_i8")
+
+
+def amulet_count_i8_workspace_bytes(trans_a: bool, trans_b: bool, M: int, N: int, K: int) -> int:
+    """Bytes of workspace amulet_count_i8_general needs for these layouts (0 for row-major)."""
+    return int(load_library().amulet_count_i8_workspace_bytes(int(trans_a), int(trans_b), M, N, K))
+
+
+def amulet_count_i8_general(A, B, R, workspace=None, *, trans_a: bool = False, trans_b: bool = False, stream=None):
+    """The join count with A stored K x M (trans_a) and / or B stored N x K (trans_b); `workspace`
+    is a contiguous device tensor of at least amulet_count_i8_workspace_bytes(...) bytes."""
+    lib = load_library()
+    pa, ra, ca, lda = _mat(A, "torch.int8", "A")
+    pb, rb, cb, ldb = _mat(B, "torch.int8", "B")
+    pr, M, N, ldr = _mat(R, "torch.int32", "R")
+    Ma, K = (ca, ra) if trans_a else (ra, ca)
+    K2, Nb = (cb, rb) if trans_b else (rb, cb)
+    if K2 != K or Ma != M or Nb != N:
+        raise ValueError("shape mismatch between A, B and R")
+    pw, nw = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous device tensor")
+        pw, nw = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib.amulet_count_i8_general(int(trans_a), int(trans_b), M, N, K, pa, lda, pb, ldb, pr, ldr, pw, nw,
+                                       _stream_ptr(stream)), "amulet_count_i8_general")
 
 
 def amulet_count_i8_shape(shape: int, A, B, R, stream=None):

@@ -503,6 +503,52 @@ int amulet_count_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t ld
                      stream);
 }
 
+// Row pitch of a transposed copy in the workspace: whole 128-byte lines (so the streamed kernel
+// takes it), never a multiple of 4 KiB.
+static int64_t i8_copy_ld(int64_t cols) { return amulet_packed_ld(cols, 1); }
+
+size_t amulet_count_i8_workspace_bytes(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    size_t n = 0;
+    if (trans_a) n += (size_t)M * (size_t)i8_copy_ld(K);
+    if (trans_b) n += (size_t)K * (size_t)i8_copy_ld(N);
+    return n;
+}
+
+int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const int8_t *A,
+                            int64_t lda, const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
+    if (M == 0 || N == 0 || K == 0) return AMULET_OK;
+    if (!A || !B || !R) return AMULET_ERR_NULL;
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldr < N) return AMULET_ERR_LD;
+    if (trans_a || trans_b) {
+        if (!workspace) return AMULET_ERR_NULL;
+        if (workspace_bytes < amulet_count_i8_workspace_bytes(trans_a, trans_b, M, N, K)) return AMULET_ERR_WORKSPACE;
+    }
+    int8_t *w = (int8_t *)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (trans_a) {   // stored K x M: the copy is M x K
+        const int64_t ld = i8_copy_ld(K);
+        const hipError_t e = launch_transpose_i8(K, M, A, lda, w, ld, s);
+        g_last_hip_error = e;
+        if (e != hipSuccess) return AMULET_ERR_LAUNCH;
+        A = w; lda = ld;
+        w += M * ld;
+    }
+    if (trans_b) {   // stored N x K: the copy is K x N
+        const int64_t ld = i8_copy_ld(N);
+        const hipError_t e = launch_transpose_i8(N, K, B, ldb, w, ld, s);
+        g_last_hip_error = e;
+        if (e != hipSuccess) return AMULET_ERR_LAUNCH;
+        B = w; ldb = ld;
+    }
+    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, K), M, N, K, A, lda, B, ldb, R, ldr, stream);
+}
+
 int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
                           const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
 {

@@ -219,6 +219,9 @@ struct MmlikeArgsF64 {
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
 
+// dst (cols x rows, pitch ld_dst) = transpose of src (rows x cols, pitch ld_src), bytes (pack.hip)
+hipError_t launch_transpose_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
+                               int64_t ld_dst, hipStream_t s);
 // strided 2-D copy of rows x cols elements of 1, 4 or 8 bytes (pack.hip)
 hipError_t launch_pack(int elem_bytes, int64_t rows, int64_t cols, const void *src, int64_t ld_src,
                        void *dst, int64_t ld_dst, hipStream_t s);

@@ -40,6 +40,60 @@ pack_rows_elem_kernel(const T *src, int64_t ld_src, T *dst, int64_t ld_dst, int6
     }
 }
 
+// dst[c][r] = src[r][c] for a rows x cols matrix of bytes: 64 x 64 tiles through LDS, so that
+// both the reads (along src rows) and the writes (along dst rows) are contiguous runs of 64
+// bytes (16 per lane: one 16-byte access where the tile is interior and `vec` says both
+// matrices are 16-byte aligned).  Pitches in bytes.  Tiles are walked with a grid stride.
+__global__ void __launch_bounds__(256)
+transpose_i8_kernel(const int8_t *src, int64_t pitch_src, int8_t *dst, int64_t pitch_dst, int64_t rows,
+                    int64_t cols, int vec)
+{
+    __shared__ __attribute__((aligned(16))) int8_t tile[64][64 + 16];
+    const int64_t tiles_c = (cols + 63) / 64, tiles_r = (rows + 63) / 64;
+    const int lr = threadIdx.x >> 2, lq = (threadIdx.x & 3) * 16;   // row of the tile, 16-byte quarter of it
+    for (int64_t t = blockIdx.x; t < tiles_r * tiles_c; t += gridDim.x) {
+        const int64_t r0 = (t / tiles_c) * 64, c0 = (t % tiles_c) * 64;
+        const bool interior = vec && r0 + 64 <= rows && c0 + 64 <= cols;
+        if (interior) {
+            *(pk_u4 *)&tile[lr][lq] = *(const pk_u4 *)(src + (r0 + lr) * pitch_src + c0 + lq);
+        } else {
+            const int64_t r = r0 + lr;
+            for (int e = 0; e < 16; ++e) {
+                const int64_t c = c0 + lq + e;
+                tile[lr][lq + e] = (r < rows && c < cols) ? src[r * pitch_src + c] : (int8_t)0;
+            }
+        }
+        __syncthreads();
+        {
+            // row c0 + lr of dst, bytes lq .. lq + 15 of it: column lr of the tile, rows lq ...
+            unsigned int w[4] = {0u, 0u, 0u, 0u};
+            for (int e = 0; e < 16; ++e) w[e >> 2] |= (unsigned int)(uint8_t)tile[lq + e][lr] << (8 * (e & 3));
+            const int64_t c = c0 + lr;
+            if (interior) {
+                pk_u4 v = {w[0], w[1], w[2], w[3]};
+                *(pk_u4 *)(dst + c * pitch_dst + r0 + lq) = v;
+            } else if (c < cols) {
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t r = r0 + lq + e;
+                    if (r < rows) dst[c * pitch_dst + r] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_transpose_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
+                               int64_t ld_dst, hipStream_t s)
+{
+    const int64_t tiles = ((rows + 63) / 64) * ((cols + 63) / 64);
+    const int64_t grid = tiles < 65536 ? tiles : 65536;
+    const int vec = ((((uintptr_t)src | (uintptr_t)dst) & 15u) == 0 && ld_src % 16 == 0 && ld_dst % 16 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(transpose_i8_kernel, dim3((unsigned)grid), dim3(256), 0, s, src, ld_src, dst, ld_dst, rows,
+                       cols, vec);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(int elem_bytes, int64_t rows, int64_t cols, const void *src, int64_t ld_src,
                        void *dst, int64_t ld_dst, hipStream_t s)
 {

@@ -232,6 +232,41 @@ def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
         assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
 
 
+@pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True), (False, False)])
+def test_count_i8_transposed_operands(am, tA, tB):
+    """A stored K x M and / or B stored N x K: transposed into the lent workspace, then the
+    row-major kernels.  Ragged and whole-tile sizes, padded pitches, non-zero R_in; bit-exact."""
+    for idx, (M, N, K, pad) in enumerate([(70, 300, 37, 0), (129, 1030, 77, 5), (256, 512, 128, 0),
+                                           (1, 1, 1, 0), (300, 70, 1000, 16), (512, 1024, 640, 0)]):
+        g = np.random.Generator(np.random.PCG64(420 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        As, Bs = (A.T.copy() if tA else A), (B.T.copy() if tB else B)
+        bufA = torch.full((As.shape[0], As.shape[1] + pad), 55, dtype=torch.int8, device="cuda")
+        bufB = torch.full((Bs.shape[0], Bs.shape[1] + pad), 66, dtype=torch.int8, device="cuda")
+        bufA[:, :As.shape[1]] = dev(As)
+        bufB[:, :Bs.shape[1]] = dev(Bs)
+        need = am.amulet_count_i8_workspace_bytes(tA, tB, M, N, K)
+        assert (need == 0) == (not tA and not tB)
+        ws = torch.empty(need + 1, dtype=torch.int8, device="cuda")[:need] if need else None
+        dR = dev(R_in)
+        print("i8 transposed", tA, tB, M, N, K, pad, flush=True)
+        am.amulet_count_i8_general(bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], dR, ws, trans_a=tA, trans_b=tB)
+        torch.cuda.synchronize()
+        assert np.array_equal(dR.cpu().numpy(), R_ref), (tA, tB, M, N, K)
+        if need:
+            with pytest.raises(am.AmuletError) as err:
+                am.amulet_count_i8_general(bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], dR, ws[:need - 1],
+                                           trans_a=tA, trans_b=tB)
+            assert err.value.code == -8
+            with pytest.raises(am.AmuletError) as err:
+                am.amulet_count_i8_general(bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], dR, None,
+                                           trans_a=tA, trans_b=tB)
+            assert err.value.code == -3
+
+
 def test_count_i8_strided(am):
     M, N, K = 50, 130, 75
     A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)

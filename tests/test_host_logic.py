@@ -81,6 +81,17 @@ def test_packed_pitch_never_collides_and_argument_errors(lib):
     assert lib.amulet_mmlike_f64_autopack(1, 0, 0, 0, 8, 128, 8192, one, 8192, one, 128, one, 0, one, one, 128,
                                           one, 100, None) == -8
     assert am.amulet_strerror(-8).startswith("workspace")
+    # join count with transposed operands: the workspace holds the transposed copies
+    assert am.amulet_count_i8_workspace_bytes(False, False, 100, 200, 300) == 0
+    assert am.amulet_count_i8_workspace_bytes(True, False, 100, 200, 300) == 100 * am.amulet_packed_ld(300, 1)
+    assert am.amulet_count_i8_workspace_bytes(True, True, 100, 200, 300) == \
+        100 * am.amulet_packed_ld(300, 1) + 300 * am.amulet_packed_ld(200, 1)
+    h = lib.amulet_count_i8_general
+    assert h(1, 0, 100, 200, 300, one, 100, one, 200, one, 200, None, 0, None) == -3      # needs a workspace
+    assert h(1, 0, 100, 200, 300, one, 100, one, 200, one, 200, one, 10, None) == -8      # too small
+    assert h(1, 0, 100, 200, 300, one, 99, one, 200, one, 200, one, 1 << 20, None) == -4  # lda < M
+    assert h(0, 1, 100, 200, 300, one, 300, one, 299, one, 200, one, 1 << 20, None) == -4  # ldb < K
+    assert h(0, 0, 0, 200, 300, None, 300, None, 200, None, 200, None, 0, None) == 0
 
 
 @pytest.fixture(scope="module")
