@@ -128,7 +128,7 @@ static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
     a.vec = (aligned16(c.B) && aligned16(c.R) && c.ldb % 4 == 0 && c.ldr % 4 == 0) ? 1 : 0;
     a.vecA = (aligned16(c.A) && c.lda % 4 == 0) ? 1 : 0;
     a.kchunk = (int)c.K;
-    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1;
+    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1; a.block_base = 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (c.task) {
@@ -172,6 +172,7 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.vecB = (aligned16(B) && ldb % 16 == 0) ? 1 : 0;
     a.vecR = (aligned16(R) && ldr % 4 == 0) ? 1 : 0;
     a.kchunk = (int)K;
+    a.block_base = 0;
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
@@ -373,7 +374,7 @@ int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b
     a.vecBt = b16 ? 1 : 0;
     a.vecA = (aligned16(A) && lda % 2 == 0) ? 1 : 0;
     a.kchunk = (int)K;
-    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1;
+    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1; a.block_base = 0;
     const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

@@ -71,6 +71,21 @@ inline int compute_units()
     return cached[dev];
 }
 
+// A grid dimension holds at most 2^32 - 1 work-items (workgroups x threads), fewer than the
+// 2^31 - 1 workgroups a tile order can have: a longer row of workgroups goes out as several
+// launches, each told in `args.block_base` where in the row it starts (the kernels add it to
+// blockIdx.x).  `launch(n)` enqueues n workgroups with the current args.
+template <typename Args, typename Launch>
+inline hipError_t launch_row_of_blocks(Args &args, int64_t blocks, int threads, Launch launch)
+{
+    const int64_t max_blocks = 0xFFFFFFFFLL / threads;
+    for (int64_t base = 0; base < blocks; base += max_blocks) {
+        args.block_base = (int)base;
+        launch((unsigned)(blocks - base < max_blocks ? blocks - base : max_blocks));
+    }
+    return hipGetLastError();
+}
+
 // Tail split of the vector-ALU launchers.  The chip holds `round` workgroups at once (4 waves
 // per SIMD) and workgroups take equally long, so a launch runs in rounds, and a last round with
 // few workgroups leaves most of the chip idle for a whole K loop.  The tiles of the last round
@@ -156,6 +171,7 @@ struct MmlikeArgs {
     // Tail split: blocks from tail_base on are the launch's last `tail_blocks` places of the tile
     // order, each present tail_splits times, once per k range (tail_splits <= 1: no such blocks).
     int tail_base, tail_blocks, tail_splits;
+    int block_base;   // added to blockIdx.x (launch_row_of_blocks)
 };
 
 // Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy
@@ -182,6 +198,7 @@ struct CountArgs {
     int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
     int vecR;        // 1 when R and its row pitch allow 16-byte accesses
     int kchunk;      // k range of one workgroup when a launch splits K (set by the launcher)
+    int block_base;  // added to blockIdx.x (launch_row_of_blocks)
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)
@@ -214,6 +231,7 @@ struct MmlikeArgsF64 {
     int vecBt; // transposed B: 1 when B and its row pitch allow 16-byte loads along k
     int kchunk;  // k range of one workgroup when a launch splits K (set by the launcher)
     int tail_base, tail_blocks, tail_splits;   // as in MmlikeArgs
+    int block_base;   // added to blockIdx.x (launch_row_of_blocks)
 };
 // predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);

@@ -98,7 +98,7 @@ count_i8_mfma_kernel(const CountArgs args)
     const int tiles_m = (M + BM - 1) / BM;
     const int tiles_n = (N + BN - 1) / BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    if (!xcd_tile((int)blockIdx.x + args.block_base, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * BM, col0 = tn * BN;
     const bool vecA = args.vecA != 0, vecB = args.vecB != 0;
 
@@ -281,26 +281,31 @@ static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3((unsigned)grid, (unsigned)splits),
-                       dim3(T::NT), T::LDS_BYTES, s, b);
-    return hipGetLastError();
+    return launch_row_of_blocks(b, grid, T::NT, [&](unsigned n) {
+        hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3(n, (unsigned)splits), dim3(T::NT),
+                           T::LDS_BYTES, s, b);
+    });
 }
 
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
 {
     switch (shape) {
     case 0: {
-        const int64_t gx = (a.N + 63) / 64;
-        // grid.y is limited to 65535: walk the rows in slabs
-        for (int64_t r0 = 0; r0 < a.M; r0 += 65535LL * 4) {
-            CountArgs sub = a;
-            const int64_t rows = (a.M - r0 < 65535LL * 4) ? a.M - r0 : 65535LL * 4;
-            sub.A = a.A + r0 * a.lda;
-            sub.R = a.R + r0 * a.ldr;
-            sub.M = (int)rows;
-            hipLaunchKernelGGL(count_i8_simple_kernel, dim3((unsigned)gx, (unsigned)((rows + 3) / 4)),
-                               dim3(256), 0, s, sub);
-        }
+        // grid.y is limited to 65535 and grid.x to 2^32 - 1 work-items: walk rows and columns in slabs
+        const int64_t col_slab = 64LL * (0xFFFFFFFFLL / 256);
+        for (int64_t c0 = 0; c0 < a.N; c0 += col_slab)
+            for (int64_t r0 = 0; r0 < a.M; r0 += 65535LL * 4) {
+                CountArgs sub = a;
+                const int64_t rows = (a.M - r0 < 65535LL * 4) ? a.M - r0 : 65535LL * 4;
+                const int64_t cols = (a.N - c0 < col_slab) ? a.N - c0 : col_slab;
+                sub.A = a.A + r0 * a.lda;
+                sub.B = a.B + c0;
+                sub.R = a.R + r0 * a.ldr + c0;
+                sub.M = (int)rows;
+                sub.N = (int)cols;
+                hipLaunchKernelGGL(count_i8_simple_kernel, dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 3) / 4)),
+                                   dim3(256), 0, s, sub);
+            }
         return hipGetLastError();
     }
     case 1: return launch_mfma<2, 2, 2, 2, 3, 64>(a, s);   // 128 x 128 tile, 4 waves

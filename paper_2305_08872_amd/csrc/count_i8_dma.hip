@@ -79,7 +79,7 @@ count_i8_dma_kernel(const CountArgs args)
     // XCD-aware tile order (xcd_tile in amulet_internal.h)
     const int tiles_m = args.M / DM_BM, tiles_n = args.N / DM_BN;
     int tm, tn;
-    if (!xcd_tile((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    if (!xcd_tile((int)blockIdx.x + args.block_base, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
     const int row0 = tm * DM_BM, col0 = tn * DM_BN;
 
     // ---- what each lane fetches: one A slot and B_LOADS B slots per stage ----------------
@@ -304,9 +304,9 @@ static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
     }
-    hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3((unsigned)grid, (unsigned)splits), dim3(T::NT),
-                       T::LDS_BYTES, s, b);
-    return hipGetLastError();
+    return launch_row_of_blocks(b, grid, T::NT, [&](unsigned n) {
+        hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3(n, (unsigned)splits), dim3(T::NT), T::LDS_BYTES, s, b);
+    });
 }
 
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s)

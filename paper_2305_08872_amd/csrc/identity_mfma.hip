@@ -79,7 +79,7 @@ identity_mfma_kernel(const MmlikeArgs args)
     const int tiles_n = (N + MI_BN - 1) / MI_BN;
     int tm, tn;
     // place in the tile order, and which k range of it (tail split, see choose_tail_split)
-    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
     if (tail_part) {
         const int rel = block - args.tail_base;
@@ -338,8 +338,9 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
         b.kchunk = t.chunk;
         launch_grid = dim3((unsigned)t.grid, 1u);
     }
-    hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), launch_grid, dim3(L::NT), L::LDS_BYTES, s, b);
-    return hipGetLastError();
+    return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
+        hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3(n, launch_grid.y), dim3(L::NT), L::LDS_BYTES, s, b);
+    });
 }
 
 template <int G>

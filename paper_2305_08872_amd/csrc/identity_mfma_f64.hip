@@ -67,7 +67,7 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
     const int tiles_n = (N + DI_BN - 1) / DI_BN;
     int tm, tn;
     // place in the tile order, and which k range of it (tail split, see choose_tail_split)
-    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
     if (tail_part) {
         const int rel = block - args.tail_base;
@@ -270,8 +270,9 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
         b.kchunk = t.chunk;
         launch_grid = dim3((unsigned)t.grid, 1u);
     }
-    hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), launch_grid, dim3(DI_NT), LDS, s, b);
-    return hipGetLastError();
+    return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
+        hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(n, launch_grid.y), dim3(DI_NT), LDS, s, b);
+    });
 }
 
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s)

@@ -112,7 +112,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int tiles_n = (N + D_BN - 1) / D_BN;
     int tm, tn;
     // place in the tile order, and which k range of it (tail split, see choose_tail_split)
-    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
     if (tail_part) {
         const int rel = block - args.tail_base;
@@ -360,15 +360,18 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 }
 
 template <int TASK, bool TRANS>
-static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
+static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &args, dim3 whole, hipStream_t s)
 {
-    switch (form) {
-    case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-    case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-    case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-    default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-    }
-    return hipGetLastError();
+    MmlikeArgsF64 a = args;
+    return launch_row_of_blocks(a, whole.x, D_NT, [&](unsigned n) {
+        const dim3 grid(n, whole.y);
+        switch (form) {
+        case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+        default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+        }
+    });
 }
 
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s)

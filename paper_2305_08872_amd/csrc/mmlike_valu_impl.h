@@ -127,7 +127,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int tiles_n = (N + BN - 1) / BN;
     int tm, tn;
     // place in the tile order, and which k range of it (see launch_one)
-    int block = (int)blockIdx.x, ksplit_idx = (int)blockIdx.y;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
     if (tail_part) {
         const int rel = block - args.tail_base;
@@ -504,11 +504,13 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
     auto launch = [&](int64_t n_blocks, int n_splits) {
-        const dim3 grid((unsigned)n_blocks, (unsigned)n_splits), block(64 * NW);
-        if (a.transA || a.transB)
-            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
-        else
-            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+        (void)launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
+            const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
+            if (a.transA || a.transB)
+                hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+            else
+                hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+        });
     };
     // a last round of workgroups that would leave most of the chip idle: its tiles are launched
     // once per k range instead (choose_tail_split in amulet_internal.h)

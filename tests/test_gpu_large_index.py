@@ -110,3 +110,57 @@ def test_elementwise_threshold_and_transposed_operands_beyond_2_31(am):
                                             np.zeros((len(ROWS), N), np.float32),
                                             thres_form=3, trans_a=True, trans_b=True)
     assert_parity_f32(R, R_ref, ab, None, what="general boost, 2^31+ outputs")
+
+
+MAX_DIM = 2 ** 31 - 2 ** 16 - 1      # the largest extent the library accepts
+
+
+@pytest.mark.parametrize("task", [1, 3])
+def test_largest_accepted_row_count(am, task):
+    """M at the library's limit (N = 1, K = 2): 67 million row tiles in one launch.  Operands are
+    written on the device from a short period pattern; sampled rows, the last one among them,
+    are checked against the oracle."""
+    M, N, K = MAX_DIM, 1, 2
+    lib = am.load_library()
+    assert lib.amulet_mmlike_f32(task, M + 1, N, K, 16, K, 16, N, 16, 16, N, None) == -7   # one more is refused
+    period = torch.tensor([[-3.0, 0.5], [1.0, 2.0], [2.5, -1.0], [0.25, 4.0], [7.0, 0.0], [-0.5, -0.5], [1.5, 3.0]],
+                          device="cuda")
+    reps = (M + 6) // 7
+    dA = period.repeat(reps, 1)[:M]
+    B = np.array([[2.0], [1.5]], np.float32)
+    params = np.array([[1.0], [0.25]], np.float32)[: (2 if task == 1 else 1)]
+    dR = torch.full((M, N), 1.0, dtype=torch.float32, device="cuda")
+    print("max M", task, M, N, K, flush=True)
+    am.amulet_mmlike_f32(task, dA, dev(B), dev(params), dR)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 2, 3, 4, 5, 6, 7, 2 ** 24 + 1, 2 ** 30 + 5, M - 8, M - 3, M - 2, M - 1])
+    idx = torch.from_numpy(rows).cuda()
+    R = dR[idx].cpu().numpy()
+    A_rows = dA[idx].cpu().numpy()
+    assert np.array_equal(A_rows, period.cpu().numpy()[rows % 7])      # the rows are what the pattern says
+    R_ref, ab, _ = oracle.mmlike_f32(task, A_rows, B, params, np.ones((len(rows), 1), np.float32))
+    assert np.array_equal(R, R_ref)                                     # two exact products per output
+    assert float(dR.sum(dtype=torch.float64)) == float(M) + (M // 7) * float((R_ref[:7] - 1).sum()) + \
+        float((R_ref[:M % 7] - 1).sum())
+
+
+def test_largest_accepted_column_count(am):
+    """N at the library's limit (M = 1, K = 3): 8.4 million column tiles, thresholds and discounts
+    per column."""
+    M, N, K = 1, MAX_DIM, 3
+    pat = torch.tensor([1.0, -2.0, 0.5, 3.0, 0.25, -1.5, 2.0, 4.0, -0.75, 1.25, 6.0], device="cuda")
+    reps = (N + 10) // 11
+    dB = torch.stack([pat.repeat(reps)[:N], pat.flip(0).repeat(reps)[:N], (pat * 0.5).repeat(reps)[:N]])
+    dP = torch.stack([(pat * 0.5).repeat(reps)[:N], (pat.abs() / 8).repeat(reps)[:N]]).contiguous()
+    A = np.array([[2.0, -1.0, 4.0]], np.float32)
+    dR = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    print("max N", M, N, K, flush=True)
+    am.amulet_mmlike_f32(1, dev(A), dB, dP, dR)
+    torch.cuda.synchronize()
+    cols = np.array([0, 1, 5, 10, 11, 255, 256, 2 ** 24 + 3, 2 ** 30 + 7, N - 257, N - 256, N - 2, N - 1])
+    idx = torch.from_numpy(cols).cuda()
+    R = dR[:, idx].cpu().numpy()
+    B_cols = dB[:, idx].cpu().numpy()
+    P_cols = dP[:, idx].cpu().numpy()
+    R_ref, ab, _ = oracle.mmlike_f32(1, A, B_cols, P_cols, np.zeros((1, len(cols)), np.float32))
+    assert_parity_f32(R, R_ref, ab, None, what="max N")
