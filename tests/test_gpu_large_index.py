@@ -164,3 +164,46 @@ def test_largest_accepted_column_count(am):
     P_cols = dP[:, idx].cpu().numpy()
     R_ref, ab, _ = oracle.mmlike_f32(1, A, B_cols, P_cols, np.zeros((1, len(cols)), np.float32))
     assert_parity_f32(R, R_ref, ab, None, what="max N")
+
+
+def test_largest_accepted_row_count_other_kernels(am):
+    """The same extent through the other kernel families: identity on the matrix cores, the
+    fp64 vector-ALU kernel and the int8 join count (each with its own workgroup size, so its own
+    number of launches)."""
+    M = MAX_DIM
+    rows = np.array([0, 1, 2, 3, 4, 5, 6, 7, 2 ** 24 + 1, 2 ** 30 + 5, M - 130, M - 8, M - 3, M - 2, M - 1])
+    idx = torch.from_numpy(rows).cuda()
+    period = torch.tensor([[-3.0, 0.5], [1.0, 2.0], [2.5, -1.0], [0.25, 4.0], [7.0, 0.0], [-0.5, -0.5], [1.5, 3.0]],
+                          device="cuda")
+    reps = (M + 6) // 7
+    # fp32 identity (matrix cores)
+    dA = period.repeat(reps, 1)[:M]
+    B = np.array([[2.0], [1.5]], np.float32)
+    dR = torch.full((M, 1), 1.0, dtype=torch.float32, device="cuda")
+    print("max M identity f32", flush=True)
+    am.amulet_mmlike_f32(0, dA, dev(B), None, dR)
+    torch.cuda.synchronize()
+    R_ref, _, _ = oracle.mmlike_f32(0, dA[idx].cpu().numpy(), B, None, np.ones((len(rows), 1), np.float32))
+    assert np.array_equal(dR[idx].cpu().numpy(), R_ref)
+    del dR, dA
+    # fp64 discount
+    dA64 = period.double().repeat(reps, 1)[:M]
+    dR64 = torch.full((M, 1), 1.0, dtype=torch.float64, device="cuda")
+    print("max M discount f64", flush=True)
+    am.amulet_mmlike_f64(1, dA64, dev(B.astype(np.float64)), dev(np.array([1.0])), dev(np.array([0.25])), dR64)
+    torch.cuda.synchronize()
+    R_ref, _, _ = oracle.mmlike_f64_general(1, dA64[idx].cpu().numpy(), B.astype(np.float64), np.array([1.0]),
+                                            np.array([0.25]), np.ones((len(rows), 1)))
+    assert np.array_equal(dR64[idx].cpu().numpy(), R_ref)
+    del dR64, dA64
+    # int8 join count
+    pat8 = torch.tensor([[3, -1], [0, 7], [-128, 127], [5, 5], [1, 0], [-7, 2], [100, -100]], dtype=torch.int8,
+                        device="cuda")
+    dA8 = pat8.repeat(reps, 1)[:M]
+    B8 = np.array([[2], [-3]], np.int8)
+    dR8 = torch.full((M, 1), 7, dtype=torch.int32, device="cuda")
+    print("max M count_i8", flush=True)
+    am.amulet_count_i8(dA8, dev(B8), dR8)
+    torch.cuda.synchronize()
+    R_ref, _ = oracle.count_i8(dA8[idx].cpu().numpy(), B8, np.full((len(rows), 1), 7, np.int32))
+    assert np.array_equal(dR8[idx].cpu().numpy(), R_ref)
