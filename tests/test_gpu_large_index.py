@@ -207,3 +207,26 @@ def test_largest_accepted_row_count_other_kernels(am):
     torch.cuda.synchronize()
     R_ref, _ = oracle.count_i8(dA8[idx].cpu().numpy(), B8, np.full((len(rows), 1), 7, np.int32))
     assert np.array_equal(dR8[idx].cpu().numpy(), R_ref)
+
+
+def test_largest_accepted_inner_dimension(am):
+    """K at the library's limit (M = N = 1): one tile whose K loop is split over a thousand
+    workgroups.  COUNT_GT with one product in a thousand above the threshold, so the count
+    (about 2.1 million) is exact in fp32 and has a closed form."""
+    K = MAX_DIM
+    pat = torch.full((1000,), 0.5, device="cuda")
+    pat[137] = 2.0
+    dA = pat.repeat((K + 999) // 1000)[:K].view(1, K)
+    dB = torch.ones((K, 1), device="cuda")
+    dR = torch.zeros((1, 1), device="cuda")
+    print("max K", K, flush=True)
+    am.amulet_mmlike_f32(3, dA, dB, dev(np.array([[1.0]], np.float32)), dR)
+    torch.cuda.synchronize()
+    expected = K // 1000 + (1 if K % 1000 > 137 else 0)       # the k with k % 1000 == 137
+    assert expected < 2 ** 24
+    assert float(dR[0, 0]) == float(expected)
+    # the oracle on the first and the last 5000 k agrees with the closed form used above
+    for k0 in (0, K - 5000):
+        A_part = dA[:, k0:k0 + 5000].cpu().numpy()
+        R_ref, _, _ = oracle.mmlike_f32(3, A_part, np.ones((5000, 1), np.float32), np.array([[1.0]], np.float32))
+        assert R_ref[0, 0] == sum(1 for k in range(k0, k0 + 5000) if k % 1000 == 137)
