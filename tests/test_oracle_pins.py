@@ -344,3 +344,27 @@ def test_empty_K_and_threads_do_not_change_result():
     R4, ab4, u4 = oracle.mmlike_f32(oracle.DISCOUNT, A, B, P, threads=4)
     assert u1 == 1 and u4 == 4
     assert np.array_equal(R1, R4) and np.array_equal(ab1, ab4)
+
+
+def test_subnormal_products_are_kept_not_flushed():
+    """Powers of two, so every value below is exact and known without computing it:
+    2^-100 * 2^-40 = 2^-140 is a subnormal fp32 number, 2^-100 * 2^-60 = 2^-160 rounds to 0.
+    The predicate sees the subnormal product (it is > 0 and > 2^-141, not > 2^-139), the sums
+    keep it, and the fp64 oracle does the same at 2^-1040."""
+    A = np.array([[2.0 ** -100, 2.0 ** -100]], np.float32)
+    B = np.array([[2.0 ** -40, 2.0 ** -40, 2.0 ** -40], [2.0 ** -60, 2.0 ** -60, 2.0 ** -60]], np.float32)
+    thres = np.array([0.0, 2.0 ** -141, 2.0 ** -139], np.float32)
+    cnt, _, _ = oracle.mmlike_f32(3, A, B, thres[None, :])
+    assert cnt.tolist() == [[1.0, 1.0, 0.0]]
+    ident, ab, _ = oracle.mmlike_f32(0, A, B, None)
+    assert ident.tolist() == [[2.0 ** -140] * 3] and ab.tolist() == [[2.0 ** -140] * 3]
+    dis = np.array([0.5, 0.5, 0.5], np.float32)
+    disc, _, _ = oracle.mmlike_f32(1, A, B, np.stack([thres, dis]))
+    assert disc.tolist() == [[2.0 ** -141, 2.0 ** -141, 2.0 ** -140]]
+    A64 = np.array([[2.0 ** -1000]])
+    B64 = np.array([[2.0 ** -40, 2.0 ** -40]])
+    t64 = np.array([2.0 ** -1041, 2.0 ** -1039])
+    c64, _, _ = oracle.mmlike_f64_general(3, A64, B64, t64, None, None)
+    assert c64.tolist() == [[1.0, 0.0]]
+    i64, _, _ = oracle.mmlike_f64_general(0, A64, B64, None, None, None)
+    assert i64.tolist() == [[2.0 ** -1040, 2.0 ** -1040]]
