@@ -85,10 +85,9 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
     }
 }
 
-// TRANS = true compiles in the transposed operand layouts (a(i,k) at A[k*lda + i], b(k,j) at
-// B[j*ldb + k], selected at run time by args.transA / args.transB); TRANS = false keeps their
-// addressing state out of the row-major kernels.
-template <int TASK, int TF, bool TRANS>
+// TRANS (bit 0: a(i,k) at A[k*lda + i], bit 1: b(k,j) at B[j*ldb + k]) is a compile-time choice:
+// each layout's addressing state would otherwise cost the others scalar registers in the hot loop.
+template <int TASK, int TF, int TRANS>
 __global__ void __launch_bounds__(D_NT)
 mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 {
@@ -103,7 +102,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int M = args.M, N = args.N;
     int K = args.K;
     const bool VEC = args.vec != 0;   // B and R rows are 16-byte aligned
-    const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
+    constexpr bool transA = (TRANS & 1) != 0, transB = (TRANS & 2) != 0;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
@@ -259,24 +258,25 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int n_tiles = full_tiles + (tail ? 1 : 0);
 
     // A values of the chunk of KA k starting at kn, for the wave's D_TM rows, into SGPR pairs
-    d2_a8 a_next[D_TM];
+    // (row-major A: a_next[r] holds row r's KA values; transposed A: a_next_t[kk] holds the four
+    // rows of k = kn + kk, exactly as loaded: re-sorting them at fetch time would make every fetch
+    // wait for its own loads instead of letting them land during the chunk's arithmetic)
+    d2_a8 a_next[transA ? 1 : D_TM];
+    d4_a8 a_next_t[transA ? KA : 1];
     auto fetch_a = [&](int kn) {
-        if (!transA) {
+        if constexpr (!transA) {
 #pragma unroll
             for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r] + kn);
         } else if (rows_full) {
             // the 4 rows of one k are contiguous in the transposed storage
 #pragma unroll
-            for (int kk = 0; kk < KA; ++kk) {
-                const d4_a8 t = *(sptr_d4)(As + (int64_t)(kn + kk) * args.lda + arow[0]);
-#pragma unroll
-                for (int r = 0; r < D_TM; ++r) a_next[r][kk] = t[r];
-            }
+            for (int kk = 0; kk < KA; ++kk)
+                a_next_t[kk] = *(sptr_d4)(As + (int64_t)(kn + kk) * args.lda + arow[0]);
         } else {
 #pragma unroll
             for (int kk = 0; kk < KA; ++kk)
 #pragma unroll
-                for (int r = 0; r < D_TM; ++r) a_next[r][kk] = As[(int64_t)(kn + kk) * args.lda + arow[r]];
+                for (int r = 0; r < D_TM; ++r) a_next_t[kk][r] = As[(int64_t)(kn + kk) * args.lda + arow[r]];
         }
     };
     load_tile(full_tiles > 0 ? D_BK : tail);
@@ -297,9 +297,15 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 d2 b[KA];
 #pragma unroll
                 for (int kk = 0; kk < KA; ++kk) b[kk] = *(const d2 *)(bs + (kc + kk) * D_BN);
-                d2_a8 a[D_TM];
+                d2_a8 a[transA ? 1 : D_TM];
+                d4_a8 a_t[transA ? KA : 1];
+                if constexpr (!transA) {
 #pragma unroll
-                for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                    for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < KA; ++kk) a_t[kk] = a_next_t[kk];
+                }
                 // the scalar fetch of the next chunk goes out right after the LDS wait (scalar
                 // loads return out of order: any later LDS wait would drain them too)
                 __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
@@ -314,7 +320,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 for (int kk = 0; kk < KA; ++kk) {
                     double ak[D_TM];
 #pragma unroll
-                    for (int r = 0; r < D_TM; ++r) ak[r] = a[r][kk];
+                    for (int r = 0; r < D_TM; ++r) ak[r] = transA ? a_t[transA ? kk : 0][r] : a[transA ? 0 : r][kk];
                     fold_rows<TASK>(ak, b[kk], th, q, acc);
                 }
             }
@@ -359,7 +365,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     }
 }
 
-template <int TASK, bool TRANS>
+template <int TASK, int TRANS>
 static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &args, dim3 whole, hipStream_t s)
 {
     MmlikeArgsF64 a = args;
@@ -372,6 +378,17 @@ static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &args, dim3 whol
         default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS>), grid, dim3(D_NT), 0, s, a); break;
         }
     });
+}
+
+template <int TASK>
+static hipError_t launch_f64_layout(int trans, int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
+{
+    switch (trans) {
+    case 0: return launch_f64_form<TASK, 0>(form, a, grid, s);
+    case 1: return launch_f64_form<TASK, 1>(form, a, grid, s);
+    case 2: return launch_f64_form<TASK, 2>(form, a, grid, s);
+    default: return launch_f64_form<TASK, 3>(form, a, grid, s);
+    }
 }
 
 hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s)
@@ -408,14 +425,11 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
         b.kchunk = t.chunk;
         grid = dim3((unsigned)t.grid, 1u);
     }
-    const bool trans = a.transA || a.transB;
+    const int trans = (a.transA ? 1 : 0) | (a.transB ? 2 : 0);
     switch (task) {
-    case TASK_DISCOUNT: return trans ? launch_f64_form<TASK_DISCOUNT, true>(form, b, grid, s)
-                                     : launch_f64_form<TASK_DISCOUNT, false>(form, b, grid, s);
-    case TASK_BOOST: return trans ? launch_f64_form<TASK_BOOST, true>(form, b, grid, s)
-                                  : launch_f64_form<TASK_BOOST, false>(form, b, grid, s);
-    case TASK_COUNT_GT: return trans ? launch_f64_form<TASK_COUNT_GT, true>(form, b, grid, s)
-                                     : launch_f64_form<TASK_COUNT_GT, false>(form, b, grid, s);
+    case TASK_DISCOUNT: return launch_f64_layout<TASK_DISCOUNT>(trans, form, b, grid, s);
+    case TASK_BOOST: return launch_f64_layout<TASK_BOOST>(trans, form, b, grid, s);
+    case TASK_COUNT_GT: return launch_f64_layout<TASK_COUNT_GT>(trans, form, b, grid, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -98,7 +98,7 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
     }
 }
 
-template <int TASK, int TF, bool TRANS, int TM, int NG, int NW, int BK, int KA>
+template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA>
 __global__ void __launch_bounds__(64 * NW)
 mmlike_valu_kernel(const MmlikeArgs args)
 {
@@ -144,9 +144,10 @@ mmlike_valu_kernel(const MmlikeArgs args)
     // Wave-uniform row offsets, clamped so edge waves read valid rows.  a(i,k) lives at
     // A[i*lda + k], or at A[k*lda + i] when A is stored transposed (the [k][i]-indexed
     // variant of paper Sec. 6.3): element offset = arow[r] + k * kstride.
-    // TRANS = false compiles the transposed paths out: their addressing state would otherwise
-    // cost the row-major kernels scalar registers in the hot loop.
-    const bool transA = TRANS && args.transA != 0, transB = TRANS && args.transB != 0;
+    // TRANS (bit 0: A transposed, bit 1: B transposed) is a compile-time choice: each layout's
+    // addressing state would otherwise cost the others scalar registers in the hot loop (one
+    // kernel serving both transposed operands at run time spilled 30 of them).
+    constexpr bool transA = (TRANS & 1) != 0, transB = (TRANS & 2) != 0;
     const int64_t kstride = transA ? args.lda : 1;
     // Split K (every tile when gridDim.y > 1, chosen by the host for problems with too few tiles
     // to fill the chip; else the tail blocks): this workgroup sums k in [kb, kb + kchunk) only
@@ -160,9 +161,19 @@ mmlike_valu_kernel(const MmlikeArgs args)
     }
     const bool rows_full = row0 + TM <= M;
     auto rowc = [&](int r) { const int row = row0 + r; return row < M ? row : M - 1; };
-    int64_t arow[TM];
+    // Row-major A: one 64-bit offset per row.  Transposed A: the wave's rows are neighbours in
+    // memory, so the first row's index and the count of rows that exist say it all (row r of
+    // the micro-tile reads row min(r, last valid) of them); eight scalar registers fewer.
+    int64_t arow[transA ? 1 : TM];
+    const int arow0 = row0 < M ? row0 : M - 1;
+    const int last_valid = (M - arow0 < TM ? M - arow0 : TM) - 1;
+    auto trow = [&](int r) { return arow0 + (r < last_valid ? r : last_valid); };   // transposed A: row index
+    if constexpr (!transA) {
 #pragma unroll
-    for (int r = 0; r < TM; ++r) arow[r] = transA ? (int64_t)rowc(r) : (int64_t)rowc(r) * args.lda;
+        for (int r = 0; r < TM; ++r) arow[r] = (int64_t)rowc(r) * args.lda;
+    } else {
+        arow[0] = 0;
+    }
 
     // Parameters held in registers for the whole K loop: the discount factor 1 - dis[j] per
     // column, and the threshold in the operand form TF (paper Sec. 6.3): thres[j] per column,
@@ -327,10 +338,17 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int n_tiles = full_tiles + (tail ? 1 : 0);
     constexpr int FLUSH_TILES = (FLUSH_K / BK) > 0 ? (FLUSH_K / BK) : 1;  // tiles per partial sum
 
-    // A values of the chunk of KA k starting at kn, for the wave's TM rows, into SGPRs.
+    // A values of the chunk of KA k starting at kn, for the wave's TM rows, into SGPRs: TM
+    // vectors of 4.  Row-major A: vector r holds row r's KA values.  Transposed A: vector
+    // kk * (TM / 4) + v holds rows 4v .. 4v + 3 of k = kn + kk, exactly as loaded; re-sorting them
+    // at fetch time would make every fetch wait for its own loads instead of letting them land
+    // during the chunk's arithmetic.  a_of() names element (r, kk) of either arrangement.
     av_t a_next[TM];
+    auto a_of = [](const av_t (&v)[TM], int r, int kk) -> float {
+        return transA ? v[kk * (TM / 4) + r / 4][r % 4] : v[r][kk];
+    };
     auto fetch_a = [&](int kn) {
-        if (!transA) {
+        if constexpr (!transA) {
 #pragma unroll
             for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
         } else if (rows_full) {
@@ -339,16 +357,14 @@ mmlike_valu_kernel(const MmlikeArgs args)
             for (int kk = 0; kk < KA; ++kk)
 #pragma unroll
                 for (int v = 0; v < TM / 4; ++v) {
-                    const av_t t = *(sptr_av)(As + (int64_t)(kn + kk) * args.lda + arow[4 * v]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) a_next[4 * v + e][kk] = t[e];
+                    a_next[kk * (TM / 4) + v] = *(sptr_av)(As + (int64_t)(kn + kk) * args.lda + arow0 + 4 * v);
                 }
         } else {
 #pragma unroll
             for (int kk = 0; kk < KA; ++kk)
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
-                    a_next[r][kk] = As[(int64_t)(kn + kk) * args.lda + arow[r]];
+                    a_next[kk * (TM / 4) + r / 4][r % 4] = As[(int64_t)(kn + kk) * args.lda + trow(r)];
         }
     };
     load_tile(full_tiles > 0 ? BK : tail);
@@ -409,7 +425,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                         for (int g = 0; g < NG; ++g) {
                             float t4[4];
                             thres4(r, g, t4);
-                            fold4<TASK>(a[r][kk], b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
+                            fold4<TASK>(a_of(a, r, kk), b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
                         }
                         // At most 4 rows of one k between fences: left alone, the scheduler may
                         // gather the compares of the whole chunk, and their lane masks (a scalar
@@ -427,7 +443,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 float a1[TM];
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
-                    a1[r] = As[arow[r] + (int64_t)(k0 + kk) * kstride];
+                    a1[r] = transA ? As[(int64_t)(k0 + kk) * args.lda + trow(r)] : As[arow[transA ? 0 : r] + k0 + kk];
                 f4 b[NG];
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
@@ -515,10 +531,12 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     auto launch = [&](int64_t n_blocks, int n_splits) {
         (void)launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
-            if (a.transA || a.transB)
-                hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, true, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
-            else
-                hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, false, TM, NG, NW, BK, KA>), grid, block, 0, s, b);
+            switch ((a.transA ? 1 : 0) | (a.transB ? 2 : 0)) {
+            case 0: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
+            case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
+            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
+            default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
+            }
         });
     };
     // a last round of workgroups that would leave most of the chip idle: its tiles are launched
