@@ -4,6 +4,7 @@
 #define AMULET_INTERNAL_H
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 
 namespace amulet {
@@ -60,15 +61,15 @@ __host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, in
 // Compute units of the current device (256 on MI355X), asked once per device.
 inline int compute_units()
 {
-    static int cached[16] = {0};
+    static std::atomic<int> cached[16];   // zero-initialised; several host threads may ask at once
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // A grid dimension holds at most 2^32 - 1 work-items (workgroups x threads), fewer than the
