@@ -423,8 +423,7 @@ int amulet_mmlike_f32(int task, int64_t M, int64_t N, int64_t K, const float *A,
 int amulet_pitch_collides(int64_t ld, int elem_bytes)
 {
     if (ld <= 0 || (elem_bytes != 1 && elem_bytes != 4 && elem_bytes != 8)) return 0;
-    const int64_t pitch = ld * elem_bytes;
-    return (pitch >= 65536 && pitch % 32768 == 0) ? 1 : 0;
+    return pitch_collides(ld, elem_bytes) ? 1 : 0;
 }
 
 int64_t amulet_packed_ld(int64_t cols, int elem_bytes)

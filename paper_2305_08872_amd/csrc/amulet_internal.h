@@ -72,6 +72,15 @@ inline int compute_units()
     return n;
 }
 
+// Rows `ld` elements of `elem_bytes` apart collide in the memory system (same L2 sets, same
+// channel) when their pitch is a multiple of 32 KiB of at least 64 KiB (measured on the vector-ALU
+// kernels; the exported amulet_pitch_collides is this rule).
+inline bool pitch_collides(int64_t ld, int elem_bytes)
+{
+    const int64_t pitch = ld * elem_bytes;
+    return ld > 0 && pitch >= 65536 && pitch % 32768 == 0;
+}
+
 // A grid dimension holds at most 2^32 - 1 work-items (workgroups x threads), fewer than the
 // 2^31 - 1 workgroups a tile order can have: a longer row of workgroups goes out as several
 // launches, each told in `args.block_base` where in the row it starts (the kernels add it to

@@ -98,10 +98,16 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
     }
 }
 
-template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA>
+// ALDS: the workgroup's rows of A go through LDS too (vector loads a whole tile ahead, then
+// broadcast reads), instead of through the scalar cache chunk by chunk.  Slightly more
+// registers and LDS traffic; used when the row pitch of A collides (amulet_pitch_collides):
+// the scalar path fetches each 128-byte line of A in eight pieces, and when the lines of a
+// workgroup's 32 rows all fall into the same L2 sets they are evicted between the pieces.
+template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA, bool ALDS>
 __global__ void __launch_bounds__(64 * NW)
 mmlike_valu_kernel(const MmlikeArgs args)
 {
+    static_assert(!ALDS || (TRANS == 0 && TM == 4 && NG == 1), "A through LDS: row-major operands, 4 x 4 micro-tile");
     typedef typename AccT<TASK>::type acc_t;
     static_assert(KA == 4 && TM % 4 == 0, "a transposed A is fetched as 4 rows x 4 k blocks");
     constexpr int BN = 256 * NG;           // tile columns
@@ -115,6 +121,10 @@ mmlike_valu_kernel(const MmlikeArgs args)
     typedef const __attribute__((address_space(4))) av_t *sptr_av;
 
     __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+    constexpr int A_ROWS = NW * TM, A_PITCH = BK + 4;       // rows of the workgroup; padded row of the LDS A tile
+    constexpr int A_F4 = A_ROWS * BK / 4;                   // float4 slots of one A tile (<= NT)
+    static_assert(A_F4 <= NT, "one staging slot per thread at most");
+    __shared__ __attribute__((aligned(16))) float Asl[ALDS ? 2 : 1][ALDS ? A_ROWS : 1][ALDS ? A_PITCH : 4];
 
     const int M = args.M, N = args.N;
     int K = args.K;
@@ -261,7 +271,30 @@ mmlike_valu_kernel(const MmlikeArgs args)
     const int tcol = threadIdx.x % BN;
     const int tk = (threadIdx.x / BN) * KPT;
     const float *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
+    // A tile staging (ALDS): thread t < A_F4 stages float4 slot (row t / (BK / 4), k quad t % (BK / 4))
+    const int a_sr = threadIdx.x / (BK / 4), a_sq = (threadIdx.x % (BK / 4)) * 4;
+    const float *asrc = nullptr;
+    f4 a_stage = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (ALDS) {
+        const int wg_row0 = tm * A_ROWS;
+        const int arow_c = wg_row0 + a_sr < M ? wg_row0 + a_sr : M - 1;   // rows past M are never written back
+        asrc = args.A + (ksplit ? (int64_t)ksplit_idx * args.kchunk : 0) + (int64_t)arow_c * args.lda + a_sq;
+    }
     auto load_tile = [&](int krows) {
+        if constexpr (ALDS) {
+            if (threadIdx.x < A_F4) {
+                if (krows == BK) {
+                    a_stage = args.vecA ? *(const f4 *)asrc : (f4)*(const f4_any *)asrc;
+                } else {
+                    a_stage = f4{0.0f, 0.0f, 0.0f, 0.0f};
+                    if (a_sq + 0 < krows) a_stage.x = asrc[0];
+                    if (a_sq + 1 < krows) a_stage.y = asrc[1];
+                    if (a_sq + 2 < krows) a_stage.z = asrc[2];
+                    if (a_sq + 3 < krows) a_stage.w = asrc[3];
+                }
+                asrc += BK;
+            }
+        }
         if (transB) {
             const bool colok = col0 + tcol < N;
 #pragma unroll
@@ -309,6 +342,9 @@ mmlike_valu_kernel(const MmlikeArgs args)
     float *const bdst = &Bs[0][srow][(threadIdx.x % F4_PER_ROW) * 4];
     float *const btdst = &Bs[0][tk][tcol];
     auto store_tile = [&](int buf) {
+        if constexpr (ALDS) {
+            if (threadIdx.x < A_F4) *(f4 *)&Asl[buf][a_sr][a_sq] = a_stage;
+        }
         if (transB) {
 #pragma unroll
             for (int it = 0; it < LOADS; ++it)
@@ -369,7 +405,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     };
     load_tile(full_tiles > 0 ? BK : tail);
     store_tile(0);
-    if (full_tiles > 0) fetch_a(0);
+    if (!ALDS && full_tiles > 0) fetch_a(0);
     __syncthreads();
 
     const float *bs_lane = &Bs[0][0][lane * 4];
@@ -404,19 +440,25 @@ mmlike_valu_kernel(const MmlikeArgs args)
                     for (int g = 0; g < NG; ++g)
                         b[kk][g] = *(const f4 *)(bs + (kc + kk) * BN + g * 256);
                 av_t a[TM];
+                if constexpr (ALDS) {
+                    // the wave's four rows of this chunk: one broadcast 16-byte LDS read each
 #pragma unroll
-                for (int r = 0; r < TM; ++r) a[r] = a_next[r];
-                // ... and the scalar fetch of the next chunk's A values is issued only after
-                // that wait: scalar loads return out of order, so any later LDS wait would
-                // have to drain them too.  Here they have the whole chunk's arithmetic to land.
-                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), vmcnt and expcnt untouched
-                __builtin_amdgcn_sched_barrier(0);
-                {
-                    int kn = k0 + kc + KA;
-                    kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
-                    fetch_a(kn);
+                    for (int r = 0; r < TM; ++r) a[r] = *(const f4 *)&Asl[buf][wave * TM + r][kc];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < TM; ++r) a[r] = a_next[r];
+                    // ... and the scalar fetch of the next chunk's A values is issued only after
+                    // that wait: scalar loads return out of order, so any later LDS wait would
+                    // have to drain them too.  Here they have the whole chunk's arithmetic to land.
+                    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), vmcnt and expcnt untouched
+                    __builtin_amdgcn_sched_barrier(0);
+                    {
+                        int kn = k0 + kc + KA;
+                        kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
+                        fetch_a(kn);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kk = 0; kk < KA; ++kk) {
 #pragma unroll
@@ -443,7 +485,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
                 float a1[TM];
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
-                    a1[r] = transA ? As[(int64_t)(k0 + kk) * args.lda + trow(r)] : As[arow[transA ? 0 : r] + k0 + kk];
+                    a1[r] = ALDS ? Asl[ALDS ? buf : 0][ALDS ? wave * TM + r : 0][ALDS ? kk : 0]
+                                 : transA ? As[(int64_t)(k0 + kk) * args.lda + trow(r)] : As[arow[transA ? 0 : r] + k0 + kk];
                 f4 b[NG];
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
@@ -528,14 +571,24 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         splits = (int)((a.K + chunk - 1) / chunk);
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    // rows of a row-major A whose pitch collides in the memory system go through LDS
+    const bool a_through_lds = !a.transA && !a.transB && pitch_collides(a.lda, 4);
     auto launch = [&](int64_t n_blocks, int n_splits) {
         (void)launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
             switch ((a.transA ? 1 : 0) | (a.transB ? 2 : 0)) {
-            case 0: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
-            case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
-            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
-            default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA>), grid, block, 0, s, b); break;
+            case 0:
+                if constexpr (TM == 4 && NG == 1) {
+                    if (a_through_lds) {
+                        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, true>), grid, block, 0, s, b);
+                        break;
+                    }
+                }
+                hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b);
+                break;
+            case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
+            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
+            default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
             }
         });
     };

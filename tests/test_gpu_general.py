@@ -207,6 +207,35 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
         assert_parity_f32(R, R_ref, ab, R_in, what="identity tail split shape %d" % shape)
 
 
+@pytest.mark.parametrize("task", TASKS)
+def test_rows_of_A_with_a_colliding_pitch_go_through_lds(am, task):
+    """A row-major A whose row pitch is a multiple of 32 KiB (here 64 KiB: a view of a wider
+    array) takes the kernel variant that stages A through LDS.  Every shape (those without
+    the variant run their usual kernel), every threshold form, ragged M, N and K, a K
+    remainder, a split K (few tiles, long K) and a split last round; A unaligned as well."""
+    cases = [(70, 300, 37, 0), (129, 1030, 77, 0), (33, 513, 100, 1), (3, 5, 2, 0), (64, 512, 1100, 0),
+             (770, 6100, 600, 0)]
+    for idx, (M, N, K, off) in enumerate(cases):
+        form = idx % 4 if task else 0
+        As, Bs, th, dis, R_in = make_case(task, form, False, False, M, N, K, 7300 + 10 * task + idx)
+        R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form)
+        wide = torch.zeros((M * 16384 + 4,), device="cuda")[off:off + M * 16384].view(M, 16384)   # pitch 64 KiB
+        dA = wide[:, :K]
+        dA.copy_(dev(As))
+        assert am.amulet_pitch_collides(dA.stride(0) if M > 1 else 16384, 4)
+        for shape in ((-1, 4, 5, 0, 1, 2) if idx < 5 else (-1, 4, 5)):
+            dR = dev(R_in)
+            print("A through LDS", task, form, shape, M, N, K, off, flush=True)
+            am.amulet_mmlike_f32_general(task, dA, dev(Bs), dev(th) if task else None, dev(dis) if task == 1 else None,
+                                         dR, thres_form=form, shape=shape)
+            torch.cuda.synchronize()
+            R = dR.cpu().numpy()
+            if task == 3:
+                assert np.array_equal(R, R_ref), (task, form, shape, M, N, K)
+            else:
+                assert_parity_f32(R, R_ref, ab, R_in, what="A through LDS task %d shape %d %dx%dx%d" % (task, shape, M, N, K))
+
+
 def test_compute_calls_can_be_captured_in_a_graph(am):
     """Compute calls only enqueue kernels on the caller's stream (no allocation, no sync, no
     memset), so a sequence of them can be captured once and replayed: three tasks of different
