@@ -47,9 +47,7 @@ static int n_shapes(int task)
 // staging is the measured best at every size; of its two workgroup sizes the
 // 8-wave one (32 x 256) is ahead by 2-9 % once there are two such tiles per
 // compute unit (or a long K to split, see below), the 4-wave one (16 x 256) below that.
-// `a_collides`: whether the rows of A, as the call passes them, collide (-1: not known, take a
-// contiguous A of this K).
-static int default_shape(int task, int64_t M, int64_t N, int64_t K, int a_collides = -1)
+static int default_shape(int task, int64_t M, int64_t N, int64_t K)
 {
     // Matrix cores.  Fewer 128 x 256 tiles than compute units: the register-staged 128 x 128 tile
     // with 8 waves (twice the workgroups; 2048^2 x 4096: 945 against 787 TOP/s).  Else operands
@@ -67,25 +65,22 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K, int a_collid
     // one even at 8192^3; the selector tries both)
     if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;
     // ... or, with fewer tiles, when K is long (from 8192 on) and the launcher's K split makes up
-    // the number (4096 x 512 x 8192: 31.0 against 29.2 TFLOP/s; at K <= 4096 the 4-wave tile
-    // stays ahead, 1536^2 x 4096: 28.5 against 27.2), unless many rows of a contiguous A of this
-    // K would collide (amulet_pitch_collides): the 32 rows of the larger tile then collide twice
-    // as often (4096 x 512 x 32768 in place: 20.9 against 26.8; 512 x 4096 x 32768: 30.5 against 27.8)
+    // the number (4096 x 512 x 8192: 31.0 against 29.2 TFLOP/s, 4096 x 512 x 32768: 31.3 against
+    // 26.6; at K <= 4096 the 4-wave tile stays ahead, 1536^2 x 4096: 28.5 against 27.2)
     const int64_t tiles32 = ((M + 31) / 32) * ((N + 255) / 256);
     if (tiles32 >= 512) return VALU_TILES + 1;
-    const bool collides = a_collides < 0 ? amulet_pitch_collides(K, 4) != 0 : a_collides != 0;
-    if (tiles32 >= 128 && K >= 8192 && !(M >= 2048 && collides)) return VALU_TILES + 1;
+    if (tiles32 >= 128 && K >= 8192) return VALU_TILES + 1;
     return VALU_TILES + 0;
 }
 
-static int lookup_shape(int task, int64_t M, int64_t N, int64_t K, int a_collides = -1)
+static int lookup_shape(int task, int64_t M, int64_t N, int64_t K)
 {
     {
         std::lock_guard<std::mutex> lock(g_sel_mutex);
         auto it = g_selected.find(SelKey(task, M, N, K));
         if (it != g_selected.end()) return it->second;
     }
-    return default_shape(task, M, N, K, a_collides);
+    return default_shape(task, M, N, K);
 }
 
 // text of the last HIP error a launch reported (diagnostics for AMULET_ERR_LAUNCH)
@@ -351,7 +346,7 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
     const int rc = check_mmlike(c);
     if (rc < 0) return rc;
     if (shape < 0)
-        shape = lookup_shape(task, M, N, K, trans_a ? 0 : amulet_pitch_collides(lda, 4));
+        shape = lookup_shape(task, M, N, K);
     else if (shape >= n_shapes(task))
         return AMULET_ERR_SHAPE;
     if (rc == 1) return AMULET_OK;

@@ -87,10 +87,14 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
 
 // TRANS (bit 0: a(i,k) at A[k*lda + i], bit 1: b(k,j) at B[j*ldb + k]) is a compile-time choice:
 // each layout's addressing state would otherwise cost the others scalar registers in the hot loop.
-template <int TASK, int TF, int TRANS>
+// ALDS: the workgroup's rows of A go through LDS (vector loads a whole tile ahead, broadcast
+// reads) instead of through the scalar cache; used when the row pitch of A collides in the memory
+// system (as in the fp32 kernels, where the reason is given).
+template <int TASK, int TF, int TRANS, bool ALDS>
 __global__ void __launch_bounds__(D_NT)
 mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 {
+    static_assert(!ALDS || TRANS == 0, "A through LDS: row-major operands");
     typedef typename AccD<TASK>::type acc_t;
     constexpr int D2_PER_ROW = D_BN / 2;                     // 16-byte slots in one LDS row
     constexpr int ROWS_PER_PASS = D_NT / D2_PER_ROW;         // 4
@@ -98,6 +102,10 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     constexpr int KA = 2;                                    // A is fetched two k at a time (one 16-byte scalar load per row)
 
     __shared__ __attribute__((aligned(16))) double Bs[2][D_BK][D_BN];
+    constexpr int A_ROWS = D_NW * D_TM, A_PITCH = D_BK + 2;   // rows of the workgroup; padded row of the LDS A tile
+    constexpr int A_D2 = A_ROWS * D_BK / 2;                   // 16-byte slots of one A tile
+    static_assert(A_D2 <= D_NT, "one staging slot per thread at most");
+    __shared__ __attribute__((aligned(16))) double Asl[ALDS ? 2 : 1][ALDS ? A_ROWS : 1][ALDS ? A_PITCH : 2];
 
     const int M = args.M, N = args.N;
     int K = args.K;
@@ -202,7 +210,28 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int tcol = threadIdx.x % D_BN;
     const int tk = (threadIdx.x / D_BN) * 8;
     const double *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
+    // A tile staging (ALDS): thread t < A_D2 stages slot (row t / (D_BK / 2), k pair t % (D_BK / 2))
+    const int a_sr = threadIdx.x / (D_BK / 2), a_sq = (threadIdx.x % (D_BK / 2)) * 2;
+    const double *asrc = nullptr;
+    d2 a_stage = {0.0, 0.0};
+    if constexpr (ALDS) {
+        const int wg_row0 = tm * A_ROWS;
+        const int arow_c = wg_row0 + a_sr < M ? wg_row0 + a_sr : M - 1;   // rows past M are never written back
+        asrc = args.A + (ksplit ? (int64_t)ksplit_idx * args.kchunk : 0) + (int64_t)arow_c * args.lda + a_sq;
+    }
     auto load_tile = [&](int krows) {
+        if constexpr (ALDS) {
+            if (threadIdx.x < A_D2) {
+                if (krows == D_BK) {
+                    a_stage = *(const d2_any *)asrc;
+                } else {
+                    a_stage = d2{0.0, 0.0};
+                    if (a_sq + 0 < krows) a_stage.x = asrc[0];
+                    if (a_sq + 1 < krows) a_stage.y = asrc[1];
+                }
+                asrc += D_BK;
+            }
+        }
         if (transB) {
             const bool colok = col0 + tcol < N;
 #pragma unroll
@@ -241,6 +270,9 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     double *const bdst = &Bs[0][srow][(threadIdx.x % D2_PER_ROW) * 2];
     double *const btdst = &Bs[0][tk][tcol];
     auto store_tile = [&](int buf) {
+        if constexpr (ALDS) {
+            if (threadIdx.x < A_D2) *(d2 *)&Asl[buf][a_sr][a_sq] = a_stage;
+        }
         if (transB) {
 #pragma unroll
             for (int it = 0; it < LOADS; ++it)
@@ -281,7 +313,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     };
     load_tile(full_tiles > 0 ? D_BK : tail);
     store_tile(0);
-    if (full_tiles > 0) fetch_a(0);
+    if (!ALDS && full_tiles > 0) fetch_a(0);
     __syncthreads();
 
     const double *bs_lane = &Bs[0][0][lane * 2];
@@ -299,23 +331,29 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 for (int kk = 0; kk < KA; ++kk) b[kk] = *(const d2 *)(bs + (kc + kk) * D_BN);
                 d2_a8 a[transA ? 1 : D_TM];
                 d4_a8 a_t[transA ? KA : 1];
-                if constexpr (!transA) {
+                if constexpr (ALDS) {
+                    // the wave's four rows of this chunk: one broadcast 16-byte LDS read each
 #pragma unroll
-                    for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                    for (int r = 0; r < D_TM; ++r) a[r] = *(const d2 *)&Asl[buf][wave * D_TM + r][kc];
                 } else {
+                    if constexpr (!transA) {
 #pragma unroll
-                    for (int kk = 0; kk < KA; ++kk) a_t[kk] = a_next_t[kk];
+                        for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                    } else {
+#pragma unroll
+                        for (int kk = 0; kk < KA; ++kk) a_t[kk] = a_next_t[kk];
+                    }
+                    // the scalar fetch of the next chunk goes out right after the LDS wait (scalar
+                    // loads return out of order: any later LDS wait would drain them too)
+                    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                    __builtin_amdgcn_sched_barrier(0);
+                    {
+                        int kn = k0 + kc + KA;
+                        kn = kn + KA <= K ? kn : k0 + kc;
+                        fetch_a(kn);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // the scalar fetch of the next chunk goes out right after the LDS wait (scalar
-                // loads return out of order: any later LDS wait would drain them too)
-                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-                __builtin_amdgcn_sched_barrier(0);
-                {
-                    int kn = k0 + kc + KA;
-                    kn = kn + KA <= K ? kn : k0 + kc;
-                    fetch_a(kn);
-                }
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kk = 0; kk < KA; ++kk) {
                     double ak[D_TM];
@@ -331,7 +369,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 double ak[D_TM];
 #pragma unroll
                 for (int r = 0; r < D_TM; ++r)
-                    ak[r] = transA ? As[(int64_t)(k0 + kk) * args.lda + arow[r]] : As[arow[r] + k0 + kk];
+                    ak[r] = ALDS ? Asl[ALDS ? buf : 0][ALDS ? wave * D_TM + r : 0][ALDS ? kk : 0]
+                                 : transA ? As[(int64_t)(k0 + kk) * args.lda + arow[r]] : As[arow[r] + k0 + kk];
                 fold_rows<TASK>(ak, b, th, q, acc);
             }
         }
@@ -365,17 +404,17 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     }
 }
 
-template <int TASK, int TRANS>
+template <int TASK, int TRANS, bool ALDS>
 static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &args, dim3 whole, hipStream_t s)
 {
     MmlikeArgsF64 a = args;
     return launch_row_of_blocks(a, whole.x, D_NT, [&](unsigned n) {
         const dim3 grid(n, whole.y);
         switch (form) {
-        case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-        case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-        case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS>), grid, dim3(D_NT), 0, s, a); break;
-        default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
+        default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
         }
     });
 }
@@ -384,10 +423,18 @@ template <int TASK>
 static hipError_t launch_f64_layout(int trans, int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
 {
     switch (trans) {
-    case 0: return launch_f64_form<TASK, 0>(form, a, grid, s);
-    case 1: return launch_f64_form<TASK, 1>(form, a, grid, s);
-    case 2: return launch_f64_form<TASK, 2>(form, a, grid, s);
-    default: return launch_f64_form<TASK, 3>(form, a, grid, s);
+    case 0: {
+        // Rows of a row-major A go through LDS when their pitch collides in the memory system, and
+        // in fp64 nearly always otherwise too: measured at 1024^3 ... 4096^3, A through LDS against
+        // A through the scalar cache: count 17.6-22.2 against 14.7-19.4 TFLOP/s, discount 11.8-13.7
+        // against 10.3-13.4; boost 14.0 / 15.6 against 12.7 / 14.9 at 1024^3 / 2048^3 but 15.8
+        // against 16.1 at 4096^3, so large boost problems keep the scalar path.
+        const bool lds = pitch_collides(a.lda, 8) || TASK != TASK_BOOST || (int64_t)a.M * a.N <= 2048LL * 2048LL;
+        return lds ? launch_f64_form<TASK, 0, true>(form, a, grid, s) : launch_f64_form<TASK, 0, false>(form, a, grid, s);
+    }
+    case 1: return launch_f64_form<TASK, 1, false>(form, a, grid, s);
+    case 2: return launch_f64_form<TASK, 2, false>(form, a, grid, s);
+    default: return launch_f64_form<TASK, 3, false>(form, a, grid, s);
     }
 }
 

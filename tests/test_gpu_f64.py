@@ -284,3 +284,22 @@ def test_identity_last_round_of_tiles_split_over_k(am):
     R_ref, ab, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
     R = run(am, 0, 0, dev(A), dev(B), th, dis, dev(R_in))
     check(R, R_ref, ab, R_in, 0, "f64 identity tail split")
+
+
+@pytest.mark.parametrize("task", [1, 2, 3])
+def test_rows_of_A_with_a_colliding_pitch_go_through_lds(am, task):
+    """A row-major fp64 A whose row pitch is a multiple of 32 KiB (a view of a wider array, pitch
+    64 KiB) takes the kernel variant that stages A through LDS: every threshold form, ragged
+    sizes, a K remainder, a split K and a split last round."""
+    cases = [(70, 300, 37), (129, 1030, 77), (3, 5, 2), (64, 256, 1100), (770, 3050, 600)]
+    for idx, (M, N, K) in enumerate(cases):
+        form = idx % 4
+        A, B, th, dis, R_in = make_case(form, M, N, K, seed=8300 + 10 * task + idx, exact=(task == 3))
+        R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th, dis if task == 1 else None, R_in, thres_form=form)
+        wide = torch.zeros((M, 8192), dtype=torch.float64, device="cuda")        # pitch 64 KiB
+        dA = wide[:, :K]
+        dA.copy_(dev(A))
+        assert am.amulet_pitch_collides(8192, 8)
+        print("f64 A through LDS", task, form, M, N, K, flush=True)
+        R = run(am, task, form, dA, dev(B), th, dis, dev(R_in))
+        check(R, R_ref, ab, R_in, task, "f64 A through LDS task %d form %d %dx%dx%d" % (task, form, M, N, K))
