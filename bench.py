@@ -374,7 +374,7 @@ def main() -> int:
 
     # register-only issue rate of this task's instruction mix on this chip (measured ceiling)
     probe = None
-    mix = {"identity": 0, "discount": 1, "boost": 2}.get(tname)
+    mix = {"identity": 0, "discount": 1, "boost": 2, "count_gt": 3}.get(tname)
     if mix is not None and am.amulet_shape_name(task, shape).startswith("valu"):
         pps = max(am.amulet_probe_valu(mix, w) for w in (4, 8))
         probe = {"mix": tname, "tflops_equiv": round(2.0 * pps / 1e12, 3),

@@ -355,11 +355,14 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
  * sequence of Sec. 4.3.1 with nothing around it): runs a register-only loop
  * of the instruction mix of a task (mix 0: fused multiply-add only, as the
  * identity task; 1: multiply, compare, select, FMA, as the discount task;
- * 2: fma, fma, max, add, as the boost task) with `waves_per_simd` (1..8)
- * resident waves per SIMD on every compute unit, synchronises `stream`, and
- * writes the sustained products per second.  Allocates a small scratch buffer
- * and blocks, like amulet_tune.  Returns AMULET_OK or a negative status.
+ * 2: fma, fma, max, add, as the boost task; 3: multiply, compare, predicate
+ * bit added to an integer count, as the count task) with `waves_per_simd`
+ * (1..8) resident waves per SIMD on every compute unit, synchronises `stream`,
+ * and writes the sustained products per second.  Allocates a small scratch
+ * buffer and blocks, like amulet_tune.  Returns AMULET_OK or a negative status.
  */
+int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream);
+
 /*
  * The tile order of the kernels (an MI355X-side analogue of the loop order the
  * paper's tiling fixes, Sec. 3): a launch covers a tiles_m x tiles_n grid of
@@ -373,8 +376,6 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
  */
 int64_t amulet_tile_grid(int64_t tiles_m, int64_t tiles_n);
 int amulet_tile_of_workgroup(int64_t block, int64_t tiles_m, int64_t tiles_n, int64_t *tm, int64_t *tn);
-
-int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream);
 
 /*
  * The same aid for the join count (the matrix product of Sec. 1's join

@@ -13,12 +13,15 @@ namespace amulet {
 // mix 0: fused multiply-add only (the identity task's inner operation)
 // mix 1: multiply, compare, select, fused multiply-add (the discount task)
 // mix 2: fma, fma, max, add (the boost task)
+// mix 3: multiply, compare, then the predicate bit added to an integer count (the count task)
 template <int MIX>
 __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, int iters)
 {
     float acc[16], b[16], th[16], q[16];
+    int cnt[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
+        cnt[i] = 0;
         acc[i] = threadIdx.x * 0.001f + i;
         b[i] = 1.0f + i * 0.01f + threadIdx.x * 1e-6f;
         th[i] = 1.5f + i;
@@ -44,6 +47,12 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
                     for (int c = 0; c < 4; ++c) s[c] = m[c] ? q[g * 4 + c] : 1.0f;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(p[c], s[c], acc[g * 4 + c]);
+                } else if (MIX == 3) {
+                    float p[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) p[c] = a * b[g * 4 + c];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cnt[g * 4 + c] += (int)(p[c] > th[g * 4 + c]);
                 } else {
                     float d[4];
 #pragma unroll
@@ -61,7 +70,7 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
     }
     float s = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s += acc[i];
+    for (int i = 0; i < 16; ++i) s += acc[i] + (float)cnt[i];
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
@@ -134,7 +143,7 @@ extern "C" int amulet_probe_mfma_i8(int waves_per_simd, double *macs_per_second,
 
 extern "C" int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, void *stream)
 {
-    if (mix < 0 || mix > 2) return AMULET_ERR_TASK;
+    if (mix < 0 || mix > 3) return AMULET_ERR_TASK;
     if (waves_per_simd < 1 || waves_per_simd > 8) return AMULET_ERR_DIM;
     if (!products_per_second) return AMULET_ERR_NULL;
     int dev = 0, cus = 0;
@@ -154,7 +163,8 @@ extern "C" int amulet_probe_valu(int mix, int waves_per_simd, double *products_p
             switch (mix) {
             case 0: hipLaunchKernelGGL(valu_probe_kernel<0>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
             case 1: hipLaunchKernelGGL(valu_probe_kernel<1>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
-            default: hipLaunchKernelGGL(valu_probe_kernel<2>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
+            case 2: hipLaunchKernelGGL(valu_probe_kernel<2>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
+            default: hipLaunchKernelGGL(valu_probe_kernel<3>, dim3(grid), dim3(256), 0, s, out, 1.0f, iters); break;
             }
             (void)hipEventRecord(e1, s);
         }

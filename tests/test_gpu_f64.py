@@ -199,6 +199,18 @@ def test_f64_named_workloads_full_size_sampled(am, name):
         assert np.max(np.abs(R.sum(0) - ref) / scale) < 1e-12
 
 
+def test_vector_alu_probes_report_plausible_rates(am):
+    """The register-only loops behind the bench's measured ceilings: every instruction mix gives
+    a rate between 5 and 80 T products/s (the chip issues 78.6 T lane-operations/s), the pure
+    FMA mix the highest; an unknown mix or wave count is refused."""
+    rates = [am.amulet_probe_valu(mix, 4) for mix in (0, 1, 2, 3)]
+    assert all(5e12 < r < 80e12 for r in rates), rates
+    assert rates[0] == max(rates)
+    for bad in ((4, 4), (-1, 4), (1, 0), (1, 9)):
+        with pytest.raises(am.AmuletError):
+            am.amulet_probe_valu(*bad)
+
+
 def test_matrix_core_probe_reports_a_plausible_rate(am):
     macs = am.amulet_probe_mfma_i8(4)
     # between a tenth of and the whole nominal int8 peak (2.5e15 multiply-adds per second)
