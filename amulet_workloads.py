@@ -98,6 +98,8 @@ CONFIGS = {
     "cfg4_discount_16384x2048x8192": dict(task=DISCOUNT, M=16384, N=2048, K=8192, seed=4,
                                           gen="retail"),
     "headline_discount_8192": dict(task=DISCOUNT, M=8192, N=8192, K=8192, seed=4, gen="retail"),
+    # Query 3 (count of products over a threshold) on the retail data, the paper's square size
+    "query3_count_gt_4096": dict(task=COUNT_GT, M=4096, N=4096, K=4096, seed=8, gen="price_counts"),
     # the paper's own element type (its listings are double): same recipes, widened to fp64
     "f64_discount_4096": dict(task=DISCOUNT, M=4096, N=4096, K=4096, seed=5, gen="retail", dtype="f64"),
     "f64_boost_2048": dict(task=BOOST, M=2048, N=2048, K=2048, seed=6, gen="signal", dtype="f64"),

@@ -335,6 +335,24 @@ def test_headline_discount_8192_sampled(am):
     _sampled_rows_cols(am, "headline_discount_8192", n_rows=12, n_cols=12)
 
 
+def test_query3_count_gt_4096_sampled(am):
+    """Query 3 at the paper's square size: integer counts, so sampled rows and columns must
+    match the oracle bit for bit (and they pass assert_parity_f32 a fortiori)."""
+    spec, A, B, P = wl.make("query3_count_gt_4096")
+    M, N = spec["M"], spec["N"]
+    R = run_gpu(am, spec["task"], A, B, P, np.zeros((M, N), np.float32))
+    g = np.random.Generator(np.random.PCG64(4343))
+    rows = np.sort(g.choice(M, 24, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 24, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    R_ref, _, _ = oracle.mmlike_f32(spec["task"], np.ascontiguousarray(A[rows]), B, P)
+    assert np.array_equal(R[rows], R_ref)
+    R_ref, _, _ = oracle.mmlike_f32(spec["task"], A, np.ascontiguousarray(B[:, cols]), np.ascontiguousarray(P[:, cols]))
+    assert np.array_equal(R[:, cols], R_ref)
+    assert 0 < R.mean() < spec["K"]          # neither never nor always triggered
+
+
 def test_cfg3_join_count_full_size_sampled(am):
     spec, A, B, _ = wl.make("cfg3_count_i8_8192x8192x4096")
     M, N = spec["M"], spec["N"]
