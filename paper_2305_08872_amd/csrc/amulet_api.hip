@@ -288,7 +288,12 @@ static int64_t trial_rows(const MmlikeCall &c, int shape)
         tile_cols = 256LL * kValuShapes[shape].NG;
     }
     const int64_t tiles_n = (c.N + tile_cols - 1) / tile_cols;
-    const int64_t row_tiles = (1280 + tiles_n - 1) / tiles_n;
+    // (matrix-core tiles: a compute unit is at full rate with three resident 128 x 128 tiles,
+    // and holds one 256 x 256 tile at a time, so three tiles resp. one tile per unit is enough)
+    const int64_t want_tiles = shape == IDENTITY_MFMA_BIG_SHAPE ? 256
+                               : shape == IDENTITY_MFMA_SHAPE   ? 768
+                                                                : 1280;
+    const int64_t row_tiles = (want_tiles + tiles_n - 1) / tiles_n;
     return row_tiles * tile_rows;
 }
 
@@ -613,13 +618,19 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const 
     // too small to spare even two trial slabs: run it whole with the default shape
     const bool can_test = 2 * trial_rows(c, VALU_TILES + 0) <= x.budget_rows;
     if (can_test && hipEventCreate(&x.e0) == hipSuccess && hipEventCreate(&x.e1) == hipSuccess) {
-        // the dense contraction also has its matrix-core kernel: its slab goes first
-        const double t_mfma = task == TASK_IDENTITY ? adaptive_trial(&x, IDENTITY_MFMA_SHAPE) : 1e300;
-        int b0 = 0, b1 = 0;
-        x.best_valu_score = 1e300;
-        amulet_greedy_search(VALU_DEPTHS, VALU_TILES, adaptive_valu_score, &x, &b0, &b1);
-        best = b0 * VALU_TILES + b1;
-        if (t_mfma <= x.best_valu_score) best = IDENTITY_MFMA_SHAPE;
+        if (task == TASK_IDENTITY) {
+            // the dense contraction runs on the matrix cores: its two tiles are the candidates
+            // (a vector-ALU slab runs at a sixth of their rate: one such trial on the caller's
+            // rows cost 20 % of an 8192^3 call, and none ever won)
+            const double t_small = adaptive_trial(&x, IDENTITY_MFMA_SHAPE);
+            const double t_big = adaptive_trial(&x, IDENTITY_MFMA_BIG_SHAPE);
+            best = t_big < t_small ? IDENTITY_MFMA_BIG_SHAPE : IDENTITY_MFMA_SHAPE;
+        } else {
+            int b0 = 0, b1 = 0;
+            x.best_valu_score = 1e300;
+            amulet_greedy_search(VALU_DEPTHS, VALU_TILES, adaptive_valu_score, &x, &b0, &b1);
+            best = b0 * VALU_TILES + b1;
+        }
     }
     if (x.e0) (void)hipEventDestroy(x.e0);
     if (x.e1) (void)hipEventDestroy(x.e1);

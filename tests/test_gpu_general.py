@@ -163,7 +163,7 @@ def test_adaptive_execution_trials_contribute_to_the_result(am):
     torch.cuda.synchronize()
     R_ref, ab, _ = oracle.mmlike_f32(0, A3, B3, None)
     assert_parity_f32(dR3.cpu().numpy(), R_ref, ab, what="adaptive identity")
-    assert t3 >= 2
+    assert t3 >= 1 and c3 in (8, 9)         # only the matrix-core tiles are tried for the dense contraction
     am.amulet_clear_selections()
 
 
