@@ -40,7 +40,12 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
 {
     static_assert(TASK == TASK_DISCOUNT || TASK == TASK_BOOST || TASK == TASK_COUNT_GT, "predicate tasks only");
     if constexpr (TASK == TASK_DISCOUNT) {
-        double p[D_TM][2], s[D_TM][2];
+        // A 64-bit select is two instructions, so the discount is applied under the execution
+        // mask instead: the compare writes the mask, the lanes whose product is over the
+        // threshold multiply it by q = 1 - dis[j], the mask is put back (a scalar move), and
+        // every lane adds its term: 4 vector instructions per product instead of 5.
+        const uint64_t active = __builtin_amdgcn_read_exec();   // the lanes running here: put back after each compare
+        double p[D_TM][2];
 #pragma unroll
         for (int r = 0; r < D_TM; ++r)
 #pragma unroll
@@ -48,11 +53,15 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
 #pragma unroll
         for (int r = 0; r < D_TM; ++r)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) s[r][c] = (p[r][c] > th[r][c]) ? q[c] : 1.0;   // q = 1 - dis[j]
+            for (int c = 0; c < 2; ++c)
+                asm volatile("v_cmpx_gt_f64_e32 vcc, %0, %1\n\tv_mul_f64 %0, %0, %2\n\ts_mov_b64 exec, %3"
+                             : "+v"(p[r][c])
+                             : "v"(th[r][c]), "v"(q[c]), "s"(active)
+                             : "vcc");
 #pragma unroll
         for (int r = 0; r < D_TM; ++r)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) acc[r][c] = __builtin_fma(p[r][c], s[r][c], acc[r][c]);
+            for (int c = 0; c < 2; ++c) acc[r][c] += p[r][c];
     } else if constexpr (TASK == TASK_BOOST) {
         // p + max(p - th, 0): continuous in p, so the fused product is within tolerance
         double d[D_TM][2];
@@ -426,8 +435,8 @@ static hipError_t launch_f64_layout(int trans, int form, const MmlikeArgsF64 &a,
     case 0: {
         // Rows of a row-major A go through LDS when their pitch collides in the memory system, and
         // in fp64 nearly always otherwise too: measured at 1024^3 ... 4096^3, A through LDS against
-        // A through the scalar cache: count 17.6-22.2 against 14.7-19.4 TFLOP/s, discount 11.8-13.7
-        // against 10.3-13.4; boost 14.0 / 15.6 against 12.7 / 14.9 at 1024^3 / 2048^3 but 15.8
+        // A through the scalar cache: count 17.6-22.2 against 14.7-19.4 TFLOP/s, discount 14.8-15.9
+        // against 11.8-13.0; boost 14.0 / 15.6 against 12.7 / 14.9 at 1024^3 / 2048^3 but 15.8
         // against 16.1 at 4096^3, so large boost problems keep the scalar path.
         const bool lds = pitch_collides(a.lda, 8) || TASK != TASK_BOOST || (int64_t)a.M * a.N <= 2048LL * 2048LL;
         return lds ? launch_f64_form<TASK, 0, true>(form, a, grid, s) : launch_f64_form<TASK, 0, false>(form, a, grid, s);
