@@ -25,7 +25,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # lane-operations per product (discount: multiply, compare, select, FMA), so its ceiling
 # in the metric's 2-flop-per-product convention is 2 x 78.6e12 / ops.
 VALU_LANE_OPS_PER_S = 256 * 128 * 2.4e9
-VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 3, "identity": 1}
+VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 4, "identity": 1}
 
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, 5.0 POP/s

@@ -355,8 +355,8 @@ int amulet_choose_kernel_height(int I_h_max, int I_w, int S_w, int n_const, int 
  * sequence of Sec. 4.3.1 with nothing around it): runs a register-only loop
  * of the instruction mix of a task (mix 0: fused multiply-add only, as the
  * identity task; 1: multiply, compare, select, FMA, as the discount task;
- * 2: fma, fma, max, add, as the boost task; 3: multiply, compare, predicate
- * bit added to an integer count, as the count task) with `waves_per_simd`
+ * 2: fma, fma, max, add, as the boost task; 3: multiply, subtract, sign bit
+ * of the difference added to an integer count, as the count task) with `waves_per_simd`
  * (1..8) resident waves per SIMD on every compute unit, synchronises `stream`,
  * and writes the sustained products per second.  Allocates a small scratch
  * buffer and blocks, like amulet_tune.  Returns AMULET_OK or a negative status.

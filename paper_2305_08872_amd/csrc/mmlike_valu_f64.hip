@@ -82,6 +82,8 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
 #pragma unroll
             for (int c = 0; c < 2; ++c) acc[r][c] += d[r][c];
     } else {
+        // (the sign bit of th - p, which replaces compare and select in the fp32 kernel, measured
+        // 10 % slower here: the subtraction is a second full-width fp64 operation)
         double p[D_TM][2];
 #pragma unroll
         for (int r = 0; r < D_TM; ++r)

@@ -86,15 +86,22 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c] += d[c];
     } else {
-        // multiply, compare, then the predicate bits are summed into the integer count.
-        // (An add-with-carry form is one instruction shorter but measured slower on
-        // gfx950: carry-in/carry-out traffic through the scalar registers costs more
-        // than the select + 3-input adds the compiler emits for this.)
-        float p[4];
+        // The count needs no lane mask: p > th exactly when th - p is negative (a difference of
+        // two floats is zero only when they are equal, subnormal results included, and x - x is
+        // +0), so the sign bit of the rounded difference is the predicate bit.  The one
+        // exception, -0 - (+0) = -0, is excluded by the caller: it never passes a threshold of -0.  multiply,
+        // subtract, shift, add: four plain vector instructions, against multiply, compare,
+        // select, add, where the compare and the select pass a lane mask through the scalar
+        // registers (a register-only loop of such a pair takes about as long as four plain
+        // instructions).  Measured: +5 % with A through LDS, +12-14 % with A in scalar registers,
+        // which the masks used to crowd out.
+        float p[4], d[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) p[c] = a * b[c];
+        for (int c = 0; c < 4; ++c) p[c] = a * b[c];          // one RN multiply (contraction is off)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[c] += (int)(p[c] > th[c]);
+        for (int c = 0; c < 4; ++c) d[c] = th[c] - p[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += (int)(__builtin_bit_cast(unsigned, d[c]) >> 31);
     }
 }
 
@@ -189,16 +196,20 @@ mmlike_valu_kernel(const MmlikeArgs args)
     // column, and the threshold in the operand form TF (paper Sec. 6.3): thres[j] per column,
     // thres[i] per row (wave-uniform, scalar), one constant, or thres[i][j] per output (read
     // once per tile, not once per product as a CPU kernel must).
+    // The count task reads its predicate from the sign of th - p (see fold4), which takes a
+    // threshold of -0 for a negative number when p is +0: thresholds are held as th + 0, which
+    // turns -0 into +0 and changes nothing else.
+    auto held = [](float t) { return TASK == TASK_COUNT_GT ? t + 0.0f : t; };
     float q[NG * 4];
     float th_col[TF == THRES_COL ? NG * 4 : 1];
     float th_row[TF == THRES_ROW ? TM : 1];
     float th_el[TF == THRES_ELEM ? TM : 1][TF == THRES_ELEM ? NG * 4 : 1];
     float th_const = __builtin_inff();
     if constexpr (TASK != TASK_IDENTITY) {
-        if constexpr (TF == THRES_CONST) th_const = ((sptr_f)args.thres)[0];
+        if constexpr (TF == THRES_CONST) th_const = held(((sptr_f)args.thres)[0]);
         if constexpr (TF == THRES_ROW) {
 #pragma unroll
-            for (int r = 0; r < TM; ++r) th_row[r] = ((sptr_f)args.thres)[rowc(r)];
+            for (int r = 0; r < TM; ++r) th_row[r] = held(((sptr_f)args.thres)[rowc(r)]);
         }
         // Wave-uniform thresholds are held in vector registers all the same: a compare whose
         // threshold operand is a scalar register measured 25 % slower in this loop (4096^3
@@ -218,13 +229,13 @@ mmlike_valu_kernel(const MmlikeArgs args)
             q[g * 4 + c] = 1.0f;
             if constexpr (TF == THRES_COL) th_col[g * 4 + c] = __builtin_inff();
             if (TASK != TASK_IDENTITY && col < N) {
-                if constexpr (TF == THRES_COL) th_col[g * 4 + c] = args.thres[col];
+                if constexpr (TF == THRES_COL) th_col[g * 4 + c] = held(args.thres[col]);
                 if (TASK == TASK_DISCOUNT) q[g * 4 + c] = 1.0f - args.dis[col];
             }
             if constexpr (TF == THRES_ELEM && TASK != TASK_IDENTITY) {
 #pragma unroll
                 for (int r = 0; r < TM; ++r)
-                    th_el[r][g * 4 + c] = (col < N) ? args.thres[(int64_t)rowc(r) * args.ldt + col]
+                    th_el[r][g * 4 + c] = (col < N) ? held(args.thres[(int64_t)rowc(r) * args.ldt + col])
                                                     : __builtin_inff();
             }
         }
@@ -571,12 +582,11 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         splits = (int)((a.K + chunk - 1) / chunk);
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
-    // rows of a row-major A whose pitch collides in the memory system go through LDS
-    // ... and so do those of the count task at any pitch: measured at 2048^3 ... 8192^3, A through
-    // LDS against A through the scalar cache: count 34.7-35.4 against 28.9-32.0 TFLOP/s (its lane
-    // masks already load the scalar register file); boost within +-4 % either way depending on
-    // the data, discount 30.4-31.0 against 31.3-31.9: both keep the scalar path
-    const bool a_through_lds = !a.transA && !a.transB && (pitch_collides(a.lda, 4) || TASK == TASK_COUNT_GT);
+    // Rows of a row-major A whose pitch collides in the memory system go through LDS; at other
+    // pitches the scalar path is as fast or faster for every task (measured at 2048^3 ... 8192^3,
+    // A through LDS against A through the scalar cache: discount 30.4-31.0 against 31.3-31.9
+    // TFLOP/s, count 36.4-37.2 against 36.9-40.4, boost within +-4 % either way).
+    const bool a_through_lds = !a.transA && !a.transB && pitch_collides(a.lda, 4);
     auto launch = [&](int64_t n_blocks, int n_splits) {
         (void)launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);

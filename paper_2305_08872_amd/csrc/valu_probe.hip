@@ -13,7 +13,7 @@ namespace amulet {
 // mix 0: fused multiply-add only (the identity task's inner operation)
 // mix 1: multiply, compare, select, fused multiply-add (the discount task)
 // mix 2: fma, fma, max, add (the boost task)
-// mix 3: multiply, compare, then the predicate bit added to an integer count (the count task)
+// mix 3: multiply, subtract, then the sign bit of the difference added to an integer count (the count task)
 template <int MIX>
 __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, int iters)
 {
@@ -48,11 +48,13 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(p[c], s[c], acc[g * 4 + c]);
                 } else if (MIX == 3) {
-                    float p[4];
+                    float p[4], d[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) p[c] = a * b[g * 4 + c];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) cnt[g * 4 + c] += (int)(p[c] > th[g * 4 + c]);
+                    for (int c = 0; c < 4; ++c) d[c] = th[g * 4 + c] - p[c];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cnt[g * 4 + c] += (int)(__builtin_bit_cast(unsigned, d[c]) >> 31);
                 } else {
                     float d[4];
 #pragma unroll
