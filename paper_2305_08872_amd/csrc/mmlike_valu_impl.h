@@ -470,6 +470,32 @@ mmlike_valu_kernel(const MmlikeArgs args)
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if constexpr (TASK == TASK_DISCOUNT && TM == 4 && NG == 1) {
+                    // The whole chunk as one software pipeline: compare i, multiply i + 1, FMA i - 1,
+                    // select i.  Every compare writes the same lane-mask register (vcc, the 32-bit
+                    // encodings) and its select reads it two instructions later, with one fill and
+                    // one drain per chunk.  (Left to fold4 and a fence per k the compiler finds the
+                    // same order inside each k, but fills and drains four times per chunk: this is
+                    // +2 % at 2048^3 ... 4096^3, +4 % at 4100^3, +1 % at 8192^3.)
+                    constexpr int NP = KA * TM * 4;
+                    float t4[TM][4];
+#pragma unroll
+                    for (int r = 0; r < TM; ++r) thres4(r, 0, t4[r]);
+                    float p[NP + 1], sel[NP];
+                    p[0] = a_of(a, 0, 0) * b[0][0][0];
+#pragma unroll
+                    for (int i = 0; i < NP; ++i) {
+                        const bool m = p[i] > t4[(i / 4) % TM][i % 4];
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (i + 1 < NP) p[i + 1] = a_of(a, ((i + 1) / 4) % TM, (i + 1) / (4 * TM)) * b[(i + 1) / (4 * TM)][0][(i + 1) % 4];
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (i > 0) part[((i - 1) / 4) % TM][(i - 1) % 4] = __builtin_fmaf(p[i - 1], sel[i - 1], part[((i - 1) / 4) % TM][(i - 1) % 4]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        sel[i] = m ? q[i % 4] : 1.0f;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    part[((NP - 1) / 4) % TM][(NP - 1) % 4] = __builtin_fmaf(p[NP - 1], sel[NP - 1], part[((NP - 1) / 4) % TM][(NP - 1) % 4]);
+                } else
 #pragma unroll
                 for (int kk = 0; kk < KA; ++kk) {
 #pragma unroll
@@ -484,7 +510,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
                         // gather the compares of the whole chunk, and their lane masks (a scalar
                         // register pair each) overflow the scalar register file into spills.
                         // (The 8-row micro-tiles spill their A values regardless and lose more
-                        // from the fence than they gain: they are left to the scheduler.)
+                        // from the fence than they gain: they are left to the scheduler.  The
+                        // count task has no masks but measured 3 % faster with the fence.)
                         if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
                             if (r == 3) __builtin_amdgcn_sched_barrier(0);
                     }

@@ -11,7 +11,7 @@
 namespace amulet {
 
 // mix 0: fused multiply-add only (the identity task's inner operation)
-// mix 1: multiply, compare, select, fused multiply-add (the discount task)
+// mix 1: multiply, compare, select, fused multiply-add (the discount task), interleaved as in the kernel
 // mix 2: fma, fma, max, add (the boost task)
 // mix 3: multiply, subtract, then the sign bit of the difference added to an integer count (the count task)
 template <int MIX>
@@ -24,29 +24,41 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
         cnt[i] = 0;
         acc[i] = threadIdx.x * 0.001f + i;
         b[i] = 1.0f + i * 0.01f + threadIdx.x * 1e-6f;
-        th[i] = 1.5f + i;
-        q[i] = 0.9f - i * 0.01f;
+        // per-lane values, as in the kernels: a wave-uniform threshold would be kept in a scalar
+        // register, and a compare with a scalar threshold operand issues slower
+        th[i] = 1.5f + i + threadIdx.x * 1e-4f;
+        q[i] = 0.9f - i * 0.01f - threadIdx.x * 1e-5f;
     }
     float a = a0;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            if (MIX == 1) {
+                // in the order the kernel's inner loop runs them: compare i, multiply i + 1, FMA
+                // i - 1, select i, so that every compare can write the same lane-mask register and
+                // its select reads it two instructions later
+                float p[17], s[16];
+                p[0] = a * b[0];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const bool m = p[i] > th[i];
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i + 1 < 16) p[i + 1] = a * b[i + 1];
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i > 0) acc[i - 1] = __builtin_fmaf(p[i - 1], s[i - 1], acc[i - 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    s[i] = m ? q[i] : 1.0f;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[15] = __builtin_fmaf(p[15], s[15], acc[15]);
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 if (MIX == 0) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(a, b[g * 4 + c], acc[g * 4 + c]);
                 } else if (MIX == 1) {
-                    float p[4], s[4];
-                    bool m[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) p[c] = a * b[g * 4 + c];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) m[c] = p[c] > th[g * 4 + c];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) s[c] = m[c] ? q[g * 4 + c] : 1.0f;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(p[c], s[c], acc[g * 4 + c]);
+                    // (above)
                 } else if (MIX == 3) {
                     float p[4], d[4];
 #pragma unroll
