@@ -37,8 +37,9 @@
  *    ordinary device memory (hipMalloc or a framework's device allocator):
  *    the hardware atomics used there are not defined on fine-grained or
  *    host-mapped memory.
- *  - A or B holding NaN or +-inf gives unspecified results; +-inf in thres is
- *    supported (thres = +inf never triggers, -inf always does).
+ *  - A or B holding NaN or +-inf gives unspecified results, and so does a NaN
+ *    in thres; +-inf in thres is supported (thres = +inf never triggers, -inf
+ *    always does), and so are zeros of either sign and subnormal values.
  */
 #ifndef AMULET_H
 #define AMULET_H
