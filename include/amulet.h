@@ -268,8 +268,23 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
  * The result is that of amulet_count_i8 on the row-major operands, exact.
  * AMULET_ERR_NULL if a workspace is needed and NULL, AMULET_ERR_WORKSPACE if
  * it is too small; other errors as amulet_count_i8.
+ *
+ * A larger workspace, of amulet_count_i8_repack_workspace_bytes(M, N, K) bytes
+ * and 16-byte aligned, is also the operands' aligned home when they need one
+ * (this is the packing of Sec. 3.1 for the join count: the fastest kernel
+ * streams whole 16-byte units of rows that start on 16-byte boundaries, 64 k
+ * at a time, and a workgroup whose whole tile of A rows and B columns exists
+ * in memory loads without guards).  An operand whose base or row pitch is not
+ * a multiple of 16 bytes, or whose M resp. N is not a multiple of 256, is
+ * copied to an aligned pitch with room for whole tiles around it, and when K
+ * is not a multiple of 64 both operands are copied with K padded by zero
+ * bytes, which add nothing to a count.  The copies are one kernel per operand
+ * on `stream`; operands that need none are read in place.  Same result,
+ * exact.  (R is never copied: rows of R that are not 16-byte aligned are
+ * written by the slower write-back.)
  */
 size_t amulet_count_i8_workspace_bytes(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K);
+size_t amulet_count_i8_repack_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
                             const int8_t *A, int64_t lda,
                             const int8_t *B, int64_t ldb,

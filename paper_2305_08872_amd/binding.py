@@ -81,6 +81,8 @@ def load_library():
     lib.amulet_mmlike_f64_autopack.argtypes = lib.amulet_mmlike_f32_autopack.argtypes
     lib.amulet_count_i8_workspace_bytes.restype = ctypes.c_size_t
     lib.amulet_count_i8_workspace_bytes.argtypes = [i32, i32, i64, i64, i64]
+    lib.amulet_count_i8_repack_workspace_bytes.restype = ctypes.c_size_t
+    lib.amulet_count_i8_repack_workspace_bytes.argtypes = [i64, i64, i64]
     lib.amulet_count_i8_general.restype = i32
     lib.amulet_count_i8_general.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
     lib.amulet_count_i8_shape.restype = i32
@@ -329,9 +331,16 @@ def amulet_count_i8_workspace_bytes(trans_a: bool, trans_b: bool, M: int, N: int
     return int(load_library().amulet_count_i8_workspace_bytes(int(trans_a), int(trans_b), M, N, K))
 
 
+def amulet_count_i8_repack_workspace_bytes(M: int, N: int, K: int) -> int:
+    """Bytes of workspace with which amulet_count_i8_general also gives unaligned operands, or
+    operands whose K is not a multiple of 64, an aligned, zero-padded home."""
+    return int(load_library().amulet_count_i8_repack_workspace_bytes(M, N, K))
+
+
 def amulet_count_i8_general(A, B, R, workspace=None, *, trans_a: bool = False, trans_b: bool = False, stream=None):
     """The join count with A stored K x M (trans_a) and / or B stored N x K (trans_b); `workspace`
-    is a contiguous device tensor of at least amulet_count_i8_workspace_bytes(...) bytes."""
+    is a contiguous device tensor of at least amulet_count_i8_workspace_bytes(...) bytes, or of
+    amulet_count_i8_repack_workspace_bytes(...) to have unaligned operands re-pitched as well."""
     lib = load_library()
     pa, ra, ca, lda = _mat(A, "torch.int8", "A")
     pb, rb, cb, ldb = _mat(B, "torch.int8", "B")

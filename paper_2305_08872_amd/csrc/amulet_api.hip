@@ -166,13 +166,17 @@ static int check_mmlike(const MmlikeCall &c)
     return AMULET_OK;
 }
 
+// m_load / n_load: rows of A / columns of B that exist in memory (0: just M, N)
 static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
-                     const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+                     const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream,
+                     int64_t m_load = 0, int64_t n_load = 0)
 {
     CountArgs a;
     a.A = A; a.B = B; a.R = R;
     a.lda = lda; a.ldb = ldb; a.ldr = ldr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.Mload = (int)(m_load > M ? m_load : M);
+    a.Nload = (int)(n_load > N ? n_load : N);
     a.vecA = (aligned16(A) && lda % 16 == 0) ? 1 : 0;
     a.vecB = (aligned16(B) && ldb % 16 == 0) ? 1 : 0;
     a.vecR = (aligned16(R) && ldr % 4 == 0) ? 1 : 0;
@@ -526,6 +530,18 @@ size_t amulet_count_i8_workspace_bytes(int trans_a, int trans_b, int64_t M, int6
     return n;
 }
 
+// Extents of the copies in a repacking workspace: K in whole 64s (zero filled), and room for
+// whole 256 x 256 tiles around M and N (never initialised: what is computed from it belongs to
+// outputs that do not exist and is not written).
+static int64_t i8_tile_up(int64_t n) { return (n + 255) / 256 * 256; }
+
+size_t amulet_count_i8_repack_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const int64_t Kp = (K + 63) / 64 * 64;
+    return (size_t)i8_tile_up(M) * (size_t)i8_copy_ld(Kp) + (size_t)Kp * (size_t)i8_copy_ld(i8_tile_up(N));
+}
+
 int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const int8_t *A,
                             int64_t lda, const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr,
                             void *workspace, size_t workspace_bytes, void *stream)
@@ -541,22 +557,49 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
     }
     int8_t *w = (int8_t *)workspace;
     hipStream_t s = (hipStream_t)stream;
+    // With room for both operands the workspace also serves as their aligned home: an operand
+    // whose rows are not 16-byte aligned, or whose extent is not whole tiles, is copied to a
+    // pitch that is aligned, with room for whole tiles around it, and when K is not a multiple
+    // of 64 both are copied with K padded by zeros (which add nothing to a count).  Every
+    // workgroup then loads without guards, and the streamed kernel takes the whole-tile part.
+    const int64_t Kp = (K + 63) / 64 * 64;
+    const bool repack = workspace && ((uintptr_t)workspace & 15u) == 0 &&
+                        workspace_bytes >= amulet_count_i8_repack_workspace_bytes(M, N, K);
+    auto rows_aligned = [](const void *p, int64_t ld) { return ((uintptr_t)p & 15u) == 0 && ld % 16 == 0; };
+    const bool pad_k = repack && Kp != K;
+    const int64_t Kc = pad_k ? Kp : K;               // k extent of the copies
+    int64_t m_load = M, n_load = N;
+    hipError_t e = hipSuccess;
     if (trans_a) {   // stored K x M: the copy is M x K
-        const int64_t ld = i8_copy_ld(K);
-        const hipError_t e = launch_transpose_i8(K, M, A, lda, w, ld, s);
-        g_last_hip_error = e;
-        if (e != hipSuccess) return AMULET_ERR_LAUNCH;
+        const int64_t ld = i8_copy_ld(Kc);
+        e = launch_transpose_i8(K, M, A, lda, w, ld, s);
+        if (e == hipSuccess && pad_k) e = launch_zero_block_i8(w, ld, 0, M, K, Kp - K, s);
         A = w; lda = ld;
-        w += M * ld;
+        if (repack) m_load = i8_tile_up(M);
+        w += (repack ? i8_tile_up(M) : M) * ld;
+    } else if (repack && (pad_k || !rows_aligned(A, lda) || M % 256 != 0)) {
+        const int64_t ld = i8_copy_ld(Kc);
+        e = launch_pack_pad_i8(M, K, A, lda, w, ld, M, (Kc + 15) / 16 * 16, s);
+        A = w; lda = ld;
+        m_load = i8_tile_up(M);
+        w += i8_tile_up(M) * ld;
     }
+    if (e != hipSuccess) { g_last_hip_error = e; return AMULET_ERR_LAUNCH; }
     if (trans_b) {   // stored N x K: the copy is K x N
-        const int64_t ld = i8_copy_ld(N);
-        const hipError_t e = launch_transpose_i8(N, K, B, ldb, w, ld, s);
-        g_last_hip_error = e;
-        if (e != hipSuccess) return AMULET_ERR_LAUNCH;
+        const int64_t ld = repack ? i8_copy_ld(i8_tile_up(N)) : i8_copy_ld(N);
+        e = launch_transpose_i8(N, K, B, ldb, w, ld, s);
+        if (e == hipSuccess && pad_k) e = launch_zero_block_i8(w, ld, K, Kp - K, 0, N, s);
         B = w; ldb = ld;
+        if (repack) n_load = i8_tile_up(N);
+    } else if (repack && (pad_k || !rows_aligned(B, ldb) || N % 256 != 0)) {
+        const int64_t ld = i8_copy_ld(i8_tile_up(N));
+        e = launch_pack_pad_i8(K, N, B, ldb, w, ld, Kc, (N + 15) / 16 * 16, s);
+        B = w; ldb = ld;
+        n_load = i8_tile_up(N);
     }
-    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, K), M, N, K, A, lda, B, ldb, R, ldr, stream);
+    if (e != hipSuccess) { g_last_hip_error = e; return AMULET_ERR_LAUNCH; }
+    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, Kc), M, N, Kc, A, lda, B, ldb, R, ldr, stream,
+                     m_load, n_load);
 }
 
 int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,

@@ -205,6 +205,7 @@ struct CountArgs {
     int32_t *R;
     int64_t lda, ldb, ldr;
     int M, N, K;
+    int Mload, Nload;  // rows of A / columns of B that exist in memory (>= M, N): a tile inside them loads without guards
     int vecA, vecB;  // 1 when the operand and its row pitch allow 16-byte loads
     int vecR;        // 1 when R and its row pitch allow 16-byte accesses
     int kchunk;      // k range of one workgroup when a launch splits K (set by the launcher)
@@ -248,6 +249,10 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
 
 // dst (cols x rows, pitch ld_dst) = transpose of src (rows x cols, pitch ld_src), bytes (pack.hip)
+hipError_t launch_pack_pad_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
+                              int64_t ld_dst, int64_t rows_p, int64_t cols_p, hipStream_t s);
+hipError_t launch_zero_block_i8(int8_t *dst, int64_t ld, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
+                                hipStream_t s);
 hipError_t launch_transpose_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
                                int64_t ld_dst, hipStream_t s);
 // strided 2-D copy of rows x cols elements of 1, 4 or 8 bytes (pack.hip)

@@ -83,6 +83,69 @@ transpose_i8_kernel(const int8_t *src, int64_t pitch_src, int8_t *dst, int64_t p
     }
 }
 
+// Copy of a rows x cols byte matrix into rows_p x cols_p (cols_p a multiple of 16, dst 16-byte
+// aligned rows), zero beyond the source: a thread writes one aligned 16-byte unit and reads its
+// 16 source bytes with one load at whatever address they have (global accesses take any
+// address on this target), bytewise only across the source's right-hand edge.
+typedef pk_u4 pk_u4_any __attribute__((aligned(1)));
+__global__ void __launch_bounds__(256)
+pack_pad_i8_kernel(const int8_t *src, int64_t pitch_src, int64_t rows, int64_t cols, int8_t *dst, int64_t pitch_dst,
+                   int64_t rows_p, int64_t units)
+{
+    for (int64_t r = blockIdx.y; r < rows_p; r += gridDim.y) {
+        const int8_t *srow = src + r * pitch_src;
+        for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (int64_t)gridDim.x * 256) {
+            const int64_t c0 = u * 16;
+            pk_u4 v = {0u, 0u, 0u, 0u};
+            if (r < rows) {
+                if (c0 + 16 <= cols) {
+                    v = *(const pk_u4_any *)(srow + c0);
+                } else {
+                    unsigned int w[4] = {0u, 0u, 0u, 0u};
+                    for (int e = 0; e < 16; ++e)
+                        if (c0 + e < cols) w[e >> 2] |= (unsigned int)(uint8_t)srow[c0 + e] << (8 * (e & 3));
+                    v = pk_u4{w[0], w[1], w[2], w[3]};
+                }
+            }
+            *(pk_u4 *)(dst + r * pitch_dst + c0) = v;
+        }
+    }
+}
+
+// Zero the bytes [col0, col0 + ncols) of rows [row0, row0 + nrows): the padding around a
+// transposed copy (a fill kernel rather than a memset, so that a caller may capture the call).
+__global__ void __launch_bounds__(256)
+zero_block_i8_kernel(int8_t *dst, int64_t pitch, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols)
+{
+    for (int64_t r = blockIdx.y; r < nrows; r += gridDim.y)
+        for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < ncols; c += (int64_t)gridDim.x * 256)
+            dst[(row0 + r) * pitch + col0 + c] = 0;
+}
+
+hipError_t launch_pack_pad_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
+                              int64_t ld_dst, int64_t rows_p, int64_t cols_p, hipStream_t s)
+{
+    const int64_t units = cols_p / 16;
+    int64_t gx = (units + 255) / 256;
+    if (gx > 64) gx = 64;
+    const int64_t gy = rows_p < 65535 ? rows_p : 65535;
+    hipLaunchKernelGGL(pack_pad_i8_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, src, ld_src, rows, cols,
+                       dst, ld_dst, rows_p, units);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_block_i8(int8_t *dst, int64_t ld, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
+                                hipStream_t s)
+{
+    if (nrows <= 0 || ncols <= 0) return hipSuccess;
+    int64_t gx = (ncols + 255) / 256;
+    if (gx > 64) gx = 64;
+    const int64_t gy = nrows < 65535 ? nrows : 65535;
+    hipLaunchKernelGGL(zero_block_i8_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s, dst, ld, row0, nrows,
+                       col0, ncols);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,
                                int64_t ld_dst, hipStream_t s)
 {

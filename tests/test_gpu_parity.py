@@ -267,6 +267,40 @@ def test_count_i8_transposed_operands(am, tA, tB):
             assert err.value.code == -3
 
 
+@pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
+def test_count_i8_repacked_operands(am, tA, tB):
+    """With the larger workspace the general entry point re-pitches operands whose rows are not
+    16-byte aligned and pads a K that is not a multiple of 64 with zeros: same counts, bit for bit.
+    The workspace starts out poisoned, the operands sit at odd byte offsets inside larger buffers,
+    and sizes span whole streamed tiles plus ragged edges."""
+    for idx, (M, N, K, pad, off) in enumerate([(300, 777, 1000, 3, 1), (512, 1024, 640, 0, 0), (257, 513, 63, 5, 7),
+                                               (640, 600, 1030, 1, 3), (1, 1, 1, 0, 1), (520, 530, 129, 2, 0)]):
+        g = np.random.Generator(np.random.PCG64(470 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        As, Bs = (A.T.copy() if tA else A), (B.T.copy() if tB else B)
+
+        def place(X, fill):     # X at byte offset `off` of a buffer with row pitch cols + pad
+            r, c = X.shape
+            flat = torch.full((off + r * (c + pad) + 16,), fill, dtype=torch.int8, device="cuda")
+            view = flat[off:off + r * (c + pad)].view(r, c + pad)[:, :c]
+            view.copy_(dev(X))
+            return view
+
+        vA, vB = place(As, 55), place(Bs, 66)
+        need = am.amulet_count_i8_repack_workspace_bytes(M, N, K)
+        assert need >= am.amulet_count_i8_workspace_bytes(tA, tB, M, N, K)
+        ws = torch.full((need,), 77, dtype=torch.int8, device="cuda")
+        assert ws.data_ptr() % 16 == 0
+        dR = dev(R_in)
+        print("i8 repacked", tA, tB, M, N, K, pad, off, flush=True)
+        am.amulet_count_i8_general(vA, vB, dR, ws, trans_a=tA, trans_b=tB)
+        torch.cuda.synchronize()
+        assert np.array_equal(dR.cpu().numpy(), R_ref), (tA, tB, M, N, K)
+
+
 def test_count_i8_strided(am):
     M, N, K = 50, 130, 75
     A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)

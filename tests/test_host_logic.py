@@ -83,6 +83,9 @@ def test_packed_pitch_never_collides_and_argument_errors(lib):
     assert am.amulet_strerror(-8).startswith("workspace")
     # join count with transposed operands: the workspace holds the transposed copies
     assert am.amulet_count_i8_workspace_bytes(False, False, 100, 200, 300) == 0
+    assert am.amulet_count_i8_repack_workspace_bytes(100, 200, 300) == \
+        256 * am.amulet_packed_ld(320, 1) + 320 * am.amulet_packed_ld(256, 1)   # K in 64s, M and N in 256s
+    assert am.amulet_count_i8_repack_workspace_bytes(0, 200, 300) == 0
     assert am.amulet_count_i8_workspace_bytes(True, False, 100, 200, 300) == 100 * am.amulet_packed_ld(300, 1)
     assert am.amulet_count_i8_workspace_bytes(True, True, 100, 200, 300) == \
         100 * am.amulet_packed_ld(300, 1) + 300 * am.amulet_packed_ld(200, 1)
