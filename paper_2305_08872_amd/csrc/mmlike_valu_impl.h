@@ -110,10 +110,13 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
 // registers and LDS traffic; used when the row pitch of A collides (amulet_pitch_collides):
 // the scalar path fetches each 128-byte line of A in eight pieces, and when the lines of a
 // workgroup's 32 rows all fall into the same L2 sets they are evicted between the pieces.
-template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA, bool ALDS>
+// PIPE (discount task, 4 x 4 micro-tile): a chunk runs as one software pipeline instead of k by k
+// (see the chunk loop); the launcher says when.
+template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA, bool ALDS, bool PIPE = false>
 __global__ void __launch_bounds__(64 * NW)
 mmlike_valu_kernel(const MmlikeArgs args)
 {
+    static_assert(!PIPE || (TASK == TASK_DISCOUNT && TM == 4 && NG == 1), "chunk pipeline: discount task, 4 x 4 micro-tile");
     static_assert(!ALDS || (TRANS == 0 && TM == 4 && NG == 1), "A through LDS: row-major operands, 4 x 4 micro-tile");
     typedef typename AccT<TASK>::type acc_t;
     static_assert(KA == 4 && TM % 4 == 0, "a transposed A is fetched as 4 rows x 4 k blocks");
@@ -470,51 +473,58 @@ mmlike_valu_kernel(const MmlikeArgs args)
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if constexpr (TASK == TASK_DISCOUNT && TM == 4 && NG == 1) {
-                    // The whole chunk as one software pipeline: compare i, multiply i + 1, FMA i - 1,
-                    // select i.  Every compare writes the same lane-mask register (vcc, the 32-bit
-                    // encodings) and its select reads it two instructions later, with one fill and
-                    // one drain per chunk.  (Left to fold4 and a fence per k the compiler finds the
-                    // same order inside each k, but fills and drains four times per chunk: this is
-                    // +2 % at 2048^3 ... 4096^3, +4 % at 4100^3, +1 % at 8192^3.)
-                    constexpr int NP = KA * TM * 4;
-                    float t4[TM][4];
+                // one k at a time through fold4, rows in order
+                auto chunk_by_k = [&]() {
 #pragma unroll
-                    for (int r = 0; r < TM; ++r) thres4(r, 0, t4[r]);
-                    float p[NP + 1], sel[NP];
-                    p[0] = a_of(a, 0, 0) * b[0][0][0];
+                    for (int kk = 0; kk < KA; ++kk) {
 #pragma unroll
-                    for (int i = 0; i < NP; ++i) {
-                        const bool m = p[i] > t4[(i / 4) % TM][i % 4];
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (i + 1 < NP) p[i + 1] = a_of(a, ((i + 1) / 4) % TM, (i + 1) / (4 * TM)) * b[(i + 1) / (4 * TM)][0][(i + 1) % 4];
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (i > 0) part[((i - 1) / 4) % TM][(i - 1) % 4] = __builtin_fmaf(p[i - 1], sel[i - 1], part[((i - 1) / 4) % TM][(i - 1) % 4]);
-                        __builtin_amdgcn_sched_barrier(0);
-                        sel[i] = m ? q[i % 4] : 1.0f;
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    part[((NP - 1) / 4) % TM][(NP - 1) % 4] = __builtin_fmaf(p[NP - 1], sel[NP - 1], part[((NP - 1) / 4) % TM][(NP - 1) % 4]);
-                } else
+                        for (int r = 0; r < TM; ++r) {
 #pragma unroll
-                for (int kk = 0; kk < KA; ++kk) {
-#pragma unroll
-                    for (int r = 0; r < TM; ++r) {
-#pragma unroll
-                        for (int g = 0; g < NG; ++g) {
-                            float t4[4];
-                            thres4(r, g, t4);
-                            fold4<TASK>(a_of(a, r, kk), b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
+                            for (int g = 0; g < NG; ++g) {
+                                float t4[4];
+                                thres4(r, g, t4);
+                                fold4<TASK>(a_of(a, r, kk), b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
+                            }
+                            // At most 4 rows of one k between fences: left alone, the scheduler may
+                            // gather the compares of the whole chunk, and their lane masks (a scalar
+                            // register pair each) overflow the scalar register file into spills.
+                            // (The 8-row micro-tiles spill their A values regardless and lose more
+                            // from the fence than they gain: they are left to the scheduler.  The
+                            // count task has no masks but measured 3 % faster with the fence.)
+                            if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
+                                if (r == 3) __builtin_amdgcn_sched_barrier(0);
                         }
-                        // At most 4 rows of one k between fences: left alone, the scheduler may
-                        // gather the compares of the whole chunk, and their lane masks (a scalar
-                        // register pair each) overflow the scalar register file into spills.
-                        // (The 8-row micro-tiles spill their A values regardless and lose more
-                        // from the fence than they gain: they are left to the scheduler.  The
-                        // count task has no masks but measured 3 % faster with the fence.)
-                        if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
-                            if (r == 3) __builtin_amdgcn_sched_barrier(0);
                     }
+                };
+                if constexpr (PIPE) {
+                    {
+                        // The whole chunk as one software pipeline: compare i, multiply i + 1, FMA
+                        // i - 1, select i.  Every compare writes the same lane-mask register (vcc,
+                        // the 32-bit encodings) and its select reads it two instructions later, with
+                        // one fill and one drain per chunk.  (Through fold4 and a fence per k the
+                        // compiler finds the same order inside each k, but fills and drains four
+                        // times per chunk.)
+                        constexpr int NP = KA * TM * 4;
+                        float t4[TM][4];
+#pragma unroll
+                        for (int r = 0; r < TM; ++r) thres4(r, 0, t4[r]);
+                        float p[NP + 1], sel[NP];
+                        p[0] = a_of(a, 0, 0) * b[0][0][0];
+#pragma unroll
+                        for (int i = 0; i < NP; ++i) {
+                            const bool m = p[i] > t4[(i / 4) % TM][i % 4];
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (i + 1 < NP) p[i + 1] = a_of(a, ((i + 1) / 4) % TM, (i + 1) / (4 * TM)) * b[(i + 1) / (4 * TM)][0][(i + 1) % 4];
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (i > 0) part[((i - 1) / 4) % TM][(i - 1) % 4] = __builtin_fmaf(p[i - 1], sel[i - 1], part[((i - 1) / 4) % TM][(i - 1) % 4]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            sel[i] = m ? q[i % 4] : 1.0f;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        part[((NP - 1) / 4) % TM][(NP - 1) % 4] = __builtin_fmaf(p[NP - 1], sel[NP - 1], part[((NP - 1) / 4) % TM][(NP - 1) % 4]);
+                    }
+                } else {
+                    chunk_by_k();
                 }
             }
         } else {
@@ -609,6 +619,11 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         splits = (int)((a.K + chunk - 1) / chunk);
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    // Discount task: the chunk-wide pipeline is 2-4 % faster up to a few thousand workgroups
+    // (2048^3 ... 4096^3 +2 %, 4100^3 +4 %, 16384 x 2048 x 8192 +1 %) and no faster at 8192^3,
+    // where its workgroups also share less through the L2s (18.8 against 8.9 GB fetched per
+    // launch, same request count): large launches keep the k-by-k form.
+    const bool pipe = TASK == TASK_DISCOUNT && TM == 4 && NG == 1 && wgs <= 4096;
     // Rows of a row-major A whose pitch collides in the memory system go through LDS; at other
     // pitches the scalar path is as fast or faster for every task (measured at 2048^3 ... 8192^3,
     // A through LDS against A through the scalar cache: discount 30.4-31.0 against 31.3-31.9
@@ -619,6 +634,15 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
             switch ((a.transA ? 1 : 0) | (a.transB ? 2 : 0)) {
             case 0:
+                if constexpr (TASK == TASK_DISCOUNT && TM == 4 && NG == 1) {
+                    if (pipe) {
+                        if (a_through_lds)
+                            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, true, true>), grid, block, 0, s, b);
+                        else
+                            hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false, true>), grid, block, 0, s, b);
+                        break;
+                    }
+                }
                 if constexpr (TM == 4 && NG == 1) {
                     if (a_through_lds) {
                         hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, true>), grid, block, 0, s, b);
