@@ -162,13 +162,26 @@ count_i8_mfma_kernel(const CountArgs args)
         lb[it] = Bs + (u / (BN / 16)) * BPITCH + (u % (BN / 16)) * 16;
     }
 
+    // Edge workgroups of aligned operands whose N is a whole number of 16-byte units take the
+    // same loader with the buffers' extents set to where the operands end: a unit of a row of A
+    // past M lies past the extent and reads as zero, a unit of B past N reads bytes of the next
+    // row, or zero past the last one, and either only feeds outputs that do not exist.  (Every
+    // unit that feeds an existing output is whole and inside the extent: full stages only, and
+    // N % 16 == 0.)
+    const bool edge_fast = !interior && vecA && vecB && (N & 15) == 0 &&
+                           (int64_t)BM * args.lda < 0x7fffffffLL && (int64_t)CI_BK * args.ldb < 0x7fffffffLL;
+    auto extent = [](int64_t bytes) { return (int)(bytes < 0 ? 0 : bytes > 0x7fffffffLL ? 0x7fffffffLL : bytes); };
+
     v4i sa[A_UNITS], sb[B_UNITS];
     auto load_stage = [&](int k0) {
-        if (interior && k0 + CI_BK <= K) {
+        if ((interior || edge_fast) && k0 + CI_BK <= K) {
+            // bytes from the stage's first byte to the end of the operand's last row
+            const int ext_a = interior ? 0x7fffffff : extent((int64_t)(M - 1 - row0) * args.lda + (K - k0));
+            const int ext_b = interior ? 0x7fffffff : extent((int64_t)(K - 1 - k0) * args.ldb + (N - col0));
             const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(a_base + k0), 0, 0x7fffffff, 0x00020000);
+                (void *)(a_base + k0), 0, ext_a, 0x00020000);
             const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(b_base + (int64_t)k0 * args.ldb), 0, 0x7fffffff, 0x00020000);
+                (void *)(b_base + (int64_t)k0 * args.ldb), 0, ext_b, 0x00020000);
 #pragma unroll
             for (int it = 0; it < A_UNITS; ++it) sa[it] = __builtin_amdgcn_raw_buffer_load_b128(ra, offa[it], 0, 0);
 #pragma unroll

@@ -301,6 +301,31 @@ def test_count_i8_repacked_operands(am, tA, tB):
         assert np.array_equal(dR.cpu().numpy(), R_ref), (tA, tB, M, N, K)
 
 
+def test_count_i8_aligned_ragged_edges(am):
+    """Aligned operands (rows on 16-byte boundaries, N a whole number of 16-byte units) whose M and N
+    are not whole tiles: the edge workgroups load through range-checked buffers instead of the
+    guarded loader.  Every matrix-core shape, full int8 range, non-zero R, K with and without a
+    partial last stage; the operands sit inside larger poisoned buffers."""
+    for idx, (M, N, K) in enumerate([(300, 400, 1008), (257, 528, 1024), (130, 272, 960), (700, 1296, 2048),
+                                     (129, 16, 64), (513, 784, 1040)]):
+        g = np.random.Generator(np.random.PCG64(480 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        bufA = torch.full((M + 3, K + 32), 99, dtype=torch.int8, device="cuda")
+        bufB = torch.full((K + 3, N + 48), -77, dtype=torch.int8, device="cuda")
+        bufA[:M, :K] = dev(A)
+        bufB[:K, :N] = dev(B)
+        for shape in range(1, am.amulet_shape_count(100)):
+            for (vA, vB) in ((dev(A), dev(B)), (bufA[:M, :K], bufB[:K, :N])):
+                dR = dev(R_in)
+                print("i8 aligned ragged", M, N, K, shape, vA.stride(0), vB.stride(0), flush=True)
+                am.amulet_count_i8_shape(shape, vA, vB, dR)
+                torch.cuda.synchronize()
+                assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K, shape)
+
+
 def test_count_i8_strided(am):
     M, N, K = 50, 130, 75
     A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)
