@@ -118,14 +118,27 @@ identity_mfma_kernel(const MmlikeArgs args)
         offb[it] = ((unsigned)(u / QB) * (unsigned)args.ldb + (unsigned)(u % QB) * 4u) * 4u;
     }
 
+    // Edge workgroups of aligned row-major operands whose N is a whole number of 16-byte units take
+    // the same loader with the buffers' extents set to where the operands end: a unit of a row
+    // of A past M lies past the extent and reads as zero, a unit of B past N reads values of the
+    // next row, or zero past the last one, and either only feeds outputs that do not exist.
+    // (Every unit that feeds an existing output is whole and inside the extent: full stages
+    // only, and N % 4 == 0.)
+    const bool edge_fast = !interior && !TA && !TB && vecA && vecB && (N & 3) == 0 &&
+                           (int64_t)MI_BM * args.lda * 4 < 0x7fffffffLL && (int64_t)MI_BK * args.ldb * 4 < 0x7fffffffLL;
+    auto extent = [](int64_t bytes) { return (int)(bytes < 0 ? 0 : bytes > 0x7fffffffLL ? 0x7fffffffLL : bytes); };
+
     f4 sa[ITERS], sb[ITERS];
     auto load_stage = [&](int k0) {
-        if (interior && k0 + MI_BK <= K) {
-            // buffer loads: scalar resource (uniform base) + 32-bit per-thread byte offset
+        if ((interior || edge_fast) && k0 + MI_BK <= K) {
+            // buffer loads: scalar resource (uniform base) + 32-bit per-thread byte offset;
+            // extent = bytes from the stage's first element to the end of the operand's last row
+            const int ext_a = interior ? 0x7fffffff : extent(((int64_t)(M - 1 - row0) * args.lda + (K - k0)) * 4);
+            const int ext_b = interior ? 0x7fffffff : extent(((int64_t)(K - 1 - k0) * args.ldb + (N - col0)) * 4);
             const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(a_base + k0), 0, 0x7fffffff, 0x00020000);
+                (void *)(a_base + k0), 0, ext_a, 0x00020000);
             const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(b_base + (int64_t)k0 * args.ldb), 0, 0x7fffffff, 0x00020000);
+                (void *)(b_base + (int64_t)k0 * args.ldb), 0, ext_b, 0x00020000);
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
                 sa[it] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(ra, offa[it], 0, 0));

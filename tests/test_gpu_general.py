@@ -133,6 +133,26 @@ def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
                 assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity trans %r %r" % (tA, tB))
 
 
+def test_identity_aligned_ragged_edges_on_the_matrix_cores(am):
+    """Aligned row-major operands (16-byte aligned rows, N a multiple of 4) whose M and N are not
+    whole tiles: the edge workgroups of the matrix-core kernel load through range-checked buffers.
+    The operands sit inside larger buffers filled with NaN, so anything read from outside them
+    that reached an existing output would show."""
+    for idx, (M, N, K) in enumerate([(300, 400, 1008), (257, 528, 1024), (130, 272, 96), (513, 784, 1040),
+                                     (129, 4, 16), (700, 1296, 208)]):
+        As, Bs, th, dis, R_in = make_case(0, 0, False, False, M, N, K, 5300 + idx)
+        R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
+        bufA = torch.full((M + 3, K + 8), float("nan"), device="cuda"); bufA[:M, :K] = dev(As)
+        bufB = torch.full((K + 3, N + 12), float("nan"), device="cuda"); bufB[:K, :N] = dev(Bs)
+        for shape in (8, 9, -1):
+            for (vA, vB) in ((dev(As), dev(Bs)), (bufA[:M, :K], bufB[:K, :N])):
+                print("identity aligned ragged", M, N, K, shape, vA.stride(0), vB.stride(0), flush=True)
+                dR = dev(R_in)
+                am.amulet_mmlike_f32_general(0, vA, vB, None, None, dR, shape=shape)
+                torch.cuda.synchronize()
+                assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity aligned ragged %d" % shape)
+
+
 def test_adaptive_execution_trials_contribute_to_the_result(am):
     import amulet_workloads as wl
     M, N, K = 8192, 8192, 48
