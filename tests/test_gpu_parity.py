@@ -326,6 +326,29 @@ def test_count_i8_aligned_ragged_edges(am):
                 assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K, shape)
 
 
+def test_count_i8_long_ragged_k(am):
+    """Aligned operands with a long K that is not a whole number of 64-byte stages (so the last
+    stage of every tile is partial), M and N ragged as well: default shape and both shapes that
+    stream whole-stage problems."""
+    for idx, (M, N, K) in enumerate([(260, 272, 4100), (512, 512, 4159), (300, 528, 4097)]):
+        g = np.random.Generator(np.random.PCG64(490 + idx))
+        A = g.integers(-128, 128, (M, K)).astype(np.int8)
+        B = g.integers(-128, 128, (K, N)).astype(np.int8)
+        R_in = g.integers(-1000, 1000, (M, N)).astype(np.int32)
+        R_ref, _ = oracle.count_i8(A, B, R_in)
+        bufA = torch.full((M, (K + 15) // 16 * 16 + 16), 99, dtype=torch.int8, device="cuda")
+        bufA[:, :K] = dev(A)
+        for shape in (-1, 6, 7):
+            dR = dev(R_in)
+            print("i8 long ragged K", M, N, K, shape, flush=True)
+            if shape < 0:
+                am.amulet_count_i8(bufA[:, :K], dev(B), dR)
+            else:
+                am.amulet_count_i8_shape(shape, bufA[:, :K], dev(B), dR)
+            torch.cuda.synchronize()
+            assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K, shape)
+
+
 def test_count_i8_strided(am):
     M, N, K = 50, 130, 75
     A, B = wl.join_indicator(M, N, K, seed=8, density=0.3)
