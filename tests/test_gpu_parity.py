@@ -454,6 +454,36 @@ def test_cfg3_join_count_full_size_sampled(am):
     assert np.array_equal(R.astype(np.int64).sum(0), A.astype(np.int64).sum(0) @ B.astype(np.int64))
 
 
+def test_join_count_odd_full_size_repacked_and_in_place_sampled(am):
+    """The join count at 8191 x 8191 x 4095 (nothing aligned, nothing a whole tile or stage), in
+    place and through the repacking workspace, in the launch configurations the library picks
+    at that size: sampled rows and columns against the oracle, and the whole-matrix checksums."""
+    M, N, K = 8191, 8191, 4095
+    A, B = wl.join_indicator(M, N, K, seed=31, density=0.05)
+    g = np.random.Generator(np.random.PCG64(4244))
+    rows = np.sort(g.choice(M, 16, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 16, replace=False)); cols[0], cols[-1] = 0, N - 1
+    R_rows, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B)
+    R_cols, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]))
+    row_sums = A.astype(np.int64) @ B.astype(np.int64).sum(1)
+    col_sums = A.astype(np.int64).sum(0) @ B.astype(np.int64)
+    dA, dB = dev(A), dev(B)
+    ws = torch.full((am.amulet_count_i8_repack_workspace_bytes(M, N, K),), 77, dtype=torch.int8, device="cuda")
+    for how in ("in place", "repacked"):
+        dR = torch.zeros(M, N, dtype=torch.int32, device="cuda")
+        print("join count odd full size", how, flush=True)
+        if how == "in place":
+            am.amulet_count_i8(dA, dB, dR)
+        else:
+            am.amulet_count_i8_general(dA, dB, dR, ws)
+        torch.cuda.synchronize()
+        R = dR.cpu().numpy()
+        assert np.array_equal(R[rows], R_rows), how
+        assert np.array_equal(R[:, cols], R_cols), how
+        assert np.array_equal(R.astype(np.int64).sum(1), row_sums), how
+        assert np.array_equal(R.astype(np.int64).sum(0), col_sums), how
+
+
 def test_tune_picks_a_valid_shape_and_result_still_matches(am):
     M, N, K = 512, 1024, 256
     chosen = am.amulet_tune(1, M, N, K)
