@@ -75,7 +75,13 @@ typedef enum {
  *
  * p is one IEEE round-to-nearest fp32 multiply and "p > thres[j]" is decided
  * on that rounded value, strictly, exactly as a plain fp32 loop would; the
- * predicate acts as a mask (the paper's "Mask -" node, Sec. 4.3.1).  The k-sum
+ * predicate acts as a mask (the paper's "Mask -" node, Sec. 4.3.1).  This holds
+ * bit for bit for DISCOUNT and COUNT_GT, whose g jumps at p = thres.  BOOST's
+ * g = p + max(p - thres, 0) is continuous in p, and the kernels evaluate it
+ * with fused multiply-adds on the unrounded product: a term differs from the
+ * rounded-product term by at most one rounding of p (2^-24 |p|, twice that for
+ * a triggered term), inside the tolerance below but not bit-identical to a
+ * loop that rounds p first.  The k-sum
  * is formed in fp32 in an order the library chooses (the paper's loop is
  * order-free, Sec. 4.1): results agree with a double-accumulating loop to
  * within 1e-5 * sum_k |term|.
@@ -300,7 +306,8 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
  * contributes its part of R ("these intermediate computations also all
  * contribute to the final result").  At most half of the rows serve as
  * trials; a task too small for two trial slabs runs whole with the default
- * shape.  The winner is cached for (task, M, N, K) as amulet_tune does.
+ * shape.  The winner is cached for the size bucket of (task, M, N, K) as
+ * amulet_tune does.
  * Unlike amulet_mmlike_f32 this call synchronises with `stream` after each
  * trial (it reads their timings); the remainder is only enqueued.  It
  * allocates no device memory.  Arguments as amulet_mmlike_f32; chosen_shape
@@ -319,7 +326,8 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K,
  * Sec. 4.4-4.6): times the candidate tile shapes of `task` on synthetic
  * operands of this size that the call allocates and frees itself, walks them
  * with the paper's two-stage greedy search, caches the winner for
- * (task, M, N, K) and synchronises `stream`.  The device is first run up to
+ * (task, M, N, K) and every size in the same bucket (each of M, N, K rounded
+ * up to a multiple of 256) and synchronises `stream`.  The device is first run up to
  * its loaded clocks, a trial is the better of two spans of about 2 ms of
  * back-to-back launches, and the search's winner replaces the built-in default
  * only if it also beats it in a direct rematch.  Unlike the compute calls this
@@ -409,6 +417,32 @@ const char *amulet_strerror(int code);
 /* HIP's text for the error behind the calling thread's last AMULET_ERR_LAUNCH
  * ("no error" if its last launch succeeded).  Static storage. */
 const char *amulet_last_launch_error(void);
+
+/*
+ * Reproducible floating-point results.  By default a launch may split K over
+ * several workgroups per tile (see the conventions at the top: few tiles, or a
+ * nearly empty last round of workgroups), whose parts reach R through float
+ * atomics in an order that differs from run to run.  With the deterministic
+ * mode on (amulet_set_deterministic(1), or AMULET_DETERMINISTIC=1 in the
+ * environment when the library is first used) no fp32 / fp64 launch splits K:
+ * every output is summed by one workgroup in a fixed order, and two calls on
+ * the same inputs with the same tile shape give the same bits, at the price of
+ * the idle compute units the split was there to fill.  The integer join count
+ * is exact either way and is not affected.  Process-wide; takes effect for
+ * calls made after it returns.
+ */
+void amulet_set_deterministic(int on);
+int amulet_get_deterministic(void);
+
+/*
+ * Test seam for the error path (the sum order and tiling of Sec. 3-4 play no
+ * part): the next n kernel-launch attempts of this process are refused on the
+ * host and reported as a failed launch, so that callers and tests can check
+ * that AMULET_ERR_LAUNCH comes back, that nothing is cached for a shape that
+ * did not run, and that R is left untouched.  Nothing reaches the device for a
+ * refused launch.  n <= 0 switches it off.
+ */
+void amulet_debug_fail_launches(int n);
 
 /* Library version string (static storage). */
 const char *amulet_version(void);

@@ -116,6 +116,12 @@ def load_library():
     lib.amulet_strerror.argtypes = [i32]
     lib.amulet_last_launch_error.restype = ctypes.c_char_p
     lib.amulet_last_launch_error.argtypes = []
+    lib.amulet_set_deterministic.restype = None
+    lib.amulet_set_deterministic.argtypes = [i32]
+    lib.amulet_get_deterministic.restype = i32
+    lib.amulet_get_deterministic.argtypes = []
+    lib.amulet_debug_fail_launches.restype = None
+    lib.amulet_debug_fail_launches.argtypes = [i32]
     lib.amulet_version.restype = ctypes.c_char_p
     lib.amulet_version.argtypes = []
     _lib = lib
@@ -449,6 +455,20 @@ def amulet_strerror(code: int) -> str:
 
 def amulet_last_launch_error() -> str:
     return load_library().amulet_last_launch_error().decode()
+
+
+def amulet_set_deterministic(on: bool) -> None:
+    """No launch splits K while on: floating-point results are reproducible bit for bit."""
+    load_library().amulet_set_deterministic(int(bool(on)))
+
+
+def amulet_get_deterministic() -> bool:
+    return bool(load_library().amulet_get_deterministic())
+
+
+def amulet_debug_fail_launches(n: int) -> None:
+    """Test seam: the next n kernel launches are refused on the host and reported as failed."""
+    load_library().amulet_debug_fail_launches(int(n))
 
 
 def amulet_version() -> str:

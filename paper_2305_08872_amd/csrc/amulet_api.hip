@@ -29,9 +29,18 @@ static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", 
                                                                 "mfma_i8_256x256_w16_dma3"};
 
 // ---- selection cache ---------------------------------------------------------
+// Keyed by task and by size buckets of 256 (the widest tile edge of any shape): sizes that share
+// a bucket triple have the same tile grid up to ragged edges, so a choice timed at 8192^3 also
+// serves 8191^3 or 8000 x 8192 x 8100.  Every shape of a task accepts every size, so a cached
+// id is always valid for the whole bucket.
 typedef std::tuple<int, int64_t, int64_t, int64_t> SelKey;
 static std::mutex g_sel_mutex;
 static std::map<SelKey, int> g_selected;
+static inline int64_t sel_bucket(int64_t n) { return (n + 255) / 256; }
+static inline SelKey sel_key(int task, int64_t M, int64_t N, int64_t K)
+{
+    return SelKey(task, sel_bucket(M), sel_bucket(N), sel_bucket(K));
+}
 
 static int n_shapes(int task)
 {
@@ -77,7 +86,7 @@ static int lookup_shape(int task, int64_t M, int64_t N, int64_t K)
 {
     {
         std::lock_guard<std::mutex> lock(g_sel_mutex);
-        auto it = g_selected.find(SelKey(task, M, N, K));
+        auto it = g_selected.find(sel_key(task, M, N, K));
         if (it != g_selected.end()) return it->second;
     }
     return default_shape(task, M, N, K);
@@ -598,7 +607,7 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
         n_load = i8_tile_up(N);
     }
     if (e != hipSuccess) { g_last_hip_error = e; return AMULET_ERR_LAUNCH; }
-    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, Kc), M, N, Kc, A, lda, B, ldb, R, ldr, stream,
+    return run_count(lookup_shape(AMULET_TASK_COUNT_I8, M, N, K), M, N, Kc, A, lda, B, ldb, R, ldr, stream,
                      m_load, n_load);
 }
 
@@ -682,7 +691,7 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const 
     if (x.next_row < M) out = run_rows(c, best, x.next_row, M - x.next_row, x.stream);
     if (out == AMULET_OK && x.trials > 0) {
         std::lock_guard<std::mutex> lock(g_sel_mutex);
-        g_selected[SelKey(task, M, N, K)] = best;
+        g_selected[sel_key(task, M, N, K)] = best;
     }
     if (chosen_shape) *chosen_shape = best;
     if (n_trials) *n_trials = x.trials;
@@ -772,7 +781,7 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
         (void)hipStreamSynchronize(c.stream);
         if (c.status == AMULET_OK) {
             std::lock_guard<std::mutex> lock(g_sel_mutex);
-            g_selected[SelKey(task, M, N, K)] = chosen;
+            g_selected[sel_key(task, M, N, K)] = chosen;
             result = chosen;
         }
     }
@@ -863,6 +872,12 @@ const char *amulet_strerror(int code)
 }
 
 const char *amulet_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
+
+void amulet_set_deterministic(int on) { g_deterministic.store(on ? 1 : 0, std::memory_order_relaxed); }
+
+int amulet_get_deterministic(void) { return k_split_allowed() ? 0 : 1; }
+
+void amulet_debug_fail_launches(int n) { g_forced_launch_failures.store(n > 0 ? n : 0, std::memory_order_relaxed); }
 
 const char *amulet_version(void) { return "amulet-gfx950 0.1"; }
 

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <atomic>
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace amulet {
 
@@ -84,16 +85,48 @@ inline bool pitch_collides(int64_t ld, int elem_bytes)
 // A grid dimension holds at most 2^32 - 1 work-items (workgroups x threads), fewer than the
 // 2^31 - 1 workgroups a tile order can have: a longer row of workgroups goes out as several
 // launches, each told in `args.block_base` where in the row it starts (the kernels add it to
-// blockIdx.x).  `launch(n)` enqueues n workgroups with the current args.
+// blockIdx.x).  `launch(n)` enqueues n workgroups with the current args.  Returns the first
+// launch error (later parts are then not sent).
+// Test seam (amulet_debug_fail_launches): while positive, each launch attempt is refused on the
+// host, counted down, and reported as hipErrorLaunchFailure; nothing reaches the device.
+inline std::atomic<int> g_forced_launch_failures{0};
+inline bool forced_launch_failure()
+{
+    int n = g_forced_launch_failures.load(std::memory_order_relaxed);
+    while (n > 0)
+        if (g_forced_launch_failures.compare_exchange_weak(n, n - 1, std::memory_order_relaxed)) return true;
+    return false;
+}
+
 template <typename Args, typename Launch>
 inline hipError_t launch_row_of_blocks(Args &args, int64_t blocks, int threads, Launch launch)
 {
     const int64_t max_blocks = 0xFFFFFFFFLL / threads;
     for (int64_t base = 0; base < blocks; base += max_blocks) {
+        if (forced_launch_failure()) return hipErrorLaunchFailure;
         args.block_base = (int)base;
         launch((unsigned)(blocks - base < max_blocks ? blocks - base : max_blocks));
+        // a refused launch (bad grid, LDS not granted, a stream in error) ends the row: the error is
+        // read, and so reset, exactly once, here, and handed up as the call's status
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    return hipGetLastError();
+    return hipSuccess;
+}
+
+// Reproducible floating-point results (amulet_set_deterministic, or AMULET_DETERMINISTIC=1 in the
+// environment when the library is first used): no launch splits K, so no tile is summed by
+// several workgroups through float atomics, whose order of arrival differs from run to run.
+inline std::atomic<int> g_deterministic{-1};   // -1: not asked yet, read the environment
+inline bool k_split_allowed()
+{
+    int d = g_deterministic.load(std::memory_order_relaxed);
+    if (d < 0) {
+        const char *e = getenv("AMULET_DETERMINISTIC");
+        d = (e && e[0] && e[0] != '0') ? 1 : 0;
+        g_deterministic.store(d, std::memory_order_relaxed);
+    }
+    return d == 0;
 }
 
 // Tail split of the vector-ALU launchers.  The chip holds `round` workgroups at once (4 waves
@@ -113,7 +146,7 @@ struct TailSplit {
 };
 inline bool choose_tail_split(int64_t real, int64_t wgs, int64_t round, int64_t K, int k_align, TailSplit &t)
 {
-    if (K < 512 || round <= 0 || real % round == 0) return false;
+    if (K < 512 || round <= 0 || real % round == 0 || !k_split_allowed()) return false;
     const int64_t tail = real % round;
     const int max_s = K / 256 < 8 ? (int)(K / 256) : 8;
     double best_cost = (double)((real + round - 1) / round);   // rounds of the plain launch
@@ -153,6 +186,7 @@ inline bool choose_tail_split(int64_t real, int64_t wgs, int64_t round, int64_t 
 inline int choose_full_split(int64_t part_tiles, int64_t units_per_xcd, int64_t K, const double *rate,
                              int n_rates)
 {
+    if (!k_split_allowed()) return 1;
     const int max_s = K / 256 < 8 ? (int)(K / 256) : 8;
     int best_s = 1;
     double best = 0.0;

@@ -315,7 +315,7 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * G * G;
-    if (2 * tiles_m * tiles_n <= compute_units() && a.K >= 256) {
+    if (k_split_allowed() && 2 * tiles_m * tiles_n <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;

@@ -236,7 +236,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = (int64_t)n_tiles * (DI_NT / 64);
-    if (2 * n_tiles <= compute_units() && a.K >= 256) {
+    if (k_split_allowed() && 2 * n_tiles <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;

@@ -463,7 +463,7 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * D_NW;
-    if (waves <= 2048 && a.K >= 128) {
+    if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
         int64_t want = 4096 / waves;
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;

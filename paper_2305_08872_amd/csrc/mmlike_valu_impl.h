@@ -610,7 +610,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * NW;
-    if (waves <= 2048 && a.K >= 128) {
+    if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
         int64_t want = 4096 / waves;   // as many as still fit the chip at once (4 waves per SIMD)
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;
@@ -629,8 +629,8 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     // A through LDS against A through the scalar cache: discount 30.4-31.0 against 31.3-31.9
     // TFLOP/s, count 36.4-37.2 against 36.9-40.4, boost within +-4 % either way).
     const bool a_through_lds = !a.transA && !a.transB && pitch_collides(a.lda, 4);
-    auto launch = [&](int64_t n_blocks, int n_splits) {
-        (void)launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
+    auto launch = [&](int64_t n_blocks, int n_splits) -> hipError_t {
+        return launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
             switch ((a.transA ? 1 : 0) | (a.transB ? 2 : 0)) {
             case 0:
@@ -665,11 +665,9 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;
         b.kchunk = t.chunk;
-        launch(t.grid, 1);
-        return hipGetLastError();
+        return launch(t.grid, 1);
     }
-    launch(wgs, splits);
-    return hipGetLastError();
+    return launch(wgs, splits);
 }
 
 // Shape id = depth index * VALU_TILES + tile index (see amulet_internal.h).

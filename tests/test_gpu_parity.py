@@ -163,6 +163,24 @@ def test_predicate_on_rounded_product(am):
     assert np.array_equal(R, R_ref)
 
 
+def test_boost_at_a_straddling_threshold_stays_inside_the_tolerance(am):
+    """The boost task is evaluated with fused operations on the unrounded product (its g is
+    continuous in p), so at a threshold that the exact product exceeds and the rounded product
+    only equals, a term may differ from the oracle's rounded-product term by one rounding of p:
+    inside the tolerance, not necessarily the same bits."""
+    a = np.float32(1 + 2.0 ** -12)
+    p32 = np.float32(a * a)
+    A = np.full((3, 5), a, np.float32)
+    B = np.full((5, 260), a, np.float32)
+    th = np.full((1, 260), p32, np.float32)
+    R0 = np.zeros((3, 260), np.float32)
+    R = run_gpu(am, 2, A, B, th, R0)
+    R_ref, ab, _ = oracle.mmlike_f32(2, A, B, th, R0)
+    assert_parity_f32(R, R_ref, ab, what="boost at a straddling threshold")
+    # the oracle itself does not trigger here (tie on the rounded product): its result is the plain sum
+    assert np.array_equal(R_ref, oracle.mmlike_f32(0, A, B, None, R0)[0])
+
+
 def test_empty_dimensions_are_noops(am):
     R = torch.full((4, 6), 2.5, device="cuda")
     am.amulet_mmlike_f32(1, torch.zeros(4, 0, device="cuda"), torch.zeros(0, 6, device="cuda"),
@@ -417,6 +435,24 @@ def test_headline_discount_8192_sampled(am):
     _sampled_rows_cols(am, "headline_discount_8192", n_rows=12, n_cols=12)
 
 
+def test_headline_discount_8192_whole_matrix_closed_form(am):
+    """The headline size in the default launch configuration on operands whose result has a
+    closed form: A = B = 1, thres = 0.5, dis = 0.5, so every product is 1, triggers, and adds
+    exactly 0.5; every one of the 8192^2 outputs must equal R_in + K / 2 bit for bit (integer
+    R_in).  A tile computed twice, skipped, or fed a wrong k range shows."""
+    M = N = K = 8192
+    dA = torch.ones(M, K, device="cuda")
+    dB = torch.ones(K, N, device="cuda")
+    dP = torch.full((2, N), 0.5, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    dR = torch.randint(-3, 4, (M, N), device="cuda", generator=g).float()
+    want = dR + K / 2
+    print("headline closed form: gpu run", flush=True)
+    am.amulet_mmlike_f32(1, dA, dB, dP, dR)
+    torch.cuda.synchronize()
+    assert torch.equal(dR, want)
+
+
 def test_query3_count_gt_4096_sampled(am):
     """Query 3 at the paper's square size: integer counts, so sampled rows and columns must
     match the oracle bit for bit (and they pass assert_parity_f32 a fortiori)."""
@@ -494,3 +530,72 @@ def test_tune_picks_a_valid_shape_and_result_still_matches(am):
     R = run_gpu(am, 1, A, B, P, np.zeros_like(R_ref))
     assert_parity_f32(R, R_ref, ab, what="after tune")
     am.amulet_clear_selections()
+
+
+def test_tuned_choice_serves_the_whole_size_bucket(am):
+    """The selection cache is keyed by size buckets of 256: a choice tuned at one size is the
+    one used at neighbouring sizes of the same bucket, and not beyond."""
+    am.amulet_clear_selections()
+    chosen = am.amulet_tune(1, 512, 1024, 256)
+    assert am.amulet_selected_shape(1, 500, 1000, 250) == chosen
+    assert am.amulet_selected_shape(1, 257, 769, 1) == chosen
+    am.amulet_clear_selections()
+    assert am.amulet_selected_shape(1, 512, 1024, 256) == am.amulet_selected_shape(1, 500, 1000, 250)
+
+
+def test_refused_launch_leaves_R_untouched_and_nothing_cached(am):
+    """Launches refused on the host (the library's test seam): every compute call reports the
+    failure, R keeps its contents, and neither amulet_tune nor the adaptive call caches a shape
+    that never ran."""
+    M, N, K = 4096, 4096, 512
+    A, B, P = wl.retail(M, N, K, seed=77)
+    dA, dB, dP = dev(A), dev(B), dev(P)
+    dR = torch.full((M, N), 3.0, device="cuda")
+    am.amulet_clear_selections()
+    before = am.amulet_selected_shape(1, M, N, K)
+    try:
+        am.amulet_debug_fail_launches(1)
+        with pytest.raises(am.AmuletError) as e:
+            am.amulet_mmlike_f32(1, dA, dB, dP, dR)
+        assert e.value.code == -5
+        am.amulet_debug_fail_launches(1 << 20)
+        with pytest.raises(am.AmuletError) as e:
+            am.amulet_tune(1, M, N, K)
+        assert e.value.code == -5
+        with pytest.raises(am.AmuletError) as e:
+            am.amulet_mmlike_f32_adaptive(1, dA, dB, dP, dR)
+        assert e.value.code == -5
+        with pytest.raises(am.AmuletError):
+            am.amulet_count_i8(torch.ones(256, 64, dtype=torch.int8, device="cuda"),
+                               torch.ones(64, 256, dtype=torch.int8, device="cuda"),
+                               torch.zeros(256, 256, dtype=torch.int32, device="cuda"))
+    finally:
+        am.amulet_debug_fail_launches(0)
+    torch.cuda.synchronize()
+    assert torch.all(dR == 3.0)
+    assert am.amulet_selected_shape(1, M, N, K) == before
+    # and the library works as before once the seam is off
+    am.amulet_mmlike_f32(1, dA, dB, dP, dR)
+    torch.cuda.synchronize()
+    rows = np.arange(0, M, 257)
+    R_ref, ab, _ = oracle.mmlike_f32(1, np.ascontiguousarray(A[rows]), B, P, np.full((len(rows), N), 3.0, np.float32))
+    assert_parity_f32(dR.cpu().numpy()[rows], R_ref, ab, np.full((len(rows), N), 3.0, np.float32), what="after the seam")
+
+
+@pytest.mark.parametrize("task,M,N,K", [(1, 256, 256, 256), (2, 64, 64, 20000), (1, 770, 6100, 1100), (0, 300, 300, 4096)])
+def test_deterministic_mode_gives_the_same_bits_twice(am, task, M, N, K):
+    """Sizes whose default launch splits K (few tiles; a nearly empty last round): with the
+    deterministic mode on, two runs agree bit for bit and match the oracle to the tolerance."""
+    A, B, params, R_in = rand_case(task, M, N, K, seed=900 + task)
+    R_ref, ab, _ = oracle.mmlike_f32(task, A, B, params, R_in)
+    was = am.amulet_get_deterministic()
+    try:
+        am.amulet_set_deterministic(True)
+        R1 = run_gpu(am, task, A, B, params, R_in)
+        R2 = run_gpu(am, task, A, B, params, R_in)
+    finally:
+        am.amulet_set_deterministic(was)
+    assert np.array_equal(R1, R2)
+    assert_parity_f32(R1, R_ref, ab, R_in, what="deterministic mode, task %d" % task)
+    R3 = run_gpu(am, task, A, B, params, R_in)   # default mode: split K, same tolerance
+    assert_parity_f32(R3, R_ref, ab, R_in, what="default mode, task %d" % task)

@@ -194,3 +194,50 @@ def test_tile_order_covers_every_tile_exactly_once(lib):
     assert am.amulet_tile_of_workgroup(8 * 4 * 512 - 1, 512, 32) == (511, 31)
     with pytest.raises(am.AmuletError):
         am.amulet_tile_of_workgroup(10 ** 9, 4, 4)
+
+
+def test_refused_launch_is_reported_by_the_vector_alu_path(lib):
+    """A launch the runtime refuses must come back as AMULET_ERR_LAUNCH from every vector-ALU task
+    and threshold form (the launcher once dropped the error and returned success).  The seam
+    refuses the launch on the host, so this runs without a GPU: the pointers are never read."""
+    one = ctypes.c_void_p(256)
+    try:
+        for task in (am.AMULET_DISCOUNT, am.AMULET_BOOST, am.AMULET_COUNT_GT):
+            for shape in range(am.amulet_shape_count(task)):
+                am.amulet_debug_fail_launches(1)
+                rc = lib.amulet_mmlike_f32_shape(task, shape, 300, 700, 200, one, 200, one, 700, one, one, 700, None)
+                assert rc == -5, (task, shape, rc)
+            for form in range(4):
+                for ta, tb in [(0, 0), (1, 0), (0, 1), (1, 1)]:
+                    am.amulet_debug_fail_launches(1)
+                    rc = lib.amulet_mmlike_f32_general(task, form, ta, tb, -1, 300, 700, 200, one, 300 if ta else 200,
+                                                       one, 200 if tb else 700, one, 700, one, one, 700, None)
+                    assert rc == -5, (task, form, ta, tb, rc)
+        # a launch that goes out in several parts stops at the part that was refused
+        am.amulet_debug_fail_launches(1)
+        assert lib.amulet_mmlike_f32(1, 64, 2 ** 31 - 2 ** 16 - 1, 4, one, 4, one, 2 ** 31, one, one, 2 ** 31, None) == -5
+        assert "fail" in am.amulet_last_launch_error().lower() or "launch" in am.amulet_last_launch_error().lower()
+        am.amulet_debug_fail_launches(1)
+        assert lib.amulet_mmlike_f64(1, 0, 300, 700, 200, one, 200, one, 700, one, 0, one, one, 700, None) == -5
+    finally:
+        am.amulet_debug_fail_launches(0)
+
+
+def test_selection_cache_is_keyed_by_size_bucket(lib):
+    """Without a tuned entry every size gets the built-in default; the default of a bucket's
+    sizes is the same function of the sizes as before (the cache key alone changed)."""
+    am.amulet_clear_selections()
+    assert am.amulet_selected_shape(1, 8192, 8192, 8192) == am.amulet_selected_shape(1, 8191, 8000, 8100)
+    with pytest.raises(am.AmuletError):
+        am.amulet_selected_shape(77, 8, 8, 8)
+
+
+def test_deterministic_mode_switch(lib):
+    was = am.amulet_get_deterministic()
+    try:
+        am.amulet_set_deterministic(True)
+        assert am.amulet_get_deterministic() is True
+        am.amulet_set_deterministic(False)
+        assert am.amulet_get_deterministic() is False
+    finally:
+        am.amulet_set_deterministic(was)
