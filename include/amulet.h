@@ -299,6 +299,33 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
                             void *stream);
 
 /*
+ * amulet_count_i8_general for callers that cannot allocate and have no
+ * workspace to lend: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same exact result; the copies of transposed, unaligned or ragged
+ * operands go into a scratch array of AMULET_STATIC_SCRATCH_BYTES (32 MiB) that
+ * is part of the library's device image: every GPU the library runs on holds
+ * its own copy from load until the process ends.  The call allocates nothing
+ * (no hipMalloc, no hipFree, no allocating library routine); its first call on
+ * a device looks the array's device address up once.
+ *   - AMULET_ERR_WORKSPACE when the copies the general call could make for
+ *     this (M, N, K) -- amulet_count_i8_repack_workspace_bytes(M, N, K), about
+ *     M*K + K*N bytes rounded up to whole tiles -- do not fit the array;
+ *     nothing is enqueued then.  Other errors as amulet_count_i8_general.
+ *   - All calls on one GPU share that GPU's array, and it keeps the last
+ *     call's contents (the copies overwrite and zero-pad what they need; no
+ *     call relies on it being clear).  Two calls whose work overlaps in time on
+ *     one GPU (different streams, or threads) race on it: serialise them, or
+ *     use amulet_count_i8_general with a workspace per stream.
+ */
+#define AMULET_STATIC_SCRATCH_BYTES (32u << 20)
+int amulet_count_i8_static(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                           const int8_t *A, int64_t lda,
+                           const int8_t *B, int64_t ldb,
+                           int32_t *R, int64_t ldr,
+                           void *stream);
+
+/*
  * Adaptive execution as the paper runs it (Sec. 4.4-4.6): the task is split
  * into disjoint row slabs; the first slabs are computed with trial tile
  * shapes, walked by the two-stage greedy search and scored by time per row,

@@ -85,6 +85,8 @@ def load_library():
     lib.amulet_count_i8_repack_workspace_bytes.argtypes = [i64, i64, i64]
     lib.amulet_count_i8_general.restype = i32
     lib.amulet_count_i8_general.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
+    lib.amulet_count_i8_static.restype = i32
+    lib.amulet_count_i8_static.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_count_i8_shape.restype = i32
     lib.amulet_count_i8_shape.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_tune.restype = i32
@@ -362,6 +364,24 @@ def amulet_count_i8_general(A, B, R, workspace=None, *, trans_a: bool = False, t
         pw, nw = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     _check(lib.amulet_count_i8_general(int(trans_a), int(trans_b), M, N, K, pa, lda, pb, ldb, pr, ldr, pw, nw,
                                        _stream_ptr(stream)), "amulet_count_i8_general")
+
+
+AMULET_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def amulet_count_i8_static(A, B, R, *, trans_a: bool = False, trans_b: bool = False, stream=None):
+    """amulet_count_i8_general without a workspace argument: the copies go into the library's own
+    static device array (AMULET_STATIC_SCRATCH_BYTES); the call allocates nothing."""
+    lib = load_library()
+    pa, ra, ca, lda = _mat(A, "torch.int8", "A")
+    pb, rb, cb, ldb = _mat(B, "torch.int8", "B")
+    pr, M, N, ldr = _mat(R, "torch.int32", "R")
+    Ma, K = (ca, ra) if trans_a else (ra, ca)
+    K2, Nb = (cb, rb) if trans_b else (rb, cb)
+    if K2 != K or Ma != M or Nb != N:
+        raise ValueError("shape mismatch between A, B and R")
+    _check(lib.amulet_count_i8_static(int(trans_a), int(trans_b), M, N, K, pa, lda, pb, ldb, pr, ldr,
+                                      _stream_ptr(stream)), "amulet_count_i8_static")
 
 
 def amulet_count_i8_shape(shape: int, A, B, R, stream=None):

@@ -611,6 +611,57 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
                      m_load, n_load);
 }
 
+// ---- the join count for callers that cannot allocate --------------------------------------
+// The workspace of amulet_count_i8_general, as a file-scope device array: one copy per GPU the
+// library is loaded on, held until the process ends.  In host code the array's name is only a
+// stand-in for the symbol; the device address is asked for once per device
+// (hipGetSymbolAddress, with that device current) and kept, and only that pointer is ever
+// handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[AMULET_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[16];   // per device, NULL until asked
+
+static int scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= 16)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
+            if (e == hipSuccess) g_scratch_ptr[dev] = p;
+        }
+        *out = g_scratch_ptr[dev];
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        return AMULET_ERR_LAUNCH;
+    }
+    return AMULET_OK;
+}
+
+int amulet_count_i8_static(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const int8_t *A,
+                           int64_t lda, const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
+    if (M == 0 || N == 0 || K == 0) return AMULET_OK;
+    // the repacking workspace is the larger of the two sizes the general call knows, so a
+    // problem that fits it may take any of that call's paths
+    const size_t need = amulet_count_i8_repack_workspace_bytes(M, N, K);
+    if (need > (size_t)AMULET_STATIC_SCRATCH_BYTES ||
+        amulet_count_i8_workspace_bytes(trans_a, trans_b, M, N, K) > (size_t)AMULET_STATIC_SCRATCH_BYTES)
+        return AMULET_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc != AMULET_OK) return rc;
+    return amulet_count_i8_general(trans_a, trans_b, M, N, K, A, lda, B, ldb, R, ldr, ws,
+                                   (size_t)AMULET_STATIC_SCRATCH_BYTES, stream);
+}
+
 int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
                           const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
 {
