@@ -6,7 +6,11 @@ A step is one amulet_mmlike_f32 call (the whole hot path: operand staging, per-p
 k-reduction, R += write-back) on synthetic retail-style inputs already resident in HBM.
 Prints one JSON line: effective GFLOP/s = 2MNK/t (the paper's SPR times two), the kernel's
 share of the fp32 vector peak ("roofline"), and the CPU oracle timed on a bounded sample of
-the same workload ("cpu_baseline", a reported baseline only).
+the same workload ("cpu_baseline", a reported baseline only).  The default run then adds a
+`configs` array to the same line: every other named workload (cfg0-cfg4, Query 3, the fp64
+variants) as a short leg of its own after the headline's timed region, with its kernel time,
+roofline fraction, sampled parity against the oracle and, for the identity task, the library
+SGEMM on the same buffers.  The exit status is 3 when any sampled parity check fails.
 """
 import argparse
 import json
@@ -32,7 +36,7 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, 5.0 POP/s
 FP64_VECTOR_PEAK_TFLOPS = 78.6  # MI355X fp64 vector peak
 
 
-def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
+def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     """Secondary line: the int8 join count (R += A.B, exact) on the matrix cores."""
     M, N, K = spec["M"], spec["N"], spec["K"]
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
@@ -74,7 +78,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
         exact = bool(np.array_equal(Rz[torch.from_numpy(rows).cuda()].cpu().numpy(), R_ref))
         cpu = {"value": round(2.0 * len(rows) * N * K / cpu_s / 1e9, 3), "unit": "GOP/s (2MNK/t)", "cores": threads,
                "kind": "oracle", "sample": "%d whole rows of the %dx%dx%d workload, %.1f s" % (len(rows), M, N, K, cpu_s)}
-    print(json.dumps({
+    return {
         "metric": "effective GOP/s (2MNK/t), int8 join count %dx%dx%d" % (M, N, K),
         "value": round(ops / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
@@ -88,11 +92,11 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> int:
                      "compulsory_bytes": M * K + K * N + 8 * M * N,
                      "mfma_probe_tops": round(probe_tops, 1),
                      "frac_of_mfma_probe": round(achieved / probe_tops, 4)},
-        "cpu_baseline": cpu, "bit_exact_on_sample": exact}))
-    return 0
+        "cpu_baseline": cpu, "bit_exact_on_sample": exact,
+        "parity_ok": None if exact is None else bool(exact)}
 
 
-def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
+def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> dict:
     """Secondary line: a task in the paper's own element type (fp64) on the vector ALU."""
     task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
     tname = wl.TASK_NAMES[task]
@@ -152,7 +156,7 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
                "cores": threads, "kind": "oracle",
                "sample": "%d whole rows of the %dx%dx%d workload, %.1f s" % (len(rows), M, N, K, cpu_s)}
         parity = float(np.max(np.abs(R_rows - R_ref) / np.where(ab > 0, ab, 1.0)))
-    print(json.dumps({
+    return {
         "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp64" % (tname, M, N, K),
         "value": round(flops / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -165,9 +169,9 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> int:
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(FP64_VECTOR_PEAK_TFLOPS / ops, 3),
                      "frac_of_op_mix_ceiling": round(achieved * ops / FP64_VECTOR_PEAK_TFLOPS, 4)},
-        "cpu_baseline": cpu, "parity_worst_ratio_on_sample": parity, "library_dgemm": lib_ratio,
-        "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)"}))
-    return 0
+        "cpu_baseline": cpu, "parity_worst_ratio_on_sample": parity,
+        "parity_ok": None if parity is None else bool(parity <= 1e-12), "library_dgemm": lib_ratio,
+        "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)"}
 
 
 def bench_nonsquare(args, am, torch) -> int:
@@ -228,42 +232,8 @@ def bench_nonsquare(args, am, torch) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="headline_discount_8192")
-    ap.add_argument("--no-tune", action="store_true", help="use the built-in default tile shape")
-    ap.add_argument("--cpu-rows", type=int, default=512,
-                    help="rows of the workload the CPU oracle is timed on (0 = skip); 512 rows of the "
-                         "headline workload are about 13 s on 16 host threads")
-    ap.add_argument("--nonsquare", choices=["discount", "boost", "count_gt", "identity"], default=None,
-                    help="instead of the workload: the paper's non-square protocol (18 shapes of equal work "
-                         "around 4096^3) for this task, in place and with packing allowed")
-    ap.add_argument("--traffic-probe", action="store_true",
-                    help="for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes, "
-                         "the counter calibration) followed by --steps launches of the kernel; prints no JSON")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over rows of A "
-              "without any exchange, but no multi-GPU run is part of it.", file=sys.stderr)
-        return 2
-
-    import numpy as np
-    import torch
-
-    import amulet_workloads as wl
-    import paper_2305_08872_amd as am
-
-    am.load_library()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 1
-    torch.cuda.set_device(0)
-
-    if args.nonsquare:
-        return bench_nonsquare(args, am, torch)
+def bench_workload(args, am, torch, np, wl) -> dict:
+    """One named workload, measured as the header says: returns the JSON record."""
     spec, A, B, P = wl.make(args.workload)
     task, M, N, K = spec["task"], spec["M"], spec["N"], spec["K"]
     if task == "count_i8":
@@ -289,7 +259,7 @@ def main() -> int:
         torch.cuda.synchronize()
         print("traffic probe done: 1 copy of %d bytes, %d launches of %s" %
               (src.numel() * 4, args.steps, am.amulet_shape_name(task, am.amulet_selected_shape(task, M, N, K))))
-        return 0
+        return {}
 
     t0 = time.perf_counter()
     shape = am.amulet_selected_shape(task, M, N, K) if args.no_tune else am.amulet_tune(task, M, N, K)
@@ -355,8 +325,9 @@ def main() -> int:
                "cores": threads, "kind": "oracle",
                "sample": "%d whole rows of the %dx%dx%d workload (%.2e products), %.1f s"
                          % (len(rows), M, N, K, float(len(rows)) * N * K, cpu_s)}
-        den = np.where(ab > 0, ab, 1.0)
-        parity = float(np.max(np.abs(R_rows.astype(np.float64) - R_ref) / den))
+        diff = np.abs(R_rows.astype(np.float64) - R_ref)
+        # outputs whose terms are all zero must match exactly
+        parity = float("inf") if np.any(diff[ab == 0] != 0) else float(np.max(diff / np.where(ab > 0, ab, 1.0)))
 
     # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/), when recorded for this workload
     traffic = None
@@ -375,12 +346,25 @@ def main() -> int:
     # register-only issue rate of this task's instruction mix on this chip (measured ceiling)
     probe = None
     mix = {"identity": 0, "discount": 1, "boost": 2, "count_gt": 3}.get(tname)
-    if mix is not None and am.amulet_shape_name(task, shape).startswith("valu"):
+    on_valu = am.amulet_shape_name(task, shape).startswith("valu")
+    if mix is not None and on_valu and args.probe:
         pps = max(am.amulet_probe_valu(mix, w) for w in (4, 8))
         probe = {"mix": tname, "tflops_equiv": round(2.0 * pps / 1e12, 3),
                  "kernel_over_probe": round(achieved_tflops / (2.0 * pps / 1e12), 4)}
 
-    out = {
+    # the stated targets: predicate tasks at >= 60 % of the fp32 vector peak at 8192^3 (above the
+    # 25 % that four lane-operations per product allow: reported as missed, with the reason);
+    # the identity task within 15 % of the library SGEMM
+    target = None
+    if tname == "identity" and lib_ratio is not None:
+        target = {"what": "identity within 15 % of the library SGEMM", "met": bool(lib_ratio["ours_over_library_rate"] >= 0.85)}
+    elif on_valu and tname != "identity":
+        frac = achieved_tflops / FP32_VECTOR_PEAK_TFLOPS
+        target = {"what": ">= 60 % of the fp32 vector peak", "met": bool(frac >= 0.60),
+                  "note": "%d vector lane-operations per product cap the metric at %.1f %% of that peak"
+                          % (ops, 100.0 / ops)}
+
+    return {
         "metric": "effective GFLOP/s (2MNK/t), %s task %dx%dx%d fp32" % (tname, M, N, K),
         "value": round(value, 1),
         "unit": "GFLOP/s",
@@ -397,7 +381,7 @@ def main() -> int:
                    "tile_shape": am.amulet_shape_name(task, shape), "tuned": not args.no_tune,
                    "tune_seconds": round(tune_s, 3)},
         "pct_of_fp32_vector_peak": round(100.0 * value / 1e3 / FP32_VECTOR_PEAK_TFLOPS, 2),
-        "roofline": {"bound": "mfma" if am.amulet_shape_name(task, shape).startswith("mfma") else "alu", "achieved": round(achieved_tflops, 3),
+        "roofline": {"bound": "alu" if on_valu else "mfma", "achieved": round(achieved_tflops, 3),
                      "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved_tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": traffic,
                      "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
@@ -407,10 +391,103 @@ def main() -> int:
         "valu_probe": probe,
         "cpu_baseline": cpu,
         "parity_worst_ratio_on_sample": parity,
+        "parity_ok": None if parity is None else bool(parity <= 1e-5),
+        "target_met": target,
         "library_sgemm": lib_ratio,
         "paper_context": "AMULET Query 1 on one Xeon 6312U thread, double: SPR 7.50 = 15.0 GFLOP/s (Table 4)",
     }
+
+
+# the other named workloads, measured after the headline's timed region in the default run
+CONFIG_LEGS = ["cfg0_discount_256", "cfg1_boost_2048", "cfg2_identity_4096", "cfg3_count_i8_8192x8192x4096",
+               "cfg4_discount_16384x2048x8192", "query3_count_gt_4096",
+               "f64_discount_4096", "f64_boost_2048", "f64_identity_4096"]
+
+
+def config_leg(name, args, am, torch, np, wl) -> dict:
+    """A short run of one more named workload (3 warm-ups, 10 timed launches, the oracle on a
+    small sample of whole rows): the figures a reader needs, without the headline's extras."""
+    t0 = time.perf_counter()
+    sub = argparse.Namespace(**vars(args))
+    sub.workload, sub.steps, sub.warmup, sub.probe = name, max(10, min(args.steps, 20)), max(3, args.warmup), False
+    M = wl.CONFIGS[name]["M"]
+    sub.cpu_rows = min(M, 64) if wl.CONFIGS[name]["task"] != "count_i8" else 16   # count_i8 samples 4 x this
+    rec = bench_workload(sub, am, torch, np, wl)
+    roof = rec["roofline"]
+    out = {"workload": name, "value": rec["value"], "unit": rec["unit"], "steps": sub.steps, "warmup": sub.warmup,
+           "ms_per_step": rec["ms_per_step"], "kernel_ms_avg": roof["kernel_ms_avg"], "dtype": rec["dtype"],
+           "tile_shape": rec["config"]["tile_shape"],
+           "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "frac_of_op_mix_ceiling",
+                                             "frac_of_mfma_probe") if k in roof},
+           "parity_on_sample": rec.get("parity_worst_ratio_on_sample", rec.get("bit_exact_on_sample")),
+           "parity_ok": rec["parity_ok"], "parity_sample": rec["cpu_baseline"]["sample"] if rec["cpu_baseline"] else None}
+    for key in ("library_sgemm", "library_dgemm"):
+        if rec.get(key):
+            out[key] = rec[key]
+    if rec.get("target_met"):
+        out["target_met"] = rec["target_met"]
+    out["seconds"] = round(time.perf_counter() - t0, 1)
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="headline_discount_8192")
+    ap.add_argument("--no-tune", action="store_true", help="use the built-in default tile shape")
+    ap.add_argument("--cpu-rows", type=int, default=512,
+                    help="rows of the workload the CPU oracle is timed on (0 = skip); 512 rows of the "
+                         "headline workload are about 13 s on 16 host threads")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="default run only: leave out the short legs over the other named workloads "
+                         "(the `configs` array of the JSON line)")
+    ap.add_argument("--nonsquare", choices=["discount", "boost", "count_gt", "identity"], default=None,
+                    help="instead of the workload: the paper's non-square protocol (18 shapes of equal work "
+                         "around 4096^3) for this task, in place and with packing allowed")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes, "
+                         "the counter calibration) followed by --steps launches of the kernel; prints no JSON")
+    args = ap.parse_args()
+    args.probe = True
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards over rows of A "
+              "without any exchange, but no multi-GPU run is part of it.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import amulet_workloads as wl
+    import paper_2305_08872_amd as am
+
+    am.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+
+    if args.nonsquare:
+        return bench_nonsquare(args, am, torch)
+    out = bench_workload(args, am, torch, np, wl)
+    if not out:
+        return 0
+    # The default run also puts every other named workload on record, each as a short leg of its
+    # own after the headline's timed region (nothing of them runs inside it).
+    if args.workload == "headline_discount_8192" and not args.no_configs:
+        legs = []
+        for name in CONFIG_LEGS:
+            torch.cuda.empty_cache()
+            legs.append(config_leg(name, args, am, torch, np, wl))
+        out["configs"] = legs
+        out["configs_seconds"] = round(sum(l["seconds"] for l in legs), 1)
     print(json.dumps(out))
+    bad = [out["config"]["workload"]] if out.get("parity_ok") is False else []
+    bad += [l["workload"] for l in out.get("configs", []) if l.get("parity_ok") is False]
+    if bad:
+        print("bench.py: sampled parity against the oracle FAILED for " + ", ".join(bad), file=sys.stderr)
+        return 3
     return 0
 
 
