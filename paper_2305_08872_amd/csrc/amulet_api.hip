@@ -3,6 +3,7 @@
 // (or a few for very tall int8 problems) on the caller's stream and returns.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -26,7 +27,7 @@ const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
                                                                 "mfma_i8_256x256_k64", "mfma_i8_128x256_k64",
                                                                 "mfma_i8_128x128_w8_k128", "mfma_i8_256x256_w16_k64", "mfma_i8_128x256_dma3",
-                                                                "mfma_i8_256x256_w16_dma3"};
+                                                                "mfma_i8_256x256_w16_dma4", "mfma_i8_256x256_w16_dma4_persistent"};
 
 // ---- selection cache ---------------------------------------------------------
 // Keyed by task and by size buckets of 256 (the widest tile edge of any shape): sizes that share
@@ -68,7 +69,9 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
         const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (tiles128 < 256) return 4;
-        return (tiles256 >= 512 && tiles256 % 256 == 0) ? 7 : 6;
+        // (from two whole rounds of 256 x 256 tiles on: the persistent form of that kernel, whose
+        // workgroups walk their tiles out of phase: 8192 x 8192 x 4096 0.242 against 0.249 ms)
+        return (tiles256 >= 512 && tiles256 % 256 == 0) ? 8 : 6;
     }
     // a dense contraction: matrix cores (the 128 x 128 tile measures 1 % ahead of the 256 x 256
     // one even at 8192^3; the selector tries both)
@@ -175,6 +178,9 @@ static int check_mmlike(const MmlikeCall &c)
     return AMULET_OK;
 }
 
+// phases of the persistent join-count kernels (see count_i8_dma_persistent_kernel)
+static int g_pers_halves = 1, g_pers_xcds = 2;
+
 // m_load / n_load: rows of A / columns of B that exist in memory (0: just M, N)
 static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
                      const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream,
@@ -191,6 +197,12 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.vecR = (aligned16(R) && ldr % 4 == 0) ? 1 : 0;
     a.kchunk = (int)K;
     a.block_base = 0;
+    a.pers_halves = g_pers_halves;
+    a.pers_xcds = g_pers_xcds;
+    if (const char *e = getenv("AMULET_I8_PHASES")) {   // diagnostic override, "halves,xcds"
+        int h = 1, x = 1;
+        if (sscanf(e, "%d,%d", &h, &x) == 2 && x >= 1 && x <= 8) { a.pers_halves = h ? 1 : 0; a.pers_xcds = x; }
+    }
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
     g_last_hip_error = e;
     return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;

@@ -244,14 +244,17 @@ struct CountArgs {
     int vecR;        // 1 when R and its row pitch allow 16-byte accesses
     int kchunk;      // k range of one workgroup when a launch splits K (set by the launcher)
     int block_base;  // added to blockIdx.x (launch_row_of_blocks)
+    // persistent streamed kernel: workgroups of the second half of an XCD's slots start half a
+    // tile out of phase (pers_halves), XCDs are spread over pers_xcds further phases
+    int pers_halves, pers_xcds;
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)
-enum { COUNT_SHAPE_COUNT = 8 };
+enum { COUNT_SHAPE_COUNT = 9 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 // direct HBM -> LDS kernels: tile (64 * wr) x 256, wr = 2 or 4
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
-hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s);
+hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent = false);
 
 // Identity task on the fp32 matrix cores; its two shape ids follow the VALU shapes:
 // a 128 x 128 tile (4 waves) and a 256 x 256 tile (16 waves).

@@ -360,20 +360,25 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
     case 4: return launch_mfma<2, 1, 2, 4, 4, 128>(a, s);  // 128 x 128 tile, 8 waves of 64 x 32, 128-byte stages
     case 5: return launch_mfma<2, 2, 4, 4, 4, 64>(a, s);   // 256 x 256 tile, 16 waves of 64 x 64
     case 6:   // 128 x 256 tile streamed HBM -> LDS directly
-    case 7: { // 256 x 256 tile, 16 waves, streamed HBM -> LDS directly
+    case 7:   // 256 x 256 tile, 16 waves, streamed HBM -> LDS directly
+    case 8: { // the same tile with persistent workgroups (one per compute unit) walking the tile order
         // The streamed kernels take whole tiles of aligned operands with K % 64 == 0.  A problem
         // with ragged M or N is cut into its interior (whole tiles, streamed) and up to two edge
         // strips (bottom rows, right-hand columns) that the register-staged kernel of the same
         // tile handles: the three launches write disjoint parts of R.
-        const bool aligned = a.vecA && a.vecB && a.vecR && a.K % 64 == 0;
-        int wr = (shape == 7) ? 4 : 2;
+        // (and rows short enough for the streamed kernels' 32-bit lane offsets: 256 rows of A,
+        // 64 k rows of B)
+        const bool aligned = a.vecA && a.vecB && a.vecR && a.K % 64 == 0 &&
+                             a.lda <= (int64_t)(0xFFFFFFFFu - 64) / 256 && a.ldb <= (int64_t)(0xFFFFFFFFu - 256) / 64;
+        int wr = shape == 6 ? 2 : 4;
+        const bool persistent = shape == 8;
         if (wr == 4 && a.M < 256) wr = 2;
         const int bm = 64 * wr;
         const int Mi = aligned ? a.M - a.M % bm : 0, Ni = aligned ? a.N - a.N % 256 : 0;
         if (Mi == 0 || Ni == 0) return launch_mfma<2, 2, 2, 4, 4, 64>(a, s);
         CountArgs in = a;
         in.M = Mi; in.N = Ni;
-        hipError_t e = launch_count_i8_dma(in, wr, s);
+        hipError_t e = launch_count_i8_dma(in, wr, s, persistent && wr == 4);
         if (e == hipSuccess && a.M > Mi) {          // bottom strip: rows Mi.., all columns
             CountArgs bot = a;
             bot.A = a.A + (int64_t)Mi * a.lda; bot.R = a.R + (int64_t)Mi * a.ldr; bot.M = a.M - Mi;

@@ -54,47 +54,51 @@ struct DmaTile {
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
 };
 
+// the operand ring (and, after the K loop, the image the result tile is transposed through)
+extern __shared__ __attribute__((aligned(16))) int8_t dma_smem[];
+
+// One work item: the product of rows [row0, row0 + 64 WR) of A with columns [col0, col0 + 256) of B
+// over k in [kb, kb + K), K a multiple of 64, added to that tile of R.  `ksplit`: several
+// workgroups own the tile at once (split K) and add their parts with integer atomics.  All waves
+// of the workgroup call it together; the LDS ring may be reused as soon as it returns.
 template <int WR, int NSTAGE>
-__global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4, 4)))
-count_i8_dma_kernel(const CountArgs args)
+__device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, const int col0, const int kb,
+                                         const int K, const bool ksplit)
 {
     typedef DmaTile<WR, NSTAGE> T;
     static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
-    constexpr int DM_BM = T::BM, DM_A_BYTES = T::A_BYTES, DM_STAGE_BYTES = T::STAGE_BYTES;
+    constexpr int DM_A_BYTES = T::A_BYTES, DM_STAGE_BYTES = T::STAGE_BYTES;
     constexpr int NW = T::NW, B_LOADS = T::B_LOADS;
     static_assert(WR == 2 || WR == 4, "wave grid is 2 x 4 or 4 x 4");
-    extern __shared__ __attribute__((aligned(16))) int8_t dma_smem[];
 
-    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
-    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
-    const bool ksplit = gridDim.y > 1;
-    const int kb = ksplit ? (int)blockIdx.y * args.kchunk : 0;
-    const int K = ksplit ? ((args.K - kb < args.kchunk) ? args.K - kb : args.kchunk) : args.K;
-    const int tid = threadIdx.x;
+    // The thread index is made opaque per item: everything derived from it is then recomputed at
+    // the start of each item (a few vector instructions) instead of being hoisted out of a
+    // persistent workgroup's item loop and held in registers, or spilled, across the K loop.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // WR x 4 grid
     const int wr = wave >> 2, wc = wave & 3;
     const int li = lane & 31, lh = lane >> 5;
 
-    // XCD-aware tile order (xcd_tile in amulet_internal.h)
-    const int tiles_m = args.M / DM_BM, tiles_n = args.N / DM_BN;
-    int tm, tn;
-    if (!xcd_tile((int)blockIdx.x + args.block_base, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
-    const int row0 = tm * DM_BM, col0 = tn * DM_BN;
-
     // ---- what each lane fetches: one A slot and B_LOADS B slots per stage ----------------
+    // An address is a wave-uniform base in scalar registers (tile origin and stage, advanced on
+    // the scalar unit) plus a 32-bit byte offset per lane that never changes (the launcher runs
+    // this kernel only where those offsets fit: count_i8_dma_eligible).
     // A: wave w owns LDS slots [64w, 64w+64): slot s = 64w + lane -> row s/4, physical unit s%4
     const int a_row = wave * 16 + (lane >> 2);
     const int a_log = (lane & 3) ^ ((a_row >> 2) & 3);
-    const int8_t *ga = args.A + (int64_t)(row0 + a_row) * args.lda + kb + a_log * 16;
+    const uint32_t a_voff = (uint32_t)a_row * (uint32_t)args.lda + (uint32_t)(a_log * 16);
+    const int8_t *const a_base = args.A + (int64_t)row0 * args.lda + kb;
     // B: wave w owns slot groups j = w (+ NW): slot s = 64j + lane -> k row s/16, physical unit s%16
-    const int8_t *gb[B_LOADS];
+    uint32_t b_voff[B_LOADS];
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) {
         const int krow = (wave + NW * q) * 4 + (lane >> 4);
         const int blog = (lane & 15) ^ ((krow & 7) << 1);
-        gb[q] = args.B + (int64_t)(kb + krow) * args.ldb + col0 + blog * 16;
+        b_voff[q] = (uint32_t)krow * (uint32_t)args.ldb + (uint32_t)(blog * 16);
     }
+    const int8_t *const b_base = args.B + (int64_t)kb * args.ldb + col0;
     const int64_t b_stage = (int64_t)DM_BK * args.ldb;
 
     // The loads are written as asm so that the compiler's wait-count pass does not see a
@@ -103,18 +107,18 @@ count_i8_dma_kernel(const CountArgs args)
     // hand below: s_waitcnt vmcnt(loads per stage) / vmcnt(0) before the stage's barrier.  M0 carries the
     // wave-uniform LDS destination; each lane's 16 bytes land at M0 + 16 * lane.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)dma_smem;
-    auto dma16 = [&](const int8_t *g, uint32_t lds_addr) {
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    auto dma16 = [&](const int8_t *base, uint32_t voff, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                      :
-                     : "v"(g), "s"(lds_addr)
+                     : "v"(voff), "s"(base), "s"(lds_addr)
                      : "memory", "m0");
     };
     auto issue = [&](int stage, int buf) {
         const uint32_t base = lds_base + (uint32_t)(buf * DM_STAGE_BYTES);
-        dma16(ga + (int64_t)stage * DM_BK, base + (uint32_t)wave * 1024u);
+        dma16(a_base + (int64_t)stage * DM_BK, a_voff, base + (uint32_t)wave * 1024u);
 #pragma unroll
         for (int q = 0; q < B_LOADS; ++q)
-            dma16(gb[q] + (int64_t)stage * b_stage, base + (uint32_t)(DM_A_BYTES + (wave + NW * q) * 1024));
+            dma16(b_base + (int64_t)stage * b_stage, b_voff[q], base + (uint32_t)(DM_A_BYTES + (wave + NW * q) * 1024));
     };
 
     // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
@@ -233,6 +237,29 @@ count_i8_dma_kernel(const CountArgs args)
     static_assert(64 * IMG_PITCH * 4 <= NSTAGE * DM_STAGE_BYTES, "the image must fit in the ring");
     constexpr int ROWS_PER_WAVE = 64 / NW;
     int32_t *const img = (int32_t *)dma_smem;
+    // The write-back is a chain of round trips to HBM (read the rows of R, add, store), and it is
+    // short only if many of them are in flight at once.  R has one owner, so its rows may be read
+    // as early as registers allow: the fragment registers are free once the last matrix
+    // instruction has issued, which is room for DEPTH groups of four rows per wave.  Those are
+    // requested before the first part's scatter and barriers, and each group's registers are
+    // refilled with the rows DEPTH groups later as soon as its sums are formed.
+    constexpr int GROUP = 4, GROUPS = ROWS_PER_WAVE / GROUP, NGROUPS = WR * GROUPS, DEPTH = 2;
+    static_assert(ROWS_PER_WAVE % GROUP == 0, "a wave's rows of a part come in groups of four");
+    v4i rbuf[DEPTH][GROUP];
+    // group q of the tile: part q / GROUPS, rows (q % GROUPS) * GROUP .. + GROUP - 1 of this wave's share.
+    // A row's address is a wave-uniform base (scalar registers) plus 16 bytes per lane.
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    auto r_row = [&](int q, int j) {
+        const int row = (q / GROUPS) * 64 + wave * ROWS_PER_WAVE + (q % GROUPS) * GROUP + j;
+        char *base = (char *)(args.R + (int64_t)(row0 + row) * args.ldr + col0);   // uniform over the wave
+        return (v4i *)(base + lane16);
+    };
+    if (!ksplit) {
+#pragma unroll
+        for (int q = 0; q < DEPTH && q < NGROUPS; ++q)
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_row(q, j));
+    }
 #pragma unroll
     for (int part = 0; part < WR; ++part) {
         __builtin_amdgcn_s_barrier();          // the ring (or the previous part's image) is no longer read
@@ -248,28 +275,105 @@ count_i8_dma_kernel(const CountArgs args)
                         img[r * IMG_PITCH + (wc * 2 + ni) * 32 + li] = acc[mi][ni][v];
                     }
         }
-        __syncthreads();
+        // The image is complete for everyone once each wave's LDS writes are done: wait for those
+        // only.  (__syncthreads() is a full fence: it would also wait for the rows of R already
+        // requested from HBM, and put their latency back into every part.)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (ksplit) {
 #pragma unroll
-        for (int j = 0; j < ROWS_PER_WAVE; ++j) {
-            const int r = wave * ROWS_PER_WAVE + j;           // row of the part this wave adds
-            if (ksplit) {
+            for (int j = 0; j < ROWS_PER_WAVE; ++j) {
+                const int r = wave * ROWS_PER_WAVE + j;           // row of the part this wave adds
                 // several workgroups own this tile: integer atomic adds (exact in any order),
                 // 256 contiguous bytes per wave instruction
                 int32_t *drow = args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     atomicAdd(drow + e * 64 + lane, img[r * IMG_PITCH + e * 64 + lane]);
-                continue;
             }
-            const v4i part4 = *(const v4i *)(img + r * IMG_PITCH + lane * 4);
-            v4i *dst = (v4i *)(args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0 + lane * 4);
-            v4i cur = *dst;
-            cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
-            cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
-            cur.z = (int)((uint32_t)cur.z + (uint32_t)part4.z);
-            cur.w = (int)((uint32_t)cur.w + (uint32_t)part4.w);
-            *dst = cur;
+            continue;
         }
+#pragma unroll
+        for (int grp = 0; grp < GROUPS; ++grp) {
+            const int q = part * GROUPS + grp;
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) {
+                const v4i part4 = *(const v4i *)(img + (wave * ROWS_PER_WAVE + grp * GROUP + j) * IMG_PITCH + lane * 4);
+                v4i cur = rbuf[q % DEPTH][j];
+                cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
+                cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
+                cur.z = (int)((uint32_t)cur.z + (uint32_t)part4.z);
+                cur.w = (int)((uint32_t)cur.w + (uint32_t)part4.w);
+                __builtin_nontemporal_store(cur, r_row(q, j));
+                if (q + DEPTH < NGROUPS) rbuf[q % DEPTH][j] = __builtin_nontemporal_load(r_row(q + DEPTH, j));   // this register's next row
+            }
+        }
+    }
+}
+
+template <int WR, int NSTAGE>
+__global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4, 4)))
+count_i8_dma_kernel(const CountArgs args)
+{
+    typedef DmaTile<WR, NSTAGE> T;
+    // Split K (gridDim.y > 1, chosen by the host when the tiles are too few to fill the chip):
+    // this workgroup multiplies k in [kb, kb + kchunk) only and adds its part to R atomically.
+    const bool ksplit = gridDim.y > 1;
+    const int kb = ksplit ? (int)blockIdx.y * args.kchunk : 0;
+    const int K = ksplit ? ((args.K - kb < args.kchunk) ? args.K - kb : args.kchunk) : args.K;
+    // XCD-aware tile order (xcd_tile in amulet_internal.h)
+    const int tiles_m = args.M / T::BM, tiles_n = args.N / DM_BN;
+    int tm, tn;
+    if (!xcd_tile((int)blockIdx.x + args.block_base, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    dma_item<WR, NSTAGE>(args, tm * T::BM, tn * DM_BN, kb, K, ksplit);
+}
+
+// Persistent form: one launch of as many workgroups as the chip holds at once (a compute unit
+// holds one 256 x 256 workgroup or two 128 x 256 ones), each walking its share of its XCD's part
+// of the tile order: workgroup b (XCD b % 8, slot b / 8 of n_slots) takes the places slot,
+// slot + n_slots, ... of that part, so the workgroups resident on an XCD at any moment still
+// form the compact block of R that shares A rows and B columns through that L2.
+//
+// What the loop is for: all tiles take equally long, so workgroups launched together reach their
+// write-back together, and the launch alternates between a phase in which only the matrix cores
+// work and one in which only the memory system does (the read-modify-write of R ran at HBM
+// speed for a third of the launch, with the matrix cores idle).  Here a workgroup's first item is
+// only a leading fraction `phase / 16` of its first tile's k range, and the rest of that range is
+// its last item (same owner, plain adds: "+=" makes a tile in two passes as good as in one), so
+// that from then on the workgroups of different phases write back at different times: the two
+// workgroups sharing a compute unit half a tile apart (`halves`: one multiplies while the other
+// writes), and the XCDs spread over the remainder (`xcds` phases).
+template <int WR, int NSTAGE>
+__global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4, 4)))
+count_i8_dma_persistent_kernel(const CountArgs args)
+{
+    typedef DmaTile<WR, NSTAGE> T;
+    const int tiles_m = args.M / T::BM, tiles_n = args.N / DM_BN;
+    const XcdParts g = xcd_parts(tiles_m, tiles_n);
+    const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3, n_slots = (int)gridDim.x >> 3;
+    const int places = g.cw * g.rh;              // places of one XCD's part (some may be padding)
+    auto tile_at = [&](int place, int &row0, int &col0) {
+        const int tn = (xcd % g.px) * g.cw + place % g.cw;
+        const int tm = (xcd / g.px) * g.rh + place / g.cw;
+        row0 = tm * T::BM;
+        col0 = tn * DM_BN;
+        return tn < tiles_n && tm < tiles_m;
+    };
+    int phase = 0;                               // sixteenths of a tile's k range
+    if (args.pers_halves && 2 * slot >= n_slots) phase += 8;
+    if (args.pers_xcds > 1) phase += (xcd % args.pers_xcds) * (args.pers_halves ? 8 : 16) / args.pers_xcds;
+    phase &= 15;
+    const int kq = (int)((int64_t)(args.K / DM_BK) * phase / 16) * DM_BK;
+    int row0, col0;
+    const int n_mine = slot < places ? (places - slot + n_slots - 1) / n_slots : 0;   // places slot, slot + n_slots, ...
+    const bool split_first = kq > 0 && n_mine > 0 && tile_at(slot, row0, col0);
+    const int n_steps = n_mine + (split_first ? 1 : 0);
+    for (int step = 0; step < n_steps; ++step) {
+        int place = slot + step * n_slots, kb = 0, kl = args.K;
+        if (split_first && step == 0) kl = kq;
+        if (split_first && step == n_mine) { place = slot; kb = kq; kl = args.K - kq; }
+        if (!tile_at(place, row0, col0)) continue;   // padding (uniform over the workgroup)
+        dma_item<WR, NSTAGE>(args, row0, col0, kb, kl, false);
+        __builtin_amdgcn_s_barrier();            // every wave is done with the ring and the image
     }
 }
 
@@ -277,7 +381,10 @@ count_i8_dma_kernel(const CountArgs args)
 // (everything interior and aligned).
 bool count_i8_dma_eligible(const CountArgs &a, int wr)
 {
-    return a.vecA && a.vecB && a.vecR && a.M % (64 * wr) == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
+    // a lane's fixed byte offset from its tile's origin must fit 32 bits: the tile's last row of A,
+    // the stage's last k row of B
+    const bool offsets_fit = a.lda <= (int64_t)(0xFFFFFFFFu - 64) / (64 * wr) && a.ldb <= (int64_t)(0xFFFFFFFFu - 256) / DM_BK;
+    return offsets_fit && a.vecA && a.vecB && a.vecR && a.M % (64 * wr) == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
 }
 
 template <int WR, int NSTAGE>
@@ -309,9 +416,42 @@ static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
     });
 }
 
-hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s)
+// Workgroups of the persistent form: what one XCD holds at once (its share of the compute units
+// times the workgroups one unit holds: one of 256 x 256, two of 128 x 256), times 8.  Zero when the
+// persistent form does not apply: every workgroup should have at least two tiles to walk, and the
+// launch must fit one grid.
+template <int WR>
+static int64_t persistent_grid(const CountArgs &a)
 {
-    return wr == 4 ? launch_dma<4, 4>(a, s) : launch_dma<2, 3>(a, s);
+    const int64_t tiles_m = a.M / (64 * WR), tiles_n = a.N / DM_BN;
+    const XcdParts g = xcd_parts(tiles_m, tiles_n);
+    const int64_t places = (int64_t)g.cw * g.rh;
+    const int64_t slots = (int64_t)(compute_units() / 8) * (WR == 4 ? 1 : 2);
+    if (slots <= 0 || places < 2 * slots || a.K < 2 * DM_BK) return 0;
+    return 8 * slots;
+}
+
+template <int WR, int NSTAGE>
+static hipError_t launch_dma_persistent(const CountArgs &a, hipStream_t s)
+{
+    typedef DmaTile<WR, NSTAGE> T;
+    const int64_t grid = persistent_grid<WR>(a);
+    if (grid == 0) return launch_dma<WR, NSTAGE>(a, s);
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&count_i8_dma_persistent_kernel<WR, NSTAGE>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    if (granted != hipSuccess) return granted;
+    CountArgs b = a;
+    b.kchunk = a.K;
+    b.block_base = 0;
+    if (forced_launch_failure()) return hipErrorLaunchFailure;
+    hipLaunchKernelGGL((count_i8_dma_persistent_kernel<WR, NSTAGE>), dim3((unsigned)grid), dim3(T::NT), T::LDS_BYTES, s, b);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent)
+{
+    if (wr == 4) return persistent ? launch_dma_persistent<4, 4>(a, s) : launch_dma<4, 4>(a, s);
+    return launch_dma<2, 3>(a, s);
 }
 
 }  // namespace amulet

@@ -211,7 +211,7 @@ def test_last_round_of_workgroups_split_over_k(am, task, shape):
 
 
 # ---- join count -----------------------------------------------------------------
-@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("shape", [None, 0, 1, 2, 3, 4, 5, 6, 7, 8])
 def test_count_i8_bit_exact_ragged(am, shape):
     for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (1, 1, 1), (257, 129, 1000), (64, 64, 64),
                                        (300, 272, 128), (512, 256, 192), (256, 512, 64), (384, 768, 448),
@@ -230,7 +230,7 @@ def test_count_i8_bit_exact_ragged(am, shape):
         assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
 
 
-@pytest.mark.parametrize("shape", [None, 1, 3, 5, 6, 7])
+@pytest.mark.parametrize("shape", [None, 1, 3, 5, 6, 7, 8])
 def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
     """Tiny M x N with a long K: K is split over several workgroups per tile, which add their parts
     to R with integer atomics (exact in any order), in the streamed and the register-staged kernels."""
@@ -248,6 +248,39 @@ def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
             am.amulet_count_i8_shape(shape, dev(A), dev(B), dR)
         torch.cuda.synchronize()
         assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
+
+
+@pytest.mark.parametrize("phases", ["1,1", "0,1", "1,4", "0,8", "1,2"])
+@pytest.mark.parametrize("shape", [8, None])
+def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
+    """Sizes large enough for the persistent streamed kernels (every workgroup walks at least two
+    tiles of its XCD's part), with ragged edges around the whole-tile interior and a K of five
+    stages, so that a workgroup's first tile is summed in two passes (2 + 3 stages, or 1 + 4 ...
+    by phase).  Every phase arrangement, full int8 value range, non-zero R_in, bit-exact; the row
+    and column checksums cover the whole matrix, sampled rows and columns go against the oracle."""
+    monkeypatch.setenv("AMULET_I8_PHASES", phases)
+    M, N, K = (8192 + 77, 4096 + 33, 320) if shape is not None else (8192, 8192, 320)
+    g = np.random.Generator(np.random.PCG64(377 + (shape or 0)))
+    A = g.integers(-128, 128, (M, K)).astype(np.int8)
+    B = g.integers(-128, 128, (K, N)).astype(np.int8)
+    dR = torch.full((M, N), 7, dtype=torch.int32, device="cuda")
+    print("i8 persistent case", shape, phases, M, N, K, flush=True)
+    if shape is None:
+        assert am.amulet_selected_shape(am.AMULET_TASK_COUNT_I8, M, N, K) == 8   # the default at this size
+        am.amulet_count_i8(dev(A), dev(B), dR)
+    else:
+        am.amulet_count_i8_shape(shape, dev(A), dev(B), dR)
+    torch.cuda.synchronize()
+    R = dR.cpu().numpy()
+    rows = np.sort(g.choice(M, 40, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 40, replace=False)); cols[0], cols[-1] = 0, N - 1
+    R_ref, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B, np.full((len(rows), N), 7, np.int32))
+    assert np.array_equal(R[rows], R_ref)
+    R_ref, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]), np.full((M, len(cols)), 7, np.int32))
+    assert np.array_equal(R[:, cols], R_ref)
+    A64, B64 = A.astype(np.int64), B.astype(np.int64)
+    assert np.array_equal(R.astype(np.int64).sum(1), A64 @ B64.sum(1) + 7 * N)
+    assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64 + 7 * M)
 
 
 @pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True), (False, False)])
