@@ -40,7 +40,8 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # AMULET_ORACLE_LIB: a build of amulet_oracle.c made elsewhere (the sanitizer test's)
+        lib = ctypes.CDLL(os.environ.get("AMULET_ORACLE_LIB") or build())
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.oracle_mmlike_f32.restype = i32
         lib.oracle_mmlike_f32.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64,
