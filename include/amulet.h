@@ -331,7 +331,10 @@ int amulet_count_i8_static(int trans_a, int trans_b, int64_t M, int64_t N, int64
 /*
  * Adaptive execution as the paper runs it (Sec. 4.4-4.6): the task is split
  * into disjoint row slabs; the first slabs are computed with trial tile
- * shapes, walked by the two-stage greedy search and scored by time per row,
+ * shapes, walked by the two-stage greedy search (first the k axis of the
+ * shape grid: staging depth, then every tile's K in 1, 2, 4, 8 parts, the
+ * paper's k_c sequence K, K/2, K/4, ...; then the tile axis upward with an
+ * early stop, its n_c walk) and scored by time per row,
  * and the rest of the task runs with the winner, so every trial also
  * contributes its part of R ("these intermediate computations also all
  * contribute to the final result").  At most half of the rows serve as
@@ -350,6 +353,23 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K,
                                const float *params,
                                float *R, int64_t ldr,
                                void *stream, int *chosen_shape, int *n_trials);
+
+/*
+ * The same adaptive execution for the general form of the test queries
+ * (Sec. 6.3; the paper adapts every kernel it generates): threshold operand
+ * form and transposed layouts as in amulet_mmlike_f32_general, the remaining
+ * arguments as in amulet_mmlike_f32_adaptive, which is this call with thres[j],
+ * no transposition and planar params.  Row slabs of a transposed A are column
+ * ranges of its storage, of thres[i] / thres[i][j] the matching rows.
+ */
+int amulet_mmlike_f32_adaptive_general(int task, int thres_form, int trans_a, int trans_b,
+                                       int64_t M, int64_t N, int64_t K,
+                                       const float *A, int64_t lda,
+                                       const float *B, int64_t ldb,
+                                       const float *thres, int64_t ldt,
+                                       const float *dis,
+                                       float *R, int64_t ldr,
+                                       void *stream, int *chosen_shape, int *n_trials);
 
 /*
  * Adaptive shape selection (the stand-in for the paper's adaptive execution,

@@ -64,6 +64,9 @@ def load_library():
     lib.amulet_mmlike_f32_adaptive.restype = i32
     lib.amulet_mmlike_f32_adaptive.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp,
                                                ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.amulet_mmlike_f32_adaptive_general.restype = i32
+    lib.amulet_mmlike_f32_adaptive_general.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64,
+                                                       vp, vp, i64, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.amulet_count_i8.restype = i32
     lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_pitch_collides.restype = i32
@@ -250,6 +253,19 @@ def amulet_mmlike_f32_general(task: int, A, B, thres, dis, R, *, thres_form: int
     args = _general_args("torch.float32", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
     _check(lib.amulet_mmlike_f32_general(task, thres_form, int(trans_a), int(trans_b), shape, *args,
                                          _stream_ptr(stream)), "amulet_mmlike_f32_general")
+
+
+def amulet_mmlike_f32_adaptive_general(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
+                                       trans_a: bool = False, trans_b: bool = False, stream=None):
+    """The general test-query form with the paper's in-flight adaptive execution.  Returns
+    (chosen shape id, number of trial slabs)."""
+    lib = load_library()
+    args = _general_args("torch.float32", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
+    chosen, trials = ctypes.c_int(-1), ctypes.c_int(0)
+    _check(lib.amulet_mmlike_f32_adaptive_general(task, thres_form, int(trans_a), int(trans_b), *args,
+                                                  _stream_ptr(stream), ctypes.byref(chosen), ctypes.byref(trials)),
+           "amulet_mmlike_f32_adaptive_general")
+    return chosen.value, trials.value
 
 
 def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,

@@ -18,10 +18,16 @@
 namespace amulet {
 
 const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT] = {
-    {4, 1, 4, 8, "valu_16x256_k8"},   {4, 1, 8, 8, "valu_32x256_w8_k8"},
-    {8, 1, 8, 8, "valu_64x256_k8"},   {4, 2, 8, 8, "valu_32x512_k8"},
-    {4, 1, 4, 16, "valu_16x256_k16"}, {4, 1, 8, 16, "valu_32x256_w8_k16"},
-    {8, 1, 8, 16, "valu_64x256_k16"}, {4, 2, 8, 16, "valu_32x512_k16"},
+    {4, 1, 4, 8, 0, "valu_16x256_k8"},      {4, 1, 8, 8, 0, "valu_32x256_w8_k8"},
+    {8, 1, 8, 8, 0, "valu_64x256_k8"},      {4, 2, 8, 8, 0, "valu_32x512_k8"},
+    {4, 1, 4, 16, 0, "valu_16x256_k16"},    {4, 1, 8, 16, 0, "valu_32x256_w8_k16"},
+    {8, 1, 8, 16, 0, "valu_64x256_k16"},    {4, 2, 8, 16, 0, "valu_32x512_k16"},
+    {4, 1, 4, 16, 2, "valu_16x256_k16_s2"}, {4, 1, 8, 16, 2, "valu_32x256_w8_k16_s2"},
+    {8, 1, 8, 16, 2, "valu_64x256_k16_s2"}, {4, 2, 8, 16, 2, "valu_32x512_k16_s2"},
+    {4, 1, 4, 16, 4, "valu_16x256_k16_s4"}, {4, 1, 8, 16, 4, "valu_32x256_w8_k16_s4"},
+    {8, 1, 8, 16, 4, "valu_64x256_k16_s4"}, {4, 2, 8, 16, 4, "valu_32x512_k16_s4"},
+    {4, 1, 4, 16, 8, "valu_16x256_k16_s8"}, {4, 1, 8, 16, 8, "valu_32x256_w8_k16_s8"},
+    {8, 1, 8, 16, 8, "valu_64x256_k16_s8"}, {4, 2, 8, 16, 8, "valu_32x512_k16_s8"},
 };
 
 static const char *const kCountShapeNames[COUNT_SHAPE_COUNT] = {"count_simple", "mfma_i8_128x128_k64",
@@ -45,7 +51,7 @@ static inline SelKey sel_key(int task, int64_t M, int64_t N, int64_t K)
 
 static int n_shapes(int task)
 {
-    if (task == TASK_IDENTITY) return VALU_SHAPE_COUNT + 2;  // plus the two matrix-core tiles
+    if (task == TASK_IDENTITY) return IDENTITY_MFMA_BIG_SHAPE + 1;  // eight vector-ALU shapes and the two matrix-core tiles
     if (task > TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
     if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
     return 0;
@@ -146,6 +152,7 @@ static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
     a.vecA = (aligned16(c.A) && c.lda % 4 == 0) ? 1 : 0;
     a.kchunk = (int)c.K;
     a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1; a.block_base = 0;
+    a.force_splits = 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     switch (c.task) {
@@ -300,25 +307,41 @@ struct AdaptiveCtx {
     hipEvent_t e0, e1;
     int status;
     int trials;
-    double best_valu_score;  // lowest score a vector-ALU shape reached
+    double best_score;    // lowest score of any trial so far, and the shape that reached it
+    int best_shape;
+    double score_of[VALU_SHAPE_COUNT];   // score of a shape already tried (negative: not yet)
 };
 
+static bool is_mfma_shape(int task, int shape) { return task == TASK_IDENTITY && shape >= IDENTITY_MFMA_SHAPE; }
+
+// Rows of one trial slab: enough row tiles for 1280 workgroups, i.e. one and a quarter rounds of
+// 4-wave workgroups on 256 compute units, two and a half of 8-wave ones.  (A slab of exactly one
+// round measured 20 % below the steady rate, its first and last workgroups running on a
+// half-empty chip, and seven such slabs cost an 8192^3 call 12 %; at this size six cost 1-2 %.)
 static int64_t trial_rows(const MmlikeCall &c, int shape)
 {
-    // enough row tiles for about five workgroups on each of the 256 compute units
     int64_t tile_rows = 128, tile_cols = 128;
-    if (shape == IDENTITY_MFMA_BIG_SHAPE) tile_rows = tile_cols = 256;
-    if (shape < VALU_SHAPE_COUNT) {
-        tile_rows = (int64_t)kValuShapes[shape].NW * kValuShapes[shape].TM;
-        tile_cols = 256LL * kValuShapes[shape].NG;
+    const bool mfma = is_mfma_shape(c.task, shape);
+    if (mfma && shape == IDENTITY_MFMA_BIG_SHAPE) tile_rows = tile_cols = 256;
+    int64_t want_tiles = 1280;
+    if (!mfma) {
+        const ValuShapeDesc &d = kValuShapes[shape];
+        tile_rows = (int64_t)d.NW * d.TM;
+        tile_cols = 256LL * d.NG;
+        // a shape that sums every tile's K in s parts launches s workgroups per tile
+        if (d.splits > 1 && c.K >= 128) {
+            int64_t sp = d.splits;
+            if (sp > c.K / 64) sp = c.K / 64;
+            want_tiles /= sp > 1 ? sp : 1;
+        }
+    } else {
+        // (matrix-core tiles: a compute unit is at full rate with three resident 128 x 128 tiles,
+        // and holds one 256 x 256 tile at a time, so three tiles resp. one tile per unit is enough)
+        want_tiles = shape == IDENTITY_MFMA_BIG_SHAPE ? 256 : 768;
     }
     const int64_t tiles_n = (c.N + tile_cols - 1) / tile_cols;
-    // (matrix-core tiles: a compute unit is at full rate with three resident 128 x 128 tiles,
-    // and holds one 256 x 256 tile at a time, so three tiles resp. one tile per unit is enough)
-    const int64_t want_tiles = shape == IDENTITY_MFMA_BIG_SHAPE ? 256
-                               : shape == IDENTITY_MFMA_SHAPE   ? 768
-                                                                : 1280;
-    const int64_t row_tiles = (want_tiles + tiles_n - 1) / tiles_n;
+    int64_t row_tiles = (want_tiles + tiles_n - 1) / tiles_n;
+    if (row_tiles < 1) row_tiles = 1;
     return row_tiles * tile_rows;
 }
 
@@ -349,15 +372,17 @@ static double adaptive_trial(AdaptiveCtx *x, int shape)
     x->trials += 1;
     float ms = 0.0f;
     (void)hipEventElapsedTime(&ms, x->e0, x->e1);
-    return (double)ms / (double)rows;   // the paper's score: execution time per unit of work
+    const double sc = (double)ms / (double)rows;   // the paper's score: execution time per unit of work
+    if (sc < x->best_score) { x->best_score = sc; x->best_shape = shape; }
+    return sc;
 }
 
 static double adaptive_valu_score(int i0, int i1, void *ctx)
 {
     AdaptiveCtx *x = (AdaptiveCtx *)ctx;
-    const double sc = adaptive_trial(x, i0 * VALU_TILES + i1);
-    if (sc < x->best_valu_score) x->best_valu_score = sc;
-    return sc;
+    const int shape = i0 * VALU_TILES + i1;
+    if (x->score_of[shape] < 0.0) x->score_of[shape] = adaptive_trial(x, shape);   // a shape is tried once
+    return x->score_of[shape];
 }
 
 }  // namespace amulet
@@ -712,12 +737,13 @@ int amulet_greedy_search(int n0, int n1, amulet_score_fn score, void *ctx, int *
     return calls;
 }
 
-int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
-                               const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
-                               void *stream, int *chosen_shape, int *n_trials)
+int amulet_mmlike_f32_adaptive_general(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
+                                       int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                                       const float *thres, int64_t ldt, const float *dis, float *R, int64_t ldr,
+                                       void *stream, int *chosen_shape, int *n_trials)
 {
-    const MmlikeCall c = {task, THRES_COL, 0, 0, M, N, K, A, lda, B, ldb, params, 0,
-                          params ? params + N : nullptr, R, ldr};
+    const MmlikeCall c = {task, thres_form, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb,
+                          thres, ldt, dis, R, ldr};
     const int rc = check_mmlike(c);
     if (rc < 0) return rc;
     if (chosen_shape) *chosen_shape = lookup_shape(task, M, N, K);
@@ -729,23 +755,30 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const 
     x.call = c;
     x.stream = (hipStream_t)stream;
     x.budget_rows = M / 2;   // at least half of the task runs with the winner
+    x.best_score = 1e300;
+    x.best_shape = -1;
+    for (double &sc : x.score_of) sc = -1.0;
     int best = lookup_shape(task, M, N, K);
-    // too small to spare even two trial slabs: run it whole with the default shape
-    const bool can_test = 2 * trial_rows(c, VALU_TILES + 0) <= x.budget_rows;
+    // too small to spare the default shape's slab and two more: run it whole with that shape
+    const bool can_test = trial_rows(c, best) + 2 * trial_rows(c, VALU_TILES + 0) <= x.budget_rows;
     if (can_test && hipEventCreate(&x.e0) == hipSuccess && hipEventCreate(&x.e1) == hipSuccess) {
         if (task == TASK_IDENTITY) {
             // the dense contraction runs on the matrix cores: its two tiles are the candidates
             // (a vector-ALU slab runs at a sixth of their rate: one such trial on the caller's
             // rows cost 20 % of an 8192^3 call, and none ever won)
-            const double t_small = adaptive_trial(&x, IDENTITY_MFMA_SHAPE);
-            const double t_big = adaptive_trial(&x, IDENTITY_MFMA_BIG_SHAPE);
-            best = t_big < t_small ? IDENTITY_MFMA_BIG_SHAPE : IDENTITY_MFMA_SHAPE;
+            (void)adaptive_trial(&x, IDENTITY_MFMA_SHAPE);
+            (void)adaptive_trial(&x, IDENTITY_MFMA_BIG_SHAPE);
         } else {
+            // The shape a plain call would use is tried first, so that the walk can only replace
+            // it by something that measured faster on this very task.  Then the paper's order:
+            // the k axis (Sec. 4.5), then the tile axis upward with an early stop (Sec. 4.6); a
+            // candidate for which no untested rows are left scores as infinitely slow, which
+            // ends the walk.  The winner is the fastest slab of all.
+            if (best >= 0 && best < VALU_SHAPE_COUNT) x.score_of[best] = adaptive_trial(&x, best);
             int b0 = 0, b1 = 0;
-            x.best_valu_score = 1e300;
-            amulet_greedy_search(VALU_DEPTHS, VALU_TILES, adaptive_valu_score, &x, &b0, &b1);
-            best = b0 * VALU_TILES + b1;
+            amulet_greedy_search(VALU_KAXIS, VALU_TILES, adaptive_valu_score, &x, &b0, &b1);
         }
+        if (x.best_shape >= 0) best = x.best_shape;
     }
     if (x.e0) (void)hipEventDestroy(x.e0);
     if (x.e1) (void)hipEventDestroy(x.e1);
@@ -759,6 +792,14 @@ int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const 
     if (chosen_shape) *chosen_shape = best;
     if (n_trials) *n_trials = x.trials;
     return out;
+}
+
+int amulet_mmlike_f32_adaptive(int task, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                               const float *B, int64_t ldb, const float *params, float *R, int64_t ldr,
+                               void *stream, int *chosen_shape, int *n_trials)
+{
+    return amulet_mmlike_f32_adaptive_general(task, THRES_COL, 0, 0, M, N, K, A, lda, B, ldb, params, 0,
+                                              params ? params + N : nullptr, R, ldr, stream, chosen_shape, n_trials);
 }
 
 int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
@@ -828,7 +869,9 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
             }
         } else {
             int b0 = 0, b1 = 0;
-            amulet_greedy_search(VALU_DEPTHS, VALU_TILES, valu_trial_score, &c, &b0, &b1);
+            // identity on the vector ALU has the two staging depths only; the predicate tasks walk
+            // the whole k axis (staging depth, then K in 1, 2, 4, 8 parts per tile)
+            amulet_greedy_search(task == TASK_IDENTITY ? VALU_DEPTHS : VALU_KAXIS, VALU_TILES, valu_trial_score, &c, &b0, &b1);
             chosen = b0 * VALU_TILES + b1;
             if (task == TASK_IDENTITY) {
                 double best = time_shape(&c, chosen);
@@ -879,8 +922,7 @@ const char *amulet_shape_name(int task, int shape)
 {
     if (shape < 0 || shape >= n_shapes(task)) return "invalid";
     if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
-    if (shape == IDENTITY_MFMA_SHAPE) return "mfma_f32_128x128_k16";
-    if (shape == IDENTITY_MFMA_BIG_SHAPE) return "mfma_f32_256x256_w16_k16";
+    if (is_mfma_shape(task, shape)) return shape == IDENTITY_MFMA_SHAPE ? "mfma_f32_128x128_k16" : "mfma_f32_256x256_w16_k16";
     return kValuShapes[shape].name;
 }
 

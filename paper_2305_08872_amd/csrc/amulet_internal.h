@@ -216,18 +216,27 @@ struct MmlikeArgs {
     // order, each present tail_splits times, once per k range (tail_splits <= 1: no such blocks).
     int tail_base, tail_blocks, tail_splits;
     int block_base;   // added to blockIdx.x (launch_row_of_blocks)
+    int force_splits; // > 1: every tile's K in this many parts (a k-axis point of the shape grid); 0: the launcher's rule
 };
 
-// Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy
-// parameter search walks (paper Sec. 4.4): axis 0 is the depth BK of the B tile
-// staged per barrier (the k_c analogue), axis 1 the workgroup's R tile from
-// narrow to wide (the n_c analogue).  shape id = depth index * VALU_TILES + tile.
+// Tile shapes of the VALU kernels, laid out as the two-axis grid the greedy parameter search
+// walks (paper Sec. 4.4-4.6).  Axis 0 is the k axis, the analogue of the paper's k_c (how much
+// of K one unit of work covers): the depth BK of the B tile staged per barrier, and then how
+// much of K one workgroup sums, K itself or K / 2, K / 4, K / 8 (the paper's sequence K,
+// ceil(K / 2), ceil(K / 4), ...; the parts reach R through atomic adds).  Axis 1 is the
+// workgroup's R tile from narrow to wide (the n_c analogue).
+// shape id = k-axis index * VALU_TILES + tile.
+//   k axis 0: BK 8    1: BK 16 (K split only where the launcher's own rule asks for it)
+//          2, 3, 4: BK 16, every tile's K in 2, 4, 8 parts
 //   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 4x4, 8 waves -> 32 x 256
 //   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 4x8, 8 waves -> 32 x 512
-enum { VALU_DEPTHS = 2, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES };
+// The identity task keeps the first two k-axis points (ids 0-7) and adds its two matrix-core
+// tiles (ids 8, 9); the predicate tasks have all VALU_SHAPE_COUNT ids.
+enum { VALU_DEPTHS = 2, VALU_KAXIS = 5, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_KAXIS * VALU_TILES };
 
 struct ValuShapeDesc {
     int TM, NG, NW, BK;
+    int splits;   // 0: the launcher's rule; else every tile's K in this many parts
     const char *name;
 };
 extern const ValuShapeDesc kValuShapes[VALU_SHAPE_COUNT];
@@ -256,9 +265,9 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent = false);
 
-// Identity task on the fp32 matrix cores; its two shape ids follow the VALU shapes:
+// Identity task on the fp32 matrix cores; its two shape ids follow its eight VALU shapes:
 // a 128 x 128 tile (4 waves) and a 256 x 256 tile (16 waves).
-enum { IDENTITY_MFMA_SHAPE = VALU_SHAPE_COUNT, IDENTITY_MFMA_BIG_SHAPE = VALU_SHAPE_COUNT + 1 };
+enum { IDENTITY_MFMA_SHAPE = VALU_DEPTHS * VALU_TILES, IDENTITY_MFMA_BIG_SHAPE = VALU_DEPTHS * VALU_TILES + 1 };
 hipError_t launch_identity_mfma(const MmlikeArgs &a, int big, hipStream_t s);
 
 template <int TASK, int TF>

@@ -610,7 +610,17 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * NW;
-    if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
+    if (a.force_splits > 1) {
+        // a k-axis point of the shape grid: every tile's K in (up to) force_splits parts of whole
+        // partial-sum periods; nothing to split in the deterministic mode or when K is short
+        if (k_split_allowed() && a.K >= 128) {
+            int64_t want = a.force_splits;
+            if (want > a.K / 64) want = a.K / 64;
+            const int64_t chunk = ((a.K + want - 1) / want + 63) / 64 * 64;
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+        }
+    } else if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
         int64_t want = 4096 / waves;   // as many as still fit the chip at once (4 waves per SIMD)
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;
@@ -660,7 +670,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     // a last round of workgroups that would leave most of the chip idle: its tiles are launched
     // once per k range instead (choose_tail_split in amulet_internal.h)
     TailSplit t;
-    if (splits == 1 && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / NW), a.K, 64, t)) {
+    if (splits == 1 && a.force_splits <= 1 && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / NW), a.K, 64, t)) {
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;
@@ -670,20 +680,27 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     return launch(wgs, splits);
 }
 
-// Shape id = depth index * VALU_TILES + tile index (see amulet_internal.h).
+// Shape id = k-axis index * VALU_TILES + tile index (see amulet_internal.h).
 template <int TASK, int TF>
-hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s)
+hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &args, hipStream_t s)
 {
-    switch (shape) {
-    case 0: return launch_one<TASK, TF, 4, 1, 4, 8, 4>(a, s);
-    case 1: return launch_one<TASK, TF, 4, 1, 8, 8, 4>(a, s);
-    case 2: return launch_one<TASK, TF, 8, 1, 8, 8, 4>(a, s);
-    case 3: return launch_one<TASK, TF, 4, 2, 8, 8, 4>(a, s);
-    case 4: return launch_one<TASK, TF, 4, 1, 4, 16, 4>(a, s);
-    case 5: return launch_one<TASK, TF, 4, 1, 8, 16, 4>(a, s);
-    case 6: return launch_one<TASK, TF, 8, 1, 8, 16, 4>(a, s);
-    case 7: return launch_one<TASK, TF, 4, 2, 8, 16, 4>(a, s);
-    default: return hipErrorInvalidValue;
+    if (shape < 0 || shape >= VALU_SHAPE_COUNT) return hipErrorInvalidValue;
+    MmlikeArgs a = args;
+    a.force_splits = kValuShapes[shape].splits;
+    const int tile = shape % VALU_TILES;
+    if (kValuShapes[shape].BK == 8) {
+        switch (tile) {
+        case 0: return launch_one<TASK, TF, 4, 1, 4, 8, 4>(a, s);
+        case 1: return launch_one<TASK, TF, 4, 1, 8, 8, 4>(a, s);
+        case 2: return launch_one<TASK, TF, 8, 1, 8, 8, 4>(a, s);
+        default: return launch_one<TASK, TF, 4, 2, 8, 8, 4>(a, s);
+        }
+    }
+    switch (tile) {
+    case 0: return launch_one<TASK, TF, 4, 1, 4, 16, 4>(a, s);
+    case 1: return launch_one<TASK, TF, 4, 1, 8, 16, 4>(a, s);
+    case 2: return launch_one<TASK, TF, 8, 1, 8, 16, 4>(a, s);
+    default: return launch_one<TASK, TF, 4, 2, 8, 16, 4>(a, s);
     }
 }
 

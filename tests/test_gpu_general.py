@@ -187,6 +187,37 @@ def test_adaptive_execution_trials_contribute_to_the_result(am):
     am.amulet_clear_selections()
 
 
+@pytest.mark.parametrize("task,form,tA,tB", [(1, 1, False, False), (2, 3, True, False), (3, 2, False, True), (1, 0, True, True)])
+def test_adaptive_execution_of_the_general_form(am, task, form, tA, tB):
+    """In-flight adaptive execution with the other threshold operand forms and transposed layouts:
+    trials on row slabs of the caller's R (rows of a transposed A are columns of its storage, the
+    rows of thres[i] / thres[i][j] move with the slab), K long enough for the k axis's split
+    points to act; the whole R against the oracle."""
+    M, N, K = 8192, 8192, 300
+    g = np.random.Generator(np.random.PCG64(700 + task))
+    A = g.integers(0, 10, (M, K)).astype(np.float32)
+    B = g.uniform(1, 100, (K, N)).astype(np.float32)
+    th = {0: g.uniform(100, 500, N), 1: g.uniform(100, 500, M), 2: np.array([250.0]),
+          3: g.uniform(100, 500, (M, N))}[form].astype(np.float32)
+    dis = g.uniform(0.05, 0.3, N).astype(np.float32)
+    R_in = np.rint(g.standard_normal((M, N)) * 3).astype(np.float32)
+    dR = dev(R_in)
+    am.amulet_clear_selections()
+    print("adaptive general", task, form, tA, tB, flush=True)
+    chosen, trials = am.amulet_mmlike_f32_adaptive_general(
+        task, dev(A.T) if tA else dev(A), dev(B.T) if tB else dev(B), dev(th), dev(dis) if task == 1 else None, dR,
+        thres_form=form, trans_a=tA, trans_b=tB)
+    torch.cuda.synchronize()
+    assert 0 <= chosen < am.amulet_shape_count(task) and trials >= 6   # the default shape, then the whole k axis
+    assert am.amulet_selected_shape(task, M, N, K) == chosen
+    R_ref, ab, _ = oracle.mmlike_f32_general(task, A, B, th, dis if task == 1 else None, R_in, thres_form=form)
+    if task == 3:
+        assert np.array_equal(dR.cpu().numpy(), R_ref)
+    else:
+        assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="adaptive general form")
+    am.amulet_clear_selections()
+
+
 @pytest.mark.parametrize("task", [0, 1, 2, 3])
 def test_few_tiles_long_k_split_over_workgroups(am, task):
     """Tiny M x N with a long K: the launcher splits K over several workgroups per tile, which add

@@ -54,11 +54,11 @@ def run_gpu(am, task, A, B, params, R_in, shape=None):
 
 
 # several tiles in each direction plus ragged tails in M, N and K for every shape
-ODD_SHAPES = [(70, 300, 37), (33, 513, 100), (1, 1, 1), (129, 1030, 77), (5, 257, 16), (64, 512, 8)]
+ODD_SHAPES = [(70, 300, 37), (33, 513, 100), (1, 1, 1), (129, 1030, 77), (5, 257, 16), (64, 512, 8), (40, 520, 700)]
 
 
 @pytest.mark.parametrize("task", TASKS)
-@pytest.mark.parametrize("shape", range(10))
+@pytest.mark.parametrize("shape", range(20))
 def test_every_shape_on_ragged_sizes(am, task, shape):
     if shape >= am.amulet_shape_count(task):
         pytest.skip("task %d has no shape %d" % (task, shape))
@@ -67,7 +67,7 @@ def test_every_shape_on_ragged_sizes(am, task, shape):
         print("case", task, shape, M, N, K, flush=True)
         R_ref, ab, _ = oracle.mmlike_f32(task, A, B, params, R_in)
         R = run_gpu(am, task, A, B, params, R_in, shape)
-        if task == 3:
+        if task == 3 and K < 128:   # (a count added to a fractional R_in in several parts is rounded once per part)
             assert np.array_equal(R, R_ref), (task, shape, M, N, K)
         else:
             assert_parity_f32(R, R_ref, ab, R_in, what="task %d shape %d %dx%dx%d" % (task, shape, M, N, K))
