@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "amulet_internal.h"
 
 // the LDS-DMA asm below sets M0 itself and says so in its clobber list
@@ -57,13 +59,25 @@ struct DmaTile {
 // the operand ring (and, after the K loop, the image the result tile is transposed through)
 extern __shared__ __attribute__((aligned(16))) int8_t dma_smem[];
 
+// What a persistent workgroup knows of the item it will run after the current one.
+struct NextItem {
+    int row0, col0, kb, K;   // K == 0: there is none
+};
+
 // One work item: the product of rows [row0, row0 + 64 WR) of A with columns [col0, col0 + 256) of B
 // over k in [kb, kb + K), K a multiple of 64, added to that tile of R.  `ksplit`: several
 // workgroups own the tile at once (split K) and add their parts with integer atomics.  All waves
-// of the workgroup call it together; the LDS ring may be reused as soon as it returns.
+// of the workgroup call it together.
+// A persistent workgroup chains items: `ring0` is the ring slot that holds this item's stage 0,
+// `pre` the number of its stages the item before already requested (0 for a first item), and
+// when `next` names an item, this one requests the first stages of it (PREFETCH of them) into
+// the half of the ring its own write-back does not use, right after its K loop, so that they
+// arrive during the write-back instead of after it.  Returns how many stages it requested
+// for `next`.
 template <int WR, int NSTAGE>
-__device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, const int col0, const int kb,
-                                         const int K, const bool ksplit)
+__device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, const int col0, const int kb,
+                                        const int K, const bool ksplit, const int ring0 = 0, const int pre = 0,
+                                        const NextItem next = NextItem{0, 0, 0, 0})
 {
     typedef DmaTile<WR, NSTAGE> T;
     static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
@@ -113,13 +127,15 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
                      : "v"(voff), "s"(base), "s"(lds_addr)
                      : "memory", "m0");
     };
-    auto issue = [&](int stage, int buf) {
+    auto issue_from = [&](const int8_t *abase, const int8_t *bbase, int stage, int buf) {
         const uint32_t base = lds_base + (uint32_t)(buf * DM_STAGE_BYTES);
-        dma16(a_base + (int64_t)stage * DM_BK, a_voff, base + (uint32_t)wave * 1024u);
+        dma16(abase + (int64_t)stage * DM_BK, a_voff, base + (uint32_t)wave * 1024u);
 #pragma unroll
         for (int q = 0; q < B_LOADS; ++q)
-            dma16(b_base + (int64_t)stage * b_stage, b_voff[q], base + (uint32_t)(DM_A_BYTES + (wave + NW * q) * 1024));
+            dma16(bbase + (int64_t)stage * b_stage, b_voff[q], base + (uint32_t)(DM_A_BYTES + (wave + NW * q) * 1024));
     };
+    auto slot_of = [&](int stage) { return (ring0 + stage) % NSTAGE; };   // ring slot of a stage of this item
+    auto issue = [&](int stage) { issue_from(a_base, b_base, stage, slot_of(stage)); };
 
     // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
     int a_off[2];   // per k-step of 32; the second row block is + 32 rows = + 2048 bytes
@@ -162,18 +178,28 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
             for (int ni = 0; ni < 2; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
     };
-    // wait until at most `stages` stages of this wave's loads are still in flight
-    auto wait_pending = [&](int stages) {
-        if (stages <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (stages == 1) {
-            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        } else if (stages == 2) {
-            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        } else {
-            if constexpr (T::LOADS == 3) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    // Wait until the loads of stage `t` of this item have landed.  Vector memory operations
+    // retire in the order they were issued, so this is a wait until at most as many are
+    // outstanding as were issued after that stage's: T::LOADS per later stage requested so far
+    // (`upto`: the last one), and, for a stage the item before requested, the EXTRA operations
+    // of that item's write-back, all of which came after the request.
+    constexpr int PREFETCH = 2;                     // stages requested for the next item
+    // (the write-back reads R in groups of WB_GROUP rows per wave, WB_DEPTH groups ahead; 8 waves
+    // have registers for one group only)
+    constexpr int WB_GROUP = 4, WB_DEPTH = WR == 4 ? 2 : 1;
+    constexpr int EXTRA = 2 * WR * (64 / NW) - WB_DEPTH * WB_GROUP;   // per wave: a tile's loads and stores of R rows, less the loads that precede the request
+    static_assert(T::LOADS * (NSTAGE - 2) + EXTRA <= 63, "the wait count is a 6-bit field");
+    auto wait_stage = [&](int t, int upto) {
+        const int n = T::LOADS * (upto - t) + (t < pre ? EXTRA : 0);
+        // (the count is an immediate operand: one instruction per value that can occur)
+        switch (n) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+#define AMULET_WAIT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+        AMULET_WAIT_CASE(2) AMULET_WAIT_CASE(3) AMULET_WAIT_CASE(4) AMULET_WAIT_CASE(6) AMULET_WAIT_CASE(9)
+        AMULET_WAIT_CASE(24) AMULET_WAIT_CASE(26) AMULET_WAIT_CASE(28) AMULET_WAIT_CASE(30)
+        AMULET_WAIT_CASE(56) AMULET_WAIT_CASE(59) AMULET_WAIT_CASE(62)
+#undef AMULET_WAIT_CASE
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never too little: waits for everything
         }
     };
 
@@ -192,34 +218,53 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0;
-    int issued = 0;
+    int requested = pre;                          // stages of this item requested so far
 #pragma unroll
     for (int d = 0; d < NSTAGE - 1; ++d)
-        if (d < n_stages) { issue(d, d); ++issued; }
-    wait_pending(issued - 1);
+        if (d >= pre && d < n_stages) { issue(d); requested = d + 1; }
+    wait_stage(0, requested - 1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
     v4i fa0[2], fb0[2], fa1[2], fb1[2];
-    read_frags(0, 0, fa0, fb0);
-    int buf = 0;                                  // buffer of stage s
-    for (int s = 0; s + 1 < n_stages; ++s) {
+    int buf = ring0;                              // ring slot of stage s
+    int ibuf = ring0 == 0 ? NSTAGE - 1 : ring0 - 1;   // ring slot the next request goes to: the one stage s-1 has left
+    read_frags(buf, 0, fa0, fb0);
+    // One iteration: k-step 0 of stage s, the wait for stage s+1 and the barrier, the request for
+    // stage s+NSTAGE-1, k-step 1 of stage s.  STEADY: the common iteration (stage s+1 is this
+    // item's own request, a later stage is still to be requested: one constant wait count, no
+    // case distinction), kept apart from the few first and last ones so that the loop that runs
+    // nearly all of K stays short.
+    auto iteration = [&](int s, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         read_frags(buf, 1, fa1, fb1);
         mma(fa0, fb0);
         __builtin_amdgcn_sched_barrier(0);
-        // in flight now: stages s+1 .. min(s+NSTAGE-2, n_stages-1); stage s+1 must have landed
-        const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
-        wait_pending(last - (s + 1));
+        // requested so far: stages up to min(s+NSTAGE-2, n_stages-1); stage s+1 must have landed
+        if constexpr (STEADY) {
+            if constexpr (T::LOADS * (NSTAGE - 3) == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else if constexpr (T::LOADS * (NSTAGE - 3) == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else wait_stage(s + 1, s + NSTAGE - 2);
+        } else {
+            const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
+            wait_stage(s + 1, last);
+        }
         // A bare s_barrier: the full fence of __syncthreads() would drain the loads in flight.
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (s + NSTAGE - 1 < n_stages) issue(s + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        if (STEADY || s + NSTAGE - 1 < n_stages) issue_from(a_base, b_base, s + NSTAGE - 1, ibuf);   // into the slot stage s-1 has left
         read_frags(nbuf, 0, fa0, fb0);
         __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1);
+        ibuf = buf;
         buf = nbuf;
-    }
+    };
+    const int steady_end = n_stages - (NSTAGE - 1);   // first s that requests nothing more
+    int s = 0;
+    for (; s < pre && s + 1 < n_stages; ++s) iteration(s, std::false_type());
+    for (; s < steady_end; ++s) iteration(s, std::true_type());
+    for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
     // last stage: nothing left to wait for or to fetch
     read_frags(buf, 1, fa1, fb1);
     mma(fa0, fb0);
@@ -231,10 +276,16 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
     // in WR parts of 64 rows x 256 columns: the waves owning the part scatter their accumulators
     // into a row-major image, then all waves add it to R with 16-byte accesses, one full 1 KB
     // tile row per wave instruction.
-    // Image row pitch 264 words: the two half-waves of a scatter store write rows 4 apart,
-    // and 4 * 264 words is 32 banks off, so the 64 lanes hit 64 distinct banks.
-    constexpr int IMG_PITCH = DM_BN + 8;
+    // The image has no padding (64 rows x 1 KB: the first 64 KB of the ring, which leaves the rest
+    // of the ring to the next item's first stages): the two half-waves of a scatter store write
+    // rows 4 apart, which fall on the same banks, so every other group of four rows is kept with
+    // its two 128-byte halves of each 256-byte bank row exchanged (column ^ 32): the 64 lanes of a
+    // store hit 64 distinct banks, and a row is still read back as whole 16-byte units.
+    constexpr int IMG_PITCH = DM_BN;
     static_assert(64 * IMG_PITCH * 4 <= NSTAGE * DM_STAGE_BYTES, "the image must fit in the ring");
+    static_assert(64 * IMG_PITCH * 4 + PREFETCH * DM_STAGE_BYTES <= NSTAGE * DM_STAGE_BYTES || WR == 2,
+                  "the image and the next item's first stages share the ring");
+    auto img_swz = [](int r) { return ((r >> 2) & 1) << 5; };
     constexpr int ROWS_PER_WAVE = 64 / NW;
     int32_t *const img = (int32_t *)dma_smem;
     // The write-back is a chain of round trips to HBM (read the rows of R, add, store), and it is
@@ -243,7 +294,7 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
     // instruction has issued, which is room for DEPTH groups of four rows per wave.  Those are
     // requested before the first part's scatter and barriers, and each group's registers are
     // refilled with the rows DEPTH groups later as soon as its sums are formed.
-    constexpr int GROUP = 4, GROUPS = ROWS_PER_WAVE / GROUP, NGROUPS = WR * GROUPS, DEPTH = 2;
+    constexpr int GROUP = WB_GROUP, GROUPS = ROWS_PER_WAVE / GROUP, NGROUPS = WR * GROUPS, DEPTH = WB_DEPTH;
     static_assert(ROWS_PER_WAVE % GROUP == 0, "a wave's rows of a part come in groups of four");
     v4i rbuf[DEPTH][GROUP];
     // group q of the tile: part q / GROUPS, rows (q % GROUPS) * GROUP .. + GROUP - 1 of this wave's share.
@@ -260,10 +311,20 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
 #pragma unroll
             for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_row(q, j));
     }
+    int next_requested = 0;
 #pragma unroll
     for (int part = 0; part < WR; ++part) {
         __builtin_amdgcn_s_barrier();          // the ring (or the previous part's image) is no longer read
         asm volatile("" ::: "memory");
+        if (part == 0 && next.K > 0) {
+            // the next item's first stages, into the ring slots behind the image; that item
+            // then starts at slot NSTAGE - PREFETCH
+            const int8_t *const an = args.A + (int64_t)next.row0 * args.lda + next.kb;
+            const int8_t *const bn = args.B + (int64_t)next.kb * args.ldb + next.col0;
+#pragma unroll
+            for (int d = 0; d < PREFETCH; ++d)
+                if (d * DM_BK < next.K) { issue_from(an, bn, d, NSTAGE - PREFETCH + d); next_requested = d + 1; }
+        }
         if (wr == part) {
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
@@ -272,7 +333,7 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int r = mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        img[r * IMG_PITCH + (wc * 2 + ni) * 32 + li] = acc[mi][ni][v];
+                        img[r * IMG_PITCH + (((wc * 2 + ni) * 32 + li) ^ img_swz(r))] = acc[mi][ni][v];
                     }
         }
         // The image is complete for everyone once each wave's LDS writes are done: wait for those
@@ -288,7 +349,7 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
                 int32_t *drow = args.R + (int64_t)(row0 + part * 64 + r) * args.ldr + col0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    atomicAdd(drow + e * 64 + lane, img[r * IMG_PITCH + e * 64 + lane]);
+                    atomicAdd(drow + e * 64 + lane, img[r * IMG_PITCH + ((e * 64 + lane) ^ img_swz(r))]);
             }
             continue;
         }
@@ -297,7 +358,8 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
             const int q = part * GROUPS + grp;
 #pragma unroll
             for (int j = 0; j < GROUP; ++j) {
-                const v4i part4 = *(const v4i *)(img + (wave * ROWS_PER_WAVE + grp * GROUP + j) * IMG_PITCH + lane * 4);
+                const int ir = wave * ROWS_PER_WAVE + grp * GROUP + j;
+                const v4i part4 = *(const v4i *)(img + ir * IMG_PITCH + ((lane * 4) ^ img_swz(ir)));
                 v4i cur = rbuf[q % DEPTH][j];
                 cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
                 cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
@@ -308,6 +370,7 @@ __device__ __forceinline__ void dma_item(const CountArgs &args, const int row0, 
             }
         }
     }
+    return next_requested;
 }
 
 template <int WR, int NSTAGE>
@@ -324,7 +387,7 @@ count_i8_dma_kernel(const CountArgs args)
     const int tiles_m = args.M / T::BM, tiles_n = args.N / DM_BN;
     int tm, tn;
     if (!xcd_tile((int)blockIdx.x + args.block_base, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
-    dma_item<WR, NSTAGE>(args, tm * T::BM, tn * DM_BN, kb, K, ksplit);
+    (void)dma_item<WR, NSTAGE>(args, tm * T::BM, tn * DM_BN, kb, K, ksplit);
 }
 
 // Persistent form: one launch of as many workgroups as the chip holds at once (a compute unit
@@ -367,13 +430,31 @@ count_i8_dma_persistent_kernel(const CountArgs args)
     const int n_mine = slot < places ? (places - slot + n_slots - 1) / n_slots : 0;   // places slot, slot + n_slots, ...
     const bool split_first = kq > 0 && n_mine > 0 && tile_at(slot, row0, col0);
     const int n_steps = n_mine + (split_first ? 1 : 0);
-    for (int step = 0; step < n_steps; ++step) {
-        int place = slot + step * n_slots, kb = 0, kl = args.K;
-        if (split_first && step == 0) kl = kq;
-        if (split_first && step == n_mine) { place = slot; kb = kq; kl = args.K - kq; }
-        if (!tile_at(place, row0, col0)) continue;   // padding (uniform over the workgroup)
-        dma_item<WR, NSTAGE>(args, row0, col0, kb, kl, false);
-        __builtin_amdgcn_s_barrier();            // every wave is done with the ring and the image
+    // item `step` of this workgroup (false: that place is padding)
+    auto item_at = [&](int step, NextItem &it) {
+        int place = slot + step * n_slots;
+        it.kb = 0;
+        it.K = args.K;
+        if (split_first && step == 0) it.K = kq;
+        if (split_first && step == n_mine) { place = slot; it.kb = kq; it.K = args.K - kq; }
+        return tile_at(place, it.row0, it.col0);
+    };
+    auto next_real = [&](int step, NextItem &it) {   // first real item from `step` on, or n_steps
+        while (step < n_steps && !item_at(step, it)) ++step;
+        if (step >= n_steps) it.K = 0;
+        return step;
+    };
+    NextItem cur, nxt;
+    int step = next_real(0, cur);
+    int ring0 = 0, pre = 0;
+    while (step < n_steps) {
+        const int nstep = next_real(step + 1, nxt);
+        const int req = dma_item<WR, NSTAGE>(args, cur.row0, cur.col0, cur.kb, cur.K, false, ring0, pre, nxt);
+        __builtin_amdgcn_s_barrier();            // every wave is done with the image: the ring is the next item's
+        ring0 = req > 0 ? NSTAGE - 2 : 0;
+        pre = req;
+        cur = nxt;
+        step = nstep;
     }
 }
 
