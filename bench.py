@@ -42,6 +42,22 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dR = torch.zeros(M, N, dtype=torch.int32, device="cuda")
     T = am.AMULET_TASK_COUNT_I8
+    if args.traffic_probe:
+        # for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes: the counter
+        # calibration), then --steps launches of the kernel
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        if not args.no_tune:
+            am.amulet_tune(T, M, N, K)
+        for _ in range(args.steps):
+            am.amulet_count_i8(dA, dB, dR)
+        torch.cuda.synchronize()
+        print("traffic probe done: 1 copy of %d bytes, %d launches of %s" %
+              (src.numel() * 4, args.steps, am.amulet_shape_name(T, am.amulet_selected_shape(T, M, N, K))))
+        return {}
     t0 = time.perf_counter()
     shape = am.amulet_selected_shape(T, M, N, K) if args.no_tune else am.amulet_tune(T, M, N, K)
     tune_s = time.perf_counter() - t0
