@@ -112,10 +112,11 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
 // workgroup's 32 rows all fall into the same L2 sets they are evicted between the pieces.
 // PIPE (discount task, 4 x 4 micro-tile): a chunk runs as one software pipeline instead of k by k
 // (see the chunk loop); the launcher says when.
-template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA, bool ALDS, bool PIPE = false>
+template <int TASK, int TF, int TRANS, int TM, int NG, int NW, int BK, int KA, bool ALDS, bool PIPE = false, bool BPRE = false>
 __global__ void __launch_bounds__(64 * NW)
 mmlike_valu_kernel(const MmlikeArgs args)
 {
+    static_assert(!BPRE || (!ALDS && TM == 4 && NG == 1), "B values a chunk ahead: scalar-path A, 4 x 4 micro-tile");
     static_assert(!PIPE || (TASK == TASK_DISCOUNT && TM == 4 && NG == 1), "chunk pipeline: discount task, 4 x 4 micro-tile");
     static_assert(!ALDS || (TRANS == 0 && TM == 4 && NG == 1), "A through LDS: row-major operands, 4 x 4 micro-tile");
     typedef typename AccT<TASK>::type acc_t;
@@ -422,6 +423,58 @@ mmlike_valu_kernel(const MmlikeArgs args)
     if (!ALDS && full_tiles > 0) fetch_a(0);
     __syncthreads();
 
+    // The arithmetic of one chunk: KA k of the wave's TM rows against a lane's 4 NG columns.
+    auto compute_chunk = [&](const av_t (&a)[TM], const f4 (&b)[KA][NG]) {
+        if constexpr (PIPE) {
+            // The whole chunk as one software pipeline: compare i, multiply i + 1, FMA
+            // i - 1, select i.  Every compare writes the same lane-mask register (vcc,
+            // the 32-bit encodings) and its select reads it two instructions later, with
+            // one fill and one drain per chunk.  (Through fold4 and a fence per k the
+            // compiler finds the same order inside each k, but fills and drains four
+            // times per chunk.)
+            constexpr int NP = KA * TM * 4;
+            float t4[TM][4];
+#pragma unroll
+            for (int r = 0; r < TM; ++r) thres4(r, 0, t4[r]);
+            float p[NP + 1], sel[NP];
+            p[0] = a_of(a, 0, 0) * b[0][0][0];
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const bool m = p[i] > t4[(i / 4) % TM][i % 4];
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 1 < NP) p[i + 1] = a_of(a, ((i + 1) / 4) % TM, (i + 1) / (4 * TM)) * b[(i + 1) / (4 * TM)][0][(i + 1) % 4];
+                __builtin_amdgcn_sched_barrier(0);
+                if (i > 0) part[((i - 1) / 4) % TM][(i - 1) % 4] = __builtin_fmaf(p[i - 1], sel[i - 1], part[((i - 1) / 4) % TM][(i - 1) % 4]);
+                __builtin_amdgcn_sched_barrier(0);
+                sel[i] = m ? q[i % 4] : 1.0f;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            part[((NP - 1) / 4) % TM][(NP - 1) % 4] = __builtin_fmaf(p[NP - 1], sel[NP - 1], part[((NP - 1) / 4) % TM][(NP - 1) % 4]);
+        } else {
+            // one k at a time through fold4, rows in order
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk) {
+#pragma unroll
+                for (int r = 0; r < TM; ++r) {
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        float t4[4];
+                        thres4(r, g, t4);
+                        fold4<TASK>(a_of(a, r, kk), b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
+                    }
+                    // At most 4 rows of one k between fences: left alone, the scheduler may
+                    // gather the compares of the whole chunk, and their lane masks (a scalar
+                    // register pair each) overflow the scalar register file into spills.
+                    // (The 8-row micro-tiles spill their A values regardless and lose more
+                    // from the fence than they gain: they are left to the scheduler.  The
+                    // count task has no masks but measured 3 % faster with the fence.)
+                    if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
+                        if (r == 3) __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    };
+
     const float *bs_lane = &Bs[0][0][lane * 4];
     // Workgroups 256 apart in launch order tend to share a compute unit (8 XCDs x 32 CUs are
     // filled round-robin).  Their wave priority rotates with the tile step so that they take
@@ -443,7 +496,40 @@ mmlike_valu_kernel(const MmlikeArgs args)
             load_tile((t + 1 < full_tiles) ? BK : tail);
         const float *bs = bs_lane + buf * (BK * BN);
 
-        if (t < full_tiles) {
+        if constexpr (BPRE) {
+          if (t < full_tiles) {
+            // The B values of a chunk are read from LDS while the chunk before it computes: the
+            // wave waits for LDS once per tile (its first chunk) instead of once per chunk.
+            f4 bq[2][KA][NG];
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                for (int g = 0; g < NG; ++g) bq[0][kk][g] = *(const f4 *)(bs + kk * BN + g * 256);
+#pragma unroll
+            for (int c = 0; c < BK / KA; ++c) {
+                const int kc = c * KA;
+                av_t a[TM];
+#pragma unroll
+                for (int r = 0; r < TM; ++r) a[r] = a_next[r];
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this chunk's B and A values have landed
+                __builtin_amdgcn_sched_barrier(0);
+                if (c + 1 < BK / KA) {
+#pragma unroll
+                    for (int kk = 0; kk < KA; ++kk)
+#pragma unroll
+                        for (int g = 0; g < NG; ++g) bq[(c + 1) & 1][kk][g] = *(const f4 *)(bs + (kc + KA + kk) * BN + g * 256);
+                }
+                {
+                    int kn = k0 + kc + KA;
+                    kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
+                    fetch_a(kn);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                compute_chunk(a, bq[c & 1]);
+            }
+          }
+        }
+        if (!BPRE && t < full_tiles) {
 #pragma unroll 1
             for (int kc = 0; kc < BK; kc += KA) {
                 // B values of the whole chunk first, so that one wait covers them ...
@@ -473,61 +559,9 @@ mmlike_valu_kernel(const MmlikeArgs args)
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // one k at a time through fold4, rows in order
-                auto chunk_by_k = [&]() {
-#pragma unroll
-                    for (int kk = 0; kk < KA; ++kk) {
-#pragma unroll
-                        for (int r = 0; r < TM; ++r) {
-#pragma unroll
-                            for (int g = 0; g < NG; ++g) {
-                                float t4[4];
-                                thres4(r, g, t4);
-                                fold4<TASK>(a_of(a, r, kk), b[kk][g], t4, &q[g * 4], &part[r][g * 4]);
-                            }
-                            // At most 4 rows of one k between fences: left alone, the scheduler may
-                            // gather the compares of the whole chunk, and their lane masks (a scalar
-                            // register pair each) overflow the scalar register file into spills.
-                            // (The 8-row micro-tiles spill their A values regardless and lose more
-                            // from the fence than they gain: they are left to the scheduler.  The
-                            // count task has no masks but measured 3 % faster with the fence.)
-                            if constexpr ((TASK == TASK_DISCOUNT || TASK == TASK_COUNT_GT) && TM == 4)
-                                if (r == 3) __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                };
-                if constexpr (PIPE) {
-                    {
-                        // The whole chunk as one software pipeline: compare i, multiply i + 1, FMA
-                        // i - 1, select i.  Every compare writes the same lane-mask register (vcc,
-                        // the 32-bit encodings) and its select reads it two instructions later, with
-                        // one fill and one drain per chunk.  (Through fold4 and a fence per k the
-                        // compiler finds the same order inside each k, but fills and drains four
-                        // times per chunk.)
-                        constexpr int NP = KA * TM * 4;
-                        float t4[TM][4];
-#pragma unroll
-                        for (int r = 0; r < TM; ++r) thres4(r, 0, t4[r]);
-                        float p[NP + 1], sel[NP];
-                        p[0] = a_of(a, 0, 0) * b[0][0][0];
-#pragma unroll
-                        for (int i = 0; i < NP; ++i) {
-                            const bool m = p[i] > t4[(i / 4) % TM][i % 4];
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (i + 1 < NP) p[i + 1] = a_of(a, ((i + 1) / 4) % TM, (i + 1) / (4 * TM)) * b[(i + 1) / (4 * TM)][0][(i + 1) % 4];
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (i > 0) part[((i - 1) / 4) % TM][(i - 1) % 4] = __builtin_fmaf(p[i - 1], sel[i - 1], part[((i - 1) / 4) % TM][(i - 1) % 4]);
-                            __builtin_amdgcn_sched_barrier(0);
-                            sel[i] = m ? q[i % 4] : 1.0f;
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        part[((NP - 1) / 4) % TM][(NP - 1) % 4] = __builtin_fmaf(p[NP - 1], sel[NP - 1], part[((NP - 1) / 4) % TM][(NP - 1) % 4]);
-                    }
-                } else {
-                    chunk_by_k();
-                }
+                compute_chunk(a, b);
             }
-        } else {
+        } else if (t >= full_tiles) {
             // K remainder: k by k, so no padded product is ever evaluated.
             for (int kk = 0; kk < tail; ++kk) {
                 float a1[TM];
@@ -629,10 +663,13 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
         splits = (int)((a.K + chunk - 1) / chunk);
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
-    // Discount task: the chunk-wide pipeline is 2-4 % faster up to a few thousand workgroups
-    // (2048^3 ... 4096^3 +2 %, 4100^3 +4 %, 16384 x 2048 x 8192 +1 %) and no faster at 8192^3,
-    // where its workgroups also share less through the L2s (18.8 against 8.9 GB fetched per
-    // launch, same request count): large launches keep the k-by-k form.
+    // Discount task.  With 16-deep staging and A on the scalar path the kernel runs a chunk as one
+    // compare / multiply / FMA / select pipeline whose B values were read from LDS a chunk ahead,
+    // at every size (8192^3 31.9 -> 34.2 TFLOP/s, 4096^3 32.8 -> 33.9, 16384 x 2048 x 8192 33.1 ->
+    // 34.0: the pipeline alone was no faster at 8192^3, the earlier reads alone gave +1.5 %).
+    // The other discount instantiations (8-deep staging, A through LDS) keep the pipeline without
+    // the earlier reads up to 4096 workgroups, where it measured 2-4 % faster, and the k-by-k form
+    // above that.
     const bool pipe = TASK == TASK_DISCOUNT && TM == 4 && NG == 1 && wgs <= 4096;
     // Rows of a row-major A whose pitch collides in the memory system go through LDS; at other
     // pitches the scalar path is as fast or faster for every task (measured at 2048^3 ... 8192^3,
@@ -644,6 +681,13 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
             switch ((a.transA ? 1 : 0) | (a.transB ? 2 : 0)) {
             case 0:
+                if constexpr (TASK == TASK_DISCOUNT && TM == 4 && NG == 1 && BK == 16) {
+                    // the chunk-wide pipeline fed with B values read a chunk ahead: at every size
+                    if (!a_through_lds) {
+                        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false, true, true>), grid, block, 0, s, b);
+                        break;
+                    }
+                }
                 if constexpr (TASK == TASK_DISCOUNT && TM == 4 && NG == 1) {
                     if (pipe) {
                         if (a_through_lds)
