@@ -334,7 +334,61 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
         if (t + 1 < n_tiles) load_tile((t + 1 < full_tiles) ? D_BK : tail);
         const double *bs = bs_lane + buf * (D_BK * D_BN);
 
-        if (t < full_tiles) {
+        if (ALDS && t < full_tiles) {
+            // The B values (and, through LDS, the A values) of a chunk are read while the chunk
+            // before it computes: a chunk is only 16 products per lane here, so a wait for LDS at
+            // the start of every chunk left the wave idle for a good part of it.  Now the wave
+            // waits for LDS once per tile, for its first chunk.  (A through LDS only: unrolled over
+            // the tile's chunks, the scalar-path variants spill scalar registers.)
+            constexpr int NCH = D_BK / KA;
+            d2 bq[2][KA];
+            d2_a8 aq[2][ALDS ? D_TM : 1];
+            auto read_chunk = [&](int c, int slot) {
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk) bq[slot][kk] = *(const d2 *)(bs + (c * KA + kk) * D_BN);
+                if constexpr (ALDS) {
+                    // the wave's four rows of the chunk: one broadcast 16-byte LDS read each
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r) aq[slot][r] = *(const d2 *)&Asl[buf][wave * D_TM + r][c * KA];
+                }
+            };
+            read_chunk(0, 0);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int kc = c * KA;
+                d2_a8 a[transA ? 1 : D_TM];
+                d4_a8 a_t[transA ? KA : 1];
+                if constexpr (!ALDS) {
+                    if constexpr (!transA) {
+#pragma unroll
+                        for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                    } else {
+#pragma unroll
+                        for (int kk = 0; kk < KA; ++kk) a_t[kk] = a_next_t[kk];
+                    }
+                }
+                // this chunk's values have landed; the reads of the next chunk and the scalar fetch
+                // of its A values go out right after the wait (scalar loads return out of order:
+                // any later LDS wait would drain them too)
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                if (c + 1 < NCH) read_chunk(c + 1, (c + 1) & 1);
+                if constexpr (!ALDS) {
+                    int kn = k0 + kc + KA;
+                    kn = kn + KA <= K ? kn : k0 + kc;
+                    fetch_a(kn);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk) {
+                    double ak[D_TM];
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r)
+                        ak[r] = ALDS ? aq[c & 1][ALDS ? r : 0][kk] : transA ? a_t[transA ? kk : 0][r] : a[transA ? 0 : r][kk];
+                    fold_rows<TASK>(ak, bq[c & 1][kk], th, q, acc);
+                }
+            }
+        } else if (t < full_tiles) {
 #pragma unroll 1
             for (int kc = 0; kc < D_BK; kc += KA) {
                 d2 b[KA];
