@@ -51,7 +51,7 @@ static inline SelKey sel_key(int task, int64_t M, int64_t N, int64_t K)
 
 static int n_shapes(int task)
 {
-    if (task == TASK_IDENTITY) return IDENTITY_MFMA_BIG_SHAPE + 1;  // eight vector-ALU shapes and the two matrix-core tiles
+    if (task == TASK_IDENTITY) return IDENTITY_SHAPE_COUNT;  // eight vector-ALU shapes and the four matrix-core ones
     if (task > TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
     if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
     return 0;
@@ -79,9 +79,10 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         // workgroups walk their tiles out of phase: 8192 x 8192 x 4096 0.242 against 0.249 ms)
         return (tiles256 >= 512 && tiles256 % 256 == 0) ? 8 : 6;
     }
-    // a dense contraction: matrix cores (the 128 x 128 tile measures 1 % ahead of the 256 x 256
-    // one even at 8192^3; the selector tries both)
-    if (task == TASK_IDENTITY) return IDENTITY_MFMA_SHAPE;
+    // a dense contraction: matrix cores, 128 x 128 tile, operands streamed HBM -> LDS where the
+    // problem allows it (whole tiles, aligned row-major operands; the register-staged kernel
+    // otherwise).  The 256 x 256 tile measures 1-3 % behind even at 8192^3; the selector tries all.
+    if (task == TASK_IDENTITY) return IDENTITY_MFMA_DMA3_SHAPE;
     // ... or, with fewer tiles, when K is long (from 8192 on) and the launcher's K split makes up
     // the number (4096 x 512 x 8192: 31.0 against 29.2 TFLOP/s, 4096 x 512 x 32768: 31.3 against
     // 26.6; at K <= 4096 the 4-wave tile stays ahead, 1536^2 x 4096: 28.5 against 27.2)
@@ -157,7 +158,7 @@ static int run_mmlike(const MmlikeCall &c, int shape, void *stream)
     hipError_t e;
     switch (c.task) {
     case TASK_IDENTITY:
-        e = shape >= IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, shape == IDENTITY_MFMA_BIG_SHAPE, s)
+        e = shape >= IDENTITY_MFMA_SHAPE ? launch_identity_mfma(a, shape - IDENTITY_MFMA_SHAPE, s)
                                          : launch_mmlike_valu_task<TASK_IDENTITY, THRES_COL>(shape, a, s);
         break;
     case TASK_DISCOUNT: e = launch_form<TASK_DISCOUNT>(c.thres_form, shape, a, s); break;
@@ -766,7 +767,7 @@ int amulet_mmlike_f32_adaptive_general(int task, int thres_form, int trans_a, in
             // the dense contraction runs on the matrix cores: its two tiles are the candidates
             // (a vector-ALU slab runs at a sixth of their rate: one such trial on the caller's
             // rows cost 20 % of an 8192^3 call, and none ever won)
-            (void)adaptive_trial(&x, IDENTITY_MFMA_SHAPE);
+            (void)adaptive_trial(&x, IDENTITY_MFMA_DMA3_SHAPE);   // (the register-staged kernel where it cannot stream)
             (void)adaptive_trial(&x, IDENTITY_MFMA_BIG_SHAPE);
         } else {
             // The shape a plain call would use is tried first, so that the walk can only replace
@@ -875,7 +876,7 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
             chosen = b0 * VALU_TILES + b1;
             if (task == TASK_IDENTITY) {
                 double best = time_shape(&c, chosen);
-                for (int sidx = IDENTITY_MFMA_SHAPE; sidx <= IDENTITY_MFMA_BIG_SHAPE; ++sidx) {
+                for (int sidx = IDENTITY_MFMA_SHAPE; sidx < IDENTITY_SHAPE_COUNT; ++sidx) {
                     const double t = time_shape(&c, sidx);
                     if (t < best) { best = t; chosen = sidx; }
                 }
@@ -922,7 +923,11 @@ const char *amulet_shape_name(int task, int shape)
 {
     if (shape < 0 || shape >= n_shapes(task)) return "invalid";
     if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
-    if (is_mfma_shape(task, shape)) return shape == IDENTITY_MFMA_SHAPE ? "mfma_f32_128x128_k16" : "mfma_f32_256x256_w16_k16";
+    if (is_mfma_shape(task, shape)) {
+        static const char *const names[4] = {"mfma_f32_128x128_k16", "mfma_f32_256x256_w16_k16", "mfma_f32_128x128_dma3",
+                                             "mfma_f32_128x128_dma4"};
+        return names[shape - IDENTITY_MFMA_SHAPE];
+    }
     return kValuShapes[shape].name;
 }
 

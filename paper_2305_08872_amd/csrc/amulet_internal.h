@@ -199,6 +199,45 @@ inline int choose_full_split(int64_t part_tiles, int64_t units_per_xcd, int64_t 
     return best_s;
 }
 
+// K split of every tile for the streamed identity kernel (identity_mfma_dma.hip), whose
+// workgroups hold `cap` to a compute unit and run at rate[c - 1] of the unit's full rate with c
+// of them resident (measured: 0.92 / 0.985 / 1.0).  An XCD's `part_tiles` tiles, each launched
+// once per k range, s ranges, are W = part_tiles s workgroups of K / s k each on S = units cap
+// slots.  They run in W / S full rounds of cap K / s each, and the remainder either is the whole
+// launch (spread evenly, c = ceil(W / units) per unit: c (K / s) / rate(c)) or follows full
+// rounds, where the dispatcher refills the units that free first, so that a remainder piles up
+// on a few units instead of spreading: after one full round it costs at least two workgroups'
+// time, after two or more (the units have drifted apart by then) a whole round's (1024 tiles
+// unsplit, 768 + 256 workgroups, took as long as two full rounds; in two ranges, 2 x 768 + 512,
+// as long as three).  Each range also pays its
+// set-up and write-back, in units of one k of a tile at full rate: 210 alone, 175 s with atomic
+// adds (12 and 10 us at 57.5 ns per k).  The s <= 8 with at least 128 k per range and the lowest
+// estimate is returned (1: do not split).  Checked against sweeps of s = 1..8 at 144 ... 1024
+// tiles (K = 1536 ... 4096): the chosen s is the best or within 2 % of the best one measured.
+inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int cap, const double *rate)
+{
+    if (!k_split_allowed() || part_tiles <= 0 || units <= 0) return 1;
+    const int max_s = K / 128 < 8 ? (int)(K / 128) : 8;
+    int best_s = 1;
+    double best = 0.0;
+    for (int sp = 1; sp <= max_s; ++sp) {
+        const int64_t W = part_tiles * sp, S = units * cap;
+        const int64_t q = W / S, r = W % S;
+        const double work = (double)K / sp;
+        double cost = (double)q * cap * work;
+        if (r > 0) {
+            const int64_t c = (r + units - 1) / units;
+            double left = (double)c / rate[c - 1];
+            if (q == 1 && left < 2.0) left = 2.0;
+            if (q >= 2) left = (double)cap;
+            cost += left * work;
+        }
+        cost += sp == 1 ? 210.0 : 175.0 * sp;
+        if (sp == 1 || cost < best * 0.99) { best = cost; best_s = sp; }
+    }
+    return best_s;
+}
+
 // Arguments of an fp32 task launch, already validated on the host.
 struct MmlikeArgs {
     const float *A;
@@ -231,7 +270,7 @@ struct MmlikeArgs {
 //   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 4x4, 8 waves -> 32 x 256
 //   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 4x8, 8 waves -> 32 x 512
 // The identity task keeps the first two k-axis points (ids 0-7) and adds its two matrix-core
-// tiles (ids 8, 9); the predicate tasks have all VALU_SHAPE_COUNT ids.
+// shapes (ids 8 to 11); the predicate tasks have all VALU_SHAPE_COUNT ids.
 enum { VALU_DEPTHS = 2, VALU_KAXIS = 5, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_KAXIS * VALU_TILES };
 
 struct ValuShapeDesc {
@@ -265,10 +304,17 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent = false);
 
-// Identity task on the fp32 matrix cores; its two shape ids follow its eight VALU shapes:
-// a 128 x 128 tile (4 waves) and a 256 x 256 tile (16 waves).
-enum { IDENTITY_MFMA_SHAPE = VALU_DEPTHS * VALU_TILES, IDENTITY_MFMA_BIG_SHAPE = VALU_DEPTHS * VALU_TILES + 1 };
-hipError_t launch_identity_mfma(const MmlikeArgs &a, int big, hipStream_t s);
+// Identity task on the fp32 matrix cores; its four shape ids follow its eight VALU shapes: a
+// 128 x 128 tile (4 waves, register staged), a 256 x 256 tile (16 waves), and the 128 x 128 tile
+// with its operands streamed HBM -> LDS through a ring of 3 or 4 stages.
+enum { IDENTITY_MFMA_SHAPE = VALU_DEPTHS * VALU_TILES, IDENTITY_MFMA_BIG_SHAPE = VALU_DEPTHS * VALU_TILES + 1,
+       IDENTITY_MFMA_DMA3_SHAPE = VALU_DEPTHS * VALU_TILES + 2, IDENTITY_MFMA_DMA4_SHAPE = VALU_DEPTHS * VALU_TILES + 3,
+       IDENTITY_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES + 4 };
+// variant = shape id - IDENTITY_MFMA_SHAPE
+hipError_t launch_identity_mfma(const MmlikeArgs &a, int variant, hipStream_t s);
+// the streamed kernel (identity_mfma_dma.hip)
+bool identity_dma_eligible(const MmlikeArgs &a);
+hipError_t enqueue_identity_dma(const MmlikeArgs &a, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s);
 
 template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);

@@ -298,8 +298,10 @@ identity_mfma_kernel(const MmlikeArgs args)
         }
 }
 
+// `dma_stages` > 0: run the streamed kernel (identity_mfma_dma.hip) with a ring of that many
+// stages where the problem allows it (128 x 128 tile, row-major operands).
 template <int G, bool TA, bool TB>
-static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
+static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hipStream_t s)
 {
     typedef MiLayout<G, TA, TB> L;
     const int64_t tiles_m = (a.M + L::BM - 1) / L::BM;
@@ -325,10 +327,25 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
     dim3 launch_grid((unsigned)grid, (unsigned)splits);
-    // Up to four tiles per compute unit: every tile once per k range, as many ranges as the
-    // occupancy model likes best (choose_full_split in amulet_internal.h).
     const int64_t tiles = tiles_m * tiles_n;
-    if (splits == 1 && tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
+    // The streamed kernel where the problem allows it: three workgroups to a compute unit.
+    bool streamed = false;
+    if constexpr (G == 2 && !TA && !TB) streamed = dma_stages > 0 && identity_dma_eligible(b);
+    const int per_unit = streamed ? (dma_stages == 3 ? 3 : 2) : 4;
+    if (streamed && splits == 1 && tiles <= 2 * per_unit * (int64_t)compute_units()) {
+        // at most two rounds of tiles: every tile once per k range (choose_stream_split)
+        static const double rate3[3] = {0.92, 0.985, 1.0}, rate2[2] = {0.93, 1.0};
+        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, per_unit, per_unit == 3 ? rate3 : rate2);
+        if (sp > 1) {
+            const int64_t chunk = ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK;
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+            launch_grid = dim3((unsigned)grid, (unsigned)splits);
+        }
+    }
+    // Register-staged kernel, up to four tiles per compute unit: every tile once per k range, as
+    // many ranges as the occupancy model likes best (choose_full_split in amulet_internal.h).
+    if (!streamed && splits == 1 && tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
         static const double rate[3] = {0.72, 0.81, 1.0};
         const int sp = choose_full_split(grid / 8, compute_units() / 8, a.K, rate, 3);
         if (sp > 1) {
@@ -338,37 +355,50 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, hipStream_t s)
             launch_grid = dim3((unsigned)grid, (unsigned)splits);
         }
     }
-    // More tiles than that: the launch runs in rounds of about one tile per compute unit, and a
-    // last round with few tiles leaves most of the chip idle for a whole K loop: its tiles are
-    // launched once per k range instead (choose_tail_split in amulet_internal.h; rounds of 1, 2,
-    // 3 and 4 workgroups per compute unit were tried in the model: 1 is never worse).
+    // More tiles than that: the launch runs in rounds (one tile per compute unit for the
+    // register-staged kernel: rounds of 1, 2, 3 and 4 workgroups per unit were tried in the
+    // model and 1 is never worse; as many as a unit holds for the streamed one), and a last round
+    // with few tiles leaves most of the chip idle for a whole K loop: its tiles are launched once
+    // per k range instead (choose_tail_split in amulet_internal.h).
     TailSplit t;
-    if (splits == 1 && tiles > 4 * (int64_t)compute_units() &&
-        choose_tail_split(tiles, grid, compute_units(), a.K, MI_BK, t)) {
+    const int64_t round = streamed ? per_unit * (int64_t)compute_units() : (int64_t)compute_units();
+    if (splits == 1 && tiles > (streamed ? 2 * per_unit : 4) * (int64_t)compute_units() &&
+        choose_tail_split(tiles, grid, round, a.K, MI_BK, t)) {
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;
         b.kchunk = t.chunk;
         launch_grid = dim3((unsigned)t.grid, 1u);
     }
+    if (streamed)
+        return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
+            (void)enqueue_identity_dma(b, dma_stages, n, launch_grid.y, s);
+        });
     return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
         hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3(n, launch_grid.y), dim3(L::NT), L::LDS_BYTES, s, b);
     });
 }
 
 template <int G>
-static hipError_t launch_identity_grid(const MmlikeArgs &a, hipStream_t s)
+static hipError_t launch_identity_grid(const MmlikeArgs &a, int dma_stages, hipStream_t s)
 {
-    if (a.transA && a.transB) return launch_identity_layout<G, true, true>(a, s);
-    if (a.transA) return launch_identity_layout<G, true, false>(a, s);
-    if (a.transB) return launch_identity_layout<G, false, true>(a, s);
-    return launch_identity_layout<G, false, false>(a, s);
+    if (a.transA && a.transB) return launch_identity_layout<G, true, true>(a, dma_stages, s);
+    if (a.transA) return launch_identity_layout<G, true, false>(a, dma_stages, s);
+    if (a.transB) return launch_identity_layout<G, false, true>(a, dma_stages, s);
+    return launch_identity_layout<G, false, false>(a, dma_stages, s);
 }
 
-// big = 0: 128 x 128 tile (4 waves); big = 1: 256 x 256 tile (16 waves)
-hipError_t launch_identity_mfma(const MmlikeArgs &a, int big, hipStream_t s)
+// variant 0: 128 x 128 tile (4 waves), register staged; 1: 256 x 256 tile (16 waves); 2, 3: the
+// 128 x 128 tile streamed through a ring of 3 or 4 LDS stages where the problem allows it
+hipError_t launch_identity_mfma(const MmlikeArgs &a, int variant, hipStream_t s)
 {
-    return big ? launch_identity_grid<4>(a, s) : launch_identity_grid<2>(a, s);
+    switch (variant) {
+    case 0: return launch_identity_grid<2>(a, 0, s);
+    case 1: return launch_identity_grid<4>(a, 0, s);
+    case 2: return launch_identity_grid<2>(a, 3, s);
+    case 3: return launch_identity_grid<2>(a, 4, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace amulet

@@ -1,0 +1,291 @@
+// Identity task (g = p, plain matmul; paper Sec. 6.1) on the fp32 matrix cores, operands
+// streamed HBM -> LDS directly (global_load_lds_dwordx4, gfx950) through a ring of NSTAGE
+// LDS stages.
+//
+// Same arithmetic, tile (128 x 128, 4 waves of 64 x 64) and fragment conventions as
+// identity_mfma_kernel (identity_mfma.hip); what differs is the operand path.  That kernel
+// stages a 16-k slice through registers one stage ahead, which is less than the memory latency:
+// it reaches its rate only with three or four workgroups per compute unit covering for each
+// other, and a problem of one or two tiles per unit runs at 0.72-0.81 of it.  Here a
+// workgroup has NSTAGE - 1 stages in flight by itself, needs no staging registers and no
+// ds_write, and the per-lane global addresses are fixed offsets from a scalar base.
+//
+// LDS layout of a stage (16 KB), un-padded and XOR-swizzled at 16-byte granularity by choosing
+// what each lane fetches:
+//   A tile [128 rows][4 units of 4 k]: row r keeps logical unit u at physical unit
+//     u ^ ((r >> 2) & 3); the 16 lanes a ds_read_b128 is served per clock (16 neighbouring
+//     rows, one unit each) then fall in 16 distinct 16-byte bank groups.
+//   B tile [16 k][32 units of 4 columns]: k-row k keeps logical unit u at u ^ (8 * ((k >> 2) & 1));
+//     a fragment read (ds_read_b32) takes 32 columns of row k in lanes 0-31 and of row k + 4
+//     in lanes 32-63, which land on the two halves of the 64 banks.
+// One barrier per stage, between the stage's two groups of 8 k (see the loop).
+//
+// Used for row-major operands with 16-byte aligned rows when M and N are whole tiles and K a
+// whole number of stages; everything else runs identity_mfma_kernel.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "amulet_internal.h"
+
+// the LDS-DMA asm below sets M0 itself and says so in its clobber list
+#pragma clang diagnostic ignored "-Winline-asm"
+
+namespace amulet {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+constexpr int ID_BM = 128, ID_BN = 128, ID_BK = 16;
+constexpr int ID_A_BYTES = ID_BM * ID_BK * 4;       // 8 KB = 8 wave-loads
+constexpr int ID_B_BYTES = ID_BK * ID_BN * 4;       // 8 KB = 8 wave-loads
+constexpr int ID_STAGE_BYTES = ID_A_BYTES + ID_B_BYTES;
+constexpr int ID_LOADS = 4;                         // DMA instructions per wave per stage
+
+extern __shared__ __attribute__((aligned(16))) char id_smem[];
+
+template <int NSTAGE>
+__global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs args)
+{
+    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    const int M = args.M, N = args.N;
+    int K = args.K;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int li = lane & 31, lh = lane >> 5;
+
+    // place in the XCD-aware tile order, and which k range of it (same conventions as
+    // identity_mfma_kernel: split K over gridDim.y, tail split from tail_base on)
+    const int tiles_m = M / ID_BM, tiles_n = N / ID_BN;
+    int tm, tn;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    const int row0 = tm * ID_BM, col0 = tn * ID_BN;
+    const bool ksplit = gridDim.y > 1 || tail_part;
+    int kb = 0;
+    if (ksplit) {
+        kb = ksplit_idx * args.kchunk;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
+    const int n_stages = K > 0 ? K / ID_BK : 0;
+    if (n_stages <= 0) return;
+
+    // ---- what each lane fetches: two A slots and two B slots per stage ---------------------
+    // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile
+    uint32_t a_voff[2], b_voff[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int j = wave + 4 * q;
+        const int row = 16 * j + (lane >> 2);
+        const int ua = (lane & 3) ^ ((row >> 2) & 3);
+        a_voff[q] = ((uint32_t)row * (uint32_t)args.lda + (uint32_t)(ua * 4)) * 4u;
+        const int k = 2 * j + (lane >> 5);
+        const int ub = (lane & 31) ^ (((k >> 2) & 1) << 3);
+        b_voff[q] = ((uint32_t)k * (uint32_t)args.ldb + (uint32_t)(ub * 4)) * 4u;
+    }
+    const float *const a_base = args.A + (int64_t)row0 * args.lda + kb;
+    const float *const b_base = args.B + (int64_t)kb * args.ldb + col0;
+    const int64_t b_stage = (int64_t)ID_BK * args.ldb;
+
+    // The loads are asm so that the compiler's wait-count pass does not see a vector-memory
+    // instruction writing LDS (it would drain all outstanding loads before every LDS read);
+    // completion is tracked by hand: s_waitcnt vmcnt(n) before the stage's barrier.  M0 carries
+    // the wave-uniform LDS destination; each lane's 16 bytes land at M0 + 16 * lane.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)id_smem;
+    auto dma16 = [&](const float *base, uint32_t voff, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(voff), "s"(base), "s"(lds_addr)
+                     : "memory", "m0");
+    };
+    // load i (0..3) of a stage whose operands start at (ap, bp), into ring slot `buf`
+    auto issue_one = [&](const float *ap, const float *bp, int buf, int i) {
+        const int q = i >> 1;
+        const uint32_t dst = lds_base + (uint32_t)(buf * ID_STAGE_BYTES) + (uint32_t)((wave + 4 * q) * 1024);
+        if (i & 1) dma16(bp, b_voff[q], dst + (uint32_t)ID_A_BYTES);
+        else dma16(ap, a_voff[q], dst);
+    };
+
+    // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
+    // A: values k = 8g + 4 lh + (0..3) of row wr*64 + mi*32 + li: one 16-byte read per (g, mi)
+    // B: value k = 8g + 4 lh + t of column wc*64 + ni*32 + li: one 4-byte read per (g, t, ni)
+    int a_off[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int row = wr * 64 + li;
+        a_off[g] = row * 64 + (((2 * g + lh) ^ ((row >> 2) & 3)) * 16);   // + mi * 2048
+    }
+    int b_off[2];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int unit = wc * 16 + ni * 8 + (li >> 2);
+        b_off[ni] = ID_A_BYTES + (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + (li & 3) * 4;   // + (8g + t) * 512
+    }
+    // fragment read i (0..9) of group g of the stage in slot `buf`: 0, 1 = A (mi), 2..9 = B (t, ni)
+    auto read_one = [&](int buf, int g, int i, f4 (&a)[2], float (&b)[4][2]) {
+        const char *st = id_smem + buf * ID_STAGE_BYTES;
+        if (i < 2) a[i] = *(const f4 *)(st + a_off[g] + i * 2048);
+        else b[(i - 2) >> 1][(i - 2) & 1] = *(const float *)(st + b_off[(i - 2) & 1] + (8 * g + ((i - 2) >> 1)) * 512);
+    };
+    f16v acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+    // The 16 matrix instructions of one group of 8 k (the hardware pairs k-slot h = lane / 32 of
+    // A with k-slot h of B: instruction t of group g multiplies k = 8g + 4h + t), with `side(i)`
+    // issued right after instruction i.  A wave issues in order, and a matrix instruction
+    // occupies the matrix core for 64 cycles during which the wave may issue other instructions:
+    // the stage's LDS reads, loads and scalar bookkeeping are spread over those gaps, a piece per
+    // matrix instruction, instead of standing between two runs of matrix instructions, where the
+    // matrix core idles while they issue (a run of them cost 10-15 % of the loop).
+    auto mma_with = [&](const f4 (&a)[2], const float (&b)[4][2], auto side) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][t], b[t][ni], acc[mi][ni], 0, 0, 0);
+                    side(t * 4 + mi * 2 + ni);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    };
+    // Wait until this wave's loads of stage t have landed, `upto` being the last stage requested
+    // so far: vector memory operations retire in order, so at most the ID_LOADS per later stage
+    // may still be outstanding.  (The count is an immediate: one instruction per value.)
+    auto wait_stage = [&](int t, int upto) {
+        switch (upto - t) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never too little
+        }
+    };
+
+    // The barrier of a stage sits BETWEEN its two groups of 8 k, so that the wait for the other
+    // waves and the latency of the LDS reads that follow it are covered by matrix-core work
+    // already queued: a wave reaches barrier s with the fragments of group 1 of stage s in
+    // registers, and after it runs group 1 of stage s while it requests a later stage and reads
+    // the fragments of group 0 of stage s+1.  Barrier s certifies for all waves: the loads of
+    // stage s+1 have landed, and every read of stage s-1 is complete (its last fragments were
+    // consumed by matrix instructions before the barrier), so the slot of stage s-1 is refilled
+    // after it with stage s+NSTAGE-1.
+    int requested = 0;
+    const float *ap = a_base, *bp = b_base;        // operands of the next stage to request
+#pragma unroll
+    for (int d = 0; d < NSTAGE - 1; ++d)
+        if (d < n_stages) {
+#pragma unroll
+            for (int i = 0; i < ID_LOADS; ++i) issue_one(ap, bp, d, i);
+            ap += ID_BK;
+            bp += b_stage;
+            requested = d + 1;
+        }
+    wait_stage(0, requested - 1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    f4 fa0[2], fa1[2];
+    float fb0[4][2], fb1[4][2];
+    int buf = 0, ibuf = NSTAGE - 1;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) read_one(0, 0, i, fa0, fb0);
+    auto iteration = [&](int s, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
+        const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
+        // group 0 of stage s; the fragments of group 1 are read meanwhile
+        mma_with(fa0, fb0, [&](int i) { if (i < 10) read_one(buf, 1, i, fa1, fb1); });
+        if constexpr (STEADY) {
+            // stages up to s+NSTAGE-2 are requested; s+1 must have landed
+            if constexpr (NSTAGE == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else if constexpr (NSTAGE == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        } else {
+            const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
+            wait_stage(s + 1, last);
+        }
+        __builtin_amdgcn_s_barrier();   // bare: the fence of __syncthreads() would drain the loads in flight
+        asm volatile("" ::: "memory");
+        // group 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
+        // has left) and the fragment reads of group 0 of stage s+1
+        const bool more = STEADY || s + NSTAGE - 1 < n_stages;
+        mma_with(fa1, fb1, [&](int i) {
+            if (i < ID_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
+            else if (i < ID_LOADS + 10) read_one(nbuf, 0, i - ID_LOADS, fa0, fb0);
+        });
+        ap += ID_BK;
+        bp += b_stage;
+        ibuf = buf;
+        buf = nbuf;
+    };
+    const int steady_end = n_stages - (NSTAGE - 1);   // first s that requests nothing more
+    int s = 0;
+    for (; s < steady_end; ++s) iteration(s, std::true_type());
+    for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
+    mma_with(fa0, fb0, [&](int i) { if (i < 10) read_one(buf, 1, i, fa1, fb1); });
+    mma_with(fa1, fb1, [&](int) {});
+
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int col = col0 + wc * 64 + ni * 32 + li;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                float *dst = args.R + (int64_t)row * args.ldr + col;
+                if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                else *dst += acc[mi][ni][v];
+            }
+        }
+}
+
+// Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
+// offsets that fit 32 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+bool identity_dma_eligible(const MmlikeArgs &a)
+{
+    if (a.transA || a.transB || !a.vec || !a.vecA) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.M % ID_BM || a.N % ID_BN || a.K % ID_BK || a.kchunk % ID_BK) return false;
+    if (a.lda > (int64_t)((0xFFFFFFFFLL / 4 - 16) / ID_BM) || a.ldb > (int64_t)((0xFFFFFFFFLL / 4 - ID_BN) / ID_BK)) return false;
+    return true;
+}
+
+int identity_dma_lds_bytes(int nstage) { return nstage * ID_STAGE_BYTES; }
+
+// Enqueues grid.x x grid.y workgroups of the streamed kernel (the caller has checked
+// identity_dma_eligible and fills the split fields of `a` as for identity_mfma_kernel).
+hipError_t enqueue_identity_dma(const MmlikeArgs &a, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    const int lds = identity_dma_lds_bytes(nstage);
+    if (nstage == 3) {
+        static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<3>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 3 * ID_STAGE_BYTES);
+        if (granted != hipSuccess) return granted;
+        hipLaunchKernelGGL((identity_mfma_dma_kernel<3>), dim3(grid_x, grid_y), dim3(256), lds, s, a);
+    } else if (nstage == 4) {
+        static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<4>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ID_STAGE_BYTES);
+        if (granted != hipSuccess) return granted;
+        hipLaunchKernelGGL((identity_mfma_dma_kernel<4>), dim3(grid_x, grid_y), dim3(256), lds, s, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipSuccess;
+}
+
+}  // namespace amulet

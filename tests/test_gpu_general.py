@@ -115,7 +115,7 @@ def test_transposed_strided_unaligned(am):
 
 @pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True)])
 def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
-    """The matrix-core identity kernel (shape 8, the default) with transposed operands: ragged
+    """The matrix-core identity kernel (shape 8; what the default falls back to for these layouts) with transposed operands: ragged
     and multi-tile sizes, odd pitches (scalar path) and aligned ones (16-byte path)."""
     for idx, (M, N, K) in enumerate([(70, 300, 37), (129, 1030, 77), (3, 5, 2), (256, 256, 64), (200, 136, 100),
                                      (130, 129, 17)]):
@@ -124,7 +124,7 @@ def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
         for pad in (0, 3):
             bufA = torch.zeros(As.shape[0], As.shape[1] + pad, device="cuda"); bufA[:, :As.shape[1]] = dev(As)
             bufB = torch.zeros(Bs.shape[0], Bs.shape[1] + pad, device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
-            for shape in (8, 9, -1):
+            for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
                 print("identity trans", tA, tB, M, N, K, pad, shape, flush=True)
                 dR = dev(R_in)
                 am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,
@@ -144,7 +144,7 @@ def test_identity_aligned_ragged_edges_on_the_matrix_cores(am):
         R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
         bufA = torch.full((M + 3, K + 8), float("nan"), device="cuda"); bufA[:M, :K] = dev(As)
         bufB = torch.full((K + 3, N + 12), float("nan"), device="cuda"); bufB[:K, :N] = dev(Bs)
-        for shape in (8, 9, -1):
+        for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
             for (vA, vB) in ((dev(As), dev(Bs)), (bufA[:M, :K], bufB[:K, :N])):
                 print("identity aligned ragged", M, N, K, shape, vA.stride(0), vB.stride(0), flush=True)
                 dR = dev(R_in)
@@ -225,7 +225,7 @@ def test_few_tiles_long_k_split_over_workgroups(am, task):
     transposed layout and data whose sums are exact in any order (bit-exact then)."""
     cases = [(64, 64, 5000, False), (20, 300, 1037, False), (130, 260, 777, True), (5, 5, 4096, False)]
     for idx, (M, N, K, trans) in enumerate(cases):
-        for shape in (4, 0, 5, 7) + ((8, 9) if task == 0 else ()):   # 8, 9: the matrix-core identity kernels
+        for shape in (4, 0, 5, 7) + ((8, 9, 10, 11) if task == 0 else ()):   # 8-11: the matrix-core identity kernels
             form = (idx + shape) % 4 if task else 0
             As, Bs, th, dis, R_in = make_case(task, form, trans, trans, M, N, K, 6100 + 10 * task + idx)
             R_ref, ab, _ = oracle.mmlike_f32_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=trans,
@@ -252,10 +252,36 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
     M, N, K = 1300, 3200, 1100
     As, Bs, th, dis, R_in = make_case(0, 0, trans, trans, M, N, K, 6400 + int(trans))
     R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=trans, trans_b=trans)
-    for shape in (8, 9, -1):
+    for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
         print("identity tail split", trans, shape, M, N, K, flush=True)
         R = run(am, 0, 0, trans, trans, As, Bs, th, dis, R_in, shape)
         assert_parity_f32(R, R_ref, ab, R_in, what="identity tail split shape %d" % shape)
+
+
+def test_identity_streamed_kernel_on_whole_tiles(am):
+    """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: rings
+    of 3 and 4 stages) runs only on whole 128 x 128 tiles, whole 16-k stages and aligned row-major
+    operands.  Cases: fewer stages than the ring holds, one tile, several tiles with padded
+    pitches and a non-zero R_in, few tiles with a long K (every tile split over workgroups),
+    and a few more tiles than compute units (the last round's tiles split).  Every output is
+    checked against the oracle; data whose sums are exact must match bit for bit."""
+    cases = [(128, 128, 16, 0), (128, 128, 32, 0), (256, 384, 208, 4), (128, 256, 4096, 0), (1408, 3200, 1104, 8)]
+    for idx, (M, N, K, pad) in enumerate(cases):
+        As, Bs, th, dis, R_in = make_case(0, 0, False, False, M, N, K, 6500 + idx)
+        R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
+        bufA = torch.full((M, K + pad), float("nan"), device="cuda"); bufA[:, :K] = dev(As)
+        bufB = torch.full((K, N + pad), float("nan"), device="cuda"); bufB[:, :N] = dev(Bs)
+        for shape in (10, 11):
+            print("identity streamed", M, N, K, pad, shape, flush=True)
+            dR = dev(R_in)
+            am.amulet_mmlike_f32_general(0, bufA[:, :K], bufB[:, :N], None, None, dR, shape=shape)
+            torch.cuda.synchronize()
+            assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity streamed %d %dx%dx%d" % (shape, M, N, K))
+    As, Bs, th, dis, R_in = make_case(0, 0, False, False, 256, 256, 1600, 6600, exact=True)
+    R_ref, _, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
+    for shape in (10, 11):
+        R = run(am, 0, 0, False, False, As, Bs, None, None, R_in, shape)
+        assert np.array_equal(R, R_ref), shape
 
 
 @pytest.mark.parametrize("task", TASKS)
