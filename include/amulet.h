@@ -154,9 +154,10 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
  * One IEEE fp64 multiply per product, strict fp64 comparison, fp64 accumulation
  * in unspecified order.  Row-major operands only; `thres_form`, `thres`, `ldt`
  * and `dis` as for amulet_mmlike_f32_general; all pointers are device pointers
- * to doubles (8-byte aligned), owned by the caller; pitches in elements.  One
- * vector-ALU tile shape (16 x 128, 16 k per stage).  Enqueues on `stream` and
- * returns; same error codes as the fp32 calls.
+ * to doubles (8-byte aligned), owned by the caller; pitches in elements.  The
+ * vector-ALU tile shape is the one selected for the size (amulet_mmlike_f64_adaptive),
+ * else a built-in choice.  Enqueues on `stream` and returns; same error codes as
+ * the fp32 calls.
  */
 int amulet_mmlike_f64(int task, int thres_form,
                       int64_t M, int64_t N, int64_t K,
@@ -180,6 +181,54 @@ int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b
                               const double *dis,
                               double *R, int64_t ldr,
                               void *stream);
+
+/*
+ * fp64 tile shapes (the counterpart of the fp32 shape grid, Sec. 4.4-4.6): shape id =
+ * k-axis index * 2 + tile; tile 0 = 16 x 128 (4 waves), 1 = 32 x 128 (8 waves); k axis
+ * 0 = a workgroup sums a tile's whole K (split only where the launcher's own rule asks
+ * for it), 1, 2 = every tile's K in 2, 4 parts added to R with fp64 atomics (not
+ * bit-reproducible; ignored in deterministic mode).  The identity task runs on the
+ * matrix cores whatever the shape.
+ *   amulet_f64_shape_count      number of shape ids (6)
+ *   amulet_f64_shape_name       static string, "invalid" for a bad id
+ *   amulet_selected_shape_f64   shape a plain call uses for (task, M, N, K): the cached
+ *                               selection of its size bucket, else the built-in choice;
+ *                               AMULET_ERR_TASK for a bad task
+ *   amulet_mmlike_f64_shape     amulet_mmlike_f64_general with an explicit shape
+ *                               (-1: as selected); AMULET_ERR_SHAPE for an id >= count
+ */
+int amulet_f64_shape_count(void);
+const char *amulet_f64_shape_name(int shape);
+int amulet_selected_shape_f64(int task, int64_t M, int64_t N, int64_t K);
+int amulet_mmlike_f64_shape(int task, int shape, int thres_form, int trans_a, int trans_b,
+                            int64_t M, int64_t N, int64_t K,
+                            const double *A, int64_t lda,
+                            const double *B, int64_t ldb,
+                            const double *thres, int64_t ldt,
+                            const double *dis,
+                            double *R, int64_t ldr,
+                            void *stream);
+
+/*
+ * In-flight adaptive execution (Sec. 4.4-4.6) in the paper's own element type: as
+ * amulet_mmlike_f32_adaptive_general, on the fp64 shape grid.  Trials are disjoint row
+ * slabs of the caller's R (the shape a plain call would use first, then the k axis,
+ * then the tile axis with an early stop; at most half of the rows), scored by time per
+ * row; the rest runs with the fastest slab's shape, which is cached for the size
+ * bucket and used by later plain fp64 calls.  The result is the complete task, as if
+ * amulet_mmlike_f64_general had been called.  Allocates two events and blocks the
+ * host while trials run; tasks too small for three slabs, and the identity task (one
+ * matrix-core kernel), run whole without trials.  `chosen_shape`, `n_trials` may be
+ * NULL.  Same error codes as amulet_mmlike_f64_general.
+ */
+int amulet_mmlike_f64_adaptive(int task, int thres_form, int trans_a, int trans_b,
+                               int64_t M, int64_t N, int64_t K,
+                               const double *A, int64_t lda,
+                               const double *B, int64_t ldb,
+                               const double *thres, int64_t ldt,
+                               const double *dis,
+                               double *R, int64_t ldr,
+                               void *stream, int *chosen_shape, int *n_trials);
 
 /*
  * Packing (Sec. 3.1 and the "with packing" series of Sec. 6): an operand is copied

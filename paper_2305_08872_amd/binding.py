@@ -80,6 +80,18 @@ def load_library():
     lib.amulet_mmlike_f32_autopack.restype = i32
     lib.amulet_mmlike_f32_autopack.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp,
                                                i64, vp, ctypes.c_size_t, vp]
+    lib.amulet_mmlike_f64_shape.restype = i32
+    lib.amulet_mmlike_f64_shape.argtypes = [i32, i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp,
+                                            i64, vp]
+    lib.amulet_mmlike_f64_adaptive.restype = i32
+    lib.amulet_mmlike_f64_adaptive.argtypes = [i32, i32, i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp,
+                                               i64, vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.amulet_f64_shape_count.restype = i32
+    lib.amulet_f64_shape_count.argtypes = []
+    lib.amulet_f64_shape_name.restype = ctypes.c_char_p
+    lib.amulet_f64_shape_name.argtypes = [i32]
+    lib.amulet_selected_shape_f64.restype = i32
+    lib.amulet_selected_shape_f64.argtypes = [i32, i64, i64, i64]
     lib.amulet_mmlike_f64_autopack.restype = i32
     lib.amulet_mmlike_f64_autopack.argtypes = lib.amulet_mmlike_f32_autopack.argtypes
     lib.amulet_count_i8_workspace_bytes.restype = ctypes.c_size_t
@@ -269,14 +281,39 @@ def amulet_mmlike_f32_adaptive_general(task: int, A, B, thres, dis, R, *, thres_
 
 
 def amulet_mmlike_f64(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
-                      trans_a: bool = False, trans_b: bool = False, stream=None):
+                      trans_a: bool = False, trans_b: bool = False, shape: int = -1, stream=None):
     """The tasks in the paper's own element type: fp64 device tensors; A may be stored K x M
     (trans_a), B N x K (trans_b); `thres` holds N, M, 1 or M x N values according to
-    `thres_form`; `dis` has N values."""
+    `thres_form`; `dis` has N values; `shape` -1 is the selected (else the built-in) fp64 shape."""
     lib = load_library()
     args = _general_args("torch.float64", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
-    _check(lib.amulet_mmlike_f64_general(task, thres_form, int(trans_a), int(trans_b), *args,
-                                         _stream_ptr(stream)), "amulet_mmlike_f64_general")
+    _check(lib.amulet_mmlike_f64_shape(task, shape, thres_form, int(trans_a), int(trans_b), *args,
+                                       _stream_ptr(stream)), "amulet_mmlike_f64_shape")
+
+
+def amulet_mmlike_f64_adaptive(task: int, A, B, thres, dis, R, *, thres_form: int = AMULET_THRES_COL,
+                               trans_a: bool = False, trans_b: bool = False, stream=None):
+    """The fp64 tasks with the paper's in-flight adaptive execution.  Returns (chosen fp64 shape
+    id, number of trial slabs)."""
+    lib = load_library()
+    args = _general_args("torch.float64", task, A, B, thres, dis, R, thres_form, trans_a, trans_b)
+    chosen, trials = ctypes.c_int(-1), ctypes.c_int(0)
+    _check(lib.amulet_mmlike_f64_adaptive(task, thres_form, int(trans_a), int(trans_b), *args, _stream_ptr(stream),
+                                          ctypes.byref(chosen), ctypes.byref(trials)), "amulet_mmlike_f64_adaptive")
+    return chosen.value, trials.value
+
+
+def amulet_f64_shape_count() -> int:
+    return int(load_library().amulet_f64_shape_count())
+
+
+def amulet_f64_shape_name(shape: int) -> str:
+    return load_library().amulet_f64_shape_name(shape).decode()
+
+
+def amulet_selected_shape_f64(task: int, M: int, N: int, K: int) -> int:
+    """The fp64 shape a plain call would use for this size (cached selection, else built-in)."""
+    return _check(load_library().amulet_selected_shape_f64(task, M, N, K), "amulet_selected_shape_f64")
 
 
 def amulet_pitch_collides(ld: int, elem_bytes: int) -> bool:

@@ -409,36 +409,217 @@ int amulet_mmlike_f32_general(int task, int thres_form, int trans_a, int trans_b
     return run_mmlike(c, shape, stream);
 }
 
+// ---- fp64 ------------------------------------------------------------------------------------
+struct F64Call {
+    int task, thres_form, trans_a, trans_b;
+    int64_t M, N, K;
+    const double *A; int64_t lda;
+    const double *B; int64_t ldb;
+    const double *thres; int64_t ldt;
+    const double *dis;
+    double *R; int64_t ldr;
+};
+
+// < 0: error code; 1: nothing to do; 0: go
+static int check_f64(const F64Call &c)
+{
+    if (c.task < TASK_IDENTITY || c.task > TASK_COUNT_GT) return AMULET_ERR_TASK;
+    if (c.thres_form < THRES_COL || c.thres_form > THRES_ELEM) return AMULET_ERR_TASK;
+    if (c.M < 0 || c.N < 0 || c.K < 0) return AMULET_ERR_DIM;
+    if (c.M > kMaxDim || c.N > kMaxDim || c.K > kMaxDim) return AMULET_ERR_RANGE;
+    if (c.M == 0 || c.N == 0 || c.K == 0) return 1;
+    if (!c.A || !c.B || !c.R) return AMULET_ERR_NULL;
+    if (c.task != TASK_IDENTITY && !c.thres) return AMULET_ERR_NULL;
+    if (c.task == TASK_DISCOUNT && !c.dis) return AMULET_ERR_NULL;
+    if (c.lda < (c.trans_a ? c.M : c.K) || c.ldb < (c.trans_b ? c.K : c.N) || c.ldr < c.N) return AMULET_ERR_LD;
+    if (c.task != TASK_IDENTITY && c.thres_form == THRES_ELEM && c.ldt < c.N) return AMULET_ERR_LD;
+    return 0;
+}
+
+// The fp64 selections share the cache of the fp32 ones under task ids of their own.
+static inline int f64_cache_task(int task) { return 1000 + task; }
+
+// Built-in fp64 choice when nothing was adapted: the 4-wave 16 x 128 tile (measured at 4096^3,
+// 8192^2 x 2048, 2048^3, 16 x 128 against 32 x 128 with 8 waves: discount 17.0 / 16.6, 16.5 / 16.5;
+// count 22.5 / 21.3; boost 16.0 / 15.5 TFLOP/s), except for boost problems of up to 2048^2 outputs
+// (15.9 / 16.4), where a workgroup that brings two waves per SIMD fills a launch of one or two
+// rounds better.
+static int default_shape_f64(int task, int64_t M, int64_t N)
+{
+    return task == TASK_BOOST && M * N <= 2048LL * 2048LL && M * N >= 1024LL * 1024LL ? 1 : 0;
+}
+
+static int lookup_shape_f64(int task, int64_t M, int64_t N, int64_t K)
+{
+    if (task == TASK_IDENTITY) return 0;
+    {
+        std::lock_guard<std::mutex> lock(g_sel_mutex);
+        auto it = g_selected.find(sel_key(f64_cache_task(task), M, N, K));
+        if (it != g_selected.end()) return it->second;
+    }
+    return default_shape_f64(task, M, N);
+}
+
+// Rows [r0, r0 + rows) of the task with `shape`.
+static int run_f64_rows(const F64Call &c, int shape, int64_t r0, int64_t rows, void *stream)
+{
+    MmlikeArgsF64 a;
+    a.A = c.trans_a ? c.A + r0 : c.A + r0 * c.lda;
+    a.B = c.B; a.dis = c.dis;
+    a.thres = c.thres;
+    if (c.thres_form == THRES_ROW && c.thres) a.thres = c.thres + r0;
+    if (c.thres_form == THRES_ELEM && c.thres) a.thres = c.thres + r0 * c.ldt;
+    a.R = c.R + r0 * c.ldr;
+    a.lda = c.lda; a.ldb = c.ldb; a.ldr = c.ldr; a.ldt = c.ldt;
+    a.M = (int)rows; a.N = (int)c.N; a.K = (int)c.K;
+    a.transA = c.trans_a; a.transB = c.trans_b;
+    const bool b16 = aligned16(a.B) && c.ldb % 2 == 0;
+    // vec: 16-byte accesses to R, and to the rows of a row-major B
+    a.vec = (aligned16(a.R) && c.ldr % 2 == 0 && (a.transB || b16)) ? 1 : 0;
+    a.vecBt = b16 ? 1 : 0;
+    a.vecA = (aligned16(a.A) && c.lda % 2 == 0) ? 1 : 0;
+    a.kchunk = (int)c.K;
+    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1; a.block_base = 0;
+    const hipError_t e = launch_mmlike_f64(c.task, c.thres_form, shape, a, (hipStream_t)stream);
+    g_last_hip_error = e;
+    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+}
+
+int amulet_mmlike_f64_shape(int task, int shape, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
+                            int64_t K, const double *A, int64_t lda, const double *B, int64_t ldb,
+                            const double *thres, int64_t ldt, const double *dis, double *R, int64_t ldr,
+                            void *stream)
+{
+    const F64Call c = {task, thres_form, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb, thres, ldt, dis, R, ldr};
+    const int rc = check_f64(c);
+    if (rc < 0) return rc;
+    if (shape >= F64_SHAPE_COUNT) return AMULET_ERR_SHAPE;
+    if (shape < 0) shape = lookup_shape_f64(task, M, N, K);
+    if (rc == 1) return AMULET_OK;
+    return run_f64_rows(c, shape, 0, M, stream);
+}
+
 int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N,
                               int64_t K, const double *A, int64_t lda, const double *B, int64_t ldb,
                               const double *thres, int64_t ldt, const double *dis, double *R, int64_t ldr,
                               void *stream)
 {
+    return amulet_mmlike_f64_shape(task, -1, thres_form, trans_a, trans_b, M, N, K, A, lda, B, ldb, thres, ldt, dis,
+                                   R, ldr, stream);
+}
+
+int amulet_f64_shape_count(void) { return F64_SHAPE_COUNT; }
+
+const char *amulet_f64_shape_name(int shape)
+{
+    static const char *const names[F64_SHAPE_COUNT] = {"valu_f64_16x128_k16", "valu_f64_32x128_w8_k16",
+                                                       "valu_f64_16x128_k16_s2", "valu_f64_32x128_w8_k16_s2",
+                                                       "valu_f64_16x128_k16_s4", "valu_f64_32x128_w8_k16_s4"};
+    return shape >= 0 && shape < F64_SHAPE_COUNT ? names[shape] : "invalid";
+}
+
+int amulet_selected_shape_f64(int task, int64_t M, int64_t N, int64_t K)
+{
     if (task < TASK_IDENTITY || task > TASK_COUNT_GT) return AMULET_ERR_TASK;
-    if (thres_form < THRES_COL || thres_form > THRES_ELEM) return AMULET_ERR_TASK;
-    if (M < 0 || N < 0 || K < 0) return AMULET_ERR_DIM;
-    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return AMULET_ERR_RANGE;
-    if (M == 0 || N == 0 || K == 0) return AMULET_OK;
-    if (!A || !B || !R) return AMULET_ERR_NULL;
-    if (task != TASK_IDENTITY && !thres) return AMULET_ERR_NULL;
-    if (task == TASK_DISCOUNT && !dis) return AMULET_ERR_NULL;
-    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldr < N) return AMULET_ERR_LD;
-    if (task != TASK_IDENTITY && thres_form == THRES_ELEM && ldt < N) return AMULET_ERR_LD;
-    MmlikeArgsF64 a;
-    a.A = A; a.B = B; a.thres = thres; a.dis = dis; a.R = R;
-    a.lda = lda; a.ldb = ldb; a.ldr = ldr; a.ldt = ldt;
-    a.M = (int)M; a.N = (int)N; a.K = (int)K;
-    a.transA = trans_a ? 1 : 0; a.transB = trans_b ? 1 : 0;
-    const bool b16 = aligned16(B) && ldb % 2 == 0;
-    // vec: 16-byte accesses to R, and to the rows of a row-major B
-    a.vec = (aligned16(R) && ldr % 2 == 0 && (a.transB || b16)) ? 1 : 0;
-    a.vecBt = b16 ? 1 : 0;
-    a.vecA = (aligned16(A) && lda % 2 == 0) ? 1 : 0;
-    a.kchunk = (int)K;
-    a.tail_base = 0; a.tail_blocks = 0; a.tail_splits = 1; a.block_base = 0;
-    const hipError_t e = launch_mmlike_f64(task, thres_form, a, (hipStream_t)stream);
-    g_last_hip_error = e;
-    return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+    return lookup_shape_f64(task, M, N, K);
+}
+
+// In-flight adaptive execution in fp64 (paper Sec. 4.4-4.6 in the paper's own element type):
+// the scheme of amulet_mmlike_f32_adaptive_general on the fp64 shape grid.
+struct AdaptiveF64 {
+    F64Call call;
+    int64_t next_row, budget_rows;
+    hipStream_t stream;
+    hipEvent_t e0, e1;
+    int status, trials, best_shape;
+    double best_score;
+    double score_of[F64_SHAPE_COUNT];
+};
+
+// A slab of a round and a quarter of workgroups (1280 of 4 waves, 640 of 8), divided by the
+// number of K parts of a split shape, which launches that many workgroups per tile.
+static int64_t trial_rows_f64(const F64Call &c, int shape)
+{
+    const int64_t tile_rows = shape % F64_TILES == 1 ? 32 : 16;
+    int64_t want = shape % F64_TILES == 1 ? 640 : 1280;
+    const int sp = 1 << (shape / F64_TILES);
+    if (sp > 1 && c.K >= 128) want /= sp;
+    const int64_t tiles_n = (c.N + 127) / 128;
+    int64_t row_tiles = (want + tiles_n - 1) / tiles_n;
+    if (row_tiles < 1) row_tiles = 1;
+    return row_tiles * tile_rows;
+}
+
+static double adaptive_f64_score(int i0, int i1, void *ctx)
+{
+    AdaptiveF64 *x = (AdaptiveF64 *)ctx;
+    const int shape = i0 * F64_TILES + i1;
+    if (x->score_of[shape] >= 0.0) return x->score_of[shape];   // a shape is tried once
+    const int64_t rows = trial_rows_f64(x->call, shape);
+    double sc = 1e300;   // no rows left to test on: infinitely slow, which ends the walk
+    if (x->status == AMULET_OK && x->next_row + rows <= x->budget_rows) {
+        (void)hipEventRecord(x->e0, x->stream);
+        const int rc = run_f64_rows(x->call, shape, x->next_row, rows, x->stream);
+        (void)hipEventRecord(x->e1, x->stream);
+        if (rc != AMULET_OK || hipEventSynchronize(x->e1) != hipSuccess) {
+            x->status = AMULET_ERR_LAUNCH;
+        } else {
+            x->next_row += rows;
+            x->trials += 1;
+            float ms = 0.0f;
+            (void)hipEventElapsedTime(&ms, x->e0, x->e1);
+            sc = (double)ms / (double)rows;   // the paper's score: execution time per unit of work
+            if (sc < x->best_score) { x->best_score = sc; x->best_shape = shape; }
+        }
+    }
+    x->score_of[shape] = sc;
+    return sc;
+}
+
+int amulet_mmlike_f64_adaptive(int task, int thres_form, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                               const double *A, int64_t lda, const double *B, int64_t ldb, const double *thres,
+                               int64_t ldt, const double *dis, double *R, int64_t ldr, void *stream,
+                               int *chosen_shape, int *n_trials)
+{
+    const F64Call c = {task, thres_form, trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, lda, B, ldb, thres, ldt, dis, R, ldr};
+    const int rc = check_f64(c);
+    if (rc < 0) return rc;
+    int best = lookup_shape_f64(task, M, N, K);
+    if (chosen_shape) *chosen_shape = best;
+    if (n_trials) *n_trials = 0;
+    if (rc == 1) return AMULET_OK;
+    AdaptiveF64 x;
+    memset(&x, 0, sizeof(x));
+    x.call = c;
+    x.stream = (hipStream_t)stream;
+    x.budget_rows = M / 2;   // at least half of the task runs with the winner
+    x.best_score = 1e300;
+    x.best_shape = -1;
+    for (double &sc : x.score_of) sc = -1.0;
+    // the identity task has one fp64 kernel (matrix cores); a task too small to spare the
+    // default shape's slab and two more runs whole with that shape
+    const bool can_test = task != TASK_IDENTITY &&
+                          trial_rows_f64(c, best) + 2 * trial_rows_f64(c, 0) <= x.budget_rows;
+    if (can_test && hipEventCreate(&x.e0) == hipSuccess && hipEventCreate(&x.e1) == hipSuccess) {
+        // the shape a plain call would use first, then the paper's order: the k axis, then the
+        // tile axis upward with an early stop; the winner is the fastest slab of all
+        (void)adaptive_f64_score(best / F64_TILES, best % F64_TILES, &x);
+        int b0 = 0, b1 = 0;
+        amulet_greedy_search(F64_KAXIS, F64_TILES, adaptive_f64_score, &x, &b0, &b1);
+        if (x.best_shape >= 0) best = x.best_shape;
+    }
+    if (x.e0) (void)hipEventDestroy(x.e0);
+    if (x.e1) (void)hipEventDestroy(x.e1);
+    if (x.status != AMULET_OK) return x.status;
+    int out = AMULET_OK;
+    if (x.next_row < M) out = run_f64_rows(c, best, x.next_row, M - x.next_row, stream);
+    if (out == AMULET_OK && x.trials > 0) {
+        std::lock_guard<std::mutex> lock(g_sel_mutex);
+        g_selected[sel_key(f64_cache_task(task), M, N, K)] = best;
+    }
+    if (chosen_shape) *chosen_shape = best;
+    if (n_trials) *n_trials = x.trials;
+    return out;
 }
 
 int amulet_mmlike_f64(int task, int thres_form, int64_t M, int64_t N, int64_t K, const double *A,

@@ -337,7 +337,10 @@ struct MmlikeArgsF64 {
     int block_base;   // added to blockIdx.x (launch_row_of_blocks)
 };
 // predicate tasks: vector-ALU kernel; identity task: fp64 matrix-core kernel
-hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s);
+// fp64 shapes of the predicate tasks: a small grid of the same two axes as the fp32 one
+// (k axis: K whole, in 2, in 4 parts per tile; tile: 16 x 128 with 4 waves, 32 x 128 with 8).
+enum { F64_KAXIS = 3, F64_TILES = 2, F64_SHAPE_COUNT = F64_KAXIS * F64_TILES };
+hipError_t launch_mmlike_f64(int task, int form, int shape, const MmlikeArgsF64 &a, hipStream_t s);
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
 
 // dst (cols x rows, pitch ld_dst) = transpose of src (rows x cols, pitch ld_src), bytes (pack.hip)

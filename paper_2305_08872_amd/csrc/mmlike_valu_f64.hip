@@ -25,7 +25,8 @@ typedef double d4r __attribute__((ext_vector_type(4)));
 typedef d4r d4_a8 __attribute__((aligned(8)));
 typedef const __attribute__((address_space(4))) d4_a8 *sptr_d4;
 
-constexpr int D_TM = 4, D_NW = 4, D_BK = 16, D_BN = 128, D_NT = 64 * D_NW;
+// (the workgroup has D_NW = 4 or 8 waves, a template parameter: tile 16 x 128 or 32 x 128)
+constexpr int D_TM = 4, D_BK = 16, D_BN = 128;
 
 template <int TASK> struct AccD { typedef double type; };
 template <> struct AccD<TASK_COUNT_GT> { typedef int type; };
@@ -101,15 +102,17 @@ __device__ __forceinline__ void fold_rows(const double (&a)[D_TM], d2 b, const d
 // ALDS: the workgroup's rows of A go through LDS (vector loads a whole tile ahead, broadcast
 // reads) instead of through the scalar cache; used when the row pitch of A collides in the memory
 // system (as in the fp32 kernels, where the reason is given).
-template <int TASK, int TF, int TRANS, bool ALDS>
-__global__ void __launch_bounds__(D_NT)
+template <int TASK, int TF, int TRANS, bool ALDS, int D_NW>
+__global__ void __launch_bounds__(64 * D_NW)
 mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
 {
     static_assert(!ALDS || TRANS == 0, "A through LDS: row-major operands");
+    static_assert(D_NW == 4 || D_NW == 8, "4 or 8 waves");
+    constexpr int D_NT = 64 * D_NW;
     typedef typename AccD<TASK>::type acc_t;
     constexpr int D2_PER_ROW = D_BN / 2;                     // 16-byte slots in one LDS row
-    constexpr int ROWS_PER_PASS = D_NT / D2_PER_ROW;         // 4
-    constexpr int LOADS = D_BK / ROWS_PER_PASS;              // 4 slots staged per thread per tile
+    constexpr int ROWS_PER_PASS = D_NT / D2_PER_ROW;         // 4 or 8
+    constexpr int LOADS = D_BK / ROWS_PER_PASS;              // 4 or 2 slots staged per thread per tile
     constexpr int KA = 2;                                    // A is fetched two k at a time (one 16-byte scalar load per row)
 
     __shared__ __attribute__((aligned(16))) double Bs[2][D_BK][D_BN];
@@ -214,12 +217,12 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     const int64_t pass_stride = (int64_t)ROWS_PER_PASS * args.ldb;
     const int64_t tile_stride = (int64_t)D_BK * args.ldb;
     d2 stage[LOADS];
-    // B stored transposed: a thread owns one column of the tile and 8 consecutive k of it,
-    // read as four 16-byte pieces along k and scattered into the same [k][n] LDS tile
+    // B stored transposed: a thread owns one column of the tile and 2 LOADS (8 or 4) consecutive
+    // k of it, read as 16-byte pieces along k and scattered into the same [k][n] LDS tile
     // (neighbouring lanes hit neighbouring banks).
-    static_assert(D_NT == 2 * D_BN && D_BK == 16 && LOADS == 4, "transposed-B slot mapping");
+    static_assert((D_NT / D_BN) * 2 * LOADS == D_BK, "transposed-B slot mapping");
     const int tcol = threadIdx.x % D_BN;
-    const int tk = (threadIdx.x / D_BN) * 8;
+    const int tk = (threadIdx.x / D_BN) * 2 * LOADS;
     const double *btsrc = Bg + (int64_t)(col0 + tcol < N ? col0 + tcol : N - 1) * args.ldb + tk;
     // A tile staging (ALDS): thread t < A_D2 stages slot (row t / (D_BK / 2), k pair t % (D_BK / 2))
     const int a_sr = threadIdx.x / (D_BK / 2), a_sq = (threadIdx.x % (D_BK / 2)) * 2;
@@ -469,22 +472,23 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     }
 }
 
-template <int TASK, int TRANS, bool ALDS>
+template <int TASK, int TRANS, bool ALDS, int D_NW>
 static hipError_t launch_f64_form(int form, const MmlikeArgsF64 &args, dim3 whole, hipStream_t s)
 {
+    constexpr int D_NT = 64 * D_NW;
     MmlikeArgsF64 a = args;
     return launch_row_of_blocks(a, whole.x, D_NT, [&](unsigned n) {
         const dim3 grid(n, whole.y);
         switch (form) {
-        case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
-        case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
-        case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
-        default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS, ALDS>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_COL: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_COL, TRANS, ALDS, D_NW>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_ROW: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ROW, TRANS, ALDS, D_NW>), grid, dim3(D_NT), 0, s, a); break;
+        case THRES_CONST: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_CONST, TRANS, ALDS, D_NW>), grid, dim3(D_NT), 0, s, a); break;
+        default: hipLaunchKernelGGL((mmlike_valu_f64_kernel<TASK, THRES_ELEM, TRANS, ALDS, D_NW>), grid, dim3(D_NT), 0, s, a); break;
         }
     });
 }
 
-template <int TASK>
+template <int TASK, int D_NW>
 static hipError_t launch_f64_layout(int trans, int form, const MmlikeArgsF64 &a, dim3 grid, hipStream_t s)
 {
     switch (trans) {
@@ -495,21 +499,22 @@ static hipError_t launch_f64_layout(int trans, int form, const MmlikeArgsF64 &a,
         // against 11.8-13.0; boost 14.0 / 15.6 against 12.7 / 14.9 at 1024^3 / 2048^3 but 15.8
         // against 16.1 at 4096^3, so large boost problems keep the scalar path.
         const bool lds = pitch_collides(a.lda, 8) || TASK != TASK_BOOST || (int64_t)a.M * a.N <= 2048LL * 2048LL;
-        return lds ? launch_f64_form<TASK, 0, true>(form, a, grid, s) : launch_f64_form<TASK, 0, false>(form, a, grid, s);
+        return lds ? launch_f64_form<TASK, 0, true, D_NW>(form, a, grid, s) : launch_f64_form<TASK, 0, false, D_NW>(form, a, grid, s);
     }
-    case 1: return launch_f64_form<TASK, 1, false>(form, a, grid, s);
-    case 2: return launch_f64_form<TASK, 2, false>(form, a, grid, s);
-    default: return launch_f64_form<TASK, 3, false>(form, a, grid, s);
+    case 1: return launch_f64_form<TASK, 1, false, D_NW>(form, a, grid, s);
+    case 2: return launch_f64_form<TASK, 2, false, D_NW>(form, a, grid, s);
+    default: return launch_f64_form<TASK, 3, false, D_NW>(form, a, grid, s);
     }
 }
 
-hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStream_t s)
+// force_splits > 1: every tile's K in that many parts (a k-axis point of the shape grid)
+template <int D_NW>
+static hipError_t launch_mmlike_f64_waves(int task, int form, int force_splits, const MmlikeArgsF64 &a, hipStream_t s)
 {
     const int64_t tiles_m = (a.M + D_NW * D_TM - 1) / (D_NW * D_TM);
     const int64_t tiles_n = (a.N + D_BN - 1) / D_BN;
     const int64_t wgs = xcd_grid(tiles_m, tiles_n);
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
     // tiles for at most half of the waves the chip holds at once (4 per SIMD): split K over
     // as many workgroups per tile as still fit (at least 64 k each), which add their parts
     // to R with hardware fp64 atomics
@@ -517,8 +522,9 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     int splits = 1;
     b.kchunk = a.K;
     const int64_t waves = tiles_m * tiles_n * D_NW;
-    if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
-        int64_t want = 4096 / waves;
+    const bool forced = force_splits > 1 && k_split_allowed() && a.K >= 128;
+    if (forced || (k_split_allowed() && waves <= 2048 && a.K >= 128)) {
+        int64_t want = forced ? force_splits : 4096 / waves;
         if (want > a.K / 64) want = a.K / 64;
         if (want > 1024) want = 1024;
         const int64_t chunk = ((a.K + want - 1) / want + D_BK - 1) / D_BK * D_BK;
@@ -530,7 +536,7 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     // a last round of workgroups that would leave most of the chip idle: its tiles are launched
     // once per k range instead (choose_tail_split in amulet_internal.h)
     TailSplit t;
-    if (splits == 1 && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / D_NW), a.K, D_BK, t)) {
+    if (splits == 1 && !forced && choose_tail_split(tiles_m * tiles_n, wgs, (int64_t)compute_units() * (16 / D_NW), a.K, D_BK, t)) {
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;
@@ -539,11 +545,23 @@ hipError_t launch_mmlike_f64(int task, int form, const MmlikeArgsF64 &a, hipStre
     }
     const int trans = (a.transA ? 1 : 0) | (a.transB ? 2 : 0);
     switch (task) {
-    case TASK_DISCOUNT: return launch_f64_layout<TASK_DISCOUNT>(trans, form, b, grid, s);
-    case TASK_BOOST: return launch_f64_layout<TASK_BOOST>(trans, form, b, grid, s);
-    case TASK_COUNT_GT: return launch_f64_layout<TASK_COUNT_GT>(trans, form, b, grid, s);
+    case TASK_DISCOUNT: return launch_f64_layout<TASK_DISCOUNT, D_NW>(trans, form, b, grid, s);
+    case TASK_BOOST: return launch_f64_layout<TASK_BOOST, D_NW>(trans, form, b, grid, s);
+    case TASK_COUNT_GT: return launch_f64_layout<TASK_COUNT_GT, D_NW>(trans, form, b, grid, s);
     default: return hipErrorInvalidValue;
     }
+}
+
+// shape = k-axis index * F64_TILES + tile; tile 0: 16 x 128 (4 waves), tile 1: 32 x 128 (8 waves);
+// k axis 0: K split only where the launcher's own rule asks for it, 1, 2: every tile's K in 2, 4
+// parts.  The identity task runs on the matrix cores whatever the shape.
+hipError_t launch_mmlike_f64(int task, int form, int shape, const MmlikeArgsF64 &a, hipStream_t s)
+{
+    if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
+    if (shape < 0 || shape >= F64_SHAPE_COUNT) return hipErrorInvalidValue;
+    const int force = shape / F64_TILES == 0 ? 0 : 1 << (shape / F64_TILES);
+    return shape % F64_TILES == 1 ? launch_mmlike_f64_waves<8>(task, form, force, a, s)
+                                  : launch_mmlike_f64_waves<4>(task, form, force, a, s);
 }
 
 }  // namespace amulet

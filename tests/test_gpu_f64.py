@@ -315,3 +315,76 @@ def test_rows_of_A_with_a_colliding_pitch_go_through_lds(am, task):
         print("f64 A through LDS", task, form, M, N, K, flush=True)
         R = run(am, task, form, dA, dev(B), th, dis, dev(R_in))
         check(R, R_ref, ab, R_in, task, "f64 A through LDS task %d form %d %dx%dx%d" % (task, form, M, N, K))
+
+
+@pytest.mark.parametrize("task", [1, 2, 3])
+@pytest.mark.parametrize("shape", range(6))
+def test_f64_every_shape_on_ragged_sizes(am, task, shape):
+    """Every point of the fp64 shape grid (tile 16 x 128 or 32 x 128, K whole or in 2 or 4 parts per
+    tile): ragged sizes, every threshold form, row-major and transposed operands, one case long
+    enough in K for the forced split to apply, and exact data bit for bit."""
+    assert am.amulet_f64_shape_count() == 6 and am.amulet_f64_shape_name(shape) != "invalid"
+    cases = [(70, 300, 37, False, False), (33, 513, 100, True, False), (129, 130, 77, False, True),
+             (3, 5, 2, True, True), (40, 260, 700, False, False), (65, 129, 333, True, True)]
+    for idx, (M, N, K, tA, tB) in enumerate(cases):
+        form = (idx + task + shape) % 4
+        A, B, th, dis, R_in = make_case(form, M, N, K, 9000 + 100 * task + 10 * shape + idx)
+        As = np.ascontiguousarray(A.T) if tA else A
+        Bs = np.ascontiguousarray(B.T) if tB else B
+        print("case f64 shape", task, shape, form, M, N, K, tA, tB, flush=True)
+        R_ref, ab, _ = oracle.mmlike_f64_general(task, As, Bs, th, dis, R_in, thres_form=form, trans_a=tA, trans_b=tB)
+        dR = dev(R_in)
+        am.amulet_mmlike_f64(task, dev(As), dev(Bs), dev(th), dev(dis) if task == 1 else None, dR,
+                             thres_form=form, trans_a=tA, trans_b=tB, shape=shape)
+        torch.cuda.synchronize()
+        check(dR.cpu().numpy(), R_ref, ab, R_in, task, "f64 shape %d task %d %dx%dx%d" % (shape, task, M, N, K))
+    A, B, th, dis, R_in = make_case(0, 48, 200, 1500, 9900 + task, exact=True)
+    R_ref, _, _ = oracle.mmlike_f64_general(task, A, B, th, dis, R_in)
+    dR = dev(R_in)
+    am.amulet_mmlike_f64(task, dev(A), dev(B), dev(th), dev(dis) if task == 1 else None, dR, shape=shape)
+    torch.cuda.synchronize()
+    assert np.array_equal(dR.cpu().numpy(), R_ref)
+    with pytest.raises(am.AmuletError):
+        am.amulet_mmlike_f64(task, dev(A), dev(B), dev(th), dev(dis) if task == 1 else None, dR, shape=6)
+
+
+def test_f64_adaptive_execution_trials_contribute_to_the_result(am):
+    """In-flight adaptive execution in fp64: the trial slabs are rows of the caller's R computed
+    with different shapes, the rest runs with the winner, and the whole R must match the oracle
+    (general form: thres[i], transposed A).  The winner is cached for the size bucket and used by
+    a later plain call; the identity task and small tasks run whole, without trials."""
+    M, N, K = 8192, 4096, 160
+    form, tA = 1, True
+    A, B, th, dis, R_in = make_case(form, M, N, K, 9950)
+    As = np.ascontiguousarray(A.T)
+    R_ref, ab, _ = oracle.mmlike_f64_general(1, As, B, th, dis, R_in, thres_form=form, trans_a=tA)
+    am.amulet_clear_selections()
+    dA, dB, dth, ddis = dev(As), dev(B), dev(th), dev(dis)
+    dR = dev(R_in)
+    chosen, trials = am.amulet_mmlike_f64_adaptive(1, dA, dB, dth, ddis, dR, thres_form=form, trans_a=tA)
+    torch.cuda.synchronize()
+    print("f64 adaptive chose", chosen, am.amulet_f64_shape_name(chosen), "after", trials, "trials", flush=True)
+    assert 0 <= chosen < am.amulet_f64_shape_count() and trials >= 4   # the default, the k axis, one more tile
+    check(dR.cpu().numpy(), R_ref, ab, R_in, 1, "f64 adaptive")
+    assert am.amulet_selected_shape_f64(1, M, N, K) == chosen
+    assert am.amulet_selected_shape_f64(1, M - 3, N - 1, K) == chosen      # same size bucket
+    dR2 = dev(R_in)
+    am.amulet_mmlike_f64(1, dA, dB, dth, ddis, dR2, thres_form=form, trans_a=tA)
+    torch.cuda.synchronize()
+    check(dR2.cpu().numpy(), R_ref, ab, R_in, 1, "f64 plain after adaptive")
+    # too small for three slabs: no trials, still the whole result
+    A, B, th, dis, R_in = make_case(0, 300, 260, 50, 9951)
+    R_ref, ab, _ = oracle.mmlike_f64_general(2, A, B, th, None, R_in)
+    dR = dev(R_in)
+    chosen, trials = am.amulet_mmlike_f64_adaptive(2, dev(A), dev(B), dev(th), None, dR)
+    torch.cuda.synchronize()
+    assert trials == 0
+    check(dR.cpu().numpy(), R_ref, ab, R_in, 2, "f64 adaptive small")
+    # identity: one matrix-core kernel, no trials
+    R_ref, ab, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
+    dR = dev(R_in)
+    chosen, trials = am.amulet_mmlike_f64_adaptive(0, dev(A), dev(B), None, None, dR)
+    torch.cuda.synchronize()
+    assert trials == 0
+    check(dR.cpu().numpy(), R_ref, ab, R_in, 0, "f64 adaptive identity")
+    am.amulet_clear_selections()
