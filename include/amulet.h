@@ -429,7 +429,7 @@ int amulet_mmlike_f32_adaptive_general(int task, int thres_form, int trans_a, in
  * up to a multiple of 256) and synchronises `stream`.  The device is first run up to
  * its loaded clocks, a trial is the better of two spans of about 2 ms of
  * back-to-back launches, and the search's winner replaces the built-in default
- * only if it also beats it in a direct rematch.  Unlike the compute calls this
+ * only if it also beats it in a direct rematch by more than 3 %.  Unlike the compute calls this
  * one allocates and blocks; it is meant to run once, outside the hot path.
  * task may be 0..3, or AMULET_TASK_COUNT_I8 for amulet_count_i8.
  * Returns the chosen shape id (>= 0) or a negative status.

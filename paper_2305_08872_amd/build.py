@@ -22,7 +22,7 @@ SOURCES = ["amulet_api.hip", "mmlike_valu_identity_col.hip"] + [
     "mmlike_valu_%s_%s.hip" % (task, form)
     for task in ("discount", "boost", "count_gt")
     for form in ("col", "row", "const", "elem")
-] + ["identity_mfma.hip", "identity_mfma_dma.hip", "count_i8.hip", "count_i8_dma.hip", "valu_probe.hip", "mmlike_valu_f64.hip", "identity_mfma_f64.hip", "pack.hip"]
+] + ["identity_mfma.hip", "identity_mfma_dma.hip", "count_i8.hip", "count_i8_dma.hip", "valu_probe.hip", "mmlike_valu_f64.hip", "identity_mfma_f64.hip", "identity_mfma_f64_dma.hip", "pack.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -1063,8 +1063,9 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
                 }
             }
         }
-        // the search's winner replaces the built-in default only if it also wins a direct rematch
-        if (c.status == AMULET_OK && chosen != dflt && time_shape(&c, chosen) >= time_shape(&c, dflt))
+        // the search's winner replaces the built-in default only if it also wins a direct rematch,
+        // by more than the 3 % that two timings of one shape can differ by
+        if (c.status == AMULET_OK && chosen != dflt && time_shape(&c, chosen) >= 0.97 * time_shape(&c, dflt))
             chosen = dflt;
         (void)hipStreamSynchronize(c.stream);
         if (c.status == AMULET_OK) {

@@ -210,11 +210,13 @@ inline int choose_full_split(int64_t part_tiles, int64_t units_per_xcd, int64_t 
 // time, after two or more (the units have drifted apart by then) a whole round's (1024 tiles
 // unsplit, 768 + 256 workgroups, took as long as two full rounds; in two ranges, 2 x 768 + 512,
 // as long as three).  Each range also pays its
-// set-up and write-back, in units of one k of a tile at full rate: 210 alone, 175 s with atomic
-// adds (12 and 10 us at 57.5 ns per k).  The s <= 8 with at least 128 k per range and the lowest
+// set-up and write-back, in units of one k of a tile at full rate: `ovh_alone`, or `ovh_split` s
+// with atomic adds (fp32: 210 and 175, i.e. 12 and 10 us at 57.5 ns per k; fp64, 115 ns per k: 105
+// and 87).  The s <= 8 with at least 128 k per range and the lowest
 // estimate is returned (1: do not split).  Checked against sweeps of s = 1..8 at 144 ... 1024
 // tiles (K = 1536 ... 4096): the chosen s is the best or within 2 % of the best one measured.
-inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int cap, const double *rate)
+inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int cap, const double *rate,
+                               double ovh_alone = 210.0, double ovh_split = 175.0)
 {
     if (!k_split_allowed() || part_tiles <= 0 || units <= 0) return 1;
     const int max_s = K / 128 < 8 ? (int)(K / 128) : 8;
@@ -232,7 +234,7 @@ inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int
             if (q >= 2) left = (double)cap;
             cost += left * work;
         }
-        cost += sp == 1 ? 210.0 : 175.0 * sp;
+        cost += sp == 1 ? ovh_alone : ovh_split * sp;
         if (sp == 1 || cost < best * 0.99) { best = cost; best_s = sp; }
     }
     return best_s;
@@ -342,6 +344,9 @@ struct MmlikeArgsF64 {
 enum { F64_KAXIS = 3, F64_TILES = 2, F64_SHAPE_COUNT = F64_KAXIS * F64_TILES };
 hipError_t launch_mmlike_f64(int task, int form, int shape, const MmlikeArgsF64 &a, hipStream_t s);
 hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
+// the streamed fp64 identity kernel (identity_mfma_f64_dma.hip)
+bool identity_f64_dma_eligible(const MmlikeArgsF64 &a);
+hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s);
 
 // dst (cols x rows, pitch ld_dst) = transpose of src (rows x cols, pitch ld_src), bytes (pack.hip)
 hipError_t launch_pack_pad_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,

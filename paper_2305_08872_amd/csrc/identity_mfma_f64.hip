@@ -246,9 +246,24 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
     dim3 launch_grid(grid, (unsigned)splits);
-    // Up to four tiles per compute unit: every tile once per k range, as many ranges as the
-    // occupancy model likes best (choose_full_split in amulet_internal.h).
-    if (splits == 1 && n_tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
+    // The streamed kernel where the problem allows it (row-major operands, whole tiles): two
+    // workgroups to a compute unit; with at most two rounds of tiles every tile is launched once
+    // per k range (choose_stream_split in amulet_internal.h).
+    bool streamed = false;
+    if constexpr (!TA && !TB) streamed = identity_f64_dma_eligible(b);
+    if (streamed && splits == 1 && n_tiles <= 4 * (int64_t)compute_units()) {
+        static const double rate2[2] = {0.93, 1.0};
+        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, 2, rate2, 105.0, 87.0);
+        if (sp > 1) {
+            const int64_t chunk = ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK;
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+            launch_grid = dim3(grid, (unsigned)splits);
+        }
+    }
+    // Register-staged kernel, up to four tiles per compute unit: every tile once per k range, as
+    // many ranges as the occupancy model likes best (choose_full_split in amulet_internal.h).
+    if (!streamed && splits == 1 && n_tiles <= 4 * (int64_t)compute_units() && a.K >= 512) {
         static const double rate[2] = {0.86, 1.0};
         const int sp = choose_full_split(grid / 8, compute_units() / 8, a.K, rate, 2);
         if (sp > 1) {
@@ -258,18 +273,23 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
             launch_grid = dim3(grid, (unsigned)splits);
         }
     }
-    // more tiles than that: the launch runs in rounds of about one tile per compute unit (as in
-    // the fp32 kernel); the tiles of a nearly empty last round are launched once per k range
-    // instead (choose_tail_split in amulet_internal.h)
+    // more tiles than that: the launch runs in rounds (about one tile per compute unit for the
+    // register-staged kernel, as in the fp32 kernel; two for the streamed one); the tiles of a
+    // nearly empty last round are launched once per k range instead (choose_tail_split in
+    // amulet_internal.h)
     TailSplit t;
     if (splits == 1 && n_tiles > 4 * (int64_t)compute_units() &&
-        choose_tail_split(n_tiles, grid, compute_units(), a.K, DI_BK, t)) {
+        choose_tail_split(n_tiles, grid, (streamed ? 2 : 1) * (int64_t)compute_units(), a.K, DI_BK, t)) {
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;
         b.kchunk = t.chunk;
         launch_grid = dim3((unsigned)t.grid, 1u);
     }
+    if (streamed)
+        return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
+            (void)enqueue_identity_f64_dma(b, n, launch_grid.y, s);
+        });
     return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
         hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(n, launch_grid.y), dim3(DI_NT), LDS, s, b);
     });

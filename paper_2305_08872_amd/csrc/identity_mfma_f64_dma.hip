@@ -1,0 +1,266 @@
+// Identity task (g = p, plain matmul; paper Sec. 6.1) in fp64 on the matrix cores, operands
+// streamed HBM -> LDS directly (global_load_lds_dwordx4, gfx950) through a ring of NSTAGE LDS
+// stages: the fp64 counterpart of identity_mfma_dma_kernel (identity_mfma_dma.hip), where the
+// reasons are given.
+//
+// Same arithmetic, tile (128 x 128, 8 waves of 32 x 64 = 2 x 4 blocks of v_mfma_f64_16x16x4_f64)
+// and result layout as identity_mfma_f64_kernel.  A stage is 8 k deep (A 128 x 8 and B 8 x 128
+// doubles, 16 KB); a ring of 4 stages is 64 KB, two workgroups per compute unit.  The hardware
+// pairs k-slot h (= lane / 16) of A with k-slot h of B, so which k a slot carries is free: the
+// stage's first matrix step takes k = h, the second k = 4 + h.
+//
+// LDS layout of a stage, un-padded and XOR-swizzled at 16-byte granularity by choosing what each
+// lane fetches:
+//   A tile [128 rows][4 units of 2 k]: row r keeps logical unit u at u ^ ((r >> 2) & 3); a fragment
+//     read (ds_read_b64) takes 16 neighbouring rows x 2 k-slots per clock, which then fall in 32
+//     distinct 8-byte bank pairs;
+//   B tile [8 k][64 units of 2 columns]: k-row k keeps logical unit u at u ^ (8 * (k & 1)); a
+//     fragment read takes 16 columns of rows k and k + 1 per clock, which land on the two halves
+//     of the banks.
+// One barrier per stage, between its two matrix steps.
+//
+// Used for row-major operands with 16-byte aligned rows when M and N are whole tiles and K a
+// whole number of stages; everything else runs identity_mfma_f64_kernel.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "amulet_internal.h"
+
+// the LDS-DMA asm below sets M0 itself and says so in its clobber list
+#pragma clang diagnostic ignored "-Winline-asm"
+
+namespace amulet {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+constexpr int DD_BM = 128, DD_BN = 128, DD_BK = 8, DD_NT = 512;
+constexpr int DD_A_BYTES = DD_BM * DD_BK * 8;       // 8 KB = 8 wave-loads
+constexpr int DD_B_BYTES = DD_BK * DD_BN * 8;       // 8 KB = 8 wave-loads
+constexpr int DD_STAGE_BYTES = DD_A_BYTES + DD_B_BYTES;
+constexpr int DD_LOADS = 2;                         // DMA instructions per wave per stage
+
+extern __shared__ __attribute__((aligned(16))) char dd_smem[];
+
+template <int NSTAGE>
+__global__ void __launch_bounds__(DD_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
+{
+    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    const int M = args.M, N = args.N;
+    int K = args.K;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int li = lane & 15, lh = lane >> 4;
+
+    // place in the XCD-aware tile order, and which k range of it (same conventions as
+    // identity_mfma_f64_kernel: split K over gridDim.y, tail split from tail_base on)
+    const int tiles_m = M / DD_BM, tiles_n = N / DD_BN;
+    int tm, tn;
+    int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
+    const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
+    if (tail_part) {
+        const int rel = block - args.tail_base;
+        block = args.tail_base + rel % args.tail_blocks;
+        ksplit_idx = rel / args.tail_blocks;
+    }
+    if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
+    const int row0 = tm * DD_BM, col0 = tn * DD_BN;
+    const bool ksplit = gridDim.y > 1 || tail_part;
+    int kb = 0;
+    if (ksplit) {
+        kb = ksplit_idx * args.kchunk;
+        K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
+    }
+    const int n_stages = K > 0 ? K / DD_BK : 0;
+    if (n_stages <= 0) return;
+
+    // ---- what each lane fetches: one A slot and one B slot per stage -----------------------
+    // wave w owns the 1 KB slot group w of each operand's tile: A rows 16w .. 16w+15, B k-row w
+    const int a_row = 16 * wave + (lane >> 2);
+    const int a_u = (lane & 3) ^ ((a_row >> 2) & 3);
+    const uint32_t a_voff = ((uint32_t)a_row * (uint32_t)args.lda + (uint32_t)(a_u * 2)) * 8u;
+    const int b_u = lane ^ ((wave & 1) << 3);
+    const uint32_t b_voff = ((uint32_t)wave * (uint32_t)args.ldb + (uint32_t)(b_u * 2)) * 8u;
+    const double *const a_base = args.A + (int64_t)row0 * args.lda + kb;
+    const double *const b_base = args.B + (int64_t)kb * args.ldb + col0;
+    const int64_t b_stage = (int64_t)DD_BK * args.ldb;
+
+    // The loads are asm so that the compiler's wait-count pass does not see a vector-memory
+    // instruction writing LDS (it would drain all outstanding loads before every LDS read);
+    // completion is tracked by hand: s_waitcnt vmcnt(n) before the stage's barrier.  M0 carries
+    // the wave-uniform LDS destination; each lane's 16 bytes land at M0 + 16 * lane.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)dd_smem;
+    auto dma16 = [&](const double *base, uint32_t voff, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(voff), "s"(base), "s"(lds_addr)
+                     : "memory", "m0");
+    };
+    // load i (0: A, 1: B) of a stage whose operands start at (ap, bp), into ring slot `buf`
+    auto issue_one = [&](const double *ap, const double *bp, int buf, int i) {
+        const uint32_t dst = lds_base + (uint32_t)(buf * DD_STAGE_BYTES) + (uint32_t)(wave * 1024);
+        if (i & 1) dma16(bp, b_voff, dst + (uint32_t)DD_A_BYTES);
+        else dma16(ap, a_voff, dst);
+    };
+
+    // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
+    // matrix step g of the stage multiplies k = 4g + lh:
+    //   A: value k of row wr*32 + mi*16 + li; B: value k of column wc*64 + ni*16 + li
+    int a_off[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int row = wr * 32 + li, k = 4 * g + lh;
+        a_off[g] = row * 64 + (((k >> 1) ^ ((row >> 2) & 3)) * 16) + (k & 1) * 8;   // + mi * 1024
+    }
+    int b_off[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const int unit = wc * 32 + ni * 8 + (li >> 1);
+        b_off[ni] = DD_A_BYTES + lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + (li & 1) * 8;   // + g * 4096
+    }
+    // fragment read i (0..5) of matrix step g of the stage in slot `buf`: 0, 1 = A (mi), 2..5 = B (ni)
+    auto read_one = [&](int buf, int g, int i, double (&a)[2], double (&b)[4]) {
+        const char *st = dd_smem + buf * DD_STAGE_BYTES;
+        if (i < 2) a[i] = *(const double *)(st + a_off[g] + i * 1024);
+        else b[i - 2] = *(const double *)(st + b_off[i - 2] + g * 4096);
+    };
+    d4 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[mi][ni][v] = 0.0;
+    // The 8 matrix instructions of one matrix step, with `side(i)` issued right after
+    // instruction i: a wave issues in order and a matrix instruction occupies the matrix core for
+    // 64 cycles during which the wave may issue other instructions, so the stage's LDS reads and
+    // loads are spread over those gaps instead of standing between two runs of matrix
+    // instructions.
+    auto mma_with = [&](const double (&a)[2], const double (&b)[4], auto side) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+                acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+                side(mi * 4 + ni);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    };
+    // Wait until this wave's loads of stage t have landed, `upto` being the last stage requested
+    // so far: vector memory operations retire in order, so at most the DD_LOADS per later stage
+    // may still be outstanding.  (The count is an immediate: one instruction per value.)
+    auto wait_stage = [&](int t, int upto) {
+        switch (upto - t) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never too little
+        }
+    };
+
+    // The barrier of a stage sits BETWEEN its two matrix steps: a wave reaches barrier s with the
+    // fragments of step 1 of stage s in registers, and after it runs step 1 of stage s while it
+    // requests a later stage and reads the fragments of step 0 of stage s+1.  Barrier s certifies
+    // for all waves: the loads of stage s+1 have landed, and every read of stage s-1 is complete
+    // (its last fragments were consumed by matrix instructions before the barrier), so the slot of
+    // stage s-1 is refilled after it with stage s+NSTAGE-1.
+    int requested = 0;
+    const double *ap = a_base, *bp = b_base;        // operands of the next stage to request
+#pragma unroll
+    for (int d = 0; d < NSTAGE - 1; ++d)
+        if (d < n_stages) {
+#pragma unroll
+            for (int i = 0; i < DD_LOADS; ++i) issue_one(ap, bp, d, i);
+            ap += DD_BK;
+            bp += b_stage;
+            requested = d + 1;
+        }
+    wait_stage(0, requested - 1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    double fa0[2], fa1[2], fb0[4], fb1[4];
+    int buf = 0, ibuf = NSTAGE - 1;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) read_one(0, 0, i, fa0, fb0);
+    auto iteration = [&](int s, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
+        const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
+        // step 0 of stage s; the fragments of step 1 are read meanwhile
+        mma_with(fa0, fb0, [&](int i) { if (i < 6) read_one(buf, 1, i, fa1, fb1); });
+        if constexpr (STEADY) {
+            // stages up to s+NSTAGE-2 are requested; s+1 must have landed
+            if constexpr (NSTAGE == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else if constexpr (NSTAGE == 4) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else {
+            const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
+            wait_stage(s + 1, last);
+        }
+        __builtin_amdgcn_s_barrier();   // bare: the fence of __syncthreads() would drain the loads in flight
+        asm volatile("" ::: "memory");
+        // step 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
+        // has left) and the fragment reads of step 0 of stage s+1
+        const bool more = STEADY || s + NSTAGE - 1 < n_stages;
+        mma_with(fa1, fb1, [&](int i) {
+            if (i < DD_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
+            else read_one(nbuf, 0, i - DD_LOADS, fa0, fb0);
+        });
+        ap += DD_BK;
+        bp += b_stage;
+        ibuf = buf;
+        buf = nbuf;
+    };
+    const int steady_end = n_stages - (NSTAGE - 1);   // first s that requests nothing more
+    int s = 0;
+    for (; s < steady_end; ++s) iteration(s, std::true_type());
+    for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
+    mma_with(fa0, fb0, [&](int i) { if (i < 6) read_one(buf, 1, i, fa1, fb1); });
+    mma_with(fa1, fb1, [&](int) {});
+
+    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const int col = col0 + wc * 64 + ni * 16 + li;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
+                double *dst = args.R + (int64_t)row * args.ldr + col;
+                if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                else *dst += acc[mi][ni][v];
+            }
+        }
+}
+
+// Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
+// offsets that fit 32 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
+{
+    if (a.transA || a.transB || !a.vec || !a.vecA) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.M % DD_BM || a.N % DD_BN || a.K % DD_BK || a.kchunk % DD_BK) return false;
+    if (a.lda > (int64_t)((0xFFFFFFFFLL / 8 - 8) / DD_BM) || a.ldb > (int64_t)((0xFFFFFFFFLL / 8 - DD_BN) / DD_BK)) return false;
+    return true;
+}
+
+// Enqueues grid.x x grid.y workgroups of the streamed kernel (ring of 4 stages; the caller has
+// checked identity_f64_dma_eligible and fills the split fields of `a` as for
+// identity_mfma_f64_kernel).
+hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    constexpr int NSTAGE = 4;
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_dma_kernel<NSTAGE>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * DD_STAGE_BYTES);
+    if (granted != hipSuccess) return granted;
+    hipLaunchKernelGGL((identity_mfma_f64_dma_kernel<NSTAGE>), dim3(grid_x, grid_y), dim3(DD_NT), NSTAGE * DD_STAGE_BYTES, s, a);
+    return hipSuccess;
+}
+
+}  // namespace amulet
