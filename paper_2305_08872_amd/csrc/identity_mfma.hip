@@ -308,9 +308,6 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     const int64_t tiles_n = (a.N + L::BN - 1) / L::BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
-    if (granted != hipSuccess) return granted;
     // tiles for at most half of the compute units: split K over several workgroups per tile
     // (at least 128 k each), which add their parts to R with hardware float atomics
     MmlikeArgs b = a;
@@ -374,6 +371,9 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
         return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
             (void)enqueue_identity_dma(b, dma_stages, n, launch_grid.y, s);
         });
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
+    if (granted != hipSuccess) return granted;
     return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
         hipLaunchKernelGGL((identity_mfma_kernel<G, TA, TB>), dim3(n, launch_grid.y), dim3(L::NT), L::LDS_BYTES, s, b);
     });

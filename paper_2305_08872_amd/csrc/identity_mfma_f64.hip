@@ -227,9 +227,6 @@ template <bool TA, bool TB>
 static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_t n_tiles, hipStream_t s)
 {
     constexpr int LDS = DiLayout<TA, TB>::LDS_BYTES;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (granted != hipSuccess) return granted;
     // tiles for at most half of the compute units: split K over several workgroups per tile
     // (at least 128 k each), which add their parts to R with hardware fp64 atomics
     MmlikeArgsF64 b = a;
@@ -290,6 +287,9 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
         return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
             (void)enqueue_identity_f64_dma(b, n, launch_grid.y, s);
         });
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (granted != hipSuccess) return granted;
     return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
         hipLaunchKernelGGL((identity_mfma_f64_kernel<TA, TB>), dim3(n, launch_grid.y), dim3(DI_NT), LDS, s, b);
     });

@@ -135,6 +135,37 @@ int main()
                                                                  tb ? K : N, fp, N, fp, fp, N, nullptr);
                         CHECK(rc == AMULET_ERR_LAUNCH);
                     }
+    // ---- the streamed identity kernels' K-split model over many sizes
+    for (int64_t part = 1; part <= 700; part += 3)
+        for (int64_t K : {16LL, 128LL, 500LL, 1024LL, 4096LL, 100000LL, 2147418111LL})
+            for (int cap : {2, 3}) {
+                static const double rate3[3] = {0.92, 0.985, 1.0}, rate2[2] = {0.93, 1.0};
+                const int sp = amulet::choose_stream_split(part, 32, K, cap, cap == 3 ? rate3 : rate2);
+                CHECK(sp >= 1 && sp <= 8 && (sp == 1 || K / sp >= 128));
+            }
+    // ---- every identity launch plan (vector-ALU shapes, both matrix-core tiles, the streamed
+    // kernel and what it falls back to), fp32 and fp64, refused at the launch
+    const int64_t id_sizes[][3] = {{1, 1, 1}, {300, 700, 200}, {4096, 4096, 4096}, {2048, 2048, 2048}, {1408, 3200, 1104},
+                                   {128, 256, 100000}, {1536, 1536, 4096}, {8192, 8192, 8192}, {2147418111LL, 128, 16}};
+    double *dp = (double *)(uintptr_t)4096;
+    for (auto &sz : id_sizes)
+        for (int layout = 0; layout < 4; ++layout) {
+            const int ta = layout & 1, tb = layout >> 1;
+            const int64_t M = sz[0], N = sz[1], K = sz[2];
+            for (int shape = -1; shape < amulet_shape_count(0); ++shape) {
+                amulet_debug_fail_launches(1);
+                CHECK(amulet_mmlike_f32_general(0, 0, ta, tb, shape, M, N, K, fp, ta ? M : K, fp, tb ? K : N, nullptr, 0,
+                                                nullptr, fp, N, nullptr) == AMULET_ERR_LAUNCH);
+            }
+            for (int task = 0; task <= 3; ++task)
+                for (int shape = -1; shape < amulet_f64_shape_count(); ++shape) {
+                    amulet_debug_fail_launches(1);
+                    CHECK(amulet_mmlike_f64_shape(task, shape, (task + shape + 4) % 4, ta, tb, M, N, K, dp, ta ? M : K, dp,
+                                                  tb ? K : N, dp, N, dp, dp, N, nullptr) == AMULET_ERR_LAUNCH);
+                }
+        }
+    CHECK(amulet_mmlike_f64_shape(1, 6, 0, 0, 0, 8, 8, 8, dp, 8, dp, 8, dp, 8, dp, dp, 8, nullptr) == AMULET_ERR_SHAPE);
+    CHECK(amulet_selected_shape_f64(9, 8, 8, 8) == AMULET_ERR_TASK);
     amulet_debug_fail_launches(0);
     CHECK(amulet_get_deterministic() == 0 || amulet_get_deterministic() == 1);
     amulet_set_deterministic(1);
