@@ -82,7 +82,17 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
     // a dense contraction: matrix cores, 128 x 128 tile, operands streamed HBM -> LDS where the
     // problem allows it (whole tiles, aligned row-major operands; the register-staged kernel
     // otherwise).  The 256 x 256 tile measures 1-3 % behind even at 8192^3; the selector tries all.
-    if (task == TASK_IDENTITY) return IDENTITY_MFMA_DMA3_SHAPE;
+    if (task == TASK_IDENTITY) {
+        // Ring of 3 stages (three workgroups per compute unit, 768 at a time) up to one round of
+        // tiles, where the K-split model has the most to choose from; beyond that the ring whose
+        // rounds the tiles fill better, 4 stages (512 at a time) unless 3 wastes clearly less
+        // (1024 tiles: 145 against 132-146 TFLOP/s, 1280: 145.5 against 142, 1536: 143.5 against 146).
+        const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+        const int64_t round3 = 3 * (int64_t)compute_units(), round4 = 2 * (int64_t)compute_units();
+        if (tiles <= round3) return IDENTITY_MFMA_DMA3_SHAPE;
+        auto waste = [&](int64_t slots) { const int64_t r = (tiles + slots - 1) / slots * slots; return (double)(r - tiles) / (double)r; };
+        return waste(round3) < waste(round4) - 0.05 ? IDENTITY_MFMA_DMA3_SHAPE : IDENTITY_MFMA_DMA4_SHAPE;
+    }
     // ... or, with fewer tiles, when K is long (from 8192 on) and the launcher's K split makes up
     // the number (4096 x 512 x 8192: 31.0 against 29.2 TFLOP/s, 4096 x 512 x 32768: 31.3 against
     // 26.6; at K <= 4096 the 4-wave tile stays ahead, 1536^2 x 4096: 28.5 against 27.2)

@@ -199,30 +199,32 @@ inline int choose_full_split(int64_t part_tiles, int64_t units_per_xcd, int64_t 
     return best_s;
 }
 
-// K split of every tile for the streamed identity kernel (identity_mfma_dma.hip), whose
-// workgroups hold `cap` to a compute unit and run at rate[c - 1] of the unit's full rate with c
-// of them resident (measured: 0.92 / 0.985 / 1.0).  An XCD's `part_tiles` tiles, each launched
-// once per k range, s ranges, are W = part_tiles s workgroups of K / s k each on S = units cap
-// slots.  They run in W / S full rounds of cap K / s each, and the remainder either is the whole
-// launch (spread evenly, c = ceil(W / units) per unit: c (K / s) / rate(c)) or follows full
-// rounds, where the dispatcher refills the units that free first, so that a remainder piles up
-// on a few units instead of spreading: after one full round it costs at least two workgroups'
-// time, after two or more (the units have drifted apart by then) a whole round's (1024 tiles
-// unsplit, 768 + 256 workgroups, took as long as two full rounds; in two ranges, 2 x 768 + 512,
-// as long as three).  Each range also pays its
-// set-up and write-back, in units of one k of a tile at full rate: `ovh_alone`, or `ovh_split` s
-// with atomic adds (fp32: 210 and 175, i.e. 12 and 10 us at 57.5 ns per k; fp64, 115 ns per k: 105
-// and 87).  The s <= 8 with at least 128 k per range and the lowest
-// estimate is returned (1: do not split).  Checked against sweeps of s = 1..8 at 144 ... 1024
-// tiles (K = 1536 ... 4096): the chosen s is the best or within 2 % of the best one measured.
+// K split of every tile for the streamed identity kernels (identity_mfma_dma.hip,
+// identity_mfma_f64_dma.hip), whose workgroups hold `cap` to a compute unit and run at
+// rate[c - 1] of the unit's full rate with c of them resident (fp32, measured: 0.92 / 0.985 /
+// 1.0).  An XCD's `part_tiles` tiles, each launched once per k range, s ranges, are W =
+// part_tiles s workgroups of K / s k each on S = units cap slots.  They run in W / S full rounds
+// of cap K / s each, and the remainder either is the whole launch (spread evenly, c = ceil(W /
+// units) per unit: c (K / s) / rate(c)) or follows full rounds, where the dispatcher refills the
+// units that free first, so that a remainder piles up on a few units instead of spreading: after
+// one full round it costs at least two workgroups' time, after two or more (the units have
+// drifted apart by then) a whole round's (fp32, 1280 tiles: unsplit 123, in 3 ranges = five full
+// rounds 142 TFLOP/s).  Costs are in units of one k of a tile at full rate (fp32 57.5 ns, fp64
+// 115 ns).  A workgroup's set-up and write-back add `ovh_alone` (3 us: 50 / 30); a split launch
+// adds its atomic adds, which the L2s retire at about 0.42 T per second for the whole chip:
+// `atom_per_tile` (16384 adds: 0.68 / 0.34) x tiles x s (measured: 256 tiles in 2 ranges + 20 us,
+// 64 tiles in 8 ranges + 23 us).  The s <= 1024 with at least 128 k per range and the lowest
+// estimate is returned (1: do not split).  Checked against sweeps of s = 1..8 at 64 ... 1536 tiles
+// (K = 512 ... 4096): the chosen s is the best or within 3 % of the best one measured.
 inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int cap, const double *rate,
-                               double ovh_alone = 210.0, double ovh_split = 175.0)
+                               double ovh_alone = 50.0, double atom_per_tile = 0.68)
 {
     if (!k_split_allowed() || part_tiles <= 0 || units <= 0) return 1;
-    const int max_s = K / 128 < 8 ? (int)(K / 128) : 8;
+    const int max_s = K / 128 < 1024 ? (int)(K / 128) : 1024;
     int best_s = 1;
     double best = 0.0;
-    for (int sp = 1; sp <= max_s; ++sp) {
+    // every s up to 16, then a coarser ladder (problems of a tile or two with a very long K)
+    for (int sp = 1; sp <= max_s; sp = sp < 16 ? sp + 1 : sp < 64 ? sp + 8 : sp < 256 ? sp + 32 : sp + 128) {
         const int64_t W = part_tiles * sp, S = units * cap;
         const int64_t q = W / S, r = W % S;
         const double work = (double)K / sp;
@@ -234,7 +236,8 @@ inline int choose_stream_split(int64_t part_tiles, int64_t units, int64_t K, int
             if (q >= 2) left = (double)cap;
             cost += left * work;
         }
-        cost += sp == 1 ? ovh_alone : ovh_split * sp;
+        cost += ovh_alone;
+        if (sp > 1) cost += atom_per_tile * (double)(part_tiles * 8) * sp;
         if (sp == 1 || cost < best * 0.99) { best = cost; best_s = sp; }
     }
     return best_s;

@@ -279,7 +279,10 @@ identity_mfma_kernel(const MmlikeArgs args)
         __syncthreads();
     }
 
-    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
+    // R += acc: eight values of a block at a time are all read before the first is written back
+    // (as "*dst += acc" per element the compiler must keep every store behind the load before it,
+    // and the write-back is a chain of 64 round trips to memory).
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -287,12 +290,26 @@ identity_mfma_kernel(const MmlikeArgs args)
             const int col = col0 + wc * 64 + ni * 32 + li;
             if (col >= N) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < M) {
+            for (int h = 0; h < 2; ++h) {
+                float old[8];
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    const int v = 8 * h + w;
+                    const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                     float *dst = args.R + (int64_t)row * args.ldr + col;
-                    if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                    else *dst += acc[mi][ni][v];
+                    if (ksplit) {
+                        if (row < M) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                    } else {
+                        old[w] = row < M ? *dst : 0.0f;
+                    }
+                }
+                if (!ksplit) {
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        const int v = 8 * h + w;
+                        const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                        if (row < M) args.R[(int64_t)row * args.ldr + col] = old[w] + acc[mi][ni][v];
+                    }
                 }
             }
         }
@@ -308,13 +325,18 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     const int64_t tiles_n = (a.N + L::BN - 1) / L::BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    // tiles for at most half of the compute units: split K over several workgroups per tile
-    // (at least 128 k each), which add their parts to R with hardware float atomics
     MmlikeArgs b = a;
     int splits = 1;
     b.kchunk = a.K;
+    // The streamed kernel where the problem allows it: three workgroups (ring of 3 stages) or
+    // two (4 stages) to a compute unit.
+    bool streamed = false;
+    if constexpr (G == 2 && !TA && !TB) streamed = dma_stages > 0 && identity_dma_eligible(b);
+    // Register-staged kernel, tiles for at most half of the compute units: split K over several
+    // workgroups per tile (at least 128 k each), which add their parts to R with hardware float
+    // atomics
     const int64_t waves = tiles_m * tiles_n * G * G;
-    if (k_split_allowed() && 2 * tiles_m * tiles_n <= compute_units() && a.K >= 256) {
+    if (!streamed && k_split_allowed() && 2 * tiles_m * tiles_n <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;
@@ -325,9 +347,6 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
     dim3 launch_grid((unsigned)grid, (unsigned)splits);
     const int64_t tiles = tiles_m * tiles_n;
-    // The streamed kernel where the problem allows it: three workgroups to a compute unit.
-    bool streamed = false;
-    if constexpr (G == 2 && !TA && !TB) streamed = dma_stages > 0 && identity_dma_eligible(b);
     const int per_unit = streamed ? (dma_stages == 3 ? 3 : 2) : 4;
     if (streamed && splits == 1 && tiles <= 2 * per_unit * (int64_t)compute_units()) {
         // at most two rounds of tiles: every tile once per k range (choose_stream_split)

@@ -239,20 +239,38 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     mma_with(fa0, fb0, [&](int i) { if (i < 10) read_one(buf, 1, i, fa1, fb1); });
     mma_with(fa1, fb1, [&](int) {});
 
-    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
+    // R += acc: the 32 values of a row block are all read before the first is written back (as
+    // "*dst += acc" per element the compiler must keep every store behind the load before it and
+    // the write-back is a chain of 64 round trips to memory, 15 us of a tile).
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi) {
+        float *dst[2][16];
+        float old[2][16];
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const int col = col0 + wc * 64 + ni * 32 + li;
+        for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
+                const int col = col0 + wc * 64 + ni * 32 + li;
                 const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                float *dst = args.R + (int64_t)row * args.ldr + col;
-                if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                else *dst += acc[mi][ni][v];
+                dst[ni][v] = args.R + (int64_t)row * args.ldr + col;
             }
+        if (ksplit) {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) unsafeAtomicAdd(dst[ni][v], acc[mi][ni][v]);
+        } else {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) old[ni][v] = *dst[ni][v];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) *dst[ni][v] = old[ni][v] + acc[mi][ni][v];
         }
+    }
 }
 
 // Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte

@@ -204,21 +204,39 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
         __syncthreads();
     }
 
-    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block
+    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc: the 8 values
+    // of two blocks are all read before the first is written back (as "*dst += acc" per element
+    // the write-back is a chain of 32 round trips to memory).
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const int col = col0 + wc * 64 + ni * 16 + li;
-            if (col >= N) continue;
+        for (int np = 0; np < 2; ++np) {
+            double old[2][4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
-                if (row < M) {
+            for (int nq = 0; nq < 2; ++nq)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ni = 2 * np + nq;
+                    const int col = col0 + wc * 64 + ni * 16 + li;
+                    const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
                     double *dst = args.R + (int64_t)row * args.ldr + col;
-                    if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                    else *dst += acc[mi][ni][v];
+                    const bool live = row < M && col < N;
+                    if (ksplit) {
+                        if (live) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                    } else {
+                        old[nq][v] = live ? *dst : 0.0;
+                    }
                 }
+            if (!ksplit) {
+#pragma unroll
+                for (int nq = 0; nq < 2; ++nq)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int ni = 2 * np + nq;
+                        const int col = col0 + wc * 64 + ni * 16 + li;
+                        const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
+                        if (row < M && col < N) args.R[(int64_t)row * args.ldr + col] = old[nq][v] + acc[mi][ni][v];
+                    }
             }
         }
 }
@@ -227,13 +245,18 @@ template <bool TA, bool TB>
 static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_t n_tiles, hipStream_t s)
 {
     constexpr int LDS = DiLayout<TA, TB>::LDS_BYTES;
-    // tiles for at most half of the compute units: split K over several workgroups per tile
-    // (at least 128 k each), which add their parts to R with hardware fp64 atomics
     MmlikeArgsF64 b = a;
     int splits = 1;
     b.kchunk = a.K;
+    // The streamed kernel where the problem allows it (row-major operands, whole tiles): two
+    // workgroups to a compute unit.
+    bool streamed = false;
+    if constexpr (!TA && !TB) streamed = identity_f64_dma_eligible(b);
+    // Register-staged kernel, tiles for at most half of the compute units: split K over several
+    // workgroups per tile (at least 128 k each), which add their parts to R with hardware fp64
+    // atomics
     const int64_t waves = (int64_t)n_tiles * (DI_NT / 64);
-    if (k_split_allowed() && 2 * n_tiles <= compute_units() && a.K >= 256) {
+    if (!streamed && k_split_allowed() && 2 * n_tiles <= compute_units() && a.K >= 256) {
         int64_t want = (2048 + waves - 1) / waves;
         if (want > a.K / 128) want = a.K / 128;
         if (want > 1024) want = 1024;
@@ -243,14 +266,11 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     }
     b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
     dim3 launch_grid(grid, (unsigned)splits);
-    // The streamed kernel where the problem allows it (row-major operands, whole tiles): two
-    // workgroups to a compute unit; with at most two rounds of tiles every tile is launched once
-    // per k range (choose_stream_split in amulet_internal.h).
-    bool streamed = false;
-    if constexpr (!TA && !TB) streamed = identity_f64_dma_eligible(b);
+    // Streamed kernel: with at most two rounds of tiles every tile is launched once per k range
+    // (choose_stream_split in amulet_internal.h).
     if (streamed && splits == 1 && n_tiles <= 4 * (int64_t)compute_units()) {
         static const double rate2[2] = {0.93, 1.0};
-        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, 2, rate2, 105.0, 87.0);
+        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, 2, rate2, 30.0, 0.34);
         if (sp > 1) {
             const int64_t chunk = ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK;
             b.kchunk = (int)chunk;

@@ -224,20 +224,33 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     mma_with(fa0, fb0, [&](int i) { if (i < 6) read_one(buf, 1, i, fa1, fb1); });
     mma_with(fa1, fb1, [&](int) {});
 
-    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block
+    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc: the 16 values
+    // of a row of blocks are all read before the first is written back (as "*dst += acc" per
+    // element the compiler must keep every store behind the load before it, a chain of 32 round
+    // trips to memory).
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi) {
+        double *dst[4];
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const int col = col0 + wc * 64 + ni * 16 + li;
+        for (int v = 0; v < 4; ++v)
+            dst[v] = args.R + (int64_t)(row0 + wr * 32 + mi * 16 + 4 * v + lh) * args.ldr + col0 + wc * 64 + li;
+        if (ksplit) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
-                double *dst = args.R + (int64_t)row * args.ldr + col;
-                if (ksplit) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                else *dst += acc[mi][ni][v];
-            }
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) unsafeAtomicAdd(dst[v] + ni * 16, acc[mi][ni][v]);
+        } else {
+            double old[4][4];
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) old[ni][v] = dst[v][ni * 16];
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dst[v][ni * 16] = old[ni][v] + acc[mi][ni][v];
         }
+    }
 }
 
 // Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte

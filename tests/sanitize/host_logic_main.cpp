@@ -141,7 +141,7 @@ int main()
             for (int cap : {2, 3}) {
                 static const double rate3[3] = {0.92, 0.985, 1.0}, rate2[2] = {0.93, 1.0};
                 const int sp = amulet::choose_stream_split(part, 32, K, cap, cap == 3 ? rate3 : rate2);
-                CHECK(sp >= 1 && sp <= 8 && (sp == 1 || K / sp >= 128));
+                CHECK(sp >= 1 && sp <= 1024 && (sp == 1 || K / sp >= 128));
             }
     // ---- every identity launch plan (vector-ALU shapes, both matrix-core tiles, the streamed
     // kernel and what it falls back to), fp32 and fp64, refused at the launch
