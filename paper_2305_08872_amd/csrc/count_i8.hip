@@ -263,7 +263,10 @@ count_i8_mfma_kernel(const CountArgs args)
         __syncthreads();
     }
 
-    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block
+    // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
+    // R += acc: eight values of a block at a time are all read before the first is written back
+    // (as "*dst += acc" per element the compiler must keep every store behind the load before it,
+    // and the write-back is a chain of serial round trips to memory).
 #pragma unroll
     for (int mi = 0; mi < MB; ++mi)
 #pragma unroll
@@ -271,12 +274,26 @@ count_i8_mfma_kernel(const CountArgs args)
             const int col = col0 + (wc * NB + ni) * 32 + li;
             if (col >= N) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + (wr * MB + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < M) {
+            for (int h = 0; h < 2; ++h) {
+                uint32_t old[8];
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    const int v = 8 * h + w;
+                    const int row = row0 + (wr * MB + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                     int32_t *dst = args.R + (int64_t)row * args.ldr + col;
-                    if (ksplit) atomicAdd(dst, acc[mi][ni][v]);
-                    else *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc[mi][ni][v]);
+                    if (ksplit) {
+                        if (row < M) atomicAdd(dst, acc[mi][ni][v]);
+                    } else {
+                        old[w] = row < M ? (uint32_t)*dst : 0u;
+                    }
+                }
+                if (!ksplit) {
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        const int v = 8 * h + w;
+                        const int row = row0 + (wr * MB + mi) * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                        if (row < M) args.R[(int64_t)row * args.ldr + col] = (int32_t)(old[w] + (uint32_t)acc[mi][ni][v]);
+                    }
                 }
             }
         }
