@@ -431,6 +431,10 @@ def config_leg(name, args, am, torch, np, wl) -> dict:
     ms_guess = {"cfg0_discount_256": 0.02, "cfg1_boost_2048": 0.6, "cfg2_identity_4096": 1.0,
                 "cfg3_count_i8_8192x8192x4096": 0.25}.get(name, 5.0)
     sub.workload, sub.steps, sub.probe = name, max(10, min(args.steps, 20)), False
+    # the legs run the built-in shape choices (the headline is the run that times amulet_tune): a
+    # tune of a 0.2 ms kernel right after another workload has picked a shape that then ran 5 %
+    # slower than the default, and a leg should measure the kernel, not that noise
+    sub.no_tune = True
     sub.warmup = max(3, args.warmup, min(400, int(100.0 / ms_guess)))
     M = wl.CONFIGS[name]["M"]
     sub.cpu_rows = min(M, 64) if wl.CONFIGS[name]["task"] != "count_i8" else 16   # count_i8 samples 4 x this

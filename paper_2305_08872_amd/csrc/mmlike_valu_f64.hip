@@ -447,6 +447,18 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     }
 
     // ---- write-back: R += acc ------------------------------------------------------------
+    // The aligned 16-byte pieces of R are all read before the first sum is stored (one
+    // read-modify-write after the other is a chain of round trips to memory: the compiler must
+    // keep every store behind the load before it).
+    d2 old[D_TM];
+    bool fast[D_TM];
+#pragma unroll
+    for (int r = 0; r < D_TM; ++r) {
+        const int col = col0 + lane * 2;
+        fast[r] = !ksplit && VEC && row0 + r < M && col + 1 < N;
+        old[r] = d2{0.0, 0.0};
+        if (fast[r]) old[r] = *(const d2 *)(args.R + (int64_t)(row0 + r) * args.ldr + col);
+    }
 #pragma unroll
     for (int r = 0; r < D_TM; ++r) {
         const int row = row0 + r;
@@ -458,8 +470,8 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
             // several workgroups own this tile: hardware fp64 adds, in whatever order
             if (col + 0 < N) unsafeAtomicAdd(dst_row + col + 0, v0);
             if (col + 1 < N) unsafeAtomicAdd(dst_row + col + 1, v1);
-        } else if (VEC && col + 1 < N) {
-            d2 o = *(d2 *)(dst_row + col);
+        } else if (fast[r]) {
+            d2 o = old[r];
             o.x += v0; o.y += v1;
             *(d2 *)(dst_row + col) = o;
         } else if (col + 1 < N) {

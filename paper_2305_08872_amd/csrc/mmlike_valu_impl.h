@@ -595,6 +595,20 @@ mmlike_valu_kernel(const MmlikeArgs args)
     flush();
 
     // ---- write-back: R += acc, once per tile ---------------------------------
+    // The aligned 16-byte pieces of R are all read before the first sum is stored: as one
+    // read-modify-write after the other the compiler must keep every store behind the load before
+    // it (the pointers might alias), a chain of TM x NG round trips to memory.
+    f4 old[TM][NG];
+    bool fast[TM][NG];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int col = col0 + g * 256 + lane * 4;
+            fast[r][g] = !ksplit && VEC && row0 + r < M && col + 3 < N;
+            old[r][g] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (fast[r][g]) old[r][g] = *(const f4 *)(args.R + (int64_t)(row0 + r) * args.ldr + col);
+        }
 #pragma unroll
     for (int r = 0; r < TM; ++r) {
         const int row = row0 + r;
@@ -612,8 +626,8 @@ mmlike_valu_kernel(const MmlikeArgs args)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
                     if (col + c < N) unsafeAtomicAdd(dst_row + col + c, v[c]);
-            } else if (VEC && col + 3 < N) {
-                f4 o = *(f4 *)(dst_row + col);
+            } else if (fast[r][g]) {
+                f4 o = old[r][g];
                 o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
                 *(f4 *)(dst_row + col) = o;
             } else if (col + 3 < N) {
