@@ -1043,11 +1043,16 @@ int amulet_tune(int task, int64_t M, int64_t N, int64_t K, void *stream)
         // Bring the device to its loaded clocks first: launches right after idle run up to 10 %
         // faster than the same ones a few milliseconds later, which would favour whichever
         // candidate is tried first.
+        // (30 ms of the default shape; 150 ms for the matrix-core tasks, whose clocks keep
+        // settling for longer: the persistent join-count kernel measures 0.245 ms cold and 0.223
+        // warm, which decided a tune against it)
         const int dflt = default_shape(task, M, N, K);
-        for (int i = 0, spent = 0; i < 64 && spent < 30; ++i) {
+        const float warm_ms = (i8 || task == TASK_IDENTITY) ? 150.0f : 30.0f;
+        float spent = 0.0f;
+        for (int i = 0; i < 4096 && spent < warm_ms; ++i) {
             const float ms = trial_span_ms(&c, dflt, 1);
             if (ms < 0.0f) break;
-            spent += (int)ms + 1;
+            spent += ms > 0.02f ? ms : 0.02f;
         }
         int chosen;
         if (i8) {
