@@ -413,3 +413,23 @@ def test_f64_identity_streamed_kernel_on_whole_tiles(am):
     am.amulet_mmlike_f64(0, dev(A), dev(B), None, None, dR)
     torch.cuda.synchronize()
     assert np.array_equal(dR.cpu().numpy(), R_ref)
+
+
+@pytest.mark.parametrize("task,M,N,K", [(1, 64, 128, 20000), (3, 770, 3050, 1100), (0, 1536, 1536, 2048), (0, 300, 300, 4096)])
+def test_f64_deterministic_mode_gives_the_same_bits_twice(am, task, M, N, K):
+    """fp64 sizes whose default launch splits K (few tiles, a nearly empty last round, the streamed
+    and the register-staged identity kernel): with the deterministic mode on, two runs agree bit
+    for bit and match the oracle; so does the default mode, to the tolerance."""
+    A, B, th, dis, R_in = make_case(0, M, N, K, 9980 + task)
+    R_ref, ab, _ = oracle.mmlike_f64_general(task, A, B, th if task else None, dis if task == 1 else None, R_in)
+    was = am.amulet_get_deterministic()
+    try:
+        am.amulet_set_deterministic(True)
+        R1 = run(am, task, 0, dev(A), dev(B), th, dis, dev(R_in))
+        R2 = run(am, task, 0, dev(A), dev(B), th, dis, dev(R_in))
+    finally:
+        am.amulet_set_deterministic(was)
+    assert np.array_equal(R1, R2)
+    check(R1, R_ref, ab, R_in, task, "f64 deterministic mode, task %d" % task)
+    R3 = run(am, task, 0, dev(A), dev(B), th, dis, dev(R_in))
+    check(R3, R_ref, ab, R_in, task, "f64 default mode, task %d" % task)

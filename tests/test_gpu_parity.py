@@ -615,7 +615,8 @@ def test_refused_launch_leaves_R_untouched_and_nothing_cached(am):
     assert_parity_f32(dR.cpu().numpy()[rows], R_ref, ab, np.full((len(rows), N), 3.0, np.float32), what="after the seam")
 
 
-@pytest.mark.parametrize("task,M,N,K", [(1, 256, 256, 256), (2, 64, 64, 20000), (1, 770, 6100, 1100), (0, 300, 300, 4096)])
+@pytest.mark.parametrize("task,M,N,K", [(1, 256, 256, 256), (2, 64, 64, 20000), (1, 770, 6100, 1100), (0, 300, 300, 4096),
+                                        (0, 1536, 1536, 2048)])   # the last: whole tiles, the streamed identity kernel
 def test_deterministic_mode_gives_the_same_bits_twice(am, task, M, N, K):
     """Sizes whose default launch splits K (few tiles; a nearly empty last round): with the
     deterministic mode on, two runs agree bit for bit and match the oracle to the tolerance."""
