@@ -351,6 +351,23 @@ int amulet_count_i8_general(int trans_a, int trans_b, int64_t M, int64_t N, int6
                             void *stream);
 
 /*
+ * amulet_count_i8 with in-flight adaptive execution (Sec. 4.4): the matrix-core kernels of
+ * the join count are tried on disjoint slabs of rows of the caller's R (the shape a plain
+ * call would use first, then the others from the widest tile down; about two tiles per
+ * compute unit each; only rows of the first half of R), time per row decides, the rest of R
+ * runs with the winner, which is cached for the size bucket.  The result is the complete
+ * count, bit for bit that of amulet_count_i8.  Allocates two events and blocks the host
+ * while trials run; problems too small for two slabs (below about four tiles per compute
+ * unit: 8192 x 8192 outputs and less) run whole with the built-in or cached shape.
+ * `chosen_shape`, `n_trials` may be NULL.  Same arguments and error codes as amulet_count_i8.
+ */
+int amulet_count_i8_adaptive(int64_t M, int64_t N, int64_t K,
+                             const int8_t *A, int64_t lda,
+                             const int8_t *B, int64_t ldb,
+                             int32_t *R, int64_t ldr,
+                             void *stream, int *chosen_shape, int *n_trials);
+
+/*
  * amulet_count_i8_general for callers that cannot allocate and have no
  * workspace to lend: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments without the workspace, same

@@ -69,6 +69,9 @@ def load_library():
                                                        vp, vp, i64, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.amulet_count_i8.restype = i32
     lib.amulet_count_i8.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.amulet_count_i8_adaptive.restype = i32
+    lib.amulet_count_i8_adaptive.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ctypes.POINTER(ctypes.c_int),
+                                             ctypes.POINTER(ctypes.c_int)]
     lib.amulet_pitch_collides.restype = i32
     lib.amulet_pitch_collides.argtypes = [i64, i32]
     lib.amulet_packed_ld.restype = i64
@@ -385,6 +388,22 @@ def amulet_count_i8(A, B, R, stream=None):
         raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
     _check(lib.amulet_count_i8(M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
            "amulet_count_i8")
+
+
+def amulet_count_i8_adaptive(A, B, R, stream=None):
+    """amulet_count_i8 with the paper's in-flight adaptive execution: the matrix-core kernels are
+    tried on slabs of rows of R, the rest runs with the fastest.  Returns (chosen shape id, number
+    of trial slabs)."""
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.int8", "A")
+    pb, K2, N, ldb = _mat(B, "torch.int8", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.int32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    chosen, trials = ctypes.c_int(-1), ctypes.c_int(0)
+    _check(lib.amulet_count_i8_adaptive(M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream), ctypes.byref(chosen),
+                                        ctypes.byref(trials)), "amulet_count_i8_adaptive")
+    return chosen.value, trials.value
 
 
 def amulet_count_i8_workspace_bytes(trans_a: bool, trans_b: bool, M: int, N: int, K: int) -> int:

@@ -755,6 +755,73 @@ int amulet_count_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t ld
                      stream);
 }
 
+// In-flight adaptive execution for the join count (paper Sec. 4.4): the candidates here are
+// not points of a two-parameter grid but the matrix-core kernels themselves (register-staged and
+// streamed, 128- to 256-row tiles, one tile per workgroup or persistent), so the walk is flat:
+// the shape a plain call would use first, then the others from the widest tile down, each on a
+// slab of rows of the caller's R of about two tiles per compute unit, as long as untested rows
+// are left in the first half of R; time per row decides, the rest runs with the winner.
+int amulet_count_i8_adaptive(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
+                             int64_t ldb, int32_t *R, int64_t ldr, void *stream, int *chosen_shape, int *n_trials)
+{
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    int best = lookup_shape(AMULET_TASK_COUNT_I8, M, N, K);
+    if (chosen_shape) *chosen_shape = best;
+    if (n_trials) *n_trials = 0;
+    if (rc == 1) return AMULET_OK;
+    // tile height and width of each matrix-core shape (shape 0, the plain loop, is no candidate)
+    static const int tile_rows[COUNT_SHAPE_COUNT] = {0, 128, 256, 128, 128, 256, 128, 256, 256};
+    static const int tile_cols[COUNT_SHAPE_COUNT] = {0, 128, 256, 256, 128, 256, 256, 256, 256};
+    auto slab_rows = [&](int shape) {
+        const int64_t tiles_n = (N + tile_cols[shape] - 1) / tile_cols[shape];
+        int64_t row_tiles = (2 * (int64_t)compute_units() + tiles_n - 1) / tiles_n;
+        if (row_tiles < 1) row_tiles = 1;
+        return row_tiles * tile_rows[shape];
+    };
+    int order[COUNT_SHAPE_COUNT], n_order = 0;
+    order[n_order++] = best;
+    for (int sidx = COUNT_SHAPE_COUNT - 1; sidx >= 1; --sidx)
+        if (sidx != best) order[n_order++] = sidx;
+    const int64_t budget = M / 2;
+    int64_t next_row = 0;
+    int trials = 0, status = AMULET_OK;
+    double best_score = 1e300;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    // a task too small to spare the default shape's slab and one more runs whole with that shape
+    const bool can_test = best >= 1 && slab_rows(best) + slab_rows(order[1]) <= budget;
+    if (can_test && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
+        for (int i = 0; i < n_order && status == AMULET_OK; ++i) {
+            const int shape = order[i];
+            const int64_t rows = slab_rows(shape);
+            if (next_row + rows > budget) continue;   // no rows left for this one: a narrower tile may still fit
+            (void)hipEventRecord(e0, (hipStream_t)stream);
+            const int r = run_count(shape, rows, N, K, A + next_row * lda, lda, B, ldb, R + next_row * ldr, ldr, stream);
+            (void)hipEventRecord(e1, (hipStream_t)stream);
+            if (r != AMULET_OK || hipEventSynchronize(e1) != hipSuccess) { status = AMULET_ERR_LAUNCH; break; }
+            float ms = 0.0f;
+            (void)hipEventElapsedTime(&ms, e0, e1);
+            next_row += rows;
+            trials += 1;
+            const double sc = (double)ms / (double)rows;
+            if (sc < best_score) { best_score = sc; best = shape; }
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (status != AMULET_OK) return status;
+    int out = AMULET_OK;
+    if (next_row < M)
+        out = run_count(best, M - next_row, N, K, A + next_row * lda, lda, B, ldb, R + next_row * ldr, ldr, stream);
+    if (out == AMULET_OK && trials > 1) {
+        std::lock_guard<std::mutex> lock(g_sel_mutex);
+        g_selected[sel_key(AMULET_TASK_COUNT_I8, M, N, K)] = best;
+    }
+    if (chosen_shape) *chosen_shape = best;
+    if (n_trials) *n_trials = trials;
+    return out;
+}
+
 // Row pitch of a transposed copy in the workspace: whole 128-byte lines (so the streamed kernel
 // takes it), never a multiple of 4 KiB.
 static int64_t i8_copy_ld(int64_t cols) { return amulet_packed_ld(cols, 1); }

@@ -119,6 +119,9 @@ int main()
     CHECK(amulet_count_i8(2, 3, 4, bp, 3, bp, 3, ip, 3, nullptr) == AMULET_ERR_LD);
     CHECK(amulet_count_i8_static(0, 0, 8191, 8191, 4095, bp, 4095, bp, 8191, ip, 8191, nullptr) == AMULET_ERR_WORKSPACE);
     CHECK(amulet_tune(55, 8, 8, 8, nullptr) == AMULET_ERR_TASK);
+    CHECK(amulet_count_i8_adaptive(2, 3, 4, bp, 3, bp, 3, ip, 3, nullptr, nullptr, nullptr) == AMULET_ERR_LD);
+    amulet_debug_fail_launches(1);
+    CHECK(amulet_count_i8_adaptive(12288, 16384, 128, bp, 128, bp, 16384, ip, 16384, nullptr, nullptr, nullptr) == AMULET_ERR_LAUNCH);
 
     // ---- every vector-ALU launch plan, refused at the launch: shapes x tasks x forms x layouts x sizes
     const int64_t sizes[][3] = {{1, 1, 1}, {300, 700, 200}, {8192, 8192, 8192}, {770, 6100, 1100}, {64, 64, 100000},

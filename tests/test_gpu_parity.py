@@ -283,6 +283,45 @@ def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64 + 7 * M)
 
 
+def test_count_i8_adaptive_execution_trials_contribute_to_the_result(am):
+    """In-flight adaptive execution of the join count: slabs of rows of the caller's R are computed
+    by different matrix-core kernels, the rest by the fastest; the whole R must be the exact count
+    (sampled rows and columns against the oracle, whole-matrix row and column checksums).  The
+    winner is cached; a problem too small for two slabs runs whole, without trials."""
+    M, N, K = 12288, 16384, 128
+    g = np.random.Generator(np.random.PCG64(391))
+    A = g.integers(-128, 128, (M, K)).astype(np.int8)
+    B = g.integers(-128, 128, (K, N)).astype(np.int8)
+    dR = torch.full((M, N), 7, dtype=torch.int32, device="cuda")
+    am.amulet_clear_selections()
+    chosen, trials = am.amulet_count_i8_adaptive(dev(A), dev(B), dR)
+    torch.cuda.synchronize()
+    print("i8 adaptive chose", chosen, am.amulet_shape_name(am.AMULET_TASK_COUNT_I8, chosen), "after", trials, "trials", flush=True)
+    assert 1 <= chosen < am.amulet_shape_count(am.AMULET_TASK_COUNT_I8) and trials >= 3
+    assert am.amulet_selected_shape(am.AMULET_TASK_COUNT_I8, M, N, K) == chosen
+    R = dR.cpu().numpy()
+    rows = np.sort(g.choice(M, 48, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 24, replace=False)); cols[0], cols[-1] = 0, N - 1
+    R_ref, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B, np.full((len(rows), N), 7, np.int32))
+    assert np.array_equal(R[rows], R_ref)
+    R_ref, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]), np.full((M, len(cols)), 7, np.int32))
+    assert np.array_equal(R[:, cols], R_ref)
+    A64, B64 = A.astype(np.int64), B.astype(np.int64)
+    assert np.array_equal(R.astype(np.int64).sum(1), A64 @ B64.sum(1) + 7 * N)
+    assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64 + 7 * M)
+    del R, dR
+    am.amulet_clear_selections()
+    # too small for two slabs: the whole count with the built-in shape, no trials
+    A, B = A[:300, :100], B[:100, :500]
+    R_in = g.integers(-1000, 1000, (300, 500)).astype(np.int32)
+    dR = dev(R_in)
+    chosen, trials = am.amulet_count_i8_adaptive(dev(A), dev(B), dR)
+    torch.cuda.synchronize()
+    assert trials == 0
+    R_ref, _ = oracle.count_i8(np.ascontiguousarray(A), np.ascontiguousarray(B), R_in)
+    assert np.array_equal(dR.cpu().numpy(), R_ref)
+
+
 @pytest.mark.parametrize("tA,tB", [(True, False), (False, True), (True, True), (False, False)])
 def test_count_i8_transposed_operands(am, tA, tB):
     """A stored K x M and / or B stored N x K: transposed into the lent workspace, then the
