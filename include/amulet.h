@@ -210,6 +210,13 @@ int amulet_mmlike_f64_shape(int task, int shape, int thres_form, int trans_a, in
                             void *stream);
 
 /*
+ * (All adaptive calls: a trial's end is waited for on the host before the next is chosen,
+ * which costs the GPU some tens of microseconds of idling per trial; when the first trial
+ * shows the whole task to be shorter than 3 ms, no further trial is run and the task goes on
+ * with the shape just tried.  The environment variable AMULET_ADAPTIVE_MIN_TASK_MS overrides
+ * the 3; 0 switches the rule off.  Candidates whose order is fixed in advance -- the identity
+ * task's and the join count's -- are enqueued back to back and waited for once.)
+ *
  * In-flight adaptive execution (Sec. 4.4-4.6) in the paper's own element type: as
  * amulet_mmlike_f32_adaptive_general, on the fp64 shape grid.  Trials are disjoint row
  * slabs of the caller's R (the shape a plain call would use first, then the k axis,

@@ -83,13 +83,15 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
     // problem allows it (whole tiles, aligned row-major operands; the register-staged kernel
     // otherwise).  The 256 x 256 tile measures 1-3 % behind even at 8192^3; the selector tries all.
     if (task == TASK_IDENTITY) {
-        // Ring of 3 stages (three workgroups per compute unit, 768 at a time) up to one round of
-        // tiles, where the K-split model has the most to choose from; beyond that the ring whose
-        // rounds the tiles fill better, 4 stages (512 at a time) unless 3 wastes clearly less
-        // (1024 tiles: 145 against 132-146 TFLOP/s, 1280: 145.5 against 142, 1536: 143.5 against 146).
+        // Ring of 3 stages (three workgroups per compute unit, 768 at a time) except between one
+        // and three rounds of the ring of 4 (512 at a time), where whole rounds matter and the
+        // ring of 4 fills its rounds better unless 3 wastes clearly less (1024 tiles: 145 against
+        // 132-146 TFLOP/s, 1280: 145.5 against 142, 1536: 143.5 against 146).  With more rounds
+        // the workgroups' finishing times spread and the fuller unit wins (2048 tiles: 145 against
+        // 141, 4096: 149 against 147, 8192 tiles x K = 512: 134 against 128).
         const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
         const int64_t round3 = 3 * (int64_t)compute_units(), round4 = 2 * (int64_t)compute_units();
-        if (tiles <= round3) return IDENTITY_MFMA_DMA3_SHAPE;
+        if (tiles <= round3 || tiles > 3 * round4) return IDENTITY_MFMA_DMA3_SHAPE;
         auto waste = [&](int64_t slots) { const int64_t r = (tiles + slots - 1) / slots * slots; return (double)(r - tiles) / (double)r; };
         return waste(round3) < waste(round4) - 0.05 ? IDENTITY_MFMA_DMA3_SHAPE : IDENTITY_MFMA_DMA4_SHAPE;
     }
@@ -310,7 +312,56 @@ static double valu_trial_score(int i0, int i1, void *ctx)
 // ---- in-flight adaptive execution (paper Sec. 4.4-4.6) ---------------------------
 // Trials run on disjoint row slabs of the caller's own task, so every trial also
 // contributes its part of R; whatever is left runs with the winner.
+// Estimated duration of a whole task below which an adaptive call stops after its first trial
+// (milliseconds; the environment variable AMULET_ADAPTIVE_MIN_TASK_MS overrides it, 0 = never stop).
+static double adaptive_min_task_ms()
+{
+    if (const char *e = getenv("AMULET_ADAPTIVE_MIN_TASK_MS")) return atof(e);
+    return 3.0;
+}
+
+// Trials whose order does not depend on each other's outcome (a flat list of candidates) are
+// enqueued back to back with an event between them and waited for once: one host round trip
+// for all of them instead of one each.
+struct BatchedTrials {
+    enum { MAX = 9 };
+    hipEvent_t ev[MAX + 1];
+    int shape[MAX];
+    int64_t rows[MAX];
+    int n;
+    bool ok;
+    BatchedTrials() : n(0), ok(true) { for (auto &e : ev) e = nullptr; }
+    ~BatchedTrials() { for (auto &e : ev) if (e) (void)hipEventDestroy(e); }
+    bool begin(hipStream_t s)
+    {
+        for (auto &e : ev)
+            if (hipEventCreate(&e) != hipSuccess) { e = nullptr; ok = false; return false; }
+        return hipEventRecord(ev[0], s) == hipSuccess;
+    }
+    // call after the trial's work was enqueued
+    void mark(int shape_id, int64_t n_rows, hipStream_t s)
+    {
+        shape[n] = shape_id; rows[n] = n_rows; ++n;
+        if (hipEventRecord(ev[n], s) != hipSuccess) ok = false;
+    }
+    // waits for the last trial; returns the index of the fastest per row, or -1
+    int finish()
+    {
+        if (!ok || n == 0 || hipEventSynchronize(ev[n]) != hipSuccess) return -1;
+        int best = -1;
+        double best_sc = 1e300;
+        for (int i = 0; i < n; ++i) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) return -1;
+            const double sc = (double)ms / (double)rows[i];
+            if (sc < best_sc) { best_sc = sc; best = i; }
+        }
+        return best;
+    }
+};
+
 struct AdaptiveCtx {
+    bool short_task;      // the first trial showed a task too short to be worth more trials
     MmlikeCall call;      // the whole task
     int64_t next_row;     // first row no trial has computed yet
     int64_t budget_rows;  // trials may use rows below this
@@ -346,9 +397,9 @@ static int64_t trial_rows(const MmlikeCall &c, int shape)
             want_tiles /= sp > 1 ? sp : 1;
         }
     } else {
-        // (matrix-core tiles: a compute unit is at full rate with three resident 128 x 128 tiles,
-        // and holds one 256 x 256 tile at a time, so three tiles resp. one tile per unit is enough)
-        want_tiles = shape == IDENTITY_MFMA_BIG_SHAPE ? 256 : 768;
+        // (matrix-core tiles: one round of what a compute unit holds: three 128 x 128 tiles of the
+        // streamed kernel with a ring of 3 stages, two with a ring of 4, one 256 x 256 tile)
+        want_tiles = shape == IDENTITY_MFMA_BIG_SHAPE ? 256 : shape == IDENTITY_MFMA_DMA4_SHAPE ? 512 : 768;
     }
     const int64_t tiles_n = (c.N + tile_cols - 1) / tile_cols;
     int64_t row_tiles = (want_tiles + tiles_n - 1) / tiles_n;
@@ -372,6 +423,7 @@ static double adaptive_trial(AdaptiveCtx *x, int shape)
 {
     const int64_t rows = trial_rows(x->call, shape);
     if (x->status != AMULET_OK || x->next_row + rows > x->budget_rows) return 1e300;  // no data left to test on
+    if (x->short_task) return 1e300;   // (see below)
     (void)hipEventRecord(x->e0, x->stream);
     const int rc = run_rows(x->call, shape, x->next_row, rows, x->stream);
     (void)hipEventRecord(x->e1, x->stream);
@@ -385,6 +437,11 @@ static double adaptive_trial(AdaptiveCtx *x, int shape)
     (void)hipEventElapsedTime(&ms, x->e0, x->e1);
     const double sc = (double)ms / (double)rows;   // the paper's score: execution time per unit of work
     if (sc < x->best_score) { x->best_score = sc; x->best_shape = shape; }
+    // Every trial costs a host round trip (its end is waited for before the next is chosen):
+    // some tens of microseconds in which the GPU idles.  A task that the first trial shows to
+    // be a few milliseconds in all is not worth more of them (16384 x 8192 x 1024 identity,
+    // 1.9 ms: three trials cost 13 %); it runs on with the shape just tried.
+    if (x->trials == 1 && sc * (double)x->call.M < adaptive_min_task_ms()) x->short_task = true;
     return sc;
 }
 
@@ -537,6 +594,7 @@ int amulet_selected_shape_f64(int task, int64_t M, int64_t N, int64_t K)
 // In-flight adaptive execution in fp64 (paper Sec. 4.4-4.6 in the paper's own element type):
 // the scheme of amulet_mmlike_f32_adaptive_general on the fp64 shape grid.
 struct AdaptiveF64 {
+    bool short_task;
     F64Call call;
     int64_t next_row, budget_rows;
     hipStream_t stream;
@@ -567,7 +625,7 @@ static double adaptive_f64_score(int i0, int i1, void *ctx)
     if (x->score_of[shape] >= 0.0) return x->score_of[shape];   // a shape is tried once
     const int64_t rows = trial_rows_f64(x->call, shape);
     double sc = 1e300;   // no rows left to test on: infinitely slow, which ends the walk
-    if (x->status == AMULET_OK && x->next_row + rows <= x->budget_rows) {
+    if (x->status == AMULET_OK && x->next_row + rows <= x->budget_rows && !x->short_task) {
         (void)hipEventRecord(x->e0, x->stream);
         const int rc = run_f64_rows(x->call, shape, x->next_row, rows, x->stream);
         (void)hipEventRecord(x->e1, x->stream);
@@ -580,6 +638,8 @@ static double adaptive_f64_score(int i0, int i1, void *ctx)
             (void)hipEventElapsedTime(&ms, x->e0, x->e1);
             sc = (double)ms / (double)rows;   // the paper's score: execution time per unit of work
             if (sc < x->best_score) { x->best_score = sc; x->best_shape = shape; }
+            // (a task of a few milliseconds is not worth more host round trips: see adaptive_trial)
+            if (x->trials == 1 && sc * (double)x->call.M < adaptive_min_task_ms()) x->short_task = true;
         }
     }
     x->score_of[shape] = sc;
@@ -786,29 +846,35 @@ int amulet_count_i8_adaptive(int64_t M, int64_t N, int64_t K, const int8_t *A, i
     const int64_t budget = M / 2;
     int64_t next_row = 0;
     int trials = 0, status = AMULET_OK;
-    double best_score = 1e300;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    // a task too small to spare the default shape's slab and one more runs whole with that shape
-    const bool can_test = best >= 1 && slab_rows(best) + slab_rows(order[1]) <= budget;
-    if (can_test && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
-        for (int i = 0; i < n_order && status == AMULET_OK; ++i) {
-            const int shape = order[i];
-            const int64_t rows = slab_rows(shape);
-            if (next_row + rows > budget) continue;   // no rows left for this one: a narrower tile may still fit
-            (void)hipEventRecord(e0, (hipStream_t)stream);
-            const int r = run_count(shape, rows, N, K, A + next_row * lda, lda, B, ldb, R + next_row * ldr, ldr, stream);
-            (void)hipEventRecord(e1, (hipStream_t)stream);
-            if (r != AMULET_OK || hipEventSynchronize(e1) != hipSuccess) { status = AMULET_ERR_LAUNCH; break; }
-            float ms = 0.0f;
-            (void)hipEventElapsedTime(&ms, e0, e1);
-            next_row += rows;
-            trials += 1;
-            const double sc = (double)ms / (double)rows;
-            if (sc < best_score) { best_score = sc; best = shape; }
+    // a task too small to spare the default shape's slab and one more runs whole with that shape,
+    // and so does one of a few milliseconds (estimated at 2.2 POP/s plus the read-modify-write of
+    // R at 5 TB/s): each slab is a launch with a last round of its own
+    const double est_ms = (2.0 * (double)M * (double)N * (double)K / 2.2e15 + 8.0 * (double)M * (double)N / 5.0e12) * 1e3;
+    const bool can_test = best >= 1 && slab_rows(best) + slab_rows(order[1]) <= budget && est_ms >= adaptive_min_task_ms();
+    if (can_test) {
+        // the candidates' order is fixed: enqueued back to back, one wait for all (BatchedTrials)
+        BatchedTrials bt;
+        if (bt.begin((hipStream_t)stream)) {
+            for (int i = 0; i < n_order && status == AMULET_OK; ++i) {
+                const int shape = order[i];
+                const int64_t rows = slab_rows(shape);
+                if (next_row + rows > budget) continue;   // no rows left for this one: a narrower tile may still fit
+                if (run_count(shape, rows, N, K, A + next_row * lda, lda, B, ldb, R + next_row * ldr, ldr, stream) !=
+                    AMULET_OK) {
+                    status = AMULET_ERR_LAUNCH;
+                    break;
+                }
+                bt.mark(shape, rows, (hipStream_t)stream);
+                next_row += rows;
+                trials += 1;
+            }
+            if (status == AMULET_OK && trials > 0) {
+                const int w = bt.finish();
+                if (w < 0) status = AMULET_ERR_LAUNCH;
+                else best = bt.shape[w];
+            }
         }
     }
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
     if (status != AMULET_OK) return status;
     int out = AMULET_OK;
     if (next_row < M)
@@ -1025,8 +1091,30 @@ int amulet_mmlike_f32_adaptive_general(int task, int thres_form, int trans_a, in
             // the dense contraction runs on the matrix cores: its two tiles are the candidates
             // (a vector-ALU slab runs at a sixth of their rate: one such trial on the caller's
             // rows cost 20 % of an 8192^3 call, and none ever won)
-            (void)adaptive_trial(&x, IDENTITY_MFMA_DMA3_SHAPE);   // (the register-staged kernel where it cannot stream)
-            (void)adaptive_trial(&x, IDENTITY_MFMA_BIG_SHAPE);
+            // (the streamed shapes fall back to the register-staged kernel where they cannot stream)
+            // Three candidates whose order is fixed: enqueued back to back, one wait for all.
+            const int first = best >= IDENTITY_MFMA_SHAPE ? best : IDENTITY_MFMA_DMA3_SHAPE;
+            const int cand[3] = {first, first == IDENTITY_MFMA_DMA4_SHAPE ? IDENTITY_MFMA_DMA3_SHAPE : IDENTITY_MFMA_DMA4_SHAPE,
+                                 IDENTITY_MFMA_BIG_SHAPE};
+            // (Not for a task of a few milliseconds, estimated at 140 TFLOP/s: each slab is a launch
+            // with a last round of its own, which cost 16384 x 8192 x 1024, 1.9 ms, 13 %.)
+            const bool worth_it = 2.0 * (double)M * (double)N * (double)K / 1.4e11 >= adaptive_min_task_ms();
+            BatchedTrials bt;
+            if (worth_it && bt.begin(x.stream)) {
+                for (int i = 0; i < 3 && x.status == AMULET_OK; ++i) {
+                    const int64_t rows = trial_rows(c, cand[i]);
+                    if (x.next_row + rows > x.budget_rows) continue;
+                    if (run_rows(c, cand[i], x.next_row, rows, x.stream) != AMULET_OK) { x.status = AMULET_ERR_LAUNCH; break; }
+                    bt.mark(cand[i], rows, x.stream);
+                    x.next_row += rows;
+                    x.trials += 1;
+                }
+                if (x.status == AMULET_OK && x.trials > 0) {
+                    const int w = bt.finish();
+                    if (w < 0) x.status = AMULET_ERR_LAUNCH;
+                    else x.best_shape = bt.shape[w];
+                }
+            }
         } else {
             // The shape a plain call would use is tried first, so that the walk can only replace
             // it by something that measured faster on this very task.  Then the paper's order:

@@ -348,11 +348,12 @@ def test_f64_every_shape_on_ragged_sizes(am, task, shape):
         am.amulet_mmlike_f64(task, dev(A), dev(B), dev(th), dev(dis) if task == 1 else None, dR, shape=6)
 
 
-def test_f64_adaptive_execution_trials_contribute_to_the_result(am):
+def test_f64_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch):
     """In-flight adaptive execution in fp64: the trial slabs are rows of the caller's R computed
     with different shapes, the rest runs with the winner, and the whole R must match the oracle
     (general form: thres[i], transposed A).  The winner is cached for the size bucket and used by
     a later plain call; the identity task and small tasks run whole, without trials."""
+    monkeypatch.setenv("AMULET_ADAPTIVE_MIN_TASK_MS", "0")   # (a task of about a millisecond: lift the one-trial limit)
     M, N, K = 8192, 4096, 160
     form, tA = 1, True
     A, B, th, dis, R_in = make_case(form, M, N, K, 9950)

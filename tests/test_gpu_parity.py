@@ -283,11 +283,12 @@ def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64 + 7 * M)
 
 
-def test_count_i8_adaptive_execution_trials_contribute_to_the_result(am):
+def test_count_i8_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch):
     """In-flight adaptive execution of the join count: slabs of rows of the caller's R are computed
     by different matrix-core kernels, the rest by the fastest; the whole R must be the exact count
     (sampled rows and columns against the oracle, whole-matrix row and column checksums).  The
     winner is cached; a problem too small for two slabs runs whole, without trials."""
+    monkeypatch.setenv("AMULET_ADAPTIVE_MIN_TASK_MS", "0")   # (a sub-millisecond task: lift the no-trials limit)
     M, N, K = 12288, 16384, 128
     g = np.random.Generator(np.random.PCG64(391))
     A = g.integers(-128, 128, (M, K)).astype(np.int8)
