@@ -690,6 +690,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     // A through LDS against A through the scalar cache: discount 30.4-31.0 against 31.3-31.9
     // TFLOP/s, count 36.4-37.2 against 36.9-40.4, boost within +-4 % either way).
     const bool a_through_lds = !a.transA && !a.transB && pitch_collides(a.lda, 4);
+    constexpr bool DPIPE = TASK == TASK_DISCOUNT && TM == 4 && NG == 1 && BK == 16;
     auto launch = [&](int64_t n_blocks, int n_splits) -> hipError_t {
         return launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
@@ -719,9 +720,12 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
                 }
                 hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b);
                 break;
-            case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
-            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
-            default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA, false>), grid, block, 0, s, b); break;
+            // (transposed layouts: the discount task's pipelined form; with B a chunk ahead where A
+            // is row-major -- with a transposed A the unrolled tile keeps the A values of all its
+            // chunks in scalar registers at once and spills 80-130 of them)
+            case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA, false, DPIPE, false>), grid, block, 0, s, b); break;
+            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA, false, DPIPE, DPIPE>), grid, block, 0, s, b); break;
+            default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA, false, DPIPE, false>), grid, block, 0, s, b); break;
             }
         });
     };
