@@ -386,7 +386,7 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s)
         // (and rows short enough for the streamed kernels' 32-bit lane offsets: 256 rows of A,
         // 64 k rows of B)
         const bool aligned = a.vecA && a.vecB && a.vecR && a.K % 64 == 0 &&
-                             a.lda <= (int64_t)(0xFFFFFFFFu - 64) / 256 && a.ldb <= (int64_t)(0xFFFFFFFFu - 256) / 64;
+                             a.lda <= (int64_t)(0x7FFFFFFF - 64) / 256 && a.ldb <= (int64_t)(0x7FFFFFFF - 256) / 64;
         int wr = shape == 6 ? 2 : 4;
         const bool persistent = shape == 8;
         if (wr == 4 && a.M < 256) wr = 2;

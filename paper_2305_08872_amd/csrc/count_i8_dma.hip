@@ -462,9 +462,9 @@ count_i8_dma_persistent_kernel(const CountArgs args)
 // (everything interior and aligned).
 bool count_i8_dma_eligible(const CountArgs &a, int wr)
 {
-    // a lane's fixed byte offset from its tile's origin must fit 32 bits: the tile's last row of A,
-    // the stage's last k row of B
-    const bool offsets_fit = a.lda <= (int64_t)(0xFFFFFFFFu - 64) / (64 * wr) && a.ldb <= (int64_t)(0xFFFFFFFFu - 256) / DM_BK;
+    // a lane's fixed byte offset from its tile's origin must fit 31 bits (kept clear of the sign
+    // bit): the tile's last row of A, the stage's last k row of B
+    const bool offsets_fit = a.lda <= (int64_t)(0x7FFFFFFF - 64) / (64 * wr) && a.ldb <= (int64_t)(0x7FFFFFFF - 256) / DM_BK;
     return offsets_fit && a.vecA && a.vecB && a.vecR && a.M % (64 * wr) == 0 && a.N % DM_BN == 0 && a.K % DM_BK == 0;
 }
 

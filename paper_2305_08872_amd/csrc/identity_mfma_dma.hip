@@ -274,12 +274,12 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
 }
 
 // Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
-// offsets that fit 32 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_dma_eligible(const MmlikeArgs &a)
 {
     if (a.transA || a.transB || !a.vec || !a.vecA) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.M % ID_BM || a.N % ID_BN || a.K % ID_BK || a.kchunk % ID_BK) return false;
-    if (a.lda > (int64_t)((0xFFFFFFFFLL / 4 - 16) / ID_BM) || a.ldb > (int64_t)((0xFFFFFFFFLL / 4 - ID_BN) / ID_BK)) return false;
+    if (a.lda > (int64_t)((0x7FFFFFFFLL / 4 - 16) / ID_BM) || a.ldb > (int64_t)((0x7FFFFFFFLL / 4 - ID_BN) / ID_BK)) return false;
     return true;
 }
 

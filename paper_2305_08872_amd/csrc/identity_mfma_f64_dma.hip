@@ -254,12 +254,12 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 }
 
 // Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
-// offsets that fit 32 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
     if (a.transA || a.transB || !a.vec || !a.vecA) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.M % DD_BM || a.N % DD_BN || a.K % DD_BK || a.kchunk % DD_BK) return false;
-    if (a.lda > (int64_t)((0xFFFFFFFFLL / 8 - 8) / DD_BM) || a.ldb > (int64_t)((0xFFFFFFFFLL / 8 - DD_BN) / DD_BK)) return false;
+    if (a.lda > (int64_t)((0x7FFFFFFFLL / 8 - 8) / DD_BM) || a.ldb > (int64_t)((0x7FFFFFFFLL / 8 - DD_BN) / DD_BK)) return false;
     return true;
 }
 
