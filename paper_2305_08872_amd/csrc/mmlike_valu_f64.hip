@@ -331,9 +331,23 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     __syncthreads();
 
     const double *bs_lane = &Bs[0][0][lane * 2];
+    // Wave priority rotates with the tile step, offset by the workgroup's place among those that
+    // tend to share a compute unit (256 apart in launch order), so that co-resident workgroups
+    // take turns being served first, as in the fp32 kernel (where the reason is given).  Measured
+    // with / without: discount 2048^3 16.3 / 15.9 TFLOP/s, 1536^2 x 4096 16.8 / 16.2, 4096^3 16.5 /
+    // 16.4; boost 2048^3 16.5 / 16.3; the count task 22.3 / 22.5, so it is left out there.
+    const int prio_phase = block >> 8;
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         const int k0 = t * D_BK;
+        if constexpr (TASK != TASK_COUNT_GT) {
+            switch ((t + prio_phase) & 3) {
+            case 0: __builtin_amdgcn_s_setprio(0); break;
+            case 1: __builtin_amdgcn_s_setprio(1); break;
+            case 2: __builtin_amdgcn_s_setprio(2); break;
+            default: __builtin_amdgcn_s_setprio(3); break;
+            }
+        }
         if (t + 1 < n_tiles) load_tile((t + 1 < full_tiles) ? D_BK : tail);
         const double *bs = bs_lane + buf * (D_BK * D_BN);
 
