@@ -316,7 +316,7 @@ identity_mfma_kernel(const MmlikeArgs args)
 }
 
 // `dma_stages` > 0: run the streamed kernel (identity_mfma_dma.hip) with a ring of that many
-// stages where the problem allows it (128 x 128 tile, row-major operands).
+// stages where the problem allows it (128 x 128 tile; whole tiles, aligned rows, either layout).
 template <int G, bool TA, bool TB>
 static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hipStream_t s)
 {
@@ -331,7 +331,7 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     // The streamed kernel where the problem allows it: three workgroups (ring of 3 stages) or
     // two (4 stages) to a compute unit.
     bool streamed = false;
-    if constexpr (G == 2 && !TA && !TB) streamed = dma_stages > 0 && identity_dma_eligible(b);
+    if constexpr (G == 2) streamed = dma_stages > 0 && identity_dma_eligible(b);
     // Register-staged kernel, tiles for at most half of the compute units: split K over several
     // workgroups per tile (at least 128 k each), which add their parts to R with hardware float
     // atomics

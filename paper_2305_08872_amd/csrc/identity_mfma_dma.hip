@@ -20,8 +20,8 @@
 //     in lanes 32-63, which land on the two halves of the 64 banks.
 // One barrier per stage, between the stage's two groups of 8 k (see the loop).
 //
-// Used for row-major operands with 16-byte aligned rows when M and N are whole tiles and K a
-// whole number of stages; everything else runs identity_mfma_kernel.
+// Used for operands with 16-byte aligned rows, row-major or transposed, when M and N are whole
+// tiles and K a whole number of stages; everything else runs identity_mfma_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -46,10 +46,15 @@ constexpr int ID_LOADS = 4;                         // DMA instructions per wave
 
 extern __shared__ __attribute__((aligned(16))) char id_smem[];
 
-template <int NSTAGE>
+// TA / TB: the operand is stored transposed (A as K x M, B as N x K; paper Sec. 6.3).  An operand's
+// 16-k slice of the tile keeps its global layout in LDS, "k-minor" (128 lines x 16 k, k contiguous:
+// row-major A, transposed B) or "k-major" (16 k x 128 lines: row-major B, transposed A), with the
+// swizzles given above for A and B respectively.
+template <int NSTAGE, bool TA, bool TB>
 __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs args)
 {
     static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    constexpr bool A_KMINOR = !TA, B_KMINOR = TB;
     const int M = args.M, N = args.N;
     int K = args.K;
     const int tid = threadIdx.x;
@@ -81,21 +86,31 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     if (n_stages <= 0) return;
 
     // ---- what each lane fetches: two A slots and two B slots per stage ---------------------
-    // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile
+    // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile:
+    //   k-minor tile: slot 64 j + lane -> line 16 j + lane / 4, physical unit lane % 4
+    //   k-major tile: slot 64 j + lane -> k 2 j + lane / 32, physical unit lane % 32
+    auto lane_offset = [&](bool kminor, int j, int64_t ld) {
+        if (kminor) {
+            const int line = 16 * j + (lane >> 2);
+            const int u = (lane & 3) ^ ((line >> 2) & 3);
+            return ((uint32_t)line * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
+        }
+        const int k = 2 * j + (lane >> 5);
+        const int u = (lane & 31) ^ (((k >> 2) & 1) << 3);
+        return ((uint32_t)k * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
+    };
     uint32_t a_voff[2], b_voff[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        const int j = wave + 4 * q;
-        const int row = 16 * j + (lane >> 2);
-        const int ua = (lane & 3) ^ ((row >> 2) & 3);
-        a_voff[q] = ((uint32_t)row * (uint32_t)args.lda + (uint32_t)(ua * 4)) * 4u;
-        const int k = 2 * j + (lane >> 5);
-        const int ub = (lane & 31) ^ (((k >> 2) & 1) << 3);
-        b_voff[q] = ((uint32_t)k * (uint32_t)args.ldb + (uint32_t)(ub * 4)) * 4u;
+        a_voff[q] = lane_offset(A_KMINOR, wave + 4 * q, args.lda);
+        b_voff[q] = lane_offset(B_KMINOR, wave + 4 * q, args.ldb);
     }
-    const float *const a_base = args.A + (int64_t)row0 * args.lda + kb;
-    const float *const b_base = args.B + (int64_t)kb * args.ldb + col0;
-    const int64_t b_stage = (int64_t)ID_BK * args.ldb;
+    // the tile's first stage, and what a stage adds (floats): 16 k along a k-minor operand's rows,
+    // 16 rows of a k-major one
+    const float *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0;
+    const float *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0;
+    const int64_t a_stage = A_KMINOR ? (int64_t)ID_BK : (int64_t)ID_BK * args.lda;
+    const int64_t b_stage = B_KMINOR ? (int64_t)ID_BK : (int64_t)ID_BK * args.ldb;
 
     // The loads are asm so that the compiler's wait-count pass does not see a vector-memory
     // instruction writing LDS (it would drain all outstanding loads before every LDS read);
@@ -116,26 +131,40 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         else dma16(ap, a_voff[q], dst);
     };
 
-    // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
-    // A: values k = 8g + 4 lh + (0..3) of row wr*64 + mi*32 + li: one 16-byte read per (g, mi)
-    // B: value k = 8g + 4 lh + t of column wc*64 + ni*32 + li: one 4-byte read per (g, t, ni)
-    int a_off[2];
+    // ---- where each lane reads its fragments (byte offsets inside an operand's slice) --------
+    // The lane's line is wr*64 + blk*32 + li of A, wc*64 + blk*32 + li of B (blk = mi, ni), and
+    // matrix instruction t of group g multiplies k = 8g + 4 lh + t:
+    //   k-minor: the four k of a group are one 16-byte read per block;
+    //   k-major: one 4-byte read per (t, block).
+    auto minor_off = [&](int line, int g) { return line * 64 + (((2 * g + lh) ^ ((line >> 2) & 3)) * 16); };   // + blk * 2048
+    auto major_off = [&](int line0, int blk) {
+        const int unit = (line0 >> 2) + blk * 8 + (li >> 2);
+        return (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + (li & 3) * 4;   // + (8g + t) * 512
+    };
+    int a_off[2], b_off[2];   // k-minor: per group g; k-major: per block
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
-        const int row = wr * 64 + li;
-        a_off[g] = row * 64 + (((2 * g + lh) ^ ((row >> 2) & 3)) * 16);   // + mi * 2048
+    for (int x = 0; x < 2; ++x) {
+        a_off[x] = A_KMINOR ? minor_off(wr * 64 + li, x) : major_off(wr * 64, x);
+        b_off[x] = ID_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x) : major_off(wc * 64, x));
     }
-    int b_off[2];
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int unit = wc * 16 + ni * 8 + (li >> 2);
-        b_off[ni] = ID_A_BYTES + (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + (li & 3) * 4;   // + (8g + t) * 512
-    }
-    // fragment read i (0..9) of group g of the stage in slot `buf`: 0, 1 = A (mi), 2..9 = B (t, ni)
-    auto read_one = [&](int buf, int g, int i, f4 (&a)[2], float (&b)[4][2]) {
+    // One group's fragments of an operand: a k-minor operand's as two 16-byte values (block, then
+    // component t), a k-major one's as 4 x 2 floats (t, block).
+    struct Frag {
+        f4 v4[2];
+        float v1[4][2];
+    };
+    constexpr int A_READS = A_KMINOR ? 2 : 8, B_READS = B_KMINOR ? 2 : 8, READS = A_READS + B_READS;
+    // fragment read i (0 .. READS-1) of group g of the stage in slot `buf`: A's first, then B's
+    auto read_one = [&](int buf, int g, int i, Frag &a, Frag &b) {
         const char *st = id_smem + buf * ID_STAGE_BYTES;
-        if (i < 2) a[i] = *(const f4 *)(st + a_off[g] + i * 2048);
-        else b[(i - 2) >> 1][(i - 2) & 1] = *(const float *)(st + b_off[(i - 2) & 1] + (8 * g + ((i - 2) >> 1)) * 512);
+        if (i < A_READS) {
+            if constexpr (A_KMINOR) a.v4[i] = *(const f4 *)(st + a_off[g] + i * 2048);
+            else a.v1[i >> 1][i & 1] = *(const float *)(st + a_off[i & 1] + (8 * g + (i >> 1)) * 512);
+        } else {
+            const int j = i - A_READS;
+            if constexpr (B_KMINOR) b.v4[j] = *(const f4 *)(st + b_off[g] + j * 2048);
+            else b.v1[j >> 1][j & 1] = *(const float *)(st + b_off[j & 1] + (8 * g + (j >> 1)) * 512);
+        }
     };
     f16v acc[2][2];
 #pragma unroll
@@ -148,17 +177,19 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // A with k-slot h of B: instruction t of group g multiplies k = 8g + 4h + t), with `side(i)`
     // issued right after instruction i.  A wave issues in order, and a matrix instruction
     // occupies the matrix core for 64 cycles during which the wave may issue other instructions:
-    // the stage's LDS reads, loads and scalar bookkeeping are spread over those gaps, a piece per
-    // matrix instruction, instead of standing between two runs of matrix instructions, where the
-    // matrix core idles while they issue (a run of them cost 10-15 % of the loop).
-    auto mma_with = [&](const f4 (&a)[2], const float (&b)[4][2], auto side) {
+    // the stage's LDS reads, loads and scalar bookkeeping are spread over those gaps, a piece or
+    // two per matrix instruction, instead of standing between two runs of matrix instructions,
+    // where the matrix core idles while they issue.
+    auto mma_with = [&](const Frag &a, const Frag &b, auto side) {
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) {
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][t], b[t][ni], acc[mi][ni], 0, 0, 0);
+                    const float av = A_KMINOR ? a.v4[mi][t] : a.v1[t][mi];
+                    const float bv = B_KMINOR ? b.v4[ni][t] : b.v1[t][ni];
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[mi][ni], 0, 0, 0);
                     side(t * 4 + mi * 2 + ni);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -191,7 +222,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         if (d < n_stages) {
 #pragma unroll
             for (int i = 0; i < ID_LOADS; ++i) issue_one(ap, bp, d, i);
-            ap += ID_BK;
+            ap += a_stage;
             bp += b_stage;
             requested = d + 1;
         }
@@ -199,16 +230,15 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
-    f4 fa0[2], fa1[2];
-    float fb0[4][2], fb1[4][2];
+    Frag fa0, fb0, fa1, fb1;
     int buf = 0, ibuf = NSTAGE - 1;
 #pragma unroll
-    for (int i = 0; i < 10; ++i) read_one(0, 0, i, fa0, fb0);
+    for (int i = 0; i < READS; ++i) read_one(0, 0, i, fa0, fb0);
     auto iteration = [&](int s, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         // group 0 of stage s; the fragments of group 1 are read meanwhile
-        mma_with(fa0, fb0, [&](int i) { if (i < 10) read_one(buf, 1, i, fa1, fb1); });
+        mma_with(fa0, fb0, [&](int i) { if (i < READS) read_one(buf, 1, i, fa1, fb1); });
         if constexpr (STEADY) {
             // stages up to s+NSTAGE-2 are requested; s+1 must have landed
             if constexpr (NSTAGE == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -221,13 +251,15 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         __builtin_amdgcn_s_barrier();   // bare: the fence of __syncthreads() would drain the loads in flight
         asm volatile("" ::: "memory");
         // group 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
-        // has left) and the fragment reads of group 0 of stage s+1
+        // has left) and the fragment reads of group 0 of stage s+1: ID_LOADS + READS pieces over 16
+        // matrix instructions, the first few of which take two
         const bool more = STEADY || s + NSTAGE - 1 < n_stages;
-        mma_with(fa1, fb1, [&](int i) {
+        auto piece = [&](int i) {
             if (i < ID_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
-            else if (i < ID_LOADS + 10) read_one(nbuf, 0, i - ID_LOADS, fa0, fb0);
-        });
-        ap += ID_BK;
+            else if (i < ID_LOADS + READS) read_one(nbuf, 0, i - ID_LOADS, fa0, fb0);
+        };
+        mma_with(fa1, fb1, [&](int i) { piece(i); piece(i + 16); });
+        ap += a_stage;
         bp += b_stage;
         ibuf = buf;
         buf = nbuf;
@@ -236,7 +268,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     int s = 0;
     for (; s < steady_end; ++s) iteration(s, std::true_type());
     for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
-    mma_with(fa0, fb0, [&](int i) { if (i < 10) read_one(buf, 1, i, fa1, fb1); });
+    mma_with(fa0, fb0, [&](int i) { if (i < READS) read_one(buf, 1, i, fa1, fb1); });
     mma_with(fa1, fb1, [&](int) {});
 
     // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
@@ -273,37 +305,44 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     }
 }
 
-// Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
+// Whole tiles, whole stages, operands with 16-byte aligned rows (in either layout), per-lane byte
 // offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_dma_eligible(const MmlikeArgs &a)
 {
-    if (a.transA || a.transB || !a.vec || !a.vecA) return false;
+    if (!a.vec || !a.vecA) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.M % ID_BM || a.N % ID_BN || a.K % ID_BK || a.kchunk % ID_BK) return false;
-    if (a.lda > (int64_t)((0x7FFFFFFFLL / 4 - 16) / ID_BM) || a.ldb > (int64_t)((0x7FFFFFFFLL / 4 - ID_BN) / ID_BK)) return false;
+    // a k-minor slice spans 128 lines of the operand's storage, a k-major one 16
+    const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / ID_BM, major_max = (0x7FFFFFFFLL / 4 - ID_BN) / ID_BK;
+    if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;
     return true;
 }
 
-int identity_dma_lds_bytes(int nstage) { return nstage * ID_STAGE_BYTES; }
+template <int NSTAGE, bool TA, bool TB>
+static hipError_t enqueue_layout(const MmlikeArgs &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<NSTAGE, TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * ID_STAGE_BYTES);
+    if (granted != hipSuccess) return granted;
+    hipLaunchKernelGGL((identity_mfma_dma_kernel<NSTAGE, TA, TB>), dim3(grid_x, grid_y), dim3(256), NSTAGE * ID_STAGE_BYTES, s, a);
+    return hipSuccess;
+}
+
+template <int NSTAGE>
+static hipError_t enqueue_stages(const MmlikeArgs &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    if (a.transA && a.transB) return enqueue_layout<NSTAGE, true, true>(a, grid_x, grid_y, s);
+    if (a.transA) return enqueue_layout<NSTAGE, true, false>(a, grid_x, grid_y, s);
+    if (a.transB) return enqueue_layout<NSTAGE, false, true>(a, grid_x, grid_y, s);
+    return enqueue_layout<NSTAGE, false, false>(a, grid_x, grid_y, s);
+}
 
 // Enqueues grid.x x grid.y workgroups of the streamed kernel (the caller has checked
 // identity_dma_eligible and fills the split fields of `a` as for identity_mfma_kernel).
 hipError_t enqueue_identity_dma(const MmlikeArgs &a, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    const int lds = identity_dma_lds_bytes(nstage);
-    if (nstage == 3) {
-        static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<3>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 3 * ID_STAGE_BYTES);
-        if (granted != hipSuccess) return granted;
-        hipLaunchKernelGGL((identity_mfma_dma_kernel<3>), dim3(grid_x, grid_y), dim3(256), lds, s, a);
-    } else if (nstage == 4) {
-        static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<4>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ID_STAGE_BYTES);
-        if (granted != hipSuccess) return granted;
-        hipLaunchKernelGGL((identity_mfma_dma_kernel<4>), dim3(grid_x, grid_y), dim3(256), lds, s, a);
-    } else {
-        return hipErrorInvalidValue;
-    }
-    return hipSuccess;
+    if (nstage == 3) return enqueue_stages<3>(a, grid_x, grid_y, s);
+    if (nstage == 4) return enqueue_stages<4>(a, grid_x, grid_y, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace amulet

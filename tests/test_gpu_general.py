@@ -261,29 +261,32 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
         assert_parity_f32(R, R_ref, ab, R_in, what="identity tail split shape %d" % shape)
 
 
-def test_identity_streamed_kernel_on_whole_tiles(am):
+@pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
+def test_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
     """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: rings
-    of 3 and 4 stages) runs only on whole 128 x 128 tiles, whole 16-k stages and aligned row-major
-    operands.  Cases: fewer stages than the ring holds, one tile, several tiles with padded
-    pitches and a non-zero R_in, few tiles with a long K (every tile split over workgroups),
-    and a few more tiles than compute units (the last round's tiles split).  Every output is
-    checked against the oracle; data whose sums are exact must match bit for bit."""
+    of 3 and 4 stages) runs only on whole 128 x 128 tiles, whole 16-k stages and operands with
+    aligned rows, in any of the four operand layouts.  Cases: fewer stages than the ring holds,
+    one tile, several tiles with padded pitches and a non-zero R_in, few tiles with a long K (every
+    tile split over workgroups), and a few more tiles than compute units (the last round's tiles
+    split).  Every output is checked against the oracle; data whose sums are exact must match
+    bit for bit."""
     cases = [(128, 128, 16, 0), (128, 128, 32, 0), (256, 384, 208, 4), (128, 256, 4096, 0), (1408, 3200, 1104, 8)]
     for idx, (M, N, K, pad) in enumerate(cases):
-        As, Bs, th, dis, R_in = make_case(0, 0, False, False, M, N, K, 6500 + idx)
-        R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
-        bufA = torch.full((M, K + pad), float("nan"), device="cuda"); bufA[:, :K] = dev(As)
-        bufB = torch.full((K, N + pad), float("nan"), device="cuda"); bufB[:, :N] = dev(Bs)
+        As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, M, N, K, 6500 + idx)
+        R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
+        bufA = torch.full((As.shape[0], As.shape[1] + pad), float("nan"), device="cuda"); bufA[:, :As.shape[1]] = dev(As)
+        bufB = torch.full((Bs.shape[0], Bs.shape[1] + pad), float("nan"), device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
         for shape in (10, 11):
-            print("identity streamed", M, N, K, pad, shape, flush=True)
+            print("identity streamed", tA, tB, M, N, K, pad, shape, flush=True)
             dR = dev(R_in)
-            am.amulet_mmlike_f32_general(0, bufA[:, :K], bufB[:, :N], None, None, dR, shape=shape)
+            am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,
+                                         trans_a=tA, trans_b=tB, shape=shape)
             torch.cuda.synchronize()
             assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity streamed %d %dx%dx%d" % (shape, M, N, K))
-    As, Bs, th, dis, R_in = make_case(0, 0, False, False, 256, 256, 1600, 6600, exact=True)
-    R_ref, _, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
+    As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, 256, 256, 1600, 6600, exact=True)
+    R_ref, _, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
     for shape in (10, 11):
-        R = run(am, 0, 0, False, False, As, Bs, None, None, R_in, shape)
+        R = run(am, 0, 0, tA, tB, As, Bs, None, None, R_in, shape)
         assert np.array_equal(R, R_ref), shape
 
 
