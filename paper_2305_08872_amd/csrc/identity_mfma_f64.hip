@@ -251,7 +251,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     // The streamed kernel where the problem allows it (row-major operands, whole tiles): two
     // workgroups to a compute unit.
     bool streamed = false;
-    if constexpr (!TA && !TB) streamed = identity_f64_dma_eligible(b);
+    streamed = identity_f64_dma_eligible(b);
     // Register-staged kernel, tiles for at most half of the compute units: split K over several
     // workgroups per tile (at least 128 k each), which add their parts to R with hardware fp64
     // atomics

@@ -19,8 +19,8 @@
 //     of the banks.
 // One barrier per stage, between its two matrix steps.
 //
-// Used for row-major operands with 16-byte aligned rows when M and N are whole tiles and K a
-// whole number of stages; everything else runs identity_mfma_f64_kernel.
+// Used for operands with 16-byte aligned rows, row-major or transposed, when M and N are whole
+// tiles and K a whole number of stages; everything else runs identity_mfma_f64_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -44,11 +44,16 @@ constexpr int DD_LOADS = 2;                         // DMA instructions per wave
 
 extern __shared__ __attribute__((aligned(16))) char dd_smem[];
 
-template <int NSTAGE>
+// TA / TB: the operand is stored transposed (A as K x M, B as N x K; paper Sec. 6.3).  An operand's
+// 8-k slice of the tile keeps its global layout in LDS, "k-minor" (128 lines x 8 k, k contiguous:
+// row-major A, transposed B) or "k-major" (8 k x 128 lines: row-major B, transposed A), with the
+// swizzles given above for A and B respectively.
+template <int NSTAGE, bool TA, bool TB>
 __global__ void __launch_bounds__(DD_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 {
     static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    constexpr bool A_KMINOR = !TA, B_KMINOR = TB;
     const int M = args.M, N = args.N;
     int K = args.K;
     const int tid = threadIdx.x;
@@ -80,15 +85,25 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     if (n_stages <= 0) return;
 
     // ---- what each lane fetches: one A slot and one B slot per stage -----------------------
-    // wave w owns the 1 KB slot group w of each operand's tile: A rows 16w .. 16w+15, B k-row w
-    const int a_row = 16 * wave + (lane >> 2);
-    const int a_u = (lane & 3) ^ ((a_row >> 2) & 3);
-    const uint32_t a_voff = ((uint32_t)a_row * (uint32_t)args.lda + (uint32_t)(a_u * 2)) * 8u;
-    const int b_u = lane ^ ((wave & 1) << 3);
-    const uint32_t b_voff = ((uint32_t)wave * (uint32_t)args.ldb + (uint32_t)(b_u * 2)) * 8u;
-    const double *const a_base = args.A + (int64_t)row0 * args.lda + kb;
-    const double *const b_base = args.B + (int64_t)kb * args.ldb + col0;
-    const int64_t b_stage = (int64_t)DD_BK * args.ldb;
+    // wave w owns the 1 KB slot group w of each operand's slice:
+    //   k-minor slice: slot 64 w + lane -> line 16 w + lane / 4, physical unit lane % 4
+    //   k-major slice: k-row w, physical unit lane
+    auto lane_offset = [&](bool kminor, int64_t ld) {
+        if (kminor) {
+            const int line = 16 * wave + (lane >> 2);
+            const int u = (lane & 3) ^ ((line >> 2) & 3);
+            return ((uint32_t)line * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
+        }
+        const int u = lane ^ ((wave & 1) << 3);
+        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
+    };
+    const uint32_t a_voff = lane_offset(A_KMINOR, args.lda), b_voff = lane_offset(B_KMINOR, args.ldb);
+    // the tile's first stage, and what a stage adds (doubles): 8 k along a k-minor operand's rows,
+    // 8 rows of a k-major one
+    const double *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0;
+    const double *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0;
+    const int64_t a_stage = A_KMINOR ? (int64_t)DD_BK : (int64_t)DD_BK * args.lda;
+    const int64_t b_stage = B_KMINOR ? (int64_t)DD_BK : (int64_t)DD_BK * args.ldb;
 
     // The loads are asm so that the compiler's wait-count pass does not see a vector-memory
     // instruction writing LDS (it would drain all outstanding loads before every LDS read);
@@ -108,26 +123,30 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         else dma16(ap, a_voff, dst);
     };
 
-    // ---- where each lane reads its fragments (byte offsets inside a stage) -----------------
-    // matrix step g of the stage multiplies k = 4g + lh:
-    //   A: value k of row wr*32 + mi*16 + li; B: value k of column wc*64 + ni*16 + li
-    int a_off[2];
+    // ---- where each lane reads its fragments (byte offsets inside an operand's slice) --------
+    // matrix step g of the stage multiplies k = 4g + lh; the lane's line is wr*32 + mi*16 + li of
+    // A, wc*64 + ni*16 + li of B; one 8-byte read per block in either layout:
+    //   k-minor: line * 64 + swizzled unit of k, per step g (+ 1024 per block)
+    //   k-major: k-row * 1024 + swizzled unit of the line, per block (+ 4096 per step)
+    auto minor_off = [&](int line, int g) {
+        const int k = 4 * g + lh;
+        return line * 64 + (((k >> 1) ^ ((line >> 2) & 3)) * 16) + (k & 1) * 8;
+    };
+    auto major_off = [&](int line0, int blk) {
+        const int unit = (line0 >> 1) + blk * 8 + (li >> 1);
+        return lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + (li & 1) * 8;
+    };
+    int a_off[2], b_off[4];   // k-minor: per step g; k-major: per block
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
-        const int row = wr * 32 + li, k = 4 * g + lh;
-        a_off[g] = row * 64 + (((k >> 1) ^ ((row >> 2) & 3)) * 16) + (k & 1) * 8;   // + mi * 1024
-    }
-    int b_off[4];
+    for (int x = 0; x < 2; ++x) a_off[x] = A_KMINOR ? minor_off(wr * 32 + li, x) : major_off(wr * 32, x);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        const int unit = wc * 32 + ni * 8 + (li >> 1);
-        b_off[ni] = DD_A_BYTES + lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + (li & 1) * 8;   // + g * 4096
-    }
+    for (int x = 0; x < 4; ++x)
+        b_off[x] = DD_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x & 1) : major_off(wc * 64, x));
     // fragment read i (0..5) of matrix step g of the stage in slot `buf`: 0, 1 = A (mi), 2..5 = B (ni)
     auto read_one = [&](int buf, int g, int i, double (&a)[2], double (&b)[4]) {
         const char *st = dd_smem + buf * DD_STAGE_BYTES;
-        if (i < 2) a[i] = *(const double *)(st + a_off[g] + i * 1024);
-        else b[i - 2] = *(const double *)(st + b_off[i - 2] + g * 4096);
+        if (i < 2) a[i] = *(const double *)(st + (A_KMINOR ? a_off[g] + i * 1024 : a_off[i] + g * 4096));
+        else b[i - 2] = *(const double *)(st + (B_KMINOR ? b_off[g] + (i - 2) * 1024 : b_off[i - 2] + g * 4096));
     };
     d4 acc[2][4];
 #pragma unroll
@@ -177,7 +196,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         if (d < n_stages) {
 #pragma unroll
             for (int i = 0; i < DD_LOADS; ++i) issue_one(ap, bp, d, i);
-            ap += DD_BK;
+            ap += a_stage;
             bp += b_stage;
             requested = d + 1;
         }
@@ -212,7 +231,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
             if (i < DD_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
             else read_one(nbuf, 0, i - DD_LOADS, fa0, fb0);
         });
-        ap += DD_BK;
+        ap += a_stage;
         bp += b_stage;
         ibuf = buf;
         buf = nbuf;
@@ -253,14 +272,29 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     }
 }
 
-// Whole tiles, whole stages, row-major operands with 16-byte aligned rows, per-lane byte
+// Whole tiles, whole stages, operands with 16-byte aligned rows (in either layout), per-lane byte
 // offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
-    if (a.transA || a.transB || !a.vec || !a.vecA) return false;
+    // (16-byte pieces along each operand's contiguous axis: vecA for A; for B, vec when it is
+    // row-major, vecBt when it is stored transposed)
+    if (!a.vecA || !(a.transB ? a.vecBt : a.vec)) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.M % DD_BM || a.N % DD_BN || a.K % DD_BK || a.kchunk % DD_BK) return false;
-    if (a.lda > (int64_t)((0x7FFFFFFFLL / 8 - 8) / DD_BM) || a.ldb > (int64_t)((0x7FFFFFFFLL / 8 - DD_BN) / DD_BK)) return false;
+    // a k-minor slice spans 128 lines of the operand's storage, a k-major one 8
+    const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / DD_BM, major_max = (0x7FFFFFFFLL / 8 - DD_BN) / DD_BK;
+    if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;
     return true;
+}
+
+template <bool TA, bool TB>
+static hipError_t enqueue_f64_layout(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    constexpr int NSTAGE = 4;
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_dma_kernel<NSTAGE, TA, TB>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * DD_STAGE_BYTES);
+    if (granted != hipSuccess) return granted;
+    hipLaunchKernelGGL((identity_mfma_f64_dma_kernel<NSTAGE, TA, TB>), dim3(grid_x, grid_y), dim3(DD_NT), NSTAGE * DD_STAGE_BYTES, s, a);
+    return hipSuccess;
 }
 
 // Enqueues grid.x x grid.y workgroups of the streamed kernel (ring of 4 stages; the caller has
@@ -268,12 +302,10 @@ bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 // identity_mfma_f64_kernel).
 hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    constexpr int NSTAGE = 4;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_dma_kernel<NSTAGE>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * DD_STAGE_BYTES);
-    if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((identity_mfma_f64_dma_kernel<NSTAGE>), dim3(grid_x, grid_y), dim3(DD_NT), NSTAGE * DD_STAGE_BYTES, s, a);
-    return hipSuccess;
+    if (a.transA && a.transB) return enqueue_f64_layout<true, true>(a, grid_x, grid_y, s);
+    if (a.transA) return enqueue_f64_layout<true, false>(a, grid_x, grid_y, s);
+    if (a.transB) return enqueue_f64_layout<false, true>(a, grid_x, grid_y, s);
+    return enqueue_f64_layout<false, false>(a, grid_x, grid_y, s);
 }
 
 }  // namespace amulet

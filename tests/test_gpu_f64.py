@@ -391,27 +391,35 @@ def test_f64_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch)
     am.amulet_clear_selections()
 
 
-def test_f64_identity_streamed_kernel_on_whole_tiles(am):
+@pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
+def test_f64_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
     """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS runs only on whole
-    128 x 128 tiles, whole 8-k stages and aligned row-major operands.  Cases: fewer stages than the
-    ring holds, one tile, several tiles with padded pitches and a non-zero R_in, few tiles with a
-    long K (every tile split over workgroups), a few more tiles than compute units (the last
-    round's tiles split), and exact data bit for bit.  Every output is checked."""
+    128 x 128 tiles, whole 8-k stages and operands with aligned rows, in any of the four operand
+    layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
+    and a non-zero R_in, few tiles with a long K (every tile split over workgroups), a few more
+    tiles than compute units (the last round's tiles split), and exact data bit for bit.  Every
+    output is checked."""
     cases = [(128, 128, 8, 0), (128, 128, 24, 0), (256, 384, 200, 2), (128, 256, 4096, 0), (1408, 3200, 1104, 6)]
     for idx, (M, N, K, pad) in enumerate(cases):
         A, B, th, dis, R_in = make_case(0, M, N, K, 9960 + idx)
-        R_ref, ab, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
-        bufA = torch.full((M, K + pad), float("nan"), dtype=torch.float64, device="cuda"); bufA[:, :K] = dev(A)
-        bufB = torch.full((K, N + pad), float("nan"), dtype=torch.float64, device="cuda"); bufB[:, :N] = dev(B)
-        print("f64 identity streamed", M, N, K, pad, flush=True)
+        As = np.ascontiguousarray(A.T) if tA else A
+        Bs = np.ascontiguousarray(B.T) if tB else B
+        R_ref, ab, _ = oracle.mmlike_f64_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
+        bufA = torch.full((As.shape[0], As.shape[1] + pad), float("nan"), dtype=torch.float64, device="cuda")
+        bufA[:, :As.shape[1]] = dev(As)
+        bufB = torch.full((Bs.shape[0], Bs.shape[1] + pad), float("nan"), dtype=torch.float64, device="cuda")
+        bufB[:, :Bs.shape[1]] = dev(Bs)
+        print("f64 identity streamed", tA, tB, M, N, K, pad, flush=True)
         dR = dev(R_in)
-        am.amulet_mmlike_f64(0, bufA[:, :K], bufB[:, :N], None, None, dR)
+        am.amulet_mmlike_f64(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR, trans_a=tA, trans_b=tB)
         torch.cuda.synchronize()
         check(dR.cpu().numpy(), R_ref, ab, R_in, 0, "f64 identity streamed %dx%dx%d" % (M, N, K))
     A, B, th, dis, R_in = make_case(0, 256, 256, 1600, 9970, exact=True)
-    R_ref, _, _ = oracle.mmlike_f64_general(0, A, B, None, None, R_in)
+    As = np.ascontiguousarray(A.T) if tA else A
+    Bs = np.ascontiguousarray(B.T) if tB else B
+    R_ref, _, _ = oracle.mmlike_f64_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
     dR = dev(R_in)
-    am.amulet_mmlike_f64(0, dev(A), dev(B), None, None, dR)
+    am.amulet_mmlike_f64(0, dev(As), dev(Bs), None, None, dR, trans_a=tA, trans_b=tB)
     torch.cuda.synchronize()
     assert np.array_equal(dR.cpu().numpy(), R_ref)
 
