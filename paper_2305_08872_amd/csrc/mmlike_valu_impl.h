@@ -76,15 +76,19 @@ __device__ __forceinline__ void fold4(float a, f4 b, const float *th, const floa
     } else if constexpr (TASK == TASK_BOOST) {
         // p + (p > th)(p - th) = p + max(p - th, 0) is continuous in p, so the
         // unrounded product inside the fused operations is within tolerance.
-        float d[4];
+        // One product at a time, fenced: fma, fma, max, add.  Three of the four read a scalar
+        // register or an inline constant, and long runs of such instructions issue slower than
+        // the same instructions interleaved with the all-vector add (register-only loops: 9.1-9.7
+        // clocks per 64 products in groups of four, 8.4 one at a time; the kernel 30.3 -> 32.3
+        // TFLOP/s at 8192^3).  Left alone the scheduler builds pairs and runs of ten.
 #pragma unroll
-        for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaf(a, b[c], -th[c]);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[c] = __builtin_fmaf(a, b[c], acc[c]);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaxf(d[c], 0.0f);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[c] += d[c];
+        for (int c = 0; c < 4; ++c) {
+            float d = __builtin_fmaf(a, b[c], -th[c]);
+            acc[c] = __builtin_fmaf(a, b[c], acc[c]);
+            d = __builtin_fmaxf(d, 0.0f);
+            acc[c] += d;
+            __builtin_amdgcn_sched_barrier(0);
+        }
     } else {
         // The count needs no lane mask: p > th exactly when th - p is negative (a difference of
         // two floats is zero only when they are equal, subnormal results included, and x - x is
@@ -691,6 +695,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
     // TFLOP/s, count 36.4-37.2 against 36.9-40.4, boost within +-4 % either way).
     const bool a_through_lds = !a.transA && !a.transB && pitch_collides(a.lda, 4);
     constexpr bool DPIPE = TASK == TASK_DISCOUNT && TM == 4 && NG == 1 && BK == 16;
+    constexpr bool BAHEAD = (TASK == TASK_DISCOUNT || TASK == TASK_BOOST) && TM == 4 && NG == 1 && BK == 16;   // B values a chunk ahead
     auto launch = [&](int64_t n_blocks, int n_splits) -> hipError_t {
         return launch_row_of_blocks(b, n_blocks, 64 * NW, [&](unsigned n) {
             const dim3 grid(n, (unsigned)n_splits), block(64 * NW);
@@ -700,6 +705,14 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
                     // the chunk-wide pipeline fed with B values read a chunk ahead: at every size
                     if (!a_through_lds) {
                         hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false, true, true>), grid, block, 0, s, b);
+                        break;
+                    }
+                }
+                if constexpr (TASK == TASK_BOOST && TM == 4 && NG == 1 && BK == 16) {
+                    // B values read a chunk ahead (no chunk pipeline: the boost has no lane mask
+                    // to keep at a distance): +0.5-1.5 %
+                    if (!a_through_lds) {
+                        hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 0, TM, NG, NW, BK, KA, false, false, true>), grid, block, 0, s, b);
                         break;
                     }
                 }
@@ -724,7 +737,7 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
             // is row-major -- with a transposed A the unrolled tile keeps the A values of all its
             // chunks in scalar registers at once and spills 80-130 of them)
             case 1: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 1, TM, NG, NW, BK, KA, false, DPIPE, false>), grid, block, 0, s, b); break;
-            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA, false, DPIPE, DPIPE>), grid, block, 0, s, b); break;
+            case 2: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 2, TM, NG, NW, BK, KA, false, DPIPE, BAHEAD>), grid, block, 0, s, b); break;
             default: hipLaunchKernelGGL((mmlike_valu_kernel<TASK, TF, 3, TM, NG, NW, BK, KA, false, DPIPE, false>), grid, block, 0, s, b); break;
             }
         });

@@ -12,7 +12,7 @@ namespace amulet {
 
 // mix 0: fused multiply-add only (the identity task's inner operation)
 // mix 1: multiply, compare, select, fused multiply-add (the discount task), interleaved as in the kernel
-// mix 2: fma, fma, max, add (the boost task)
+// mix 2: fma, fma, max, add (the boost task), one product at a time as in the kernel
 // mix 3: multiply, subtract, then the sign bit of the difference added to an integer count (the count task)
 template <int MIX>
 __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, int iters)
@@ -68,15 +68,15 @@ __global__ void __launch_bounds__(256) valu_probe_kernel(float *out, float a0, i
 #pragma unroll
                     for (int c = 0; c < 4; ++c) cnt[g * 4 + c] += (int)(__builtin_bit_cast(unsigned, d[c]) >> 31);
                 } else {
-                    float d[4];
+                    // one product at a time, as the kernel runs them
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaf(a, b[g * 4 + c], -th[g * 4 + c]);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] = __builtin_fmaf(a, b[g * 4 + c], acc[g * 4 + c]);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) d[c] = __builtin_fmaxf(d[c], 0.0f);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[g * 4 + c] += d[c];
+                    for (int c = 0; c < 4; ++c) {
+                        float d = __builtin_fmaf(a, b[g * 4 + c], -th[g * 4 + c]);
+                        acc[g * 4 + c] = __builtin_fmaf(a, b[g * 4 + c], acc[g * 4 + c]);
+                        d = __builtin_fmaxf(d, 0.0f);
+                        acc[g * 4 + c] += d;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
             a += 1e-7f;
