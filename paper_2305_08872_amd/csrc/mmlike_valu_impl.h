@@ -402,10 +402,19 @@ mmlike_valu_kernel(const MmlikeArgs args)
     auto a_of = [](const av_t (&v)[TM], int r, int kk) -> float {
         return transA ? v[kk * (TM / 4) + r / 4][r % 4] : v[r][kk];
     };
-    auto fetch_a = [&](int kn) {
+    // (the chunk at k = kt + rel: kt a tile's first k, so that a row-major A costs one address per
+    // row and tile, and the chunks whose rel is a constant are loads at immediate offsets from it)
+    auto fetch_a = [&](int kt, int rel) {
+        const int kn = kt + rel;
         if constexpr (!transA) {
+            // the byte offset of the chunk as a 32-bit scalar the compiler cannot see through:
+            // left visible, loads at constant offsets from one row address are merged into
+            // one load per row and tile, issued at the tile's start and waited for there
+            uint32_t relb = (uint32_t)rel * 4u;
+            asm volatile("" : "+s"(relb));
+            typedef const __attribute__((address_space(4))) char *sptr_c;
 #pragma unroll
-            for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)(As + arow[r] + kn);
+            for (int r = 0; r < TM; ++r) a_next[r] = *(sptr_av)((sptr_c)(As + (arow[r] + kt)) + relb);
         } else if (rows_full) {
             // 4 consecutive rows of one k are contiguous in the transposed storage
 #pragma unroll
@@ -424,7 +433,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
     };
     load_tile(full_tiles > 0 ? BK : tail);
     store_tile(0);
-    if (!ALDS && full_tiles > 0) fetch_a(0);
+    if (!ALDS && full_tiles > 0) fetch_a(0, 0);
     __syncthreads();
 
     // The arithmetic of one chunk: KA k of the wave's TM rows against a lane's 4 NG columns.
@@ -523,11 +532,10 @@ mmlike_valu_kernel(const MmlikeArgs args)
 #pragma unroll
                         for (int g = 0; g < NG; ++g) bq[(c + 1) & 1][kk][g] = *(const f4 *)(bs + (kc + KA + kk) * BN + g * 256);
                 }
-                {
-                    int kn = k0 + kc + KA;
-                    kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
-                    fetch_a(kn);
-                }
+                // the next chunk's A values: inside this (full) tile, or the next tile's first chunk
+                // (past the last full chunk: this one again)
+                if (c + 1 < BK / KA) fetch_a(k0, kc + KA);
+                else fetch_a(k0, k0 + BK + KA <= K ? BK : BK - KA);
                 __builtin_amdgcn_sched_barrier(0);
                 compute_chunk(a, bq[c & 1]);
             }
@@ -556,11 +564,7 @@ mmlike_valu_kernel(const MmlikeArgs args)
                     // have to drain them too.  Here they have the whole chunk's arithmetic to land.
                     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), vmcnt and expcnt untouched
                     __builtin_amdgcn_sched_barrier(0);
-                    {
-                        int kn = k0 + kc + KA;
-                        kn = kn + KA <= K ? kn : k0 + kc;  // past the last full chunk: re-read this one
-                        fetch_a(kn);
-                    }
+                    fetch_a(k0, k0 + kc + 2 * KA <= K ? kc + KA : kc);   // past the last full chunk: re-read this one
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 compute_chunk(a, b);
