@@ -309,10 +309,17 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     // wait for its own loads instead of letting them land during the chunk's arithmetic)
     d2_a8 a_next[transA ? 1 : D_TM];
     d4_a8 a_next_t[transA ? KA : 1];
-    auto fetch_a = [&](int kn) {
+    // (the chunk at k = kt + rel, kt a tile's first k: a row-major A costs one address per row and
+    // tile, and the chunk is a 32-bit scalar offset of the load -- kept opaque to the compiler, which
+    // would otherwise merge a tile's loads into one per row, issued and waited for at the tile's start)
+    auto fetch_a = [&](int kt, int rel) {
+        const int kn = kt + rel;
         if constexpr (!transA) {
+            uint32_t relb = (uint32_t)rel * 8u;
+            asm volatile("" : "+s"(relb));
+            typedef const __attribute__((address_space(4))) char *sptr_c;
 #pragma unroll
-            for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)(As + arow[r] + kn);
+            for (int r = 0; r < D_TM; ++r) a_next[r] = *(sptr_d2)((sptr_c)(As + (arow[r] + kt)) + relb);
         } else if (rows_full) {
             // the 4 rows of one k are contiguous in the transposed storage
 #pragma unroll
@@ -327,7 +334,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
     };
     load_tile(full_tiles > 0 ? D_BK : tail);
     store_tile(0);
-    if (!ALDS && full_tiles > 0) fetch_a(0);
+    if (!ALDS && full_tiles > 0) fetch_a(0, 0);
     __syncthreads();
 
     const double *bs_lane = &Bs[0][0][lane * 2];
@@ -390,11 +397,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                 __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + 1 < NCH) read_chunk(c + 1, (c + 1) & 1);
-                if constexpr (!ALDS) {
-                    int kn = k0 + kc + KA;
-                    kn = kn + KA <= K ? kn : k0 + kc;
-                    fetch_a(kn);
-                }
+                if constexpr (!ALDS) fetch_a(k0, k0 + kc + 2 * KA <= K ? kc + KA : kc);   // past the last full chunk: this one again
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kk = 0; kk < KA; ++kk) {
@@ -429,11 +432,7 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                     // loads return out of order: any later LDS wait would drain them too)
                     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
                     __builtin_amdgcn_sched_barrier(0);
-                    {
-                        int kn = k0 + kc + KA;
-                        kn = kn + KA <= K ? kn : k0 + kc;
-                        fetch_a(kn);
-                    }
+                    fetch_a(k0, k0 + kc + 2 * KA <= K ? kc + KA : kc);   // past the last full chunk: this one again
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
