@@ -32,6 +32,63 @@ VALU_LANE_OPS_PER_S = 256 * 128 * 2.4e9
 VALU_OPS_PER_PRODUCT = {"discount": 4, "boost": 4, "count_gt": 4, "identity": 1}
 
 
+class ShaderClock:
+    """Samples the GPU's current shader clock (the starred line of the driver's pp_dpm_sclk file)
+    from a thread while a timed region runs.  The published peaks are at 2.4 GHz; under a full
+    vector-ALU load the chip holds less (power), and the sample says how much.  Context only:
+    `frac` stays against the published peak.  Reports None where the file cannot be read."""
+
+    def __init__(self, period_s=0.02):
+        import glob
+        self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.period_s = period_s
+        self.samples = []
+        self._stop = None
+        self._thread = None
+
+    def _read(self):
+        for path in self.paths:
+            try:
+                with open(path) as f:
+                    for line in f:
+                        if "*" in line:
+                            digits = "".join(c for c in line.split(":", 1)[-1] if c.isdigit())
+                            if digits:
+                                return int(digits)
+            except OSError:
+                continue
+        return None
+
+    def __enter__(self):
+        import threading
+        self._stop = threading.Event()
+
+        def loop():
+            while not self._stop.is_set():
+                mhz = self._read()
+                if mhz:
+                    self.samples.append(mhz)
+                self._stop.wait(self.period_s)
+
+        if self.paths:
+            self._thread = threading.Thread(target=loop, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self._thread is not None:
+            self._thread.join()
+        return False
+
+    def median_mhz(self):
+        # (the first samples may predate the first launch: idle clock; the median of a region of
+        # tens of milliseconds or more is the loaded clock)
+        if len(self.samples) < 5:    # a region of less than about 100 ms: too few samples to say
+            return None
+        return sorted(self.samples)[len(self.samples) // 2]
+
+
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, 5.0 POP/s
 FP64_VECTOR_PEAK_TFLOPS = 78.6  # MI355X fp64 vector peak
 
@@ -66,13 +123,15 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
-    w0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record()
-        am.amulet_count_i8(dA, dB, dR)
-        stops[i].record()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
+    with ShaderClock() as sclk:
+        w0 = time.perf_counter()
+        for i in range(args.steps):
+            starts[i].record()
+            am.amulet_count_i8(dA, dB, dR)
+            stops[i].record()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
+    sclk_mhz = sclk.median_mhz()
     kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
     kernel_ms_avg = sum(kern_ms) / args.steps
     kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
@@ -105,6 +164,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
                      "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
+                     "shader_clock_mhz": sclk_mhz,
                      "compulsory_bytes": M * K + K * N + 8 * M * N,
                      "mfma_probe_tops": round(probe_tops, 1),
                      "frac_of_mfma_probe": round(achieved / probe_tops, 4)},
@@ -137,13 +197,15 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> dict:
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
-    w0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record()
-        am.amulet_mmlike_f64(task, dA, dB, th, dis, dR)
-        stops[i].record()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
+    with ShaderClock() as sclk:
+        w0 = time.perf_counter()
+        for i in range(args.steps):
+            starts[i].record()
+            am.amulet_mmlike_f64(task, dA, dB, th, dis, dR)
+            stops[i].record()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
+    sclk_mhz = sclk.median_mhz()
     kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
     kernel_ms_avg = sum(kern_ms) / args.steps
     kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
@@ -183,6 +245,7 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> dict:
         "roofline": {"bound": "mfma" if tname == "identity" else "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
                      "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
+                     "shader_clock_mhz": sclk_mhz,
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(FP64_VECTOR_PEAK_TFLOPS / ops, 3),
                      "frac_of_op_mix_ceiling": round(achieved * ops / FP64_VECTOR_PEAK_TFLOPS, 4)},
@@ -305,13 +368,15 @@ def bench_workload(args, am, torch, np, wl) -> dict:
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
-    w0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record()
-        am.amulet_mmlike_f32(task, dA, dB, dP, dR)
-        stops[i].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - w0) * 1e3
+    with ShaderClock() as sclk:
+        w0 = time.perf_counter()
+        for i in range(args.steps):
+            starts[i].record()
+            am.amulet_mmlike_f32(task, dA, dB, dP, dR)
+            stops[i].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - w0) * 1e3
+    sclk_mhz = sclk.median_mhz()
     kern_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
     ms_per_step = wall_ms / args.steps
     kernel_ms_avg = sum(kern_ms) / len(kern_ms)
@@ -404,7 +469,10 @@ def bench_workload(args, am, torch, np, wl) -> dict:
                      "kernel_ms_avg": round(kernel_ms_avg, 4), "kernel_ms_median": round(kernel_ms_median, 4),
                      "valu_ops_per_product": ops,
                      "op_mix_ceiling_tflops": round(ceiling_tflops, 3),
-                     "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4)},
+                     "frac_of_op_mix_ceiling": round(achieved_tflops / ceiling_tflops, 4),
+                     "shader_clock_mhz": sclk_mhz,
+                     "frac_of_op_mix_ceiling_at_clock": None if not sclk_mhz else
+                     round(achieved_tflops / (ceiling_tflops * sclk_mhz / 2400.0), 4)},
         "valu_probe": probe,
         "cpu_baseline": cpu,
         "parity_worst_ratio_on_sample": parity,
@@ -444,7 +512,8 @@ def config_leg(name, args, am, torch, np, wl) -> dict:
            "ms_per_step": rec["ms_per_step"], "kernel_ms_avg": roof["kernel_ms_avg"], "dtype": rec["dtype"],
            "tile_shape": rec["config"]["tile_shape"],
            "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "frac_of_op_mix_ceiling",
-                                             "frac_of_mfma_probe") if k in roof},
+                                             "frac_of_mfma_probe", "shader_clock_mhz",
+                                             "frac_of_op_mix_ceiling_at_clock") if k in roof},
            "parity_on_sample": rec.get("parity_worst_ratio_on_sample", rec.get("bit_exact_on_sample")),
            "parity_ok": rec["parity_ok"], "parity_sample": rec["cpu_baseline"]["sample"] if rec["cpu_baseline"] else None}
     for key in ("library_sgemm", "library_dgemm"):
