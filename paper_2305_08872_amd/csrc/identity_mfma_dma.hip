@@ -20,8 +20,11 @@
 //     in lanes 32-63, which land on the two halves of the 64 banks.
 // One barrier per stage, between the stage's two groups of 8 k (see the loop).
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, when M and N are whole
-// tiles and K a whole number of stages; everything else runs identity_mfma_kernel.
+// Used for operands with 16-byte aligned rows, row-major or transposed, when K is a whole number
+// of stages; everything else runs identity_mfma_kernel.  M and N need not be whole tiles: a lane
+// whose line (or 16-byte unit of lines) lies past the edge fetches the last one inside instead, so
+// every load stays inside the operand, what it brings only reaches rows and columns of the tile
+// that do not exist, and those are not written back.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -65,7 +68,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
 
     // place in the XCD-aware tile order, and which k range of it (same conventions as
     // identity_mfma_kernel: split K over gridDim.y, tail split from tail_base on)
-    const int tiles_m = M / ID_BM, tiles_n = N / ID_BN;
+    const int tiles_m = (M + ID_BM - 1) / ID_BM, tiles_n = (N + ID_BN - 1) / ID_BN;
     int tm, tn;
     int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
@@ -89,21 +92,27 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile:
     //   k-minor tile: slot 64 j + lane -> line 16 j + lane / 4, physical unit lane % 4
     //   k-major tile: slot 64 j + lane -> k 2 j + lane / 32, physical unit lane % 32
-    auto lane_offset = [&](bool kminor, int j, int64_t ld) {
+    // `lines` of the tile exist (128 but in an edge tile): a line past them is replaced by the last
+    // one inside, in a k-major tile a unit of four lines by the last whole unit (the host admits
+    // k-major operands only with a multiple of four lines)
+    auto lane_offset = [&](bool kminor, int j, int64_t ld, int lines) {
         if (kminor) {
             const int line = 16 * j + (lane >> 2);
             const int u = (lane & 3) ^ ((line >> 2) & 3);
-            return ((uint32_t)line * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
+            const int line_in = line < lines ? line : lines - 1;
+            return ((uint32_t)line_in * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
         }
         const int k = 2 * j + (lane >> 5);
         const int u = (lane & 31) ^ (((k >> 2) & 1) << 3);
-        return ((uint32_t)k * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
+        const int u_in = 4 * u < lines ? u : (lines >> 2) - 1;
+        return ((uint32_t)k * (uint32_t)ld + (uint32_t)(u_in * 4)) * 4u;
     };
+    const int rows_in = M - row0 < ID_BM ? M - row0 : ID_BM, cols_in = N - col0 < ID_BN ? N - col0 : ID_BN;
     uint32_t a_voff[2], b_voff[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        a_voff[q] = lane_offset(A_KMINOR, wave + 4 * q, args.lda);
-        b_voff[q] = lane_offset(B_KMINOR, wave + 4 * q, args.ldb);
+        a_voff[q] = lane_offset(A_KMINOR, wave + 4 * q, args.lda, rows_in);
+        b_voff[q] = lane_offset(B_KMINOR, wave + 4 * q, args.ldb, cols_in);
     }
     // the tile's first stage, and what a stage adds (floats): 16 k along a k-minor operand's rows,
     // 16 rows of a k-major one
@@ -275,6 +284,35 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // R += acc: the 32 values of a row block are all read before the first is written back (as
     // "*dst += acc" per element the compiler must keep every store behind the load before it and
     // the write-back is a chain of 64 round trips to memory, 15 us of a tile).
+    if (rows_in < ID_BM || cols_in < ID_BN) {
+        // an edge tile: element by element, the rows and columns that exist
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const int col = wc * 64 + ni * 32 + li;
+                float *const rcol = args.R + (int64_t)row0 * args.ldr + col0 + col;
+                float old[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    const bool in = row < rows_in && col < cols_in;
+                    if (ksplit) {
+                        if (in) unsafeAtomicAdd(rcol + (int64_t)row * args.ldr, acc[mi][ni][v]);
+                    } else {
+                        old[v] = in ? rcol[(int64_t)row * args.ldr] : 0.0f;
+                    }
+                }
+                if (!ksplit) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                        if (row < rows_in && col < cols_in) rcol[(int64_t)row * args.ldr] = old[v] + acc[mi][ni][v];
+                    }
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         float *dst[2][16];
@@ -305,12 +343,14 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     }
 }
 
-// Whole tiles, whole stages, operands with 16-byte aligned rows (in either layout), per-lane byte
-// offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// Whole stages, operands with 16-byte aligned rows (in either layout; a k-major operand with a
+// multiple of four lines, so that every 16-byte unit of it is whole), per-lane byte offsets that
+// fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_dma_eligible(const MmlikeArgs &a)
 {
     if (!a.vec || !a.vecA) return false;
-    if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.M % ID_BM || a.N % ID_BN || a.K % ID_BK || a.kchunk % ID_BK) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.K % ID_BK || a.kchunk % ID_BK) return false;
+    if ((a.transA && a.M % 4) || (!a.transB && a.N % 4)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 16
     const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / ID_BM, major_max = (0x7FFFFFFFLL / 4 - ID_BN) / ID_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;

@@ -19,8 +19,8 @@
 //     of the banks.
 // One barrier per stage, between its two matrix steps.
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, when M and N are whole
-// tiles and K a whole number of stages; everything else runs identity_mfma_f64_kernel.
+// Used for operands with 16-byte aligned rows, row-major or transposed, when K is a whole number
+// of stages (M and N need not be whole tiles); everything else runs identity_mfma_f64_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -64,7 +64,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 
     // place in the XCD-aware tile order, and which k range of it (same conventions as
     // identity_mfma_f64_kernel: split K over gridDim.y, tail split from tail_base on)
-    const int tiles_m = M / DD_BM, tiles_n = N / DD_BN;
+    const int tiles_m = (M + DD_BM - 1) / DD_BM, tiles_n = (N + DD_BN - 1) / DD_BN;
     int tm, tn;
     int block = (int)blockIdx.x + args.block_base, ksplit_idx = (int)blockIdx.y;
     const bool tail_part = args.tail_splits > 1 && block >= args.tail_base;
@@ -88,16 +88,23 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // wave w owns the 1 KB slot group w of each operand's slice:
     //   k-minor slice: slot 64 w + lane -> line 16 w + lane / 4, physical unit lane % 4
     //   k-major slice: k-row w, physical unit lane
-    auto lane_offset = [&](bool kminor, int64_t ld) {
+    // `lines` of the tile exist (128 but in an edge tile): a line past them is replaced by the last
+    // one inside, in a k-major slice a unit of two lines by the last whole unit (the host admits
+    // k-major operands only with an even number of lines), so that every load stays inside the
+    // operand; what it brings only reaches rows and columns that are not written back
+    auto lane_offset = [&](bool kminor, int64_t ld, int lines) {
         if (kminor) {
             const int line = 16 * wave + (lane >> 2);
             const int u = (lane & 3) ^ ((line >> 2) & 3);
-            return ((uint32_t)line * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
+            const int line_in = line < lines ? line : lines - 1;
+            return ((uint32_t)line_in * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
         }
         const int u = lane ^ ((wave & 1) << 3);
-        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
+        const int u_in = 2 * u < lines ? u : (lines >> 1) - 1;
+        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)(u_in * 2)) * 8u;
     };
-    const uint32_t a_voff = lane_offset(A_KMINOR, args.lda), b_voff = lane_offset(B_KMINOR, args.ldb);
+    const int rows_in = M - row0 < DD_BM ? M - row0 : DD_BM, cols_in = N - col0 < DD_BN ? N - col0 : DD_BN;
+    const uint32_t a_voff = lane_offset(A_KMINOR, args.lda, rows_in), b_voff = lane_offset(B_KMINOR, args.ldb, cols_in);
     // the tile's first stage, and what a stage adds (doubles): 8 k along a k-minor operand's rows,
     // 8 rows of a k-major one
     const double *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0;
@@ -247,6 +254,37 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // of a row of blocks are all read before the first is written back (as "*dst += acc" per
     // element the compiler must keep every store behind the load before it, a chain of 32 round
     // trips to memory).
+    if (rows_in < DD_BM || cols_in < DD_BN) {
+        // an edge tile: element by element, the rows and columns that exist
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            double old[4][4];
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
+                    double *const dst = args.R + (int64_t)(row0 + row) * args.ldr + col0 + col;
+                    const bool in = row < rows_in && col < cols_in;
+                    if (ksplit) {
+                        if (in) unsafeAtomicAdd(dst, acc[mi][ni][v]);
+                    } else {
+                        old[ni][v] = in ? *dst : 0.0;
+                    }
+                }
+            if (!ksplit) {
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
+                        if (row < rows_in && col < cols_in)
+                            args.R[(int64_t)(row0 + row) * args.ldr + col0 + col] = old[ni][v] + acc[mi][ni][v];
+                    }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         double *dst[4];
@@ -272,14 +310,16 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     }
 }
 
-// Whole tiles, whole stages, operands with 16-byte aligned rows (in either layout), per-lane byte
-// offsets that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// Whole stages, operands with 16-byte aligned rows (in either layout; a k-major operand with an
+// even number of lines, so that every 16-byte unit of it is whole), per-lane byte offsets that fit
+// 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
     // (16-byte pieces along each operand's contiguous axis: vecA for A; for B, vec when it is
     // row-major, vecBt when it is stored transposed)
     if (!a.vecA || !(a.transB ? a.vecBt : a.vec)) return false;
-    if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.M % DD_BM || a.N % DD_BN || a.K % DD_BK || a.kchunk % DD_BK) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.K % DD_BK || a.kchunk % DD_BK) return false;
+    if ((a.transA && a.M % 2) || (!a.transB && a.N % 2)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 8
     const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / DD_BM, major_max = (0x7FFFFFFFLL / 8 - DD_BN) / DD_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;
