@@ -78,7 +78,9 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         ksplit_idx = rel / args.tail_blocks;
     }
     if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
-    const int row0 = tm * ID_BM, col0 = tn * ID_BN;
+    // (wave-uniform by construction; said so explicitly, so that everything derived from them --
+    // the operand bases the loads take in scalar registers among it -- stays on the scalar unit)
+    const int row0 = __builtin_amdgcn_readfirstlane(tm * ID_BM), col0 = __builtin_amdgcn_readfirstlane(tn * ID_BN);
     const bool ksplit = gridDim.y > 1 || tail_part;
     int kb = 0;
     if (ksplit) {
@@ -284,35 +286,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // R += acc: the 32 values of a row block are all read before the first is written back (as
     // "*dst += acc" per element the compiler must keep every store behind the load before it and
     // the write-back is a chain of 64 round trips to memory, 15 us of a tile).
-    if (rows_in < ID_BM || cols_in < ID_BN) {
-        // an edge tile: element by element, the rows and columns that exist
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int col = wc * 64 + ni * 32 + li;
-                float *const rcol = args.R + (int64_t)row0 * args.ldr + col0 + col;
-                float old[16];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    const bool in = row < rows_in && col < cols_in;
-                    if (ksplit) {
-                        if (in) unsafeAtomicAdd(rcol + (int64_t)row * args.ldr, acc[mi][ni][v]);
-                    } else {
-                        old[v] = in ? rcol[(int64_t)row * args.ldr] : 0.0f;
-                    }
-                }
-                if (!ksplit) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        if (row < rows_in && col < cols_in) rcol[(int64_t)row * args.ldr] = old[v] + acc[mi][ni][v];
-                    }
-                }
-            }
-        return;
-    }
+    const bool edge = rows_in < ID_BM || cols_in < ID_BN;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         float *dst[2][16];
@@ -321,15 +295,22 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int col = col0 + wc * 64 + ni * 32 + li;
-                const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                dst[ni][v] = args.R + (int64_t)row * args.ldr + col;
+                const int col = wc * 64 + ni * 32 + li;
+                const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                dst[ni][v] = args.R + (int64_t)(row0 + row) * args.ldr + col0 + col;
             }
-        if (ksplit) {
+        if (ksplit || edge) {
+            // (an edge tile adds with atomics too, the elements that exist: R has one owner here, so
+            // the sum is the same single rounding, and an atomic needs no round trip to memory
+            // before the store, which under a per-element mask would be one after the other)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) unsafeAtomicAdd(dst[ni][v], acc[mi][ni][v]);
+                for (int v = 0; v < 16; ++v) {
+                    const int col = wc * 64 + ni * 32 + li;
+                    const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (row < rows_in && col < cols_in) unsafeAtomicAdd(dst[ni][v], acc[mi][ni][v]);
+                }
         } else {
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)

@@ -74,7 +74,9 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         ksplit_idx = rel / args.tail_blocks;
     }
     if (!xcd_tile(block, tiles_m, tiles_n, tm, tn)) return;   // padding: the whole workgroup leaves
-    const int row0 = tm * DD_BM, col0 = tn * DD_BN;
+    // (wave-uniform by construction; said so explicitly, so that everything derived from them --
+    // the operand bases the loads take in scalar registers among it -- stays on the scalar unit)
+    const int row0 = __builtin_amdgcn_readfirstlane(tm * DD_BM), col0 = __builtin_amdgcn_readfirstlane(tn * DD_BN);
     const bool ksplit = gridDim.y > 1 || tail_part;
     int kb = 0;
     if (ksplit) {
@@ -254,48 +256,24 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // of a row of blocks are all read before the first is written back (as "*dst += acc" per
     // element the compiler must keep every store behind the load before it, a chain of 32 round
     // trips to memory).
-    if (rows_in < DD_BM || cols_in < DD_BN) {
-        // an edge tile: element by element, the rows and columns that exist
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            double old[4][4];
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
-                    double *const dst = args.R + (int64_t)(row0 + row) * args.ldr + col0 + col;
-                    const bool in = row < rows_in && col < cols_in;
-                    if (ksplit) {
-                        if (in) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                    } else {
-                        old[ni][v] = in ? *dst : 0.0;
-                    }
-                }
-            if (!ksplit) {
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
-                        if (row < rows_in && col < cols_in)
-                            args.R[(int64_t)(row0 + row) * args.ldr + col0 + col] = old[ni][v] + acc[mi][ni][v];
-                    }
-            }
-        }
-        return;
-    }
+    const bool edge = rows_in < DD_BM || cols_in < DD_BN;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         double *dst[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             dst[v] = args.R + (int64_t)(row0 + wr * 32 + mi * 16 + 4 * v + lh) * args.ldr + col0 + wc * 64 + li;
-        if (ksplit) {
+        if (ksplit || edge) {
+            // (an edge tile adds with atomics too, the elements that exist: R has one owner here, so
+            // the sum is the same single rounding, and an atomic needs no round trip to memory
+            // before the store, which under a per-element mask would be one after the other)
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) unsafeAtomicAdd(dst[v] + ni * 16, acc[mi][ni][v]);
+                for (int v = 0; v < 4; ++v) {
+                    const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
+                    if (row < rows_in && col < cols_in) unsafeAtomicAdd(dst[v] + ni * 16, acc[mi][ni][v]);
+                }
         } else {
             double old[4][4];
 #pragma unroll
