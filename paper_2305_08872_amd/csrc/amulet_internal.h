@@ -137,6 +137,16 @@ inline bool k_split_allowed()
 // ceil(x s) / s rounds.  They add their parts to R with hardware atomics and follow the whole
 // tiles in the same grid, so they start as the last whole tiles finish.  Counted in real tiles:
 // the blocks that pad the XCD parts to equal length come last in launch order and leave at once.
+// A k range per workgroup for the streamed identity kernels: `chunk` (a multiple of the stage,
+// `gran` k) made longer until the last range, K mod chunk, is empty or holds a whole stage too: the
+// kernels multiply the k past a range's last whole stage from values fetched per lane, after
+// streaming at least one stage.
+inline int64_t chunk_with_a_whole_last_stage(int64_t K, int64_t chunk, int gran)
+{
+    while (chunk < K && K % chunk != 0 && K % chunk < gran) chunk += gran;
+    return chunk;
+}
+
 struct TailSplit {
     int64_t base;     // first block (place in the tile order) of the split region
     int64_t blocks;   // places from there to the end of the padded order

@@ -280,15 +280,26 @@ identity_mfma_kernel(const MmlikeArgs args)
     }
 
     // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
-    // R += acc: eight values of a block at a time are all read before the first is written back
-    // (as "*dst += acc" per element the compiler must keep every store behind the load before it,
-    // and the write-back is a chain of 64 round trips to memory).
+    // R += acc.  A whole tile: eight values of a block at a time are all read before the first is
+    // written back (as "*dst += acc" per element the compiler must keep every store behind the
+    // load before it, and the write-back is a chain of 64 round trips to memory).  An edge tile
+    // adds the elements that exist with atomics, like a tile whose K is split: R has one owner
+    // there, so the sum is the same single rounding, and reads under a per-element mask would be
+    // that chain of round trips again.
+    const bool whole = row0 + L::BM <= M && col0 + L::BN <= N;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
             const int col = col0 + wc * 64 + ni * 32 + li;
-            if (col >= N) continue;
+            if (ksplit || !whole) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (row < M && col < N) unsafeAtomicAdd(args.R + (int64_t)row * args.ldr + col, acc[mi][ni][v]);
+                }
+                continue;
+            }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 float old[8];
@@ -296,20 +307,13 @@ identity_mfma_kernel(const MmlikeArgs args)
                 for (int w = 0; w < 8; ++w) {
                     const int v = 8 * h + w;
                     const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    float *dst = args.R + (int64_t)row * args.ldr + col;
-                    if (ksplit) {
-                        if (row < M) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                    } else {
-                        old[w] = row < M ? *dst : 0.0f;
-                    }
+                    old[w] = args.R[(int64_t)row * args.ldr + col];
                 }
-                if (!ksplit) {
 #pragma unroll
-                    for (int w = 0; w < 8; ++w) {
-                        const int v = 8 * h + w;
-                        const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        if (row < M) args.R[(int64_t)row * args.ldr + col] = old[w] + acc[mi][ni][v];
-                    }
+                for (int w = 0; w < 8; ++w) {
+                    const int v = 8 * h + w;
+                    const int row = row0 + wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    args.R[(int64_t)row * args.ldr + col] = old[w] + acc[mi][ni][v];
                 }
             }
         }
@@ -353,7 +357,7 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
         static const double rate3[3] = {0.92, 0.985, 1.0}, rate2[2] = {0.93, 1.0};
         const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, per_unit, per_unit == 3 ? rate3 : rate2);
         if (sp > 1) {
-            const int64_t chunk = ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK;
+            const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK, MI_BK);
             b.kchunk = (int)chunk;
             splits = (int)((a.K + chunk - 1) / chunk);
             launch_grid = dim3((unsigned)grid, (unsigned)splits);
@@ -380,6 +384,11 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     const int64_t round = streamed ? per_unit * (int64_t)compute_units() : (int64_t)compute_units();
     if (splits == 1 && tiles > (streamed ? 2 * per_unit : 4) * (int64_t)compute_units() &&
         choose_tail_split(tiles, grid, round, a.K, MI_BK, t)) {
+        if (streamed) {
+            t.chunk = (int)chunk_with_a_whole_last_stage(a.K, t.chunk, MI_BK);
+            t.splits = (int)((a.K + t.chunk - 1) / t.chunk);
+            t.grid = t.base + t.blocks * t.splits;
+        }
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;

@@ -20,8 +20,10 @@
 //     in lanes 32-63, which land on the two halves of the 64 banks.
 // One barrier per stage, between the stage's two groups of 8 k (see the loop).
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, when K is a whole number
-// of stages; everything else runs identity_mfma_kernel.  M and N need not be whole tiles: a lane
+// Used for operands with 16-byte aligned rows, row-major or transposed, and at least one stage of
+// K; everything else runs identity_mfma_kernel.  K need not be a whole number of stages (the k
+// past the last whole one are multiplied from values each lane fetches itself, see the kernel's
+// end), nor M and N whole tiles: a lane
 // whose line (or 16-byte unit of lines) lies past the edge fetches the last one inside instead, so
 // every load stays inside the operand, what it brings only reaches rows and columns of the tile
 // that do not exist, and those are not written back.
@@ -87,8 +89,11 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         kb = ksplit_idx * args.kchunk;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
     }
+    // whole stages stream through LDS; the k that remain (fewer than a stage, in the last k range
+    // only: the others are whole stages) are multiplied from values each lane fetches itself
     const int n_stages = K > 0 ? K / ID_BK : 0;
-    if (n_stages <= 0) return;
+    const int ktail = K > 0 ? K - n_stages * ID_BK : 0;
+    if (n_stages <= 0) return;   // (the host never makes a k range shorter than a stage)
 
     // ---- what each lane fetches: two A slots and two B slots per stage ---------------------
     // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile:
@@ -237,6 +242,47 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
             bp += b_stage;
             requested = d + 1;
         }
+    // While the first stages are on their way and few registers are live: the k past the last whole
+    // stage (1 .. 15 of them, in the last k range only).  Each matrix instruction `step` multiplies
+    // k = kt + 2 step + lh, and each lane reads its own A and B values of that k from memory (its
+    // row and column clamped into the tile's existing ones, a k past the end read at the last k
+    // and replaced by zero), eight k at a time.
+    if (ktail > 0) {
+        const int kt = kb + n_stages * ID_BK, kend = kb + K;
+        int64_t a_line[2], b_line[2];
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            const int r = wr * 64 + x * 32 + li, c = wc * 64 + x * 32 + li;
+            a_line[x] = row0 + (r < rows_in ? r : rows_in - 1);
+            b_line[x] = col0 + (c < cols_in ? c : cols_in - 1);
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (8 * half >= ktail) break;
+            float av[4][2], bv[4][2];
+#pragma unroll
+            for (int step = 0; step < 4; ++step) {
+                const int k = kt + 8 * half + 2 * step + lh;
+                const bool ok = k < kend;
+                const int64_t kc = ok ? k : kend - 1;
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const float a = TA ? args.A[kc * args.lda + a_line[x]] : args.A[a_line[x] * args.lda + kc];
+                    const float b = TB ? args.B[b_line[x] * args.ldb + kc] : args.B[kc * args.ldb + b_line[x]];
+                    av[step][x] = ok ? a : 0.0f;
+                    bv[step][x] = ok ? b : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int step = 0; step < 4; ++step)
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[step][mi], bv[step][ni], acc[mi][ni], 0, 0, 0);
+        }
+    }
+
     wait_stage(0, requested - 1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -324,13 +370,13 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     }
 }
 
-// Whole stages, operands with 16-byte aligned rows (in either layout; a k-major operand with a
-// multiple of four lines, so that every 16-byte unit of it is whole), per-lane byte offsets that
-// fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// At least one stage of K, operands with 16-byte aligned rows (in either layout; a k-major operand
+// with a multiple of four lines, so that every 16-byte unit of it is whole), per-lane byte offsets
+// that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_dma_eligible(const MmlikeArgs &a)
 {
     if (!a.vec || !a.vecA) return false;
-    if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || a.K % ID_BK || a.kchunk % ID_BK) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || (a.kchunk < a.K && a.kchunk % ID_BK)) return false;
     if ((a.transA && a.M % 4) || (!a.transB && a.N % 4)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 16
     const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / ID_BM, major_max = (0x7FFFFFFFLL / 4 - ID_BN) / ID_BK;

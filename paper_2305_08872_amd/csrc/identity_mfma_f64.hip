@@ -204,13 +204,29 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
         __syncthreads();
     }
 
-    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc: the 8 values
-    // of two blocks are all read before the first is written back (as "*dst += acc" per element
-    // the write-back is a chain of 32 round trips to memory).
+    // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc.  A whole tile:
+    // the 8 values of two blocks are all read before the first is written back (as "*dst += acc"
+    // per element the write-back is a chain of 32 round trips to memory).  An edge tile adds the
+    // elements that exist with atomics, like a tile whose K is split: R has one owner there, so
+    // the sum is the same single rounding, and reads under a per-element mask would be that chain
+    // of round trips again.
+    const bool whole = row0 + DI_BM <= M && col0 + DI_BN <= N;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int np = 0; np < 2; ++np) {
+            if (ksplit || !whole) {
+#pragma unroll
+                for (int nq = 0; nq < 2; ++nq)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int ni = 2 * np + nq;
+                        const int col = col0 + wc * 64 + ni * 16 + li;
+                        const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
+                        if (row < M && col < N) unsafeAtomicAdd(args.R + (int64_t)row * args.ldr + col, acc[mi][ni][v]);
+                    }
+                continue;
+            }
             double old[2][4];
 #pragma unroll
             for (int nq = 0; nq < 2; ++nq)
@@ -219,25 +235,17 @@ identity_mfma_f64_kernel(const MmlikeArgsF64 args)
                     const int ni = 2 * np + nq;
                     const int col = col0 + wc * 64 + ni * 16 + li;
                     const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
-                    double *dst = args.R + (int64_t)row * args.ldr + col;
-                    const bool live = row < M && col < N;
-                    if (ksplit) {
-                        if (live) unsafeAtomicAdd(dst, acc[mi][ni][v]);
-                    } else {
-                        old[nq][v] = live ? *dst : 0.0;
-                    }
+                    old[nq][v] = args.R[(int64_t)row * args.ldr + col];
                 }
-            if (!ksplit) {
 #pragma unroll
-                for (int nq = 0; nq < 2; ++nq)
+            for (int nq = 0; nq < 2; ++nq)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int ni = 2 * np + nq;
-                        const int col = col0 + wc * 64 + ni * 16 + li;
-                        const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
-                        if (row < M && col < N) args.R[(int64_t)row * args.ldr + col] = old[nq][v] + acc[mi][ni][v];
-                    }
-            }
+                for (int v = 0; v < 4; ++v) {
+                    const int ni = 2 * np + nq;
+                    const int col = col0 + wc * 64 + ni * 16 + li;
+                    const int row = row0 + wr * 32 + mi * 16 + 4 * v + lh;
+                    args.R[(int64_t)row * args.ldr + col] = old[nq][v] + acc[mi][ni][v];
+                }
         }
 }
 
@@ -272,7 +280,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
         static const double rate2[2] = {0.93, 1.0};
         const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, 2, rate2, 30.0, 0.34);
         if (sp > 1) {
-            const int64_t chunk = ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK;
+            const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK, DI_BK);
             b.kchunk = (int)chunk;
             splits = (int)((a.K + chunk - 1) / chunk);
             launch_grid = dim3(grid, (unsigned)splits);
@@ -297,6 +305,11 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     TailSplit t;
     if (splits == 1 && n_tiles > 4 * (int64_t)compute_units() &&
         choose_tail_split(n_tiles, grid, (streamed ? 2 : 1) * (int64_t)compute_units(), a.K, DI_BK, t)) {
+        if (streamed) {
+            t.chunk = (int)chunk_with_a_whole_last_stage(a.K, t.chunk, DI_BK);
+            t.splits = (int)((a.K + t.chunk - 1) / t.chunk);
+            t.grid = t.base + t.blocks * t.splits;
+        }
         b.tail_base = (int)t.base;
         b.tail_blocks = (int)t.blocks;
         b.tail_splits = t.splits;

@@ -19,8 +19,9 @@
 //     of the banks.
 // One barrier per stage, between its two matrix steps.
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, when K is a whole number
-// of stages (M and N need not be whole tiles); everything else runs identity_mfma_f64_kernel.
+// Used for operands with 16-byte aligned rows, row-major or transposed, and at least one stage of K
+// (K need not be a whole number of stages, nor M and N whole tiles); everything else runs
+// identity_mfma_f64_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -83,8 +84,11 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         kb = ksplit_idx * args.kchunk;
         K = (K - kb < args.kchunk) ? K - kb : args.kchunk;
     }
+    // whole stages stream through LDS; the k that remain (fewer than a stage, in the last k range
+    // only: the others are whole stages) are multiplied from values each lane fetches itself
     const int n_stages = K > 0 ? K / DD_BK : 0;
-    if (n_stages <= 0) return;
+    const int ktail = K > 0 ? K - n_stages * DD_BK : 0;
+    if (n_stages <= 0) return;   // (the host never makes a k range shorter than a stage)
 
     // ---- what each lane fetches: one A slot and one B slot per stage -----------------------
     // wave w owns the 1 KB slot group w of each operand's slice:
@@ -209,6 +213,41 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
             bp += b_stage;
             requested = d + 1;
         }
+    // While the first stages are on their way and few registers are live: the k past the last whole
+    // stage (1 .. 7 of them, in the last k range only).  Matrix instruction `step` multiplies
+    // k = kt + 4 step + lh, and each lane reads its own A and B values of that k from memory (its
+    // row and column clamped into the tile's existing ones, a k past the end read at the last k
+    // and replaced by zero).
+    if (ktail > 0) {
+        const int kt = kb + n_stages * DD_BK, kend = kb + K;
+#pragma unroll
+        for (int step = 0; step < 2; ++step) {
+            if (4 * step >= ktail) break;
+            const int k = kt + 4 * step + lh;
+            const bool ok = k < kend;
+            const int64_t kc = ok ? k : kend - 1;
+            double av[2], bv[4];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const int r = wr * 32 + mi * 16 + li;
+                const int64_t line = row0 + (r < rows_in ? r : rows_in - 1);
+                const double a = TA ? args.A[kc * args.lda + line] : args.A[line * args.lda + kc];
+                av[mi] = ok ? a : 0.0;
+            }
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+                const int c = wc * 64 + ni * 16 + li;
+                const int64_t line = col0 + (c < cols_in ? c : cols_in - 1);
+                const double b = TB ? args.B[line * args.ldb + kc] : args.B[kc * args.ldb + line];
+                bv[ni] = ok ? b : 0.0;
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+        }
+    }
     wait_stage(0, requested - 1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -288,15 +327,15 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     }
 }
 
-// Whole stages, operands with 16-byte aligned rows (in either layout; a k-major operand with an
-// even number of lines, so that every 16-byte unit of it is whole), per-lane byte offsets that fit
-// 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// At least one stage of K, operands with 16-byte aligned rows (in either layout; a k-major operand
+// with an even number of lines, so that every 16-byte unit of it is whole), per-lane byte offsets
+// that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
     // (16-byte pieces along each operand's contiguous axis: vecA for A; for B, vec when it is
     // row-major, vecBt when it is stored transposed)
     if (!a.vecA || !(a.transB ? a.vecBt : a.vec)) return false;
-    if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || a.K % DD_BK || a.kchunk % DD_BK) return false;
+    if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || (a.kchunk < a.K && a.kchunk % DD_BK)) return false;
     if ((a.transA && a.M % 2) || (!a.transB && a.N % 2)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 8
     const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / DD_BM, major_max = (0x7FFFFFFFLL / 8 - DD_BN) / DD_BK;

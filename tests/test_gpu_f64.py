@@ -393,8 +393,8 @@ def test_f64_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch)
 
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
 def test_f64_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
-    """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS runs on whole 8-k
-    stages and operands with aligned rows, in any of the four operand layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
+    """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS runs on operands
+    with aligned rows and at least one 8-k stage, in any of the four operand layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
     and a non-zero R_in, few tiles with a long K (every tile split over workgroups), a few more
     tiles than compute units (the last round's tiles split), and exact data bit for bit.  Every
     output is checked."""
@@ -402,7 +402,10 @@ def test_f64_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
              # M and N that are not whole tiles: fewer rows than a tile, one more row or unit than
              # whole tiles, odd sizes (streamed only where the operand's lines run along k), a split
              # K with edge tiles, a split last round with edge tiles
-             (100, 130, 64, 0), (257, 258, 200, 2), (129, 131, 32, 0), (60, 4098, 4096, 0), (1300, 3202, 1104, 6)]
+             (100, 130, 64, 0), (257, 258, 200, 2), (129, 131, 32, 0), (60, 4098, 4096, 0), (1300, 3202, 1104, 6),
+             # K that is no whole number of 8-k stages: one stage and a bit, padded pitches, a split K,
+             # a split last round, together with edge tiles
+             (128, 128, 12, 0), (256, 384, 202, 2), (128, 256, 4102, 0), (1408, 3200, 1106, 6), (100, 130, 1034, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         A, B, th, dis, R_in = make_case(0, M, N, K, 9960 + idx)
         As = np.ascontiguousarray(A.T) if tA else A

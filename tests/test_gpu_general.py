@@ -264,7 +264,7 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
 def test_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
     """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: rings
-    of 3 and 4 stages) runs on whole 16-k stages and operands with aligned rows, in any of the
+    of 3 and 4 stages) runs on operands with aligned rows and at least one 16-k stage, in any of the
     four operand layouts.  Cases: fewer stages than the ring holds,
     one tile, several tiles with padded pitches and a non-zero R_in, few tiles with a long K (every
     tile split over workgroups), and a few more tiles than compute units (the last round's tiles
@@ -275,7 +275,11 @@ def test_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
              # what exists): fewer rows than a tile, one more row or unit than whole tiles, sizes
              # that are no multiple of four (streamed only where the operand's lines run along k),
              # a split K with edge tiles, a split last round with edge tiles
-             (100, 132, 64, 0), (257, 260, 208, 4), (130, 131, 32, 0), (60, 4100, 4096, 0), (1300, 3204, 1104, 8)]
+             (100, 132, 64, 0), (257, 260, 208, 4), (130, 131, 32, 0), (60, 4100, 4096, 0), (1300, 3204, 1104, 8),
+             # K that is no whole number of 16-k stages (the k past the last whole stage are multiplied
+             # from values each lane fetches itself): one stage and a bit, padded pitches, a split K,
+             # a split last round, together with edge tiles
+             (128, 128, 20, 0), (256, 384, 204, 4), (128, 256, 4100, 0), (1408, 3200, 1108, 8), (100, 132, 1036, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, M, N, K, 6500 + idx)
         R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
