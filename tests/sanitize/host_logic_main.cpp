@@ -146,10 +146,20 @@ int main()
                 const int sp = amulet::choose_stream_split(part, 32, K, cap, cap == 3 ? rate3 : rate2);
                 CHECK(sp >= 1 && sp <= 1024 && (sp == 1 || K / sp >= 128));
             }
+    // ---- a k range of the streamed identity kernels never ends in less than a stage
+    for (int64_t K = 16; K <= 3000; ++K)
+        for (int sp = 2; sp <= 40; ++sp) {
+            const int64_t c0 = ((K + sp - 1) / sp + 15) / 16 * 16;
+            const int64_t chunk = amulet::chunk_with_a_whole_last_stage(K, c0, 16);
+            CHECK(chunk >= c0 && chunk % 16 == 0);
+            CHECK(chunk >= K || K % chunk == 0 || K % chunk >= 16);
+        }
+    CHECK(amulet::chunk_with_a_whole_last_stage(1028, 128, 16) == 144);   // 1028 = 8 x 128 + 4
     // ---- every identity launch plan (vector-ALU shapes, both matrix-core tiles, the streamed
     // kernel and what it falls back to), fp32 and fp64, refused at the launch
     const int64_t id_sizes[][3] = {{1, 1, 1}, {300, 700, 200}, {4096, 4096, 4096}, {2048, 2048, 2048}, {1408, 3200, 1104},
-                                   {128, 256, 100000}, {1536, 1536, 4096}, {8192, 8192, 8192}, {2147418111LL, 128, 16}};
+                                   {128, 256, 100000}, {1536, 1536, 4096}, {8192, 8192, 8192}, {2147418111LL, 128, 16},
+                                   {4000, 4100, 4004}, {128, 256, 1028}, {1300, 3204, 1108}};
     double *dp = (double *)(uintptr_t)4096;
     for (auto &sz : id_sizes)
         for (int layout = 0; layout < 4; ++layout) {
