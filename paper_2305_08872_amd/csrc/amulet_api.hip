@@ -199,7 +199,7 @@ static int check_mmlike(const MmlikeCall &c)
 }
 
 // phases of the persistent join-count kernels (see count_i8_dma_persistent_kernel)
-static int g_pers_halves = 1, g_pers_xcds = 2;
+static const int kPersPhases[4] = {8, 2, 2, 16};   // groups, stages between groups, XCD modulus, XCD span (sixteenths)
 
 // m_load / n_load: rows of A / columns of B that exist in memory (0: just M, N)
 static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
@@ -217,11 +217,16 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.vecR = (aligned16(R) && ldr % 4 == 0) ? 1 : 0;
     a.kchunk = (int)K;
     a.block_base = 0;
-    a.pers_halves = g_pers_halves;
-    a.pers_xcds = g_pers_xcds;
-    if (const char *e = getenv("AMULET_I8_PHASES")) {   // diagnostic override, "halves,xcds"
-        int h = 1, x = 1;
-        if (sscanf(e, "%d,%d", &h, &x) == 2 && x >= 1 && x <= 8) { a.pers_halves = h ? 1 : 0; a.pers_xcds = x; }
+    a.pers_groups = kPersPhases[0];
+    a.pers_group_stages = kPersPhases[1];
+    a.pers_xcds = kPersPhases[2];
+    a.pers_xcd_span = kPersPhases[3];
+    if (const char *e = getenv("AMULET_I8_PHASES")) {   // diagnostic override, "groups,stages,xcds,span"
+        int g = 1, st = 0, x = 1, sp = 0;
+        if (sscanf(e, "%d,%d,%d,%d", &g, &st, &x, &sp) == 4 && g >= 1 && g <= 64 && st >= 0 && st <= 64 && x >= 1 && x <= 8 &&
+            sp >= 0 && sp <= 16) {
+            a.pers_groups = g; a.pers_group_stages = st; a.pers_xcds = x; a.pers_xcd_span = sp;
+        }
     }
     hipError_t e = launch_count_i8(shape, a, (hipStream_t)stream);
     g_last_hip_error = e;

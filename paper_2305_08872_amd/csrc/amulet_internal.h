@@ -307,9 +307,10 @@ struct CountArgs {
     int vecR;        // 1 when R and its row pitch allow 16-byte accesses
     int kchunk;      // k range of one workgroup when a launch splits K (set by the launcher)
     int block_base;  // added to blockIdx.x (launch_row_of_blocks)
-    // persistent streamed kernel: workgroups of the second half of an XCD's slots start half a
-    // tile out of phase (pers_halves), XCDs are spread over pers_xcds further phases
-    int pers_halves, pers_xcds;
+    // persistent streamed kernel, where in its first tile's k range a workgroup starts: the slots
+    // of an XCD in pers_groups groups, pers_group_stages stages (of 64 k) apart, and XCD x another
+    // (x % pers_xcds) * pers_xcd_span / pers_xcds sixteenths of the range
+    int pers_groups, pers_group_stages, pers_xcds, pers_xcd_span;
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)

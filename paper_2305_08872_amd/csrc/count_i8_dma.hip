@@ -400,11 +400,16 @@ count_i8_dma_kernel(const CountArgs args)
 // write-back together, and the launch alternates between a phase in which only the matrix cores
 // work and one in which only the memory system does (the read-modify-write of R ran at HBM
 // speed for a third of the launch, with the matrix cores idle).  Here a workgroup's first item is
-// only a leading fraction `phase / 16` of its first tile's k range, and the rest of that range is
-// its last item (same owner, plain adds: "+=" makes a tile in two passes as good as in one), so
-// that from then on the workgroups of different phases write back at different times: the two
-// workgroups sharing a compute unit half a tile apart (`halves`: one multiplies while the other
-// writes), and the XCDs spread over the remainder (`xcds` phases).
+// only a leading part of its first tile's k range, and the rest of that range is its last item
+// (same owner, plain adds: "+=" makes a tile in two passes as good as in one), so that from then
+// on workgroups of different phases write back at different times.  The phases: odd XCDs half a
+// tile behind even ones, and within an XCD the slots in eight groups two stages (about a
+// microsecond) apart -- close enough in k that the groups still find each other's operand lines
+// in the L2 (workgroups half a tile apart do not: the L2 holds about twenty stages of an XCD's
+// traffic), far enough that their write-backs do not start together.  Measured (ms; no phases /
+// halves of an XCD's slots half a tile apart and XCD pairs a quarter / this arrangement):
+// 8192 x 8192 x 4096 0.236 / 0.2215 / 0.2125, x 1024 0.132 / 0.135 / 0.124, x 8192 0.373 / 0.356 / 0.343,
+// 16384 x 8192 x 4096 0.447 / 0.430 / 0.395, 16384 x 16384 x 4096 0.834 / 0.820 / 0.832.
 template <int WR, int NSTAGE>
 __global__ void __launch_bounds__(256 * WR) __attribute__((amdgpu_waves_per_eu(4, 4)))
 count_i8_dma_persistent_kernel(const CountArgs args)
@@ -421,11 +426,10 @@ count_i8_dma_persistent_kernel(const CountArgs args)
         col0 = tn * DM_BN;
         return tn < tiles_n && tm < tiles_m;
     };
-    int phase = 0;                               // sixteenths of a tile's k range
-    if (args.pers_halves && 2 * slot >= n_slots) phase += 8;
-    if (args.pers_xcds > 1) phase += (xcd % args.pers_xcds) * (args.pers_halves ? 8 : 16) / args.pers_xcds;
-    phase &= 15;
-    const int kq = (int)((int64_t)(args.K / DM_BK) * phase / 16) * DM_BK;
+    const int n_st = args.K / DM_BK;             // stages of a tile's k range
+    int phase = (slot * args.pers_groups / n_slots) * args.pers_group_stages;   // in stages
+    if (args.pers_xcds > 1) phase += (int)((int64_t)n_st * ((xcd % args.pers_xcds) * args.pers_xcd_span / args.pers_xcds) / 16);
+    const int kq = (phase % n_st) * DM_BK;
     int row0, col0;
     const int n_mine = slot < places ? (places - slot + n_slots - 1) / n_slots : 0;   // places slot, slot + n_slots, ...
     const bool split_first = kq > 0 && n_mine > 0 && tile_at(slot, row0, col0);
