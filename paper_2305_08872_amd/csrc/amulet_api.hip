@@ -75,9 +75,12 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
         const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (tiles128 < 256) return 4;
-        // (from two whole rounds of 256 x 256 tiles on: the persistent form of that kernel, whose
-        // workgroups walk their tiles out of phase: 8192 x 8192 x 4096 0.242 against 0.249 ms)
-        return (tiles256 >= 512 && tiles256 % 256 == 0) ? 8 : 6;
+        // (from three rounds of 256 x 256 tiles on: the persistent form of that kernel, whose
+        // workgroups walk their tiles out of phase; measured, persistent against one tile per
+        // workgroup, ms: 768 tiles x K = 8192 0.265 / 0.280, 896 x 4096 0.204 / 0.213, 1024 0.2125 /
+        // 0.230, 1152 0.249 / 0.267, 1408 0.296 / 0.320, 1536 0.312 / 0.337; below that the one-tile
+        // kernel is ahead: 512 tiles 0.125 / 0.121, 576 0.156 / 0.154, 640 x K = 2048 0.114 / 0.106)
+        return tiles256 >= 768 ? 8 : 6;
     }
     // a dense contraction: matrix cores, 128 x 128 tile, operands streamed HBM -> LDS where the
     // problem allows it (whole tiles, aligned row-major operands; the register-staged kernel
