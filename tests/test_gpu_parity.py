@@ -250,16 +250,21 @@ def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
         assert np.array_equal(dR.cpu().numpy(), R_ref), (M, N, K)
 
 
-@pytest.mark.parametrize("phases", ["1,1", "0,1", "1,4", "0,8", "1,2"])
-@pytest.mark.parametrize("shape", [8, None])
+@pytest.mark.parametrize("phases", ["1,0,1,0", "2,2,2,8", "8,2,2,16", "4,1,8,16", "16,3,4,12"])
+@pytest.mark.parametrize("shape", [8, 108, None])
 def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     """Sizes large enough for the persistent streamed kernels (every workgroup walks at least two
     tiles of its XCD's part), with ragged edges around the whole-tile interior and a K of five
     stages, so that a workgroup's first tile is summed in two passes (2 + 3 stages, or 1 + 4 ...
-    by phase).  Every phase arrangement, full int8 value range, non-zero R_in, bit-exact; the row
-    and column checksums cover the whole matrix, sampled rows and columns go against the oracle."""
+    by phase).  Phase arrangements "slot groups, stages between them, XCD modulus, XCD span in
+    sixteenths of K" (none, coarse, the default, fine, odd), full int8 value range, non-zero R_in,
+    bit-exact; the row and column checksums cover the whole matrix, sampled rows and columns go
+    against the oracle.  Shape 108: shape 8 on a tile count that is no whole number of rounds
+    (22 x 32 tiles: the XCDs' parts hold padding places and their workgroups walk 2 or 3 tiles)."""
     monkeypatch.setenv("AMULET_I8_PHASES", phases)
-    M, N, K = (8192 + 77, 4096 + 33, 320) if shape is not None else (8192, 8192, 320)
+    M, N, K = {8: (8192 + 77, 4096 + 33, 320), 108: (5632 + 5, 8192 + 1, 320), None: (8192, 8192, 320)}[shape]
+    if shape == 108:
+        shape = 8
     g = np.random.Generator(np.random.PCG64(377 + (shape or 0)))
     A = g.integers(-128, 128, (M, K)).astype(np.int8)
     B = g.integers(-128, 128, (K, N)).astype(np.int8)
