@@ -303,9 +303,11 @@ int amulet_mmlike_f64_autopack(int task, int thres_form, int trans_a, int trans_
  * workload is 0/1 indicators), int32 result, exact (wraps modulo 2^32 only if
  * the true sum leaves int32).  A is M x K (lda >= K), B is K x N (ldb >= N),
  * R is M x N int32 (ldr >= N).
- * (Diagnostic: the environment variable AMULET_I8_PHASES="h,x", h in {0,1},
- * x in 1..8, overrides how the persistent kernels of large problems spread
- * their workgroups' write-backs in time; it changes timing only, never results.)
+ * (Diagnostic: the environment variable AMULET_I8_PHASES="g,s,x,h" -- g slot
+ * groups per XCD, s 64-k stages between them, XCD modulus x in 1..8, XCD span h
+ * in sixteenths of K -- overrides how the persistent kernel of large problems
+ * spreads its workgroups' write-backs in time; it changes timing only, never
+ * results.)
  */
 int amulet_count_i8(int64_t M, int64_t N, int64_t K,
                     const int8_t *A, int64_t lda,
