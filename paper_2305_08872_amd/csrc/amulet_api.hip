@@ -83,8 +83,8 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         return tiles256 >= 768 ? 8 : 6;
     }
     // a dense contraction: matrix cores, 128 x 128 tile, operands streamed HBM -> LDS where the
-    // problem allows it (whole tiles, aligned row-major operands; the register-staged kernel
-    // otherwise).  The 256 x 256 tile measures 1-3 % behind even at 8192^3; the selector tries all.
+    // problem allows it (operands with 16-byte aligned rows in any layout, at least a stage of K;
+    // the register-staged kernel otherwise).  The 256 x 256 tile measures 1-3 % behind even at 8192^3; the selector tries all.
     if (task == TASK_IDENTITY) {
         // Ring of 3 stages (three workgroups per compute unit, 768 at a time) except between one
         // and three rounds of the ring of 4 (512 at a time), where whole rounds matter and the

@@ -320,7 +320,7 @@ identity_mfma_kernel(const MmlikeArgs args)
 }
 
 // `dma_stages` > 0: run the streamed kernel (identity_mfma_dma.hip) with a ring of that many
-// stages where the problem allows it (128 x 128 tile; whole tiles, aligned rows, either layout).
+// stages where the problem allows it (128 x 128 tile; aligned rows, any layout, any M, N and K >= 16).
 template <int G, bool TA, bool TB>
 static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hipStream_t s)
 {

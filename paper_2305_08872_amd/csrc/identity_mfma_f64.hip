@@ -256,7 +256,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     MmlikeArgsF64 b = a;
     int splits = 1;
     b.kchunk = a.K;
-    // The streamed kernel where the problem allows it (row-major operands, whole tiles): two
+    // The streamed kernel where the problem allows it (aligned rows, any layout, any M, N and K >= 8): two
     // workgroups to a compute unit.
     bool streamed = false;
     streamed = identity_f64_dma_eligible(b);
