@@ -20,8 +20,8 @@
 //     in lanes 32-63, which land on the two halves of the 64 banks.
 // One barrier per stage, between the stage's two groups of 8 k (see the loop).
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, and at least one stage of
-// K; everything else runs identity_mfma_kernel.  K need not be a whole number of stages (the k
+// Used for row-major or transposed operands of any alignment and size with at least one stage of
+// K (and four lines in an operand whose lines run across k); everything else runs identity_mfma_kernel.  K need not be a whole number of stages (the k
 // past the last whole one are multiplied from values each lane fetches itself, see the kernel's
 // end), nor M and N whole tiles: a lane
 // whose line (or 16-byte unit of lines) lies past the edge fetches the last one inside instead, so
@@ -99,9 +99,13 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile:
     //   k-minor tile: slot 64 j + lane -> line 16 j + lane / 4, physical unit lane % 4
     //   k-major tile: slot 64 j + lane -> k 2 j + lane / 32, physical unit lane % 32
-    // `lines` of the tile exist (128 but in an edge tile): a line past them is replaced by the last
-    // one inside, in a k-major tile a unit of four lines by the last whole unit (the host admits
-    // k-major operands only with a multiple of four lines)
+    // `lines` of the tile exist (128 but in an edge tile).  k-minor: a line past them is replaced
+    // by the last one inside.  k-major: a unit of four lines that would end past them is fetched
+    // as the four lines that end AT the edge (a 16-byte piece may start at any 4-byte aligned
+    // address), so a unit the edge cuts holds its existing lines shifted up by 4 - lines % 4
+    // places -- the fragment reads of those lines look there (`edge_shift` below) -- and nothing
+    // is read past a row's last element.  A tile with fewer than four lines takes the lines before
+    // it in as well (`lead`: the base moves back; the operand has at least four, the host checks).
     auto lane_offset = [&](bool kminor, int j, int64_t ld, int lines) {
         if (kminor) {
             const int line = 16 * j + (lane >> 2);
@@ -111,10 +115,12 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         }
         const int k = 2 * j + (lane >> 5);
         const int u = (lane & 31) ^ (((k >> 2) & 1) << 3);
-        const int u_in = 4 * u < lines ? u : (lines >> 2) - 1;
-        return ((uint32_t)k * (uint32_t)ld + (uint32_t)(u_in * 4)) * 4u;
+        const int lead = lines < 4 ? 4 - lines : 0;
+        const int start = 4 * u + 4 <= lines ? 4 * u + lead : lines - 4 + lead;
+        return ((uint32_t)k * (uint32_t)ld + (uint32_t)start) * 4u;
     };
     const int rows_in = M - row0 < ID_BM ? M - row0 : ID_BM, cols_in = N - col0 < ID_BN ? N - col0 : ID_BN;
+    const int a_lead = !A_KMINOR && rows_in < 4 ? 4 - rows_in : 0, b_lead = !B_KMINOR && cols_in < 4 ? 4 - cols_in : 0;
     uint32_t a_voff[2], b_voff[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -123,8 +129,8 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     }
     // the tile's first stage, and what a stage adds (floats): 16 k along a k-minor operand's rows,
     // 16 rows of a k-major one
-    const float *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0;
-    const float *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0;
+    const float *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0 - a_lead;
+    const float *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0 - b_lead;
     const int64_t a_stage = A_KMINOR ? (int64_t)ID_BK : (int64_t)ID_BK * args.lda;
     const int64_t b_stage = B_KMINOR ? (int64_t)ID_BK : (int64_t)ID_BK * args.ldb;
 
@@ -153,15 +159,17 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     //   k-minor: the four k of a group are one 16-byte read per block;
     //   k-major: one 4-byte read per (t, block).
     auto minor_off = [&](int line, int g) { return line * 64 + (((2 * g + lh) ^ ((line >> 2) & 3)) * 16); };   // + blk * 2048
-    auto major_off = [&](int line0, int blk) {
+    auto major_off = [&](int line0, int blk, int lines) {
         const int unit = (line0 >> 2) + blk * 8 + (li >> 2);
-        return (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + (li & 3) * 4;   // + (8g + t) * 512
+        // (a line of the unit the tile's edge cuts sits 4 - lines % 4 places further up)
+        const int edge_shift = (lines & 3) && line0 + blk * 32 + li >= (lines & ~3) ? 4 - (lines & 3) : 0;
+        return (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + ((li & 3) + edge_shift) * 4;   // + (8g + t) * 512
     };
     int a_off[2], b_off[2];   // k-minor: per group g; k-major: per block
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-        a_off[x] = A_KMINOR ? minor_off(wr * 64 + li, x) : major_off(wr * 64, x);
-        b_off[x] = ID_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x) : major_off(wc * 64, x));
+        a_off[x] = A_KMINOR ? minor_off(wr * 64 + li, x) : major_off(wr * 64, x, rows_in);
+        b_off[x] = ID_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x) : major_off(wc * 64, x, cols_in));
     }
     // One group's fragments of an operand: a k-minor operand's as two 16-byte values (block, then
     // component t), a k-major one's as 4 x 2 floats (t, block).
@@ -370,14 +378,14 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     }
 }
 
-// At least one stage of K, operands with 16-byte aligned rows (in either layout; a k-major operand
-// with a multiple of four lines, so that every 16-byte unit of it is whole), per-lane byte offsets
-// that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// At least one stage of K, at least four lines in an operand whose lines run across k (its 16-byte
+// pieces are four lines wide), per-lane byte offsets that fit 31 bits, and k ranges (`kchunk`, when
+// the launch splits K) of whole stages.  Rows need not be 16-byte aligned: a direct-to-LDS load
+// of 16 bytes takes any 4-byte aligned address.
 bool identity_dma_eligible(const MmlikeArgs &a)
 {
-    if (!a.vec || !a.vecA) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || (a.kchunk < a.K && a.kchunk % ID_BK)) return false;
-    if ((a.transA && a.M % 4) || (!a.transB && a.N % 4)) return false;
+    if ((a.transA && a.M < 4) || (!a.transB && a.N < 4)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 16
     const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / ID_BM, major_max = (0x7FFFFFFFLL / 4 - ID_BN) / ID_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;

@@ -19,8 +19,8 @@
 //     of the banks.
 // One barrier per stage, between its two matrix steps.
 //
-// Used for operands with 16-byte aligned rows, row-major or transposed, and at least one stage of K
-// (K need not be a whole number of stages, nor M and N whole tiles); everything else runs
+// Used for row-major or transposed operands of any alignment and size with at least one stage of K
+// (and two lines in an operand whose lines run across k); everything else runs
 // identity_mfma_f64_kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -94,10 +94,14 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // wave w owns the 1 KB slot group w of each operand's slice:
     //   k-minor slice: slot 64 w + lane -> line 16 w + lane / 4, physical unit lane % 4
     //   k-major slice: k-row w, physical unit lane
-    // `lines` of the tile exist (128 but in an edge tile): a line past them is replaced by the last
-    // one inside, in a k-major slice a unit of two lines by the last whole unit (the host admits
-    // k-major operands only with an even number of lines), so that every load stays inside the
-    // operand; what it brings only reaches rows and columns that are not written back
+    // `lines` of the tile exist (128 but in an edge tile), and every load stays inside the operand.
+    // k-minor: a line past them is replaced by the last one inside.  k-major: a unit of two lines
+    // that would end past them is fetched as the two lines that end AT the edge (a 16-byte piece
+    // may start at any 8-byte aligned address), so the unit an odd edge cuts holds its existing
+    // line one place further up -- the fragment reads of that line look there (`edge_shift`
+    // below).  A tile of one line takes the line before it in as well (`lead`: the base moves
+    // back; the operand has at least two, the host checks).  What the lanes past the edge bring
+    // only reaches rows and columns that are not written back.
     auto lane_offset = [&](bool kminor, int64_t ld, int lines) {
         if (kminor) {
             const int line = 16 * wave + (lane >> 2);
@@ -106,15 +110,17 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
             return ((uint32_t)line_in * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
         }
         const int u = lane ^ ((wave & 1) << 3);
-        const int u_in = 2 * u < lines ? u : (lines >> 1) - 1;
-        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)(u_in * 2)) * 8u;
+        const int lead = lines < 2 ? 2 - lines : 0;
+        const int start = 2 * u + 2 <= lines ? 2 * u + lead : lines - 2 + lead;
+        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)start) * 8u;
     };
     const int rows_in = M - row0 < DD_BM ? M - row0 : DD_BM, cols_in = N - col0 < DD_BN ? N - col0 : DD_BN;
+    const int a_lead = !A_KMINOR && rows_in < 2 ? 2 - rows_in : 0, b_lead = !B_KMINOR && cols_in < 2 ? 2 - cols_in : 0;
     const uint32_t a_voff = lane_offset(A_KMINOR, args.lda, rows_in), b_voff = lane_offset(B_KMINOR, args.ldb, cols_in);
     // the tile's first stage, and what a stage adds (doubles): 8 k along a k-minor operand's rows,
     // 8 rows of a k-major one
-    const double *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0;
-    const double *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0;
+    const double *const a_base = A_KMINOR ? args.A + (int64_t)row0 * args.lda + kb : args.A + (int64_t)kb * args.lda + row0 - a_lead;
+    const double *const b_base = B_KMINOR ? args.B + (int64_t)col0 * args.ldb + kb : args.B + (int64_t)kb * args.ldb + col0 - b_lead;
     const int64_t a_stage = A_KMINOR ? (int64_t)DD_BK : (int64_t)DD_BK * args.lda;
     const int64_t b_stage = B_KMINOR ? (int64_t)DD_BK : (int64_t)DD_BK * args.ldb;
 
@@ -145,16 +151,18 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         const int k = 4 * g + lh;
         return line * 64 + (((k >> 1) ^ ((line >> 2) & 3)) * 16) + (k & 1) * 8;
     };
-    auto major_off = [&](int line0, int blk) {
+    auto major_off = [&](int line0, int blk, int lines) {
         const int unit = (line0 >> 1) + blk * 8 + (li >> 1);
-        return lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + (li & 1) * 8;
+        // (the line of the unit an odd edge cuts sits one place further up)
+        const int edge_shift = (lines & 1) && line0 + blk * 16 + li >= (lines & ~1) ? 1 : 0;
+        return lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + ((li & 1) + edge_shift) * 8;
     };
     int a_off[2], b_off[4];   // k-minor: per step g; k-major: per block
 #pragma unroll
-    for (int x = 0; x < 2; ++x) a_off[x] = A_KMINOR ? minor_off(wr * 32 + li, x) : major_off(wr * 32, x);
+    for (int x = 0; x < 2; ++x) a_off[x] = A_KMINOR ? minor_off(wr * 32 + li, x) : major_off(wr * 32, x, rows_in);
 #pragma unroll
     for (int x = 0; x < 4; ++x)
-        b_off[x] = DD_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x & 1) : major_off(wc * 64, x));
+        b_off[x] = DD_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x & 1) : major_off(wc * 64, x, cols_in));
     // fragment read i (0..5) of matrix step g of the stage in slot `buf`: 0, 1 = A (mi), 2..5 = B (ni)
     auto read_one = [&](int buf, int g, int i, double (&a)[2], double (&b)[4]) {
         const char *st = dd_smem + buf * DD_STAGE_BYTES;
@@ -327,16 +335,14 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     }
 }
 
-// At least one stage of K, operands with 16-byte aligned rows (in either layout; a k-major operand
-// with an even number of lines, so that every 16-byte unit of it is whole), per-lane byte offsets
-// that fit 31 bits, and k ranges (`kchunk`, when the launch splits K) of whole stages.
+// At least one stage of K, at least two lines in an operand whose lines run across k (its 16-byte
+// pieces are two lines wide), per-lane byte offsets that fit 31 bits, and k ranges (`kchunk`, when
+// the launch splits K) of whole stages.  Rows need not be 16-byte aligned: a direct-to-LDS load of
+// 16 bytes takes any 8-byte aligned address.
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
-    // (16-byte pieces along each operand's contiguous axis: vecA for A; for B, vec when it is
-    // row-major, vecBt when it is stored transposed)
-    if (!a.vecA || !(a.transB ? a.vecBt : a.vec)) return false;
     if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || (a.kchunk < a.K && a.kchunk % DD_BK)) return false;
-    if ((a.transA && a.M % 2) || (!a.transB && a.N % 2)) return false;
+    if ((a.transA && a.M < 2) || (!a.transB && a.N < 2)) return false;
     // a k-minor slice spans 128 lines of the operand's storage, a k-major one 8
     const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / DD_BM, major_max = (0x7FFFFFFFLL / 8 - DD_BN) / DD_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;

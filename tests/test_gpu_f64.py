@@ -392,9 +392,9 @@ def test_f64_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch)
 
 
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
-def test_f64_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
+def test_f64_identity_streamed_kernel_on_every_size(am, tA, tB):
     """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS runs on operands
-    with aligned rows and at least one 8-k stage, in any of the four operand layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
+    of any size and alignment with at least one 8-k stage, in any of the four operand layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
     and a non-zero R_in, few tiles with a long K (every tile split over workgroups), a few more
     tiles than compute units (the last round's tiles split), and exact data bit for bit.  Every
     output is checked."""
@@ -405,7 +405,11 @@ def test_f64_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
              (100, 130, 64, 0), (257, 258, 200, 2), (129, 131, 32, 0), (60, 4098, 4096, 0), (1300, 3202, 1104, 6),
              # K that is no whole number of 8-k stages: one stage and a bit, padded pitches, a split K,
              # a split last round, together with edge tiles
-             (128, 128, 12, 0), (256, 384, 202, 2), (128, 256, 4102, 0), (1408, 3200, 1106, 6), (100, 130, 1034, 0)]
+             (128, 128, 12, 0), (256, 384, 202, 2), (128, 256, 4102, 0), (1408, 3200, 1106, 6), (100, 130, 1034, 0),
+             # odd sizes and pitches: rows that are not 16-byte aligned, edges that cut a two-line
+             # unit, tiles of one line (129 = 128 + 1), the smallest operands the kernel takes
+             (129, 131, 17, 0), (257, 259, 203, 1), (127, 129, 1001, 0), (3, 5, 24, 0), (2, 2, 8, 0), (130, 133, 1037, 3),
+             (1301, 3203, 1109, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         A, B, th, dis, R_in = make_case(0, M, N, K, 9960 + idx)
         As = np.ascontiguousarray(A.T) if tA else A

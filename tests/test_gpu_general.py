@@ -262,10 +262,10 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
 
 
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
-def test_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
+def test_identity_streamed_kernel_on_every_size(am, tA, tB):
     """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: rings
-    of 3 and 4 stages) runs on operands with aligned rows and at least one 16-k stage, in any of the
-    four operand layouts.  Cases: fewer stages than the ring holds,
+    of 3 and 4 stages) runs on operands of any size and alignment with at least one 16-k stage, in
+    any of the four operand layouts.  Cases: fewer stages than the ring holds,
     one tile, several tiles with padded pitches and a non-zero R_in, few tiles with a long K (every
     tile split over workgroups), and a few more tiles than compute units (the last round's tiles
     split).  Every output is checked against the oracle; data whose sums are exact must match
@@ -279,7 +279,12 @@ def test_identity_streamed_kernel_on_whole_tiles(am, tA, tB):
              # K that is no whole number of 16-k stages (the k past the last whole stage are multiplied
              # from values each lane fetches itself): one stage and a bit, padded pitches, a split K,
              # a split last round, together with edge tiles
-             (128, 128, 20, 0), (256, 384, 204, 4), (128, 256, 4100, 0), (1408, 3200, 1108, 8), (100, 132, 1036, 0)]
+             (128, 128, 20, 0), (256, 384, 204, 4), (128, 256, 4100, 0), (1408, 3200, 1108, 8), (100, 132, 1036, 0),
+             # odd sizes and pitches: rows that are not 16-byte aligned (16-byte pieces fetched at
+             # 4-byte aligned addresses), edges that cut a four-line unit, tiles with fewer than four
+             # lines (129 = 128 + 1), the smallest operands the kernel takes
+             (129, 131, 33, 0), (257, 259, 211, 1), (127, 129, 1001, 0), (5, 7, 48, 0), (4, 4, 16, 0), (130, 133, 1037, 3),
+             (1301, 3203, 1109, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, M, N, K, 6500 + idx)
         R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
