@@ -51,7 +51,7 @@ static inline SelKey sel_key(int task, int64_t M, int64_t N, int64_t K)
 
 static int n_shapes(int task)
 {
-    if (task == TASK_IDENTITY) return IDENTITY_SHAPE_COUNT;  // eight vector-ALU shapes and the four matrix-core ones
+    if (task == TASK_IDENTITY) return IDENTITY_SHAPE_COUNT;  // eight vector-ALU shapes and the five matrix-core ones
     if (task > TASK_IDENTITY && task <= TASK_COUNT_GT) return VALU_SHAPE_COUNT;
     if (task == AMULET_TASK_COUNT_I8) return COUNT_SHAPE_COUNT;
     return 0;
@@ -93,6 +93,10 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         // the workgroups' finishing times spread and the fuller unit wins (2048 tiles: 145 against
         // 141, 4096: 149 against 147, 8192 tiles x K = 512: 134 against 128).
         const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+        // Fewer 128 x 128 tiles than compute units: 64 x 64 tiles (us, against the ring of 3: 512^3
+        // 10.1 / 13.4, 1024^3 21.4 / 30.7, 1792^3 104 / 113, 1536^2 x 4096 154 / 166, 512^2 x 8192 40 / 46;
+        // from 256 tiles on the larger tile is level or ahead, 2048^3 135 / 129).
+        if (tiles < compute_units()) return IDENTITY_MFMA_SMALL_SHAPE;
         const int64_t round3 = 3 * (int64_t)compute_units(), round4 = 2 * (int64_t)compute_units();
         if (tiles <= round3 || tiles > 3 * round4) return IDENTITY_MFMA_DMA3_SHAPE;
         auto waste = [&](int64_t slots) { const int64_t r = (tiles + slots - 1) / slots * slots; return (double)(r - tiles) / (double)r; };
@@ -393,6 +397,7 @@ static int64_t trial_rows(const MmlikeCall &c, int shape)
     int64_t tile_rows = 128, tile_cols = 128;
     const bool mfma = is_mfma_shape(c.task, shape);
     if (mfma && shape == IDENTITY_MFMA_BIG_SHAPE) tile_rows = tile_cols = 256;
+    if (mfma && shape == IDENTITY_MFMA_SMALL_SHAPE) tile_rows = tile_cols = 64;
     int64_t want_tiles = 1280;
     if (!mfma) {
         const ValuShapeDesc &d = kValuShapes[shape];
@@ -1284,8 +1289,8 @@ const char *amulet_shape_name(int task, int shape)
     if (shape < 0 || shape >= n_shapes(task)) return "invalid";
     if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
     if (is_mfma_shape(task, shape)) {
-        static const char *const names[4] = {"mfma_f32_128x128_k16", "mfma_f32_256x256_w16_k16", "mfma_f32_128x128_dma3",
-                                             "mfma_f32_128x128_dma4"};
+        static const char *const names[5] = {"mfma_f32_128x128_k16", "mfma_f32_256x256_w16_k16", "mfma_f32_128x128_dma3",
+                                             "mfma_f32_128x128_dma4", "mfma_f32_64x64_dma6"};
         return names[shape - IDENTITY_MFMA_SHAPE];
     }
     return kValuShapes[shape].name;

@@ -320,17 +320,19 @@ hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent = false);
 
-// Identity task on the fp32 matrix cores; its four shape ids follow its eight VALU shapes: a
-// 128 x 128 tile (4 waves, register staged), a 256 x 256 tile (16 waves), and the 128 x 128 tile
-// with its operands streamed HBM -> LDS through a ring of 3 or 4 stages.
+// Identity task on the fp32 matrix cores; its five shape ids follow its eight VALU shapes: a
+// 128 x 128 tile (4 waves, register staged), a 256 x 256 tile (16 waves), the 128 x 128 tile
+// with its operands streamed HBM -> LDS through a ring of 3 or 4 stages, and a streamed 64 x 64
+// tile for problems of few tiles.
 enum { IDENTITY_MFMA_SHAPE = VALU_DEPTHS * VALU_TILES, IDENTITY_MFMA_BIG_SHAPE = VALU_DEPTHS * VALU_TILES + 1,
        IDENTITY_MFMA_DMA3_SHAPE = VALU_DEPTHS * VALU_TILES + 2, IDENTITY_MFMA_DMA4_SHAPE = VALU_DEPTHS * VALU_TILES + 3,
-       IDENTITY_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES + 4 };
+       IDENTITY_MFMA_SMALL_SHAPE = VALU_DEPTHS * VALU_TILES + 4, IDENTITY_SHAPE_COUNT = VALU_DEPTHS * VALU_TILES + 5 };
 // variant = shape id - IDENTITY_MFMA_SHAPE
 hipError_t launch_identity_mfma(const MmlikeArgs &a, int variant, hipStream_t s);
 // the streamed kernel (identity_mfma_dma.hip)
 bool identity_dma_eligible(const MmlikeArgs &a);
-hipError_t enqueue_identity_dma(const MmlikeArgs &a, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s);
+constexpr int ID_SMALL_STAGES = 6;   // ring depth of the streamed 64 x 64 tile
+hipError_t enqueue_identity_dma(const MmlikeArgs &a, int tile, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s);
 
 template <int TASK, int TF>
 hipError_t launch_mmlike_valu_task(int shape, const MmlikeArgs &a, hipStream_t s);

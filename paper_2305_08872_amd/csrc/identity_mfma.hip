@@ -397,7 +397,7 @@ static hipError_t launch_identity_layout(const MmlikeArgs &a, int dma_stages, hi
     }
     if (streamed)
         return launch_row_of_blocks(b, launch_grid.x, L::NT, [&](unsigned n) {
-            (void)enqueue_identity_dma(b, dma_stages, n, launch_grid.y, s);
+            (void)enqueue_identity_dma(b, 128, dma_stages, n, launch_grid.y, s);
         });
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_kernel<G, TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
@@ -416,11 +416,46 @@ static hipError_t launch_identity_grid(const MmlikeArgs &a, int dma_stages, hipS
     return launch_identity_layout<G, false, false>(a, dma_stages, s);
 }
 
+// The streamed 64 x 64 tile (a problem the streamed kernel does not take: the 128 x 128 shapes).
+// Four times the tiles of the 128 x 128 shape, so a problem with fewer of those than compute units
+// fills the chip without a K split or with a smaller one, and more of its write-back is plain
+// stores instead of atomic adds; a workgroup streams twice the operand bytes per operation and
+// has 8 matrix instructions per wave between barriers instead of 32, which is why the larger tile
+// is ahead once it has a tile per compute unit (2048^3: 129 against 135 us; 1024^3: 31 against 21).
+// K split: the streamed kernels' model with three workgroups (rings of 48 KB) to a unit; checked
+// against forced splits of 1 ... 12 at 512^3 ... 1792^3 and K up to 8192: the best or within 7 %.
+static hipError_t launch_identity_small(const MmlikeArgs &a, hipStream_t s)
+{
+    MmlikeArgs b = a;
+    b.kchunk = a.K;
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    if (!identity_dma_eligible(b)) return launch_identity_grid<2>(a, 3, s);
+    const int64_t tiles_m = (a.M + 63) / 64, tiles_n = (a.N + 63) / 64;
+    const int64_t grid = xcd_grid(tiles_m, tiles_n);
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    int splits = 1;
+    const int cap = 3;
+    if (tiles_m * tiles_n <= 2 * cap * (int64_t)compute_units()) {
+        static const double rate[3] = {0.80, 0.93, 1.0};
+        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, cap, rate, 200.0);
+        if (sp > 1) {
+            const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK, MI_BK);
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+        }
+    }
+    return launch_row_of_blocks(b, grid, 256, [&](unsigned n) {
+        (void)enqueue_identity_dma(b, 64, ID_SMALL_STAGES, n, (unsigned)splits, s);
+    });
+}
+
 // variant 0: 128 x 128 tile (4 waves), register staged; 1: 256 x 256 tile (16 waves); 2, 3: the
-// 128 x 128 tile streamed through a ring of 3 or 4 LDS stages where the problem allows it
+// 128 x 128 tile streamed through a ring of 3 or 4 LDS stages where the problem allows it; 4: the
+// streamed 64 x 64 tile
 hipError_t launch_identity_mfma(const MmlikeArgs &a, int variant, hipStream_t s)
 {
     switch (variant) {
+    case 4: return launch_identity_small(a, s);
     case 0: return launch_identity_grid<2>(a, 0, s);
     case 1: return launch_identity_grid<4>(a, 0, s);
     case 2: return launch_identity_grid<2>(a, 3, s);

@@ -43,11 +43,26 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-constexpr int ID_BM = 128, ID_BN = 128, ID_BK = 16;
-constexpr int ID_A_BYTES = ID_BM * ID_BK * 4;       // 8 KB = 8 wave-loads
-constexpr int ID_B_BYTES = ID_BK * ID_BN * 4;       // 8 KB = 8 wave-loads
-constexpr int ID_STAGE_BYTES = ID_A_BYTES + ID_B_BYTES;
-constexpr int ID_LOADS = 4;                         // DMA instructions per wave per stage
+constexpr int ID_BK = 16;
+// BLK: 32 x 32 blocks per wave and direction.  2: the 128 x 128 tile; 1: a 64 x 64 tile for problems
+// with fewer 128 x 128 tiles than compute units (same code, half the lines per operand slice).
+template <int BLK>
+struct IdTile {
+    static constexpr int T = 64 * BLK;                  // rows of A and columns of B in a tile
+    static constexpr int OP_BYTES = T * ID_BK * 4;      // one operand's 16-k slice: 8 KB / 4 KB
+    static constexpr int STAGE_BYTES = 2 * OP_BYTES;
+    static constexpr int LOADS = 2 * BLK;               // DMA instructions per wave per stage
+    static constexpr int ROW_BYTES = T * 4;             // a k-row of a k-major slice
+    static constexpr int ROW_UNITS = T / 4;             // its 16-byte units
+    static constexpr int WAVE_LINES = 32 * BLK;         // lines of a wave's part of the tile
+    static constexpr int NACC = BLK == 1 ? 2 : 1;       // accumulator sets (see mma_with)
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 extern __shared__ __attribute__((aligned(16))) char id_smem[];
 
@@ -55,10 +70,13 @@ extern __shared__ __attribute__((aligned(16))) char id_smem[];
 // 16-k slice of the tile keeps its global layout in LDS, "k-minor" (128 lines x 16 k, k contiguous:
 // row-major A, transposed B) or "k-major" (16 k x 128 lines: row-major B, transposed A), with the
 // swizzles given above for A and B respectively.
-template <int NSTAGE, bool TA, bool TB>
+template <int NSTAGE, bool TA, bool TB, int BLK>
 __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs args)
 {
-    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    static_assert(NSTAGE >= 3 && NSTAGE <= 8, "the wait counts are written for rings of 3 to 8 stages");
+    typedef IdTile<BLK> TL;
+    constexpr int ID_BM = TL::T, ID_BN = TL::T, ID_A_BYTES = TL::OP_BYTES, ID_STAGE_BYTES = TL::STAGE_BYTES;
+    constexpr int ID_LOADS = TL::LOADS, ROWB = TL::ROW_BYTES, WL = TL::WAVE_LINES, NACC = TL::NACC;
     constexpr bool A_KMINOR = !TA, B_KMINOR = TB;
     const int M = args.M, N = args.N;
     int K = args.K;
@@ -96,9 +114,9 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     if (n_stages <= 0) return;   // (the host never makes a k range shorter than a stage)
 
     // ---- what each lane fetches: two A slots and two B slots per stage ---------------------
-    // wave w owns the 1 KB slot groups j = w and w + 4 of each operand's tile:
+    // wave w owns the 1 KB slot groups j = w (and w + 4 in the 128-line tile) of each operand's tile:
     //   k-minor tile: slot 64 j + lane -> line 16 j + lane / 4, physical unit lane % 4
-    //   k-major tile: slot 64 j + lane -> k 2 j + lane / 32, physical unit lane % 32
+    //   k-major tile: slot 64 j + lane -> k and physical unit = quotient and remainder by the units of a k-row
     // `lines` of the tile exist (128 but in an edge tile).  k-minor: a line past them is replaced
     // by the last one inside.  k-major: a unit of four lines that would end past them is fetched
     // as the four lines that end AT the edge (a 16-byte piece may start at any 4-byte aligned
@@ -113,17 +131,18 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
             const int line_in = line < lines ? line : lines - 1;
             return ((uint32_t)line_in * (uint32_t)ld + (uint32_t)(u * 4)) * 4u;
         }
-        const int k = 2 * j + (lane >> 5);
-        const int u = (lane & 31) ^ (((k >> 2) & 1) << 3);
+        const int slot = 64 * j + lane;
+        const int k = slot / TL::ROW_UNITS;
+        const int u = (slot % TL::ROW_UNITS) ^ (((k >> 2) & 1) << 3);
         const int lead = lines < 4 ? 4 - lines : 0;
         const int start = 4 * u + 4 <= lines ? 4 * u + lead : lines - 4 + lead;
         return ((uint32_t)k * (uint32_t)ld + (uint32_t)start) * 4u;
     };
     const int rows_in = M - row0 < ID_BM ? M - row0 : ID_BM, cols_in = N - col0 < ID_BN ? N - col0 : ID_BN;
     const int a_lead = !A_KMINOR && rows_in < 4 ? 4 - rows_in : 0, b_lead = !B_KMINOR && cols_in < 4 ? 4 - cols_in : 0;
-    uint32_t a_voff[2], b_voff[2];
+    uint32_t a_voff[BLK], b_voff[BLK];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < BLK; ++q) {
         a_voff[q] = lane_offset(A_KMINOR, wave + 4 * q, args.lda, rows_in);
         b_voff[q] = lane_offset(B_KMINOR, wave + 4 * q, args.ldb, cols_in);
     }
@@ -145,7 +164,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
                      : "v"(voff), "s"(base), "s"(lds_addr)
                      : "memory", "m0");
     };
-    // load i (0..3) of a stage whose operands start at (ap, bp), into ring slot `buf`
+    // load i (0 .. ID_LOADS-1) of a stage whose operands start at (ap, bp), into ring slot `buf`
     auto issue_one = [&](const float *ap, const float *bp, int buf, int i) {
         const int q = i >> 1;
         const uint32_t dst = lds_base + (uint32_t)(buf * ID_STAGE_BYTES) + (uint32_t)((wave + 4 * q) * 1024);
@@ -154,7 +173,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     };
 
     // ---- where each lane reads its fragments (byte offsets inside an operand's slice) --------
-    // The lane's line is wr*64 + blk*32 + li of A, wc*64 + blk*32 + li of B (blk = mi, ni), and
+    // The lane's line is wr*WL + blk*32 + li of A, wc*WL + blk*32 + li of B (blk = mi, ni), and
     // matrix instruction t of group g multiplies k = 8g + 4 lh + t:
     //   k-minor: the four k of a group are one 16-byte read per block;
     //   k-major: one 4-byte read per (t, block).
@@ -163,41 +182,46 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         const int unit = (line0 >> 2) + blk * 8 + (li >> 2);
         // (a line of the unit the tile's edge cuts sits 4 - lines % 4 places further up)
         const int edge_shift = (lines & 3) && line0 + blk * 32 + li >= (lines & ~3) ? 4 - (lines & 3) : 0;
-        return (4 * lh) * 512 + ((unit ^ (lh << 3)) * 16) + ((li & 3) + edge_shift) * 4;   // + (8g + t) * 512
+        return (4 * lh) * ROWB + ((unit ^ (lh << 3)) * 16) + ((li & 3) + edge_shift) * 4;   // + (8g + t) * ROWB
     };
     int a_off[2], b_off[2];   // k-minor: per group g; k-major: per block
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-        a_off[x] = A_KMINOR ? minor_off(wr * 64 + li, x) : major_off(wr * 64, x, rows_in);
-        b_off[x] = ID_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x) : major_off(wc * 64, x, cols_in));
+        a_off[x] = A_KMINOR ? minor_off(wr * WL + li, x) : major_off(wr * WL, x < BLK ? x : 0, rows_in);
+        b_off[x] = ID_A_BYTES + (B_KMINOR ? minor_off(wc * WL + li, x) : major_off(wc * WL, x < BLK ? x : 0, cols_in));
     }
-    // One group's fragments of an operand: a k-minor operand's as two 16-byte values (block, then
-    // component t), a k-major one's as 4 x 2 floats (t, block).
+    // One group's fragments of an operand: a k-minor operand's as one 16-byte value per block
+    // (component t), a k-major one's as 4 x BLK floats (t, block).
     struct Frag {
-        f4 v4[2];
-        float v1[4][2];
+        f4 v4[BLK];
+        float v1[4][BLK];
     };
-    constexpr int A_READS = A_KMINOR ? 2 : 8, B_READS = B_KMINOR ? 2 : 8, READS = A_READS + B_READS;
+    constexpr int A_READS = A_KMINOR ? BLK : 4 * BLK, B_READS = B_KMINOR ? BLK : 4 * BLK, READS = A_READS + B_READS;
     // fragment read i (0 .. READS-1) of group g of the stage in slot `buf`: A's first, then B's
     auto read_one = [&](int buf, int g, int i, Frag &a, Frag &b) {
         const char *st = id_smem + buf * ID_STAGE_BYTES;
         if (i < A_READS) {
             if constexpr (A_KMINOR) a.v4[i] = *(const f4 *)(st + a_off[g] + i * 2048);
-            else a.v1[i >> 1][i & 1] = *(const float *)(st + a_off[i & 1] + (8 * g + (i >> 1)) * 512);
+            else a.v1[i / BLK][i % BLK] = *(const float *)(st + a_off[i % BLK] + (8 * g + i / BLK) * ROWB);
         } else {
             const int j = i - A_READS;
             if constexpr (B_KMINOR) b.v4[j] = *(const f4 *)(st + b_off[g] + j * 2048);
-            else b.v1[j >> 1][j & 1] = *(const float *)(st + b_off[j & 1] + (8 * g + (j >> 1)) * 512);
+            else b.v1[j / BLK][j % BLK] = *(const float *)(st + b_off[j % BLK] + (8 * g + j / BLK) * ROWB);
         }
     };
-    f16v acc[2][2];
+    // (the 64 x 64 tile has one block per wave: two accumulator sets, for even and odd t, so that
+    // consecutive matrix instructions do not wait for each other's result; added up at the end)
+    f16v acc[NACC][BLK][BLK];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int c = 0; c < NACC; ++c)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int mi = 0; mi < BLK; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
-    // The 16 matrix instructions of one group of 8 k (the hardware pairs k-slot h = lane / 32 of
+            for (int ni = 0; ni < BLK; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[c][mi][ni][v] = 0.0f;
+    constexpr int NM = 4 * BLK * BLK;   // matrix instructions of a group
+    // The NM matrix instructions of one group of 8 k (the hardware pairs k-slot h = lane / 32 of
     // A with k-slot h of B: instruction t of group g multiplies k = 8g + 4h + t), with `side(i)`
     // issued right after instruction i.  A wave issues in order, and a matrix instruction
     // occupies the matrix core for 64 cycles during which the wave may issue other instructions:
@@ -208,13 +232,13 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < BLK; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
+                for (int ni = 0; ni < BLK; ++ni) {
                     const float av = A_KMINOR ? a.v4[mi][t] : a.v1[t][mi];
                     const float bv = B_KMINOR ? b.v4[ni][t] : b.v1[t][ni];
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[mi][ni], 0, 0, 0);
-                    side(t * 4 + mi * 2 + ni);
+                    acc[t % NACC][mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[t % NACC][mi][ni], 0, 0, 0);
+                    side((t * BLK + mi) * BLK + ni);
                     __builtin_amdgcn_sched_barrier(0);
                 }
     };
@@ -223,11 +247,13 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // may still be outstanding.  (The count is an immediate: one instruction per value.)
     auto wait_stage = [&](int t, int upto) {
         switch (upto - t) {
-        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-        case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-        case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-        case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never too little
+        case 1: wait_vmcnt<ID_LOADS>(); break;
+        case 2: wait_vmcnt<2 * ID_LOADS>(); break;
+        case 3: wait_vmcnt<3 * ID_LOADS>(); break;
+        case 4: wait_vmcnt<4 * ID_LOADS>(); break;
+        case 5: wait_vmcnt<5 * ID_LOADS>(); break;
+        case 6: wait_vmcnt<6 * ID_LOADS>(); break;
+        default: wait_vmcnt<0>(); break;   // never too little
         }
     };
 
@@ -257,24 +283,24 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // and replaced by zero), eight k at a time.
     if (ktail > 0) {
         const int kt = kb + n_stages * ID_BK, kend = kb + K;
-        int64_t a_line[2], b_line[2];
+        int64_t a_line[BLK], b_line[BLK];
 #pragma unroll
-        for (int x = 0; x < 2; ++x) {
-            const int r = wr * 64 + x * 32 + li, c = wc * 64 + x * 32 + li;
+        for (int x = 0; x < BLK; ++x) {
+            const int r = wr * WL + x * 32 + li, c = wc * WL + x * 32 + li;
             a_line[x] = row0 + (r < rows_in ? r : rows_in - 1);
             b_line[x] = col0 + (c < cols_in ? c : cols_in - 1);
         }
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             if (8 * half >= ktail) break;
-            float av[4][2], bv[4][2];
+            float av[4][BLK], bv[4][BLK];
 #pragma unroll
             for (int step = 0; step < 4; ++step) {
                 const int k = kt + 8 * half + 2 * step + lh;
                 const bool ok = k < kend;
                 const int64_t kc = ok ? k : kend - 1;
 #pragma unroll
-                for (int x = 0; x < 2; ++x) {
+                for (int x = 0; x < BLK; ++x) {
                     const float a = TA ? args.A[kc * args.lda + a_line[x]] : args.A[a_line[x] * args.lda + kc];
                     const float b = TB ? args.B[b_line[x] * args.ldb + kc] : args.B[kc * args.ldb + b_line[x]];
                     av[step][x] = ok ? a : 0.0f;
@@ -284,10 +310,11 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
 #pragma unroll
             for (int step = 0; step < 4; ++step)
 #pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
+                for (int mi = 0; mi < BLK; ++mi)
 #pragma unroll
-                    for (int ni = 0; ni < 2; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[step][mi], bv[step][ni], acc[mi][ni], 0, 0, 0);
+                    for (int ni = 0; ni < BLK; ++ni)
+                        acc[step % NACC][mi][ni] =
+                            __builtin_amdgcn_mfma_f32_32x32x2f32(av[step][mi], bv[step][ni], acc[step % NACC][mi][ni], 0, 0, 0);
         }
     }
 
@@ -303,12 +330,13 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         // group 0 of stage s; the fragments of group 1 are read meanwhile
-        mma_with(fa0, fb0, [&](int i) { if (i < READS) read_one(buf, 1, i, fa1, fb1); });
+        mma_with(fa0, fb0, [&](int i) {
+#pragma unroll
+            for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
+        });
         if constexpr (STEADY) {
             // stages up to s+NSTAGE-2 are requested; s+1 must have landed
-            if constexpr (NSTAGE == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            else if constexpr (NSTAGE == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            wait_vmcnt<(NSTAGE - 3) * ID_LOADS>();
         } else {
             const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
             wait_stage(s + 1, last);
@@ -316,14 +344,17 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         __builtin_amdgcn_s_barrier();   // bare: the fence of __syncthreads() would drain the loads in flight
         asm volatile("" ::: "memory");
         // group 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
-        // has left) and the fragment reads of group 0 of stage s+1: ID_LOADS + READS pieces over 16
-        // matrix instructions, the first few of which take two
+        // has left) and the fragment reads of group 0 of stage s+1: ID_LOADS + READS pieces over NM
+        // matrix instructions, the first few of which take one more than the rest
         const bool more = STEADY || s + NSTAGE - 1 < n_stages;
         auto piece = [&](int i) {
             if (i < ID_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
             else if (i < ID_LOADS + READS) read_one(nbuf, 0, i - ID_LOADS, fa0, fb0);
         };
-        mma_with(fa1, fb1, [&](int i) { piece(i); piece(i + 16); });
+        mma_with(fa1, fb1, [&](int i) {
+#pragma unroll
+            for (int p = i; p < ID_LOADS + READS; p += NM) piece(p);
+        });
         ap += a_stage;
         bp += b_stage;
         ibuf = buf;
@@ -333,8 +364,17 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     int s = 0;
     for (; s < steady_end; ++s) iteration(s, std::true_type());
     for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
-    mma_with(fa0, fb0, [&](int i) { if (i < READS) read_one(buf, 1, i, fa1, fb1); });
+    mma_with(fa0, fb0, [&](int i) {
+#pragma unroll
+        for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
+    });
     mma_with(fa1, fb1, [&](int) {});
+    if constexpr (NACC == 2) {
+#pragma unroll
+        for (int mi = 0; mi < BLK; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < BLK; ++ni) acc[0][mi][ni] += acc[1][mi][ni];
+    }
 
     // accumulator element v of lane l is R[8*(v/4) + 4*(l/32) + v%4][l%32] of its 32x32 block.
     // R += acc: the 32 values of a row block are all read before the first is written back (as
@@ -342,15 +382,15 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     // the write-back is a chain of 64 round trips to memory, 15 us of a tile).
     const bool edge = rows_in < ID_BM || cols_in < ID_BN;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        float *dst[2][16];
-        float old[2][16];
+    for (int mi = 0; mi < BLK; ++mi) {
+        float *dst[BLK][16];
+        float old[BLK][16];
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < BLK; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int col = wc * 64 + ni * 32 + li;
-                const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                const int col = wc * WL + ni * 32 + li;
+                const int row = wr * WL + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 dst[ni][v] = args.R + (int64_t)(row0 + row) * args.ldr + col0 + col;
             }
         if (ksplit || edge) {
@@ -358,22 +398,22 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
             // the sum is the same single rounding, and an atomic needs no round trip to memory
             // before the store, which under a per-element mask would be one after the other)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < BLK; ++ni)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int col = wc * 64 + ni * 32 + li;
-                    const int row = wr * 64 + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    if (row < rows_in && col < cols_in) unsafeAtomicAdd(dst[ni][v], acc[mi][ni][v]);
+                    const int col = wc * WL + ni * 32 + li;
+                    const int row = wr * WL + mi * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (row < rows_in && col < cols_in) unsafeAtomicAdd(dst[ni][v], acc[0][mi][ni][v]);
                 }
         } else {
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < BLK; ++ni)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) old[ni][v] = *dst[ni][v];
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < BLK; ++ni)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) *dst[ni][v] = old[ni][v] + acc[mi][ni][v];
+                for (int v = 0; v < 16; ++v) *dst[ni][v] = old[ni][v] + acc[0][mi][ni][v];
         }
     }
 }
@@ -386,37 +426,41 @@ bool identity_dma_eligible(const MmlikeArgs &a)
 {
     if (a.M <= 0 || a.N <= 0 || a.K < ID_BK || (a.kchunk < a.K && a.kchunk % ID_BK)) return false;
     if ((a.transA && a.M < 4) || (!a.transB && a.N < 4)) return false;
-    // a k-minor slice spans 128 lines of the operand's storage, a k-major one 16
-    const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / ID_BM, major_max = (0x7FFFFFFFLL / 4 - ID_BN) / ID_BK;
+    // a k-minor slice spans up to 128 lines of the operand's storage, a k-major one 16
+    const int64_t minor_max = (0x7FFFFFFFLL / 4 - 16) / 128, major_max = (0x7FFFFFFFLL / 4 - 128) / ID_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;
     return true;
 }
 
-template <int NSTAGE, bool TA, bool TB>
+template <int NSTAGE, bool TA, bool TB, int BLK>
 static hipError_t enqueue_layout(const MmlikeArgs &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<NSTAGE, TA, TB>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * ID_STAGE_BYTES);
+    constexpr int LDS = NSTAGE * IdTile<BLK>::STAGE_BYTES;
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_dma_kernel<NSTAGE, TA, TB, BLK>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((identity_mfma_dma_kernel<NSTAGE, TA, TB>), dim3(grid_x, grid_y), dim3(256), NSTAGE * ID_STAGE_BYTES, s, a);
+    hipLaunchKernelGGL((identity_mfma_dma_kernel<NSTAGE, TA, TB, BLK>), dim3(grid_x, grid_y), dim3(256), LDS, s, a);
     return hipSuccess;
 }
 
-template <int NSTAGE>
+template <int NSTAGE, int BLK>
 static hipError_t enqueue_stages(const MmlikeArgs &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    if (a.transA && a.transB) return enqueue_layout<NSTAGE, true, true>(a, grid_x, grid_y, s);
-    if (a.transA) return enqueue_layout<NSTAGE, true, false>(a, grid_x, grid_y, s);
-    if (a.transB) return enqueue_layout<NSTAGE, false, true>(a, grid_x, grid_y, s);
-    return enqueue_layout<NSTAGE, false, false>(a, grid_x, grid_y, s);
+    if (a.transA && a.transB) return enqueue_layout<NSTAGE, true, true, BLK>(a, grid_x, grid_y, s);
+    if (a.transA) return enqueue_layout<NSTAGE, true, false, BLK>(a, grid_x, grid_y, s);
+    if (a.transB) return enqueue_layout<NSTAGE, false, true, BLK>(a, grid_x, grid_y, s);
+    return enqueue_layout<NSTAGE, false, false, BLK>(a, grid_x, grid_y, s);
 }
 
 // Enqueues grid.x x grid.y workgroups of the streamed kernel (the caller has checked
-// identity_dma_eligible and fills the split fields of `a` as for identity_mfma_kernel).
-hipError_t enqueue_identity_dma(const MmlikeArgs &a, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s)
+// identity_dma_eligible and fills the split fields of `a` as for identity_mfma_kernel): tiles of
+// `tile` = 128 rows and columns through a ring of 3 or 4 stages, or of 64 through a ring of
+// ID_SMALL_STAGES.
+hipError_t enqueue_identity_dma(const MmlikeArgs &a, int tile, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    if (nstage == 3) return enqueue_stages<3>(a, grid_x, grid_y, s);
-    if (nstage == 4) return enqueue_stages<4>(a, grid_x, grid_y, s);
+    if (tile == 128 && nstage == 3) return enqueue_stages<3, 2>(a, grid_x, grid_y, s);
+    if (tile == 128 && nstage == 4) return enqueue_stages<4, 2>(a, grid_x, grid_y, s);
+    if (tile == 64 && nstage == ID_SMALL_STAGES) return enqueue_stages<ID_SMALL_STAGES, 1>(a, grid_x, grid_y, s);
     return hipErrorInvalidValue;
 }
 

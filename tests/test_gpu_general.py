@@ -124,7 +124,7 @@ def test_identity_transposed_on_the_matrix_cores(am, tA, tB):
         for pad in (0, 3):
             bufA = torch.zeros(As.shape[0], As.shape[1] + pad, device="cuda"); bufA[:, :As.shape[1]] = dev(As)
             bufB = torch.zeros(Bs.shape[0], Bs.shape[1] + pad, device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
-            for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
+            for shape in (8, 9, 10, 11, 12, -1):   # 10, 11, 12: the streamed kernels where the size allows it
                 print("identity trans", tA, tB, M, N, K, pad, shape, flush=True)
                 dR = dev(R_in)
                 am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,
@@ -144,7 +144,7 @@ def test_identity_aligned_ragged_edges_on_the_matrix_cores(am):
         R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in)
         bufA = torch.full((M + 3, K + 8), float("nan"), device="cuda"); bufA[:M, :K] = dev(As)
         bufB = torch.full((K + 3, N + 12), float("nan"), device="cuda"); bufB[:K, :N] = dev(Bs)
-        for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
+        for shape in (8, 9, 10, 11, 12, -1):   # 10, 11, 12: the streamed kernels where the size allows it
             for (vA, vB) in ((dev(As), dev(Bs)), (bufA[:M, :K], bufB[:K, :N])):
                 print("identity aligned ragged", M, N, K, shape, vA.stride(0), vB.stride(0), flush=True)
                 dR = dev(R_in)
@@ -255,7 +255,7 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
     M, N, K = 1300, 3200, 1100
     As, Bs, th, dis, R_in = make_case(0, 0, trans, trans, M, N, K, 6400 + int(trans))
     R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=trans, trans_b=trans)
-    for shape in (8, 9, 10, 11, -1):   # 10, 11: the streamed kernel where the size allows it
+    for shape in (8, 9, 10, 11, 12, -1):   # 10, 11, 12: the streamed kernels where the size allows it
         print("identity tail split", trans, shape, M, N, K, flush=True)
         R = run(am, 0, 0, trans, trans, As, Bs, th, dis, R_in, shape)
         assert_parity_f32(R, R_ref, ab, R_in, what="identity tail split shape %d" % shape)
@@ -263,8 +263,8 @@ def test_identity_last_round_of_tiles_split_over_k(am, trans):
 
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
 def test_identity_streamed_kernel_on_every_size(am, tA, tB):
-    """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: rings
-    of 3 and 4 stages) runs on operands of any size and alignment with at least one 16-k stage, in
+    """The matrix-core identity kernel that streams its operands HBM -> LDS (shapes 10, 11: 128 x
+    128 tiles, rings of 3 and 4 stages; 12: 64 x 64 tiles, ring of 6) runs on operands of any size and alignment with at least one 16-k stage, in
     any of the four operand layouts.  Cases: fewer stages than the ring holds,
     one tile, several tiles with padded pitches and a non-zero R_in, few tiles with a long K (every
     tile split over workgroups), and a few more tiles than compute units (the last round's tiles
@@ -284,13 +284,16 @@ def test_identity_streamed_kernel_on_every_size(am, tA, tB):
              # 4-byte aligned addresses), edges that cut a four-line unit, tiles with fewer than four
              # lines (129 = 128 + 1), the smallest operands the kernel takes
              (129, 131, 33, 0), (257, 259, 211, 1), (127, 129, 1001, 0), (5, 7, 48, 0), (4, 4, 16, 0), (130, 133, 1037, 3),
-             (1301, 3203, 1109, 0)]
+             (1301, 3203, 1109, 0),
+             # around the 64 x 64 tile: one tile and one stage, a line more than whole tiles, a K of
+             # fewer stages than its ring holds plus a tail, few tiles with a long K
+             (64, 64, 16, 0), (65, 67, 33, 0), (190, 70, 100, 2), (192, 320, 2100, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, M, N, K, 6500 + idx)
         R_ref, ab, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
         bufA = torch.full((As.shape[0], As.shape[1] + pad), float("nan"), device="cuda"); bufA[:, :As.shape[1]] = dev(As)
         bufB = torch.full((Bs.shape[0], Bs.shape[1] + pad), float("nan"), device="cuda"); bufB[:, :Bs.shape[1]] = dev(Bs)
-        for shape in (10, 11):
+        for shape in (10, 11, 12):
             print("identity streamed", tA, tB, M, N, K, pad, shape, flush=True)
             dR = dev(R_in)
             am.amulet_mmlike_f32_general(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR,
@@ -299,7 +302,7 @@ def test_identity_streamed_kernel_on_every_size(am, tA, tB):
             assert_parity_f32(dR.cpu().numpy(), R_ref, ab, R_in, what="identity streamed %d %dx%dx%d" % (shape, M, N, K))
     As, Bs, th, dis, R_in = make_case(0, 0, tA, tB, 256, 256, 1600, 6600, exact=True)
     R_ref, _, _ = oracle.mmlike_f32_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
-    for shape in (10, 11):
+    for shape in (10, 11, 12):
         R = run(am, 0, 0, tA, tB, As, Bs, None, None, R_in, shape)
         assert np.array_equal(R, R_ref), shape
 

@@ -150,7 +150,7 @@ def test_register_rule_matches_paper_worked_example(lib, golden_dir):
 def test_shape_table_is_the_two_axis_grid(lib):
     n = am.amulet_shape_count(am.AMULET_DISCOUNT)
     assert n == 20 and am.amulet_shape_count(77) == 0      # k axis of 5 points x 4 tiles
-    assert am.amulet_shape_count(am.AMULET_IDENTITY) == 12  # two staging depths x 4 tiles, plus the four matrix-core shapes
+    assert am.amulet_shape_count(am.AMULET_IDENTITY) == 13  # two staging depths x 4 tiles, plus the five matrix-core shapes
     assert am.amulet_shape_name(1, 9) == "valu_32x256_w8_k16_s2" and am.amulet_shape_name(0, 9).startswith("mfma_")
     names = [am.amulet_shape_name(1, i) for i in range(n)]
     assert len(set(names)) == n and all(x.startswith("valu_") for x in names)
