@@ -188,7 +188,9 @@ int amulet_mmlike_f64_general(int task, int thres_form, int trans_a, int trans_b
  * 0 = a workgroup sums a tile's whole K (split only where the launcher's own rule asks
  * for it), 1, 2 = every tile's K in 2, 4 parts added to R with fp64 atomics (not
  * bit-reproducible; ignored in deterministic mode).  The identity task runs on the
- * matrix cores whatever the shape.
+ * matrix cores whatever the shape; to it only the tile index means something: 0 = tiles
+ * of 64 x 64, 1 = of 128 x 128 (the built-in choice: 64 x 64 for a problem with fewer
+ * 128 x 128 tiles than the chip has compute units).
  *   amulet_f64_shape_count      number of shape ids (6)
  *   amulet_f64_shape_name       static string, "invalid" for a bad id
  *   amulet_selected_shape_f64   shape a plain call uses for (task, M, N, K): the cached

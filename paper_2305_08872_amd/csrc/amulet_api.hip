@@ -531,7 +531,8 @@ static int default_shape_f64(int task, int64_t M, int64_t N)
 
 static int lookup_shape_f64(int task, int64_t M, int64_t N, int64_t K)
 {
-    if (task == TASK_IDENTITY) return 0;
+    // (identity: the matrix-core tile; 64 x 64 with fewer 128 x 128 tiles than compute units)
+    if (task == TASK_IDENTITY) return ((M + 127) / 128) * ((N + 127) / 128) < compute_units() ? 0 : 1;
     {
         std::lock_guard<std::mutex> lock(g_sel_mutex);
         auto it = g_selected.find(sel_key(f64_cache_task(task), M, N, K));

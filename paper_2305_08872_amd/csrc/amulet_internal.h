@@ -284,8 +284,8 @@ struct MmlikeArgs {
 //          2, 3, 4: BK 16, every tile's K in 2, 4, 8 parts
 //   tile 0: 4x4 per lane, 4 waves  -> 16 x 256      tile 1: 4x4, 8 waves -> 32 x 256
 //   tile 2: 8x4 per lane, 8 waves  -> 64 x 256      tile 3: 4x8, 8 waves -> 32 x 512
-// The identity task keeps the first two k-axis points (ids 0-7) and adds its two matrix-core
-// shapes (ids 8 to 11); the predicate tasks have all VALU_SHAPE_COUNT ids.
+// The identity task keeps the first two k-axis points (ids 0-7) and adds its matrix-core
+// shapes (ids 8 to 12); the predicate tasks have all VALU_SHAPE_COUNT ids.
 enum { VALU_DEPTHS = 2, VALU_KAXIS = 5, VALU_TILES = 4, VALU_SHAPE_COUNT = VALU_KAXIS * VALU_TILES };
 
 struct ValuShapeDesc {
@@ -359,10 +359,10 @@ struct MmlikeArgsF64 {
 // (k axis: K whole, in 2, in 4 parts per tile; tile: 16 x 128 with 4 waves, 32 x 128 with 8).
 enum { F64_KAXIS = 3, F64_TILES = 2, F64_SHAPE_COUNT = F64_KAXIS * F64_TILES };
 hipError_t launch_mmlike_f64(int task, int form, int shape, const MmlikeArgsF64 &a, hipStream_t s);
-hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s);
+hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, int tile, hipStream_t s);
 // the streamed fp64 identity kernel (identity_mfma_f64_dma.hip)
 bool identity_f64_dma_eligible(const MmlikeArgsF64 &a);
-hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s);
+hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, int tile, unsigned grid_x, unsigned grid_y, hipStream_t s);
 
 // dst (cols x rows, pitch ld_dst) = transpose of src (rows x cols, pitch ld_src), bytes (pack.hip)
 hipError_t launch_pack_pad_i8(int64_t rows, int64_t cols, const int8_t *src, int64_t ld_src, int8_t *dst,

@@ -3,7 +3,9 @@
 // LDS stages.
 //
 // Same arithmetic, tile (128 x 128, 4 waves of 64 x 64) and fragment conventions as
-// identity_mfma_kernel (identity_mfma.hip); what differs is the operand path.  That kernel
+// identity_mfma_kernel (identity_mfma.hip); what differs is the operand path.  (Also as a 64 x 64
+// tile, 4 waves of 32 x 32, for problems of few tiles: the template's BLK.  The layouts below are
+// given for the 128 x 128 tile; with 64 x 64 a slice has half the lines.)  That kernel
 // stages a 16-k slice through registers one stage ahead, which is less than the memory latency:
 // it reaches its rate only with three or four workgroups per compute unit covering for each
 // other, and a problem of one or two tiles per unit runs at 0.72-0.81 of it.  Here a

@@ -318,7 +318,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     }
     if (streamed)
         return launch_row_of_blocks(b, launch_grid.x, DI_NT, [&](unsigned n) {
-            (void)enqueue_identity_f64_dma(b, n, launch_grid.y, s);
+            (void)enqueue_identity_f64_dma(b, 128, n, launch_grid.y, s);
         });
     static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_kernel<TA, TB>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -328,8 +328,41 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
     });
 }
 
-hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, hipStream_t s)
+// The streamed 64 x 64 tile, for problems with fewer 128 x 128 tiles than compute units (the fp64
+// counterpart of the fp32 kernel's small tile, identity_mfma.hip, where the reasons are given):
+// K split by the streamed kernels' model with three workgroups (rings of 48 KB) to a unit.
+static hipError_t launch_di_small(const MmlikeArgsF64 &a, hipStream_t s)
 {
+    MmlikeArgsF64 b = a;
+    b.kchunk = a.K;
+    b.tail_base = 0; b.tail_blocks = 0; b.tail_splits = 1;
+    const int64_t tiles_m = (a.M + 63) / 64, tiles_n = (a.N + 63) / 64;
+    const int64_t grid = xcd_grid(tiles_m, tiles_n);
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    int splits = 1;
+    const int cap = 3;
+    if (tiles_m * tiles_n <= 2 * cap * (int64_t)compute_units()) {
+        static const double rate[3] = {0.80, 0.93, 1.0};
+        const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, cap, rate, 100.0, 0.34);
+        if (sp > 1) {
+            const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK, DI_BK);
+            b.kchunk = (int)chunk;
+            splits = (int)((a.K + chunk - 1) / chunk);
+        }
+    }
+    return launch_row_of_blocks(b, grid, 256, [&](unsigned n) {
+        (void)enqueue_identity_f64_dma(b, 64, n, (unsigned)splits, s);
+    });
+}
+
+// tile: 64 = the streamed 64 x 64 tile where the streamed kernel takes the problem; else 128 x 128
+hipError_t launch_identity_mfma_f64(const MmlikeArgsF64 &a, int tile, hipStream_t s)
+{
+    if (tile == 64) {
+        MmlikeArgsF64 b = a;
+        b.kchunk = a.K;
+        if (identity_f64_dma_eligible(b)) return launch_di_small(a, s);
+    }
     const int64_t tiles_m = (a.M + DI_BM - 1) / DI_BM;
     const int64_t tiles_n = (a.N + DI_BN - 1) / DI_BN;
     const int64_t grid = xcd_grid(tiles_m, tiles_n);

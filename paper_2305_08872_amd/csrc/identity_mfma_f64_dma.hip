@@ -5,7 +5,9 @@
 //
 // Same arithmetic, tile (128 x 128, 8 waves of 32 x 64 = 2 x 4 blocks of v_mfma_f64_16x16x4_f64)
 // and result layout as identity_mfma_f64_kernel.  A stage is 8 k deep (A 128 x 8 and B 8 x 128
-// doubles, 16 KB); a ring of 4 stages is 64 KB, two workgroups per compute unit.  The hardware
+// doubles, 16 KB); a ring of 4 stages is 64 KB, two workgroups per compute unit.  (Also as a
+// 64 x 64 tile, 4 waves of 32 x 32, 8 KB stages, for problems of few tiles: the template's T.  The
+// layouts below are given for T = 128; with 64 a slice has half the lines.)  The hardware
 // pairs k-slot h (= lane / 16) of A with k-slot h of B, so which k a slot carries is free: the
 // stage's first matrix step takes k = h, the second k = 4 + h.
 //
@@ -37,11 +39,26 @@ namespace amulet {
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-constexpr int DD_BM = 128, DD_BN = 128, DD_BK = 8, DD_NT = 512;
-constexpr int DD_A_BYTES = DD_BM * DD_BK * 8;       // 8 KB = 8 wave-loads
-constexpr int DD_B_BYTES = DD_BK * DD_BN * 8;       // 8 KB = 8 wave-loads
-constexpr int DD_STAGE_BYTES = DD_A_BYTES + DD_B_BYTES;
+constexpr int DD_BK = 8;
 constexpr int DD_LOADS = 2;                         // DMA instructions per wave per stage
+// T: rows and columns of a tile.  128: 8 waves of 32 x 64; 64: 4 waves of 32 x 32, for problems with
+// fewer 128 x 128 tiles than compute units (same code: a wave loads 1 KB of each operand's slice
+// per stage either way).
+template <int T>
+struct DdTile {
+    static constexpr int NT = T * 4;                    // threads: one wave per 16 lines of a slice
+    static constexpr int NB = T / 32;                   // 16-column blocks per wave
+    static constexpr int OP_BYTES = T * DD_BK * 8;      // one operand's 8-k slice: 8 KB / 4 KB
+    static constexpr int STAGE_BYTES = 2 * OP_BYTES;
+    static constexpr int ROW_BYTES = T * 8;             // a k-row of a k-major slice
+    static constexpr int ROW_UNITS = T / 2;             // its 16-byte units
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_f64()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 extern __shared__ __attribute__((aligned(16))) char dd_smem[];
 
@@ -49,11 +66,14 @@ extern __shared__ __attribute__((aligned(16))) char dd_smem[];
 // 8-k slice of the tile keeps its global layout in LDS, "k-minor" (128 lines x 8 k, k contiguous:
 // row-major A, transposed B) or "k-major" (8 k x 128 lines: row-major B, transposed A), with the
 // swizzles given above for A and B respectively.
-template <int NSTAGE, bool TA, bool TB>
-__global__ void __launch_bounds__(DD_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+template <int NSTAGE, bool TA, bool TB, int T>
+__global__ void __launch_bounds__(T * 4) __attribute__((amdgpu_waves_per_eu(4, 4)))
 identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 {
-    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
+    static_assert(NSTAGE >= 3 && NSTAGE <= 8, "the wait counts are written for rings of 3 to 8 stages");
+    typedef DdTile<T> TL;
+    constexpr int DD_BM = T, DD_BN = T, DD_A_BYTES = TL::OP_BYTES, DD_STAGE_BYTES = TL::STAGE_BYTES;
+    constexpr int NB = TL::NB, WC = 16 * NB, ROWB = TL::ROW_BYTES, NM = 2 * NB, READS = 2 + NB;
     constexpr bool A_KMINOR = !TA, B_KMINOR = TB;
     const int M = args.M, N = args.N;
     int K = args.K;
@@ -93,7 +113,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // ---- what each lane fetches: one A slot and one B slot per stage -----------------------
     // wave w owns the 1 KB slot group w of each operand's slice:
     //   k-minor slice: slot 64 w + lane -> line 16 w + lane / 4, physical unit lane % 4
-    //   k-major slice: k-row w, physical unit lane
+    //   k-major slice: slot 64 w + lane -> k and physical unit = quotient and remainder by the units of a k-row
     // `lines` of the tile exist (128 but in an edge tile), and every load stays inside the operand.
     // k-minor: a line past them is replaced by the last one inside.  k-major: a unit of two lines
     // that would end past them is fetched as the two lines that end AT the edge (a 16-byte piece
@@ -109,10 +129,12 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
             const int line_in = line < lines ? line : lines - 1;
             return ((uint32_t)line_in * (uint32_t)ld + (uint32_t)(u * 2)) * 8u;
         }
-        const int u = lane ^ ((wave & 1) << 3);
+        const int slot = 64 * wave + lane;
+        const int k = slot / TL::ROW_UNITS;
+        const int u = (slot % TL::ROW_UNITS) ^ ((k & 1) << 3);
         const int lead = lines < 2 ? 2 - lines : 0;
         const int start = 2 * u + 2 <= lines ? 2 * u + lead : lines - 2 + lead;
-        return ((uint32_t)wave * (uint32_t)ld + (uint32_t)start) * 8u;
+        return ((uint32_t)k * (uint32_t)ld + (uint32_t)start) * 8u;
     };
     const int rows_in = M - row0 < DD_BM ? M - row0 : DD_BM, cols_in = N - col0 < DD_BN ? N - col0 : DD_BN;
     const int a_lead = !A_KMINOR && rows_in < 2 ? 2 - rows_in : 0, b_lead = !B_KMINOR && cols_in < 2 ? 2 - cols_in : 0;
@@ -144,9 +166,9 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 
     // ---- where each lane reads its fragments (byte offsets inside an operand's slice) --------
     // matrix step g of the stage multiplies k = 4g + lh; the lane's line is wr*32 + mi*16 + li of
-    // A, wc*64 + ni*16 + li of B; one 8-byte read per block in either layout:
+    // A, wc*WC + ni*16 + li of B; one 8-byte read per block in either layout:
     //   k-minor: line * 64 + swizzled unit of k, per step g (+ 1024 per block)
-    //   k-major: k-row * 1024 + swizzled unit of the line, per block (+ 4096 per step)
+    //   k-major: k-row * ROWB + swizzled unit of the line, per block (+ 4 ROWB per step)
     auto minor_off = [&](int line, int g) {
         const int k = 4 * g + lh;
         return line * 64 + (((k >> 1) ^ ((line >> 2) & 3)) * 16) + (k & 1) * 8;
@@ -155,39 +177,39 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         const int unit = (line0 >> 1) + blk * 8 + (li >> 1);
         // (the line of the unit an odd edge cuts sits one place further up)
         const int edge_shift = (lines & 1) && line0 + blk * 16 + li >= (lines & ~1) ? 1 : 0;
-        return lh * 1024 + ((unit ^ ((lh & 1) << 3)) * 16) + ((li & 1) + edge_shift) * 8;
+        return lh * ROWB + ((unit ^ ((lh & 1) << 3)) * 16) + ((li & 1) + edge_shift) * 8;
     };
-    int a_off[2], b_off[4];   // k-minor: per step g; k-major: per block
+    int a_off[2], b_off[NB];   // k-minor: per step g; k-major: per block
 #pragma unroll
     for (int x = 0; x < 2; ++x) a_off[x] = A_KMINOR ? minor_off(wr * 32 + li, x) : major_off(wr * 32, x, rows_in);
 #pragma unroll
-    for (int x = 0; x < 4; ++x)
-        b_off[x] = DD_A_BYTES + (B_KMINOR ? minor_off(wc * 64 + li, x & 1) : major_off(wc * 64, x, cols_in));
-    // fragment read i (0..5) of matrix step g of the stage in slot `buf`: 0, 1 = A (mi), 2..5 = B (ni)
-    auto read_one = [&](int buf, int g, int i, double (&a)[2], double (&b)[4]) {
+    for (int x = 0; x < NB; ++x)
+        b_off[x] = DD_A_BYTES + (B_KMINOR ? minor_off(wc * WC + li, x & 1) : major_off(wc * WC, x, cols_in));
+    // fragment read i (0 .. READS-1) of matrix step g of the stage in slot `buf`: 0, 1 = A (mi), then B (ni)
+    auto read_one = [&](int buf, int g, int i, double (&a)[2], double (&b)[NB]) {
         const char *st = dd_smem + buf * DD_STAGE_BYTES;
-        if (i < 2) a[i] = *(const double *)(st + (A_KMINOR ? a_off[g] + i * 1024 : a_off[i] + g * 4096));
-        else b[i - 2] = *(const double *)(st + (B_KMINOR ? b_off[g] + (i - 2) * 1024 : b_off[i - 2] + g * 4096));
+        if (i < 2) a[i] = *(const double *)(st + (A_KMINOR ? a_off[g] + i * 1024 : a_off[i] + g * 4 * ROWB));
+        else b[i - 2] = *(const double *)(st + (B_KMINOR ? b_off[g] + (i - 2) * 1024 : b_off[i - 2] + g * 4 * ROWB));
     };
-    d4 acc[2][4];
+    d4 acc[2][NB];
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
+        for (int ni = 0; ni < NB; ++ni)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[mi][ni][v] = 0.0;
-    // The 8 matrix instructions of one matrix step, with `side(i)` issued right after
+    // The NM matrix instructions of one matrix step, with `side(i)` issued right after
     // instruction i: a wave issues in order and a matrix instruction occupies the matrix core for
     // 64 cycles during which the wave may issue other instructions, so the stage's LDS reads and
     // loads are spread over those gaps instead of standing between two runs of matrix
     // instructions.
-    auto mma_with = [&](const double (&a)[2], const double (&b)[4], auto side) {
+    auto mma_with = [&](const double (&a)[2], const double (&b)[NB], auto side) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
+            for (int ni = 0; ni < NB; ++ni) {
                 acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-                side(mi * 4 + ni);
+                side(mi * NB + ni);
                 __builtin_amdgcn_sched_barrier(0);
             }
     };
@@ -196,11 +218,13 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     // may still be outstanding.  (The count is an immediate: one instruction per value.)
     auto wait_stage = [&](int t, int upto) {
         switch (upto - t) {
-        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-        case 1: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
-        case 2: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-        case 3: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never too little
+        case 1: wait_vmcnt_f64<DD_LOADS>(); break;
+        case 2: wait_vmcnt_f64<2 * DD_LOADS>(); break;
+        case 3: wait_vmcnt_f64<3 * DD_LOADS>(); break;
+        case 4: wait_vmcnt_f64<4 * DD_LOADS>(); break;
+        case 5: wait_vmcnt_f64<5 * DD_LOADS>(); break;
+        case 6: wait_vmcnt_f64<6 * DD_LOADS>(); break;
+        default: wait_vmcnt_f64<0>(); break;   // never too little
         }
     };
 
@@ -234,7 +258,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
             const int k = kt + 4 * step + lh;
             const bool ok = k < kend;
             const int64_t kc = ok ? k : kend - 1;
-            double av[2], bv[4];
+            double av[2], bv[NB];
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
                 const int r = wr * 32 + mi * 16 + li;
@@ -243,8 +267,8 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
                 av[mi] = ok ? a : 0.0;
             }
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                const int c = wc * 64 + ni * 16 + li;
+            for (int ni = 0; ni < NB; ++ni) {
+                const int c = wc * WC + ni * 16 + li;
                 const int64_t line = col0 + (c < cols_in ? c : cols_in - 1);
                 const double b = TB ? args.B[line * args.ldb + kc] : args.B[kc * args.ldb + line];
                 bv[ni] = ok ? b : 0.0;
@@ -252,7 +276,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
+                for (int ni = 0; ni < NB; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
         }
     }
@@ -260,20 +284,21 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
-    double fa0[2], fa1[2], fb0[4], fb1[4];
+    double fa0[2], fa1[2], fb0[NB], fb1[NB];
     int buf = 0, ibuf = NSTAGE - 1;
 #pragma unroll
-    for (int i = 0; i < 6; ++i) read_one(0, 0, i, fa0, fb0);
+    for (int i = 0; i < READS; ++i) read_one(0, 0, i, fa0, fb0);
     auto iteration = [&](int s, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         // step 0 of stage s; the fragments of step 1 are read meanwhile
-        mma_with(fa0, fb0, [&](int i) { if (i < 6) read_one(buf, 1, i, fa1, fb1); });
+        mma_with(fa0, fb0, [&](int i) {
+#pragma unroll
+            for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
+        });
         if constexpr (STEADY) {
             // stages up to s+NSTAGE-2 are requested; s+1 must have landed
-            if constexpr (NSTAGE == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            else if constexpr (NSTAGE == 4) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            wait_vmcnt_f64<(NSTAGE - 3) * DD_LOADS>();
         } else {
             const int last = s + NSTAGE - 2 < n_stages - 1 ? s + NSTAGE - 2 : n_stages - 1;
             wait_stage(s + 1, last);
@@ -283,9 +308,13 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         // step 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
         // has left) and the fragment reads of step 0 of stage s+1
         const bool more = STEADY || s + NSTAGE - 1 < n_stages;
-        mma_with(fa1, fb1, [&](int i) {
+        auto piece = [&](int i) {
             if (i < DD_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
             else read_one(nbuf, 0, i - DD_LOADS, fa0, fb0);
+        };
+        mma_with(fa1, fb1, [&](int i) {
+#pragma unroll
+            for (int p = i; p < DD_LOADS + READS; p += NM) piece(p);
         });
         ap += a_stage;
         bp += b_stage;
@@ -296,7 +325,10 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     int s = 0;
     for (; s < steady_end; ++s) iteration(s, std::true_type());
     for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
-    mma_with(fa0, fb0, [&](int i) { if (i < 6) read_one(buf, 1, i, fa1, fb1); });
+    mma_with(fa0, fb0, [&](int i) {
+#pragma unroll
+        for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
+    });
     mma_with(fa1, fb1, [&](int) {});
 
     // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc: the 16 values
@@ -309,26 +341,26 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         double *dst[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            dst[v] = args.R + (int64_t)(row0 + wr * 32 + mi * 16 + 4 * v + lh) * args.ldr + col0 + wc * 64 + li;
+            dst[v] = args.R + (int64_t)(row0 + wr * 32 + mi * 16 + 4 * v + lh) * args.ldr + col0 + wc * WC + li;
         if (ksplit || edge) {
             // (an edge tile adds with atomics too, the elements that exist: R has one owner here, so
             // the sum is the same single rounding, and an atomic needs no round trip to memory
             // before the store, which under a per-element mask would be one after the other)
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
+            for (int ni = 0; ni < NB; ++ni)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * 64 + ni * 16 + li;
+                    const int row = wr * 32 + mi * 16 + 4 * v + lh, col = wc * WC + ni * 16 + li;
                     if (row < rows_in && col < cols_in) unsafeAtomicAdd(dst[v] + ni * 16, acc[mi][ni][v]);
                 }
         } else {
-            double old[4][4];
+            double old[NB][4];
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
+            for (int ni = 0; ni < NB; ++ni)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) old[ni][v] = dst[v][ni * 16];
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
+            for (int ni = 0; ni < NB; ++ni)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) dst[v][ni * 16] = old[ni][v] + acc[mi][ni][v];
         }
@@ -343,32 +375,41 @@ bool identity_f64_dma_eligible(const MmlikeArgsF64 &a)
 {
     if (a.M <= 0 || a.N <= 0 || a.K < DD_BK || (a.kchunk < a.K && a.kchunk % DD_BK)) return false;
     if ((a.transA && a.M < 2) || (!a.transB && a.N < 2)) return false;
-    // a k-minor slice spans 128 lines of the operand's storage, a k-major one 8
-    const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / DD_BM, major_max = (0x7FFFFFFFLL / 8 - DD_BN) / DD_BK;
+    // a k-minor slice spans up to 128 lines of the operand's storage, a k-major one 8
+    const int64_t minor_max = (0x7FFFFFFFLL / 8 - 8) / 128, major_max = (0x7FFFFFFFLL / 8 - 128) / DD_BK;
     if (a.lda > (a.transA ? major_max : minor_max) || a.ldb > (a.transB ? minor_max : major_max)) return false;
     return true;
 }
 
-template <bool TA, bool TB>
+template <int NSTAGE, bool TA, bool TB, int T>
 static hipError_t enqueue_f64_layout(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    constexpr int NSTAGE = 4;
-    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_dma_kernel<NSTAGE, TA, TB>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * DD_STAGE_BYTES);
+    constexpr int LDS = NSTAGE * DdTile<T>::STAGE_BYTES;
+    static hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void *>(&identity_mfma_f64_dma_kernel<NSTAGE, TA, TB, T>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((identity_mfma_f64_dma_kernel<NSTAGE, TA, TB>), dim3(grid_x, grid_y), dim3(DD_NT), NSTAGE * DD_STAGE_BYTES, s, a);
+    hipLaunchKernelGGL((identity_mfma_f64_dma_kernel<NSTAGE, TA, TB, T>), dim3(grid_x, grid_y), dim3(DdTile<T>::NT), LDS, s, a);
     return hipSuccess;
 }
 
-// Enqueues grid.x x grid.y workgroups of the streamed kernel (ring of 4 stages; the caller has
-// checked identity_f64_dma_eligible and fills the split fields of `a` as for
-// identity_mfma_f64_kernel).
-hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
+template <int NSTAGE, int T>
+static hipError_t enqueue_f64_tile(const MmlikeArgsF64 &a, unsigned grid_x, unsigned grid_y, hipStream_t s)
 {
-    if (a.transA && a.transB) return enqueue_f64_layout<true, true>(a, grid_x, grid_y, s);
-    if (a.transA) return enqueue_f64_layout<true, false>(a, grid_x, grid_y, s);
-    if (a.transB) return enqueue_f64_layout<false, true>(a, grid_x, grid_y, s);
-    return enqueue_f64_layout<false, false>(a, grid_x, grid_y, s);
+    if (a.transA && a.transB) return enqueue_f64_layout<NSTAGE, true, true, T>(a, grid_x, grid_y, s);
+    if (a.transA) return enqueue_f64_layout<NSTAGE, true, false, T>(a, grid_x, grid_y, s);
+    if (a.transB) return enqueue_f64_layout<NSTAGE, false, true, T>(a, grid_x, grid_y, s);
+    return enqueue_f64_layout<NSTAGE, false, false, T>(a, grid_x, grid_y, s);
+}
+
+// Enqueues grid.x x grid.y workgroups of the streamed kernel: tiles of 128 rows and columns (512
+// threads, ring of 4 stages) or of 64 (256 threads, ring of ID_SMALL_STAGES).  The caller has
+// checked identity_f64_dma_eligible and fills the split fields of `a` as for
+// identity_mfma_f64_kernel.
+hipError_t enqueue_identity_f64_dma(const MmlikeArgsF64 &a, int tile, unsigned grid_x, unsigned grid_y, hipStream_t s)
+{
+    if (tile == 128) return enqueue_f64_tile<4, 128>(a, grid_x, grid_y, s);
+    if (tile == 64) return enqueue_f64_tile<ID_SMALL_STAGES, 64>(a, grid_x, grid_y, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace amulet

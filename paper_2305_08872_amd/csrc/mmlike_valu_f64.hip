@@ -579,11 +579,12 @@ static hipError_t launch_mmlike_f64_waves(int task, int form, int force_splits, 
 
 // shape = k-axis index * F64_TILES + tile; tile 0: 16 x 128 (4 waves), tile 1: 32 x 128 (8 waves);
 // k axis 0: K split only where the launcher's own rule asks for it, 1, 2: every tile's K in 2, 4
-// parts.  The identity task runs on the matrix cores whatever the shape.
+// parts.  The identity task, a dense contraction, runs on the matrix cores whatever the shape, and
+// only the shape's tile index means something to it: 0 = 64 x 64 tiles, 1 = 128 x 128.
 hipError_t launch_mmlike_f64(int task, int form, int shape, const MmlikeArgsF64 &a, hipStream_t s)
 {
-    if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, s);   // a dense contraction: matrix cores
     if (shape < 0 || shape >= F64_SHAPE_COUNT) return hipErrorInvalidValue;
+    if (task == TASK_IDENTITY) return launch_identity_mfma_f64(a, shape % F64_TILES == 0 ? 64 : 128, s);
     const int force = shape / F64_TILES == 0 ? 0 : 1 << (shape / F64_TILES);
     return shape % F64_TILES == 1 ? launch_mmlike_f64_waves<8>(task, form, force, a, s)
                                   : launch_mmlike_f64_waves<4>(task, form, force, a, s);

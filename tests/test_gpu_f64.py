@@ -393,7 +393,8 @@ def test_f64_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch)
 
 @pytest.mark.parametrize("tA,tB", [(False, False), (True, False), (False, True), (True, True)])
 def test_f64_identity_streamed_kernel_on_every_size(am, tA, tB):
-    """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS runs on operands
+    """The fp64 matrix-core identity kernel that streams its operands HBM -> LDS (128 x 128 and
+    64 x 64 tiles) runs on operands
     of any size and alignment with at least one 8-k stage, in any of the four operand layouts.  Cases: fewer stages than the ring holds, one tile, several tiles with padded pitches
     and a non-zero R_in, few tiles with a long K (every tile split over workgroups), a few more
     tiles than compute units (the last round's tiles split), and exact data bit for bit.  Every
@@ -409,7 +410,10 @@ def test_f64_identity_streamed_kernel_on_every_size(am, tA, tB):
              # odd sizes and pitches: rows that are not 16-byte aligned, edges that cut a two-line
              # unit, tiles of one line (129 = 128 + 1), the smallest operands the kernel takes
              (129, 131, 17, 0), (257, 259, 203, 1), (127, 129, 1001, 0), (3, 5, 24, 0), (2, 2, 8, 0), (130, 133, 1037, 3),
-             (1301, 3203, 1109, 0)]
+             (1301, 3203, 1109, 0),
+             # around the 64 x 64 tile: one tile and one stage, a line more than whole tiles, fewer
+             # stages than its ring holds plus a tail, few tiles with a long K
+             (64, 64, 8, 0), (65, 67, 17, 0), (190, 70, 50, 2), (192, 320, 2100, 0)]
     for idx, (M, N, K, pad) in enumerate(cases):
         A, B, th, dis, R_in = make_case(0, M, N, K, 9960 + idx)
         As = np.ascontiguousarray(A.T) if tA else A
@@ -419,19 +423,22 @@ def test_f64_identity_streamed_kernel_on_every_size(am, tA, tB):
         bufA[:, :As.shape[1]] = dev(As)
         bufB = torch.full((Bs.shape[0], Bs.shape[1] + pad), float("nan"), dtype=torch.float64, device="cuda")
         bufB[:, :Bs.shape[1]] = dev(Bs)
-        print("f64 identity streamed", tA, tB, M, N, K, pad, flush=True)
-        dR = dev(R_in)
-        am.amulet_mmlike_f64(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR, trans_a=tA, trans_b=tB)
-        torch.cuda.synchronize()
-        check(dR.cpu().numpy(), R_ref, ab, R_in, 0, "f64 identity streamed %dx%dx%d" % (M, N, K))
+        for shape in (1, 0, -1):   # (the identity task reads the shape's tile index: 128 x 128, 64 x 64, the rule)
+            print("f64 identity streamed", tA, tB, M, N, K, pad, shape, flush=True)
+            dR = dev(R_in)
+            am.amulet_mmlike_f64(0, bufA[:, :As.shape[1]], bufB[:, :Bs.shape[1]], None, None, dR, trans_a=tA, trans_b=tB,
+                                 shape=shape)
+            torch.cuda.synchronize()
+            check(dR.cpu().numpy(), R_ref, ab, R_in, 0, "f64 identity streamed %dx%dx%d shape %d" % (M, N, K, shape))
     A, B, th, dis, R_in = make_case(0, 256, 256, 1600, 9970, exact=True)
     As = np.ascontiguousarray(A.T) if tA else A
     Bs = np.ascontiguousarray(B.T) if tB else B
     R_ref, _, _ = oracle.mmlike_f64_general(0, As, Bs, None, None, R_in, trans_a=tA, trans_b=tB)
-    dR = dev(R_in)
-    am.amulet_mmlike_f64(0, dev(As), dev(Bs), None, None, dR, trans_a=tA, trans_b=tB)
-    torch.cuda.synchronize()
-    assert np.array_equal(dR.cpu().numpy(), R_ref)
+    for shape in (1, 0):
+        dR = dev(R_in)
+        am.amulet_mmlike_f64(0, dev(As), dev(Bs), None, None, dR, trans_a=tA, trans_b=tB, shape=shape)
+        torch.cuda.synchronize()
+        assert np.array_equal(dR.cpu().numpy(), R_ref), shape
 
 
 @pytest.mark.parametrize("task,M,N,K", [(1, 64, 128, 20000), (3, 770, 3050, 1100), (0, 1536, 1536, 2048), (0, 300, 300, 4096)])
