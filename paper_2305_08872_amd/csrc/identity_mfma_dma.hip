@@ -328,14 +328,17 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     int buf = 0, ibuf = NSTAGE - 1;
 #pragma unroll
     for (int i = 0; i < READS; ++i) read_one(0, 0, i, fa0, fb0);
+    // the fragment reads of group 1 of the stage in `slot`, spread over the matrix instructions of
+    // group 0
+    auto side_reads = [&](int i, int slot) {
+#pragma unroll
+        for (int p = i; p < READS; p += NM) read_one(slot, 1, p, fa1, fb1);
+    };
     auto iteration = [&](int s, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         // group 0 of stage s; the fragments of group 1 are read meanwhile
-        mma_with(fa0, fb0, [&](int i) {
-#pragma unroll
-            for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
-        });
+        mma_with(fa0, fb0, [&](int i) { side_reads(i, buf); });
         if constexpr (STEADY) {
             // stages up to s+NSTAGE-2 are requested; s+1 must have landed
             wait_vmcnt<(NSTAGE - 3) * ID_LOADS>();
@@ -349,13 +352,20 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
         // has left) and the fragment reads of group 0 of stage s+1: ID_LOADS + READS pieces over NM
         // matrix instructions, the first few of which take one more than the rest
         const bool more = STEADY || s + NSTAGE - 1 < n_stages;
-        auto piece = [&](int i) {
-            if (i < ID_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
-            else if (i < ID_LOADS + READS) read_one(nbuf, 0, i - ID_LOADS, fa0, fb0);
-        };
         mma_with(fa1, fb1, [&](int i) {
+            if constexpr (BLK == 1) {
+                // (four matrix instructions a group: the reads first, each a whole group ahead of its
+                // use; the two loads behind the last two instructions)
 #pragma unroll
-            for (int p = i; p < ID_LOADS + READS; p += NM) piece(p);
+                for (int p = i; p < READS; p += NM) read_one(nbuf, 0, p, fa0, fb0);
+                if (i >= NM - ID_LOADS && more) issue_one(ap, bp, ibuf, i - (NM - ID_LOADS));
+            } else {
+#pragma unroll
+                for (int p = i; p < ID_LOADS + READS; p += NM) {
+                    if (p < ID_LOADS) { if (more) issue_one(ap, bp, ibuf, p); }
+                    else read_one(nbuf, 0, p - ID_LOADS, fa0, fb0);
+                }
+            }
         });
         ap += a_stage;
         bp += b_stage;
@@ -366,10 +376,7 @@ __global__ void __launch_bounds__(256) identity_mfma_dma_kernel(const MmlikeArgs
     int s = 0;
     for (; s < steady_end; ++s) iteration(s, std::true_type());
     for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
-    mma_with(fa0, fb0, [&](int i) {
-#pragma unroll
-        for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
-    });
+    mma_with(fa0, fb0, [&](int i) { side_reads(i, buf); });
     mma_with(fa1, fb1, [&](int) {});
     if constexpr (NACC == 2) {
 #pragma unroll

@@ -288,14 +288,24 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     int buf = 0, ibuf = NSTAGE - 1;
 #pragma unroll
     for (int i = 0; i < READS; ++i) read_one(0, 0, i, fa0, fb0);
+    // the fragment reads of step g of the stage in `slot`, spread over the matrix instructions of
+    // the step before.  (The 64 x 64 tile has 4 matrix instructions of 32 cycles a step: its four
+    // reads go behind the first two, in the order of their use -- a0 b0, b1 a1 -- so that each is
+    // at least two matrix instructions ahead of it.)
+    auto side_reads = [&](int i, int slot, int g, double (&a)[2], double (&b)[NB]) {
+        if constexpr (T == 64) {
+            if (i == 0) { read_one(slot, g, 0, a, b); read_one(slot, g, 2, a, b); }
+            if (i == 1) { read_one(slot, g, 3, a, b); read_one(slot, g, 1, a, b); }
+        } else {
+#pragma unroll
+            for (int p = i; p < READS; p += NM) read_one(slot, g, p, a, b);
+        }
+    };
     auto iteration = [&](int s, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
         const int nbuf = buf == NSTAGE - 1 ? 0 : buf + 1;
         // step 0 of stage s; the fragments of step 1 are read meanwhile
-        mma_with(fa0, fb0, [&](int i) {
-#pragma unroll
-            for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
-        });
+        mma_with(fa0, fb0, [&](int i) { side_reads(i, buf, 1, fa1, fb1); });
         if constexpr (STEADY) {
             // stages up to s+NSTAGE-2 are requested; s+1 must have landed
             wait_vmcnt_f64<(NSTAGE - 3) * DD_LOADS>();
@@ -308,13 +318,17 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
         // step 1 of stage s; meanwhile the request for stage s+NSTAGE-1 (into the slot stage s-1
         // has left) and the fragment reads of step 0 of stage s+1
         const bool more = STEADY || s + NSTAGE - 1 < n_stages;
-        auto piece = [&](int i) {
-            if (i < DD_LOADS) { if (more) issue_one(ap, bp, ibuf, i); }
-            else read_one(nbuf, 0, i - DD_LOADS, fa0, fb0);
-        };
         mma_with(fa1, fb1, [&](int i) {
+            if constexpr (T == 64) {
+                side_reads(i, nbuf, 0, fa0, fb0);
+                if (i >= 2 && more) issue_one(ap, bp, ibuf, i - 2);
+            } else {
 #pragma unroll
-            for (int p = i; p < DD_LOADS + READS; p += NM) piece(p);
+                for (int p = i; p < DD_LOADS + READS; p += NM) {
+                    if (p < DD_LOADS) { if (more) issue_one(ap, bp, ibuf, p); }
+                    else read_one(nbuf, 0, p - DD_LOADS, fa0, fb0);
+                }
+            }
         });
         ap += a_stage;
         bp += b_stage;
@@ -325,10 +339,7 @@ identity_mfma_f64_dma_kernel(const MmlikeArgsF64 args)
     int s = 0;
     for (; s < steady_end; ++s) iteration(s, std::true_type());
     for (; s + 1 < n_stages; ++s) iteration(s, std::false_type());
-    mma_with(fa0, fb0, [&](int i) {
-#pragma unroll
-        for (int p = i; p < READS; p += NM) read_one(buf, 1, p, fa1, fb1);
-    });
+    mma_with(fa0, fb0, [&](int i) { side_reads(i, buf, 1, fa1, fb1); });
     mma_with(fa1, fb1, [&](int) {});
 
     // element v of lane l is R[4 v + l / 16][l % 16] of its 16 x 16 block.  R += acc: the 16 values
