@@ -677,8 +677,18 @@ static hipError_t launch_one(const MmlikeArgs &a, hipStream_t s)
             splits = (int)((a.K + chunk - 1) / chunk);
         }
     } else if (k_split_allowed() && waves <= 2048 && a.K >= 128) {
-        int64_t want = 4096 / waves;   // as many as still fit the chip at once (4 waves per SIMD)
-        if (want > a.K / 64) want = a.K / 64;
+        // As many parts as fill the chip to three waves per SIMD (four when the tiles alone fill one),
+        // of at least 64 k each and, from K = 512 on, of about 192: every part pays a first load of
+        // B, a pipeline fill and a tile of atomic adds, and parts of one tile that finish together
+        // queue on the same lines of R.  Measured over forced counts 1 ... 64, us, this rule / as many
+        // parts of 64 k as fit at four waves per SIMD (the earlier rule) / best forced: 512^3 40 / 55 / 40,
+        // 640^3 49 / 55 / 46, 768^3 63 / 73 / 61, 512^2 x 1024 58 / 86 / 54, 768^2 x 384 43 / 59 / 43,
+        // 128 x 4096 x 512 42 / 64 / 42, 256^2 x 4096 56 / 85 / 55, 512^2 x 2048 80 / 93 / 78,
+        // 1024^2 x 512 71 / 76 / 65; 256^3, 384^3, 896^3, 1024^3 unchanged (17, 24, 78, 97).
+        int64_t want = (waves >= 1024 ? 4096 : 3072) / waves;
+        const int64_t most = a.K < 512 ? a.K / 64 : (a.K + 96) / 192;
+        if (want > most) want = most;
+        if (want < 1) want = 1;
         if (want > 1024) want = 1024;
         const int64_t chunk = ((a.K + want - 1) / want + 63) / 64 * 64;   // whole partial-sum periods
         b.kchunk = (int)chunk;
