@@ -63,6 +63,26 @@ static int n_shapes(int task)
 // staging is the measured best at every size; of its two workgroup sizes the
 // 8-wave one (32 x 256) is ahead by 2-9 % once there are two such tiles per
 // compute unit (or a long K to split, see below), the 4-wave one (16 x 256) below that.
+// Identity task: 64 x 64 tiles instead of 128 x 128?  With fewer large tiles than compute units,
+// always (four times the tiles fill the chip without a K split, or with a smaller one).  Up to four
+// large tiles per unit, when the small tiles' count leaves clearly less of the last tile per unit
+// unused: every unit gets a whole number of tiles, so 576 large tiles on 256 units cost three
+// tiles' time for 2.25 tiles' work while 2304 small ones are nine each (3072^3: 460 against 422 us,
+// 3072^2 x 1024: 180 / 151, 3584^3: 708-733 / 691, 2560^3: 275 / 270).  Where the counts are as even
+// the large tile is 2-6 % ahead (it streams half the bytes per operation: 2048^3 128.5 / 131,
+// 2816^3 329 / 340, 4096^3 942 / 990), and with more tiles the rounds no longer line up anyway.
+static bool identity_small_tile_wanted(int64_t M, int64_t N, bool f64 = false)
+{
+    const int64_t units = compute_units();
+    const int64_t large = ((M + 127) / 128) * ((N + 127) / 128), small = ((M + 63) / 64) * ((N + 63) / 64);
+    // (fp64, whose large tile holds two workgroups to a unit: also with exactly one large tile per
+    // unit, 2048^3 258 against 272 us, 2048^2 x 512 71 / 80)
+    if (large < units + (f64 ? 1 : 0)) return true;
+    if (large >= 4 * units) return false;
+    auto unused = [&](int64_t tiles) { const int64_t r = (tiles + units - 1) / units * units; return (double)(r - tiles) / (double)r; };
+    return unused(small) + 0.05 < unused(large);
+}
+
 static int default_shape(int task, int64_t M, int64_t N, int64_t K)
 {
     // Matrix cores.  Fewer 128 x 256 tiles than compute units: the register-staged 128 x 128 tile
@@ -93,10 +113,10 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
         // the workgroups' finishing times spread and the fuller unit wins (2048 tiles: 145 against
         // 141, 4096: 149 against 147, 8192 tiles x K = 512: 134 against 128).
         const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-        // Fewer 128 x 128 tiles than compute units: 64 x 64 tiles (us, against the ring of 3: 512^3
-        // 10.1 / 13.4, 1024^3 21.4 / 30.7, 1792^3 104 / 113, 1536^2 x 4096 154 / 166, 512^2 x 8192 40 / 46;
-        // from 256 tiles on the larger tile is level or ahead, 2048^3 135 / 129).
-        if (tiles < compute_units()) return IDENTITY_MFMA_SMALL_SHAPE;
+        // 64 x 64 tiles for problems of few tiles (us, against the ring of 3: 512^3 10.0 / 13.4, 1024^3
+        // 20.7 / 30.7, 1792^3 109 / 113, 1536^2 x 4096 148 / 166, 512^2 x 8192 40 / 46) and where their
+        // count suits the chip better (identity_small_tile_wanted).
+        if (identity_small_tile_wanted(M, N)) return IDENTITY_MFMA_SMALL_SHAPE;
         const int64_t round3 = 3 * (int64_t)compute_units(), round4 = 2 * (int64_t)compute_units();
         if (tiles <= round3 || tiles > 3 * round4) return IDENTITY_MFMA_DMA3_SHAPE;
         auto waste = [&](int64_t slots) { const int64_t r = (tiles + slots - 1) / slots * slots; return (double)(r - tiles) / (double)r; };
@@ -532,7 +552,7 @@ static int default_shape_f64(int task, int64_t M, int64_t N)
 static int lookup_shape_f64(int task, int64_t M, int64_t N, int64_t K)
 {
     // (identity: the matrix-core tile; 64 x 64 with fewer 128 x 128 tiles than compute units)
-    if (task == TASK_IDENTITY) return ((M + 127) / 128) * ((N + 127) / 128) < compute_units() ? 0 : 1;
+    if (task == TASK_IDENTITY) return identity_small_tile_wanted(M, N, true) ? 0 : 1;
     {
         std::lock_guard<std::mutex> lock(g_sel_mutex);
         auto it = g_selected.find(sel_key(f64_cache_task(task), M, N, K));
@@ -1291,7 +1311,7 @@ const char *amulet_shape_name(int task, int shape)
     if (task == AMULET_TASK_COUNT_I8) return kCountShapeNames[shape];
     if (is_mfma_shape(task, shape)) {
         static const char *const names[5] = {"mfma_f32_128x128_k16", "mfma_f32_256x256_w16_k16", "mfma_f32_128x128_dma3",
-                                             "mfma_f32_128x128_dma4", "mfma_f32_64x64_dma6"};
+                                             "mfma_f32_128x128_dma4", "mfma_f32_64x64_dma4"};
         return names[shape - IDENTITY_MFMA_SHAPE];
     }
     return kValuShapes[shape].name;

@@ -20,8 +20,9 @@ enum { THRES_COL = 0, THRES_ROW = 1, THRES_CONST = 2, THRES_ELEM = 3 };
 // part row tile by row tile: the workgroups resident on an XCD at any moment form a compact
 // block of R that shares A rows and B columns through that L2.  px is the one of 8, 4, 2, 1
 // whose largest part is smallest (ties go to more column parts), so that narrow grids and
-// column counts that are not multiples of 8 still load all XCDs evenly.  The grid is padded
-// to 8 * cw * rh workgroups; those past the edge leave at once.
+// column counts that are not multiples of 8 still give every XCD a part.  (Used as the tile order
+// when the parts cover the grid exactly, see below, and by the persistent join-count kernel, whose
+// grid is padded to 8 * cw * rh places; places past the edge hold no tile.)
 struct XcdParts {
     int px;   // column parts
     int cw;   // column tiles per part
@@ -43,20 +44,54 @@ __host__ __device__ inline XcdParts xcd_parts(int64_t tiles_m, int64_t tiles_n)
     }
     return best;
 }
+// The parts cover the grid exactly (no padding) when both tile counts divide.  Otherwise some
+// XCDs would get less than others, up to nothing (33 column tiles in 8 parts of 5: the last XCD
+// idle, the one before it at 3 / 5), and the launch takes as long as its fullest XCD.  Then the
+// tiles are put in one order instead -- column panels as wide as a part would be, row tile by
+// row tile inside a panel -- and that order is cut into 8 runs of equal length (to within one
+// tile): XCD x takes run x, still a compact block of R, and every XCD has the same number of tiles.
+__host__ __device__ inline bool xcd_parts_exact(const XcdParts &g, int64_t tiles_m, int64_t tiles_n)
+{
+    return 8LL * g.cw * g.rh == tiles_m * tiles_n;
+}
 // workgroups to launch for a tile grid
 inline int64_t xcd_grid(int64_t tiles_m, int64_t tiles_n)
 {
     const XcdParts g = xcd_parts(tiles_m, tiles_n);
-    return 8LL * g.cw * g.rh;
+    if (xcd_parts_exact(g, tiles_m, tiles_n)) return 8LL * g.cw * g.rh;
+    return 8LL * ((tiles_m * tiles_n + 7) / 8);
 }
 // tile of workgroup `block`; false when the workgroup is padding
 __host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     const XcdParts g = xcd_parts(tiles_m, tiles_n);
     const int xcd = block & 7, slot = block >> 3;
-    tn = (xcd % g.px) * g.cw + slot % g.cw;
-    tm = (xcd / g.px) * g.rh + slot / g.cw;
-    return tn < tiles_n && tm < tiles_m;
+    if (xcd_parts_exact(g, tiles_m, tiles_n)) {
+        tn = (xcd % g.px) * g.cw + slot % g.cw;
+        tm = (xcd / g.px) * g.rh + slot / g.cw;
+        return tn < tiles_n && tm < tiles_m;
+    }
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t first = tiles * xcd / 8, next = tiles * (xcd + 1) / 8;   // XCD x: places [first, next)
+    tm = 0;
+    tn = 0;
+    if (slot >= next - first) return false;
+    const int64_t idx = first + slot;
+    const int pw = (tiles_n + 7) / 8;                      // panel width, column tiles
+    const int64_t per_panel = (int64_t)pw * tiles_m;
+    const int full = tiles_n / pw;                         // panels of that width; one narrower may follow
+    const int64_t p = idx / per_panel;
+    if (p < full) {
+        const int64_t rem = idx - p * per_panel;
+        tm = (int)(rem / pw);
+        tn = (int)(p * pw + rem % pw);
+    } else {
+        const int wl = tiles_n - full * pw;
+        const int64_t rem = idx - (int64_t)full * per_panel;
+        tm = (int)(rem / wl);
+        tn = (int)(full * pw + rem % wl);
+    }
+    return true;
 }
 
 // Compute units of the current device (256 on MI355X), asked once per device.
@@ -331,7 +366,7 @@ enum { IDENTITY_MFMA_SHAPE = VALU_DEPTHS * VALU_TILES, IDENTITY_MFMA_BIG_SHAPE =
 hipError_t launch_identity_mfma(const MmlikeArgs &a, int variant, hipStream_t s);
 // the streamed kernel (identity_mfma_dma.hip)
 bool identity_dma_eligible(const MmlikeArgs &a);
-constexpr int ID_SMALL_STAGES = 6;   // ring depth of the streamed 64 x 64 tile
+constexpr int ID_SMALL_STAGES = 4;   // ring depth of the streamed 64 x 64 tiles (fp32 and fp64)
 hipError_t enqueue_identity_dma(const MmlikeArgs &a, int tile, int nstage, unsigned grid_x, unsigned grid_y, hipStream_t s);
 
 template <int TASK, int TF>

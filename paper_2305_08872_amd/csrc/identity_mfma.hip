@@ -421,9 +421,11 @@ static hipError_t launch_identity_grid(const MmlikeArgs &a, int dma_stages, hipS
 // fills the chip without a K split or with a smaller one, and more of its write-back is plain
 // stores instead of atomic adds; a workgroup streams twice the operand bytes per operation and
 // has 8 matrix instructions per wave between barriers instead of 32, which is why the larger tile
-// is ahead once it has a tile per compute unit (2048^3: 129 against 135 us; 1024^3: 31 against 21).
-// K split: the streamed kernels' model with three workgroups (rings of 48 KB) to a unit; checked
-// against forced splits of 1 ... 12 at 512^3 ... 1792^3 and K up to 8192: the best or within 7 %.
+// is ahead where both tile counts suit the chip equally (2048^3: 128.5 against 131 us; 1024^3: 31
+// against 21).  Ring of 4 stages, 32 KB, five workgroups to a compute unit (rings of 6 and 8:
+// level at one workgroup per unit, 1-5 % behind with more; of 3: 1024^3 31 us).
+// K split: the streamed kernels' model; checked against forced splits of 1 ... 12 at 512^3 ...
+// 1792^3 and K up to 8192: the best or within 7 %.
 static hipError_t launch_identity_small(const MmlikeArgs &a, hipStream_t s)
 {
     MmlikeArgs b = a;
@@ -434,9 +436,9 @@ static hipError_t launch_identity_small(const MmlikeArgs &a, hipStream_t s)
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     int splits = 1;
-    const int cap = 3;
+    const int cap = 5;
     if (tiles_m * tiles_n <= 2 * cap * (int64_t)compute_units()) {
-        static const double rate[3] = {0.80, 0.93, 1.0};
+        static const double rate[5] = {0.80, 0.93, 1.0, 1.0, 1.0};
         const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, cap, rate, 200.0);
         if (sp > 1) {
             const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + MI_BK - 1) / MI_BK * MI_BK, MI_BK);

@@ -330,7 +330,7 @@ static hipError_t launch_di_layout(const MmlikeArgsF64 &a, unsigned grid, int64_
 
 // The streamed 64 x 64 tile, for problems with fewer 128 x 128 tiles than compute units (the fp64
 // counterpart of the fp32 kernel's small tile, identity_mfma.hip, where the reasons are given):
-// K split by the streamed kernels' model with three workgroups (rings of 48 KB) to a unit.
+// K split by the streamed kernels' model with four workgroups (rings of 32 KB) to a unit.
 static hipError_t launch_di_small(const MmlikeArgsF64 &a, hipStream_t s)
 {
     MmlikeArgsF64 b = a;
@@ -340,9 +340,9 @@ static hipError_t launch_di_small(const MmlikeArgsF64 &a, hipStream_t s)
     const int64_t grid = xcd_grid(tiles_m, tiles_n);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     int splits = 1;
-    const int cap = 3;
+    const int cap = 4;   // rings of 32 KB; the kernel is built for four waves per SIMD
     if (tiles_m * tiles_n <= 2 * cap * (int64_t)compute_units()) {
-        static const double rate[3] = {0.80, 0.93, 1.0};
+        static const double rate[4] = {0.80, 0.93, 1.0, 1.0};
         const int sp = choose_stream_split(grid / 8, compute_units() / 8, a.K, cap, rate, 100.0, 0.34);
         if (sp > 1) {
             const int64_t chunk = chunk_with_a_whole_last_stage(a.K, ((a.K + sp - 1) / sp + DI_BK - 1) / DI_BK * DI_BK, DI_BK);
