@@ -21,8 +21,7 @@ enum { THRES_COL = 0, THRES_ROW = 1, THRES_CONST = 2, THRES_ELEM = 3 };
 // block of R that shares A rows and B columns through that L2.  px is the one of 8, 4, 2, 1
 // whose largest part is smallest (ties go to more column parts), so that narrow grids and
 // column counts that are not multiples of 8 still give every XCD a part.  (Used as the tile order
-// when the parts cover the grid exactly, see below, and by the persistent join-count kernel, whose
-// grid is padded to 8 * cw * rh places; places past the edge hold no tile.)
+// when the parts cover the grid exactly, see below.)
 struct XcdParts {
     int px;   // column parts
     int cw;   // column tiles per part
@@ -54,13 +53,15 @@ __host__ __device__ inline bool xcd_parts_exact(const XcdParts &g, int64_t tiles
 {
     return 8LL * g.cw * g.rh == tiles_m * tiles_n;
 }
-// workgroups to launch for a tile grid
-inline int64_t xcd_grid(int64_t tiles_m, int64_t tiles_n)
+// places of one XCD's share of the order (the last of them may hold no tile)
+__host__ __device__ inline int64_t xcd_places(int64_t tiles_m, int64_t tiles_n)
 {
     const XcdParts g = xcd_parts(tiles_m, tiles_n);
-    if (xcd_parts_exact(g, tiles_m, tiles_n)) return 8LL * g.cw * g.rh;
-    return 8LL * ((tiles_m * tiles_n + 7) / 8);
+    if (xcd_parts_exact(g, tiles_m, tiles_n)) return (int64_t)g.cw * g.rh;
+    return (tiles_m * tiles_n + 7) / 8;
 }
+// workgroups to launch for a tile grid
+inline int64_t xcd_grid(int64_t tiles_m, int64_t tiles_n) { return 8 * xcd_places(tiles_m, tiles_n); }
 // tile of workgroup `block`; false when the workgroup is padding
 __host__ __device__ inline bool xcd_tile(int block, int tiles_m, int tiles_n, int &tm, int &tn)
 {

@@ -416,15 +416,14 @@ count_i8_dma_persistent_kernel(const CountArgs args)
 {
     typedef DmaTile<WR, NSTAGE> T;
     const int tiles_m = args.M / T::BM, tiles_n = args.N / DM_BN;
-    const XcdParts g = xcd_parts(tiles_m, tiles_n);
     const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3, n_slots = (int)gridDim.x >> 3;
-    const int places = g.cw * g.rh;              // places of one XCD's part (some may be padding)
+    const int places = (int)xcd_places(tiles_m, tiles_n);   // places of one XCD's share (the last may hold no tile)
     auto tile_at = [&](int place, int &row0, int &col0) {
-        const int tn = (xcd % g.px) * g.cw + place % g.cw;
-        const int tm = (xcd / g.px) * g.rh + place / g.cw;
+        int tm, tn;
+        const bool real = xcd_tile(place * 8 + xcd, tiles_m, tiles_n, tm, tn);
         row0 = tm * T::BM;
         col0 = tn * DM_BN;
-        return tn < tiles_n && tm < tiles_m;
+        return real;
     };
     const int n_st = args.K / DM_BK;             // stages of a tile's k range
     int phase = (slot * args.pers_groups / n_slots) * args.pers_group_stages;   // in stages
@@ -509,8 +508,7 @@ template <int WR>
 static int64_t persistent_grid(const CountArgs &a)
 {
     const int64_t tiles_m = a.M / (64 * WR), tiles_n = a.N / DM_BN;
-    const XcdParts g = xcd_parts(tiles_m, tiles_n);
-    const int64_t places = (int64_t)g.cw * g.rh;
+    const int64_t places = xcd_places(tiles_m, tiles_n);
     const int64_t slots = (int64_t)(compute_units() / 8) * (WR == 4 ? 1 : 2);
     if (slots <= 0 || places < 2 * slots || a.K < 2 * DM_BK) return 0;
     return 8 * slots;

@@ -251,7 +251,7 @@ def test_count_i8_few_tiles_long_k_split_over_workgroups(am, shape):
 
 
 @pytest.mark.parametrize("phases", ["1,0,1,0", "2,2,2,8", "8,2,2,16", "4,1,8,16", "16,3,4,12"])
-@pytest.mark.parametrize("shape", [8, 108, None])
+@pytest.mark.parametrize("shape", [8, 108, 208, None])
 def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     """Sizes large enough for the persistent streamed kernels (every workgroup walks at least two
     tiles of its XCD's part), with ragged edges around the whole-tile interior and a K of five
@@ -260,10 +260,13 @@ def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     sixteenths of K" (none, coarse, the default, fine, odd), full int8 value range, non-zero R_in,
     bit-exact; the row and column checksums cover the whole matrix, sampled rows and columns go
     against the oracle.  Shape 108: shape 8 on a tile count that is no whole number of rounds
-    (22 x 32 tiles: the XCDs' parts hold padding places and their workgroups walk 2 or 3 tiles)."""
+    (22 x 32 tiles: an XCD's workgroups walk 2 or 3 tiles); 208: shape 8 on 23 x 23 tiles, which no
+    cut into 8 rectangular parts covers (the XCDs walk equal runs of one panel order, 66 or 67 tiles
+    each, the last place of some holding no tile)."""
     monkeypatch.setenv("AMULET_I8_PHASES", phases)
-    M, N, K = {8: (8192 + 77, 4096 + 33, 320), 108: (5632 + 5, 8192 + 1, 320), None: (8192, 8192, 320)}[shape]
-    if shape == 108:
+    M, N, K = {8: (8192 + 77, 4096 + 33, 320), 108: (5632 + 5, 8192 + 1, 320), 208: (5888 + 3, 5888 + 9, 320),
+               None: (8192, 8192, 320)}[shape]
+    if shape in (108, 208):
         shape = 8
     g = np.random.Generator(np.random.PCG64(377 + (shape or 0)))
     A = g.integers(-128, 128, (M, K)).astype(np.int8)
