@@ -94,7 +94,7 @@ static int default_shape(int task, int64_t M, int64_t N, int64_t K)
     if (task == AMULET_TASK_COUNT_I8) {
         const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
         const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-        if (tiles128 < 256) return 4;
+        if (tiles128 <= 256) return 4;   // (at exactly one such tile per unit too: 4096 x 2048 x 4096 46 against 57 us)
         // (from three rounds of 256 x 256 tiles on: the persistent form of that kernel, whose
         // workgroups walk their tiles out of phase; measured, persistent against one tile per
         // workgroup, ms: 768 tiles x K = 8192 0.265 / 0.280, 896 x 4096 0.204 / 0.213, 1024 0.2125 /
