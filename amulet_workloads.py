@@ -104,6 +104,9 @@ CONFIGS = {
     "f64_discount_4096": dict(task=DISCOUNT, M=4096, N=4096, K=4096, seed=5, gen="retail", dtype="f64"),
     "f64_boost_2048": dict(task=BOOST, M=2048, N=2048, K=2048, seed=6, gen="signal", dtype="f64"),
     "f64_identity_4096": dict(task=IDENTITY, M=4096, N=4096, K=4096, seed=7, gen="uniform_pm1", dtype="f64"),
+    # a plain matmul of few tiles (64 of 128 x 128 for 256 compute units): the 64 x 64 identity tiles
+    "identity_1024": dict(task=IDENTITY, M=1024, N=1024, K=1024, seed=9, gen="uniform_pm1"),
+    "f64_identity_1024": dict(task=IDENTITY, M=1024, N=1024, K=1024, seed=10, gen="uniform_pm1", dtype="f64"),
 }
 
 _GENS = {"retail": retail, "signal": signal, "uniform_pm1": uniform_pm1,

@@ -241,7 +241,8 @@ def bench_f64(args, am, torch, np, wl, spec, A, B, P) -> dict:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": args.workload, "task": tname, "M": M, "N": N, "K": K,
-                   "tile_shape": "mfma_f64_128x128_dma4" if tname == "identity" else
+                   "tile_shape": ("mfma_f64_64x64_dma4" if am.amulet_selected_shape_f64(task, M, N, K) % 2 == 0
+                                  else "mfma_f64_128x128_dma4") if tname == "identity" else
                    am.amulet_f64_shape_name(am.amulet_selected_shape_f64(task, M, N, K))},
         "roofline": {"bound": "mfma" if tname == "identity" else "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
