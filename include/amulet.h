@@ -519,7 +519,10 @@ int amulet_probe_valu(int mix, int waves_per_simd, double *products_per_second, 
  * paper's tiling fixes, Sec. 3): a launch covers a tiles_m x tiles_n grid of
  * R tiles with amulet_tile_grid() workgroups; workgroup b runs on XCD b % 8,
  * and the grid is cut into 8 rectangular parts, one per XCD, so that the
- * workgroups resident on an XCD share A rows and B columns through its L2.
+ * workgroups resident on an XCD share A rows and B columns through its L2;
+ * when the tile counts do not divide into such parts, into 8 runs of equal
+ * length (to within one tile) of one panel-wise order instead, so that every
+ * XCD gets the same number of tiles.
  * amulet_tile_of_workgroup writes the tile (tm, tn) of workgroup `block` and
  * returns 1, or returns 0 when that workgroup is padding (it exits at once),
  * or a negative status for bad arguments.  Host-only helpers; every tile is
