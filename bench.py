@@ -138,6 +138,20 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     kernel_ms_median = sorted(kern_ms)[len(kern_ms) // 2]
     ops = 2.0 * M * N * K
     achieved = ops / (kernel_ms_avg * 1e-3) / 1e12
+    # The same join written instead of accumulated (R = A.B, amulet_count_i8_assign: the workload's
+    # own definition; the write-back does not read R).  Reported beside the += form, which stays
+    # the leg's figure; R starts full of another value and is checked against the same sample.
+    Ra = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        am.amulet_count_i8_assign(dA, dB, Ra)
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        starts[i].record()
+        am.amulet_count_i8_assign(dA, dB, Ra)
+        stops[i].record()
+    torch.cuda.synchronize()
+    assign_ms = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    assign_tops = ops / (assign_ms * 1e-3) / 1e12
     # what the matrix cores sustain on this instruction with nothing around it (the clock
     # drops under matrix-core load, so this is below the nominal peak)
     probe_tops = 2.0 * am.amulet_probe_mfma_i8(4) / 1e12
@@ -151,7 +165,8 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
         c0 = time.perf_counter()
         R_ref, threads = oracle.count_i8(np.ascontiguousarray(A[rows]), B)
         cpu_s = time.perf_counter() - c0
-        exact = bool(np.array_equal(Rz[torch.from_numpy(rows).cuda()].cpu().numpy(), R_ref))
+        exact = bool(np.array_equal(Rz[torch.from_numpy(rows).cuda()].cpu().numpy(), R_ref)) and \
+            bool(np.array_equal(Ra[torch.from_numpy(rows).cuda()].cpu().numpy(), R_ref))
         cpu = {"value": round(2.0 * len(rows) * N * K / cpu_s / 1e9, 3), "unit": "GOP/s (2MNK/t)", "cores": threads,
                "kind": "oracle", "sample": "%d whole rows of the %dx%dx%d workload, %.1f s" % (len(rows), M, N, K, cpu_s)}
     return {
@@ -168,7 +183,10 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
                      "shader_clock_mhz": sclk_mhz,
                      "compulsory_bytes": M * K + K * N + 8 * M * N,
                      "mfma_probe_tops": round(probe_tops, 1),
-                     "frac_of_mfma_probe": round(achieved / probe_tops, 4)},
+                     "frac_of_mfma_probe": round(achieved / probe_tops, 4),
+                     "assign_form": {"kernel_ms_avg": round(assign_ms, 4), "achieved": round(assign_tops, 2),
+                                     "frac": round(assign_tops / INT8_MFMA_PEAK_TOPS, 4),
+                                     "compulsory_bytes": M * K + K * N + 4 * M * N}},
         "cpu_baseline": cpu, "bit_exact_on_sample": exact,
         "parity_ok": None if exact is None else bool(exact)}
 
@@ -515,7 +533,7 @@ def config_leg(name, args, am, torch, np, wl) -> dict:
            "tile_shape": rec["config"]["tile_shape"],
            "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "frac_of_op_mix_ceiling",
                                              "frac_of_mfma_probe", "shader_clock_mhz",
-                                             "frac_of_op_mix_ceiling_at_clock") if k in roof},
+                                             "frac_of_op_mix_ceiling_at_clock", "assign_form") if k in roof},
            "parity_on_sample": rec.get("parity_worst_ratio_on_sample", rec.get("bit_exact_on_sample")),
            "parity_ok": rec["parity_ok"], "parity_sample": rec["cpu_baseline"]["sample"] if rec["cpu_baseline"] else None}
     for key in ("library_sgemm", "library_dgemm"):

@@ -326,6 +326,23 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
                           void *stream);
 
 /*
+ * The join count written, not accumulated: R[i][j] = sum_k A[i][k]*B[k][j] (the
+ * count itself, as the join-as-matmul translation of Sec. 1 produces it; what R
+ * held before is ignored and need not be initialised).  Same operands, result
+ * type, exactness and error codes as amulet_count_i8; `shape` as for
+ * amulet_count_i8_shape, or -1 for the selected shape.  K == 0 sets R to zero.
+ * The kernels do not read R where one workgroup owns a tile (large problems:
+ * a third of the write-back's memory traffic less); a launch that splits K over
+ * workgroups clears R with a fill kernel first and adds.  Enqueues and returns;
+ * nothing is allocated.
+ */
+int amulet_count_i8_assign(int shape, int64_t M, int64_t N, int64_t K,
+                           const int8_t *A, int64_t lda,
+                           const int8_t *B, int64_t ldb,
+                           int32_t *R, int64_t ldr,
+                           void *stream);
+
+/*
  * The join count with operands stored transposed (the layouts of Sec. 6.3
  * applied to this task): A stored K x M (lda >= M) when trans_a != 0, B stored
  * N x K (ldb >= K) when trans_b != 0.  The matrix-core kernels read row-major

@@ -107,6 +107,8 @@ def load_library():
     lib.amulet_count_i8_static.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_count_i8_shape.restype = i32
     lib.amulet_count_i8_shape.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.amulet_count_i8_assign.restype = i32
+    lib.amulet_count_i8_assign.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.amulet_tune.restype = i32
     lib.amulet_tune.argtypes = [i32, i64, i64, i64, vp]
     lib.amulet_shape_count.restype = i32
@@ -465,6 +467,19 @@ def amulet_count_i8_shape(shape: int, A, B, R, stream=None):
         raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
     _check(lib.amulet_count_i8_shape(shape, M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
            "amulet_count_i8_shape")
+
+
+def amulet_count_i8_assign(A, B, R, shape: int = -1, stream=None):
+    """R = A @ B for int8 A, B and int32 R on the GPU, exact: the counts are written, whatever R
+    held before; `shape` -1 is the selected shape.  Enqueues and returns."""
+    lib = load_library()
+    pa, M, K, lda = _mat(A, "torch.int8", "A")
+    pb, K2, N, ldb = _mat(B, "torch.int8", "B")
+    pr, M2, N2, ldr = _mat(R, "torch.int32", "R")
+    if K2 != K or M2 != M or N2 != N:
+        raise ValueError("shape mismatch: A %dx%d, B %dx%d, R %dx%d" % (M, K, K2, N, M2, N2))
+    _check(lib.amulet_count_i8_assign(shape, M, N, K, pa, lda, pb, ldb, pr, ldr, _stream_ptr(stream)),
+           "amulet_count_i8_assign")
 
 
 def amulet_tune(task: int, M: int, N: int, K: int, stream=None) -> int:

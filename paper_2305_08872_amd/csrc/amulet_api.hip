@@ -231,9 +231,10 @@ static const int kPersPhases[4] = {8, 2, 2, 16};   // groups, stages between gro
 // m_load / n_load: rows of A / columns of B that exist in memory (0: just M, N)
 static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
                      const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream,
-                     int64_t m_load = 0, int64_t n_load = 0)
+                     int64_t m_load = 0, int64_t n_load = 0, bool assign = false)
 {
     CountArgs a;
+    a.assign = assign ? 1 : 0;
     a.A = A; a.B = B; a.R = R;
     a.lda = lda; a.ldb = ldb; a.ldr = ldr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
@@ -1066,6 +1067,26 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K, const int8
     if (rc < 0) return rc;
     if (rc == 1) return AMULET_OK;
     return run_count(shape, M, N, K, A, lda, B, ldb, R, ldr, stream);
+}
+
+int amulet_count_i8_assign(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                           const int8_t *B, int64_t ldb, int32_t *R, int64_t ldr, void *stream)
+{
+    if (shape >= COUNT_SHAPE_COUNT) return AMULET_ERR_SHAPE;
+    const int rc = check_common(M, N, K, A, lda, B, ldb, R, ldr);
+    if (rc < 0) return rc;
+    if (M == 0 || N == 0) return AMULET_OK;
+    if (!R) return AMULET_ERR_NULL;
+    if (ldr < N) return AMULET_ERR_LD;
+    if (K == 0) {   // an empty sum: R = 0
+        CountArgs z;
+        z.R = R; z.ldr = ldr; z.M = (int)M; z.N = (int)N;
+        const hipError_t e = launch_zero_r_i32(z, (hipStream_t)stream);
+        g_last_hip_error = e;
+        return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
+    }
+    if (shape < 0) shape = lookup_shape(AMULET_TASK_COUNT_I8, M, N, K);
+    return run_count(shape, M, N, K, A, lda, B, ldb, R, ldr, stream, 0, 0, true);
 }
 
 int amulet_greedy_search(int n0, int n1, amulet_score_fn score, void *ctx, int *best0, int *best1)

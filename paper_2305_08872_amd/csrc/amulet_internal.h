@@ -347,11 +347,16 @@ struct CountArgs {
     // of an XCD in pers_groups groups, pers_group_stages stages (of 64 k) apart, and XCD x another
     // (x % pers_xcds) * pers_xcd_span / pers_xcds sixteenths of the range
     int pers_groups, pers_group_stages, pers_xcds, pers_xcd_span;
+    // 1: R = the counts instead of R += (amulet_count_i8_assign): a workgroup that owns its tile
+    // alone stores its sums without reading R; a launch that splits K clears R first and adds
+    int assign = 0;
 };
 // shape 0: plain per-output loop; MFMA tiles 1: 128 x 128 (4 waves), 2: 256 x 256 (8 waves),
 // 3: 128 x 256 (8 waves)
 enum { COUNT_SHAPE_COUNT = 9 };
 hipError_t launch_count_i8(int shape, const CountArgs &a, hipStream_t s);
+// R[0..M) x [0..N) = 0 (a fill kernel: usable under graph capture)
+hipError_t launch_zero_r_i32(const CountArgs &a, hipStream_t s);
 // direct HBM -> LDS kernels: tile (64 * wr) x 256, wr = 2 or 4
 bool count_i8_dma_eligible(const CountArgs &a, int wr);
 hipError_t launch_count_i8_dma(const CountArgs &a, int wr, hipStream_t s, bool persistent = false);

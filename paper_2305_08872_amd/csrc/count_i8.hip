@@ -284,7 +284,7 @@ count_i8_mfma_kernel(const CountArgs args)
                     if (ksplit) {
                         if (row < M) atomicAdd(dst, acc[mi][ni][v]);
                     } else {
-                        old[w] = row < M ? (uint32_t)*dst : 0u;
+                        old[w] = row < M && !args.assign ? (uint32_t)*dst : 0u;
                     }
                 }
                 if (!ksplit) {
@@ -313,7 +313,25 @@ count_i8_simple_kernel(const CountArgs args)
     for (int k = 0; k < args.K; ++k)
         acc += (int)a[k] * (int)b[(int64_t)k * args.ldb];
     int32_t *dst = args.R + (int64_t)i * args.ldr + j;
-    *dst = (int32_t)((uint32_t)*dst + (uint32_t)acc);
+    *dst = args.assign ? acc : (int32_t)((uint32_t)*dst + (uint32_t)acc);
+}
+
+__global__ void __launch_bounds__(256) zero_r_i32_kernel(int32_t *R, int64_t ldr, int M, int N)
+{
+    const int64_t row = blockIdx.y;
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < N; j += (int64_t)gridDim.x * 256)
+        if (row < M) R[row * ldr + j] = 0;
+}
+
+hipError_t launch_zero_r_i32(const CountArgs &a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    const unsigned gx = (unsigned)((a.N + 255) / 256 < 1024 ? (a.N + 255) / 256 : 1024);
+    for (int64_t r0 = 0; r0 < a.M; r0 += 65535) {
+        const int64_t rows = a.M - r0 < 65535 ? a.M - r0 : 65535;
+        hipLaunchKernelGGL(zero_r_i32_kernel, dim3(gx, (unsigned)rows), dim3(256), 0, s, a.R + r0 * a.ldr, a.ldr, (int)rows, a.N);
+    }
+    return hipGetLastError();
 }
 
 template <int MB, int NB, int WR, int WC, int WPE, int BK>
@@ -343,6 +361,11 @@ static hipError_t launch_mfma(const CountArgs &a, hipStream_t s)
         const int64_t chunk = ((a.K + want - 1) / want + BK - 1) / BK * BK;
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    if (splits > 1 && a.assign) {   // several workgroups add into a tile: from zero
+        const hipError_t ez = launch_zero_r_i32(a, s);
+        if (ez != hipSuccess) return ez;
+        b.assign = 0;
     }
     return launch_row_of_blocks(b, grid, T::NT, [&](unsigned n) {
         hipLaunchKernelGGL((count_i8_mfma_kernel<MB, NB, WR, WC, WPE, BK>), dim3(n, (unsigned)splits), dim3(T::NT),

@@ -305,11 +305,21 @@ __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, c
         char *base = (char *)(args.R + (int64_t)(row0 + row) * args.ldr + col0);   // uniform over the wave
         return (v4i *)(base + lane16);
     };
+    // R = the counts (no R +=): this item's sums replace what R holds, when it owns the tile alone
+    // and starts the tile's k range (a persistent workgroup's second pass over its first tile adds
+    // to what its first pass stored).  The rows of R are then not read: the loads below fetch the
+    // first kilobyte of A instead, a line every workgroup shares through the L2, so that the number
+    // and order of the wave's vector memory operations -- which the hand-counted waits of the next
+    // item's first stages rest on -- are the same in both forms.
+    const bool assign = args.assign && kb == 0 && !ksplit;
+    auto r_src = [&](int q, int j) {
+        return assign ? (const v4i *)((const char *)args.A + lane16) : (const v4i *)r_row(q, j);
+    };
     if (!ksplit) {
 #pragma unroll
         for (int q = 0; q < DEPTH && q < NGROUPS; ++q)
 #pragma unroll
-            for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_row(q, j));
+            for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_src(q, j));
     }
     int next_requested = 0;
 #pragma unroll
@@ -361,12 +371,12 @@ __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, c
                 const int ir = wave * ROWS_PER_WAVE + grp * GROUP + j;
                 const v4i part4 = *(const v4i *)(img + ir * IMG_PITCH + ((lane * 4) ^ img_swz(ir)));
                 v4i cur = rbuf[q % DEPTH][j];
-                cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
-                cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
-                cur.z = (int)((uint32_t)cur.z + (uint32_t)part4.z);
-                cur.w = (int)((uint32_t)cur.w + (uint32_t)part4.w);
+                cur.x = assign ? part4.x : (int)((uint32_t)cur.x + (uint32_t)part4.x);
+                cur.y = assign ? part4.y : (int)((uint32_t)cur.y + (uint32_t)part4.y);
+                cur.z = assign ? part4.z : (int)((uint32_t)cur.z + (uint32_t)part4.z);
+                cur.w = assign ? part4.w : (int)((uint32_t)cur.w + (uint32_t)part4.w);
                 __builtin_nontemporal_store(cur, r_row(q, j));
-                if (q + DEPTH < NGROUPS) rbuf[q % DEPTH][j] = __builtin_nontemporal_load(r_row(q + DEPTH, j));   // this register's next row
+                if (q + DEPTH < NGROUPS) rbuf[q % DEPTH][j] = __builtin_nontemporal_load(r_src(q + DEPTH, j));   // this register's next row
             }
         }
     }
@@ -494,6 +504,11 @@ static hipError_t launch_dma(const CountArgs &a, hipStream_t s)
         const int64_t chunk = ((a.K + want - 1) / want + DM_BK - 1) / DM_BK * DM_BK;
         b.kchunk = (int)chunk;
         splits = (int)((a.K + chunk - 1) / chunk);
+    }
+    if (splits > 1 && a.assign) {   // several workgroups add into a tile: from zero
+        const hipError_t ez = launch_zero_r_i32(a, s);
+        if (ez != hipSuccess) return ez;
+        b.assign = 0;
     }
     return launch_row_of_blocks(b, grid, T::NT, [&](unsigned n) {
         hipLaunchKernelGGL((count_i8_dma_kernel<WR, NSTAGE>), dim3(n, (unsigned)splits), dim3(T::NT), T::LDS_BYTES, s, b);

@@ -291,6 +291,54 @@ def test_count_i8_persistent_workgroups(am, shape, phases, monkeypatch):
     assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64 + 7 * M)
 
 
+@pytest.mark.parametrize("case", [
+    # (shape, M, N, K): the persistent streamed kernel (a workgroup's first tile in two passes: the
+    # first stores, the second adds), the one-tile streamed kernels, a streamed interior with
+    # register-staged edge strips, the register-staged kernels with ragged sizes and unaligned K,
+    # few tiles with a long K (K split: R cleared, then atomic adds), the plain loop, the default
+    (8, 8192, 8192, 320), (7, 1024, 2048, 192), (6, 640, 1280, 128), (8, 8192 + 77, 4096 + 33, 320),
+    (1, 777, 999, 130), (4, 300, 500, 77), (5, 513, 257, 64), (3, 256, 256, 4096), (6, 256, 512, 8192),
+    (0, 70, 90, 33), (-1, 2048, 2048, 256), (-1, 100, 100, 3)])
+def test_count_i8_assign_writes_the_counts_whatever_R_held(am, case):
+    """amulet_count_i8_assign: R = A . B exactly, with R full of other values beforehand (and the
+    padding of R's rows untouched); against the oracle with a zero R_in, whole matrix for the small
+    cases, sampled rows and columns plus whole-matrix checksums for the large ones.  K = 0 gives
+    zeros; a second call gives the same R again (nothing accumulates)."""
+    shape, M, N, K = case
+    g = np.random.Generator(np.random.PCG64(431 + M + K))
+    A = g.integers(-128, 128, (M, K)).astype(np.int8)
+    B = g.integers(-128, 128, (K, N)).astype(np.int8)
+    pad = 4
+    buf = torch.full((M, N + pad), -123456, dtype=torch.int32, device="cuda")
+    dR = buf[:, :N]
+    print("i8 assign case", case, flush=True)
+    dA, dB = dev(A), dev(B)
+    for _ in range(2):
+        am.amulet_count_i8_assign(dA, dB, dR, shape=shape)
+    torch.cuda.synchronize()
+    full = buf.cpu().numpy()
+    assert np.all(full[:, N:] == -123456), "wrote outside R"
+    R = full[:, :N]
+    if M * N * K <= 300 * 500 * 4096:
+        R_ref, _ = oracle.count_i8(A, B, np.zeros((M, N), np.int32))
+        assert np.array_equal(R, R_ref)
+    else:
+        rows = np.sort(g.choice(M, 24, replace=False)); rows[0], rows[-1] = 0, M - 1
+        cols = np.sort(g.choice(N, 24, replace=False)); cols[0], cols[-1] = 0, N - 1
+        R_ref, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B, np.zeros((len(rows), N), np.int32))
+        assert np.array_equal(R[rows], R_ref)
+        R_ref, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]), np.zeros((M, len(cols)), np.int32))
+        assert np.array_equal(R[:, cols], R_ref)
+        A64, B64 = A.astype(np.int64), B.astype(np.int64)
+        assert np.array_equal(R.astype(np.int64).sum(1), A64 @ B64.sum(1))
+        assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64)
+    # an empty sum
+    am.amulet_count_i8_assign(dA[:, :0], dB[:0, :], dR, shape=shape)
+    torch.cuda.synchronize()
+    full = buf.cpu().numpy()
+    assert np.all(full[:, :N] == 0) and np.all(full[:, N:] == -123456)
+
+
 def test_count_i8_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch):
     """In-flight adaptive execution of the join count: slabs of rows of the caller's R are computed
     by different matrix-core kernels, the rest by the fastest; the whole R must be the exact count
