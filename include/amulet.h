@@ -332,7 +332,7 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
  * type, exactness and error codes as amulet_count_i8; `shape` as for
  * amulet_count_i8_shape, or -1 for the selected shape.  K == 0 sets R to zero.
  * The kernels do not read R where one workgroup owns a tile (large problems:
- * a third of the write-back's memory traffic less); a launch that splits K over
+ * half of the write-back's memory traffic less); a launch that splits K over
  * workgroups clears R with a fill kernel first and adds.  Enqueues and returns;
  * nothing is allocated.
  */

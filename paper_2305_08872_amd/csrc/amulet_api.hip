@@ -249,6 +249,13 @@ static int run_count(int shape, int64_t M, int64_t N, int64_t K, const int8_t *A
     a.pers_group_stages = kPersPhases[1];
     a.pers_xcds = kPersPhases[2];
     a.pers_xcd_span = kPersPhases[3];
+    if (assign) {
+        // R = form: all workgroups in step.  A phase makes a workgroup sum its first tile in two passes,
+        // the second of which has to read R, and the write-back the phases spread out is stores only
+        // here (cfg3 0.1875 ms in step against 0.192-0.1945 over twelve phase arrangements; 8192^2 x 1024
+        // 0.085 / 0.093).
+        a.pers_groups = 1; a.pers_group_stages = 0; a.pers_xcds = 1; a.pers_xcd_span = 0;
+    }
     if (const char *e = getenv("AMULET_I8_PHASES")) {   // diagnostic override, "groups,stages,xcds,span"
         int g = 1, st = 0, x = 1, sp = 0;
         if (sscanf(e, "%d,%d,%d,%d", &g, &st, &x, &sp) == 4 && g >= 1 && g <= 64 && st >= 0 && st <= 64 && x >= 1 && x <= 8 &&

@@ -72,12 +72,12 @@ struct NextItem {
 // `pre` the number of its stages the item before already requested (0 for a first item), and
 // when `next` names an item, this one requests the first stages of it (PREFETCH of them) into
 // the half of the ring its own write-back does not use, right after its K loop, so that they
-// arrive during the write-back instead of after it.  Returns how many stages it requested
-// for `next`.
+// arrive during the write-back instead of after it (`pre_assign`: the item before stored its sums
+// without reading R, see the write-back).  Returns how many stages it requested for `next`.
 template <int WR, int NSTAGE>
 __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, const int col0, const int kb,
                                         const int K, const bool ksplit, const int ring0 = 0, const int pre = 0,
-                                        const NextItem next = NextItem{0, 0, 0, 0})
+                                        const NextItem next = NextItem{0, 0, 0, 0}, const bool pre_assign = false)
 {
     typedef DmaTile<WR, NSTAGE> T;
     static_assert(NSTAGE >= 3 && NSTAGE <= 5, "the wait counts are written for rings of 3 to 5 stages");
@@ -188,14 +188,16 @@ __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, c
     // have registers for one group only)
     constexpr int WB_GROUP = 4, WB_DEPTH = WR == 4 ? 2 : 1;
     constexpr int EXTRA = 2 * WR * (64 / NW) - WB_DEPTH * WB_GROUP;   // per wave: a tile's loads and stores of R rows, less the loads that precede the request
+    constexpr int EXTRA_ASSIGN = WR * (64 / NW);                      // the stores alone, when the item before did not read R
     static_assert(T::LOADS * (NSTAGE - 2) + EXTRA <= 63, "the wait count is a 6-bit field");
     auto wait_stage = [&](int t, int upto) {
-        const int n = T::LOADS * (upto - t) + (t < pre ? EXTRA : 0);
+        const int n = T::LOADS * (upto - t) + (t < pre ? (pre_assign ? EXTRA_ASSIGN : EXTRA) : 0);
         // (the count is an immediate operand: one instruction per value that can occur)
         switch (n) {
         case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
 #define AMULET_WAIT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
         AMULET_WAIT_CASE(2) AMULET_WAIT_CASE(3) AMULET_WAIT_CASE(4) AMULET_WAIT_CASE(6) AMULET_WAIT_CASE(9)
+        AMULET_WAIT_CASE(16) AMULET_WAIT_CASE(18) AMULET_WAIT_CASE(19) AMULET_WAIT_CASE(20) AMULET_WAIT_CASE(22)
         AMULET_WAIT_CASE(24) AMULET_WAIT_CASE(26) AMULET_WAIT_CASE(28) AMULET_WAIT_CASE(30)
         AMULET_WAIT_CASE(56) AMULET_WAIT_CASE(59) AMULET_WAIT_CASE(62)
 #undef AMULET_WAIT_CASE
@@ -307,19 +309,15 @@ __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, c
     };
     // R = the counts (no R +=): this item's sums replace what R holds, when it owns the tile alone
     // and starts the tile's k range (a persistent workgroup's second pass over its first tile adds
-    // to what its first pass stored).  The rows of R are then not read: the loads below fetch the
-    // first kilobyte of A instead, a line every workgroup shares through the L2, so that the number
-    // and order of the wave's vector memory operations -- which the hand-counted waits of the next
-    // item's first stages rest on -- are the same in both forms.
+    // to what its first pass stored).  The rows of R are then not read at all; the item after this
+    // one is told so (`pre_assign`), because the waits for the stages requested below count the
+    // vector memory operations issued behind the request.
     const bool assign = args.assign && kb == 0 && !ksplit;
-    auto r_src = [&](int q, int j) {
-        return assign ? (const v4i *)((const char *)args.A + lane16) : (const v4i *)r_row(q, j);
-    };
-    if (!ksplit) {
+    if (!ksplit && !assign) {
 #pragma unroll
         for (int q = 0; q < DEPTH && q < NGROUPS; ++q)
 #pragma unroll
-            for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_src(q, j));
+            for (int j = 0; j < GROUP; ++j) rbuf[q][j] = __builtin_nontemporal_load(r_row(q, j));
     }
     int next_requested = 0;
 #pragma unroll
@@ -370,13 +368,17 @@ __device__ __forceinline__ int dma_item(const CountArgs &args, const int row0, c
             for (int j = 0; j < GROUP; ++j) {
                 const int ir = wave * ROWS_PER_WAVE + grp * GROUP + j;
                 const v4i part4 = *(const v4i *)(img + ir * IMG_PITCH + ((lane * 4) ^ img_swz(ir)));
+                if (assign) {
+                    __builtin_nontemporal_store(part4, r_row(q, j));
+                    continue;
+                }
                 v4i cur = rbuf[q % DEPTH][j];
-                cur.x = assign ? part4.x : (int)((uint32_t)cur.x + (uint32_t)part4.x);
-                cur.y = assign ? part4.y : (int)((uint32_t)cur.y + (uint32_t)part4.y);
-                cur.z = assign ? part4.z : (int)((uint32_t)cur.z + (uint32_t)part4.z);
-                cur.w = assign ? part4.w : (int)((uint32_t)cur.w + (uint32_t)part4.w);
+                cur.x = (int)((uint32_t)cur.x + (uint32_t)part4.x);
+                cur.y = (int)((uint32_t)cur.y + (uint32_t)part4.y);
+                cur.z = (int)((uint32_t)cur.z + (uint32_t)part4.z);
+                cur.w = (int)((uint32_t)cur.w + (uint32_t)part4.w);
                 __builtin_nontemporal_store(cur, r_row(q, j));
-                if (q + DEPTH < NGROUPS) rbuf[q % DEPTH][j] = __builtin_nontemporal_load(r_src(q + DEPTH, j));   // this register's next row
+                if (q + DEPTH < NGROUPS) rbuf[q % DEPTH][j] = __builtin_nontemporal_load(r_row(q + DEPTH, j));   // this register's next row
             }
         }
     }
@@ -460,9 +462,11 @@ count_i8_dma_persistent_kernel(const CountArgs args)
     NextItem cur, nxt;
     int step = next_real(0, cur);
     int ring0 = 0, pre = 0;
+    bool pre_assign = false;
     while (step < n_steps) {
         const int nstep = next_real(step + 1, nxt);
-        const int req = dma_item<WR, NSTAGE>(args, cur.row0, cur.col0, cur.kb, cur.K, false, ring0, pre, nxt);
+        const int req = dma_item<WR, NSTAGE>(args, cur.row0, cur.col0, cur.kb, cur.K, false, ring0, pre, nxt, pre_assign);
+        pre_assign = args.assign && cur.kb == 0;
         __builtin_amdgcn_s_barrier();            // every wave is done with the image: the ring is the next item's
         ring0 = req > 0 ? NSTAGE - 2 : 0;
         pre = req;

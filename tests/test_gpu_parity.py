@@ -339,6 +339,33 @@ def test_count_i8_assign_writes_the_counts_whatever_R_held(am, case):
     assert np.all(full[:, :N] == 0) and np.all(full[:, N:] == -123456)
 
 
+@pytest.mark.parametrize("phases", ["8,2,2,16", "4,1,8,16"])
+def test_count_i8_assign_with_phased_workgroups(am, phases, monkeypatch):
+    """The R = form runs the persistent kernel's workgroups in step by default; with phases forced, a
+    workgroup sums its first tile in two passes, of which the first stores and the second adds to
+    what the first stored.  Exact, from an R full of other values (sampled rows and columns, whole
+    matrix checksums)."""
+    monkeypatch.setenv("AMULET_I8_PHASES", phases)
+    M, N, K = 8192, 8192, 320
+    g = np.random.Generator(np.random.PCG64(433))
+    A = g.integers(-128, 128, (M, K)).astype(np.int8)
+    B = g.integers(-128, 128, (K, N)).astype(np.int8)
+    dR = torch.full((M, N), 99, dtype=torch.int32, device="cuda")
+    print("i8 assign phased", phases, flush=True)
+    am.amulet_count_i8_assign(dev(A), dev(B), dR, shape=8)
+    torch.cuda.synchronize()
+    R = dR.cpu().numpy()
+    rows = np.sort(g.choice(M, 24, replace=False)); rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(g.choice(N, 24, replace=False)); cols[0], cols[-1] = 0, N - 1
+    R_ref, _ = oracle.count_i8(np.ascontiguousarray(A[rows]), B, np.zeros((len(rows), N), np.int32))
+    assert np.array_equal(R[rows], R_ref)
+    R_ref, _ = oracle.count_i8(A, np.ascontiguousarray(B[:, cols]), np.zeros((M, len(cols)), np.int32))
+    assert np.array_equal(R[:, cols], R_ref)
+    A64, B64 = A.astype(np.int64), B.astype(np.int64)
+    assert np.array_equal(R.astype(np.int64).sum(1), A64 @ B64.sum(1))
+    assert np.array_equal(R.astype(np.int64).sum(0), A64.sum(0) @ B64)
+
+
 def test_count_i8_adaptive_execution_trials_contribute_to_the_result(am, monkeypatch):
     """In-flight adaptive execution of the join count: slabs of rows of the caller's R are computed
     by different matrix-core kernels, the rest by the fastest; the whole R must be the exact count
