@@ -100,6 +100,8 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dR = torch.zeros(M, N, dtype=torch.int32, device="cuda")
     T = am.AMULET_TASK_COUNT_I8
+    # (--i8-assign: the launches that are timed, traced or counted are of the R = form)
+    count = (lambda a, b, r: am.amulet_count_i8_assign(a, b, r)) if args.i8_assign else am.amulet_count_i8
     if args.traffic_probe:
         # for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes: the counter
         # calibration), then --steps launches of the kernel
@@ -111,7 +113,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
         if not args.no_tune:
             am.amulet_tune(T, M, N, K)
         for _ in range(args.steps):
-            am.amulet_count_i8(dA, dB, dR)
+            count(dA, dB, dR)
         torch.cuda.synchronize()
         print("traffic probe done: 1 copy of %d bytes, %d launches of %s" %
               (src.numel() * 4, args.steps, am.amulet_shape_name(T, am.amulet_selected_shape(T, M, N, K))))
@@ -120,7 +122,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
     shape = am.amulet_selected_shape(T, M, N, K) if args.no_tune else am.amulet_tune(T, M, N, K)
     tune_s = time.perf_counter() - t0
     for _ in range(args.warmup):
-        am.amulet_count_i8(dA, dB, dR)
+        count(dA, dB, dR)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -128,7 +130,7 @@ def bench_count_i8(args, am, torch, np, spec, A, B) -> dict:
         w0 = time.perf_counter()
         for i in range(args.steps):
             starts[i].record()
-            am.amulet_count_i8(dA, dB, dR)
+            count(dA, dB, dR)
             stops[i].record()
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
@@ -561,6 +563,8 @@ def main() -> int:
     ap.add_argument("--nonsquare", choices=["discount", "boost", "count_gt", "identity"], default=None,
                     help="instead of the workload: the paper's non-square protocol (18 shapes of equal work "
                          "around 4096^3) for this task, in place and with packing allowed")
+    ap.add_argument("--i8-assign", action="store_true",
+                    help="int8 join count: time (trace, count) the R = form, amulet_count_i8_assign, instead of R +=")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one plain 256 MiB device copy (known HBM bytes, "
                          "the counter calibration) followed by --steps launches of the kernel; prints no JSON")
