@@ -408,6 +408,48 @@ mmlike_valu_f64_kernel(const MmlikeArgsF64 args)
                     fold_rows<TASK>(ak, bq[c & 1][kk], th, q, acc);
                 }
             }
+        } else if (!ALDS && t < full_tiles) {
+            // A on the scalar path.  The B values of a chunk are read from LDS while the chunk before
+            // it computes (two chunks per turn of the rolled loop, so that the two sets of B registers
+            // need no copies): the wave waits for LDS with work queued, except for a tile's first chunk.
+            d2 b0[KA], b1[KA];
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk) b0[kk] = *(const d2 *)(bs + kk * D_BN);
+            auto chunk = [&](int kc, const d2 (&b)[KA], d2 (&bn)[KA], bool read_next) {
+                d2_a8 a[transA ? 1 : D_TM];
+                d4_a8 a_t[transA ? KA : 1];
+                if constexpr (!transA) {
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r) a[r] = a_next[r];
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < KA; ++kk) a_t[kk] = a_next_t[kk];
+                }
+                // this chunk's values have landed; the LDS reads of the next chunk and the scalar
+                // fetch of its A values go out right after the wait (scalar loads return out of
+                // order: any later LDS wait would drain them too)
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                if (read_next) {
+#pragma unroll
+                    for (int kk = 0; kk < KA; ++kk) bn[kk] = *(const d2 *)(bs + (kc + KA + kk) * D_BN);
+                }
+                fetch_a(k0, k0 + kc + 2 * KA <= K ? kc + KA : kc);   // past the last full chunk: this one again
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk) {
+                    double ak[D_TM];
+#pragma unroll
+                    for (int r = 0; r < D_TM; ++r) ak[r] = transA ? a_t[transA ? kk : 0][r] : a[transA ? 0 : r][kk];
+                    fold_rows<TASK>(ak, b[kk], th, q, acc);
+                }
+            };
+            static_assert((D_BK / KA) % 2 == 0, "the chunks of a tile are taken in pairs");
+#pragma unroll 1
+            for (int kc = 0; kc < D_BK; kc += 2 * KA) {
+                chunk(kc, b0, b1, true);
+                chunk(kc + KA, b1, b0, kc + 2 * KA < D_BK);
+            }
         } else if (t < full_tiles) {
 #pragma unroll 1
             for (int kc = 0; kc < D_BK; kc += KA) {
