@@ -1092,7 +1092,12 @@ int amulet_count_i8_assign(int shape, int64_t M, int64_t N, int64_t K, const int
         g_last_hip_error = e;
         return e == hipSuccess ? AMULET_OK : AMULET_ERR_LAUNCH;
     }
-    if (shape < 0) shape = lookup_shape(AMULET_TASK_COUNT_I8, M, N, K);
+    if (shape < 0) {
+        shape = lookup_shape(AMULET_TASK_COUNT_I8, M, N, K);
+        // (without the read of R the persistent kernel's edge over two 128 x 256 tiles per unit starts
+        // later: 768 tiles of 256 x 256 94 against 88 us, 1024 tiles level, 1536 tiles 272 / 277)
+        if (shape == 8 && ((M + 255) / 256) * ((N + 255) / 256) < 1024) shape = 6;
+    }
     return run_count(shape, M, N, K, A, lda, B, ldb, R, ldr, stream, 0, 0, true);
 }
 
