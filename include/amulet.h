@@ -333,8 +333,9 @@ int amulet_count_i8_shape(int shape, int64_t M, int64_t N, int64_t K,
  * amulet_count_i8_shape, or -1 for the selected shape.  K == 0 sets R to zero.
  * The kernels do not read R where one workgroup owns a tile (large problems:
  * half of the write-back's memory traffic less); a launch that splits K over
- * workgroups clears R with a fill kernel first and adds.  Enqueues and returns;
- * nothing is allocated.
+ * workgroups clears R with a fill kernel first and adds.  (The persistent
+ * kernel's workgroups run in step in this form unless AMULET_I8_PHASES says
+ * otherwise.)  Enqueues and returns; nothing is allocated.
  */
 int amulet_count_i8_assign(int shape, int64_t M, int64_t N, int64_t K,
                            const int8_t *A, int64_t lda,
