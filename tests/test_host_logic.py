@@ -159,6 +159,23 @@ def test_shape_table_is_the_two_axis_grid(lib):
     assert am.amulet_shape_count(am.AMULET_TASK_COUNT_I8) >= 1
 
 
+def test_identity_tile_follows_how_the_tile_counts_suit_the_chip(lib):
+    """The built-in choice for the identity task (256 compute units assumed where no GPU is present):
+    64 x 64 tiles with fewer 128 x 128 tiles than units, and up to four large tiles per unit where
+    the small tiles' count leaves clearly less of a unit's last tile unused; the 128 x 128 streamed
+    shapes otherwise.  fp64 reads the shape id's tile index (0 = 64 x 64, 1 = 128 x 128) and also
+    takes the small tile at exactly one large tile per unit."""
+    small = am.amulet_shape_count(am.AMULET_IDENTITY) - 1
+    assert am.amulet_shape_name(am.AMULET_IDENTITY, small) == "mfma_f32_64x64_dma4"
+    sel = lambda M, N: am.amulet_selected_shape(am.AMULET_IDENTITY, M, N, 4096)
+    for M, N in [(512, 512), (1024, 1024), (1792, 1792), (3072, 3072), (3584, 3584), (2560, 2560), (2047, 2049)]:
+        assert sel(M, N) == small, (M, N)
+    for M, N in [(2048, 2048), (4096, 4096), (2816, 2816), (8192, 512), (8192, 8192), (16384, 2300)]:
+        assert sel(M, N) in (small - 2, small - 1), (M, N)      # the ring of 3 or of 4
+    sel64 = lambda M, N: am.amulet_selected_shape_f64(am.AMULET_IDENTITY, M, N, 4096) % 2
+    assert [sel64(1024, 1024), sel64(2048, 2048), sel64(3072, 3072), sel64(2816, 2816), sel64(4096, 4096)] == [0, 0, 0, 1, 1]
+
+
 def test_tile_order_covers_every_tile_exactly_once(lib):
     """The XCD-aware workgroup -> tile map: every tile of the grid has exactly one owner, padding
     workgroups own none, and every XCD gets the same number of tiles to within one (workgroup b
