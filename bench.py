@@ -526,6 +526,10 @@ def config_leg(name, args, am, torch, np, wl) -> dict:
     # slower than the default, and a leg should measure the kernel, not that noise
     sub.no_tune = True
     sub.warmup = max(3, args.warmup, min(400, int(100.0 / ms_guess)))
+    if wl.CONFIGS[name]["task"] == "count_i8":
+        # (the matrix-core clock takes about a second of load to settle: 0.5 s of launches first, for
+        # both forms of the join count alike)
+        sub.warmup = max(sub.warmup, int(500.0 / ms_guess))
     M = wl.CONFIGS[name]["M"]
     sub.cpu_rows = min(M, 64) if wl.CONFIGS[name]["task"] != "count_i8" else 16   # count_i8 samples 4 x this
     rec = bench_workload(sub, am, torch, np, wl)
